@@ -1,0 +1,276 @@
+/*
+ * autochunk_rt — runtime execution of AutoChunk chunk plans on one MI355X (gfx950).
+ *
+ * AutoChunk (arXiv 2401.10652), section 2.2: a module Y = F(X) is "chunked" by
+ * splitting X along a chunk dimension into n segments, computing y_i = F(x_i) one
+ * segment after another and concatenating the y_i, which bounds the intermediate
+ * activation A to A/n (second activation equation) while Y stays equal to the
+ * unchunked result (section 3.3, output alignment rule).  Section 3.1 writes a
+ * region as Y^c = F(X^c, X^nc): chunkable inputs are sliced, non-chunkable inputs
+ * (weights, attention keys/values, the second triangle operand) are seen whole by
+ * every segment.  This library is that runtime step only: it takes a region list
+ * with a chunk dimension and chunk length per region (or an activation budget from
+ * which it sizes the lengths, section 3.2), a workspace sized from that plan, and
+ * runs the plan with hand-written HIP kernels.  The compiler passes of the paper
+ * (search, selection, code generation) are not part of it.
+ *
+ * Conventions for every call:
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; the library never
+ *     allocates, frees or retains device memory and never synchronises the stream,
+ *     except where a call says so.  "host" pointers are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Matrices are row-major.  Every weight matrix is [out_features, in_features].
+ *   - Storage dtype AC_BF16: every tensor in HBM (activations, weights, biases, LayerNorm
+ *     gain/shift, workspace) is bfloat16, rounded to nearest-even once per store; all sums
+ *     (GEMM, LayerNorm statistics, softmax, probability-value products, residual adds)
+ *     are fp32.  AC_F32: everything fp32.
+ *   - Return value: AC_OK (0) or a negative ac_status.  No exception or abort crosses
+ *     this boundary; ac_last_error() gives the text of the calling thread's last failure.
+ */
+#ifndef AUTOCHUNK_RT_H
+#define AUTOCHUNK_RT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ac_status {
+  AC_OK = 0,
+  AC_ERR_ARG = -1,                /* null pointer, non-positive size, inconsistent descriptor */
+  AC_ERR_ILLEGAL_CHUNK_DIM = -2,  /* the region reduces over / reshapes across that dim (rules 1-4, section 3.3) */
+  AC_ERR_BUDGET_INFEASIBLE = -3,  /* even the smallest segment exceeds the activation budget */
+  AC_ERR_WORKSPACE = -4,          /* workspace smaller than the plan needs; nothing was launched */
+  AC_ERR_ALIGN = -5,              /* a device pointer is not 256-byte aligned */
+  AC_ERR_HIP = -6,                /* a HIP call failed; text in ac_last_error() */
+  AC_ERR_STATE = -7,              /* weights not bound, or profiling not enabled */
+  AC_ERR_UNSUPPORTED = -8         /* legal, but no kernel here covers that shape or chunk dim */
+} ac_status;
+
+typedef enum ac_workload { AC_TRANSFORMER_STACK = 0, AC_PAIR_STACK = 1 } ac_workload;
+typedef enum ac_dtype { AC_F32 = 0, AC_BF16 = 1 } ac_dtype;
+typedef enum ac_activation { AC_ACT_NONE = 0, AC_ACT_GELU_ERF = 1, AC_ACT_GELU_TANH = 2,
+                             AC_ACT_RELU = 3, AC_ACT_SIGMOID = 4 } ac_activation;
+
+/* Region kinds.  Transformer layer: QKV, ATTENTION, FFN in this order.  Pair-stack block:
+ * TRIMUL_OUT, TRIMUL_IN, TRIATT_START, TRIATT_END, PAIR_TRANSITION in this order. */
+typedef enum ac_region_kind {
+  AC_REGION_QKV = 0,            /* LayerNorm 1 + packed query/key/value projection        */
+  AC_REGION_ATTENTION = 1,      /* attention of a query segment over whole keys/values +
+                                   output projection + residual                           */
+  AC_REGION_FFN = 2,            /* LayerNorm 2 + up projection + activation + down + residual */
+  AC_REGION_TRIMUL_OUT = 3,     /* triangle multiplicative update, outgoing edges         */
+  AC_REGION_TRIMUL_IN = 4,      /* triangle multiplicative update, incoming edges         */
+  AC_REGION_TRIATT_START = 5,   /* triangle self-attention around the starting node       */
+  AC_REGION_TRIATT_END = 6,     /* triangle self-attention around the ending node         */
+  AC_REGION_PAIR_TRANSITION = 7,
+  AC_REGION_KINDS = 8
+} ac_region_kind;
+
+/* Chunk dimensions are named per workload.  Transformer regions see their tensors as
+ * [batch, sequence(query), feature, head_dim, key]; pair regions as [row i, column j,
+ * channel, contraction index k].  Legal (section 3.3: no node of the region reduces over
+ * the dim): batch and sequence for every transformer region; row and column for every
+ * pair region.  Feature, head_dim, key, channel and contraction index are illegal.  Column
+ * chunks are legal but not implemented (AC_ERR_UNSUPPORTED). */
+enum { AC_DIM_BATCH = 0, AC_DIM_SEQ = 1, AC_DIM_FEATURE = 2, AC_DIM_HEAD_DIM = 3, AC_DIM_KEY = 4 };
+enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 };
+
+/* ac_model_desc.flags */
+enum {
+  AC_FLAG_UNFUSED_ELEMENTWISE = 1  /* run bias+activation and residual as standalone passes
+                                      instead of GEMM epilogues (for measuring those passes) */
+};
+
+typedef struct ac_model_desc {
+  int32_t workload;      /* ac_workload */
+  int32_t dtype;         /* ac_dtype: storage type of every tensor */
+  int32_t layers;        /* transformer: number of blocks; pair stack: number of blocks (>= 1) */
+  /* transformer stack: x and y are [batch * seq, d_model] */
+  int32_t batch, seq, d_model, heads, head_dim, d_ffn;
+  int32_t causal;        /* 1: key j visible to query i iff j <= i */
+  int32_t activation;    /* ac_activation of the feed-forward / pair transition */
+  /* pair stack: z is [n_res, n_res, c_z] */
+  int32_t n_res, c_z, c_hidden, tri_heads, tri_head_dim, transition_factor;
+  int32_t flags;
+  float ln_eps;          /* LayerNorm epsilon (biased variance) */
+} ac_model_desc;
+
+typedef struct ac_region_desc {
+  int32_t kind;          /* ac_region_kind */
+  int32_t chunk_dim;     /* AC_DIM_* of the workload */
+  int64_t chunk_len;     /* extent of one segment along chunk_dim ("rows per segment");
+                            n = ceil(extent / chunk_len), the last segment may be short.
+                            0 = largest length whose planned bytes fit the budget. */
+} ac_region_desc;
+
+typedef struct ac_region_info {
+  int32_t kind, chunk_dim;
+  int64_t extent;            /* size of the chunk dim */
+  int64_t chunk_len;         /* chosen rows per segment */
+  int64_t n_segments;        /* the paper's n */
+  uint64_t model_bytes;      /* paper-style sum X + Y + A/n of this region, ops unfused */
+  uint64_t model_bytes_unchunked; /* the same with n = 1 (first activation equation) */
+} ac_region_info;
+
+typedef struct ac_plan_info {
+  uint64_t workspace_bytes;              /* arena the caller must pass to ac_execute */
+  uint64_t io_bytes;                     /* mem(X) + mem(Y) of the whole stack */
+  uint64_t peak_bytes_planned;           /* io_bytes + arena high-water mark */
+  uint64_t peak_bytes_unchunked_planned; /* the same plan with one segment per region */
+  uint64_t peak_bytes_model;             /* max over regions of model_bytes */
+  uint64_t peak_bytes_model_unchunked;   /* max over regions of model_bytes_unchunked */
+  uint64_t weight_bytes;                 /* sum of all weight tensors (not activation memory) */
+  double flops_per_execute;              /* algorithmic flops: causal attention counts j <= i only */
+  int32_t n_weights;                     /* device pointers ac_plan_bind_weights expects */
+  int32_t n_regions;                     /* regions per layer / block */
+  ac_region_info regions[AC_REGION_KINDS];
+} ac_plan_info;
+
+typedef struct ac_weight_info {
+  char name[48];         /* e.g. "L0.w_qkv", "tmo.w_ap" */
+  int64_t rows, cols;    /* [out, in] for matrices; rows = 1 for vectors */
+  int32_t dtype;         /* ac_dtype */
+  int32_t index;
+} ac_weight_info;
+
+typedef struct ac_kernel_stat {
+  char name[32];         /* kernel class: "gemm", "attention", "layernorm", "elementwise", "trimul" */
+  int64_t launches;
+  double total_ms;       /* sum of HIP-event durations of those launches */
+  double flops;          /* algorithmic flops of those launches */
+  double bytes;          /* algorithmic HBM bytes (each operand read once, result written once) */
+} ac_kernel_stat;
+
+typedef struct ac_plan ac_plan;
+
+/*
+ * Build a chunk plan (host only; touches no device).  Section 3.1/3.2: regions, their
+ * chunk settings, and a memory budget in; a plan out.  `regions` lists at most one entry
+ * per region kind of the workload; a kind not listed runs as one segment.  The same
+ * settings apply to every layer.  `act_budget_bytes` (0 = none) bounds, per layer, both
+ * the planned executor bytes and the paper-style model bytes of every region; it sizes the
+ * regions whose chunk_len is 0 and is checked (AC_ERR_BUDGET_INFEASIBLE) for the others.
+ * Errors: AC_ERR_ARG, AC_ERR_ILLEGAL_CHUNK_DIM, AC_ERR_UNSUPPORTED, AC_ERR_BUDGET_INFEASIBLE.
+ * On success *out owns host memory only; release it with ac_plan_destroy.
+ */
+int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, int n_regions,
+                   uint64_t act_budget_bytes, ac_plan** out);
+
+/* Sizes and byte counts of a plan (host only).  `out` is host memory of the caller. */
+int ac_plan_query(const ac_plan* plan, ac_plan_info* out);
+
+/* Name, shape and dtype of weight tensor `index` (0 <= index < n_weights), in bind order. */
+int ac_plan_weight_info(const ac_plan* plan, int index, ac_weight_info* out);
+
+/*
+ * Hand the plan the device addresses of its weights, in ac_plan_weight_info order.  The
+ * pointers stay owned by the caller and must outlive every ac_execute of this plan.  Each
+ * must be 256-byte aligned (AC_ERR_ALIGN); n_ptrs must equal n_weights (AC_ERR_ARG).
+ */
+int ac_plan_bind_weights(ac_plan* plan, const void* const* dev_ptrs, int n_ptrs);
+
+/*
+ * Run the plan (section 2.2; section 3.2 "runtime pass"): for each layer, for each region,
+ * for each segment in order, compute the segment's slice of the region output.  Enqueues
+ * kernels on `stream` and returns without waiting.  x_dev [tokens, d_model] (or
+ * [n_res, n_res, c_z]) is only read; y_dev has the same shape and must not overlap x_dev;
+ * workspace_dev is scratch of at least workspace_bytes (else AC_ERR_WORKSPACE, nothing
+ * launched).  All three must be 256-byte aligned.  *measured_peak_bytes (host, may be NULL)
+ * receives io_bytes + the highest workspace offset actually handed to a kernel during
+ * this call, which the host tracks while binding buffers (no device round trip).
+ */
+int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_dev,
+               uint64_t workspace_bytes, void* stream, uint64_t* measured_peak_bytes);
+
+/* Free the plan's host memory (and its profiling events, if any).  NULL is allowed. */
+void ac_plan_destroy(ac_plan* plan);
+
+/*
+ * Per-kernel-class timing with HIP events on the execute stream.  While enabled, every
+ * kernel launch of ac_execute is bracketed by two events.  ac_plan_read_profile waits for
+ * the recorded events (hipEventSynchronize), accumulates into at most `max_stats` entries
+ * of `out` (host), stores the count in *n_out and clears the record.
+ */
+int ac_plan_set_profiling(ac_plan* plan, int enabled);
+int ac_plan_read_profile(ac_plan* plan, ac_kernel_stat* out, int max_stats, int* n_out);
+
+const char* ac_status_string(int status);
+const char* ac_last_error(void);   /* thread-local; valid until the thread's next failing call */
+
+/* ------------------------------------------------------------------------------------
+ * The kernels of the path, callable one at a time (what a region runs on one segment).
+ * All pointers are device pointers, 16-byte aligned, with row strides (ld*, in elements)
+ * that are multiples of 8 (bf16) or 4 (fp32).  They enqueue on `stream` and return.
+ * ------------------------------------------------------------------------------------ */
+
+/* y[r,:] = (x[r,:] - mean) / sqrt(var + eps) * gain + shift over `cols`; biased variance. */
+int ac_op_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,
+                    int64_t ldy, int64_t rows, int64_t cols, float eps, int dtype, void* stream);
+
+/*
+ * r[m,n] = epilogue(sum_k a[m,k] * w[n,k]): + bias[n] (if bias), activation (ac_activation),
+ * * mul[m,n] (if mul), + residual[m,n] (if residual), in that order, rounded once on store.
+ * Columns n < n_split are stored row-major, out[m * ldo + n].  Columns n >= n_split (only
+ * if out_t != NULL; otherwise every column is row-major) are stored strided:
+ *   out_t[(m / t_period) * t_s1 + (m % t_period) * t_s2 + (n - n_split) * t_s3],
+ * which writes a transposed or channel-major copy without a separate pass (t_period <= 0
+ * means "no period": the offset is m * t_s2 + (n - n_split) * t_s3).
+ */
+int ac_op_linear(const void* a, int64_t lda, const void* w, int64_t ldw, const void* bias,
+                 const void* mul, int64_t ldmul, const void* residual, int64_t ldr,
+                 void* out, int64_t ldo,
+                 void* out_t, int64_t n_split, int64_t t_period, int64_t t_s1, int64_t t_s2,
+                 int64_t t_s3, int64_t m, int64_t n, int64_t k, int activation, int dtype,
+                 void* stream);
+
+/*
+ * Attention of `sq` query rows over `sk` keys, `heads` heads of `head_dim`, `batch`
+ * independent problems: ctx = softmax(q k^T / sqrt(head_dim) + bias [causal mask]) v
+ * [* gate].  q/k/v/ctx/gate rows of one problem are ld* apart, heads are contiguous
+ * head_dim-wide column blocks, and problem b starts at b * stride_*_batch elements.
+ * With v_transposed != 0 the values are read as v[(h * head_dim + d) * ldv + key] (the
+ * layout the matrix-core kernel needs; ac_op_linear can write it with its strided store),
+ * otherwise as v[key * ldv + h * head_dim + d] (served by a slower kernel).
+ * Causal: query row r stands at position q_offset + r and sees keys j <= q_offset + r.
+ * bias (may be NULL) points at the bias row of query row 0: bias[h * stride_bias_head +
+ * r * ld_bias + key]; it is shared by all `batch` problems.
+ * The scores never leave the chip.
+ */
+int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch,
+                    const void* k, int64_t ldk, int64_t stride_k_batch,
+                    const void* v, int64_t ldv, int64_t stride_v_batch, int v_transposed,
+                    const void* bias, int64_t ld_bias, int64_t stride_bias_head,
+                    const void* gate, int64_t ldg, int64_t stride_g_batch,
+                    void* ctx, int64_t ldc, int64_t stride_c_batch,
+                    int64_t batch, int64_t sq, int64_t sk, int heads, int head_dim,
+                    int causal, int64_t q_offset, int dtype, void* stream);
+
+/* y = activation(x + bias[col]) over [rows, cols]; bias may be NULL. */
+int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy,
+                   int64_t rows, int64_t cols, int activation, int dtype, void* stream);
+
+/* y = a + b  (op 0)  or  y = a * b  (op 1) over [rows, cols]. */
+int ac_op_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
+                 int64_t rows, int64_t cols, int op, int dtype, void* stream);
+
+/* dst[c * ldd + r] = src[r * lds + c] for a [rows, cols] matrix (e.g. values -> v_transposed). */
+int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows,
+                    int64_t cols, int dtype, void* stream);
+
+/*
+ * Triangle contraction on `ni` output rows: out[i,j,c] = sum_k a[i,k,c] * b[j,k,c], with a
+ * addressed as a[i * sa_i + k * sa_k + c], b as b[j * sb_j + k * sb_k + c] and out as
+ * [ni, nj, channels] contiguous; the incoming form is the same call with the i/k strides
+ * of a (and j/k of b) exchanged.  Storage bf16, fp32 accumulation.
+ */
+int ac_op_triangle_contract(const void* a, int64_t sa_i, int64_t sa_k,
+                            const void* b, int64_t sb_j, int64_t sb_k,
+                            void* out, int64_t ni, int64_t nj, int64_t nk, int channels,
+                            int dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUTOCHUNK_RT_H */

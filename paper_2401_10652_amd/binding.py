@@ -1,0 +1,297 @@
+"""ctypes binding of libautochunk_rt.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (``ac_*``); tensors are
+torch tensors used purely as device buffers (``data_ptr()``), and the stream handed to
+the library is torch's current stream.  Nothing is computed in Python, and there is no
+fallback: if the shared library has not been built, ``lib()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+from .build import LIB_PATH
+
+AC_OK = 0
+AC_ERR_ARG, AC_ERR_ILLEGAL_CHUNK_DIM, AC_ERR_BUDGET_INFEASIBLE, AC_ERR_WORKSPACE = -1, -2, -3, -4
+AC_ERR_ALIGN, AC_ERR_HIP, AC_ERR_STATE, AC_ERR_UNSUPPORTED = -5, -6, -7, -8
+AC_TRANSFORMER_STACK, AC_PAIR_STACK = 0, 1
+AC_F32, AC_BF16 = 0, 1
+AC_ACT_NONE, AC_ACT_GELU_ERF, AC_ACT_GELU_TANH, AC_ACT_RELU, AC_ACT_SIGMOID = 0, 1, 2, 3, 4
+(AC_REGION_QKV, AC_REGION_ATTENTION, AC_REGION_FFN, AC_REGION_TRIMUL_OUT, AC_REGION_TRIMUL_IN,
+ AC_REGION_TRIATT_START, AC_REGION_TRIATT_END, AC_REGION_PAIR_TRANSITION, AC_REGION_KINDS) = range(9)
+AC_DIM_BATCH, AC_DIM_SEQ, AC_DIM_FEATURE, AC_DIM_HEAD_DIM, AC_DIM_KEY = range(5)
+AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
+AC_FLAG_UNFUSED_ELEMENTWISE = 1
+
+ACTIVATIONS = {"none": AC_ACT_NONE, "gelu_erf": AC_ACT_GELU_ERF, "gelu_tanh": AC_ACT_GELU_TANH,
+               "relu": AC_ACT_RELU, "sigmoid": AC_ACT_SIGMOID}
+DTYPES = {"f32": AC_F32, "bf16": AC_BF16}
+
+
+class ac_model_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "workload", "dtype", "layers", "batch", "seq", "d_model", "heads", "head_dim", "d_ffn",
+        "causal", "activation", "n_res", "c_z", "c_hidden", "tri_heads", "tri_head_dim",
+        "transition_factor", "flags")] + [("ln_eps", C.c_float)]
+
+
+class ac_region_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("chunk_dim", C.c_int32), ("chunk_len", C.c_int64)]
+
+
+class ac_region_info(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("chunk_dim", C.c_int32), ("extent", C.c_int64),
+                ("chunk_len", C.c_int64), ("n_segments", C.c_int64), ("model_bytes", C.c_uint64),
+                ("model_bytes_unchunked", C.c_uint64)]
+
+
+class ac_plan_info(C.Structure):
+    _fields_ = [("workspace_bytes", C.c_uint64), ("io_bytes", C.c_uint64),
+                ("peak_bytes_planned", C.c_uint64), ("peak_bytes_unchunked_planned", C.c_uint64),
+                ("peak_bytes_model", C.c_uint64), ("peak_bytes_model_unchunked", C.c_uint64),
+                ("weight_bytes", C.c_uint64), ("flops_per_execute", C.c_double),
+                ("n_weights", C.c_int32), ("n_regions", C.c_int32),
+                ("regions", ac_region_info * AC_REGION_KINDS)]
+
+
+class ac_weight_info(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("rows", C.c_int64), ("cols", C.c_int64),
+                ("dtype", C.c_int32), ("index", C.c_int32)]
+
+
+class ac_kernel_stat(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+I64, U64, VP, INT = C.c_int64, C.c_uint64, C.c_void_p, C.c_int
+
+# name -> (restype, argtypes): every symbol include/autochunk_rt.h declares.
+SIGNATURES = {
+    "ac_plan_create": (INT, [C.POINTER(ac_model_desc), C.POINTER(ac_region_desc), INT, U64, C.POINTER(VP)]),
+    "ac_plan_query": (INT, [VP, C.POINTER(ac_plan_info)]),
+    "ac_plan_weight_info": (INT, [VP, INT, C.POINTER(ac_weight_info)]),
+    "ac_plan_bind_weights": (INT, [VP, C.POINTER(VP), INT]),
+    "ac_execute": (INT, [VP, VP, VP, VP, U64, VP, C.POINTER(U64)]),
+    "ac_plan_destroy": (None, [VP]),
+    "ac_plan_set_profiling": (INT, [VP, INT]),
+    "ac_plan_read_profile": (INT, [VP, C.POINTER(ac_kernel_stat), INT, C.POINTER(INT)]),
+    "ac_status_string": (C.c_char_p, [INT]),
+    "ac_last_error": (C.c_char_p, []),
+    "ac_op_layernorm": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
+    "ac_op_linear": (INT, [VP, I64, VP, I64, VP, VP, I64, VP, I64, VP, I64, VP, I64, I64, I64, I64, I64,
+                           I64, I64, I64, INT, INT, VP]),
+    "ac_op_attention": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, INT, VP, I64, I64, VP, I64, I64,
+                              VP, I64, I64, I64, I64, I64, INT, INT, INT, I64, INT, VP]),
+    "ac_op_bias_act": (INT, [VP, I64, VP, VP, I64, I64, I64, INT, INT, VP]),
+    "ac_op_binary": (INT, [VP, I64, VP, I64, VP, I64, I64, I64, INT, INT, VP]),
+    "ac_op_transpose": (INT, [VP, I64, VP, I64, I64, I64, INT, VP]),
+    "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, INT, INT, VP]),
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2401_10652_amd.build)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+class AcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().ac_last_error().decode()
+        super().__init__(f"{where}: {lib().ac_status_string(status).decode()} ({status}): {msg}")
+
+
+def _check(status, where):
+    if status != AC_OK:
+        raise AcError(status, where)
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dt(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return AC_BF16
+    if t.dtype == torch.float32:
+        return AC_F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def transformer_desc(cfg, flags=0) -> ac_model_desc:
+    m = ac_model_desc()
+    m.workload = AC_TRANSFORMER_STACK
+    m.dtype = DTYPES[cfg.dtype]
+    m.layers, m.batch, m.seq, m.d_model = cfg.layers, cfg.batch, cfg.seq, cfg.d_model
+    m.heads, m.head_dim, m.d_ffn = cfg.heads, cfg.head_dim, cfg.d_ffn
+    m.causal = int(cfg.causal)
+    m.activation = ACTIVATIONS[cfg.activation]
+    m.flags = flags
+    m.ln_eps = cfg.ln_eps
+    return m
+
+
+def pair_desc(cfg, flags=0) -> ac_model_desc:
+    m = ac_model_desc()
+    m.workload = AC_PAIR_STACK
+    m.dtype = DTYPES[cfg.dtype]
+    m.layers = 1
+    m.n_res, m.c_z, m.c_hidden = cfg.n_res, cfg.c_z, cfg.c_hidden
+    m.tri_heads, m.tri_head_dim, m.transition_factor = cfg.heads, cfg.head_dim, cfg.transition_factor
+    m.activation = ACTIVATIONS[cfg.activation]
+    m.flags = flags
+    m.ln_eps = cfg.ln_eps
+    return m
+
+
+class Plan:
+    """Owns one ``ac_plan*``; methods carry the names of the entry points they call."""
+
+    def __init__(self, model: ac_model_desc, regions=(), act_budget_bytes=0):
+        arr = (ac_region_desc * max(1, len(regions)))()
+        for i, (kind, dim, length) in enumerate(regions):
+            arr[i].kind, arr[i].chunk_dim, arr[i].chunk_len = kind, dim, length
+        self._h = VP()
+        self._keep = []
+        _check(lib().ac_plan_create(C.byref(model), arr, len(regions), act_budget_bytes, C.byref(self._h)),
+               "ac_plan_create")
+        self.model = model
+
+    def ac_plan_query(self) -> ac_plan_info:
+        info = ac_plan_info()
+        _check(lib().ac_plan_query(self._h, C.byref(info)), "ac_plan_query")
+        return info
+
+    def ac_plan_weight_info(self, index) -> ac_weight_info:
+        wi = ac_weight_info()
+        _check(lib().ac_plan_weight_info(self._h, index, C.byref(wi)), "ac_plan_weight_info")
+        return wi
+
+    def weight_names(self):
+        n = self.ac_plan_query().n_weights
+        return [self.ac_plan_weight_info(i).name.decode() for i in range(n)]
+
+    def ac_plan_bind_weights(self, tensors):
+        ptrs = (VP * len(tensors))(*[t.data_ptr() for t in tensors])
+        _check(lib().ac_plan_bind_weights(self._h, ptrs, len(tensors)), "ac_plan_bind_weights")
+        self._keep = list(tensors)
+
+    def ac_execute(self, x, y, workspace) -> int:
+        peak = U64(0)
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(lib().ac_execute(self._h, _ptr(x), _ptr(y), _ptr(workspace), nbytes, _stream(), C.byref(peak)),
+               "ac_execute")
+        return peak.value
+
+    def ac_plan_set_profiling(self, enabled):
+        _check(lib().ac_plan_set_profiling(self._h, int(enabled)), "ac_plan_set_profiling")
+
+    def ac_plan_read_profile(self):
+        stats = (ac_kernel_stat * 8)()
+        n = INT(0)
+        _check(lib().ac_plan_read_profile(self._h, stats, 8, C.byref(n)), "ac_plan_read_profile")
+        return [dict(name=s.name.decode(), launches=s.launches, total_ms=s.total_ms, flops=s.flops,
+                     bytes=s.bytes) for s in stats[:n.value]]
+
+    def close(self):
+        if self._h:
+            lib().ac_plan_destroy(self._h)
+            self._h = VP()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- single kernels -----------------------------------------------------------------------
+
+def ac_op_layernorm(x, gain, shift, y, eps=1e-5):
+    rows, cols = x.shape
+    _check(lib().ac_op_layernorm(_ptr(x), x.stride(0), _ptr(gain), _ptr(shift), _ptr(y), y.stride(0),
+                                 rows, cols, eps, _dt(x), _stream()), "ac_op_layernorm")
+
+
+def ac_op_linear(a, w, out, bias=None, mul=None, residual=None, activation=AC_ACT_NONE,
+                 out_t=None, n_split=None, t_period=0, t_s1=0, t_s2=1, t_s3=0):
+    m, k = a.shape
+    n = w.shape[0]
+    if n_split is None:
+        n_split = n
+    _check(lib().ac_op_linear(
+        _ptr(a), a.stride(0), _ptr(w), w.stride(0), _ptr(bias),
+        _ptr(mul), 0 if mul is None else mul.stride(0),
+        _ptr(residual), 0 if residual is None else residual.stride(0),
+        _ptr(out), 0 if out is None else out.stride(0),
+        _ptr(out_t), n_split, t_period, t_s1, t_s2, t_s3, m, n, k, activation, _dt(a), _stream()),
+        "ac_op_linear")
+
+
+def ac_op_attention(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bias=None, gate=None,
+                    v_transposed=False, batch=1, strides=None):
+    """q [sq, >=heads*head_dim], k [sk, ..], v [sk, ..] or v^T [heads*head_dim, sk]; one problem
+    unless ``batch`` and ``strides`` = (q, k, v, gate, ctx batch strides in elements) are given."""
+    sq, sk = q.shape[0], k.shape[0]
+    sb = strides or (0, 0, 0, 0, 0)
+    _check(lib().ac_op_attention(
+        _ptr(q), q.stride(0), sb[0], _ptr(k), k.stride(0), sb[1], _ptr(v), v.stride(0), sb[2],
+        int(v_transposed),
+        _ptr(bias), 0 if bias is None else bias.stride(1), 0 if bias is None else bias.stride(0),
+        _ptr(gate), 0 if gate is None else gate.stride(0), sb[3],
+        _ptr(ctx), ctx.stride(0), sb[4], batch, sq, sk, heads, head_dim, int(causal), q_offset,
+        _dt(q), _stream()), "ac_op_attention")
+
+
+def ac_op_bias_act(x, bias, y, activation):
+    rows, cols = x.shape
+    _check(lib().ac_op_bias_act(_ptr(x), x.stride(0), _ptr(bias), _ptr(y), y.stride(0), rows, cols,
+                                activation, _dt(x), _stream()), "ac_op_bias_act")
+
+
+def ac_op_binary(a, b, y, op):
+    rows, cols = a.shape
+    _check(lib().ac_op_binary(_ptr(a), a.stride(0), _ptr(b), b.stride(0), _ptr(y), y.stride(0), rows, cols,
+                              op, _dt(a), _stream()), "ac_op_binary")
+
+
+def ac_op_transpose(src, dst):
+    rows, cols = src.shape
+    _check(lib().ac_op_transpose(_ptr(src), src.stride(0), _ptr(dst), dst.stride(0), rows, cols, _dt(src),
+                                 _stream()), "ac_op_transpose")
+
+
+# ---- helpers for callers (buffers only) ------------------------------------------------------
+
+def to_device(arr, dtype: str):
+    """Upload a host fp32 array that already holds storage-exact values."""
+    import numpy as np
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32))
+    return t.to(device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
+
+
+def empty_workspace(nbytes: int):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")

@@ -1,0 +1,397 @@
+// Query-chunked attention: ctx = softmax(q k^T / sqrt(d_h) [+ bias] [causal]) v [* gate]
+// for the query rows of one segment against the WHOLE key/value set (the non-chunkable
+// inputs of the attention region, AutoChunk section 3.1).  The scores never reach HBM:
+// the intermediate activation that chunking divides by n (section 2.2, second activation
+// equation) is here a 32x64 tile per wave that lives in registers, with a running
+// maximum and sum per query row.
+//
+// bf16 MFMA kernel.  One wave owns 32 query rows; a block of 4 waves shares 64-key tiles
+// of K (row-major, [key][d]) and of V^T ([d][key], as written by the projection's strided
+// store) staged in double-buffered LDS.  The wave computes the TRANSPOSED score tile
+// S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a lane holds one query column and 16
+// key rows per 32-key tile: the softmax max/sum over keys are in-lane reductions plus one
+// exchange between the two half-waves, the rescale factor is a per-lane scalar, and the
+// probabilities already sit in the register layout the next MFMA wants for its B operand
+// (O^T = V^T P^T).  The k-slot order of that second MFMA is a fixed permutation of the keys
+// of the tile, applied identically to P (registers) and V^T (two 8-byte LDS reads).
+// Key tiles are visited in the same order for every query row regardless of which segment
+// the row belongs to, so results do not depend on the chunk length.
+//
+// Generic kernel (fp32, odd head sizes, row-major v): one thread per query row.
+#include "common.h"
+
+namespace ac {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kXcdCount = 8;
+
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t pid, int64_t nb) {
+  const int64_t q = nb / kXcdCount, r = nb % kXcdCount;
+  const int64_t x = pid % kXcdCount, idx = pid / kXcdCount;
+  return x * q + (x < r ? x : r) + idx;
+}
+
+// ------------------------------------------------------------------------------------
+// Generic kernel.
+// ------------------------------------------------------------------------------------
+template <typename T, int DH>
+__global__ void __launch_bounds__(128) attention_rows(AttnArgs a) {
+  constexpr int TK = 32;
+  __shared__ float sK[TK][DH + 1];
+  __shared__ float sV[TK][DH + 1];
+  const int64_t b = blockIdx.z;
+  const int h = blockIdx.y;
+  const int64_t row = (int64_t)blockIdx.x * 128 + threadIdx.x;
+  const bool live = row < a.sq;
+  const int64_t r = live ? row : a.sq - 1;
+  const T* q = (const T*)a.q + b * a.sq_b + r * a.ldq + h * DH;
+  const T* kb = (const T*)a.k + b * a.sk_b + h * DH;
+  const T* vb = (const T*)a.v + b * a.sv_b;
+  const T* bias = a.bias ? (const T*)a.bias + h * a.s_bias_h + r * a.ld_bias : nullptr;
+  const float scale = rsqrtf((float)DH);
+  float qv[DH], o[DH];
+#pragma unroll
+  for (int d = 0; d < DH; ++d) { qv[d] = Elem<T>::ld(q + d) * scale; o[d] = 0.f; }
+  float m = -INFINITY, l = 0.f;
+  const int64_t qpos = a.q_offset + r;
+  // keys any row of this block can see
+  int64_t kend = a.sk;
+  if (a.causal) {
+    const int64_t last = a.q_offset + ((int64_t)blockIdx.x * 128 + 127 < a.sq - 1 ? (int64_t)blockIdx.x * 128 + 127 : a.sq - 1);
+    if (last + 1 < kend) kend = last + 1;
+  }
+  for (int64_t k0 = 0; k0 < kend; k0 += TK) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < TK * DH; idx += 128) {
+      const int j = idx / DH, d = idx % DH;
+      const int64_t key = k0 + j;
+      float kv = 0.f, vv = 0.f;
+      if (key < a.sk) {
+        kv = Elem<T>::ld(kb + key * a.ldk + d);
+        vv = a.v_transposed ? Elem<T>::ld(vb + (int64_t)(h * DH + d) * a.ldv + key)
+                            : Elem<T>::ld(vb + key * a.ldv + h * DH + d);
+      }
+      sK[j][d] = kv;
+      sV[j][d] = vv;
+    }
+    __syncthreads();
+    float s[TK];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < TK; ++j) {
+      float acc = 0.f;
+#pragma unroll
+      for (int d = 0; d < DH; ++d) acc = fmaf(qv[d], sK[j][d], acc);
+      const int64_t key = k0 + j;
+      if (bias && key < a.sk) acc += Elem<T>::ld(bias + key);
+      if (key >= a.sk || (a.causal && key > qpos)) acc = -INFINITY;
+      s[j] = acc;
+      mx = fmaxf(mx, acc);
+    }
+    const float m_new = fmaxf(m, mx);
+    if (m_new == -INFINITY) continue;          // nothing visible yet for this row
+    const float alpha = __expf(m - m_new);     // m = -inf gives 0
+    l *= alpha;
+#pragma unroll
+    for (int d = 0; d < DH; ++d) o[d] *= alpha;
+#pragma unroll
+    for (int j = 0; j < TK; ++j) {
+      const float p = __expf(s[j] - m_new);
+      l += p;
+#pragma unroll
+      for (int d = 0; d < DH; ++d) o[d] = fmaf(p, sV[j][d], o[d]);
+    }
+    m = m_new;
+  }
+  if (!live) return;
+  const float inv = 1.0f / l;
+  T* out = (T*)a.ctx + b * a.sc_b + row * a.ldc + h * DH;
+  const T* gate = a.gate ? (const T*)a.gate + b * a.sg_b + row * a.ldg + h * DH : nullptr;
+#pragma unroll
+  for (int d = 0; d < DH; ++d) {
+    float v = o[d] * inv;
+    if (gate) v *= Elem<T>::ld(gate + d);
+    Elem<T>::st(out + d, v);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// bf16 MFMA kernel.
+// ------------------------------------------------------------------------------------
+constexpr int kQB = 128;   // query rows per block (4 waves x 32)
+constexpr int kKB = 64;    // keys per LDS tile
+
+template <int DH, bool CAUSAL, bool BIAS>
+__global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
+  constexpr int KROW = DH + 8;        // padded K row (elements)
+  constexpr int VROW = kKB + 8;       // padded V^T row
+  constexpr int KS = DH / 16;         // k-steps of the score MFMA
+  constexpr int DT = DH / 32;         // 32-wide output tiles over d
+  constexpr int K_CHUNKS = kKB * (DH / 8) / 256;   // 16-byte chunks per thread, K tile
+  constexpr int V_CHUNKS = DH * (kKB / 8) / 256;   // and V^T tile
+  static_assert(K_CHUNKS >= 1 && V_CHUNKS >= 1, "tile too small for 256 threads");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);     // [2][kKB][KROW]
+  bf16_t* sV = sK + 2 * kKB * KROW;                      // [2][DH][VROW]
+
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int l32 = lane % 32, half = lane / 32;
+  const int64_t nqb = (a.sq + kQB - 1) / kQB;
+  const int64_t t = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int64_t bh = t / nqb;
+  int64_t qb = t % nqb;
+  if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
+  const int64_t b = bh / a.heads;
+  const int h = (int)(bh % a.heads);
+  const int64_t q0 = qb * kQB;
+
+  const bf16_t* kbase = (const bf16_t*)a.k + b * a.sk_b + h * DH;
+  const bf16_t* vbase = (const bf16_t*)a.v + b * a.sv_b + (int64_t)h * DH * a.ldv;
+
+  // this lane's query row (clamped; clamped rows compute but never store)
+  const int64_t row = q0 + wave * 32 + l32;
+  const int64_t rowc = row < a.sq ? row : a.sq - 1;
+  const int64_t qpos = a.q_offset + rowc;
+  bf16x8 qf[KS];
+  {
+    const bf16_t* qp = (const bf16_t*)a.q + b * a.sq_b + rowc * a.ldq + h * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+  const bf16_t* bias_row = BIAS ? (const bf16_t*)a.bias + h * a.s_bias_h + rowc * a.ld_bias : nullptr;
+
+  int64_t kv_end = a.sk;
+  if (CAUSAL) {
+    int64_t last = q0 + kQB - 1; if (last > a.sq - 1) last = a.sq - 1;
+    if (a.q_offset + last + 1 < kv_end) kv_end = a.q_offset + last + 1;
+  }
+  const int64_t n_tiles = (kv_end + kKB - 1) / kKB;
+  // last key position any row of this wave may see (wave-uniform)
+  int64_t wave_last = q0 + wave * 32 + 31; if (wave_last > a.sq - 1) wave_last = a.sq - 1;
+  wave_last += a.q_offset;
+
+  // staging: which chunks of a K tile / V^T tile this thread moves
+  int k_row[K_CHUNKS], k_col[K_CHUNKS], v_row[V_CHUNKS], v_col[V_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < K_CHUNKS; ++i) { const int c = tid + 256 * i; k_row[i] = c / (DH / 8); k_col[i] = (c % (DH / 8)) * 8; }
+#pragma unroll
+  for (int i = 0; i < V_CHUNKS; ++i) { const int c = tid + 256 * i; v_row[i] = c / (kKB / 8); v_col[i] = (c % (kKB / 8)) * 8; }
+  bf16x8 k_reg[K_CHUNKS], v_reg[V_CHUNKS];
+
+  auto load_tile = [&](int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < K_CHUNKS; ++i) {
+      int64_t key = k0 + k_row[i]; if (key > a.sk - 1) key = a.sk - 1;
+      k_reg[i] = *reinterpret_cast<const bf16x8*>(kbase + key * a.ldk + k_col[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < V_CHUNKS; ++i) {
+      const int64_t key = k0 + v_col[i];
+      const bf16_t* src = vbase + (int64_t)v_row[i] * a.ldv + key;
+      if (key + 8 <= a.sk) {
+        v_reg[i] = *reinterpret_cast<const bf16x8*>(src);
+      } else {   // ragged end of the key range: zero-fill so that 0 * v stays 0
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v_reg[i][j] = key + j < a.sk ? src[j] : (bf16_t)0.0f;
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+    bf16_t* dk = sK + buf * kKB * KROW;
+    bf16_t* dv = sV + buf * DH * VROW;
+#pragma unroll
+    for (int i = 0; i < K_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(dk + k_row[i] * KROW + k_col[i]) = k_reg[i];
+#pragma unroll
+    for (int i = 0; i < V_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(dv + v_row[i] * VROW + v_col[i]) = v_reg[i];
+  };
+
+  f32x16 acc_o[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float scale2 = rsqrtf((float)DH) * kLog2e;
+
+  if (n_tiles > 0) { load_tile(0); store_tile(0); }
+  __syncthreads();
+
+  for (int64_t kt = 0; kt < n_tiles; ++kt) {
+    const int buf = (int)(kt & 1);
+    const int64_t k0 = kt * kKB;
+    const bool more = kt + 1 < n_tiles;
+    if (more) load_tile(k0 + kKB);
+
+    if (!CAUSAL || k0 <= wave_last) {
+      // ---- S^T = K Q^T for two 32-key tiles
+      f32x16 acc_s[2];
+      const bf16_t* ck = sK + buf * kKB * KROW + l32 * KROW + half * 8;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_s[tt][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ck + tt * 32 * KROW + ks * 16);
+          acc_s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[tt], 0, 0, 0);
+        }
+      }
+      // ---- scale, bias, mask (log2 domain); lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4
+      const bool need_mask = (k0 + kKB > a.sk) || (CAUSAL && k0 + kKB - 1 > a.q_offset + q0 + wave * 32);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int64_t key = k0 + tt * 32 + 8 * g4 + 4 * half;
+          float bv[4] = {0.f, 0.f, 0.f, 0.f};
+          if (BIAS) {
+            if (key < a.sk) {   // sk % 4 == 0 on this path: a group of 4 keys is all in or all out
+              const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias_row + key);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) bv[j] = bf2f(bb[j]) * kLog2e;
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            float s = acc_s[tt][4 * g4 + j] * scale2 + bv[j];
+            if (need_mask) {
+              const int64_t kj = key + j;
+              if (kj >= a.sk || (CAUSAL && kj > qpos)) s = -INFINITY;
+            }
+            acc_s[tt][4 * g4 + j] = s;
+            mx = fmaxf(mx, s);
+          }
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      m_run = m_new;
+      float psum = 0.f;
+      bf16x8 pf[2][2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(acc_s[tt][r] - m_safe);
+          psum += p;
+          pf[tt][r / 8][r % 8] = f2bf(p);
+        }
+      l_run = l_run * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < DT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+      // ---- O^T += V^T P^T
+      const bf16_t* cv = sV + buf * DH * VROW + l32 * VROW + 4 * half;
+#pragma unroll
+      for (int i = 0; i < DT; ++i)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const bf16_t* p = cv + i * 32 * VROW + tt * 32 + 16 * u;
+            const bf16x4 lo = *reinterpret_cast<const bf16x4*>(p);
+            const bf16x4 hi = *reinterpret_cast<const bf16x4*>(p + 8);
+            const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt][u], acc_o[i], 0, 0, 0);
+          }
+    }
+    if (more) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  if (row >= a.sq) return;
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  bf16_t* out = (bf16_t*)a.ctx + b * a.sc_b + row * a.ldc + h * DH;
+  const bf16_t* gate = a.gate ? (const bf16_t*)a.gate + b * a.sg_b + row * a.ldg + h * DH : nullptr;
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int d = i * 32 + 8 * g4 + 4 * half;
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = acc_o[i][4 * g4 + j] * inv;
+      if (gate) {
+        const bf16x4 gg = *reinterpret_cast<const bf16x4*>(gate + d);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] *= bf2f(gg[j]);
+      }
+      const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+      *reinterpret_cast<bf16x4*>(out + d) = o;
+    }
+}
+
+template <int DH, bool CAUSAL, bool BIAS>
+static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
+  auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS>;
+  constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int64_t nqb = (a.sq + kQB - 1) / kQB;
+  const int64_t blocks = nqb * a.heads * a.batch;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int DH>
+static hipError_t mfma_attn_dispatch(const AttnArgs& a, hipStream_t s) {
+  if (a.causal) {
+    if (a.bias) return mfma_attn_launch<DH, true, true>(a, s);
+    return mfma_attn_launch<DH, true, false>(a, s);
+  }
+  if (a.bias) return mfma_attn_launch<DH, false, true>(a, s);
+  return mfma_attn_launch<DH, false, false>(a, s);
+}
+
+static bool al(const void* p, uintptr_t n) { return p == nullptr || ((uintptr_t)p % n) == 0; }
+
+static bool mfma_attn_eligible(const AttnArgs& a) {
+  if (a.dtype != AC_BF16 || !a.v_transposed) return false;
+  if (a.head_dim != 32 && a.head_dim != 64 && a.head_dim != 128) return false;
+  if (a.ldq % 8 || a.ldk % 8 || a.ldv % 8 || a.sq_b % 8 || a.sk_b % 8 || a.sv_b % 8) return false;
+  if (a.ldc % 4 || a.sc_b % 4) return false;
+  if (!al(a.q, 16) || !al(a.k, 16) || !al(a.v, 16) || !al(a.ctx, 8)) return false;
+  if (a.bias && (a.sk % 4 || a.ld_bias % 4 || a.s_bias_h % 4 || !al(a.bias, 8))) return false;
+  if (a.gate && (a.ldg % 4 || a.sg_b % 4 || !al(a.gate, 8))) return false;
+  return true;
+}
+
+template <typename T>
+static hipError_t generic_attn_dispatch(const AttnArgs& a, hipStream_t s) {
+  dim3 grid((unsigned)((a.sq + 127) / 128), (unsigned)a.heads, (unsigned)a.batch);
+  switch (a.head_dim) {
+    case 8: hipLaunchKernelGGL((attention_rows<T, 8>), grid, dim3(128), 0, s, a); break;
+    case 16: hipLaunchKernelGGL((attention_rows<T, 16>), grid, dim3(128), 0, s, a); break;
+    case 32: hipLaunchKernelGGL((attention_rows<T, 32>), grid, dim3(128), 0, s, a); break;
+    case 64: hipLaunchKernelGGL((attention_rows<T, 64>), grid, dim3(128), 0, s, a); break;
+    case 128: hipLaunchKernelGGL((attention_rows<T, 128>), grid, dim3(128), 0, s, a); break;
+    default: return hipErrorNotSupported;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+  if (a.batch <= 0 || a.sq <= 0 || a.heads <= 0) return hipSuccess;
+  if (a.sk <= 0) return hipErrorInvalidValue;
+  if (mfma_attn_eligible(a)) {
+    switch (a.head_dim) {
+      case 32: return mfma_attn_dispatch<32>(a, s);
+      case 64: return mfma_attn_dispatch<64>(a, s);
+      default: return mfma_attn_dispatch<128>(a, s);
+    }
+  }
+  if (a.dtype == AC_BF16) return generic_attn_dispatch<bf16_t>(a, s);
+  return generic_attn_dispatch<float>(a, s);
+}
+
+}  // namespace ac

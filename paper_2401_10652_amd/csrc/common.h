@@ -1,0 +1,142 @@
+// Shared device helpers and the internal launch interface of the kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/autochunk_rt.h"
+
+namespace ac {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return static_cast<float>(v); }
+__device__ __forceinline__ bf16_t f2bf(float v) { return static_cast<bf16_t>(v); }  // nearest-even
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kVec = 4;  // elements per 16-byte access
+  __device__ static __forceinline__ float ld(const float* p) { return *p; }
+  __device__ static __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+  __device__ static __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+// 16-byte vector load / store of kVec elements, widened to fp32.
+__device__ __forceinline__ void load_vec(const float* p, float (&v)[4]) {
+  f32x4 t = *reinterpret_cast<const f32x4*>(p);
+  v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+}
+__device__ __forceinline__ void load_vec(const bf16_t* p, float (&v)[8]) {
+  bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = bf2f(t[i]);
+}
+__device__ __forceinline__ void store_vec(float* p, const float (&v)[4]) {
+  f32x4 t = {v[0], v[1], v[2], v[3]};
+  *reinterpret_cast<f32x4*>(p) = t;
+}
+__device__ __forceinline__ void store_vec(bf16_t* p, const float (&v)[8]) {
+  bf16x8 t;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t[i] = f2bf(v[i]);
+  *reinterpret_cast<bf16x8*>(p) = t;
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_tanh(float x) {
+  float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+template <int ACT> __device__ __forceinline__ float apply_act(float x) {
+  if (ACT == AC_ACT_GELU_ERF) return gelu_erf(x);
+  if (ACT == AC_ACT_GELU_TANH) return gelu_tanh(x);
+  if (ACT == AC_ACT_RELU) return fmaxf(x, 0.0f);
+  if (ACT == AC_ACT_SIGMOID) return sigmoidf(x);
+  return x;
+}
+__device__ __forceinline__ float apply_act_rt(float x, int act) {
+  switch (act) {
+    case AC_ACT_GELU_ERF: return gelu_erf(x);
+    case AC_ACT_GELU_TANH: return gelu_tanh(x);
+    case AC_ACT_RELU: return fmaxf(x, 0.0f);
+    case AC_ACT_SIGMOID: return sigmoidf(x);
+    default: return x;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// Sum over groups of G consecutive lanes (G a power of two <= 64).
+template <int G> __device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = G / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Launch interface used by the executor and by the ac_op_* entry points.
+// ---------------------------------------------------------------------------------------
+
+struct LinearArgs {
+  const void* a; int64_t lda;        // [m, k]
+  const void* w; int64_t ldw;        // [n, k]
+  const void* bias;                  // [n] or null
+  const void* mul; int64_t ldmul;    // [m, n] or null
+  const void* resid; int64_t ldr;    // [m, n] or null
+  void* out; int64_t ldo;            // columns [0, n_split): out[m * ldo + n]
+  // columns [n_split, n): out_t[(m / t_period) * t_s1 + (m % t_period) * t_s2 + (n - n_split) * t_s3]
+  void* out_t; int64_t n_split; int64_t t_period, t_s1, t_s2, t_s3;
+  int64_t m, n, k;
+  int act;
+  int dtype;
+};
+
+struct AttnArgs {
+  const void* q; int64_t ldq, sq_b;
+  const void* k; int64_t ldk, sk_b;
+  // v_transposed: v is vt[(h * head_dim + d) * ldv + key]; else row-major v[key * ldv + h * head_dim + d].
+  const void* v; int64_t ldv, sv_b; int v_transposed;
+  const void* bias; int64_t ld_bias, s_bias_h;   // bias[h * s_bias_h + (row) * ld_bias + key]
+  const void* gate; int64_t ldg, sg_b;
+  void* ctx; int64_t ldc, sc_b;
+  int64_t batch, sq, sk;
+  int heads, head_dim, causal;
+  int64_t q_offset;
+  int dtype;
+};
+
+hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,
+                            int64_t ldy, int64_t rows, int64_t cols, float eps, int dtype,
+                            hipStream_t s);
+hipError_t launch_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy,
+                           int64_t rows, int64_t cols, int act, int dtype, hipStream_t s);
+hipError_t launch_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
+                         int64_t rows, int64_t cols, int op, int dtype, hipStream_t s);
+hipError_t launch_linear(const LinearArgs& g, hipStream_t s);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+// Row-major value matrix [keys, cols] -> transposed copy [cols, keys] (bf16), for callers
+// of the attention entry point that hold v row-major.
+hipError_t launch_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows,
+                            int64_t cols, int dtype, hipStream_t s);
+
+// hipErrorInvalidValue-style refusal with a message for ac_last_error().
+void set_error(const char* fmt, ...);
+
+}  // namespace ac

@@ -1,0 +1,297 @@
+// Projection GEMMs of a chunked region: out = epilogue(a[m,k] . w[n,k]^T).
+// (AutoChunk section 2.2: the QKV / output / feed-forward projections applied to one
+// segment of rows; these are dense contractions and run on the bf16 matrix cores.)
+//
+// bf16 path: v_mfma_f32_32x32x16_bf16, 256 threads = 4 waves in a 2x2 arrangement, block
+// tile BM x BN x 64 double-buffered in LDS (rows padded by 16 bytes so that the 128-bit
+// fragment reads of 32 consecutive rows hit distinct banks).  The weight rows feed the
+// MFMA "A" operand and the activation rows the "B" operand, so that every lane ends up
+// with one output row m and groups of 4 consecutive output columns n: the bias, multiplier
+// and residual are then 8-byte vector accesses and the result is stored 8 bytes at a time.
+// The K loop order does not depend on the tile's position in m, so a row's result is
+// bitwise the same for every chunk length.
+//
+// fp32 path and odd shapes: an LDS-tiled FMA kernel with full bounds checks.
+#include "common.h"
+
+namespace ac {
+
+// ------------------------------------------------------------------------------------
+// Epilogue for one element (generic kernel) — bias, activation, multiplier, residual,
+// then the row-major or the strided ("transposed") store.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void epilogue_store_one(const LinearArgs& g, int64_t m, int64_t n, float v) {
+  if (g.bias) v += Elem<T>::ld((const T*)g.bias + n);
+  v = apply_act_rt(v, g.act);
+  if (g.mul) v *= Elem<T>::ld((const T*)g.mul + m * g.ldmul + n);
+  if (g.resid) v += Elem<T>::ld((const T*)g.resid + m * g.ldr + n);
+  if (n < g.n_split) {
+    Elem<T>::st((T*)g.out + m * g.ldo + n, v);
+  } else {
+    const int64_t off = (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 + (n - g.n_split) * g.t_s3;
+    Elem<T>::st((T*)g.out_t + off, v);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) linear_fma(LinearArgs g) {
+  __shared__ float sa[16][65];
+  __shared__ float sw[16][65];
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+  const T* a = (const T*)g.a;
+  const T* w = (const T*)g.w;
+  float acc[4][4] = {};
+  for (int64_t k0 = 0; k0 < g.k; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = threadIdx.x + 256 * i;
+      const int row = idx / 16, kk = idx % 16;
+      const bool kin = k0 + kk < g.k;
+      sa[kk][row] = (kin && m0 + row < g.m) ? Elem<T>::ld(a + (m0 + row) * g.lda + k0 + kk) : 0.f;
+      sw[kk][row] = (kin && n0 + row < g.n) ? Elem<T>::ld(w + (n0 + row) * g.ldw + k0 + kk) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float av[4], wv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { av[i] = sa[kk][ty * 4 + i]; wv[i] = sw[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], wv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < g.m && n < g.n) epilogue_store_one<T>(g, m, n, acc[i][j]);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// bf16 MFMA kernel.
+// ------------------------------------------------------------------------------------
+constexpr int kBK = 64;            // k extent of one LDS stage
+constexpr int kLdsRow = kBK + 8;   // padded row, in elements (144 bytes)
+constexpr int kXcds = 8;
+
+// Block id -> tile.  Consecutive block ids go round-robin to the 8 XCDs, each with its own
+// L2; give every XCD a contiguous run of tiles, ordered in groups of 4 tile-rows so that
+// tiles resident together share activation and weight panels.
+__device__ __forceinline__ void tile_of_block(int64_t tiles_m, int64_t tiles_n, int64_t& tm, int64_t& tn) {
+  const int64_t nb = gridDim.x, pid = blockIdx.x;
+  const int64_t q = nb / kXcds, r = nb % kXcds;
+  const int64_t x = pid % kXcds, idx = pid / kXcds;
+  const int64_t t = x * q + (x < r ? x : r) + idx;
+  constexpr int64_t GM = 4;
+  const int64_t width = GM * tiles_n;
+  const int64_t group = t / width;
+  const int64_t first = group * GM;
+  const int64_t gsz = tiles_m - first < GM ? tiles_m - first : GM;
+  tm = first + (t % width) % gsz;
+  tn = (t % width) / gsz;
+}
+
+__device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, int64_t n, float (&v)[4]) {
+  if (g.bias) {
+    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
+  }
+  if (g.act != AC_ACT_NONE) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = apply_act_rt(v[j], g.act);
+  }
+  if (g.mul) {
+    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.mul + m * g.ldmul + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] *= bf2f(b[j]);
+  }
+  if (g.resid) {
+    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.resid + m * g.ldr + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
+  }
+  if (n < g.n_split) {
+    bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+    *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
+  } else {
+    const int64_t base = (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 + (n - g.n_split) * g.t_s3;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ((bf16_t*)g.out_t)[base + j * g.t_s3] = f2bf(v[j]);
+  }
+}
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
+  constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
+  constexpr int TM = WM / 32, TN = WN / 32;   // 32x32 MFMA tiles per wave
+  constexpr int A_CHUNKS = BM * 8 / 256, W_CHUNKS = BN * 8 / 256;   // 16-byte chunks per thread
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][kLdsRow]
+  bf16_t* sW = sA + 2 * BM * kLdsRow;                               // [2][BN][kLdsRow]
+
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int wave_m = wave / 2, wave_n = wave % 2;
+  const int l32 = lane % 32, half = lane / 32;
+  const int64_t tiles_m = (g.m + BM - 1) / BM, tiles_n = (g.n + BN - 1) / BN;
+  int64_t tm_, tn_;
+  tile_of_block(tiles_m, tiles_n, tm_, tn_);
+  const int64_t m0 = tm_ * BM, n0 = tn_ * BN;
+  const bf16_t* a = (const bf16_t*)g.a;
+  const bf16_t* w = (const bf16_t*)g.w;
+
+  // Global source of each 16-byte chunk this thread stages (rows clamped into range; the
+  // results of clamped rows are never stored).
+  const bf16_t* a_src[A_CHUNKS];
+  const bf16_t* w_src[W_CHUNKS];
+  int a_dst[A_CHUNKS], w_dst[W_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
+    int64_t gr = m0 + row; if (gr > g.m - 1) gr = g.m - 1;
+    a_src[i] = a + gr * g.lda + ch * 8;
+    a_dst[i] = row * kLdsRow + ch * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < W_CHUNKS; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
+    int64_t gr = n0 + row; if (gr > g.n - 1) gr = g.n - 1;
+    w_src[i] = w + gr * g.ldw + ch * 8;
+    w_dst[i] = row * kLdsRow + ch * 8;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  bf16x8 a_reg[A_CHUNKS], w_reg[W_CHUNKS];
+  const int64_t kt_count = g.k / kBK;
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i]);
+#pragma unroll
+  for (int i = 0; i < W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i]);
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(sA + a_dst[i]) = a_reg[i];
+#pragma unroll
+  for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(sW + w_dst[i]) = w_reg[i];
+  __syncthreads();
+
+  for (int64_t kt = 0; kt < kt_count; ++kt) {
+    const int buf = (int)(kt & 1);
+    const bool more = kt + 1 < kt_count;
+    if (more) {
+      const int64_t koff = (kt + 1) * kBK;
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + koff);
+#pragma unroll
+      for (int i = 0; i < W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i] + koff);
+    }
+    const bf16_t* cA = sA + buf * BM * kLdsRow + (wave_m * WM + l32) * kLdsRow + half * 8;
+    const bf16_t* cW = sW + buf * BN * kLdsRow + (wave_n * WN + l32) * kLdsRow + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      bf16x8 fa[TM], fw[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(cA + i * 32 * kLdsRow + ks * 16);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(cW + j * 32 * kLdsRow + ks * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      bf16_t* nA = sA + (buf ^ 1) * BM * kLdsRow;
+      bf16_t* nW = sW + (buf ^ 1) * BN * kLdsRow;
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(nA + a_dst[i]) = a_reg[i];
+#pragma unroll
+      for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(nW + w_dst[i]) = w_reg[i];
+    }
+    __syncthreads();
+  }
+
+  // acc[i][j][r]: row m = .. + l32, column n = .. + 8*(r/4) + 4*half + (r%4).
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int64_t m = m0 + wave_m * WM + i * 32 + l32;
+    if (m >= g.m) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t n = n0 + wave_n * WN + j * 32 + 8 * q + 4 * half;
+        if (n >= g.n) continue;
+        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        epilogue_store4(g, m, n, v);
+      }
+    }
+  }
+}
+
+template <int BM, int BN>
+constexpr size_t mfma_lds_bytes() { return (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16_t); }
+
+template <int BM, int BN>
+static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
+  auto kern = linear_mfma_bf16<BM, BN>;
+  static bool attr_set = false;   // the attribute is per function; set once per process
+  constexpr size_t lds = mfma_lds_bytes<BM, BN>();
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int64_t tiles = ((g.m + BM - 1) / BM) * ((g.n + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+static bool aligned_to(const void* p, uintptr_t a) { return p == nullptr || ((uintptr_t)p % a) == 0; }
+
+static bool mfma_eligible(const LinearArgs& g) {
+  if (g.dtype != AC_BF16) return false;
+  if (g.k < kBK || g.k % kBK != 0) return false;
+  if (g.n % 4 != 0 || g.n_split % 4 != 0) return false;
+  if (g.lda % 8 != 0 || g.ldw % 8 != 0) return false;
+  if (!aligned_to(g.a, 16) || !aligned_to(g.w, 16)) return false;
+  if (g.n_split > 0 && (g.ldo % 4 != 0 || !aligned_to(g.out, 8))) return false;
+  if (g.bias && !aligned_to(g.bias, 8)) return false;
+  if (g.mul && (g.ldmul % 4 != 0 || !aligned_to(g.mul, 8))) return false;
+  if (g.resid && (g.ldr % 4 != 0 || !aligned_to(g.resid, 8))) return false;
+  return true;
+}
+
+hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
+  LinearArgs g = g_in;
+  if (g.m <= 0 || g.n <= 0) return hipSuccess;
+  if (g.k <= 0) return hipErrorInvalidValue;
+  if (g.out_t == nullptr) g.n_split = g.n;
+  if (g.n_split > g.n) g.n_split = g.n;
+  if (g.t_period <= 0) g.t_period = INT64_MAX;
+  if (mfma_eligible(g)) {
+    // 128x128 tiles when they fill the 256 CUs, otherwise 64x64 tiles (4x as many blocks).
+    const int64_t big = ((g.m + 127) / 128) * ((g.n + 127) / 128);
+    if (big >= 192) return mfma_launch<128, 128>(g, s);
+    return mfma_launch<64, 64>(g, s);
+  }
+  dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64));
+  if (g.dtype == AC_BF16) hipLaunchKernelGGL((linear_fma<bf16_t>), grid, dim3(256), 0, s, g);
+  else hipLaunchKernelGGL((linear_fma<float>), grid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace ac

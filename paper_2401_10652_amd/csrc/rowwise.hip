@@ -1,0 +1,269 @@
+// Row-wise HBM-bound passes over one segment: LayerNorm, bias + activation, add / multiply,
+// and a tiled transpose.  Each element is read once and written once with 16-byte accesses;
+// statistics are fp32.  (AutoChunk section 2.2: these are the per-segment elementwise and
+// normalisation steps of a chunked region.)
+#include "common.h"
+
+namespace ac {
+
+// ------------------------------------------------------------------------------------
+// LayerNorm.  A group of G lanes owns one row and keeps it in registers (NV 16-byte
+// vectors per lane): mean, then the centred second moment, then the affine output.
+// cols == G * NV * kVec exactly; other widths take the generic kernel below.
+// ------------------------------------------------------------------------------------
+template <typename T, int G, int NV>
+__global__ void __launch_bounds__(256)
+layernorm_rows(const T* __restrict__ x, int64_t ldx, const T* __restrict__ gain,
+               const T* __restrict__ shift, T* __restrict__ y, int64_t ldy, int64_t rows, float eps) {
+  constexpr int V = Elem<T>::kVec;
+  constexpr int COLS = G * NV * V;
+  constexpr int ROWS_PER_BLOCK = 256 / G;
+  const int lane_in_group = threadIdx.x % G;
+  const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
+  const bool live = row < rows;
+  const int64_t r = live ? row : rows - 1;   // dead groups shadow the last row, store nothing
+  float v[NV][V];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    load_vec(x + r * ldx + (i * G + lane_in_group) * V, v[i]);
+#pragma unroll
+    for (int j = 0; j < V; ++j) sum += v[i][j];
+  }
+  const float mean = group_sum<G>(sum) * (1.0f / COLS);
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < V; ++j) { float d = v[i][j] - mean; sq += d * d; }
+  const float rstd = rsqrtf(group_sum<G>(sq) * (1.0f / COLS) + eps);
+  if (!live) return;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * G + lane_in_group) * V;
+    float g[V], b[V], o[V];
+    load_vec(gain + c, g);
+    load_vec(shift + c, b);
+#pragma unroll
+    for (int j = 0; j < V; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+    store_vec(y + row * ldy + c, o);
+  }
+}
+
+// Any width: one wave per row, three passes over the row (it stays in L2).
+template <typename T>
+__global__ void __launch_bounds__(256)
+layernorm_rows_generic(const T* __restrict__ x, int64_t ldx, const T* __restrict__ gain,
+                       const T* __restrict__ shift, T* __restrict__ y, int64_t ldy, int64_t rows,
+                       int64_t cols, float eps) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
+  if (row >= rows) return;
+  const T* xr = x + row * ldx;
+  float sum = 0.f;
+  for (int64_t c = lane; c < cols; c += kWave) sum += Elem<T>::ld(xr + c);
+  const float mean = wave_sum(sum) / (float)cols;
+  float sq = 0.f;
+  for (int64_t c = lane; c < cols; c += kWave) { float d = Elem<T>::ld(xr + c) - mean; sq += d * d; }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)cols + eps);
+  for (int64_t c = lane; c < cols; c += kWave)
+    Elem<T>::st(y + row * ldy + c,
+                (Elem<T>::ld(xr + c) - mean) * rstd * Elem<T>::ld(gain + c) + Elem<T>::ld(shift + c));
+}
+
+template <typename T, int G, int NV>
+static hipError_t ln_launch(const void* x, int64_t ldx, const void* g, const void* b, void* y, int64_t ldy,
+                            int64_t rows, float eps, hipStream_t s) {
+  const int rpb = 256 / G;
+  dim3 grid((unsigned)((rows + rpb - 1) / rpb));
+  hipLaunchKernelGGL((layernorm_rows<T, G, NV>), grid, dim3(256), 0, s, (const T*)x, ldx, (const T*)g,
+                     (const T*)b, (T*)y, ldy, rows, eps);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t ln_dispatch(const void* x, int64_t ldx, const void* g, const void* b, void* y, int64_t ldy,
+                              int64_t rows, int64_t cols, float eps, hipStream_t s) {
+  constexpr int V = Elem<T>::kVec;
+  const bool vec_ok = (ldx % V == 0) && (ldy % V == 0) && (cols % V == 0);
+  if (vec_ok) {
+    const int64_t nvec = cols / V;   // 16-byte vectors per row
+    switch (nvec) {
+      case 8:   return ln_launch<T, 8, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 16:  return ln_launch<T, 16, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 32:  return ln_launch<T, 32, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 64:  return ln_launch<T, 64, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 96:  return ln_launch<T, 32, 3>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 128: return ln_launch<T, 64, 2>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 192: return ln_launch<T, 64, 3>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 256: return ln_launch<T, 64, 4>(x, ldx, g, b, y, ldy, rows, eps, s);
+      default: break;
+    }
+  }
+  dim3 grid((unsigned)((rows + 3) / 4));
+  hipLaunchKernelGGL((layernorm_rows_generic<T>), grid, dim3(256), 0, s, (const T*)x, ldx, (const T*)g,
+                     (const T*)b, (T*)y, ldy, rows, cols, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,
+                            int64_t ldy, int64_t rows, int64_t cols, float eps, int dtype, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (dtype == AC_BF16) return ln_dispatch<bf16_t>(x, ldx, gain, shift, y, ldy, rows, cols, eps, s);
+  return ln_dispatch<float>(x, ldx, gain, shift, y, ldy, rows, cols, eps, s);
+}
+
+// ------------------------------------------------------------------------------------
+// y = act(x + bias[col]);  y = a (+|*) b.   Grid-stride over 16-byte vectors of a
+// [rows, cols] view with row strides; cols % kVec == 0 takes the vector path.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+bias_act_vec(const T* __restrict__ x, int64_t ldx, const T* __restrict__ bias, T* __restrict__ y,
+             int64_t ldy, int64_t rows, int64_t vec_per_row, int act) {
+  constexpr int V = Elem<T>::kVec;
+  const int64_t total = rows * vec_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / vec_per_row, c = (i % vec_per_row) * V;
+    float v[V], b[V];
+    load_vec(x + r * ldx + c, v);
+    if (bias) {
+      load_vec(bias + c, b);
+#pragma unroll
+      for (int j = 0; j < V; ++j) v[j] += b[j];
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) v[j] = apply_act_rt(v[j], act);
+    store_vec(y + r * ldy + c, v);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+bias_act_scalar(const T* __restrict__ x, int64_t ldx, const T* __restrict__ bias, T* __restrict__ y,
+                int64_t ldy, int64_t rows, int64_t cols, int act) {
+  const int64_t total = rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cols, c = i % cols;
+    float v = Elem<T>::ld(x + r * ldx + c);
+    if (bias) v += Elem<T>::ld(bias + c);
+    Elem<T>::st(y + r * ldy + c, apply_act_rt(v, act));
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+binary_vec(const T* __restrict__ a, int64_t lda, const T* __restrict__ b, int64_t ldb, T* __restrict__ y,
+           int64_t ldy, int64_t rows, int64_t vec_per_row, int op) {
+  constexpr int V = Elem<T>::kVec;
+  const int64_t total = rows * vec_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / vec_per_row, c = (i % vec_per_row) * V;
+    float u[V], v[V];
+    load_vec(a + r * lda + c, u);
+    load_vec(b + r * ldb + c, v);
+#pragma unroll
+    for (int j = 0; j < V; ++j) u[j] = op == 0 ? u[j] + v[j] : u[j] * v[j];
+    store_vec(y + r * ldy + c, u);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+binary_scalar(const T* __restrict__ a, int64_t lda, const T* __restrict__ b, int64_t ldb, T* __restrict__ y,
+              int64_t ldy, int64_t rows, int64_t cols, int op) {
+  const int64_t total = rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cols, c = i % cols;
+    const float u = Elem<T>::ld(a + r * lda + c), v = Elem<T>::ld(b + r * ldb + c);
+    Elem<T>::st(y + r * ldy + c, op == 0 ? u + v : u * v);
+  }
+}
+
+static unsigned stream_grid(int64_t items) {
+  int64_t blocks = (items + 255) / 256;
+  const int64_t cap = 256 * 16;   // 256 CUs, enough waves each to cover HBM latency
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (unsigned)blocks;
+}
+
+template <typename T>
+static hipError_t bias_act_dispatch(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy,
+                                    int64_t rows, int64_t cols, int act, hipStream_t s) {
+  constexpr int V = Elem<T>::kVec;
+  if (cols % V == 0 && ldx % V == 0 && ldy % V == 0) {
+    const int64_t vpr = cols / V;
+    hipLaunchKernelGGL((bias_act_vec<T>), dim3(stream_grid(rows * vpr)), dim3(256), 0, s, (const T*)x, ldx,
+                       (const T*)bias, (T*)y, ldy, rows, vpr, act);
+  } else {
+    hipLaunchKernelGGL((bias_act_scalar<T>), dim3(stream_grid(rows * cols)), dim3(256), 0, s, (const T*)x,
+                       ldx, (const T*)bias, (T*)y, ldy, rows, cols, act);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows,
+                           int64_t cols, int act, int dtype, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (dtype == AC_BF16) return bias_act_dispatch<bf16_t>(x, ldx, bias, y, ldy, rows, cols, act, s);
+  return bias_act_dispatch<float>(x, ldx, bias, y, ldy, rows, cols, act, s);
+}
+
+template <typename T>
+static hipError_t binary_dispatch(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
+                                  int64_t rows, int64_t cols, int op, hipStream_t s) {
+  constexpr int V = Elem<T>::kVec;
+  if (cols % V == 0 && lda % V == 0 && ldb % V == 0 && ldy % V == 0) {
+    const int64_t vpr = cols / V;
+    hipLaunchKernelGGL((binary_vec<T>), dim3(stream_grid(rows * vpr)), dim3(256), 0, s, (const T*)a, lda,
+                       (const T*)b, ldb, (T*)y, ldy, rows, vpr, op);
+  } else {
+    hipLaunchKernelGGL((binary_scalar<T>), dim3(stream_grid(rows * cols)), dim3(256), 0, s, (const T*)a, lda,
+                       (const T*)b, ldb, (T*)y, ldy, rows, cols, op);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
+                         int64_t rows, int64_t cols, int op, int dtype, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (dtype == AC_BF16) return binary_dispatch<bf16_t>(a, lda, b, ldb, y, ldy, rows, cols, op, s);
+  return binary_dispatch<float>(a, lda, b, ldb, y, ldy, rows, cols, op, s);
+}
+
+// ------------------------------------------------------------------------------------
+// dst[c * ldd + r] = src[r * lds + c] through a padded 64x64 LDS tile.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+transpose_tiles(const T* __restrict__ src, int64_t lds_, T* __restrict__ dst, int64_t ldd, int64_t rows,
+                int64_t cols) {
+  __shared__ T tile[64][65];
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t r = r0 + i, c = c0 + tx;
+    if (r < rows && c < cols) tile[i][tx] = src[r * lds_ + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t c = c0 + i, r = r0 + tx;
+    if (r < rows && c < cols) dst[c * ldd + r] = tile[tx][i];
+  }
+}
+
+hipError_t launch_transpose(const void* src, int64_t lds_, void* dst, int64_t ldd, int64_t rows, int64_t cols,
+                            int dtype, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+  if (dtype == AC_BF16)
+    hipLaunchKernelGGL((transpose_tiles<bf16_t>), grid, dim3(256), 0, s, (const bf16_t*)src, lds_, (bf16_t*)dst,
+                       ldd, rows, cols);
+  else
+    hipLaunchKernelGGL((transpose_tiles<float>), grid, dim3(256), 0, s, (const float*)src, lds_, (float*)dst,
+                       ldd, rows, cols);
+  return hipGetLastError();
+}
+
+}  // namespace ac

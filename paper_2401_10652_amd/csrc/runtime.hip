@@ -1,0 +1,749 @@
+// Host side of the library: chunk plan, workspace arena, segment loop, C-ABI.
+//
+// AutoChunk section 2.2 / 3.1: a region Y^c = F(X^c, X^nc) is run one segment of its
+// chunk dimension after another; only the intermediates of ONE segment are alive at a
+// time.  The arena below makes that literal: whole tensors (layer input/output, keys and
+// values, the second triangle operand) are pushed once, per-segment intermediates are
+// pushed at the start of a segment and released at its end, and the high-water mark of
+// the arena is the activation memory the plan needs.  Planning is a dry run of the very
+// same walk with launches switched off, so planned and measured peaks agree by
+// construction.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace ac {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline bool aligned256(const void* p) { return ((uintptr_t)p & 255u) == 0; }
+
+enum KClass { K_GEMM = 0, K_ATTN = 1, K_LN = 2, K_ELEM = 3, K_TRI = 4, K_CLASSES = 5 };
+static const char* const kClassName[K_CLASSES] = {"gemm", "attention", "layernorm", "elementwise", "trimul"};
+
+struct Arena {
+  uint8_t* base = nullptr;   // null during planning
+  uint64_t top = 0, high = 0;
+  void* push(uint64_t bytes) {
+    const uint64_t off = align_up(top, 256);
+    top = off + bytes;
+    high = std::max(high, top);
+    // during planning the "pointer" is only an offset and is never dereferenced
+    return base ? (void*)(base + off) : (void*)(uintptr_t)(off + 256);
+  }
+  uint64_t mark() const { return top; }
+  void release(uint64_t m) { top = m; }
+};
+
+struct Setting {   // chunk setting of one region kind (section 3.3, rule 4: one per region)
+  bool present = false;
+  int chunk_dim = 0;
+  int64_t chunk_len = 0;   // resolved: 1..extent
+  int64_t extent = 0;
+  bool sized_by_budget = false;
+};
+
+struct WeightSlot { std::string name; int64_t rows, cols; };
+
+struct ProfRec { int cls; hipEvent_t start, stop; double flops, bytes; };
+
+}  // namespace ac
+
+using namespace ac;
+
+struct ac_plan {
+  ac_model_desc m;
+  Setting set[AC_REGION_KINDS];
+  uint64_t budget = 0;
+  std::vector<WeightSlot> weights;
+  std::vector<const void*> wptr;
+  bool bound = false;
+  ac_plan_info info;
+  // profiling
+  bool profiling = false;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  size_t pool_used = 0;
+};
+
+namespace ac {
+
+static int elem_bytes(int dtype) { return dtype == AC_BF16 ? 2 : 4; }
+
+// One walk of the plan: either a dry run (planning) or the real thing.
+struct Walk {
+  ac_plan* p;
+  bool dry;
+  bool unchunked;          // planning variant: one segment per region
+  hipStream_t stream;
+  Arena arena;
+  double flops = 0;
+  hipError_t err = hipSuccess;
+  const char* err_where = "";
+
+  int eb() const { return elem_bytes(p->m.dtype); }
+  const void* w(int layer, int slot, int per_layer) const {
+    return dry ? nullptr : p->wptr[(size_t)layer * per_layer + slot];
+  }
+
+  bool ok() const { return err == hipSuccess; }
+
+  template <typename F>
+  void run(int cls, double fl, double by, const char* where, F&& launch) {
+    flops += fl;
+    if (dry || !ok()) return;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (p->profiling) {
+      if (p->pool_used + 2 > p->pool.size()) {
+        for (int i = 0; i < 64; ++i) {
+          hipEvent_t e;
+          if (hipEventCreate(&e) != hipSuccess) { err = hipGetLastError(); err_where = "hipEventCreate"; return; }
+          p->pool.push_back(e);
+        }
+      }
+      e0 = p->pool[p->pool_used++];
+      e1 = p->pool[p->pool_used++];
+      (void)hipEventRecord(e0, stream);
+    }
+    hipError_t e = launch();
+    if (e != hipSuccess) { err = e; err_where = where; return; }
+    if (p->profiling) {
+      (void)hipEventRecord(e1, stream);
+      p->recs.push_back(ProfRec{cls, e0, e1, fl, by});
+    }
+  }
+
+  void ln(const void* x, int64_t ldx, const void* g, const void* b, void* y, int64_t ldy, int64_t rows,
+          int64_t cols) {
+    const int dt = p->m.dtype;
+    const float eps = p->m.ln_eps;
+    run(K_LN, 8.0 * rows * cols, 2.0 * rows * cols * eb(), "layernorm",
+        [&] { return launch_layernorm(x, ldx, g, b, y, ldy, rows, cols, eps, dt, stream); });
+  }
+  void linear(LinearArgs g) {
+    g.dtype = p->m.dtype;
+    double by = ((double)g.m * g.k + (double)g.n * g.k + (double)g.m * g.n) * eb();
+    if (g.mul) by += (double)g.m * g.n * eb();
+    if (g.resid) by += (double)g.m * g.n * eb();
+    run(K_GEMM, 2.0 * g.m * g.n * g.k, by, "linear", [&] { return launch_linear(g, stream); });
+  }
+  void attention(AttnArgs a) {
+    a.dtype = p->m.dtype;
+    double pairs;   // visible (query, key) pairs per head and problem
+    if (a.causal) {
+      pairs = 0;
+      // rows r see min(sk, q_offset + r + 1) keys
+      const int64_t full_from = std::max<int64_t>(0, a.sk - 1 - a.q_offset);   // first r seeing all keys
+      const int64_t tri = std::min<int64_t>(a.sq, full_from);
+      pairs += (double)tri * (a.q_offset + 1) + (double)tri * (tri - 1) / 2.0;
+      pairs += (double)(a.sq - tri) * a.sk;
+    } else {
+      pairs = (double)a.sq * a.sk;
+    }
+    const double fl = 4.0 * pairs * a.head_dim * a.heads * a.batch;
+    const double by = ((double)a.sq * 2 + (double)a.sk * 2) * a.heads * a.head_dim * a.batch * eb();
+    run(K_ATTN, fl, by, "attention", [&] { return launch_attention(a, stream); });
+  }
+  void bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows, int64_t cols,
+                int act) {
+    const int dt = p->m.dtype;
+    run(K_ELEM, 2.0 * rows * cols, 2.0 * rows * cols * eb(), "bias_act",
+        [&] { return launch_bias_act(x, ldx, bias, y, ldy, rows, cols, act, dt, stream); });
+  }
+  void binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy, int64_t rows,
+              int64_t cols, int op) {
+    const int dt = p->m.dtype;
+    run(K_ELEM, 1.0 * rows * cols, 3.0 * rows * cols * eb(), "binary",
+        [&] { return launch_binary(a, lda, b, ldb, y, ldy, rows, cols, op, dt, stream); });
+  }
+
+  // out = act(a w^T + bias) [+ resid], fused in the GEMM epilogue or as standalone passes.
+  void proj(const void* a, int64_t lda, const void* wmat, int64_t kdim, const void* bias, int act,
+            const void* resid, int64_t ldr, void* out, int64_t ldo, int64_t rows, int64_t ncols) {
+    LinearArgs g{};
+    g.a = a; g.lda = lda; g.w = wmat; g.ldw = kdim; g.m = rows; g.n = ncols; g.k = kdim;
+    g.n_split = ncols;
+    const bool unfused = (p->m.flags & AC_FLAG_UNFUSED_ELEMENTWISE) != 0;
+    if (!unfused) {
+      g.bias = bias; g.act = act; g.resid = resid; g.ldr = ldr; g.out = out; g.ldo = ldo;
+      linear(g);
+      return;
+    }
+    if (resid) {
+      const uint64_t mk = arena.mark();
+      void* tmp = arena.push((uint64_t)rows * ncols * eb());
+      g.out = tmp; g.ldo = ncols; g.act = AC_ACT_NONE;
+      linear(g);
+      bias_act(tmp, ncols, bias, tmp, ncols, rows, ncols, act);
+      binary(tmp, ncols, resid, ldr, out, ldo, rows, ncols, 0);
+      arena.release(mk);
+    } else {
+      g.out = out; g.ldo = ldo; g.act = AC_ACT_NONE;
+      linear(g);
+      bias_act(out, ldo, bias, out, ldo, rows, ncols, act);
+    }
+  }
+
+  int64_t seg_len(int kind) const { return unchunked ? p->set[kind].extent : p->set[kind].chunk_len; }
+
+  void transformer(const void* x, void* y);
+};
+
+static const char* const kLayerTensor[12] = {"ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                                             "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2"};
+enum { W_LN1G, W_LN1B, W_QKV, W_BQKV, W_O, W_BO, W_LN2G, W_LN2B, W_1, W_B1, W_2, W_B2 };
+
+// Rows [r0, r1) of the flattened [batch * seq] token axis that form one segment.
+struct Seg { int64_t b0, nb, s0, ns; };
+
+static std::vector<Seg> token_segments(const ac_model_desc& m, int chunk_dim, int64_t len) {
+  std::vector<Seg> v;
+  if (chunk_dim == AC_DIM_BATCH) {
+    for (int64_t b = 0; b < m.batch; b += len) v.push_back(Seg{b, std::min<int64_t>(len, m.batch - b), 0, m.seq});
+  } else {
+    for (int64_t b = 0; b < m.batch; ++b)
+      for (int64_t s = 0; s < m.seq; s += len) v.push_back(Seg{b, 1, s, std::min<int64_t>(len, m.seq - s)});
+  }
+  return v;
+}
+
+void Walk::transformer(const void* x, void* y) {
+  const ac_model_desc& m = p->m;
+  const int64_t T = (int64_t)m.batch * m.seq, S = m.seq, d = m.d_model, F = m.d_ffn;
+  const int e = eb();
+  const bool bf = m.dtype == AC_BF16;
+  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
+  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+
+  // Whole tensors of a layer.  bf16: q,k row-major [T, 2d] and v transposed per batch
+  // element [d, S]; fp32: q,k,v row-major [T, 3d].
+  void* qk = arena.push((uint64_t)T * (bf ? 2 : 3) * d * e);
+  void* vt = bf ? arena.push((uint64_t)T * d * e) : nullptr;
+  const int64_t ldqk = (bf ? 2 : 3) * d;
+  void* hbuf = arena.push((uint64_t)T * d * e);
+  void* tbuf = m.layers > 1 ? arena.push((uint64_t)T * d * e) : nullptr;
+
+  for (int l = 0; l < m.layers && ok(); ++l) {
+    const void* in = l == 0 ? x : (const void*)tbuf;
+    void* out = l == m.layers - 1 ? y : tbuf;
+    auto W = [&](int slot) { return w(l, slot, 12); };
+
+    // ---- region 1: LayerNorm 1 + packed projection, writes whole q, k, v
+    for (const Seg& sg : token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV))) {
+      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
+      const uint64_t mk = arena.mark();
+      void* u = arena.push((uint64_t)rows * d * e);
+      ln(at(in, r0 * d), d, W(W_LN1G), W(W_LN1B), u, d, rows, d);
+      LinearArgs g{};
+      g.a = u; g.lda = d; g.w = W(W_QKV); g.ldw = d; g.m = rows; g.n = 3 * d; g.k = d;
+      g.out = atw(qk, r0 * ldqk); g.ldo = ldqk; g.n_split = 3 * d;
+      if (bf) {
+        g.n_split = 2 * d;
+        g.out_t = atw(vt, sg.b0 * d * S + sg.s0);
+        g.t_period = sg.ns; g.t_s1 = d * S; g.t_s2 = 1; g.t_s3 = S;
+      }
+      const bool unfused = (m.flags & AC_FLAG_UNFUSED_ELEMENTWISE) != 0;
+      if (!unfused || bf) {   // the strided store of v only exists as a GEMM epilogue
+        g.bias = W(W_BQKV);
+        linear(g);
+      } else {
+        linear(g);
+        bias_act(g.out, ldqk, W(W_BQKV), g.out, ldqk, rows, 3 * d, AC_ACT_NONE);
+      }
+      arena.release(mk);
+    }
+
+    // ---- region 2: attention of a query segment over whole k, v; output projection; residual
+    for (const Seg& sg : token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION))) {
+      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
+      const uint64_t mk = arena.mark();
+      void* ctx = arena.push((uint64_t)rows * d * e);
+      AttnArgs a{};
+      a.q = at(qk, r0 * ldqk); a.ldq = ldqk; a.sq_b = S * ldqk;
+      a.k = at(qk, sg.b0 * S * ldqk + d); a.ldk = ldqk; a.sk_b = S * ldqk;
+      if (bf) { a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1; }
+      else { a.v = at(qk, sg.b0 * S * ldqk + 2 * d); a.ldv = ldqk; a.sv_b = S * ldqk; a.v_transposed = 0; }
+      a.ctx = ctx; a.ldc = d; a.sc_b = sg.ns * d;
+      a.batch = sg.nb; a.sq = sg.ns; a.sk = S; a.heads = m.heads; a.head_dim = m.head_dim;
+      a.causal = m.causal; a.q_offset = sg.s0;
+      attention(a);
+      proj(ctx, d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
+      arena.release(mk);
+    }
+
+    // ---- region 3: LayerNorm 2 + feed-forward + residual
+    for (const Seg& sg : token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN))) {
+      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
+      const uint64_t mk = arena.mark();
+      void* u = arena.push((uint64_t)rows * d * e);
+      void* hid = arena.push((uint64_t)rows * F * e);
+      ln(at(hbuf, r0 * d), d, W(W_LN2G), W(W_LN2B), u, d, rows, d);
+      proj(u, d, W(W_1), d, W(W_B1), m.activation, nullptr, 0, hid, F, rows, F);
+      proj(hid, F, W(W_2), F, W(W_B2), AC_ACT_NONE, at(hbuf, r0 * d), d, atw(out, r0 * d), d, rows, d);
+      arena.release(mk);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Paper-style byte counts of the regions (section 2: M = X + Y + A, chunked M = X + Y + A/n
+// with every op output a tensor of its own), used to size chunk lengths from a budget.
+// ---------------------------------------------------------------------------------------
+static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
+  const uint64_t b = elem_bytes(m.dtype);
+  if (m.workload == AC_TRANSFORMER_STACK) {
+    // the token axis is [batch, seq]; c counts sequence rows or batch elements
+    const uint64_t T = (uint64_t)m.batch * m.seq, d = m.d_model, F = m.d_ffn, H = m.heads, S = m.seq;
+    switch (kind) {
+      case AC_REGION_QKV: return T * d * b + 3 * T * d * b + (uint64_t)c * d * b;
+      case AC_REGION_ATTENTION: return T * d * b + 3 * T * d * b + T * d * b + 2 * H * (uint64_t)c * S * b;
+      case AC_REGION_FFN: return 2 * T * d * b + (uint64_t)c * d * b + 2 * (uint64_t)c * F * b;
+      default: return 0;
+    }
+  }
+  const uint64_t n = m.n_res, cz = m.c_z, ch = m.c_hidden, hd = (uint64_t)m.tri_heads * m.tri_head_dim;
+  const uint64_t H = m.tri_heads, cc = (uint64_t)c;
+  switch (kind) {
+    case AC_REGION_TRIMUL_OUT:
+    case AC_REGION_TRIMUL_IN:
+      return 2 * n * n * cz * b + 2 * n * n * ch * b + 2 * cc * n * cz * b + 2 * cc * n * ch * b;
+    case AC_REGION_TRIATT_START:
+    case AC_REGION_TRIATT_END:
+      return 2 * n * n * cz * b + 2 * n * n * hd * b + H * n * n * b + cc * n * cz * b + 3 * cc * n * hd * b +
+             cc * H * n * n * b;
+    case AC_REGION_PAIR_TRANSITION:
+      return 2 * n * n * cz * b + cc * n * cz * b + 2 * cc * n * m.transition_factor * cz * b;
+    default: return 0;
+  }
+}
+
+// For a token-axis chunk the model counts rows of ONE segment: seq chunk -> c rows of one
+// batch element; batch chunk -> c * seq rows.
+static int64_t model_rows(const ac_model_desc& m, const Setting& s, int64_t len) {
+  if (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_BATCH) return len * m.seq;
+  return len;
+}
+
+static void region_kinds(const ac_model_desc& m, int& first, int& count) {
+  if (m.workload == AC_TRANSFORMER_STACK) { first = AC_REGION_QKV; count = 3; }
+  else { first = AC_REGION_TRIMUL_OUT; count = 5; }
+}
+
+static bool dim_legal(const ac_model_desc& m, int dim, bool& known) {
+  known = true;
+  if (m.workload == AC_TRANSFORMER_STACK) {
+    if (dim == AC_DIM_BATCH || dim == AC_DIM_SEQ) return true;
+    if (dim == AC_DIM_FEATURE || dim == AC_DIM_HEAD_DIM || dim == AC_DIM_KEY) return false;
+  } else {
+    if (dim == AC_DIM_ROW || dim == AC_DIM_COL) return true;
+    if (dim == AC_DIM_CHANNEL || dim == AC_DIM_CONTRACT) return false;
+  }
+  known = false;
+  return false;
+}
+
+static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& flops) {
+  Walk wk{p, true, unchunked, nullptr};
+  if (p->m.workload == AC_TRANSFORMER_STACK) wk.transformer(nullptr, nullptr);
+  arena_bytes = wk.arena.high;
+  flops = wk.flops;
+}
+
+static uint64_t io_bytes(const ac_model_desc& m) {
+  if (m.workload == AC_TRANSFORMER_STACK) return 2ull * m.batch * m.seq * m.d_model * elem_bytes(m.dtype);
+  return 2ull * m.n_res * m.n_res * m.c_z * elem_bytes(m.dtype);
+}
+
+}  // namespace ac
+
+// =========================================================================================
+// C-ABI
+// =========================================================================================
+extern "C" {
+
+const char* ac_status_string(int s) {
+  switch (s) {
+    case AC_OK: return "ok";
+    case AC_ERR_ARG: return "invalid argument";
+    case AC_ERR_ILLEGAL_CHUNK_DIM: return "illegal chunk dimension";
+    case AC_ERR_BUDGET_INFEASIBLE: return "activation budget infeasible";
+    case AC_ERR_WORKSPACE: return "workspace too small";
+    case AC_ERR_ALIGN: return "device pointer not 256-byte aligned";
+    case AC_ERR_HIP: return "HIP error";
+    case AC_ERR_STATE: return "invalid state";
+    case AC_ERR_UNSUPPORTED: return "unsupported";
+    default: return "unknown status";
+  }
+}
+
+const char* ac_last_error(void) { return g_err; }
+
+int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, int n_regions,
+                   uint64_t act_budget_bytes, ac_plan** out) {
+  if (!model || !out || n_regions < 0 || (n_regions > 0 && !regions))
+    return fail(AC_ERR_ARG, "ac_plan_create: null argument");
+  *out = nullptr;
+  const ac_model_desc& m = *model;
+  if (m.dtype != AC_F32 && m.dtype != AC_BF16) return fail(AC_ERR_ARG, "dtype %d unknown", m.dtype);
+  if (m.layers < 1) return fail(AC_ERR_ARG, "layers must be >= 1");
+  if (!(m.ln_eps > 0.f)) return fail(AC_ERR_ARG, "ln_eps must be > 0");
+  if (m.workload == AC_TRANSFORMER_STACK) {
+    if (m.batch < 1 || m.seq < 1 || m.d_model < 1 || m.heads < 1 || m.head_dim < 1 || m.d_ffn < 1)
+      return fail(AC_ERR_ARG, "transformer sizes must be positive");
+    if ((int64_t)m.heads * m.head_dim != m.d_model)
+      return fail(AC_ERR_ARG, "heads * head_dim (%d * %d) != d_model (%d)", m.heads, m.head_dim, m.d_model);
+    if (m.activation != AC_ACT_GELU_ERF && m.activation != AC_ACT_GELU_TANH && m.activation != AC_ACT_RELU)
+      return fail(AC_ERR_ARG, "activation %d not valid for a feed-forward", m.activation);
+    const int hd = m.head_dim;
+    if (hd != 8 && hd != 16 && hd != 32 && hd != 64 && hd != 128)
+      return fail(AC_ERR_UNSUPPORTED, "head_dim %d has no attention kernel (8, 16, 32, 64, 128)", hd);
+    if (m.dtype == AC_BF16 && (m.seq % 8 != 0 || m.d_model % 8 != 0 || m.d_ffn % 8 != 0))
+      return fail(AC_ERR_UNSUPPORTED, "bf16 needs seq, d_model and d_ffn to be multiples of 8");
+  } else if (m.workload == AC_PAIR_STACK) {
+    return fail(AC_ERR_UNSUPPORTED, "pair stack is not built yet");
+  } else {
+    return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
+  }
+
+  ac_plan* p = new (std::nothrow) ac_plan();
+  if (!p) return fail(AC_ERR_ARG, "out of host memory");
+  p->m = m;
+  p->budget = act_budget_bytes;
+  int first, count;
+  region_kinds(m, first, count);
+  for (int k = first; k < first + count; ++k) {
+    Setting& s = p->set[k];
+    s.chunk_dim = m.workload == AC_TRANSFORMER_STACK ? AC_DIM_SEQ : AC_DIM_ROW;
+    s.extent = m.workload == AC_TRANSFORMER_STACK ? m.seq : m.n_res;
+    s.chunk_len = s.extent;
+  }
+  for (int i = 0; i < n_regions; ++i) {
+    const ac_region_desc& r = regions[i];
+    if (r.kind < first || r.kind >= first + count) {
+      delete p;
+      return fail(AC_ERR_ARG, "region kind %d does not belong to this workload", r.kind);
+    }
+    Setting& s = p->set[r.kind];
+    if (s.present) { delete p; return fail(AC_ERR_ARG, "region kind %d listed twice (one chunk setting per region)", r.kind); }
+    bool known;
+    if (!dim_legal(m, r.chunk_dim, known)) {
+      delete p;
+      if (!known) return fail(AC_ERR_ARG, "chunk_dim %d unknown", r.chunk_dim);
+      return fail(AC_ERR_ILLEGAL_CHUNK_DIM,
+                  "region %d reduces over dim %d: its segments would not concatenate to the unchunked output",
+                  r.kind, r.chunk_dim);
+    }
+    if (m.workload == AC_PAIR_STACK && r.chunk_dim == AC_DIM_COL) {
+      delete p;
+      return fail(AC_ERR_UNSUPPORTED, "column chunks of pair regions are legal but not implemented");
+    }
+    if (r.chunk_len < 0) { delete p; return fail(AC_ERR_ARG, "chunk_len must be >= 0"); }
+    s.present = true;
+    s.chunk_dim = r.chunk_dim;
+    s.extent = m.workload == AC_TRANSFORMER_STACK ? (r.chunk_dim == AC_DIM_BATCH ? m.batch : m.seq) : m.n_res;
+    if (r.chunk_len == 0) {
+      s.sized_by_budget = act_budget_bytes > 0;
+      s.chunk_len = s.extent;
+    } else {
+      s.chunk_len = std::min<int64_t>(r.chunk_len, s.extent);
+    }
+  }
+
+  // ---- size the regions left open from the budget: largest length (the extent itself, or
+  // a multiple of the row granule below it) whose paper-style region bytes fit.
+  const int64_t granule = m.dtype == AC_BF16 ? 128 : 64;
+  auto rows_of = [&](const Setting& s, int64_t len) { return model_rows(m, s, len); };
+  if (act_budget_bytes > 0) {
+    for (int k = first; k < first + count; ++k) {
+      Setting& s = p->set[k];
+      if (s.sized_by_budget) {
+        int64_t c = s.extent;
+        const int64_t g = s.chunk_dim == AC_DIM_BATCH && m.workload == AC_TRANSFORMER_STACK ? 1 : granule;
+        if (model_bytes(m, k, rows_of(s, c)) > act_budget_bytes) {
+          c = (s.extent - 1) / g * g;
+          while (c >= g && model_bytes(m, k, rows_of(s, c)) > act_budget_bytes) c -= g;
+          if (c < g) {
+            const uint64_t floor_b = model_bytes(m, k, rows_of(s, g));
+            delete p;
+            return fail(AC_ERR_BUDGET_INFEASIBLE,
+                        "region %d needs %llu bytes even at chunk_len %lld; budget is %llu", k,
+                        (unsigned long long)floor_b, (long long)g, (unsigned long long)act_budget_bytes);
+          }
+        }
+        s.chunk_len = c;
+      } else if (model_bytes(m, k, rows_of(s, s.chunk_len)) > act_budget_bytes) {
+        const uint64_t need = model_bytes(m, k, rows_of(s, s.chunk_len));
+        const long long len = (long long)s.chunk_len;
+        delete p;
+        return fail(AC_ERR_BUDGET_INFEASIBLE, "region %d at chunk_len %lld needs %llu bytes; budget is %llu", k,
+                    len, (unsigned long long)need, (unsigned long long)act_budget_bytes);
+      }
+    }
+  }
+
+  // ---- weights
+  if (m.workload == AC_TRANSFORMER_STACK) {
+    const int64_t d = m.d_model, F = m.d_ffn;
+    const int64_t shp[12][2] = {{1, d}, {1, d}, {3 * d, d}, {1, 3 * d}, {d, d}, {1, d},
+                                {1, d}, {1, d}, {F, d}, {1, F}, {d, F}, {1, d}};
+    for (int l = 0; l < m.layers; ++l)
+      for (int t = 0; t < 12; ++t) {
+        char nm[48];
+        snprintf(nm, sizeof(nm), "L%d.%s", l, kLayerTensor[t]);
+        p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
+      }
+  }
+  p->wptr.assign(p->weights.size(), nullptr);
+
+  // ---- plan = dry run of the walk; shrink budget-sized regions while the executor's own
+  // bytes exceed the budget (they are a subset of the model's tensors, so this rarely bites).
+  ac_plan_info& inf = p->info;
+  memset(&inf, 0, sizeof(inf));
+  uint64_t arena = 0;
+  double flops = 0;
+  for (;;) {
+    dry_run(p, false, arena, flops);
+    if (act_budget_bytes == 0 || io_bytes(m) + arena <= act_budget_bytes) break;
+    int victim = -1;
+    for (int k = first; k < first + count; ++k)
+      if (p->set[k].sized_by_budget && p->set[k].chunk_len > granule &&
+          (victim < 0 || p->set[k].chunk_len > p->set[victim].chunk_len))
+        victim = k;
+    if (victim < 0) {
+      delete p;
+      return fail(AC_ERR_BUDGET_INFEASIBLE, "executor needs %llu bytes; budget is %llu",
+                  (unsigned long long)(io_bytes(m) + arena), (unsigned long long)act_budget_bytes);
+    }
+    Setting& s = p->set[victim];
+    s.chunk_len = std::max<int64_t>(granule, (s.chunk_len / 2 + granule - 1) / granule * granule);
+  }
+  inf.workspace_bytes = arena;
+  inf.io_bytes = io_bytes(m);
+  inf.peak_bytes_planned = inf.io_bytes + arena;
+  inf.flops_per_execute = flops;
+  uint64_t arena1 = 0;
+  double f1 = 0;
+  dry_run(p, true, arena1, f1);
+  inf.peak_bytes_unchunked_planned = inf.io_bytes + arena1;
+  inf.n_regions = count;
+  for (int k = first; k < first + count; ++k) {
+    const Setting& s = p->set[k];
+    ac_region_info& ri = inf.regions[k - first];
+    ri.kind = k;
+    ri.chunk_dim = s.chunk_dim;
+    ri.extent = s.extent;
+    ri.chunk_len = s.chunk_len;
+    ri.n_segments = ceil_div(s.extent, s.chunk_len);
+    ri.model_bytes = model_bytes(m, k, rows_of(s, s.chunk_len));
+    ri.model_bytes_unchunked = model_bytes(m, k, rows_of(s, s.extent));
+    inf.peak_bytes_model = std::max(inf.peak_bytes_model, ri.model_bytes);
+    inf.peak_bytes_model_unchunked = std::max(inf.peak_bytes_model_unchunked, ri.model_bytes_unchunked);
+  }
+  inf.n_weights = (int32_t)p->weights.size();
+  for (const WeightSlot& ws : p->weights) inf.weight_bytes += (uint64_t)ws.rows * ws.cols * elem_bytes(m.dtype);
+  *out = p;
+  return AC_OK;
+}
+
+int ac_plan_query(const ac_plan* plan, ac_plan_info* out) {
+  if (!plan || !out) return fail(AC_ERR_ARG, "ac_plan_query: null argument");
+  *out = plan->info;
+  return AC_OK;
+}
+
+int ac_plan_weight_info(const ac_plan* plan, int index, ac_weight_info* out) {
+  if (!plan || !out) return fail(AC_ERR_ARG, "ac_plan_weight_info: null argument");
+  if (index < 0 || index >= (int)plan->weights.size()) return fail(AC_ERR_ARG, "weight index %d out of range", index);
+  const WeightSlot& ws = plan->weights[index];
+  memset(out, 0, sizeof(*out));
+  snprintf(out->name, sizeof(out->name), "%s", ws.name.c_str());
+  out->rows = ws.rows;
+  out->cols = ws.cols;
+  out->dtype = plan->m.dtype;
+  out->index = index;
+  return AC_OK;
+}
+
+int ac_plan_bind_weights(ac_plan* plan, const void* const* dev_ptrs, int n_ptrs) {
+  if (!plan || !dev_ptrs) return fail(AC_ERR_ARG, "ac_plan_bind_weights: null argument");
+  if (n_ptrs != (int)plan->weights.size())
+    return fail(AC_ERR_ARG, "expected %d weight pointers, got %d", (int)plan->weights.size(), n_ptrs);
+  for (int i = 0; i < n_ptrs; ++i) {
+    if (!dev_ptrs[i]) return fail(AC_ERR_ARG, "weight %d (%s) is null", i, plan->weights[i].name.c_str());
+    if (!aligned256(dev_ptrs[i])) return fail(AC_ERR_ALIGN, "weight %d (%s) is not 256-byte aligned", i, plan->weights[i].name.c_str());
+  }
+  plan->wptr.assign(dev_ptrs, dev_ptrs + n_ptrs);
+  plan->bound = true;
+  return AC_OK;
+}
+
+int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_dev, uint64_t workspace_bytes,
+               void* stream, uint64_t* measured_peak_bytes) {
+  if (!plan || !x_dev || !y_dev) return fail(AC_ERR_ARG, "ac_execute: null argument");
+  if (!plan->bound) return fail(AC_ERR_STATE, "weights are not bound");
+  if (workspace_bytes < plan->info.workspace_bytes || (plan->info.workspace_bytes > 0 && !workspace_dev))
+    return fail(AC_ERR_WORKSPACE, "workspace has %llu bytes, plan needs %llu", (unsigned long long)workspace_bytes,
+                (unsigned long long)plan->info.workspace_bytes);
+  if (!aligned256(x_dev) || !aligned256(y_dev) || !aligned256(workspace_dev))
+    return fail(AC_ERR_ALIGN, "x, y and workspace must be 256-byte aligned");
+  const uint64_t half = plan->info.io_bytes / 2;
+  const uint8_t* xb = (const uint8_t*)x_dev;
+  const uint8_t* yb = (const uint8_t*)y_dev;
+  if (xb < yb + half && yb < xb + half) return fail(AC_ERR_ARG, "x and y overlap");
+  Walk wk{plan, false, false, (hipStream_t)stream};
+  wk.arena.base = (uint8_t*)workspace_dev;
+  if (plan->m.workload == AC_TRANSFORMER_STACK) wk.transformer(x_dev, y_dev);
+  if (measured_peak_bytes) *measured_peak_bytes = plan->info.io_bytes + wk.arena.high;
+  if (!wk.ok()) return fail(AC_ERR_HIP, "%s: %s", wk.err_where, hipGetErrorString(wk.err));
+  return AC_OK;
+}
+
+void ac_plan_destroy(ac_plan* plan) {
+  if (!plan) return;
+  for (hipEvent_t e : plan->pool) (void)hipEventDestroy(e);
+  delete plan;
+}
+
+int ac_plan_set_profiling(ac_plan* plan, int enabled) {
+  if (!plan) return fail(AC_ERR_ARG, "ac_plan_set_profiling: null plan");
+  plan->profiling = enabled != 0;
+  plan->recs.clear();
+  plan->pool_used = 0;
+  return AC_OK;
+}
+
+int ac_plan_read_profile(ac_plan* plan, ac_kernel_stat* out, int max_stats, int* n_out) {
+  if (!plan || !out || !n_out || max_stats < 1) return fail(AC_ERR_ARG, "ac_plan_read_profile: bad argument");
+  if (!plan->profiling) return fail(AC_ERR_STATE, "profiling is not enabled");
+  ac_kernel_stat acc[K_CLASSES];
+  memset(acc, 0, sizeof(acc));
+  for (int c = 0; c < K_CLASSES; ++c) snprintf(acc[c].name, sizeof(acc[c].name), "%s", kClassName[c]);
+  for (const ProfRec& r : plan->recs) {
+    hipError_t e = hipEventSynchronize(r.stop);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e != hipSuccess) return fail(AC_ERR_HIP, "event timing: %s", hipGetErrorString(e));
+    acc[r.cls].launches += 1;
+    acc[r.cls].total_ms += ms;
+    acc[r.cls].flops += r.flops;
+    acc[r.cls].bytes += r.bytes;
+  }
+  int n = 0;
+  for (int c = 0; c < K_CLASSES && n < max_stats; ++c)
+    if (acc[c].launches > 0) out[n++] = acc[c];
+  *n_out = n;
+  plan->recs.clear();
+  plan->pool_used = 0;
+  return AC_OK;
+}
+
+// ---- single kernels ---------------------------------------------------------------------
+
+static int hip_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return AC_OK;
+  if (e == hipErrorNotSupported) return fail(AC_ERR_UNSUPPORTED, "%s: no kernel covers this shape", what);
+  return fail(AC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+static bool dtype_ok(int dt) { return dt == AC_F32 || dt == AC_BF16; }
+
+int ac_op_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y, int64_t ldy,
+                    int64_t rows, int64_t cols, float eps, int dtype, void* stream) {
+  if (!x || !gain || !shift || !y || rows < 0 || cols < 1 || ldx < cols || ldy < cols || !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_layernorm: bad argument");
+  return hip_status(launch_layernorm(x, ldx, gain, shift, y, ldy, rows, cols, eps, dtype, (hipStream_t)stream),
+                    "layernorm");
+}
+
+int ac_op_linear(const void* a, int64_t lda, const void* w, int64_t ldw, const void* bias, const void* mul,
+                 int64_t ldmul, const void* residual, int64_t ldr, void* out, int64_t ldo, void* out_t,
+                 int64_t n_split, int64_t t_period, int64_t t_s1, int64_t t_s2, int64_t t_s3, int64_t m,
+                 int64_t n, int64_t k, int activation, int dtype, void* stream) {
+  if (!a || !w || m < 0 || n < 0 || k < 1 || lda < k || ldw < k || !dtype_ok(dtype) || activation < 0 ||
+      activation > AC_ACT_SIGMOID)
+    return fail(AC_ERR_ARG, "ac_op_linear: bad argument");
+  if (!out_t) n_split = n;
+  if (n_split < 0 || n_split > n || (n_split > 0 && (!out || ldo < n_split)))
+    return fail(AC_ERR_ARG, "ac_op_linear: bad output description");
+  LinearArgs g{};
+  g.a = a; g.lda = lda; g.w = w; g.ldw = ldw; g.bias = bias; g.mul = mul; g.ldmul = ldmul;
+  g.resid = residual; g.ldr = ldr; g.out = out; g.ldo = ldo; g.out_t = out_t; g.n_split = n_split;
+  g.t_period = t_period; g.t_s1 = t_s1; g.t_s2 = t_s2; g.t_s3 = t_s3; g.m = m; g.n = n; g.k = k;
+  g.act = activation; g.dtype = dtype;
+  return hip_status(launch_linear(g, (hipStream_t)stream), "linear");
+}
+
+int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch, const void* k, int64_t ldk,
+                    int64_t stride_k_batch, const void* v, int64_t ldv, int64_t stride_v_batch, int v_transposed,
+                    const void* bias, int64_t ld_bias, int64_t stride_bias_head, const void* gate, int64_t ldg,
+                    int64_t stride_g_batch, void* ctx, int64_t ldc, int64_t stride_c_batch, int64_t batch,
+                    int64_t sq, int64_t sk, int heads, int head_dim, int causal, int64_t q_offset, int dtype,
+                    void* stream) {
+  if (!q || !k || !v || !ctx || batch < 0 || sq < 0 || sk < 1 || heads < 1 || head_dim < 1 || q_offset < 0 ||
+      !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_attention: bad argument");
+  AttnArgs a{};
+  a.q = q; a.ldq = ldq; a.sq_b = stride_q_batch; a.k = k; a.ldk = ldk; a.sk_b = stride_k_batch;
+  a.v = v; a.ldv = ldv; a.sv_b = stride_v_batch; a.v_transposed = v_transposed != 0;
+  a.bias = bias; a.ld_bias = ld_bias; a.s_bias_h = stride_bias_head;
+  a.gate = gate; a.ldg = ldg; a.sg_b = stride_g_batch; a.ctx = ctx; a.ldc = ldc; a.sc_b = stride_c_batch;
+  a.batch = batch; a.sq = sq; a.sk = sk; a.heads = heads; a.head_dim = head_dim; a.causal = causal != 0;
+  a.q_offset = q_offset; a.dtype = dtype;
+  return hip_status(launch_attention(a, (hipStream_t)stream), "attention");
+}
+
+int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows, int64_t cols,
+                   int activation, int dtype, void* stream) {
+  if (!x || !y || rows < 0 || cols < 1 || ldx < cols || ldy < cols || !dtype_ok(dtype) || activation < 0 ||
+      activation > AC_ACT_SIGMOID)
+    return fail(AC_ERR_ARG, "ac_op_bias_act: bad argument");
+  return hip_status(launch_bias_act(x, ldx, bias, y, ldy, rows, cols, activation, dtype, (hipStream_t)stream),
+                    "bias_act");
+}
+
+int ac_op_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy, int64_t rows,
+                 int64_t cols, int op, int dtype, void* stream) {
+  if (!a || !b || !y || rows < 0 || cols < 1 || lda < cols || ldb < cols || ldy < cols || !dtype_ok(dtype) ||
+      (op != 0 && op != 1))
+    return fail(AC_ERR_ARG, "ac_op_binary: bad argument");
+  return hip_status(launch_binary(a, lda, b, ldb, y, ldy, rows, cols, op, dtype, (hipStream_t)stream), "binary");
+}
+
+int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows, int64_t cols, int dtype,
+                    void* stream) {
+  if (!src || !dst || rows < 0 || cols < 0 || lds < cols || ldd < rows || !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_transpose: bad argument");
+  return hip_status(launch_transpose(src, lds, dst, ldd, rows, cols, dtype, (hipStream_t)stream), "transpose");
+}
+
+int ac_op_triangle_contract(const void* a, int64_t sa_i, int64_t sa_k, const void* b, int64_t sb_j, int64_t sb_k,
+                            void* out, int64_t ni, int64_t nj, int64_t nk, int channels, int dtype, void* stream) {
+  (void)a; (void)sa_i; (void)sa_k; (void)b; (void)sb_j; (void)sb_k; (void)out; (void)ni; (void)nj; (void)nk;
+  (void)channels; (void)dtype; (void)stream;
+  return fail(AC_ERR_UNSUPPORTED, "triangle contraction is not built yet");
+}
+
+}  // extern "C"

@@ -1,0 +1,206 @@
+"""GPU parity of the single kernels against the fp64 oracle, through the C-ABI."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import transformer as O
+from util import TOL, draw, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2401_10652_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(B, arr, dtype):
+    return B.to_device(arr, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols", [(5, 64), (300, 128), (257, 768), (130, 1024), (70, 2048), (33, 100), (9, 24)])
+def test_layernorm(B, dtype, rows, cols):
+    import torch
+    from paper_2401_10652_amd.inputs import round_to_storage
+    x = round_to_storage(draw((rows, cols), 1, "f32", 2.0) + 0.5, dtype)
+    g = round_to_storage(draw((cols,), 2, "f32", 0.3) + 1, dtype)
+    b = draw((cols,), 3, dtype, 0.3)
+    dx, dg, db = dev(B, x, dtype), dev(B, g, dtype), dev(B, b, dtype)
+    y = torch.full_like(dx, float("nan"))
+    B.ac_op_layernorm(dx, dg, db, y, 1e-5)
+    torch.cuda.synchronize()
+    ref = O.layer_norm(x, g, b, 1e-5)
+    assert rel_err(host(y), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,m,n,k", [
+    ("bf16", 300, 200, 192),      # 64x64 tiles, ragged m and n
+    ("bf16", 2048, 2048, 256),    # 128x128 tiles
+    ("bf16", 1100, 3072, 128),    # 128x128 tiles, ragged m
+    ("bf16", 77, 37, 100),        # odd shape -> generic kernel
+    ("bf16", 64, 4, 128),         # n = 4 (pair-bias projection shape)
+    ("f32", 256, 192, 64),
+    ("f32", 70, 50, 33),
+])
+@pytest.mark.parametrize("epi", ["plain", "bias_gelu", "bias_resid", "sigmoid_mul_resid", "tanh", "relu"])
+def test_linear(B, dtype, m, n, k, epi):
+    import torch
+    a = draw((m, k), 10, dtype)
+    w = draw((n, k), 11, dtype, 1 / math.sqrt(k))
+    bias = draw((n,), 12, dtype, 0.5)
+    mul = draw((m, n), 13, dtype)
+    res = draw((m, n), 14, dtype)
+    da, dw = dev(B, a, dtype), dev(B, w, dtype)
+    out = torch.full((m, n), float("nan"), device="cuda", dtype=da.dtype)
+    ref = O.linear(a, w)
+    kw = {}
+    if epi == "bias_gelu":
+        kw = dict(bias=dev(B, bias, dtype), activation=B.AC_ACT_GELU_ERF)
+        ref = O.gelu_erf(ref + bias)
+    elif epi == "bias_resid":
+        kw = dict(bias=dev(B, bias, dtype), residual=dev(B, res, dtype))
+        ref = ref + bias + res
+    elif epi == "sigmoid_mul_resid":
+        kw = dict(bias=dev(B, bias, dtype), activation=B.AC_ACT_SIGMOID, mul=dev(B, mul, dtype),
+                  residual=dev(B, res, dtype))
+        ref = 1 / (1 + np.exp(-(ref + bias))) * mul + res
+    elif epi == "tanh":
+        kw = dict(activation=B.AC_ACT_GELU_TANH)
+        ref = O.gelu_tanh(ref)
+    elif epi == "relu":
+        kw = dict(activation=B.AC_ACT_RELU)
+        ref = O.relu(ref)
+    B.ac_op_linear(da, dw, out, **kw)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,m,n,k,split", [("bf16", 384, 256, 128, 128), ("bf16", 200, 96, 64, 0),
+                                               ("f32", 100, 48, 32, 16), ("bf16", 50, 30, 20, 10)])
+def test_linear_strided_store(B, dtype, m, n, k, split):
+    """Columns >= split land transposed, with a period: rows (m / P, m % P) -> [m/P][n][m%P]."""
+    import torch
+    a = draw((m, k), 20, dtype)
+    w = draw((n, k), 21, dtype, 1 / math.sqrt(k))
+    bias = draw((n,), 22, dtype, 0.5)
+    da, dw, dbias = dev(B, a, dtype), dev(B, w, dtype), dev(B, bias, dtype)
+    ref = O.linear(a, w, bias)
+    # plain transpose of the tail columns
+    out = torch.zeros((m, max(split, 1)), device="cuda", dtype=da.dtype)
+    out_t = torch.zeros((n - split, m), device="cuda", dtype=da.dtype)
+    B.ac_op_linear(da, dw, out if split else None, bias=dbias, out_t=out_t, n_split=split, t_s2=1, t_s3=m)
+    torch.cuda.synchronize()
+    if split:
+        assert rel_err(host(out)[:, :split], ref[:, :split]) <= TOL[dtype]
+    assert rel_err(host(out_t), ref[:, split:].T) <= TOL[dtype]
+    # periodic form: m = p * P + r  ->  out_t[p][n][r]
+    if m % 50 == 0:
+        P = 50
+        out_p = torch.zeros((m // P, n - split, P), device="cuda", dtype=da.dtype)
+        B.ac_op_linear(da, dw, out if split else None, bias=dbias, out_t=out_p, n_split=split,
+                       t_period=P, t_s1=(n - split) * P, t_s2=1, t_s3=P)
+        torch.cuda.synchronize()
+        want = ref[:, split:].reshape(m // P, P, n - split).transpose(0, 2, 1)
+        assert rel_err(host(out_p), want) <= TOL[dtype]
+
+
+def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate, v_t):
+    import torch
+    hd = heads * dh
+    q = draw((sq, hd), 30, dtype)
+    k = draw((sk, hd), 31, dtype)
+    v = draw((sk, hd), 32, dtype)
+    bias = draw((heads, sq, sk), 33, dtype) if use_bias else None
+    gate = draw((sq, hd), 34, dtype) if use_gate else None
+    dq, dk, dv = dev(B, q, dtype), dev(B, k, dtype), dev(B, v, dtype)
+    if v_t:
+        ld = (sk + 7) // 8 * 8
+        dvt = torch.zeros((hd, ld), device="cuda", dtype=dq.dtype)
+        B.ac_op_transpose(dv, dvt)
+        vv = dvt[:, :sk]
+    else:
+        vv = dv
+    ctx = torch.full((sq, hd), float("nan"), device="cuda", dtype=dq.dtype)
+    B.ac_op_attention(dq, dk, vv, ctx, heads, dh, causal=causal, q_offset=q_offset,
+                      bias=None if bias is None else dev(B, bias, dtype),
+                      gate=None if gate is None else dev(B, gate, dtype), v_transposed=v_t)
+    torch.cuda.synchronize()
+    ref = O.attention(q, k, v, heads, causal, bias=bias, q_offset=q_offset)
+    if gate is not None:
+        ref = ref * gate
+    got = host(ctx)
+    assert np.isfinite(got).all()
+    return rel_err(got, ref)
+
+
+@pytest.mark.parametrize("dh", [32, 64, 128])
+@pytest.mark.parametrize("sq,sk,causal,q_offset", [
+    (300, 520, False, 0),       # ragged query and key tails
+    (128, 64, False, 0),
+    (200, 456, True, 256),      # a query segment placed at its absolute position
+    (333, 336, True, 3),
+    (1, 8, True, 7),
+])
+def test_attention_mfma(B, dh, sq, sk, causal, q_offset):
+    assert _attn_case(B, "bf16", sq, sk, 3, dh, causal, q_offset, False, False, True) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dh", [32, 64])
+def test_attention_mfma_bias_gate(B, dh):
+    assert _attn_case(B, "bf16", 260, 392, 4, dh, False, 0, True, True, True) <= TOL["bf16"]
+    assert _attn_case(B, "bf16", 100, 128, 2, dh, False, 0, True, False, True) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype,dh", [("f32", 16), ("f32", 64), ("bf16", 16), ("bf16", 64)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_generic(B, dtype, dh, causal):
+    off = 40 if causal else 0
+    assert _attn_case(B, dtype, 150, 190 + off, 2, dh, causal, off, True, True, False) <= TOL[dtype]
+    assert _attn_case(B, dtype, 70, 70, 3, dh, causal, 0, False, False, False) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols", [(100, 256), (37, 51)])
+def test_elementwise(B, dtype, rows, cols):
+    import torch
+    x = draw((rows, cols), 40, dtype, 2.0)
+    r = draw((rows, cols), 41, dtype)
+    bias = draw((cols,), 42, dtype)
+    dx, dr, dbias = dev(B, x, dtype), dev(B, r, dtype), dev(B, bias, dtype)
+    y = torch.empty_like(dx)
+    for act, fn in ((B.AC_ACT_GELU_ERF, O.gelu_erf), (B.AC_ACT_GELU_TANH, O.gelu_tanh), (B.AC_ACT_RELU, O.relu),
+                    (B.AC_ACT_SIGMOID, lambda t: 1 / (1 + np.exp(-t))), (B.AC_ACT_NONE, lambda t: t)):
+        B.ac_op_bias_act(dx, dbias, y, act)
+        torch.cuda.synchronize()
+        assert rel_err(host(y), fn(x.astype(np.float64) + bias)) <= TOL[dtype]
+    B.ac_op_bias_act(dx, None, y, B.AC_ACT_GELU_ERF)
+    torch.cuda.synchronize()
+    assert rel_err(host(y), O.gelu_erf(x)) <= TOL[dtype]
+    B.ac_op_binary(dx, dr, y, 0)
+    torch.cuda.synchronize()
+    assert rel_err(host(y), x.astype(np.float64) + r) <= TOL[dtype]
+    B.ac_op_binary(dx, dr, y, 1)
+    torch.cuda.synchronize()
+    assert rel_err(host(y), x.astype(np.float64) * r) <= TOL[dtype]
+
+
+def test_bf16_store_rounds_to_nearest_even(B):
+    """x + 0 through the kernel must equal the host generator's rounding, bit for bit."""
+    import torch
+    from paper_2401_10652_amd import inputs as I
+    v = I.standard_normal(4242, 64 * 256).astype(np.float32).reshape(64, 256)
+    want = I.round_to_bf16(v)
+    # feed fp32 halves that sum to v exactly is not possible in bf16; instead add two bf16 numbers
+    hi = I.round_to_bf16(v)
+    lo = I.round_to_bf16(v - hi)
+    y = torch.empty((64, 256), device="cuda", dtype=torch.bfloat16)
+    B.ac_op_binary(B.to_device(hi, "bf16"), B.to_device(lo, "bf16"), y, 0)
+    torch.cuda.synchronize()
+    want = I.round_to_bf16(hi.astype(np.float32) + lo.astype(np.float32))
+    assert np.array_equal(y.float().cpu().numpy(), want)

@@ -1,0 +1,156 @@
+"""GPU parity of whole chunk plans against the unchunked fp64 oracle, through the C-ABI."""
+import numpy as np
+import pytest
+
+from oracle import transformer as O
+from paper_2401_10652_amd import inputs as I
+from util import TOL, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+CANARY = 0x5A
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2401_10652_amd import binding
+    binding.lib()
+    return binding
+
+
+def regions(B, c_qkv, c_attn, c_ffn, dim=None):
+    dim = B.AC_DIM_SEQ if dim is None else dim
+    return [(B.AC_REGION_QKV, dim, c_qkv), (B.AC_REGION_ATTENTION, dim, c_attn), (B.AC_REGION_FFN, dim, c_ffn)]
+
+
+class Runner:
+    """Uploads one workload, runs plans on it; every buffer is a torch tensor."""
+
+    def __init__(self, B, cfg, bias_std=0.0, ln_jitter=0.0):
+        import torch
+        self.B, self.cfg = B, cfg
+        self.x, self.layers = I.transformer_inputs(cfg, bias_std=bias_std, ln_jitter=ln_jitter)
+        self.dx = B.to_device(self.x, cfg.dtype)
+        self.dw = [B.to_device(w[name], cfg.dtype) for w in self.layers for name in I.TRANSFORMER_LAYER_TENSORS]
+        self.torch = torch
+
+    def run(self, regs, budget=0, flags=0, slack=4096):
+        B, torch = self.B, self.torch
+        p = B.Plan(B.transformer_desc(self.cfg, flags=flags), regs, budget)
+        info = p.ac_plan_query()
+        assert p.weight_names() == [f"L{l}.{n}" for l in range(self.cfg.layers) for n in I.TRANSFORMER_LAYER_TENSORS]
+        p.ac_plan_bind_weights(self.dw)
+        need = int(info.workspace_bytes)
+        ws = torch.full((need + slack,), CANARY, dtype=torch.uint8, device="cuda")
+        y = torch.full_like(self.dx, float("nan"))
+        peak = p.ac_execute(self.dx, y, ws[:need])
+        torch.cuda.synchronize()
+        # nothing beyond the declared workspace was touched, and the input is intact
+        assert bool((ws[need:] == CANARY).all())
+        assert torch.equal(self.dx, B.to_device(self.x, self.cfg.dtype))
+        assert peak == info.peak_bytes_planned
+        p.close()
+        return y, info
+
+    def oracle(self, query_block=None):
+        c = self.cfg
+        return O.transformer_stack(self.x, self.layers, c.heads, c.causal, c.activation, c.ln_eps, c.batch,
+                                   query_block=query_block)
+
+
+def test_c1_block_fp32_chunked_and_unchunked(B):
+    r = Runner(B, I.C1)
+    ref = r.oracle()
+    y4, info4 = r.run(regions(B, 64, 64, 64))
+    y1, info1 = r.run(regions(B, 256, 256, 256))
+    assert [x.n_segments for x in info4.regions[:3]] == [4, 4, 4]
+    assert rel_err(host(y4), ref) <= TOL["f32"]
+    assert rel_err(host(y1), ref) <= TOL["f32"]
+    assert info4.peak_bytes_planned < info1.peak_bytes_planned
+    assert info4.peak_bytes_unchunked_planned == info1.peak_bytes_planned
+
+
+def test_fp32_every_epilogue_and_ragged_lengths(B):
+    cfg = I.TransformerConfig("t32", 31, 2, 200, 64, 4, 160, True, "f32", None, activation="gelu_tanh")
+    r = Runner(B, cfg, bias_std=0.3, ln_jitter=0.2)
+    ref = r.oracle()
+    outs = []
+    for c in ((200, 200, 200), (64, 64, 64), (33, 77, 50), (1, 200, 7)):
+        y, _ = r.run(regions(B, *c))
+        assert rel_err(host(y), ref) <= TOL["f32"], c
+        outs.append(y)
+    yu, _ = r.run(regions(B, 64, 64, 64), flags=B.AC_FLAG_UNFUSED_ELEMENTWISE)
+    assert rel_err(host(yu), ref) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("causal,heads,act", [(True, 4, "gelu_erf"), (False, 8, "relu"), (False, 2, "gelu_tanh")])
+def test_bf16_stack_chunked_equals_oracle(B, causal, heads, act):
+    import torch
+    cfg = I.TransformerConfig("t16", 32, 2, 640, 256, heads, 1024, causal, "bf16", 0.05, activation=act)
+    r = Runner(B, cfg, bias_std=0.05, ln_jitter=0.1)
+    ref = r.oracle()
+    outs = []
+    for c in ((640, 640, 640), (128, 128, 128), (256, 384, 512), (200, 136, 72), (640, 8, 640)):
+        y, info = r.run(regions(B, *c))
+        assert rel_err(host(y), ref) <= TOL["bf16"], c
+        outs.append(y)
+    # the K loop and the key-tile order do not depend on the segment a row falls in:
+    # every chunk length gives bit-identical output
+    for y in outs[1:]:
+        assert torch.equal(y, outs[0])
+    yu, _ = r.run(regions(B, 128, 128, 128), flags=B.AC_FLAG_UNFUSED_ELEMENTWISE)
+    assert rel_err(host(yu), ref) <= TOL["bf16"]
+
+
+def test_batch_and_batch_chunks(B):
+    import torch
+    cfg = I.TransformerConfig("tb", 33, 1, 136, 128, 2, 256, True, "bf16", 0.05, batch=3)
+    r = Runner(B, cfg, bias_std=0.05, ln_jitter=0.1)
+    ref = r.oracle()
+    ys, _ = r.run(regions(B, 64, 64, 64))
+    yb, info = r.run(regions(B, 2, 1, 3, dim=B.AC_DIM_BATCH))
+    assert [x.n_segments for x in info.regions[:3]] == [2, 3, 1]
+    assert rel_err(host(ys), ref) <= TOL["bf16"] and rel_err(host(yb), ref) <= TOL["bf16"]
+    assert torch.equal(ys, yb)
+    cfg32 = I.TransformerConfig("tb32", 34, 1, 50, 32, 2, 64, False, "f32", None, batch=2)
+    r32 = Runner(B, cfg32, bias_std=0.2)
+    y, _ = r32.run(regions(B, 1, 2, 1, dim=B.AC_DIM_BATCH))
+    assert rel_err(host(y), r32.oracle()) <= TOL["f32"]
+
+
+def test_budget_sized_plan_runs(B):
+    cfg = I.TransformerConfig("tbud", 35, 1, 1024, 256, 4, 1024, True, "bf16", 0.05)
+    r = Runner(B, cfg)
+    budget = 6 << 20
+    y, info = r.run(regions(B, 0, 0, 0), budget=budget)
+    assert info.regions[1].n_segments > 1 and info.peak_bytes_model <= budget and info.peak_bytes_planned <= budget
+    assert rel_err(host(y), r.oracle()) <= TOL["bf16"]
+
+
+def test_profiling_reports_kernel_classes(B):
+    import torch
+    cfg = I.TransformerConfig("tprof", 36, 2, 256, 128, 2, 512, False, "bf16", 0.05)
+    r = Runner(B, cfg)
+    p = B.Plan(B.transformer_desc(cfg), regions(B, 128, 128, 128))
+    info = p.ac_plan_query()
+    p.ac_plan_bind_weights(r.dw)
+    ws = B.empty_workspace(info.workspace_bytes)
+    y = torch.empty_like(r.dx)
+    p.ac_plan_set_profiling(True)
+    p.ac_execute(r.dx, y, ws)
+    stats = {s["name"]: s for s in p.ac_plan_read_profile()}
+    assert set(stats) == {"gemm", "attention", "layernorm"}
+    assert stats["gemm"]["launches"] == 2 * 2 * 4 and stats["attention"]["launches"] == 4
+    assert stats["layernorm"]["launches"] == 8
+    total = sum(s["flops"] for s in stats.values())
+    assert abs(total - info.flops_per_execute) <= 1e-9 * total
+    assert all(s["total_ms"] > 0 for s in stats.values())
+    assert p.ac_plan_read_profile() == []
+    p.ac_plan_set_profiling(False)
+    with pytest.raises(B.AcError) as ei:
+        p.ac_plan_read_profile()
+    assert ei.value.status == B.AC_ERR_STATE
+    y2 = torch.empty_like(r.dx)
+    p.ac_execute(r.dx, y2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
