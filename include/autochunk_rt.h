@@ -260,15 +260,31 @@ int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_
                     int64_t cols, int dtype, void* stream);
 
 /*
- * Triangle contraction on `ni` output rows: out[i,j,c] = sum_k a[i,k,c] * b[j,k,c], with a
- * addressed as a[i * sa_i + k * sa_k + c], b as b[j * sb_j + k * sb_k + c] and out as
- * [ni, nj, channels] contiguous; the incoming form is the same call with the i/k strides
- * of a (and j/k of b) exchanged.  Storage bf16, fp32 accumulation.
+ * Triangle contraction on `ni` output rows, one product per channel c:
+ *   out_c[c][i][j] = sum_k a_t[c][i][k] * b_t[c][j][k]
+ * with a_t[c * stride_a_c + i * lda + k], b_t[c * stride_b_c + j * ldb + k] and
+ * out_c[c * stride_o_c + i * ldo + j].  The outgoing form of the triangle multiplicative
+ * update has a_t[c][i][k] = a[i,k,c]; the incoming form a_t[c][i][k] = a[k,i,c] (both operands
+ * are held channel-major with the contraction index contiguous, which ac_op_linear's strided
+ * store writes; ac_op_transpose_square_inplace turns one form into the other).
  */
-int ac_op_triangle_contract(const void* a, int64_t sa_i, int64_t sa_k,
-                            const void* b, int64_t sb_j, int64_t sb_k,
-                            void* out, int64_t ni, int64_t nj, int64_t nk, int channels,
-                            int dtype, void* stream);
+int ac_op_triangle_contract(const void* a_t, int64_t lda, int64_t stride_a_c,
+                            const void* b_t, int64_t ldb, int64_t stride_b_c,
+                            void* out_c, int64_t ldo, int64_t stride_o_c,
+                            int64_t ni, int64_t nj, int64_t nk, int channels, int dtype, void* stream);
+
+/* In-place transpose of `batch` square [n, n] matrices (row stride ld, stride_batch apart). */
+int ac_op_transpose_square_inplace(void* data, int64_t ld, int64_t stride_batch, int64_t n,
+                                   int64_t batch, int dtype, void* stream);
+
+/*
+ * LayerNorm over the channels of a channel-major tensor, written position-major:
+ * dst[p * ldd + c] = LN_c(src[c * stride_c + p]) * gain[c] + shift[c]  (what follows the
+ * triangle contraction, whose output is channel-major).
+ */
+int ac_op_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain,
+                                  const void* shift, void* dst, int64_t ldd, int64_t positions,
+                                  int64_t channels, float eps, int dtype, void* stream);
 
 #ifdef __cplusplus
 }

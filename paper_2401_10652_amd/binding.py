@@ -87,7 +87,9 @@ SIGNATURES = {
     "ac_op_bias_act": (INT, [VP, I64, VP, VP, I64, I64, I64, INT, INT, VP]),
     "ac_op_binary": (INT, [VP, I64, VP, I64, VP, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose": (INT, [VP, I64, VP, I64, I64, I64, INT, VP]),
-    "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, INT, INT, VP]),
+    "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, I64, I64, INT, INT, VP]),
+    "ac_op_transpose_square_inplace": (INT, [VP, I64, I64, I64, I64, INT, VP]),
+    "ac_op_layernorm_channel_major": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
 }
 
 _lib = None
@@ -280,6 +282,30 @@ def ac_op_transpose(src, dst):
     rows, cols = src.shape
     _check(lib().ac_op_transpose(_ptr(src), src.stride(0), _ptr(dst), dst.stride(0), rows, cols, _dt(src),
                                  _stream()), "ac_op_transpose")
+
+
+def ac_op_triangle_contract(a_t, b_t, out_c):
+    """a_t [C, ni, nk], b_t [C, nj, nk] -> out_c [C, ni, nj] (views with strides are fine)."""
+    ch, ni, nk = a_t.shape
+    nj = b_t.shape[1]
+    _check(lib().ac_op_triangle_contract(_ptr(a_t), a_t.stride(1), a_t.stride(0), _ptr(b_t), b_t.stride(1),
+                                         b_t.stride(0), _ptr(out_c), out_c.stride(1), out_c.stride(0),
+                                         ni, nj, nk, ch, _dt(a_t), _stream()), "ac_op_triangle_contract")
+
+
+def ac_op_transpose_square_inplace(data):
+    """data [batch, n, n], transposed in place per batch entry."""
+    batch, n, _ = data.shape
+    _check(lib().ac_op_transpose_square_inplace(_ptr(data), data.stride(1), data.stride(0), n, batch, _dt(data),
+                                                _stream()), "ac_op_transpose_square_inplace")
+
+
+def ac_op_layernorm_channel_major(src, gain, shift, dst, eps=1e-5):
+    """src [C, P] -> dst [P, C]."""
+    ch, pos = src.shape
+    _check(lib().ac_op_layernorm_channel_major(_ptr(src), src.stride(0), _ptr(gain), _ptr(shift), _ptr(dst),
+                                               dst.stride(0), pos, ch, eps, _dt(src), _stream()),
+           "ac_op_layernorm_channel_major")
 
 
 # ---- helpers for callers (buffers only) ------------------------------------------------------

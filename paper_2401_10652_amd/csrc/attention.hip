@@ -169,6 +169,7 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   // last key position any row of this wave may see (wave-uniform)
   int64_t wave_last = q0 + wave * 32 + 31; if (wave_last > a.sq - 1) wave_last = a.sq - 1;
   wave_last += a.q_offset;
+  const bool wave_active = q0 + wave * 32 < a.sq;   // waves past the last query row only help staging
 
   // staging: which chunks of a K tile / V^T tile this thread moves
   int k_row[K_CHUNKS], k_col[K_CHUNKS], v_row[V_CHUNKS], v_col[V_CHUNKS];
@@ -222,7 +223,7 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     const bool more = kt + 1 < n_tiles;
     if (more) load_tile(k0 + kKB);
 
-    if (!CAUSAL || k0 <= wave_last) {
+    if (wave_active && (!CAUSAL || k0 <= wave_last)) {
       // ---- S^T = K Q^T for two 32-key tiles
       f32x16 acc_s[2];
       const bf16_t* ck = sK + buf * kKB * KROW + l32 * KROW + half * 8;

@@ -106,6 +106,9 @@ struct LinearArgs {
   int64_t m, n, k;
   int act;
   int dtype;
+  // batch > 1: `batch` independent products; a, w and out advance by these strides (elements).
+  // bias / mul / resid / out_t must be null then.
+  int64_t batch, sa_b, sw_b, so_b;
 };
 
 struct AttnArgs {
@@ -135,6 +138,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 // of the attention entry point that hold v row-major.
 hipError_t launch_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows,
                             int64_t cols, int dtype, hipStream_t s);
+// In-place transpose of `batch` square [n, n] matrices (row stride ld, `stride_b` apart).
+hipError_t launch_transpose_square_inplace(void* data, int64_t ld, int64_t stride_b, int64_t n,
+                                           int64_t batch, int dtype, hipStream_t s);
+// LayerNorm over channels of a channel-major tensor: src[c * stride_c + p] -> dst[p * ldd + c].
+hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain,
+                                          const void* shift, void* dst, int64_t ldd, int64_t positions,
+                                          int64_t channels, float eps, int dtype, hipStream_t s);
 
 // hipErrorInvalidValue-style refusal with a message for ac_last_error().
 void set_error(const char* fmt, ...);

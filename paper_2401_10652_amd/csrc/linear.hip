@@ -40,8 +40,8 @@ __global__ void __launch_bounds__(256) linear_fma(LinearArgs g) {
   __shared__ float sw[16][65];
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
-  const T* a = (const T*)g.a;
-  const T* w = (const T*)g.w;
+  const T* a = (const T*)g.a + (int64_t)blockIdx.z * g.sa_b;
+  const T* w = (const T*)g.w + (int64_t)blockIdx.z * g.sw_b;
   float acc[4][4] = {};
   for (int64_t k0 = 0; k0 < g.k; k0 += 16) {
 #pragma unroll
@@ -70,7 +70,10 @@ __global__ void __launch_bounds__(256) linear_fma(LinearArgs g) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < g.m && n < g.n) epilogue_store_one<T>(g, m, n, acc[i][j]);
+      if (m < g.m && n < g.n) {
+        if (g.batch > 1) Elem<T>::st((T*)g.out + (int64_t)blockIdx.z * g.so_b + m * g.ldo + n, acc[i][j]);
+        else epilogue_store_one<T>(g, m, n, acc[i][j]);
+      }
     }
 }
 
@@ -144,8 +147,9 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
   int64_t tm_, tn_;
   tile_of_block(tiles_m, tiles_n, tm_, tn_);
   const int64_t m0 = tm_ * BM, n0 = tn_ * BN;
-  const bf16_t* a = (const bf16_t*)g.a;
-  const bf16_t* w = (const bf16_t*)g.w;
+  const bf16_t* a = (const bf16_t*)g.a + (int64_t)blockIdx.y * g.sa_b;
+  const bf16_t* w = (const bf16_t*)g.w + (int64_t)blockIdx.y * g.sw_b;
+  g.out = (bf16_t*)g.out + (int64_t)blockIdx.y * g.so_b;
 
   // Global source of each 16-byte chunk this thread stages (rows clamped into range; the
   // results of clamped rows are never stored).
@@ -256,7 +260,7 @@ static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
     attr_set = true;
   }
   const int64_t tiles = ((g.m + BM - 1) / BM) * ((g.n + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(256), lds, s, g);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)g.batch), dim3(256), lds, s, g);
   return hipGetLastError();
 }
 
@@ -269,6 +273,7 @@ static bool mfma_eligible(const LinearArgs& g) {
   if (g.lda % 8 != 0 || g.ldw % 8 != 0) return false;
   if (!aligned_to(g.a, 16) || !aligned_to(g.w, 16)) return false;
   if (g.n_split > 0 && (g.ldo % 4 != 0 || !aligned_to(g.out, 8))) return false;
+  if (g.batch > 1 && (g.sa_b % 8 != 0 || g.sw_b % 8 != 0 || g.so_b % 4 != 0)) return false;
   if (g.bias && !aligned_to(g.bias, 8)) return false;
   if (g.mul && (g.ldmul % 4 != 0 || !aligned_to(g.mul, 8))) return false;
   if (g.resid && (g.ldr % 4 != 0 || !aligned_to(g.resid, 8))) return false;
@@ -282,13 +287,16 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (g.out_t == nullptr) g.n_split = g.n;
   if (g.n_split > g.n) g.n_split = g.n;
   if (g.t_period <= 0) g.t_period = INT64_MAX;
+  if (g.batch < 1) g.batch = 1;
+  if (g.batch > 1 && (g.bias || g.mul || g.resid || g.out_t || g.act != AC_ACT_NONE)) return hipErrorInvalidValue;
+  if (g.batch > 65535) return hipErrorInvalidValue;
   if (mfma_eligible(g)) {
     // 128x128 tiles when they fill the 256 CUs, otherwise 64x64 tiles (4x as many blocks).
-    const int64_t big = ((g.m + 127) / 128) * ((g.n + 127) / 128);
-    if (big >= 192) return mfma_launch<128, 128>(g, s);
+    const int64_t big = ((g.m + 127) / 128) * ((g.n + 127) / 128) * g.batch;
+    if (big >= 192 && g.m >= 128) return mfma_launch<128, 128>(g, s);
     return mfma_launch<64, 64>(g, s);
   }
-  dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64));
+  dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)g.batch);
   if (g.dtype == AC_BF16) hipLaunchKernelGGL((linear_fma<bf16_t>), grid, dim3(256), 0, s, g);
   else hipLaunchKernelGGL((linear_fma<float>), grid, dim3(256), 0, s, g);
   return hipGetLastError();

@@ -266,4 +266,100 @@ hipError_t launch_transpose(const void* src, int64_t lds_, void* dst, int64_t ld
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------
+// In-place transpose of square matrices, by pairs of 64x64 tiles (bi <= bj): both tiles go
+// to LDS, each is written transposed into the other's place.  grid.x enumerates the tile
+// pairs of the upper triangle, grid.y the matrices.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+transpose_square_inplace(T* __restrict__ data, int64_t ld, int64_t stride_b, int64_t n, int tiles) {
+  __shared__ T ta[64][65];
+  __shared__ T tb[64][65];
+  // pair index -> (bi, bj), bi <= bj, rows of the upper triangle laid end to end
+  int p = blockIdx.x, bi = 0;
+  while (p >= tiles - bi) { p -= tiles - bi; ++bi; }
+  const int bj = bi + p;
+  T* mat = data + (int64_t)blockIdx.y * stride_b;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  const int64_t r0 = (int64_t)bi * 64, c0 = (int64_t)bj * 64;
+  for (int i = ty; i < 64; i += 4) {
+    if (r0 + i < n && c0 + tx < n) ta[i][tx] = mat[(r0 + i) * ld + c0 + tx];
+    if (bi != bj && c0 + i < n && r0 + tx < n) tb[i][tx] = mat[(c0 + i) * ld + r0 + tx];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    // tile (bj, bi) receives ta transposed; tile (bi, bj) receives tb transposed
+    if (c0 + i < n && r0 + tx < n) mat[(c0 + i) * ld + r0 + tx] = ta[tx][i];
+    if (bi != bj && r0 + i < n && c0 + tx < n) mat[(r0 + i) * ld + c0 + tx] = tb[tx][i];
+  }
+}
+
+hipError_t launch_transpose_square_inplace(void* data, int64_t ld, int64_t stride_b, int64_t n, int64_t batch,
+                                           int dtype, hipStream_t s) {
+  if (n <= 0 || batch <= 0) return hipSuccess;
+  if (batch > 65535) return hipErrorInvalidValue;
+  const int tiles = (int)((n + 63) / 64);
+  dim3 grid((unsigned)(tiles * (tiles + 1) / 2), (unsigned)batch);
+  if (dtype == AC_BF16)
+    hipLaunchKernelGGL((transpose_square_inplace<bf16_t>), grid, dim3(256), 0, s, (bf16_t*)data, ld, stride_b, n, tiles);
+  else
+    hipLaunchKernelGGL((transpose_square_inplace<float>), grid, dim3(256), 0, s, (float*)data, ld, stride_b, n, tiles);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// LayerNorm over the channels of a channel-major tensor src[c][p], written position-major
+// dst[p][c].  A block takes 64 consecutive positions: coalesced reads along p for every
+// channel into an LDS tile [64][C], then one 16-lane group per position normalises its row
+// and stores it with 16-byte accesses.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+layernorm_channel_major(const T* __restrict__ src, int64_t stride_c, const T* __restrict__ gain,
+                        const T* __restrict__ shift, T* __restrict__ dst, int64_t ldd, int64_t positions,
+                        int channels, float eps) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* tile = reinterpret_cast<float*>(smem_raw);   // [64][channels + 1]
+  const int ldt = channels + 1;
+  const int64_t p0 = (int64_t)blockIdx.x * 64;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  for (int c = ty; c < channels; c += 4) {
+    const int64_t p = p0 + tx;
+    tile[tx * ldt + c] = p < positions ? Elem<T>::ld(src + (int64_t)c * stride_c + p) : 0.f;
+  }
+  __syncthreads();
+  // 16 groups of 16 lanes; group g handles positions g, g + 16, g + 32, g + 48
+  const int grp = threadIdx.x / 16, lane = threadIdx.x % 16;
+  for (int pp = grp; pp < 64; pp += 16) {
+    const int64_t p = p0 + pp;
+    const float* row = tile + pp * ldt;
+    float sum = 0.f;
+    for (int c = lane; c < channels; c += 16) sum += row[c];
+    const float mean = group_sum<16>(sum) / (float)channels;
+    float sq = 0.f;
+    for (int c = lane; c < channels; c += 16) { const float d = row[c] - mean; sq += d * d; }
+    const float rstd = rsqrtf(group_sum<16>(sq) / (float)channels + eps);
+    if (p < positions)
+      for (int c = lane; c < channels; c += 16)
+        Elem<T>::st(dst + p * ldd + c, (row[c] - mean) * rstd * Elem<T>::ld(gain + c) + Elem<T>::ld(shift + c));
+  }
+}
+
+hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain, const void* shift,
+                                          void* dst, int64_t ldd, int64_t positions, int64_t channels, float eps,
+                                          int dtype, hipStream_t s) {
+  if (positions <= 0 || channels <= 0) return hipSuccess;
+  const size_t lds = (size_t)64 * (channels + 1) * sizeof(float);
+  if (lds > 64 * 1024) return hipErrorNotSupported;
+  dim3 grid((unsigned)((positions + 63) / 64));
+  if (dtype == AC_BF16)
+    hipLaunchKernelGGL((layernorm_channel_major<bf16_t>), grid, dim3(256), lds, s, (const bf16_t*)src, stride_c,
+                       (const bf16_t*)gain, (const bf16_t*)shift, (bf16_t*)dst, ldd, positions, (int)channels, eps);
+  else
+    hipLaunchKernelGGL((layernorm_channel_major<float>), grid, dim3(256), lds, s, (const float*)src, stride_c,
+                       (const float*)gain, (const float*)shift, (float*)dst, ldd, positions, (int)channels, eps);
+  return hipGetLastError();
+}
+
 }  // namespace ac

@@ -208,9 +208,36 @@ struct Walk {
     }
   }
 
+  void transpose_inplace(void* data, int64_t ld, int64_t stride_b, int64_t n, int64_t batch) {
+    const int dt = p->m.dtype;
+    run(K_ELEM, 0.0, 2.0 * n * n * batch * eb(), "transpose",
+        [&] { return launch_transpose_square_inplace(data, ld, stride_b, n, batch, dt, stream); });
+  }
+  void ln_channel_major(const void* src, int64_t stride_c, const void* g, const void* b, void* dst, int64_t ldd,
+                        int64_t positions, int64_t channels) {
+    const int dt = p->m.dtype;
+    const float eps = p->m.ln_eps;
+    run(K_LN, 8.0 * positions * channels, 2.0 * positions * channels * eb(), "layernorm_channel_major", [&] {
+      return launch_layernorm_channel_major(src, stride_c, g, b, dst, ldd, positions, channels, eps, dt, stream);
+    });
+  }
+  // out_c[c][i][j] = sum_k a_t[c][i][k] * b_t[c][j][k]: one NT product per channel.
+  void contract(const void* a_t, int64_t lda, int64_t sa_c, const void* b_t, int64_t ldb, int64_t sb_c, void* out_c,
+                int64_t ldo, int64_t so_c, int64_t ni, int64_t nj, int64_t nk, int64_t channels) {
+    LinearArgs g{};
+    g.a = a_t; g.lda = lda; g.sa_b = sa_c; g.w = b_t; g.ldw = ldb; g.sw_b = sb_c; g.out = out_c; g.ldo = ldo;
+    g.so_b = so_c; g.m = ni; g.n = nj; g.k = nk; g.n_split = nj; g.batch = channels; g.dtype = p->m.dtype;
+    const double by = ((double)ni * nk + (double)nj * nk + (double)ni * nj) * channels * eb();
+    run(K_TRI, 2.0 * ni * nj * nk * channels, by, "triangle_contract", [&] { return launch_linear(g, stream); });
+  }
+
   int64_t seg_len(int kind) const { return unchunked ? p->set[kind].extent : p->set[kind].chunk_len; }
 
   void transformer(const void* x, void* y);
+  void pair(const void* x, void* y);
+  void tri_mul(int kind, const void* const* W, const void* zin, void* zout);
+  void tri_att(int kind, const void* const* W, const void* zin, void* zout);
+  void transition(const void* const* W, const void* zin, void* zout);
 };
 
 static const char* const kLayerTensor[12] = {"ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -310,6 +337,224 @@ void Walk::transformer(const void* x, void* y) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Pair stack.  z is [N, N, c_z]; "rows" are the N*N positions, a segment is a run of output
+// rows i (ni * N positions).  Whole operands of a module (the non-chunkable inputs of its
+// chunked part) are built first, segment by segment, then the chunked part runs.
+// ---------------------------------------------------------------------------------------
+enum { TM_LN_IN_G, TM_LN_IN_B, TM_W_AP, TM_B_AP, TM_W_AG, TM_B_AG, TM_W_BP, TM_B_BP, TM_W_BG, TM_B_BG,
+       TM_W_G, TM_B_G, TM_LN_OUT_G, TM_LN_OUT_B, TM_W_O, TM_B_O, TM_COUNT };
+enum { TA_LN_G, TA_LN_B, TA_W_Q, TA_W_K, TA_W_V, TA_W_BIAS, TA_W_G, TA_B_G, TA_W_O, TA_B_O, TA_COUNT };
+enum { PT_LN_G, PT_LN_B, PT_W_1, PT_B_1, PT_W_2, PT_B_2, PT_COUNT };
+constexpr int kPairWeights = 2 * TM_COUNT + 2 * TA_COUNT + PT_COUNT;
+
+static const char* const kTmName[TM_COUNT] = {"ln_in_g", "ln_in_b", "w_ap", "b_ap", "w_ag", "b_ag", "w_bp", "b_bp",
+                                              "w_bg", "b_bg", "w_g", "b_g", "ln_out_g", "ln_out_b", "w_o", "b_o"};
+static const char* const kTaName[TA_COUNT] = {"ln_g", "ln_b", "w_q", "w_k", "w_v", "w_bias", "w_g", "b_g", "w_o", "b_o"};
+static const char* const kPtName[PT_COUNT] = {"ln_g", "ln_b", "w_1", "b_1", "w_2", "b_2"};
+
+struct RowSeg { int64_t i0, ni; };
+static std::vector<RowSeg> row_segments(int64_t n, int64_t len) {
+  std::vector<RowSeg> v;
+  for (int64_t i = 0; i < n; i += len) v.push_back(RowSeg{i, std::min<int64_t>(len, n - i)});
+  return v;
+}
+
+void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) {
+  const ac_model_desc& m = p->m;
+  const int64_t N = m.n_res, cz = m.c_z, ch = m.c_hidden, R = N * N;
+  const int e = eb();
+  const bool incoming = kind == AC_REGION_TRIMUL_IN;
+  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
+  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  const uint64_t mk0 = arena.mark();
+  void* a_t = arena.push((uint64_t)ch * R * e);   // [c][i][k]
+  void* b_t = arena.push((uint64_t)ch * R * e);   // [c][j][k]
+  const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
+  // ---- whole operands: a and b of every position, channel-major.  Row r = (i, k) of z lands
+  // at [c][r]; for the incoming form r = (k, i), and the per-channel matrices are transposed
+  // in place afterwards.
+  for (const RowSeg& sg : segs) {
+    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const uint64_t mk = arena.mark();
+    void* t = arena.push((uint64_t)rows * cz * e);
+    void* gate = arena.push((uint64_t)rows * ch * e);
+    ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
+    for (int which = 0; which < 2; ++which) {
+      LinearArgs g{};
+      g.a = t; g.lda = cz; g.w = W[which ? TM_W_BG : TM_W_AG]; g.ldw = cz; g.bias = W[which ? TM_B_BG : TM_B_AG];
+      g.act = AC_ACT_SIGMOID; g.out = gate; g.ldo = ch; g.m = rows; g.n = ch; g.k = cz; g.n_split = ch;
+      linear(g);
+      LinearArgs v{};
+      v.a = t; v.lda = cz; v.w = W[which ? TM_W_BP : TM_W_AP]; v.ldw = cz; v.bias = W[which ? TM_B_BP : TM_B_AP];
+      v.mul = gate; v.ldmul = ch; v.m = rows; v.n = ch; v.k = cz;
+      v.out_t = atw(which ? b_t : a_t, r0); v.n_split = 0; v.t_period = 0; v.t_s2 = 1; v.t_s3 = R;
+      linear(v);
+    }
+    arena.release(mk);
+  }
+  if (incoming) {
+    transpose_inplace(a_t, N, R, N, ch);
+    transpose_inplace(b_t, N, R, N, ch);
+  }
+  // ---- chunked part: rows i of the output
+  for (const RowSeg& sg : segs) {
+    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const uint64_t mk = arena.mark();
+    void* t = arena.push((uint64_t)rows * cz * e);
+    void* gate = arena.push((uint64_t)rows * cz * e);
+    void* o_c = arena.push((uint64_t)ch * rows * e);   // [c][i][j]
+    void* lo = arena.push((uint64_t)rows * ch * e);
+    ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
+    LinearArgs g{};
+    g.a = t; g.lda = cz; g.w = W[TM_W_G]; g.ldw = cz; g.bias = W[TM_B_G]; g.act = AC_ACT_SIGMOID;
+    g.out = gate; g.ldo = cz; g.m = rows; g.n = cz; g.k = cz; g.n_split = cz;
+    linear(g);
+    contract(at(a_t, sg.i0 * N), N, R, b_t, N, R, o_c, N, rows, sg.ni, N, N, ch);
+    ln_channel_major(o_c, rows, W[TM_LN_OUT_G], W[TM_LN_OUT_B], lo, ch, rows, ch);
+    LinearArgs o{};
+    o.a = lo; o.lda = ch; o.w = W[TM_W_O]; o.ldw = ch; o.bias = W[TM_B_O]; o.mul = gate; o.ldmul = cz;
+    o.resid = at(zin, r0 * cz); o.ldr = cz; o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = ch;
+    o.n_split = cz;
+    linear(o);
+    arena.release(mk);
+  }
+  arena.release(mk0);
+}
+
+void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) {
+  const ac_model_desc& m = p->m;
+  const int64_t N = m.n_res, cz = m.c_z, H = m.tri_heads, dh = m.tri_head_dim, hd = H * dh, R = N * N;
+  const int e = eb();
+  const bool ending = kind == AC_REGION_TRIATT_END;
+  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
+  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  const uint64_t mk0 = arena.mark();
+  const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
+  // ---- whole operands.  Starting node: the pair bias [h][j][k].  Ending node: the bias as
+  // [h][i][k] (= projection at position (k, i)), all keys [(k, j)][h*d] and all values
+  // channel-major [h*d][j][k]; the transposes are done in place per channel.
+  void* bias = arena.push((uint64_t)H * R * e);
+  void* k_all = ending ? arena.push((uint64_t)R * hd * e) : nullptr;
+  void* v_all = ending ? arena.push((uint64_t)hd * R * e) : nullptr;
+  for (const RowSeg& sg : segs) {
+    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const uint64_t mk = arena.mark();
+    void* t = arena.push((uint64_t)rows * cz * e);
+    ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
+    LinearArgs b{};
+    b.a = t; b.lda = cz; b.w = W[TA_W_BIAS]; b.ldw = cz; b.m = rows; b.n = H; b.k = cz;
+    b.out_t = atw(bias, r0); b.n_split = 0; b.t_s2 = 1; b.t_s3 = R;
+    linear(b);
+    if (ending) {
+      LinearArgs kk{};
+      kk.a = t; kk.lda = cz; kk.w = W[TA_W_K]; kk.ldw = cz; kk.m = rows; kk.n = hd; kk.k = cz;
+      kk.out = atw(k_all, r0 * hd); kk.ldo = hd; kk.n_split = hd;
+      linear(kk);
+      LinearArgs vv{};
+      vv.a = t; vv.lda = cz; vv.w = W[TA_W_V]; vv.ldw = cz; vv.m = rows; vv.n = hd; vv.k = cz;
+      vv.out_t = atw(v_all, r0); vv.n_split = 0; vv.t_s2 = 1; vv.t_s3 = R;
+      linear(vv);
+    }
+    arena.release(mk);
+  }
+  if (ending) {
+    transpose_inplace(bias, N, R, N, H);
+    transpose_inplace(v_all, N, R, N, hd);
+  }
+  // ---- chunked part
+  for (const RowSeg& sg : segs) {
+    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const uint64_t mk = arena.mark();
+    void* t = arena.push((uint64_t)rows * cz * e);
+    void* q = arena.push((uint64_t)rows * hd * e);
+    void* gate = arena.push((uint64_t)rows * hd * e);
+    void* ctx = arena.push((uint64_t)rows * hd * e);
+    void* k_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);
+    void* v_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);   // [i][h*d][k]
+    ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
+    LinearArgs lq{};
+    lq.a = t; lq.lda = cz; lq.w = W[TA_W_Q]; lq.ldw = cz; lq.m = rows; lq.n = hd; lq.k = cz;
+    lq.out = q; lq.ldo = hd; lq.n_split = hd;
+    linear(lq);
+    LinearArgs lg = lq;
+    lg.w = W[TA_W_G]; lg.bias = W[TA_B_G]; lg.act = AC_ACT_SIGMOID; lg.out = gate;
+    linear(lg);
+    AttnArgs a{};
+    a.heads = (int)H; a.head_dim = (int)dh; a.causal = 0; a.q_offset = 0; a.v_transposed = 1; a.sk = N;
+    a.q = q; a.gate = gate; a.ctx = ctx;
+    if (!ending) {
+      LinearArgs lk = lq;
+      lk.w = W[TA_W_K]; lk.out = k_seg;
+      linear(lk);
+      LinearArgs lv{};
+      lv.a = t; lv.lda = cz; lv.w = W[TA_W_V]; lv.ldw = cz; lv.m = rows; lv.n = hd; lv.k = cz;
+      lv.out_t = v_seg; lv.n_split = 0; lv.t_period = N; lv.t_s1 = hd * N; lv.t_s2 = 1; lv.t_s3 = N;
+      linear(lv);
+      // one problem per row i: queries j, keys k of the same row
+      a.batch = sg.ni; a.sq = N;
+      a.ldq = hd; a.sq_b = N * hd; a.ldg = hd; a.sg_b = N * hd; a.ldc = hd; a.sc_b = N * hd;
+      a.k = k_seg; a.ldk = hd; a.sk_b = N * hd;
+      a.v = v_seg; a.ldv = N; a.sv_b = hd * N;
+      a.bias = bias; a.ld_bias = N; a.s_bias_h = R;
+    } else {
+      // one problem per column j: queries i of the segment, keys k of that column
+      a.batch = N; a.sq = sg.ni;
+      a.ldq = N * hd; a.sq_b = hd; a.ldg = N * hd; a.sg_b = hd; a.ldc = N * hd; a.sc_b = hd;
+      a.k = k_all; a.ldk = N * hd; a.sk_b = hd;
+      a.v = v_all; a.ldv = R; a.sv_b = N;
+      a.bias = at(bias, sg.i0 * N); a.ld_bias = N; a.s_bias_h = R;
+    }
+    attention(a);
+    LinearArgs o{};
+    o.a = ctx; o.lda = hd; o.w = W[TA_W_O]; o.ldw = hd; o.bias = W[TA_B_O]; o.resid = at(zin, r0 * cz); o.ldr = cz;
+    o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = hd; o.n_split = cz;
+    linear(o);
+    arena.release(mk);
+  }
+  arena.release(mk0);
+}
+
+void Walk::transition(const void* const* W, const void* zin, void* zout) {
+  const ac_model_desc& m = p->m;
+  const int64_t N = m.n_res, cz = m.c_z, F = (int64_t)m.transition_factor * cz;
+  const int e = eb();
+  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
+  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  for (const RowSeg& sg : row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION))) {
+    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const uint64_t mk = arena.mark();
+    void* u = arena.push((uint64_t)rows * cz * e);
+    void* hid = arena.push((uint64_t)rows * F * e);
+    ln(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
+    proj(u, cz, W[PT_W_1], cz, W[PT_B_1], m.activation, nullptr, 0, hid, F, rows, F);
+    proj(hid, F, W[PT_W_2], F, W[PT_B_2], AC_ACT_NONE, at(zin, r0 * cz), cz, atw(zout, r0 * cz), cz, rows, cz);
+    arena.release(mk);
+  }
+}
+
+void Walk::pair(const void* x, void* y) {
+  const ac_model_desc& m = p->m;
+  const uint64_t zbytes = (uint64_t)m.n_res * m.n_res * m.c_z * eb();
+  const int modules = m.layers * 5;
+  void* tbuf[2] = {nullptr, nullptr};
+  if (modules > 1) tbuf[0] = arena.push(zbytes);
+  if (modules > 2) tbuf[1] = arena.push(zbytes);
+  std::vector<const void*> nullw(kPairWeights, nullptr);
+  for (int g = 0; g < modules && ok(); ++g) {
+    const void* zin = g == 0 ? x : (const void*)tbuf[(g - 1) % 2];
+    void* zout = g == modules - 1 ? y : tbuf[g % 2];
+    const void* const* base = dry ? nullw.data() : p->wptr.data() + (size_t)(g / 5) * kPairWeights;
+    switch (g % 5) {
+      case 0: tri_mul(AC_REGION_TRIMUL_OUT, base, zin, zout); break;
+      case 1: tri_mul(AC_REGION_TRIMUL_IN, base + TM_COUNT, zin, zout); break;
+      case 2: tri_att(AC_REGION_TRIATT_START, base + 2 * TM_COUNT, zin, zout); break;
+      case 3: tri_att(AC_REGION_TRIATT_END, base + 2 * TM_COUNT + TA_COUNT, zin, zout); break;
+      default: transition(base + 2 * TM_COUNT + 2 * TA_COUNT, zin, zout); break;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Paper-style byte counts of the regions (section 2: M = X + Y + A, chunked M = X + Y + A/n
 // with every op output a tensor of its own), used to size chunk lengths from a budget.
 // ---------------------------------------------------------------------------------------
@@ -369,6 +614,7 @@ static bool dim_legal(const ac_model_desc& m, int dim, bool& known) {
 static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& flops) {
   Walk wk{p, true, unchunked, nullptr};
   if (p->m.workload == AC_TRANSFORMER_STACK) wk.transformer(nullptr, nullptr);
+  else wk.pair(nullptr, nullptr);
   arena_bytes = wk.arena.high;
   flops = wk.flops;
 }
@@ -424,7 +670,19 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     if (m.dtype == AC_BF16 && (m.seq % 8 != 0 || m.d_model % 8 != 0 || m.d_ffn % 8 != 0))
       return fail(AC_ERR_UNSUPPORTED, "bf16 needs seq, d_model and d_ffn to be multiples of 8");
   } else if (m.workload == AC_PAIR_STACK) {
-    return fail(AC_ERR_UNSUPPORTED, "pair stack is not built yet");
+    if (m.n_res < 1 || m.c_z < 1 || m.c_hidden < 1 || m.tri_heads < 1 || m.tri_head_dim < 1 || m.transition_factor < 1)
+      return fail(AC_ERR_ARG, "pair-stack sizes must be positive");
+    if (m.activation != AC_ACT_GELU_ERF && m.activation != AC_ACT_GELU_TANH && m.activation != AC_ACT_RELU)
+      return fail(AC_ERR_ARG, "activation %d not valid for the pair transition", m.activation);
+    const int hd = m.tri_head_dim;
+    if (hd != 8 && hd != 16 && hd != 32 && hd != 64 && hd != 128)
+      return fail(AC_ERR_UNSUPPORTED, "tri_head_dim %d has no attention kernel (8, 16, 32, 64, 128)", hd);
+    if (m.n_res % 8 != 0 || m.c_z % 8 != 0 || m.c_hidden % 8 != 0)
+      return fail(AC_ERR_UNSUPPORTED, "n_res, c_z and c_hidden must be multiples of 8");
+    if ((int64_t)64 * (m.c_hidden + 1) * 4 > 64 * 1024)
+      return fail(AC_ERR_UNSUPPORTED, "c_hidden %d too wide for the channel-major LayerNorm tile", m.c_hidden);
+    if (m.c_hidden > 65535 || (int64_t)m.tri_heads * m.tri_head_dim > 65535)
+      return fail(AC_ERR_UNSUPPORTED, "too many channels for one launch");
   } else {
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
@@ -475,7 +733,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
 
   // ---- size the regions left open from the budget: largest length (the extent itself, or
   // a multiple of the row granule below it) whose paper-style region bytes fit.
-  const int64_t granule = m.dtype == AC_BF16 ? 128 : 64;
+  const int64_t granule = m.workload == AC_PAIR_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
   auto rows_of = [&](const Setting& s, int64_t len) { return model_rows(m, s, len); };
   if (act_budget_bytes > 0) {
     for (int k = first; k < first + count; ++k) {
@@ -516,6 +774,35 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
         snprintf(nm, sizeof(nm), "L%d.%s", l, kLayerTensor[t]);
         p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
       }
+  }
+  if (m.workload == AC_PAIR_STACK) {
+    const int64_t cz = m.c_z, ch = m.c_hidden, hd = (int64_t)m.tri_heads * m.tri_head_dim, H = m.tri_heads;
+    const int64_t ft = (int64_t)m.transition_factor * cz;
+    const int64_t tm[TM_COUNT][2] = {{1, cz}, {1, cz}, {ch, cz}, {1, ch}, {ch, cz}, {1, ch}, {ch, cz}, {1, ch},
+                                     {ch, cz}, {1, ch}, {cz, cz}, {1, cz}, {1, ch}, {1, ch}, {cz, ch}, {1, cz}};
+    const int64_t ta[TA_COUNT][2] = {{1, cz}, {1, cz}, {hd, cz}, {hd, cz}, {hd, cz}, {H, cz}, {hd, cz}, {1, hd},
+                                     {cz, hd}, {1, cz}};
+    const int64_t pt[PT_COUNT][2] = {{1, cz}, {1, cz}, {ft, cz}, {1, ft}, {cz, ft}, {1, cz}};
+    for (int l = 0; l < m.layers; ++l) {
+      char nm[48];
+      const char* pre = "";
+      char lbuf[16] = "";
+      if (m.layers > 1) { snprintf(lbuf, sizeof(lbuf), "B%d.", l); pre = lbuf; }
+      for (int mod = 0; mod < 2; ++mod)
+        for (int t = 0; t < TM_COUNT; ++t) {
+          snprintf(nm, sizeof(nm), "%s%s.%s", pre, mod ? "tmi" : "tmo", kTmName[t]);
+          p->weights.push_back(WeightSlot{nm, tm[t][0], tm[t][1]});
+        }
+      for (int mod = 0; mod < 2; ++mod)
+        for (int t = 0; t < TA_COUNT; ++t) {
+          snprintf(nm, sizeof(nm), "%s%s.%s", pre, mod ? "tae" : "tas", kTaName[t]);
+          p->weights.push_back(WeightSlot{nm, ta[t][0], ta[t][1]});
+        }
+      for (int t = 0; t < PT_COUNT; ++t) {
+        snprintf(nm, sizeof(nm), "%spt.%s", pre, kPtName[t]);
+        p->weights.push_back(WeightSlot{nm, pt[t][0], pt[t][1]});
+      }
+    }
   }
   p->wptr.assign(p->weights.size(), nullptr);
 
@@ -617,6 +904,7 @@ int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_de
   Walk wk{plan, false, false, (hipStream_t)stream};
   wk.arena.base = (uint8_t*)workspace_dev;
   if (plan->m.workload == AC_TRANSFORMER_STACK) wk.transformer(x_dev, y_dev);
+  else wk.pair(x_dev, y_dev);
   if (measured_peak_bytes) *measured_peak_bytes = plan->info.io_bytes + wk.arena.high;
   if (!wk.ok()) return fail(AC_ERR_HIP, "%s: %s", wk.err_where, hipGetErrorString(wk.err));
   return AC_OK;
@@ -739,11 +1027,36 @@ int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_
   return hip_status(launch_transpose(src, lds, dst, ldd, rows, cols, dtype, (hipStream_t)stream), "transpose");
 }
 
-int ac_op_triangle_contract(const void* a, int64_t sa_i, int64_t sa_k, const void* b, int64_t sb_j, int64_t sb_k,
-                            void* out, int64_t ni, int64_t nj, int64_t nk, int channels, int dtype, void* stream) {
-  (void)a; (void)sa_i; (void)sa_k; (void)b; (void)sb_j; (void)sb_k; (void)out; (void)ni; (void)nj; (void)nk;
-  (void)channels; (void)dtype; (void)stream;
-  return fail(AC_ERR_UNSUPPORTED, "triangle contraction is not built yet");
+int ac_op_triangle_contract(const void* a_t, int64_t lda, int64_t stride_a_c, const void* b_t, int64_t ldb,
+                            int64_t stride_b_c, void* out_c, int64_t ldo, int64_t stride_o_c, int64_t ni,
+                            int64_t nj, int64_t nk, int channels, int dtype, void* stream) {
+  if (!a_t || !b_t || !out_c || ni < 0 || nj < 0 || nk < 1 || channels < 1 || lda < nk || ldb < nk || ldo < nj ||
+      !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_triangle_contract: bad argument");
+  LinearArgs g{};
+  g.a = a_t; g.lda = lda; g.sa_b = stride_a_c; g.w = b_t; g.ldw = ldb; g.sw_b = stride_b_c; g.out = out_c;
+  g.ldo = ldo; g.so_b = stride_o_c; g.m = ni; g.n = nj; g.k = nk; g.n_split = nj; g.batch = channels;
+  g.dtype = dtype;
+  return hip_status(launch_linear(g, (hipStream_t)stream), "triangle_contract");
+}
+
+int ac_op_transpose_square_inplace(void* data, int64_t ld, int64_t stride_batch, int64_t n, int64_t batch, int dtype,
+                                   void* stream) {
+  if (!data || n < 0 || batch < 0 || ld < n || !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_transpose_square_inplace: bad argument");
+  return hip_status(launch_transpose_square_inplace(data, ld, stride_batch, n, batch, dtype, (hipStream_t)stream),
+                    "transpose_square_inplace");
+}
+
+int ac_op_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain, const void* shift, void* dst,
+                                  int64_t ldd, int64_t positions, int64_t channels, float eps, int dtype,
+                                  void* stream) {
+  if (!src || !gain || !shift || !dst || positions < 0 || channels < 1 || stride_c < positions || ldd < channels ||
+      !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_layernorm_channel_major: bad argument");
+  return hip_status(launch_layernorm_channel_major(src, stride_c, gain, shift, dst, ldd, positions, channels, eps,
+                                                   dtype, (hipStream_t)stream),
+                    "layernorm_channel_major");
 }
 
 }  // extern "C"

@@ -1,0 +1,115 @@
+"""GPU parity of the pair-stack kernels and chunk plans against the fp64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import pairstack as P
+from oracle import transformer as O
+from paper_2401_10652_amd import inputs as I
+from util import TOL, draw, host, rel_err
+
+pytestmark = pytest.mark.gpu
+CANARY = 0x5A
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2401_10652_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("dtype,ch,ni,nj,nk", [("bf16", 5, 40, 200, 192), ("bf16", 3, 64, 128, 64),
+                                               ("bf16", 4, 33, 50, 40), ("f32", 3, 20, 30, 25)])
+def test_triangle_contract(B, dtype, ch, ni, nj, nk):
+    import torch
+    a = draw((ch, ni, nk), 50, dtype)
+    b = draw((ch, nj, nk), 51, dtype)
+    out = torch.full((ch, ni, nj), float("nan"), device="cuda",
+                     dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    B.ac_op_triangle_contract(B.to_device(a, dtype), B.to_device(b, dtype), out)
+    torch.cuda.synchronize()
+    ref = np.einsum("cik,cjk->cij", a.astype(np.float64), b.astype(np.float64))
+    assert rel_err(host(out), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,batch", [(64, 3), (200, 2), (72, 5), (8, 1)])
+def test_transpose_square_inplace(B, dtype, n, batch):
+    import torch
+    a = draw((batch, n, n), 52, dtype)
+    d = B.to_device(a, dtype)
+    B.ac_op_transpose_square_inplace(d)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d), a.transpose(0, 2, 1).astype(np.float64))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("ch,pos", [(128, 1000), (16, 64), (40, 130)])
+def test_layernorm_channel_major(B, dtype, ch, pos):
+    import torch
+    from paper_2401_10652_amd.inputs import round_to_storage
+    x = round_to_storage(draw((ch, pos), 53, "f32", 2.0) + 0.5, dtype)
+    g = round_to_storage(draw((ch,), 54, "f32", 0.3) + 1, dtype)
+    b = draw((ch,), 55, dtype, 0.3)
+    dst = torch.full((pos, ch), float("nan"), device="cuda",
+                     dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    B.ac_op_layernorm_channel_major(B.to_device(x, dtype), B.to_device(g, dtype), B.to_device(b, dtype), dst)
+    torch.cuda.synchronize()
+    assert rel_err(host(dst), O.layer_norm(x.T, g, b)) <= TOL[dtype]
+
+
+def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1):
+    import torch
+    z, w = I.pair_inputs(cfg, bias_std=bias_std, ln_jitter=ln_jitter)
+    names = [n for n, _ in I.pair_tensor_shapes(cfg)]
+    dz = B.to_device(z, cfg.dtype)
+    dw = [B.to_device(w[n], cfg.dtype) for n in names]
+    regs = [(k, B.AC_DIM_ROW, c) for k, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), chunk)]
+    p = B.Plan(B.pair_desc(cfg), regs)
+    info = p.ac_plan_query()
+    assert p.weight_names() == names
+    p.ac_plan_bind_weights(dw)
+    need = int(info.workspace_bytes)
+    ws = torch.full((need + 4096,), CANARY, dtype=torch.uint8, device="cuda")
+    y = torch.full_like(dz, float("nan"))
+    peak = p.ac_execute(dz, y, ws[:need])
+    torch.cuda.synchronize()
+    assert bool((ws[need:] == CANARY).all())
+    assert torch.equal(dz, B.to_device(z, cfg.dtype))
+    assert peak == info.peak_bytes_planned
+    p.close()
+    return z, w, y, info
+
+
+@pytest.mark.parametrize("dtype,n,cz,ch,heads,dh", [("f32", 40, 32, 16, 2, 16), ("bf16", 40, 32, 16, 2, 16),
+                                                    ("bf16", 192, 64, 64, 2, 32)])
+def test_pair_block_chunked_equals_oracle(B, dtype, n, cz, ch, heads, dh):
+    import torch
+    cfg = I.PairConfig("tp", 41, n, cz, ch, heads, dh, 4, dtype)
+    outs = []
+    ref = None
+    for chunk in ((n,) * 5, (16,) * 5, (24, 8, n, 40, 3)):
+        z, w, y, info = run_pair(B, cfg, chunk)
+        if ref is None:
+            ref = P.pair_block(z, w, heads, cfg.activation, cfg.ln_eps)
+        assert np.isfinite(host(y)).all()
+        assert rel_err(host(y), ref) <= TOL[dtype], chunk
+        outs.append(y)
+    for y in outs[1:]:
+        assert torch.equal(y, outs[0])
+    assert info.n_regions == 5 and info.n_weights == 58
+
+
+def test_pair_legality(B):
+    d = B.pair_desc(I.C4)
+    for kind in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS):
+        for dim in (B.AC_DIM_CHANNEL, B.AC_DIM_CONTRACT):
+            with pytest.raises(B.AcError) as ei:
+                B.Plan(d, [(kind, dim, 64)])
+            assert ei.value.status == B.AC_ERR_ILLEGAL_CHUNK_DIM
+        with pytest.raises(B.AcError) as ei:
+            B.Plan(d, [(kind, B.AC_DIM_COL, 64)])
+        assert ei.value.status == B.AC_ERR_UNSUPPORTED
+    with pytest.raises(B.AcError) as ei:
+        B.Plan(d, [(B.AC_REGION_FFN, 0, 64)])
+    assert ei.value.status == B.AC_ERR_ARG
