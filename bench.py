@@ -28,6 +28,10 @@ def plan_regions(B, c_qkv, c_attn, c_ffn):
             (B.AC_REGION_FFN, B.AC_DIM_SEQ, c_ffn)]
 
 
+def pair_regions(B, c):
+    return [(k, B.AC_DIM_ROW, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)]
+
+
 def time_plan(B, torch, plan, dx, y, ws, steps, warmup):
     for _ in range(warmup):
         plan.ac_execute(dx, y, ws)
@@ -47,6 +51,26 @@ def profile_plan(plan, dx, y, ws, steps):
     stats = plan.ac_plan_read_profile()
     plan.ac_plan_set_profiling(False)
     return stats
+
+
+def cpu_baseline_pair(cfg, z, w):
+    """The oracle as it stands on a bounded sample: 8 output rows of each of the five modules."""
+    import numpy as np
+    from oracle import pairstack as P
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    rows = np.arange(0, cfg.n_res, cfg.n_res // 8)[:8]
+    t0 = time.perf_counter()
+    for name in P.PAIR_MODULES:
+        P.pair_module(name, z, w, cfg.heads, cfg.activation, cfg.ln_eps, rows=rows)
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) * cfg.n_res / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(rows)} of {cfg.n_res} output rows of each of the 5 modules in fp64 ({dt:.1f} s); the "
+                      "whole-tensor projections every row needs are part of the sample, so this overstates "
+                      "the per-row cost of a full run"}
 
 
 def cpu_baseline(cfg, x, layers):
@@ -71,7 +95,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--chunk", type=int, nargs=3, default=None, metavar=("QKV", "ATTN", "FFN"),
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -89,22 +113,30 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     cfg = I.CONFIGS[args.config]
-    x, layers = I.transformer_inputs(cfg)
-    dx = B.to_device(x, cfg.dtype)
-    dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
-    y = torch.empty_like(dx)
-
-    if args.chunk:
-        regs, budget = plan_regions(B, *args.chunk), 0
-    elif cfg.chunk_len:
-        regs, budget = plan_regions(B, cfg.chunk_len, cfg.chunk_len, cfg.chunk_len), 0
+    is_pair = isinstance(cfg, I.PairConfig)
+    if is_pair:
+        x, layers = I.pair_inputs(cfg)
+        dw = [B.to_device(layers[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
+        desc = B.pair_desc(cfg)
+        regs, budget = pair_regions(B, args.chunk[0] if args.chunk else cfg.chunk_len), 0
+        regs1 = pair_regions(B, cfg.n_res)
     else:
-        regs, budget = plan_regions(B, 0, 0, 0), cfg.act_budget
-    desc = B.transformer_desc(cfg)
+        x, layers = I.transformer_inputs(cfg)
+        dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
+        desc = B.transformer_desc(cfg)
+        if args.chunk:
+            regs, budget = plan_regions(B, *args.chunk), 0
+        elif cfg.chunk_len:
+            regs, budget = plan_regions(B, cfg.chunk_len, cfg.chunk_len, cfg.chunk_len), 0
+        else:
+            regs, budget = plan_regions(B, 0, 0, 0), cfg.act_budget
+        regs1 = plan_regions(B, cfg.seq, cfg.seq, cfg.seq)
+    dx = B.to_device(x, cfg.dtype)
+    y = torch.empty_like(dx)
     plan = B.Plan(desc, regs, budget)
     info = plan.ac_plan_query()
     plan.ac_plan_bind_weights(dw)
-    plan1 = B.Plan(desc, plan_regions(B, cfg.seq, cfg.seq, cfg.seq), 0)
+    plan1 = B.Plan(desc, regs1, 0)
     info1 = plan1.ac_plan_query()
     plan1.ac_plan_bind_weights(dw)
     ws = B.empty_workspace(max(info.workspace_bytes, info1.workspace_bytes))
@@ -138,15 +170,14 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {
-            "workload": cfg.name, "layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model,
-            "heads": cfg.heads, "d_ffn": cfg.d_ffn, "causal": cfg.causal,
-            "act_budget_bytes": budget,
-            "chunk_len": {"qkv": info.regions[0].chunk_len, "attention": info.regions[1].chunk_len,
-                          "ffn": info.regions[2].chunk_len},
-            "n_segments": {"qkv": info.regions[0].n_segments, "attention": info.regions[1].n_segments,
-                           "ffn": info.regions[2].n_segments},
-        },
+        "config": dict(
+            {"workload": cfg.name, "act_budget_bytes": budget,
+             "chunk_len": [info.regions[i].chunk_len for i in range(info.n_regions)],
+             "n_segments": [info.regions[i].n_segments for i in range(info.n_regions)]},
+            **({"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
+                "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
+               {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,
+                "d_ffn": cfg.d_ffn, "causal": cfg.causal})),
         "roofline": roof,
         "kernels": classes,
         "mfma_frac_whole_step": round(info.flops_per_execute / sec / PEAK["mfma_bf16"], 4),
@@ -162,9 +193,9 @@ def main():
     }
     if args.sweep:
         sweep = []
-        c = cfg.seq
-        while c >= 128:
-            ps = B.Plan(desc, plan_regions(B, c, c, c), 0)
+        c = cfg.n_res if is_pair else cfg.seq
+        while c >= (8 if is_pair else 128):
+            ps = B.Plan(desc, pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
             ps.ac_plan_bind_weights(dw)
             inf = ps.ac_plan_query()
             s_, pk_ = time_plan(B, torch, ps, dx, y, ws, max(3, args.steps // 2), 1)
@@ -174,7 +205,7 @@ def main():
             c //= 2
         out["sweep"] = sweep
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, x, layers)
+        out["cpu_baseline"] = cpu_baseline_pair(cfg, x, layers) if is_pair else cpu_baseline(cfg, x, layers)
     print(json.dumps(out))
 
 

@@ -79,8 +79,11 @@ enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 }
 
 /* ac_model_desc.flags */
 enum {
-  AC_FLAG_UNFUSED_ELEMENTWISE = 1  /* run bias+activation and residual as standalone passes
+  AC_FLAG_UNFUSED_ELEMENTWISE = 1, /* run bias+activation and residual as standalone passes
                                       instead of GEMM epilogues (for measuring those passes) */
+  AC_FLAG_LISTED_REGIONS_ONLY = 2  /* pair stack only: the block consists of just the region kinds
+                                      listed in ac_plan_create (each maps z to z), in canonical
+                                      order; weights of the others are still bound but unused */
 };
 
 typedef struct ac_model_desc {

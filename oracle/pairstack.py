@@ -51,10 +51,13 @@ def tri_mul(z, w, p, outgoing, eps=1e-5, rows=None):
     b = sigmoid(linear(t, w[p + "w_bg"], w[p + "b_bg"])) * linear(t, w[p + "w_bp"], w[p + "b_bp"])
     if outgoing:
         # o[i,j,c] = sum_k a[i,k,c] b[j,k,c]: one [rows,N]x[N,N] matmul per channel c
-        o = np.matmul(a[rows].transpose(2, 0, 1), b.transpose(2, 1, 0)).transpose(1, 2, 0)
+        ac = np.ascontiguousarray(a[rows].transpose(2, 0, 1))          # [c, i, k]
+        bc = np.ascontiguousarray(b.transpose(2, 0, 1))                # [c, j, k]
     else:
         # o[i,j,c] = sum_k a[k,i,c] b[k,j,c]
-        o = np.matmul(a[:, rows].transpose(2, 1, 0), b.transpose(2, 0, 1)).transpose(1, 2, 0)
+        ac = np.ascontiguousarray(a[:, rows].transpose(2, 1, 0))       # [c, i, k]
+        bc = np.ascontiguousarray(b.transpose(2, 1, 0))                # [c, j, k]
+    o = np.matmul(ac, bc.transpose(0, 2, 1)).transpose(1, 2, 0)
     g = sigmoid(linear(t[rows], w[p + "w_g"], w[p + "b_g"]))
     upd = g * linear(layer_norm(o, w[p + "ln_out_g"], w[p + "ln_out_b"], eps), w[p + "w_o"], w[p + "b_o"])
     return z[rows] + upd
@@ -75,6 +78,10 @@ def tri_att(z, w, p, heads, starting, eps=1e-5, rows=None):
     g = sigmoid(linear(t, w[p + "w_g"], w[p + "b_g"])).reshape(n, n, heads, dh)
     scale = 1.0 / math.sqrt(dh)
     out = np.empty((len(rows), n, cz), np.float64)
+    if not starting:
+        # the ending form reads keys and values down column j: hold them as [j, h, k, d]
+        kj = np.ascontiguousarray(k.transpose(1, 2, 0, 3))
+        vj = np.ascontiguousarray(v.transpose(1, 2, 0, 3))
     for r, i in enumerate(rows):
         o = np.empty((n, heads, dh), np.float64)
         for h in range(heads):
@@ -83,10 +90,8 @@ def tri_att(z, w, p, heads, starting, eps=1e-5, rows=None):
                 o[:, h, :] = softmax_rows(s) @ v[i, :, h, :]
             else:
                 # s[j, k] = q[i,j,h] . k[k,j,h] / sqrt(d_h) + bias[k,i,h]
-                kj = k[:, :, h, :].transpose(1, 0, 2)                               # [j, k, d]
-                vj = v[:, :, h, :].transpose(1, 0, 2)
-                s = np.matmul(kj, q[i, :, h, :, None])[:, :, 0] * scale + bias[:, i, h][None, :]
-                o[:, h, :] = np.matmul(softmax_rows(s)[:, None, :], vj)[:, 0, :]
+                s = np.matmul(kj[:, h], q[i, :, h, :, None])[:, :, 0] * scale + bias[:, i, h][None, :]
+                o[:, h, :] = np.matmul(softmax_rows(s)[:, None, :], vj[:, h])[:, 0, :]
         o = (g[i] * o).reshape(n, hd)
         out[r] = z[i] + linear(o, w[p + "w_o"], w[p + "b_o"])
     return out

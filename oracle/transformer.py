@@ -131,6 +131,26 @@ def transformer_block(x, w, heads, causal, activation="gelu_erf", eps=1e-5, batc
     return ffn_region(h, w, activation, eps)
 
 
+def transformer_block_rows(x, w, heads, causal, r0, r1, activation="gelu_erf", eps=1e-5):
+    """Rows [r0, r1) of transformer_block(x) for one sequence, without forming the other rows.
+
+    Keys and values come from every row of x (they are what every query sees); queries,
+    output projection, residuals and feed-forward are evaluated for the requested rows only.
+    Lets a test check a few rows of a sequence too long to evaluate whole.
+    """
+    x = np.asarray(x, np.float64)
+    d = x.shape[1]
+    u = layer_norm(x, w["ln1_g"], w["ln1_b"], eps)
+    wq = np.asarray(w["w_qkv"], np.float64)
+    bq = np.asarray(w["b_qkv"], np.float64)
+    k = linear(u, wq[d:2 * d], bq[d:2 * d])
+    v = linear(u, wq[2 * d:], bq[2 * d:])
+    q = linear(u[r0:r1], wq[:d], bq[:d])
+    ctx = attention(q, k, v, heads, causal, q_offset=r0)
+    h = x[r0:r1] + linear(ctx, w["w_o"], w["b_o"])
+    return ffn_region(h, w, activation, eps)
+
+
 def transformer_stack(x, layers, heads, causal, activation="gelu_erf", eps=1e-5, batch=1,
                       query_block=None):
     y = np.asarray(x, np.float64)

@@ -535,14 +535,20 @@ void Walk::transition(const void* const* W, const void* zin, void* zout) {
 void Walk::pair(const void* x, void* y) {
   const ac_model_desc& m = p->m;
   const uint64_t zbytes = (uint64_t)m.n_res * m.n_res * m.c_z * eb();
-  const int modules = m.layers * 5;
+  // the modules that run: all five per block, or only the listed kinds
+  std::vector<int> seq;
+  for (int l = 0; l < m.layers; ++l)
+    for (int k = 0; k < 5; ++k)
+      if (!(m.flags & AC_FLAG_LISTED_REGIONS_ONLY) || p->set[AC_REGION_TRIMUL_OUT + k].present) seq.push_back(l * 5 + k);
+  const int modules = (int)seq.size();
   void* tbuf[2] = {nullptr, nullptr};
   if (modules > 1) tbuf[0] = arena.push(zbytes);
   if (modules > 2) tbuf[1] = arena.push(zbytes);
   std::vector<const void*> nullw(kPairWeights, nullptr);
-  for (int g = 0; g < modules && ok(); ++g) {
-    const void* zin = g == 0 ? x : (const void*)tbuf[(g - 1) % 2];
-    void* zout = g == modules - 1 ? y : tbuf[g % 2];
+  for (int idx = 0; idx < modules && ok(); ++idx) {
+    const int g = seq[idx];
+    const void* zin = idx == 0 ? x : (const void*)tbuf[(idx - 1) % 2];
+    void* zout = idx == modules - 1 ? y : tbuf[idx % 2];
     const void* const* base = dry ? nullw.data() : p->wptr.data() + (size_t)(g / 5) * kPairWeights;
     switch (g % 5) {
       case 0: tri_mul(AC_REGION_TRIMUL_OUT, base, zin, zout); break;
@@ -687,6 +693,10 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
 
+  if (m.flags & AC_FLAG_LISTED_REGIONS_ONLY) {
+    if (m.workload != AC_PAIR_STACK) return fail(AC_ERR_ARG, "AC_FLAG_LISTED_REGIONS_ONLY applies to the pair stack only");
+    if (n_regions < 1) return fail(AC_ERR_ARG, "AC_FLAG_LISTED_REGIONS_ONLY needs at least one region");
+  }
   ac_plan* p = new (std::nothrow) ac_plan();
   if (!p) return fail(AC_ERR_ARG, "out of host memory");
   p->m = m;

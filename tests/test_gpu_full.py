@@ -1,0 +1,149 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+C1-C3: the whole stack against the whole fp64 oracle.  C4: each pair-stack module at
+N_res = 1024 against oracle rows evaluated one by one, and the whole block chunked vs
+unchunked.  C5: one layer at S = 65536 against oracle row blocks, and the two-layer stack
+chunked two ways (properties that hold at any size: finite, identical for every chunk length).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import pairstack as P
+from oracle import transformer as O
+from paper_2401_10652_amd import inputs as I
+from util import TOL, host, rel_err
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2401_10652_amd import binding
+    binding.lib()
+    return binding
+
+
+def tregions(B, c):
+    return [(B.AC_REGION_QKV, B.AC_DIM_SEQ, c[0]), (B.AC_REGION_ATTENTION, B.AC_DIM_SEQ, c[1]),
+            (B.AC_REGION_FFN, B.AC_DIM_SEQ, c[2])]
+
+
+def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None):
+    import torch
+    dx = B.to_device(x, cfg.dtype)
+    if dw is None:
+        dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
+    p = B.Plan(B.transformer_desc(cfg), regs, budget)
+    info = p.ac_plan_query()
+    p.ac_plan_bind_weights(dw)
+    ws = B.empty_workspace(info.workspace_bytes)
+    y = torch.full_like(dx, float("nan"))
+    peak = p.ac_execute(dx, y, ws)
+    torch.cuda.synchronize()
+    assert peak == info.peak_bytes_planned
+    p.close()
+    return y, info, dw
+
+
+def test_c2_gpt_full_stack(B):
+    cfg = I.C2
+    x, layers = I.transformer_inputs(cfg)
+    y, info, dw = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0)), cfg.act_budget)
+    assert info.regions[1].chunk_len == 1792 and info.peak_bytes_model <= cfg.act_budget
+    ref = O.transformer_stack(x, layers, cfg.heads, True, query_block=1024)
+    err = rel_err(host(y), ref)
+    print("C2 rel err", err)
+    assert err <= TOL["bf16"]
+    import torch
+    y2, _, _ = run_transformer(B, cfg, x, layers, tregions(B, (1024, 1024, 1024)), dw=dw)
+    assert torch.equal(y, y2)
+
+
+def test_c3_vit_full_stack(B):
+    cfg = I.C3
+    x, layers = I.transformer_inputs(cfg)
+    y, info, _ = run_transformer(B, cfg, x, layers, tregions(B, (512, 512, 512)))
+    assert [r.n_segments for r in info.regions[:3]] == [8, 8, 8]
+    ref = O.transformer_stack(x, layers, cfg.heads, False, query_block=1024)
+    err = rel_err(host(y), ref)
+    print("C3 rel err", err)
+    assert err <= TOL["bf16"]
+
+
+def test_c5_long_context(B):
+    import torch
+    cfg1 = dataclasses.replace(I.C5, layers=1)
+    x, layers = I.transformer_inputs(cfg1)
+    y, info, dw = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0)), I.C5.act_budget)
+    assert info.regions[1].chunk_len == 640 and info.regions[1].n_segments == 103
+    got = host(y)
+    assert np.isfinite(got).all()
+    scale = np.abs(got).max()
+    # row blocks: the first rows, both sides of a segment boundary (640 * 51 = 32640), the last rows
+    for r0, r1 in ((0, 64), (32608, 32672), (65472, 65536)):
+        ref = O.transformer_block_rows(x, layers[0], cfg1.heads, True, r0, r1)
+        err = np.abs(got[r0:r1] - ref).max() / max(scale, np.abs(ref).max())
+        print("C5 rows", r0, r1, "rel err", err)
+        assert err <= TOL["bf16"]
+    del got
+    # two layers, budget plan vs another chunking: identical bits
+    cfg = I.C5
+    x2, layers2 = I.transformer_inputs(cfg)
+    ya, infa, dw2 = run_transformer(B, cfg, x2, layers2, tregions(B, (0, 0, 0)), cfg.act_budget)
+    yb, _, _ = run_transformer(B, cfg, x2, layers2, tregions(B, (8192, 2048, 4096)), dw=dw2)
+    assert bool(torch.isfinite(ya.float()).all())
+    assert torch.equal(ya, yb)
+    assert infa.peak_bytes_planned <= cfg.act_budget
+
+
+def run_pair(B, cfg, z, w, kinds, chunk, flags=0, dz=None, dw=None):
+    import torch
+    if dz is None:
+        dz = B.to_device(z, cfg.dtype)
+    if dw is None:
+        dw = [B.to_device(w[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
+    p = B.Plan(B.pair_desc(cfg, flags=flags), [(k, B.AC_DIM_ROW, chunk) for k in kinds])
+    info = p.ac_plan_query()
+    p.ac_plan_bind_weights(dw)
+    ws = B.empty_workspace(info.workspace_bytes)
+    y = torch.full_like(dz, float("nan"))
+    peak = p.ac_execute(dz, y, ws)
+    torch.cuda.synchronize()
+    assert peak == info.peak_bytes_planned
+    p.close()
+    return y, info, dz, dw
+
+
+def test_c4_pair_modules_full_size(B):
+    import torch
+    cfg = I.C4
+    z, w = I.pair_inputs(cfg)
+    rows = np.array([0, 63, 64, 517, 1023])
+    dz = dw = None
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+        y, info, dz, dw = run_pair(B, cfg, z, w, [k], cfg.chunk_len, flags=B.AC_FLAG_LISTED_REGIONS_ONLY,
+                                   dz=dz, dw=dw)
+        got = host(y[torch.as_tensor(rows, device="cuda")])
+        ref = P.pair_module(name, z, w, cfg.heads, cfg.activation, cfg.ln_eps, rows=rows)
+        err = rel_err(got, ref)
+        print("C4", name, "rel err", err)
+        assert err <= TOL["bf16"], name
+        assert bool(torch.isfinite(y.float()).all())
+    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
+    ya, infa, _, _ = run_pair(B, cfg, z, w, kinds, cfg.chunk_len, dz=dz, dw=dw)
+    yb, infb, _, _ = run_pair(B, cfg, z, w, kinds, cfg.n_res, dz=dz, dw=dw)
+    assert torch.equal(ya, yb) and bool(torch.isfinite(ya.float()).all())
+    assert infa.peak_bytes_planned < infb.peak_bytes_planned
+
+
+def test_c4_pair_block_half_size_against_whole_oracle(B):
+    cfg = dataclasses.replace(I.C4, n_res=256)
+    z, w = I.pair_inputs(cfg)
+    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
+    y, _, _, _ = run_pair(B, cfg, z, w, kinds, 64)
+    ref = P.pair_block(z, w, cfg.heads, cfg.activation, cfg.ln_eps)
+    err = rel_err(host(y), ref)
+    print("C4 block N=256 rel err", err)
+    assert err <= TOL["bf16"]

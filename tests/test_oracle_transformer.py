@@ -160,3 +160,12 @@ def test_illegal_chunk_dims_change_the_output():
     b = np.concatenate([O.layer_norm(x[:, :4], w["ln1_g"][:4], w["ln1_b"][:4]),
                         O.layer_norm(x[:, 4:], w["ln1_g"][4:], w["ln1_b"][4:])], axis=1)
     assert np.abs(a - b).max() > 1e-3
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_block_rows_equals_rows_of_block(causal):
+    cfg, x, ls = tiny(seq=12, causal=causal)
+    full = O.transformer_block(x, ls[0], cfg.heads, causal)
+    for r0, r1 in ((0, 3), (5, 9), (11, 12), (0, 12)):
+        got = O.transformer_block_rows(x, ls[0], cfg.heads, causal, r0, r1)
+        assert np.abs(got - full[r0:r1]).max() < 1e-12
