@@ -12,6 +12,10 @@ LIB_PATH = os.path.join(HERE, LIB_NAME)
 
 SOURCES = ["rowwise.hip", "linear.hip", "attention.hip", "runtime.hip"]
 
+# Per-file extras.  attention.hip: keep MFMA results in VGPRs; the softmax reads every score
+# right after the matrix op, and accumulator-register copies would double its VALU work.
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -40,7 +44,7 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        out = _run([hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        out = _run([hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
         return obj

@@ -121,9 +121,12 @@ __global__ void __launch_bounds__(128) attention_rows(AttnArgs a) {
 constexpr int kQB = 128;   // query rows per block (4 waves x 32)
 constexpr int kKB = 64;    // keys per LDS tile
 
-template <int DH, bool CAUSAL, bool BIAS>
+// RAGGED: the key count is not a multiple of the tile (or of the 16-byte vector): loads are
+// guarded and keys past the end are masked.  The other instantiation has no bounds work in
+// its main loop.
+template <int DH, bool CAUSAL, bool BIAS, bool RAGGED>
 __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
-  constexpr int KROW = DH + 8;        // padded K row (elements)
+  constexpr int KROW = DH + 8;        // padded K row (elements): conflict-free 128-bit reads
   constexpr int VROW = kKB + 8;       // padded V^T row
   constexpr int KS = DH / 16;         // k-steps of the score MFMA
   constexpr int DT = DH / 32;         // 32-wide output tiles over d
@@ -136,64 +139,88 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
 
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int l32 = lane % 32, half = lane / 32;
-  const int64_t nqb = (a.sq + kQB - 1) / kQB;
+  const int sq = (int)a.sq, sk = (int)a.sk, q_offset = (int)a.q_offset;
+  const int nqb = (sq + kQB - 1) / kQB;
   const int64_t t = xcd_contiguous(blockIdx.x, gridDim.x);
   const int64_t bh = t / nqb;
-  int64_t qb = t % nqb;
+  int qb = (int)(t % nqb);
   if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
   const int64_t b = bh / a.heads;
   const int h = (int)(bh % a.heads);
-  const int64_t q0 = qb * kQB;
+  const int q0 = qb * kQB;
 
   const bf16_t* kbase = (const bf16_t*)a.k + b * a.sk_b + h * DH;
   const bf16_t* vbase = (const bf16_t*)a.v + b * a.sv_b + (int64_t)h * DH * a.ldv;
 
   // this lane's query row (clamped; clamped rows compute but never store)
-  const int64_t row = q0 + wave * 32 + l32;
-  const int64_t rowc = row < a.sq ? row : a.sq - 1;
-  const int64_t qpos = a.q_offset + rowc;
+  const int row = q0 + wave * 32 + l32;
+  const int rowc = row < sq ? row : sq - 1;
+  const int qpos = q_offset + rowc;
   bf16x8 qf[KS];
   {
-    const bf16_t* qp = (const bf16_t*)a.q + b * a.sq_b + rowc * a.ldq + h * DH + half * 8;
+    const bf16_t* qp = (const bf16_t*)a.q + b * a.sq_b + (int64_t)rowc * a.ldq + h * DH + half * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
-  const bf16_t* bias_row = BIAS ? (const bf16_t*)a.bias + h * a.s_bias_h + rowc * a.ld_bias : nullptr;
+  const bf16_t* bias_row = BIAS ? (const bf16_t*)a.bias + h * a.s_bias_h + (int64_t)rowc * a.ld_bias : nullptr;
 
-  int64_t kv_end = a.sk;
+  int kv_end = sk;
   if (CAUSAL) {
-    int64_t last = q0 + kQB - 1; if (last > a.sq - 1) last = a.sq - 1;
-    if (a.q_offset + last + 1 < kv_end) kv_end = a.q_offset + last + 1;
+    int last = q0 + kQB - 1; if (last > sq - 1) last = sq - 1;
+    if (q_offset + last + 1 < kv_end) kv_end = q_offset + last + 1;
   }
-  const int64_t n_tiles = (kv_end + kKB - 1) / kKB;
-  // last key position any row of this wave may see (wave-uniform)
-  int64_t wave_last = q0 + wave * 32 + 31; if (wave_last > a.sq - 1) wave_last = a.sq - 1;
-  wave_last += a.q_offset;
-  const bool wave_active = q0 + wave * 32 < a.sq;   // waves past the last query row only help staging
+  const int n_tiles = (kv_end + kKB - 1) / kKB;
+  // last key position any row of this wave may see, first row of the wave (wave-uniform)
+  int wave_last = q0 + wave * 32 + 31; if (wave_last > sq - 1) wave_last = sq - 1;
+  wave_last += q_offset;
+  const int wave_first = q_offset + q0 + wave * 32;
+  const bool wave_active = q0 + wave * 32 < sq;   // waves past the last query row only help staging
 
-  // staging: which chunks of a K tile / V^T tile this thread moves
+  // staging: which chunks of a K tile / V^T tile this thread moves.  A V^T chunk (8 keys of
+  // one d row) is stored as two 8-byte halves, permuted inside its 16-key group to the slot
+  // order [0-3, 8-11, 4-7, 12-15], so that the 8 keys one lane feeds to a PV MFMA are 16
+  // contiguous bytes.
   int k_row[K_CHUNKS], k_col[K_CHUNKS], v_row[V_CHUNKS], v_col[V_CHUNKS];
+  const bf16_t* k_src[K_CHUNKS];
+  const bf16_t* v_src[V_CHUNKS];
+  int k_dst[K_CHUNKS], v_dst[V_CHUNKS];
 #pragma unroll
-  for (int i = 0; i < K_CHUNKS; ++i) { const int c = tid + 256 * i; k_row[i] = c / (DH / 8); k_col[i] = (c % (DH / 8)) * 8; }
+  for (int i = 0; i < K_CHUNKS; ++i) {
+    const int c = tid + 256 * i;
+    k_row[i] = c / (DH / 8); k_col[i] = (c % (DH / 8)) * 8;
+    k_src[i] = kbase + (int64_t)k_row[i] * a.ldk + k_col[i];
+    k_dst[i] = k_row[i] * KROW + k_col[i];
+  }
 #pragma unroll
-  for (int i = 0; i < V_CHUNKS; ++i) { const int c = tid + 256 * i; v_row[i] = c / (kKB / 8); v_col[i] = (c % (kKB / 8)) * 8; }
+  for (int i = 0; i < V_CHUNKS; ++i) {
+    const int c = tid + 256 * i;
+    v_row[i] = c / (kKB / 8);
+    const int ch = c % (kKB / 8);
+    v_col[i] = ch * 8;
+    v_src[i] = vbase + (int64_t)v_row[i] * a.ldv + v_col[i];
+    v_dst[i] = v_row[i] * VROW + (ch / 2) * 16 + (ch % 2) * 4;
+  }
   bf16x8 k_reg[K_CHUNKS], v_reg[V_CHUNKS];
 
-  auto load_tile = [&](int64_t k0) {
+  auto load_tile = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < K_CHUNKS; ++i) {
-      int64_t key = k0 + k_row[i]; if (key > a.sk - 1) key = a.sk - 1;
-      k_reg[i] = *reinterpret_cast<const bf16x8*>(kbase + key * a.ldk + k_col[i]);
+      if (RAGGED) {
+        int key = k0 + k_row[i]; if (key > sk - 1) key = sk - 1;
+        k_reg[i] = *reinterpret_cast<const bf16x8*>(kbase + (int64_t)key * a.ldk + k_col[i]);
+      } else {
+        k_reg[i] = *reinterpret_cast<const bf16x8*>(k_src[i] + (int64_t)k0 * a.ldk);
+      }
     }
 #pragma unroll
     for (int i = 0; i < V_CHUNKS; ++i) {
-      const int64_t key = k0 + v_col[i];
-      const bf16_t* src = vbase + (int64_t)v_row[i] * a.ldv + key;
-      if (key + 8 <= a.sk) {
+      const bf16_t* src = v_src[i] + k0;
+      if (!RAGGED) {
         v_reg[i] = *reinterpret_cast<const bf16x8*>(src);
-      } else {   // ragged end of the key range: zero-fill so that 0 * v stays 0
+      } else {   // zero-fill past the end so that 0 * v stays 0
+        const int key = k0 + v_col[i];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v_reg[i][j] = key + j < a.sk ? src[j] : (bf16_t)0.0f;
+        for (int j = 0; j < 8; ++j) v_reg[i][j] = key + j < sk ? src[j] : (bf16_t)0.0f;
       }
     }
   };
@@ -201,9 +228,14 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     bf16_t* dk = sK + buf * kKB * KROW;
     bf16_t* dv = sV + buf * DH * VROW;
 #pragma unroll
-    for (int i = 0; i < K_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(dk + k_row[i] * KROW + k_col[i]) = k_reg[i];
+    for (int i = 0; i < K_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(dk + k_dst[i]) = k_reg[i];
 #pragma unroll
-    for (int i = 0; i < V_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(dv + v_row[i] * VROW + v_col[i]) = v_reg[i];
+    for (int i = 0; i < V_CHUNKS; ++i) {
+      const bf16x4 lo = {v_reg[i][0], v_reg[i][1], v_reg[i][2], v_reg[i][3]};
+      const bf16x4 hi = {v_reg[i][4], v_reg[i][5], v_reg[i][6], v_reg[i][7]};
+      *reinterpret_cast<bf16x4*>(dv + v_dst[i]) = lo;
+      *reinterpret_cast<bf16x4*>(dv + v_dst[i] + 8) = hi;
+    }
   };
 
   f32x16 acc_o[DT];
@@ -211,15 +243,16 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   for (int i = 0; i < DT; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+  // running maximum (of scale2 * score [+ bias]) and sum, both in the log2 domain
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = rsqrtf((float)DH) * kLog2e;
 
   if (n_tiles > 0) { load_tile(0); store_tile(0); }
   __syncthreads();
 
-  for (int64_t kt = 0; kt < n_tiles; ++kt) {
-    const int buf = (int)(kt & 1);
-    const int64_t k0 = kt * kKB;
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int buf = kt & 1;
+    const int k0 = kt * kKB;
     const bool more = kt + 1 < n_tiles;
     if (more) load_tile(k0 + kKB);
 
@@ -237,66 +270,70 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
           acc_s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[tt], 0, 0, 0);
         }
       }
-      // ---- scale, bias, mask (log2 domain); lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4
-      const bool need_mask = (k0 + kKB > a.sk) || (CAUSAL && k0 + kKB - 1 > a.q_offset + q0 + wave * 32);
-      float mx = -INFINITY;
+      // ---- lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4.  Scores go to the log2 domain
+      // only where needed: with a bias right away, otherwise folded into the exponent below.
+      if (BIAS) {
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const int64_t key = k0 + tt * 32 + 8 * g4 + 4 * half;
-          float bv[4] = {0.f, 0.f, 0.f, 0.f};
-          if (BIAS) {
-            if (key < a.sk) {   // sk % 4 == 0 on this path: a group of 4 keys is all in or all out
-              const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias_row + key);
+          for (int g4 = 0; g4 < 4; ++g4) {
+            const int key = k0 + tt * 32 + 8 * g4 + 4 * half;
+            bf16x4 bb = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+            if (!RAGGED || key < sk) bb = *reinterpret_cast<const bf16x4*>(bias_row + key);
 #pragma unroll
-              for (int j = 0; j < 4; ++j) bv[j] = bf2f(bb[j]) * kLog2e;
-            }
+            for (int j = 0; j < 4; ++j)
+              acc_s[tt][4 * g4 + j] = fmaf(acc_s[tt][4 * g4 + j], scale2, bf2f(bb[j]) * kLog2e);
           }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            float s = acc_s[tt][4 * g4 + j] * scale2 + bv[j];
-            if (need_mask) {
-              const int64_t kj = key + j;
-              if (kj >= a.sk || (CAUSAL && kj > qpos)) s = -INFINITY;
-            }
-            acc_s[tt][4 * g4 + j] = s;
-            mx = fmaxf(mx, s);
-          }
-        }
       }
+      const bool need_mask = (RAGGED && k0 + kKB > sk) || (CAUSAL && k0 + kKB - 1 > wave_first);
+      if (need_mask) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kj = k0 + tt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if ((RAGGED && kj >= sk) || (CAUSAL && kj > qpos)) acc_s[tt][r] = -INFINITY;
+          }
+      }
+      float mx = acc_s[0][0];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[tt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      m_run = m_new;
+      if (!BIAS) mx *= scale2;                       // scale2 > 0: max commutes with the scaling
+      // rescale only when some row of the wave saw a new maximum
+      if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < DT; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+      }
       float psum = 0.f;
       bf16x8 pf[2][2];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(acc_s[tt][r] - m_safe);
+          const float e = BIAS ? acc_s[tt][r] - m_run : fmaf(acc_s[tt][r], scale2, -m_run);
+          const float p = __builtin_amdgcn_exp2f(e);
           psum += p;
           pf[tt][r / 8][r % 8] = f2bf(p);
         }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < DT; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+      l_run += psum;
       // ---- O^T += V^T P^T
-      const bf16_t* cv = sV + buf * DH * VROW + l32 * VROW + 4 * half;
+      const bf16_t* cv = sV + buf * DH * VROW + l32 * VROW + 8 * half;
 #pragma unroll
       for (int i = 0; i < DT; ++i)
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
-            const bf16_t* p = cv + i * 32 * VROW + tt * 32 + 16 * u;
-            const bf16x4 lo = *reinterpret_cast<const bf16x4*>(p);
-            const bf16x4 hi = *reinterpret_cast<const bf16x4*>(p + 8);
-            const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(cv + i * 32 * VROW + (tt * 2 + u) * 16);
             acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt][u], acc_o[i], 0, 0, 0);
           }
     }
@@ -304,11 +341,11 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     __syncthreads();
   }
 
-  if (row >= a.sq) return;
+  if (row >= sq) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_tot;
-  bf16_t* out = (bf16_t*)a.ctx + b * a.sc_b + row * a.ldc + h * DH;
-  const bf16_t* gate = a.gate ? (const bf16_t*)a.gate + b * a.sg_b + row * a.ldg + h * DH : nullptr;
+  bf16_t* out = (bf16_t*)a.ctx + b * a.sc_b + (int64_t)row * a.ldc + h * DH;
+  const bf16_t* gate = a.gate ? (const bf16_t*)a.gate + b * a.sg_b + (int64_t)row * a.ldg + h * DH : nullptr;
 #pragma unroll
   for (int i = 0; i < DT; ++i)
 #pragma unroll
@@ -327,9 +364,9 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     }
 }
 
-template <int DH, bool CAUSAL, bool BIAS>
+template <int DH, bool CAUSAL, bool BIAS, bool RAGGED>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
-  auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS>;
+  auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED>;
   constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
@@ -344,14 +381,20 @@ static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int DH, bool CAUSAL, bool BIAS>
+static hipError_t mfma_attn_ragged(const AttnArgs& a, hipStream_t s) {
+  if (a.sk % kKB != 0) return mfma_attn_launch<DH, CAUSAL, BIAS, true>(a, s);
+  return mfma_attn_launch<DH, CAUSAL, BIAS, false>(a, s);
+}
+
 template <int DH>
 static hipError_t mfma_attn_dispatch(const AttnArgs& a, hipStream_t s) {
   if (a.causal) {
-    if (a.bias) return mfma_attn_launch<DH, true, true>(a, s);
-    return mfma_attn_launch<DH, true, false>(a, s);
+    if (a.bias) return mfma_attn_ragged<DH, true, true>(a, s);
+    return mfma_attn_ragged<DH, true, false>(a, s);
   }
-  if (a.bias) return mfma_attn_launch<DH, false, true>(a, s);
-  return mfma_attn_launch<DH, false, false>(a, s);
+  if (a.bias) return mfma_attn_ragged<DH, false, true>(a, s);
+  return mfma_attn_ragged<DH, false, false>(a, s);
 }
 
 static bool al(const void* p, uintptr_t n) { return p == nullptr || ((uintptr_t)p % n) == 0; }
@@ -383,7 +426,7 @@ static hipError_t generic_attn_dispatch(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   if (a.batch <= 0 || a.sq <= 0 || a.heads <= 0) return hipSuccess;
-  if (a.sk <= 0) return hipErrorInvalidValue;
+  if (a.sk <= 0 || a.sk > (1 << 30) || a.sq > (1 << 30) || a.q_offset > (1 << 30)) return hipErrorInvalidValue;
   if (mfma_attn_eligible(a)) {
     switch (a.head_dim) {
       case 32: return mfma_attn_dispatch<32>(a, s);
