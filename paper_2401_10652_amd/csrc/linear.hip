@@ -101,7 +101,8 @@ __device__ __forceinline__ void tile_of_block(int64_t tiles_m, int64_t tiles_n, 
   tn = (t % width) / gsz;
 }
 
-__device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, int64_t n, float (&v)[4]) {
+__device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, int64_t n, int64_t t_base,
+                                                float (&v)[4]) {
   if (g.bias) {
     bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + n);
 #pragma unroll
@@ -125,23 +126,25 @@ __device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, 
     bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
     *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
   } else {
-    const int64_t base = (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 + (n - g.n_split) * g.t_s3;
+    const int64_t base = t_base + (n - g.n_split) * g.t_s3;
 #pragma unroll
     for (int j = 0; j < 4; ++j) ((bf16_t*)g.out_t)[base + j * g.t_s3] = f2bf(v[j]);
   }
 }
 
-template <int BM, int BN>
-__global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
-  constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
-  constexpr int TM = WM / 32, TN = WN / 32;   // 32x32 MFMA tiles per wave
-  constexpr int A_CHUNKS = BM * 8 / 256, W_CHUNKS = BN * 8 / 256;   // 16-byte chunks per thread
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(LinearArgs g) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;           // threads
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
+  constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
+  constexpr int A_CHUNKS = BM * 8 / NT, W_CHUNKS = BN * 8 / NT;   // 16-byte chunks per thread
+  static_assert(A_CHUNKS >= 1 && W_CHUNKS >= 1 && TM >= 1 && TN >= 1, "tile / wave layout mismatch");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][kLdsRow]
   bf16_t* sW = sA + 2 * BM * kLdsRow;                               // [2][BN][kLdsRow]
 
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
-  const int wave_m = wave / 2, wave_n = wave % 2;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int l32 = lane % 32, half = lane / 32;
   const int64_t tiles_m = (g.m + BM - 1) / BM, tiles_n = (g.n + BN - 1) / BN;
   int64_t tm_, tn_;
@@ -158,14 +161,14 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
   int a_dst[A_CHUNKS], w_dst[W_CHUNKS];
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
-    const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
+    const int c = tid + NT * i, row = c >> 3, ch = c & 7;
     int64_t gr = m0 + row; if (gr > g.m - 1) gr = g.m - 1;
     a_src[i] = a + gr * g.lda + ch * 8;
     a_dst[i] = row * kLdsRow + ch * 8;
   }
 #pragma unroll
   for (int i = 0; i < W_CHUNKS; ++i) {
-    const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
+    const int c = tid + NT * i, row = c >> 3, ch = c & 7;
     int64_t gr = n0 + row; if (gr > g.n - 1) gr = g.n - 1;
     w_src[i] = w + gr * g.ldw + ch * 8;
     w_dst[i] = row * kLdsRow + ch * 8;
@@ -179,32 +182,41 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  bf16x8 a_reg[A_CHUNKS], w_reg[W_CHUNKS];
+  // Software pipeline over k tiles with two register stages.  During step kt the wave
+  //   - has the global loads of tile kt+2 in flight into one register set,
+  //   - multiplies tile kt out of LDS buffer kt & 1, and
+  //   - between the MFMA groups of that multiply, writes tile kt+1 (loaded during the
+  //     previous step, so long since landed) from the other register set into the other LDS
+  //     buffer.  LDS takes writes at about a third of its read rate, and all waves of the
+  //     block reach the barrier together, so the writes must hide under the matrix work
+  //     rather than sit between the multiply and the barrier.
+  bf16x8 a_r0[A_CHUNKS], w_r0[W_CHUNKS], a_r1[A_CHUNKS], w_r1[W_CHUNKS];
   const int64_t kt_count = g.k / kBK;
+  constexpr int KSTEPS = kBK / 16;
+  auto load_regs = [&](bf16x8 (&ar)[A_CHUNKS], bf16x8 (&wr)[W_CHUNKS], int64_t kt) {
+    const int64_t koff = kt * kBK;
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i]);
+    for (int i = 0; i < A_CHUNKS; ++i) ar[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + koff);
 #pragma unroll
-  for (int i = 0; i < W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i]);
-#pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(sA + a_dst[i]) = a_reg[i];
-#pragma unroll
-  for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(sW + w_dst[i]) = w_reg[i];
-  __syncthreads();
-
-  for (int64_t kt = 0; kt < kt_count; ++kt) {
+    for (int i = 0; i < W_CHUNKS; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(w_src[i] + koff);
+  };
+  // chunk c of the A_CHUNKS + W_CHUNKS staged chunks -> LDS buffer `buf`
+  auto store_chunk = [&](const bf16x8 (&ar)[A_CHUNKS], const bf16x8 (&wr)[W_CHUNKS], int buf, int c) {
+    if (c < A_CHUNKS) *reinterpret_cast<bf16x8*>(sA + buf * BM * kLdsRow + a_dst[c]) = ar[c];
+    else *reinterpret_cast<bf16x8*>(sW + buf * BN * kLdsRow + w_dst[c - A_CHUNKS]) = wr[c - A_CHUNKS];
+  };
+  constexpr int CHUNKS = A_CHUNKS + W_CHUNKS;
+  auto step = [&](int64_t kt, bf16x8 (&hold_a)[A_CHUNKS], bf16x8 (&hold_w)[W_CHUNKS],
+                  bf16x8 (&fill_a)[A_CHUNKS], bf16x8 (&fill_w)[W_CHUNKS]) {
+    // No branches in the step: a conditional load would make the compiler lose count of the
+    // loads in flight and wait for the newest ones before every LDS store.  Past the end the
+    // last tile is simply loaded (and stored to the idle buffer) again.
+    load_regs(fill_a, fill_w, kt + 2 < kt_count ? kt + 2 : kt_count - 1);
     const int buf = (int)(kt & 1);
-    const bool more = kt + 1 < kt_count;
-    if (more) {
-      const int64_t koff = (kt + 1) * kBK;
-#pragma unroll
-      for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + koff);
-#pragma unroll
-      for (int i = 0; i < W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i] + koff);
-    }
     const bf16_t* cA = sA + buf * BM * kLdsRow + (wave_m * WM + l32) * kLdsRow + half * 8;
     const bf16_t* cW = sW + buf * BN * kLdsRow + (wave_n * WN + l32) * kLdsRow + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
+    for (int ks = 0; ks < KSTEPS; ++ks) {
       bf16x8 fa[TM], fw[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(cA + i * 32 * kLdsRow + ks * 16);
@@ -215,23 +227,32 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      bf16_t* nA = sA + (buf ^ 1) * BM * kLdsRow;
-      bf16_t* nW = sW + (buf ^ 1) * BN * kLdsRow;
 #pragma unroll
-      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(nA + a_dst[i]) = a_reg[i];
-#pragma unroll
-      for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(nW + w_dst[i]) = w_reg[i];
+      for (int c = ks * CHUNKS / KSTEPS; c < (ks + 1) * CHUNKS / KSTEPS; ++c) store_chunk(hold_a, hold_w, buf ^ 1, c);
+      __builtin_amdgcn_sched_barrier(0);   // keep each slice of the stores with its MFMA group
     }
     __syncthreads();
+  };
+
+  load_regs(a_r0, w_r0, 0);
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) store_chunk(a_r0, w_r0, 0, c);
+  load_regs(a_r0, w_r0, kt_count > 1 ? 1 : 0);
+  __syncthreads();
+  int64_t kt = 0;
+  for (; kt + 1 < kt_count; kt += 2) {
+    step(kt, a_r0, w_r0, a_r1, w_r1);
+    step(kt + 1, a_r1, w_r1, a_r0, w_r0);
   }
+  if (kt < kt_count) step(kt, a_r0, w_r0, a_r1, w_r1);
 
   // acc[i][j][r]: row m = .. + l32, column n = .. + 8*(r/4) + 4*half + (r%4).
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int64_t m = m0 + wave_m * WM + i * 32 + l32;
     if (m >= g.m) continue;
+    // offset of row m in the strided ("transposed") output, if any
+    const int64_t t_base = g.n_split < g.n ? (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 : 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -239,7 +260,7 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
         const int64_t n = n0 + wave_n * WN + j * 32 + 8 * q + 4 * half;
         if (n >= g.n) continue;
         float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        epilogue_store4(g, m, n, v);
+        epilogue_store4(g, m, n, t_base, v);
       }
     }
   }
@@ -248,9 +269,9 @@ __global__ void __launch_bounds__(256) linear_mfma_bf16(LinearArgs g) {
 template <int BM, int BN>
 constexpr size_t mfma_lds_bytes() { return (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16_t); }
 
-template <int BM, int BN>
+template <int BM, int BN, int WAVES_M, int WAVES_N>
 static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
-  auto kern = linear_mfma_bf16<BM, BN>;
+  auto kern = linear_mfma_bf16<BM, BN, WAVES_M, WAVES_N>;
   static bool attr_set = false;   // the attribute is per function; set once per process
   constexpr size_t lds = mfma_lds_bytes<BM, BN>();
   if (!attr_set) {
@@ -260,7 +281,7 @@ static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
     attr_set = true;
   }
   const int64_t tiles = ((g.m + BM - 1) / BM) * ((g.n + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)g.batch), dim3(256), lds, s, g);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)g.batch), dim3(64 * WAVES_M * WAVES_N), lds, s, g);
   return hipGetLastError();
 }
 
@@ -291,10 +312,15 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (g.batch > 1 && (g.bias || g.mul || g.resid || g.out_t || g.act != AC_ACT_NONE)) return hipErrorInvalidValue;
   if (g.batch > 65535) return hipErrorInvalidValue;
   if (mfma_eligible(g)) {
-    // 128x128 tiles when they fill the 256 CUs, otherwise 64x64 tiles (4x as many blocks).
-    const int64_t big = ((g.m + 127) / 128) * ((g.n + 127) / 128) * g.batch;
-    if (big >= 192 && g.m >= 128) return mfma_launch<128, 128>(g, s);
-    return mfma_launch<64, 64>(g, s);
+    // A CU takes in at most 64 bytes per clock from L2 while its matrix cores retire 4096
+    // flops per clock, so a tile needs >= 64 flops per loaded byte just to break even: 128x128
+    // tiles sit exactly there, 256x256 tiles have twice that.  Take the largest tile that
+    // still gives every CU a block; the k order is the same for all of them.
+    auto tiles = [&](int64_t bm, int64_t bn) { return ((g.m + bm - 1) / bm) * ((g.n + bn - 1) / bn) * g.batch; };
+    if (tiles(256, 256) >= 224) return mfma_launch<256, 256, 2, 4>(g, s);
+    if (tiles(256, 128) >= 224) return mfma_launch<256, 128, 4, 2>(g, s);
+    if (tiles(128, 128) >= 192 && g.m >= 128) return mfma_launch<128, 128, 2, 2>(g, s);
+    return mfma_launch<64, 64, 2, 2>(g, s);
   }
   dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)g.batch);
   if (g.dtype == AC_BF16) hipLaunchKernelGGL((linear_fma<bf16_t>), grid, dim3(256), 0, s, g);
