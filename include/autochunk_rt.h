@@ -239,7 +239,7 @@ int ac_op_linear(const void* a, int64_t lda, const void* w, int64_t ldw, const v
  * Causal: query row r stands at position q_offset + r and sees keys j <= q_offset + r.
  * bias (may be NULL) points at the bias row of query row 0: bias[h * stride_bias_head +
  * r * ld_bias + key]; it is shared by all `batch` problems.
- * The scores never leave the chip.
+ * The scores never leave the chip.  n_splits / split_workspace: see below.
  */
 int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch,
                     const void* k, int64_t ldk, int64_t stride_k_batch,
@@ -248,7 +248,23 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch,
                     const void* gate, int64_t ldg, int64_t stride_g_batch,
                     void* ctx, int64_t ldc, int64_t stride_c_batch,
                     int64_t batch, int64_t sq, int64_t sk, int heads, int head_dim,
-                    int causal, int64_t q_offset, int dtype, void* stream);
+                    int causal, int64_t q_offset,
+                    int n_splits, void* split_workspace, uint64_t split_workspace_bytes,
+                    int dtype, void* stream);
+
+/*
+ * Key splits.  A launch with few query rows would leave most compute units idle, so the
+ * keys each block of queries sees can be cut into n_splits runs that separate blocks
+ * process; their fp32 partial results (unnormalised context, running maximum and sum) go to
+ * split_workspace (device, 16-byte aligned, ac_attention_split_workspace_bytes large) and a
+ * second kernel merges them.  n_splits <= 1 means one pass and no workspace.  Results for
+ * different n_splits agree to rounding, not bitwise.  ac_attention_key_splits is the count
+ * the executor uses for a launch shape (1 when the launch already fills the GPU).
+ */
+int ac_attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim,
+                            int dtype, int v_transposed);
+uint64_t ac_attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim,
+                                            int n_splits);
 
 /* y = activation(x + bias[col]) over [rows, cols]; bias may be NULL. */
 int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy,

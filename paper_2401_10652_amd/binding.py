@@ -84,7 +84,9 @@ SIGNATURES = {
     "ac_op_linear": (INT, [VP, I64, VP, I64, VP, VP, I64, VP, I64, VP, I64, VP, I64, I64, I64, I64, I64,
                            I64, I64, I64, INT, INT, VP]),
     "ac_op_attention": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, INT, VP, I64, I64, VP, I64, I64,
-                              VP, I64, I64, I64, I64, I64, INT, INT, INT, I64, INT, VP]),
+                              VP, I64, I64, I64, I64, I64, INT, INT, INT, I64, INT, VP, U64, INT, VP]),
+    "ac_attention_key_splits": (INT, [I64, I64, INT, I64, INT, INT, INT]),
+    "ac_attention_split_workspace_bytes": (U64, [I64, INT, I64, INT, INT]),
     "ac_op_bias_act": (INT, [VP, I64, VP, VP, I64, I64, I64, INT, INT, VP]),
     "ac_op_binary": (INT, [VP, I64, VP, I64, VP, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose": (INT, [VP, I64, VP, I64, I64, I64, INT, VP]),
@@ -253,7 +255,7 @@ def ac_op_linear(a, w, out, bias=None, mul=None, residual=None, activation=AC_AC
 
 
 def ac_op_attention(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bias=None, gate=None,
-                    v_transposed=False, batch=1, strides=None):
+                    v_transposed=False, batch=1, strides=None, n_splits=1, split_workspace=None):
     """q [sq, >=heads*head_dim], k [sk, ..], v [sk, ..] or v^T [heads*head_dim, sk]; one problem
     unless ``batch`` and ``strides`` = (q, k, v, gate, ctx batch strides in elements) are given."""
     sq, sk = q.shape[0], k.shape[0]
@@ -264,7 +266,17 @@ def ac_op_attention(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bia
         _ptr(bias), 0 if bias is None else bias.stride(1), 0 if bias is None else bias.stride(0),
         _ptr(gate), 0 if gate is None else gate.stride(0), sb[3],
         _ptr(ctx), ctx.stride(0), sb[4], batch, sq, sk, heads, head_dim, int(causal), q_offset,
+        n_splits, _ptr(split_workspace),
+        0 if split_workspace is None else split_workspace.numel() * split_workspace.element_size(),
         _dt(q), _stream()), "ac_op_attention")
+
+
+def ac_attention_key_splits(sq, sk, heads, batch, head_dim, dtype, v_transposed=True):
+    return lib().ac_attention_key_splits(sq, sk, heads, batch, head_dim, DTYPES[dtype], int(v_transposed))
+
+
+def ac_attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits):
+    return lib().ac_attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits)
 
 
 def ac_op_bias_act(x, bias, y, activation):

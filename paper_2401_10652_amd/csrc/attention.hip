@@ -141,9 +141,12 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   const int l32 = lane % 32, half = lane / 32;
   const int sq = (int)a.sq, sk = (int)a.sk, q_offset = (int)a.q_offset;
   const int nqb = (sq + kQB - 1) / kQB;
+  const int ns = a.n_splits > 1 ? a.n_splits : 1;
   const int64_t t = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int64_t bh = t / nqb;
-  int qb = (int)(t % nqb);
+  const int split = (int)(t % ns);
+  const int64_t bq = t / ns;
+  const int64_t bh = bq / nqb;
+  int qb = (int)(bq % nqb);
   if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
   const int64_t b = bh / a.heads;
   const int h = (int)(bh % a.heads);
@@ -169,7 +172,11 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     int last = q0 + kQB - 1; if (last > sq - 1) last = sq - 1;
     if (q_offset + last + 1 < kv_end) kv_end = q_offset + last + 1;
   }
-  const int n_tiles = (kv_end + kKB - 1) / kKB;
+  const int n_tiles_all = (kv_end + kKB - 1) / kKB;
+  // this block's share of the key tiles: split s takes tiles [s * per, (s + 1) * per)
+  const int per_split = (n_tiles_all + ns - 1) / ns;
+  const int tile_lo = split * per_split;
+  const int tile_hi = tile_lo + per_split < n_tiles_all ? tile_lo + per_split : n_tiles_all;
   // last key position any row of this wave may see, first row of the wave (wave-uniform)
   int wave_last = q0 + wave * 32 + 31; if (wave_last > sq - 1) wave_last = sq - 1;
   wave_last += q_offset;
@@ -247,13 +254,13 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = rsqrtf((float)DH) * kLog2e;
 
-  if (n_tiles > 0) { load_tile(0); store_tile(0); }
+  if (tile_lo < tile_hi) { load_tile(tile_lo * kKB); store_tile(tile_lo & 1); }
   __syncthreads();
 
-  for (int kt = 0; kt < n_tiles; ++kt) {
+  for (int kt = tile_lo; kt < tile_hi; ++kt) {
     const int buf = kt & 1;
     const int k0 = kt * kKB;
-    const bool more = kt + 1 < n_tiles;
+    const bool more = kt + 1 < tile_hi;
     if (more) load_tile(k0 + kKB);
 
     if (wave_active && (!CAUSAL || k0 <= wave_last)) {
@@ -343,6 +350,25 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
 
   if (row >= sq) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (ns > 1) {
+    // partial result of this key split: unnormalised O (fp32), running max and sum
+    const int64_t prow = ((int64_t)split * a.batch + b) * sq + row;
+    float* po = (float*)a.part_o + (prow * a.heads + h) * DH;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int d = i * 32 + 8 * g4 + 4 * half;
+        const f32x4 o = {acc_o[i][4 * g4], acc_o[i][4 * g4 + 1], acc_o[i][4 * g4 + 2], acc_o[i][4 * g4 + 3]};
+        *reinterpret_cast<f32x4*>(po + d) = o;
+      }
+    if (half == 0) {
+      float* pml = (float*)a.part_ml + (prow * a.heads + h) * 2;
+      pml[0] = m_run;
+      pml[1] = l_tot;
+    }
+    return;
+  }
   const float inv = 1.0f / l_tot;
   bf16_t* out = (bf16_t*)a.ctx + b * a.sc_b + (int64_t)row * a.ldc + h * DH;
   const bf16_t* gate = a.gate ? (const bf16_t*)a.gate + b * a.sg_b + (int64_t)row * a.ldg + h * DH : nullptr;
@@ -364,6 +390,43 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
     }
 }
 
+// Merge of the key splits: ctx = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) [* gate].
+// One thread per (problem, row, head, 4 consecutive d).
+__global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
+  const int dh4 = a.head_dim / 4;
+  const int64_t total = a.batch * a.sq * a.heads * dh4;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int d = (int)(i % dh4) * 4;
+  const int64_t rh = i / dh4;                  // (b * sq + row) * heads + h
+  const int h = (int)(rh % a.heads);
+  const int64_t br = rh / a.heads;
+  const int64_t row = br % a.sq, b = br / a.sq;
+  const int64_t stride = a.batch * a.sq * a.heads;   // (row, head) pairs per split
+  const float* ml = (const float*)a.part_ml;
+  float M = -INFINITY;
+  for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, ml[(s * stride + rh) * 2]);
+  float L = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < a.n_splits; ++s) {
+    const float m = ml[(s * stride + rh) * 2];
+    if (m == -INFINITY) continue;              // that split saw no key of this row
+    const float w = __builtin_amdgcn_exp2f(m - M);
+    L += ml[(s * stride + rh) * 2 + 1] * w;
+    const f32x4 o = *reinterpret_cast<const f32x4*>((const float*)a.part_o + (s * stride + rh) * a.head_dim + d);
+    acc += o * w;
+  }
+  const float inv = 1.0f / L;
+  float v[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+  if (a.gate) {
+    const bf16x4 gg = *reinterpret_cast<const bf16x4*>((const bf16_t*)a.gate + b * a.sg_b + row * a.ldg + h * a.head_dim + d);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] *= bf2f(gg[j]);
+  }
+  const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+  *reinterpret_cast<bf16x4*>((bf16_t*)a.ctx + b * a.sc_b + row * a.ldc + h * a.head_dim + d) = o;
+}
+
 template <int DH, bool CAUSAL, bool BIAS, bool RAGGED>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED>;
@@ -376,8 +439,13 @@ static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
     attr_set = true;
   }
   const int64_t nqb = (a.sq + kQB - 1) / kQB;
-  const int64_t blocks = nqb * a.heads * a.batch;
+  const int ns = a.n_splits > 1 ? a.n_splits : 1;
+  const int64_t blocks = nqb * a.heads * a.batch * ns;
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || ns == 1) return e;
+  const int64_t items = a.batch * a.sq * a.heads * (DH / 4);
+  hipLaunchKernelGGL(attention_merge_splits, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
@@ -424,7 +492,30 @@ static hipError_t generic_attn_dispatch(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+// Key splits for a launch that would leave most of the 256 CUs idle: enough blocks for
+// about three per CU, each split at least 512 keys long.  A pure function of the launch
+// shape, so planning and execution agree.
+int attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim, int dtype, int v_transposed) {
+  if (dtype != AC_BF16 || !v_transposed) return 1;
+  if (head_dim != 32 && head_dim != 64 && head_dim != 128) return 1;
+  const int64_t blocks = ((sq + kQB - 1) / kQB) * heads * batch;
+  if (blocks <= 0 || blocks >= 512 || sk < 1024) return 1;
+  int64_t want = (768 + blocks - 1) / blocks;
+  const int64_t by_len = sk / 512;
+  if (want > by_len) want = by_len;
+  if (want > 16) want = 16;
+  return want < 1 ? 1 : (int)want;
+}
+
+uint64_t attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim, int n_splits) {
+  if (n_splits <= 1) return 0;
+  const uint64_t rh = (uint64_t)n_splits * batch * sq * heads;
+  return rh * head_dim * 4 + rh * 2 * 4;
+}
+
+hipError_t launch_attention(const AttnArgs& a_in, hipStream_t s) {
+  AttnArgs a = a_in;
+  if (a.n_splits > 1 && (!a.part_o || !a.part_ml || !mfma_attn_eligible(a))) a.n_splits = 1;
   if (a.batch <= 0 || a.sq <= 0 || a.heads <= 0) return hipSuccess;
   if (a.sk <= 0 || a.sk > (1 << 30) || a.sq > (1 << 30) || a.q_offset > (1 << 30)) return hipErrorInvalidValue;
   if (mfma_attn_eligible(a)) {

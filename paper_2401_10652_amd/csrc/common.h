@@ -123,6 +123,12 @@ struct AttnArgs {
   int heads, head_dim, causal;
   int64_t q_offset;
   int dtype;
+  // n_splits > 1: the keys each query block sees are cut into n_splits runs handled by
+  // separate blocks; partial results go to part_o [split][b][row][head][d] (fp32) and
+  // part_ml [split][b][row][head][2] (running max, sum) and are merged by a second kernel.
+  int n_splits;
+  void* part_o;
+  void* part_ml;
 };
 
 hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,
@@ -134,6 +140,8 @@ hipError_t launch_binary(const void* a, int64_t lda, const void* b, int64_t ldb,
                          int64_t rows, int64_t cols, int op, int dtype, hipStream_t s);
 hipError_t launch_linear(const LinearArgs& g, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+int attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim, int dtype, int v_transposed);
+uint64_t attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim, int n_splits);
 // Row-major value matrix [keys, cols] -> transposed copy [cols, keys] (bf16), for callers
 // of the attention entry point that hold v row-major.
 hipError_t launch_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows,

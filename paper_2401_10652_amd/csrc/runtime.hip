@@ -166,7 +166,17 @@ struct Walk {
     }
     const double fl = 4.0 * pairs * a.head_dim * a.heads * a.batch;
     const double by = ((double)a.sq * 2 + (double)a.sk * 2) * a.heads * a.head_dim * a.batch * eb();
+    // few query rows: cut the keys into runs so that every CU gets blocks; the fp32 partial
+    // results live in the arena for the duration of this call
+    const uint64_t mk = arena.mark();
+    a.n_splits = attention_key_splits(a.sq, a.sk, a.heads, a.batch, a.head_dim, a.dtype, a.v_transposed);
+    if (a.n_splits > 1) {
+      const uint64_t rh = (uint64_t)a.n_splits * a.batch * a.sq * a.heads;
+      a.part_o = arena.push(rh * a.head_dim * 4);
+      a.part_ml = arena.push(rh * 2 * 4);
+    }
     run(K_ATTN, fl, by, "attention", [&] { return launch_attention(a, stream); });
+    arena.release(mk);
   }
   void bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows, int64_t cols,
                 int act) {
@@ -998,11 +1008,18 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch, const vo
                     int64_t stride_k_batch, const void* v, int64_t ldv, int64_t stride_v_batch, int v_transposed,
                     const void* bias, int64_t ld_bias, int64_t stride_bias_head, const void* gate, int64_t ldg,
                     int64_t stride_g_batch, void* ctx, int64_t ldc, int64_t stride_c_batch, int64_t batch,
-                    int64_t sq, int64_t sk, int heads, int head_dim, int causal, int64_t q_offset, int dtype,
-                    void* stream) {
+                    int64_t sq, int64_t sk, int heads, int head_dim, int causal, int64_t q_offset, int n_splits,
+                    void* split_workspace, uint64_t split_workspace_bytes, int dtype, void* stream) {
   if (!q || !k || !v || !ctx || batch < 0 || sq < 0 || sk < 1 || heads < 1 || head_dim < 1 || q_offset < 0 ||
-      !dtype_ok(dtype))
+      !dtype_ok(dtype) || n_splits < 0 || n_splits > 64)
     return fail(AC_ERR_ARG, "ac_op_attention: bad argument");
+  if (n_splits > 1) {
+    const uint64_t need = attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits);
+    if (!split_workspace || split_workspace_bytes < need)
+      return fail(AC_ERR_WORKSPACE, "ac_op_attention: %d key splits need %llu workspace bytes", n_splits,
+                  (unsigned long long)need);
+    if (((uintptr_t)split_workspace & 15u) != 0) return fail(AC_ERR_ALIGN, "split workspace must be 16-byte aligned");
+  }
   AttnArgs a{};
   a.q = q; a.ldq = ldq; a.sq_b = stride_q_batch; a.k = k; a.ldk = ldk; a.sk_b = stride_k_batch;
   a.v = v; a.ldv = ldv; a.sv_b = stride_v_batch; a.v_transposed = v_transposed != 0;
@@ -1010,7 +1027,21 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch, const vo
   a.gate = gate; a.ldg = ldg; a.sg_b = stride_g_batch; a.ctx = ctx; a.ldc = ldc; a.sc_b = stride_c_batch;
   a.batch = batch; a.sq = sq; a.sk = sk; a.heads = heads; a.head_dim = head_dim; a.causal = causal != 0;
   a.q_offset = q_offset; a.dtype = dtype;
+  if (n_splits > 1) {
+    a.n_splits = n_splits;
+    a.part_o = split_workspace;
+    a.part_ml = (uint8_t*)split_workspace + (uint64_t)n_splits * batch * sq * heads * head_dim * 4;
+  }
   return hip_status(launch_attention(a, (hipStream_t)stream), "attention");
+}
+
+int ac_attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim, int dtype,
+                            int v_transposed) {
+  return attention_key_splits(sq, sk, heads, batch, head_dim, dtype, v_transposed);
+}
+
+uint64_t ac_attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim, int n_splits) {
+  return attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits);
 }
 
 int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows, int64_t cols,

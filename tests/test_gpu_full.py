@@ -3,7 +3,7 @@
 C1-C3: the whole stack against the whole fp64 oracle.  C4: each pair-stack module at
 N_res = 1024 against oracle rows evaluated one by one, and the whole block chunked vs
 unchunked.  C5: one layer at S = 65536 against oracle row blocks, and the two-layer stack
-chunked two ways (properties that hold at any size: finite, identical for every chunk length).
+chunked two ways (properties that hold at any size: finite, equal to rounding for every chunk length).
 """
 import dataclasses
 
@@ -56,9 +56,11 @@ def test_c2_gpt_full_stack(B):
     err = rel_err(host(y), ref)
     print("C2 rel err", err)
     assert err <= TOL["bf16"]
-    import torch
+    # another chunking cuts the keys of the attention launches differently (key splits), so the
+    # two results agree to rounding, not bitwise
     y2, _, _ = run_transformer(B, cfg, x, layers, tregions(B, (1024, 1024, 1024)), dw=dw)
-    assert torch.equal(y, y2)
+    assert rel_err(host(y2), ref) <= TOL["bf16"]
+    assert rel_err(host(y2), host(y)) <= 0.5 * TOL["bf16"]
 
 
 def test_c3_vit_full_stack(B):
@@ -94,7 +96,7 @@ def test_c5_long_context(B):
     ya, infa, dw2 = run_transformer(B, cfg, x2, layers2, tregions(B, (0, 0, 0)), cfg.act_budget)
     yb, _, _ = run_transformer(B, cfg, x2, layers2, tregions(B, (8192, 2048, 4096)), dw=dw2)
     assert bool(torch.isfinite(ya.float()).all())
-    assert torch.equal(ya, yb)
+    assert rel_err(host(yb), host(ya)) <= 0.5 * TOL["bf16"]   # key splits differ: equal to rounding
     assert infa.peak_bytes_planned <= cfg.act_budget
 
 

@@ -110,7 +110,7 @@ def test_linear_strided_store(B, dtype, m, n, k, split):
         assert rel_err(host(out_p), want) <= TOL[dtype]
 
 
-def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate, v_t):
+def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate, v_t, n_splits=1):
     import torch
     hd = heads * dh
     q = draw((sq, hd), 30, dtype)
@@ -127,9 +127,14 @@ def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate
     else:
         vv = dv
     ctx = torch.full((sq, hd), float("nan"), device="cuda", dtype=dq.dtype)
+    ws = None
+    if n_splits > 1:
+        need = B.ac_attention_split_workspace_bytes(sq, heads, 1, dh, n_splits)
+        ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
     B.ac_op_attention(dq, dk, vv, ctx, heads, dh, causal=causal, q_offset=q_offset,
                       bias=None if bias is None else dev(B, bias, dtype),
-                      gate=None if gate is None else dev(B, gate, dtype), v_transposed=v_t)
+                      gate=None if gate is None else dev(B, gate, dtype), v_transposed=v_t,
+                      n_splits=n_splits, split_workspace=ws)
     torch.cuda.synchronize()
     ref = O.attention(q, k, v, heads, causal, bias=bias, q_offset=q_offset)
     if gate is not None:
@@ -149,6 +154,26 @@ def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate
 ])
 def test_attention_mfma(B, dh, sq, sk, causal, q_offset):
     assert _attn_case(B, "bf16", sq, sk, 3, dh, causal, q_offset, False, False, True) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dh", [32, 64, 128])
+@pytest.mark.parametrize("n_splits", [2, 3, 7])
+def test_attention_key_splits(B, dh, n_splits):
+    """Key runs handled by separate blocks and merged: same result to rounding; includes splits
+    that are empty for early query blocks (causal) and more splits than key tiles."""
+    assert _attn_case(B, "bf16", 300, 1216, 2, dh, True, 916, False, False, True, n_splits) <= TOL["bf16"]
+    assert _attn_case(B, "bf16", 200, 200, 2, dh, True, 0, False, False, True, n_splits) <= TOL["bf16"]
+    assert _attn_case(B, "bf16", 130, 1000, 3, dh, False, 0, dh != 128, True, True, n_splits) <= TOL["bf16"]
+
+
+def test_attention_split_workspace_is_checked(B):
+    import torch
+    q = torch.zeros((64, 64), device="cuda", dtype=torch.bfloat16)
+    vt = torch.zeros((64, 64), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(B.AcError) as ei:
+        B.ac_op_attention(q, q, vt, q.clone(), 1, 64, v_transposed=True, n_splits=4,
+                          split_workspace=torch.zeros(16, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == B.AC_ERR_WORKSPACE
 
 
 @pytest.mark.parametrize("dh", [32, 64])

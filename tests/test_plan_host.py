@@ -34,9 +34,21 @@ def al(v):
     return (v + 255) // 256 * 256
 
 
+def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
+    """The executor cuts the keys of a launch with fewer than 512 blocks of 128 query rows into
+    runs of at least 512 keys, enough for about 768 blocks, at most 16 (bf16 matrix-core path)."""
+    if dtype != "bf16" or dh not in (32, 64, 128):
+        return 1
+    blocks = -(-sq // 128) * heads * batch
+    if blocks >= 512 or sk < 1024:
+        return 1
+    return max(1, min(-(-768 // blocks), sk // 512, 16))
+
+
 def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False):
     """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], h (Td), inter-layer t (Td if
-    layers > 1), plus the largest per-segment set: u (c d) | ctx (c d) | u (c d) + hidden (c F)."""
+    layers > 1), plus the largest per-segment set: u (c d) | ctx (c d) + fp32 split partials
+    (ns c H (d_h + 2) floats) | u (c d) + hidden (c F)."""
     e = 2 if cfg.dtype == "bf16" else 4
     T, d, F = cfg.seq * cfg.batch, cfg.d_model, cfg.d_ffn
     whole = (al(T * 2 * d * e) + al(T * d * e)) if cfg.dtype == "bf16" else al(T * 3 * d * e)
@@ -44,7 +56,9 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False):
     if cfg.layers > 1:
         whole += al(T * d * e)
     r1 = al(c_qkv * d * e)
-    r2 = al(c_attn * d * e) + (al(c_attn * d * e) if unfused else 0)
+    ns = key_splits_by_hand(c_attn, cfg.seq, cfg.heads, 1, cfg.head_dim, cfg.dtype)
+    parts = (al(ns * c_attn * d * 4) + al(ns * c_attn * cfg.heads * 8)) if ns > 1 else 0
+    r2 = al(c_attn * d * e) + max(parts, al(c_attn * d * e) if unfused else 0)
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
     return whole + max(r1, r2, r3)
 
@@ -71,6 +85,18 @@ def test_planned_bytes_equal_the_arena_worked_by_hand(cfg, c):
     assert info.peak_bytes_model == M.transformer_layer_peak(cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, e, *c)
     assert info.peak_bytes_model_unchunked == M.transformer_layer_peak(cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, e)
     p.close()
+
+
+def test_key_split_rule():
+    for sq, sk, h, b, dh, dt in ((1792, 8192, 16, 1, 64, "bf16"), (1024, 8192, 16, 1, 64, "bf16"),
+                                 (512, 4096, 12, 1, 64, "bf16"), (640, 65536, 16, 1, 128, "bf16"),
+                                 (8192, 8192, 16, 1, 64, "bf16"), (64, 640, 4, 1, 64, "bf16"),
+                                 (1024, 1024, 4, 64, 32, "bf16"), (64, 256, 4, 1, 16, "f32")):
+        assert B.ac_attention_key_splits(sq, sk, h, b, dh, dt) == key_splits_by_hand(sq, sk, h, b, dh, dt)
+    assert B.ac_attention_key_splits(1792, 8192, 16, 1, 64, "bf16") == 4
+    assert B.ac_attention_key_splits(512, 4096, 12, 1, 64, "bf16") == 8
+    assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 3) == 3 * 2 * 100 * 4 * (64 + 2) * 4
+    assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 1) == 0
 
 
 def test_unfused_flag_adds_the_temporaries():
