@@ -101,17 +101,16 @@ __device__ __forceinline__ void tile_of_block(int64_t tiles_m, int64_t tiles_n, 
   tn = (t % width) / gsz;
 }
 
-__device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, int64_t n, int64_t t_base,
-                                                float (&v)[4]) {
+// bias, activation, multiplier, residual for 4 consecutive columns of one row (fp32)
+template <int ACT>
+__device__ __forceinline__ void epilogue_math4(const LinearArgs& g, int64_t m, int64_t n, float (&v)[4]) {
   if (g.bias) {
     bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + n);
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
   }
-  if (g.act != AC_ACT_NONE) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = apply_act_rt(v[j], g.act);
-  }
+  for (int j = 0; j < 4; ++j) v[j] = apply_act<ACT>(v[j]);
   if (g.mul) {
     bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.mul + m * g.ldmul + n);
 #pragma unroll
@@ -122,13 +121,60 @@ __device__ __forceinline__ void epilogue_store4(const LinearArgs& g, int64_t m, 
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
   }
-  if (n < g.n_split) {
-    bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
-    *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
-  } else {
-    const int64_t base = t_base + (n - g.n_split) * g.t_s3;
+}
+
+// The epilogue of one block.  A tile that lies wholly in the row-major part of the output
+// is rounded to bf16 into LDS (free after the k loop) and written out with 16-byte stores
+// whose lanes walk along rows; other tiles (strided store, narrow or misaligned outputs)
+// store 8 bytes per lane straight from the registers.
+template <int ACT, int BM, int BN, int WAVES_M, int WAVES_N>
+__device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)[BM / WAVES_M / 32][BN / WAVES_N / 32],
+                                              bf16_t* lds, int64_t m0, int64_t n0, int wave_m, int wave_n,
+                                              int l32, int half, int tid) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  constexpr int CROW = BN + 8;   // padded row of the staged tile
+  const bool staged = n0 + BN <= g.n_split && g.ldo % 8 == 0 && ((uintptr_t)g.out % 16) == 0 && g.n % 8 == 0;
+  if (staged) __syncthreads();   // every wave is done reading the k-loop buffers
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ((bf16_t*)g.out_t)[base + j * g.t_s3] = f2bf(v[j]);
+  for (int i = 0; i < TM; ++i) {
+    const int rl = wave_m * WM + i * 32 + l32;
+    const int64_t m = m0 + rl;
+    const bool row_ok = m < g.m;
+    const int64_t mc = row_ok ? m : g.m - 1;
+    // offset of row m in the strided ("transposed") output, if any
+    const int64_t t_base = g.n_split < g.n ? (mc / g.t_period) * g.t_s1 + (mc % g.t_period) * g.t_s2 : 0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int cl = wave_n * WN + j * 32 + 8 * q + 4 * half;
+        const int64_t n = n0 + cl;
+        if (!row_ok || n >= g.n) continue;
+        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        epilogue_math4<ACT>(g, m, n, v);
+        const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+        if (staged) {
+          *reinterpret_cast<bf16x4*>(lds + rl * CROW + cl) = o;
+        } else if (n < g.n_split) {
+          *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
+        } else {
+          const int64_t base = t_base + (n - g.n_split) * g.t_s3;
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) ((bf16_t*)g.out_t)[base + jj * g.t_s3] = o[jj];
+        }
+      }
+    }
+  }
+  if (!staged) return;
+  __syncthreads();
+  constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
+#pragma unroll 4
+  for (int c = tid; c < BM * CPR; c += NT) {
+    const int rl = c / CPR, cc = (c % CPR) * 8;
+    const int64_t m = m0 + rl, n = n0 + cc;
+    if (m < g.m && n < g.n)
+      *reinterpret_cast<bf16x8*>((bf16_t*)g.out + m * g.ldo + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
   }
 }
 
@@ -247,22 +293,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
   if (kt < kt_count) step(kt, a_r0, w_r0, a_r1, w_r1);
 
   // acc[i][j][r]: row m = .. + l32, column n = .. + 8*(r/4) + 4*half + (r%4).
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int64_t m = m0 + wave_m * WM + i * 32 + l32;
-    if (m >= g.m) continue;
-    // offset of row m in the strided ("transposed") output, if any
-    const int64_t t_base = g.n_split < g.n ? (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 : 0;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t n = n0 + wave_n * WN + j * 32 + 8 * q + 4 * half;
-        if (n >= g.n) continue;
-        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        epilogue_store4(g, m, n, t_base, v);
-      }
-    }
+  bf16_t* lds = reinterpret_cast<bf16_t*>(smem_raw);
+  switch (g.act) {   // one branch per launch, so the activation is inlined without a per-element switch
+    case AC_ACT_GELU_ERF: epilogue_tile<AC_ACT_GELU_ERF, BM, BN, WAVES_M, WAVES_N>(g, acc, lds, m0, n0, wave_m, wave_n, l32, half, tid); break;
+    case AC_ACT_GELU_TANH: epilogue_tile<AC_ACT_GELU_TANH, BM, BN, WAVES_M, WAVES_N>(g, acc, lds, m0, n0, wave_m, wave_n, l32, half, tid); break;
+    case AC_ACT_RELU: epilogue_tile<AC_ACT_RELU, BM, BN, WAVES_M, WAVES_N>(g, acc, lds, m0, n0, wave_m, wave_n, l32, half, tid); break;
+    case AC_ACT_SIGMOID: epilogue_tile<AC_ACT_SIGMOID, BM, BN, WAVES_M, WAVES_N>(g, acc, lds, m0, n0, wave_m, wave_n, l32, half, tid); break;
+    default: epilogue_tile<AC_ACT_NONE, BM, BN, WAVES_M, WAVES_N>(g, acc, lds, m0, n0, wave_m, wave_n, l32, half, tid); break;
   }
 }
 
