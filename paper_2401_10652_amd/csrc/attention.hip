@@ -118,21 +118,23 @@ __global__ void __launch_bounds__(128) attention_rows(AttnArgs a) {
 // ------------------------------------------------------------------------------------
 // bf16 MFMA kernel.
 // ------------------------------------------------------------------------------------
-constexpr int kQB = 128;   // query rows per block (4 waves x 32)
+constexpr int kQB = 128;   // query rows per block of the 4-wave kernel (32 per wave)
 constexpr int kKB = 64;    // keys per LDS tile
 
 // RAGGED: the key count is not a multiple of the tile (or of the 16-byte vector): loads are
 // guarded and keys past the end are masked.  The other instantiation has no bounds work in
 // its main loop.
-template <int DH, bool CAUSAL, bool BIAS, bool RAGGED>
-__global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
+template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
+__global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
+  constexpr int NT = 64 * NW;         // threads
+  constexpr int QB = 32 * NW;         // query rows per block
   constexpr int KROW = DH + 8;        // padded K row (elements): conflict-free 128-bit reads
   constexpr int VROW = kKB + 8;       // padded V^T row
   constexpr int KS = DH / 16;         // k-steps of the score MFMA
   constexpr int DT = DH / 32;         // 32-wide output tiles over d
-  constexpr int K_CHUNKS = kKB * (DH / 8) / 256;   // 16-byte chunks per thread, K tile
-  constexpr int V_CHUNKS = DH * (kKB / 8) / 256;   // and V^T tile
-  static_assert(K_CHUNKS >= 1 && V_CHUNKS >= 1, "tile too small for 256 threads");
+  constexpr int K_CHUNKS = kKB * (DH / 8) / NT;   // 16-byte chunks per thread, K tile
+  constexpr int V_CHUNKS = DH * (kKB / 8) / NT;   // and V^T tile
+  static_assert(K_CHUNKS >= 1 && V_CHUNKS >= 1, "tile too small for the block");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);     // [2][kKB][KROW]
   bf16_t* sV = sK + 2 * kKB * KROW;                      // [2][DH][VROW]
@@ -140,7 +142,7 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int l32 = lane % 32, half = lane / 32;
   const int sq = (int)a.sq, sk = (int)a.sk, q_offset = (int)a.q_offset;
-  const int nqb = (sq + kQB - 1) / kQB;
+  const int nqb = (sq + QB - 1) / QB;
   const int ns = a.n_splits > 1 ? a.n_splits : 1;
   const int64_t t = xcd_contiguous(blockIdx.x, gridDim.x);
   const int split = (int)(t % ns);
@@ -150,7 +152,7 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
   const int64_t b = bh / a.heads;
   const int h = (int)(bh % a.heads);
-  const int q0 = qb * kQB;
+  const int q0 = qb * QB;
 
   const bf16_t* kbase = (const bf16_t*)a.k + b * a.sk_b + h * DH;
   const bf16_t* vbase = (const bf16_t*)a.v + b * a.sv_b + (int64_t)h * DH * a.ldv;
@@ -169,7 +171,7 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
 
   int kv_end = sk;
   if (CAUSAL) {
-    int last = q0 + kQB - 1; if (last > sq - 1) last = sq - 1;
+    int last = q0 + QB - 1; if (last > sq - 1) last = sq - 1;
     if (q_offset + last + 1 < kv_end) kv_end = q_offset + last + 1;
   }
   const int n_tiles_all = (kv_end + kKB - 1) / kKB;
@@ -193,14 +195,14 @@ __global__ void __launch_bounds__(256) attention_mfma_bf16(AttnArgs a) {
   int k_dst[K_CHUNKS], v_dst[V_CHUNKS];
 #pragma unroll
   for (int i = 0; i < K_CHUNKS; ++i) {
-    const int c = tid + 256 * i;
+    const int c = tid + NT * i;
     k_row[i] = c / (DH / 8); k_col[i] = (c % (DH / 8)) * 8;
     k_src[i] = kbase + (int64_t)k_row[i] * a.ldk + k_col[i];
     k_dst[i] = k_row[i] * KROW + k_col[i];
   }
 #pragma unroll
   for (int i = 0; i < V_CHUNKS; ++i) {
-    const int c = tid + 256 * i;
+    const int c = tid + NT * i;
     v_row[i] = c / (kKB / 8);
     const int ch = c % (kKB / 8);
     v_col[i] = ch * 8;
@@ -427,9 +429,9 @@ __global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
   *reinterpret_cast<bf16x4*>((bf16_t*)a.ctx + b * a.sc_b + row * a.ldc + h * a.head_dim + d) = o;
 }
 
-template <int DH, bool CAUSAL, bool BIAS, bool RAGGED>
+template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
-  auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED>;
+  auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED, NW>;
   constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
@@ -438,10 +440,10 @@ static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int64_t nqb = (a.sq + kQB - 1) / kQB;
+  const int64_t nqb = (a.sq + 32 * NW - 1) / (32 * NW);
   const int ns = a.n_splits > 1 ? a.n_splits : 1;
   const int64_t blocks = nqb * a.heads * a.batch * ns;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), lds, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || ns == 1) return e;
   const int64_t items = a.batch * a.sq * a.heads * (DH / 4);
@@ -451,8 +453,13 @@ static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
 
 template <int DH, bool CAUSAL, bool BIAS>
 static hipError_t mfma_attn_ragged(const AttnArgs& a, hipStream_t s) {
-  if (a.sk % kKB != 0) return mfma_attn_launch<DH, CAUSAL, BIAS, true>(a, s);
-  return mfma_attn_launch<DH, CAUSAL, BIAS, false>(a, s);
+  // 64-row blocks (2 waves) when a problem has at most 64 query rows, so that no wave idles
+  if (a.sq <= 64) {
+    if (a.sk % kKB != 0) return mfma_attn_launch<DH, CAUSAL, BIAS, true, 2>(a, s);
+    return mfma_attn_launch<DH, CAUSAL, BIAS, false, 2>(a, s);
+  }
+  if (a.sk % kKB != 0) return mfma_attn_launch<DH, CAUSAL, BIAS, true, 4>(a, s);
+  return mfma_attn_launch<DH, CAUSAL, BIAS, false, 4>(a, s);
 }
 
 template <int DH>

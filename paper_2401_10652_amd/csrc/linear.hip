@@ -135,7 +135,12 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int CROW = BN + 8;   // padded row of the staged tile
   const bool staged = n0 + BN <= g.n_split && g.ldo % 8 == 0 && ((uintptr_t)g.out % 16) == 0 && g.n % 8 == 0;
-  if (staged) __syncthreads();   // every wave is done reading the k-loop buffers
+  // a tile wholly in the strided part whose rows run contiguously (stride 1 along m, one
+  // period) is staged TRANSPOSED, [n][m], and written with 16-byte stores along m
+  constexpr int TROW = BM + 8;
+  const bool tstaged = !staged && n0 >= g.n_split && g.t_s2 == 1 && g.m % 8 == 0 && g.t_s1 % 8 == 0 && g.t_s3 % 8 == 0 &&
+                       ((uintptr_t)g.out_t % 16) == 0 && (g.t_period == INT64_MAX || (g.t_period % BM == 0));
+  if (staged || tstaged) __syncthreads();   // every wave is done reading the k-loop buffers
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int rl = wave_m * WM + i * 32 + l32;
@@ -156,6 +161,9 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
         const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
         if (staged) {
           *reinterpret_cast<bf16x4*>(lds + rl * CROW + cl) = o;
+        } else if (tstaged) {
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) lds[(cl + jj) * TROW + rl] = o[jj];
         } else if (n < g.n_split) {
           *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
         } else {
@@ -165,6 +173,20 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
         }
       }
     }
+  }
+  if (tstaged) {
+    __syncthreads();
+    constexpr int CPT = BM / 8;   // 16-byte chunks per staged row (one output column n)
+    const int64_t t_tile = (m0 / g.t_period) * g.t_s1 + (m0 % g.t_period);   // the tile's rows share a period
+#pragma unroll 4
+    for (int c = tid; c < BN * CPT; c += NT) {
+      const int nl = c / CPT, mm = (c % CPT) * 8;
+      const int64_t n = n0 + nl;
+      if (m0 + mm < g.m && n < g.n)
+        *reinterpret_cast<bf16x8*>((bf16_t*)g.out_t + t_tile + mm + (n - g.n_split) * g.t_s3) =
+            *reinterpret_cast<const bf16x8*>(lds + nl * TROW + mm);
+    }
+    return;
   }
   if (!staged) return;
   __syncthreads();
@@ -351,13 +373,25 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (mfma_eligible(g)) {
     // A CU takes in at most 64 bytes per clock from L2 while its matrix cores retire 4096
     // flops per clock, so a tile needs >= 64 flops per loaded byte just to break even: 128x128
-    // tiles sit exactly there, 256x256 tiles have twice that.  Take the largest tile that
-    // still gives every CU a block; the k order is the same for all of them.
-    auto tiles = [&](int64_t bm, int64_t bn) { return ((g.m + bm - 1) / bm) * ((g.n + bn - 1) / bn) * g.batch; };
-    if (tiles(256, 256) >= 224) return mfma_launch<256, 256, 2, 4>(g, s);
-    if (tiles(256, 128) >= 224) return mfma_launch<256, 128, 4, 2>(g, s);
-    if (tiles(128, 128) >= 192 && g.m >= 128) return mfma_launch<128, 128, 2, 2>(g, s);
-    return mfma_launch<64, 64, 2, 2>(g, s);
+    // tiles sit exactly there, 256x256 tiles have twice that.  Pick the tile with the least
+    // estimated time: tiles per CU (rounded up) x padded tile area / measured efficiency of
+    // that tile shape.  The k order is the same for all of them.
+    struct Cand { int bm, bn; double eff; };
+    static const Cand cands[5] = {{256, 256, 0.40}, {256, 128, 0.33}, {128, 128, 0.30}, {64, 256, 0.24}, {64, 64, 0.15}};
+    int best = 4;
+    double best_t = 0;
+    for (int c = 0; c < 5; ++c) {
+      const int64_t tiles = ((g.m + cands[c].bm - 1) / cands[c].bm) * ((g.n + cands[c].bn - 1) / cands[c].bn) * g.batch;
+      const double t = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn / cands[c].eff;
+      if (c == 0 || t < best_t) { best = c; best_t = t; }
+    }
+    switch (best) {
+      case 0: return mfma_launch<256, 256, 2, 4>(g, s);
+      case 1: return mfma_launch<256, 128, 4, 2>(g, s);
+      case 2: return mfma_launch<128, 128, 2, 2>(g, s);
+      case 3: return mfma_launch<64, 256, 1, 4>(g, s);
+      default: return mfma_launch<64, 64, 2, 2>(g, s);
+    }
   }
   dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)g.batch);
   if (g.dtype == AC_BF16) hipLaunchKernelGGL((linear_fma<bf16_t>), grid, dim3(256), 0, s, g);
