@@ -82,12 +82,55 @@ def cpu_baseline(cfg, x, layers):
     except Exception:
         cores = os.cpu_count()
     t0 = time.perf_counter()
-    O.transformer_stack(x, layers[:1], cfg.heads, cfg.causal, cfg.activation, cfg.ln_eps, cfg.batch,
+    n = min(2, cfg.layers)
+    O.transformer_stack(x, layers[:n], cfg.heads, cfg.causal, cfg.activation, cfg.ln_eps, cfg.batch,
                         query_block=1024)
     dt = time.perf_counter() - t0
-    return {"value": cfg.tokens / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"layer 1 of {cfg.layers} over all {cfg.tokens} tokens in fp64 ({dt:.1f} s), "
-                      f"scaled by 1/{cfg.layers} layers"}
+    return {"value": cfg.tokens * n / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"layers 1-{n} of {cfg.layers} over all {cfg.tokens} tokens in fp64 ({dt:.1f} s), "
+                      f"scaled to {cfg.layers} layers"}
+
+
+KERNEL_SOURCES = {"gemm": ["linear.hip", "common.h"], "trimul": ["linear.hip", "common.h"],
+                  "attention": ["attention.hip", "common.h"], "layernorm": ["rowwise.hip", "common.h"],
+                  "elementwise": ["rowwise.hip", "common.h"]}
+
+
+def source_digest(kernel_class):
+    """sha256 over the sources of a kernel class: counters taken from an older kernel do not count."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES[kernel_class]:
+        with open(os.path.join(ROOT, "paper_2401_10652_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload, kernel_class):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size), or None if there is no
+    summary for this workload and kernel class or the kernel's sources changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    k = rec.get("kernels", {}).get(kernel_class)
+    if not k or k.get("sources_sha256") != source_digest(kernel_class):
+        return None
+    return round((k["fetch_kib_per_launch"] * rec["fetch_scale"] + k["write_kib_per_launch"] * rec["write_scale"]) * 1024)
+
+
+def copy_calibration(B, torch, steps):
+    """A plain copy kernel of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
+    n_rows, n_cols = 32768, 4096   # 256 MiB of bf16 read, 256 MiB written
+    x = torch.zeros((n_rows, n_cols), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(x)
+    for _ in range(steps):
+        B.ac_op_bias_act(x, None, y, B.AC_ACT_NONE)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration": True, "kernel": "bias_act_vec", "launches": steps,
+                      "bytes_read_per_launch": n_rows * n_cols * 2, "bytes_written_per_launch": n_rows * n_cols * 2}))
 
 
 def main():
@@ -100,6 +143,8 @@ def main():
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time a sweep of chunk lengths")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB copy kernel --steps times (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -112,6 +157,9 @@ def main():
 
     B.lib()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        copy_calibration(B, torch, args.steps)
+        return
     cfg = I.CONFIGS[args.config]
     is_pair = isinstance(cfg, I.PairConfig)
     if is_pair:
@@ -161,8 +209,10 @@ def main():
                               "avg_launch_us": round(per * 1e3, 2),
                               "ms_per_step": round(s["total_ms"] / args.steps, 4)}
     dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
+    s_dom = next(s for s in stats if s["name"] == dom)
     roof = dict(classes[dom])
-    roof.update({"kernel": dom, "traffic": None})
+    roof.update({"kernel": dom, "traffic": recorded_traffic(cfg.name, dom),
+                 "algorithmic_per_launch": round((s_dom["flops"] if roof["bound"] == "mfma" else s_dom["bytes"]) / s_dom["launches"])})
 
     out = {
         "metric": "tokens/s at fixed activation budget",

@@ -11,42 +11,53 @@ namespace ac {
 // vectors per lane): mean, then the centred second moment, then the affine output.
 // cols == G * NV * kVec exactly; other widths take the generic kernel below.
 // ------------------------------------------------------------------------------------
-template <typename T, int G, int NV>
+template <typename T, int G, int NV, int RPG>
 __global__ void __launch_bounds__(256)
 layernorm_rows(const T* __restrict__ x, int64_t ldx, const T* __restrict__ gain,
                const T* __restrict__ shift, T* __restrict__ y, int64_t ldy, int64_t rows, float eps) {
+  // RPG rows per group at once: their loads are all issued before the first reduction, so
+  // a thread has RPG * NV 16-byte loads in flight (one row of 128 columns alone is too little
+  // to cover HBM latency).
   constexpr int V = Elem<T>::kVec;
   constexpr int COLS = G * NV * V;
-  constexpr int ROWS_PER_BLOCK = 256 / G;
+  constexpr int ROWS_PER_BLOCK = 256 / G * RPG;
   const int lane_in_group = threadIdx.x % G;
-  const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
-  const bool live = row < rows;
-  const int64_t r = live ? row : rows - 1;   // dead groups shadow the last row, store nothing
-  float v[NV][V];
-  float sum = 0.f;
+  const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x / G) * RPG;
+  float v[RPG][NV][V];
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    load_vec(x + r * ldx + (i * G + lane_in_group) * V, v[i]);
+  for (int r = 0; r < RPG; ++r) {
+    const int64_t rr = row0 + r < rows ? row0 + r : rows - 1;   // dead rows shadow the last row, store nothing
 #pragma unroll
-    for (int j = 0; j < V; ++j) sum += v[i][j];
+    for (int i = 0; i < NV; ++i) load_vec(x + rr * ldx + (i * G + lane_in_group) * V, v[r][i]);
   }
-  const float mean = group_sum<G>(sum) * (1.0f / COLS);
-  float sq = 0.f;
-#pragma unroll
-  for (int i = 0; i < NV; ++i)
-#pragma unroll
-    for (int j = 0; j < V; ++j) { float d = v[i][j] - mean; sq += d * d; }
-  const float rstd = rsqrtf(group_sum<G>(sq) * (1.0f / COLS) + eps);
-  if (!live) return;
+  float g[NV][V], b[NV][V];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = (i * G + lane_in_group) * V;
-    float g[V], b[V], o[V];
-    load_vec(gain + c, g);
-    load_vec(shift + c, b);
+    load_vec(gain + (i * G + lane_in_group) * V, g[i]);
+    load_vec(shift + (i * G + lane_in_group) * V, b[i]);
+  }
 #pragma unroll
-    for (int j = 0; j < V; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
-    store_vec(y + row * ldy + c, o);
+  for (int r = 0; r < RPG; ++r) {
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int j = 0; j < V; ++j) sum += v[r][i][j];
+    const float mean = group_sum<G>(sum) * (1.0f / COLS);
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int j = 0; j < V; ++j) { float d = v[r][i][j] - mean; sq += d * d; }
+    const float rstd = rsqrtf(group_sum<G>(sq) * (1.0f / COLS) + eps);
+    if (row0 + r >= rows) continue;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      float o[V];
+#pragma unroll
+      for (int j = 0; j < V; ++j) o[j] = (v[r][i][j] - mean) * rstd * g[i][j] + b[i][j];
+      store_vec(y + (row0 + r) * ldy + (i * G + lane_in_group) * V, o);
+    }
   }
 }
 
@@ -74,9 +85,10 @@ layernorm_rows_generic(const T* __restrict__ x, int64_t ldx, const T* __restrict
 template <typename T, int G, int NV>
 static hipError_t ln_launch(const void* x, int64_t ldx, const void* g, const void* b, void* y, int64_t ldy,
                             int64_t rows, float eps, hipStream_t s) {
-  const int rpb = 256 / G;
+  constexpr int RPG = NV >= 4 ? 1 : (NV >= 2 ? 2 : 4);   // about four vector loads in flight per thread
+  const int rpb = 256 / G * RPG;
   dim3 grid((unsigned)((rows + rpb - 1) / rpb));
-  hipLaunchKernelGGL((layernorm_rows<T, G, NV>), grid, dim3(256), 0, s, (const T*)x, ldx, (const T*)g,
+  hipLaunchKernelGGL((layernorm_rows<T, G, NV, RPG>), grid, dim3(256), 0, s, (const T*)x, ldx, (const T*)g,
                      (const T*)b, (T*)y, ldy, rows, eps);
   return hipGetLastError();
 }
