@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--chunk", type=int, nargs=3, default=None, metavar=("QKV", "ATTN", "FFN"),
                     help="rows per segment for the three regions (default: the workload's plan)")
+    ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
+                    help="segments of a region in flight at once (2: two streams, two per-segment workspaces)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time a sweep of chunk lengths")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -165,13 +167,13 @@ def main():
     if is_pair:
         x, layers = I.pair_inputs(cfg)
         dw = [B.to_device(layers[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
-        desc = B.pair_desc(cfg)
+        desc = B.pair_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0)
         regs, budget = pair_regions(B, args.chunk[0] if args.chunk else cfg.chunk_len), 0
         regs1 = pair_regions(B, cfg.n_res)
     else:
         x, layers = I.transformer_inputs(cfg)
         dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
-        desc = B.transformer_desc(cfg)
+        desc = B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0)
         if args.chunk:
             regs, budget = plan_regions(B, *args.chunk), 0
         elif cfg.chunk_len:
@@ -221,7 +223,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": dict(
-            {"workload": cfg.name, "act_budget_bytes": budget,
+            {"workload": cfg.name, "act_budget_bytes": budget, "segments_in_flight": args.in_flight,
              "chunk_len": [info.regions[i].chunk_len for i in range(info.n_regions)],
              "n_segments": [info.regions[i].n_segments for i in range(info.n_regions)]},
             **({"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
@@ -241,6 +243,21 @@ def main():
             "ratio_vs_unchunked_measured": round(peak / peak1, 4),
         },
     }
+    if args.in_flight == 1:
+        # the same plan with two segments of a region in flight on two streams (an executor option
+        # on top of the strictly sequential schedule timed above)
+        import copy
+        desc2 = copy.copy(desc)
+        desc2.flags = desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT
+        plan2 = B.Plan(desc2, regs, budget)
+        info2 = plan2.ac_plan_query()
+        plan2.ac_plan_bind_weights(dw)
+        ws2 = B.empty_workspace(info2.workspace_bytes)
+        sec2, peak2 = time_plan(B, torch, plan2, dx, y, ws2, args.steps, args.warmup)
+        out["two_segments_in_flight"] = {"tokens_per_s": round(tokens / sec2, 1), "ms_per_step": round(sec2 * 1e3, 4),
+                                         "throughput_loss": round(1.0 - sec1 / sec2, 4), "peak_bytes_measured": peak2}
+        plan2.close()
+        del ws2
     if args.sweep:
         sweep = []
         c = cfg.n_res if is_pair else cfg.seq

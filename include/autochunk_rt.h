@@ -81,6 +81,10 @@ enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 }
 enum {
   AC_FLAG_UNFUSED_ELEMENTWISE = 1, /* run bias+activation and residual as standalone passes
                                       instead of GEMM epilogues (for measuring those passes) */
+  AC_FLAG_TWO_SEGMENTS_IN_FLIGHT = 4, /* segments of a region alternate between the caller's stream and a
+                                      second stream owned by the plan, each with its own per-segment
+                                      workspace (the plan's bytes account for both); all work is joined
+                                      back into the caller's stream at the end of every region */
   AC_FLAG_LISTED_REGIONS_ONLY = 2  /* pair stack only: the block consists of just the region kinds
                                       listed in ac_plan_create (each maps z to z), in canonical
                                       order; weights of the others are still bound but unused */

@@ -24,6 +24,7 @@ AC_DIM_BATCH, AC_DIM_SEQ, AC_DIM_FEATURE, AC_DIM_HEAD_DIM, AC_DIM_KEY = range(5)
 AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
 AC_FLAG_UNFUSED_ELEMENTWISE = 1
 AC_FLAG_LISTED_REGIONS_ONLY = 2
+AC_FLAG_TWO_SEGMENTS_IN_FLIGHT = 4
 
 ACTIVATIONS = {"none": AC_ACT_NONE, "gelu_erf": AC_ACT_GELU_ERF, "gelu_tanh": AC_ACT_GELU_TANH,
                "relu": AC_ACT_RELU, "sigmoid": AC_ACT_SIGMOID}

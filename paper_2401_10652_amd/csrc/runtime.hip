@@ -88,6 +88,10 @@ struct ac_plan {
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> pool;
   size_t pool_used = 0;
+  // second lane (AC_FLAG_TWO_SEGMENTS_IN_FLIGHT): a stream of default priority and untimed events
+  hipStream_t aux_stream = nullptr;
+  std::vector<hipEvent_t> sync_pool;
+  size_t sync_used = 0;
 };
 
 namespace ac {
@@ -99,11 +103,71 @@ struct Walk {
   ac_plan* p;
   bool dry;
   bool unchunked;          // planning variant: one segment per region
-  hipStream_t stream;
+  hipStream_t stream;      // the stream the next kernel goes to (the caller's, or the second lane's)
   Arena arena;
   double flops = 0;
   hipError_t err = hipSuccess;
   const char* err_where = "";
+  // Two segments in flight (AC_FLAG_TWO_SEGMENTS_IN_FLIGHT): segments of a region alternate
+  // between the caller's stream and a second stream of the plan, each lane with its own
+  // per-segment workspace; the lanes are joined at the end of every segment loop.
+  int lanes = 1;
+  hipStream_t lane_stream[2] = {nullptr, nullptr};
+  bool measuring = false;  // sizing pass of a segment loop: pushes only, no launches, no counts
+
+  void fork() {
+    if (dry || lanes != 2 || !ok()) return;
+    hipEvent_t e = next_sync_event();
+    if (!e) return;
+    if (hipEventRecord(e, lane_stream[0]) != hipSuccess || hipStreamWaitEvent(lane_stream[1], e, 0) != hipSuccess) {
+      err = hipGetLastError(); err_where = "fork";
+    }
+  }
+  void join() {
+    stream = lane_stream[0];
+    if (dry || lanes != 2 || !ok()) return;
+    hipEvent_t e = next_sync_event();
+    if (!e) return;
+    if (hipEventRecord(e, lane_stream[1]) != hipSuccess || hipStreamWaitEvent(lane_stream[0], e, 0) != hipSuccess) {
+      err = hipGetLastError(); err_where = "join";
+    }
+  }
+  hipEvent_t next_sync_event();
+
+  // Runs body(segment) for every segment of a region.  One lane: each segment's pushes start at
+  // the same arena offset.  Two lanes: a sizing pass finds the largest segment's extent
+  // (transient pushes included), lane 1 works that far above lane 0, segments alternate.
+  template <typename S, typename F>
+  void seg_loop(const std::vector<S>& segs, F&& body) {
+    const uint64_t base = arena.mark();
+    uint64_t extent = 0;
+    if (lanes == 2 && segs.size() > 1) {
+      const bool was = measuring;
+      const uint64_t high0 = arena.high;
+      measuring = true;
+      for (const S& sg : segs) {
+        arena.release(base);
+        arena.high = base;
+        body(sg);
+        extent = std::max(extent, arena.high - base);
+      }
+      arena.high = high0;
+      measuring = was;
+      extent = align_up(extent, 256);
+    }
+    const bool two = lanes == 2 && segs.size() > 1 && !measuring;
+    if (two) fork();
+    int i = 0;
+    for (const S& sg : segs) {
+      const int lane = two ? (i & 1) : 0;
+      arena.release(base + (uint64_t)lane * extent);
+      if (two) stream = lane_stream[lane];
+      body(sg);
+      ++i;
+    }
+    if (two) join();
+    arena.release(base);
+  }
 
   int eb() const { return elem_bytes(p->m.dtype); }
   const void* w(int layer, int slot, int per_layer) const {
@@ -114,6 +178,7 @@ struct Walk {
 
   template <typename F>
   void run(int cls, double fl, double by, const char* where, F&& launch) {
+    if (measuring) return;
     flops += fl;
     if (dry || !ok()) return;
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -250,6 +315,18 @@ struct Walk {
   void transition(const void* const* W, const void* zin, void* zout);
 };
 
+hipEvent_t Walk::next_sync_event() {
+  if (p->sync_used == p->sync_pool.size()) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      err = hipGetLastError(); err_where = "hipEventCreate";
+      return nullptr;
+    }
+    p->sync_pool.push_back(e);
+  }
+  return p->sync_pool[p->sync_used++];
+}
+
 static const char* const kLayerTensor[12] = {"ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                                              "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2"};
 enum { W_LN1G, W_LN1B, W_QKV, W_BQKV, W_O, W_BO, W_LN2G, W_LN2B, W_1, W_B1, W_2, W_B2 };
@@ -290,9 +367,8 @@ void Walk::transformer(const void* x, void* y) {
     auto W = [&](int slot) { return w(l, slot, 12); };
 
     // ---- region 1: LayerNorm 1 + packed projection, writes whole q, k, v
-    for (const Seg& sg : token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV))) {
+    seg_loop(token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      const uint64_t mk = arena.mark();
       void* u = arena.push((uint64_t)rows * d * e);
       ln(at(in, r0 * d), d, W(W_LN1G), W(W_LN1B), u, d, rows, d);
       LinearArgs g{};
@@ -311,13 +387,11 @@ void Walk::transformer(const void* x, void* y) {
         linear(g);
         bias_act(g.out, ldqk, W(W_BQKV), g.out, ldqk, rows, 3 * d, AC_ACT_NONE);
       }
-      arena.release(mk);
-    }
+    });
 
     // ---- region 2: attention of a query segment over whole k, v; output projection; residual
-    for (const Seg& sg : token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION))) {
+    seg_loop(token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      const uint64_t mk = arena.mark();
       void* ctx = arena.push((uint64_t)rows * d * e);
       AttnArgs a{};
       a.q = at(qk, r0 * ldqk); a.ldq = ldqk; a.sq_b = S * ldqk;
@@ -329,20 +403,17 @@ void Walk::transformer(const void* x, void* y) {
       a.causal = m.causal; a.q_offset = sg.s0;
       attention(a);
       proj(ctx, d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
-      arena.release(mk);
-    }
+    });
 
     // ---- region 3: LayerNorm 2 + feed-forward + residual
-    for (const Seg& sg : token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN))) {
+    seg_loop(token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      const uint64_t mk = arena.mark();
       void* u = arena.push((uint64_t)rows * d * e);
       void* hid = arena.push((uint64_t)rows * F * e);
       ln(at(hbuf, r0 * d), d, W(W_LN2G), W(W_LN2B), u, d, rows, d);
       proj(u, d, W(W_1), d, W(W_B1), m.activation, nullptr, 0, hid, F, rows, F);
       proj(hid, F, W(W_2), F, W(W_B2), AC_ACT_NONE, at(hbuf, r0 * d), d, atw(out, r0 * d), d, rows, d);
-      arena.release(mk);
-    }
+    });
   }
 }
 
@@ -383,9 +454,8 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   // ---- whole operands: a and b of every position, channel-major.  Row r = (i, k) of z lands
   // at [c][r]; for the incoming form r = (k, i), and the per-channel matrices are transposed
   // in place afterwards.
-  for (const RowSeg& sg : segs) {
+  seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    const uint64_t mk = arena.mark();
     void* t = arena.push((uint64_t)rows * cz * e);
     void* gate = arena.push((uint64_t)rows * ch * e);
     ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
@@ -400,16 +470,14 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
       v.out_t = atw(which ? b_t : a_t, r0); v.n_split = 0; v.t_period = 0; v.t_s2 = 1; v.t_s3 = R;
       linear(v);
     }
-    arena.release(mk);
-  }
+  });
   if (incoming) {
     transpose_inplace(a_t, N, R, N, ch);
     transpose_inplace(b_t, N, R, N, ch);
   }
   // ---- chunked part: rows i of the output
-  for (const RowSeg& sg : segs) {
+  seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    const uint64_t mk = arena.mark();
     void* t = arena.push((uint64_t)rows * cz * e);
     void* gate = arena.push((uint64_t)rows * cz * e);
     void* o_c = arena.push((uint64_t)ch * rows * e);   // [c][i][j]
@@ -426,8 +494,7 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
     o.resid = at(zin, r0 * cz); o.ldr = cz; o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = ch;
     o.n_split = cz;
     linear(o);
-    arena.release(mk);
-  }
+  });
   arena.release(mk0);
 }
 
@@ -446,9 +513,8 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   void* bias = arena.push((uint64_t)H * R * e);
   void* k_all = ending ? arena.push((uint64_t)R * hd * e) : nullptr;
   void* v_all = ending ? arena.push((uint64_t)hd * R * e) : nullptr;
-  for (const RowSeg& sg : segs) {
+  seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    const uint64_t mk = arena.mark();
     void* t = arena.push((uint64_t)rows * cz * e);
     ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
     LinearArgs b{};
@@ -465,16 +531,14 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
       vv.out_t = atw(v_all, r0); vv.n_split = 0; vv.t_s2 = 1; vv.t_s3 = R;
       linear(vv);
     }
-    arena.release(mk);
-  }
+  });
   if (ending) {
     transpose_inplace(bias, N, R, N, H);
     transpose_inplace(v_all, N, R, N, hd);
   }
   // ---- chunked part
-  for (const RowSeg& sg : segs) {
+  seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    const uint64_t mk = arena.mark();
     void* t = arena.push((uint64_t)rows * cz * e);
     void* q = arena.push((uint64_t)rows * hd * e);
     void* gate = arena.push((uint64_t)rows * hd * e);
@@ -519,8 +583,7 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
     o.a = ctx; o.lda = hd; o.w = W[TA_W_O]; o.ldw = hd; o.bias = W[TA_B_O]; o.resid = at(zin, r0 * cz); o.ldr = cz;
     o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = hd; o.n_split = cz;
     linear(o);
-    arena.release(mk);
-  }
+  });
   arena.release(mk0);
 }
 
@@ -530,16 +593,14 @@ void Walk::transition(const void* const* W, const void* zin, void* zout) {
   const int e = eb();
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
-  for (const RowSeg& sg : row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION))) {
+  seg_loop(row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION)), [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    const uint64_t mk = arena.mark();
     void* u = arena.push((uint64_t)rows * cz * e);
     void* hid = arena.push((uint64_t)rows * F * e);
     ln(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
     proj(u, cz, W[PT_W_1], cz, W[PT_B_1], m.activation, nullptr, 0, hid, F, rows, F);
     proj(hid, F, W[PT_W_2], F, W[PT_B_2], AC_ACT_NONE, at(zin, r0 * cz), cz, atw(zout, r0 * cz), cz, rows, cz);
-    arena.release(mk);
-  }
+  });
 }
 
 void Walk::pair(const void* x, void* y) {
@@ -629,6 +690,7 @@ static bool dim_legal(const ac_model_desc& m, int dim, bool& known) {
 
 static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& flops) {
   Walk wk{p, true, unchunked, nullptr};
+  wk.lanes = (p->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) ? 2 : 1;
   if (p->m.workload == AC_TRANSFORMER_STACK) wk.transformer(nullptr, nullptr);
   else wk.pair(nullptr, nullptr);
   arena_bytes = wk.arena.high;
@@ -923,6 +985,14 @@ int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_de
   if (xb < yb + half && yb < xb + half) return fail(AC_ERR_ARG, "x and y overlap");
   Walk wk{plan, false, false, (hipStream_t)stream};
   wk.arena.base = (uint8_t*)workspace_dev;
+  wk.lane_stream[0] = (hipStream_t)stream;
+  if (plan->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) {
+    if (!plan->aux_stream && hipStreamCreateWithFlags(&plan->aux_stream, hipStreamNonBlocking) != hipSuccess)
+      return fail(AC_ERR_HIP, "hipStreamCreate: %s", hipGetErrorString(hipGetLastError()));
+    wk.lanes = 2;
+    wk.lane_stream[1] = plan->aux_stream;
+    plan->sync_used = 0;
+  }
   if (plan->m.workload == AC_TRANSFORMER_STACK) wk.transformer(x_dev, y_dev);
   else wk.pair(x_dev, y_dev);
   if (measured_peak_bytes) *measured_peak_bytes = plan->info.io_bytes + wk.arena.high;
@@ -933,6 +1003,8 @@ int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_de
 void ac_plan_destroy(ac_plan* plan) {
   if (!plan) return;
   for (hipEvent_t e : plan->pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : plan->sync_pool) (void)hipEventDestroy(e);
+  if (plan->aux_stream) (void)hipStreamDestroy(plan->aux_stream);
   delete plan;
 }
 

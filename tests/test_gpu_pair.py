@@ -58,14 +58,14 @@ def test_layernorm_channel_major(B, dtype, ch, pos):
     assert rel_err(host(dst), O.layer_norm(x.T, g, b)) <= TOL[dtype]
 
 
-def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1):
+def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, flags=0):
     import torch
     z, w = I.pair_inputs(cfg, bias_std=bias_std, ln_jitter=ln_jitter)
     names = [n for n, _ in I.pair_tensor_shapes(cfg)]
     dz = B.to_device(z, cfg.dtype)
     dw = [B.to_device(w[n], cfg.dtype) for n in names]
     regs = [(k, B.AC_DIM_ROW, c) for k, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), chunk)]
-    p = B.Plan(B.pair_desc(cfg), regs)
+    p = B.Plan(B.pair_desc(cfg, flags=flags), regs)
     info = p.ac_plan_query()
     assert p.weight_names() == names
     p.ac_plan_bind_weights(dw)
@@ -113,3 +113,11 @@ def test_pair_legality(B):
     with pytest.raises(B.AcError) as ei:
         B.Plan(d, [(B.AC_REGION_FFN, 0, 64)])
     assert ei.value.status == B.AC_ERR_ARG
+
+
+def test_pair_two_segments_in_flight(B):
+    import torch
+    cfg = I.PairConfig("tp2", 42, 192, 64, 64, 2, 32, 4, "bf16")
+    z, w, y1, i1 = run_pair(B, cfg, (24, 8, 64, 40, 16))
+    _, _, y2, i2 = run_pair(B, cfg, (24, 8, 64, 40, 16), flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
+    assert torch.equal(y1, y2) and i2.workspace_bytes > i1.workspace_bytes

@@ -154,3 +154,34 @@ def test_profiling_reports_kernel_classes(B):
     p.ac_execute(r.dx, y2, ws)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+def test_two_segments_in_flight_equals_sequential(B):
+    """Segments alternate between two streams with separate per-segment workspaces: same bits,
+    larger planned (and measured) workspace, nothing outside it touched."""
+    import torch
+    cfg = I.TransformerConfig("t2s", 37, 3, 1152, 256, 4, 1024, True, "bf16", 0.05)
+    r = Runner(B, cfg, bias_std=0.05, ln_jitter=0.1)
+    ref = r.oracle()
+    for c in ((128, 128, 128), (256, 384, 1152), (200, 136, 72)):
+        y1, i1 = r.run(regions(B, *c))
+        y2, i2 = r.run(regions(B, *c), flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
+        assert torch.equal(y1, y2), c
+        assert i2.workspace_bytes >= i1.workspace_bytes
+        assert rel_err(host(y2), ref) <= TOL["bf16"]
+    # repeated executes of one plan reuse its second stream and events
+    p = B.Plan(B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(B, 128, 128, 128))
+    p.ac_plan_bind_weights(r.dw)
+    ws = B.empty_workspace(p.ac_plan_query().workspace_bytes)
+    outs = []
+    for _ in range(3):
+        y = torch.full_like(r.dx, float("nan"))
+        p.ac_execute(r.dx, y, ws)
+        outs.append(y)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    cfg32 = I.TransformerConfig("t2s32", 38, 1, 200, 64, 4, 160, False, "f32", None)
+    r32 = Runner(B, cfg32, bias_std=0.2)
+    ya, _ = r32.run(regions(B, 33, 77, 50))
+    yb, _ = r32.run(regions(B, 33, 77, 50), flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
+    assert torch.equal(ya, yb)

@@ -45,7 +45,7 @@ def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
     return max(1, min(-(-768 // blocks), sk // 512, 16))
 
 
-def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False):
+def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1):
     """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], h (Td), inter-layer t (Td if
     layers > 1), plus the largest per-segment set: u (c d) | ctx (c d) + fp32 split partials
     (ns c H (d_h + 2) floats) | u (c d) + hidden (c F)."""
@@ -60,7 +60,9 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False):
     parts = (al(ns * c_attn * d * 4) + al(ns * c_attn * cfg.heads * 8)) if ns > 1 else 0
     r2 = al(c_attn * d * e) + max(parts, al(c_attn * d * e) if unfused else 0)
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
-    return whole + max(r1, r2, r3)
+    # two segments in flight: a region with more than one segment holds two per-segment sets
+    mult = lambda c: lanes if c < cfg.seq else 1
+    return whole + max(r1 * mult(c_qkv), r2 * mult(c_attn), r3 * mult(c_ffn))
 
 
 @pytest.mark.parametrize("cfg,c", [(I.C1, (64, 64, 64)), (I.C3, (512, 512, 512)), (I.C2, (1024, 1024, 1024)),
@@ -97,6 +99,12 @@ def test_key_split_rule():
     assert B.ac_attention_key_splits(512, 4096, 12, 1, 64, "bf16") == 8
     assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 3) == 3 * 2 * 100 * 4 * (64 + 2) * 4
     assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 1) == 0
+
+
+def test_two_segments_in_flight_doubles_the_per_segment_sets():
+    for cfg, c in ((I.C3, (512, 512, 512)), (I.C2, (8192, 1792, 8192)), (I.C2, (1024, 1024, 1024))):
+        p = B.Plan(B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(*c))
+        assert p.ac_plan_query().workspace_bytes == arena_by_hand(cfg, *c, lanes=2)
 
 
 def test_unfused_flag_adds_the_temporaries():
