@@ -265,6 +265,8 @@ def main():
             ps = B.Plan(desc, pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
             ps.ac_plan_bind_weights(dw)
             inf = ps.ac_plan_query()
+            if inf.workspace_bytes > ws.numel():
+                ws = B.empty_workspace(inf.workspace_bytes)
             s_, pk_ = time_plan(B, torch, ps, dx, y, ws, max(3, args.steps // 2), 1)
             sweep.append({"chunk_len": c, "tokens_per_s": round(tokens / s_, 1), "peak_bytes": pk_,
                           "paper_model_bytes": inf.peak_bytes_model})
