@@ -23,8 +23,11 @@ if ROOT not in sys.path:
 PEAK = {"mfma_bf16": 2.5e15, "hbm": 8.0e12, "fp32_vector": 157.3e12}
 
 
-def plan_regions(B, c_qkv, c_attn, c_ffn):
+def plan_regions(B, c_qkv, c_attn, c_ffn, c_out=None):
+    """The four regions of a transformer layer; the output projection follows the attention's
+    chunk length unless one is given."""
     return [(B.AC_REGION_QKV, B.AC_DIM_SEQ, c_qkv), (B.AC_REGION_ATTENTION, B.AC_DIM_SEQ, c_attn),
+            (B.AC_REGION_OUT_PROJ, B.AC_DIM_SEQ, c_attn if c_out is None else c_out),
             (B.AC_REGION_FFN, B.AC_DIM_SEQ, c_ffn)]
 
 
@@ -179,7 +182,7 @@ def main():
         elif cfg.chunk_len:
             regs, budget = plan_regions(B, cfg.chunk_len, cfg.chunk_len, cfg.chunk_len), 0
         else:
-            regs, budget = plan_regions(B, 0, 0, 0), cfg.act_budget
+            regs, budget = plan_regions(B, 0, 0, 0, 0), cfg.act_budget
         regs1 = plan_regions(B, cfg.seq, cfg.seq, cfg.seq)
     dx = B.to_device(x, cfg.dtype)
     y = torch.empty_like(dx)

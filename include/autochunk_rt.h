@@ -53,19 +53,22 @@ typedef enum ac_dtype { AC_F32 = 0, AC_BF16 = 1 } ac_dtype;
 typedef enum ac_activation { AC_ACT_NONE = 0, AC_ACT_GELU_ERF = 1, AC_ACT_GELU_TANH = 2,
                              AC_ACT_RELU = 3, AC_ACT_SIGMOID = 4 } ac_activation;
 
-/* Region kinds.  Transformer layer: QKV, ATTENTION, FFN in this order.  Pair-stack block:
- * TRIMUL_OUT, TRIMUL_IN, TRIATT_START, TRIATT_END, PAIR_TRANSITION in this order. */
+/* Region kinds.  Transformer layer: QKV, ATTENTION, OUT_PROJ, FFN in this order.  Pair-stack
+ * block: TRIMUL_OUT, TRIMUL_IN, TRIATT_START, TRIATT_END, PAIR_TRANSITION in this order.
+ * The attention core is a region of its own (section 3.4: a chunk region should hold few
+ * nodes beyond the peak node), so the projection after it need not be cut as finely. */
 typedef enum ac_region_kind {
   AC_REGION_QKV = 0,            /* LayerNorm 1 + packed query/key/value projection        */
-  AC_REGION_ATTENTION = 1,      /* attention of a query segment over whole keys/values +
-                                   output projection + residual                           */
-  AC_REGION_FFN = 2,            /* LayerNorm 2 + up projection + activation + down + residual */
-  AC_REGION_TRIMUL_OUT = 3,     /* triangle multiplicative update, outgoing edges         */
-  AC_REGION_TRIMUL_IN = 4,      /* triangle multiplicative update, incoming edges         */
-  AC_REGION_TRIATT_START = 5,   /* triangle self-attention around the starting node       */
-  AC_REGION_TRIATT_END = 6,     /* triangle self-attention around the ending node         */
-  AC_REGION_PAIR_TRANSITION = 7,
-  AC_REGION_KINDS = 8
+  AC_REGION_ATTENTION = 1,      /* attention of a query segment over whole keys/values;
+                                   writes its rows of the whole context tensor            */
+  AC_REGION_OUT_PROJ = 2,       /* output projection of the context + residual            */
+  AC_REGION_FFN = 3,            /* LayerNorm 2 + up projection + activation + down + residual */
+  AC_REGION_TRIMUL_OUT = 4,     /* triangle multiplicative update, outgoing edges         */
+  AC_REGION_TRIMUL_IN = 5,      /* triangle multiplicative update, incoming edges         */
+  AC_REGION_TRIATT_START = 6,   /* triangle self-attention around the starting node       */
+  AC_REGION_TRIATT_END = 7,     /* triangle self-attention around the ending node         */
+  AC_REGION_PAIR_TRANSITION = 8,
+  AC_REGION_KINDS = 9
 } ac_region_kind;
 
 /* Chunk dimensions are named per workload.  Transformer regions see their tensors as

@@ -13,6 +13,7 @@ when the length does not divide), n = ceil(D / c):
 
   qkv projection   X = x[S,d]               A = u[S,d]                      Y = qkv[S,3d]
   attention core   X = x[S,d] + qkv[S,3d]   A = scores[H,S,S] + probs[H,S,S] Y = ctx[S,d]
+  output proj.     X = x[S,d] + ctx[S,d]    A = o[S,d] (before the residual) Y = h[S,d]
   feed-forward     X = h[S,d]               A = u[S,d] + t[S,F] + act[S,F]  Y = y[S,d]
   tri-mul          X = z + a,b[N,N,ch]*2    A = t + g + o[N,N,ch] + LN(o)    Y = z'
   tri-attention    X = z + k,v[N,N,H*dh]*2 + bias[H,N,N]
@@ -48,15 +49,21 @@ def attention_region(seq, d, heads, b, chunk_len=0):
     return x + qkv + ctx + a
 
 
+def out_proj_region(seq, d, b, chunk_len=0):
+    c = _rows(seq, chunk_len)
+    return 3 * seq * d * b + c * d * b
+
+
 def ffn_region(seq, d, f, b, chunk_len=0):
     c = _rows(seq, chunk_len)
     return 2 * seq * d * b + c * d * b + 2 * c * f * b
 
 
-def transformer_layer_peak(seq, d, heads, f, b, c_qkv=0, c_attn=0, c_ffn=0):
+def transformer_layer_peak(seq, d, heads, f, b, c_qkv=0, c_attn=0, c_ffn=0, c_out=0):
     """Regions run one after another, so a layer's peak is the largest region sum."""
     return max(qkv_region(seq, d, b, c_qkv),
                attention_region(seq, d, heads, b, c_attn),
+               out_proj_region(seq, d, b, c_out),
                ffn_region(seq, d, f, b, c_ffn))
 
 

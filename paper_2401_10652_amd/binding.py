@@ -18,8 +18,9 @@ AC_ERR_ALIGN, AC_ERR_HIP, AC_ERR_STATE, AC_ERR_UNSUPPORTED = -5, -6, -7, -8
 AC_TRANSFORMER_STACK, AC_PAIR_STACK = 0, 1
 AC_F32, AC_BF16 = 0, 1
 AC_ACT_NONE, AC_ACT_GELU_ERF, AC_ACT_GELU_TANH, AC_ACT_RELU, AC_ACT_SIGMOID = 0, 1, 2, 3, 4
-(AC_REGION_QKV, AC_REGION_ATTENTION, AC_REGION_FFN, AC_REGION_TRIMUL_OUT, AC_REGION_TRIMUL_IN,
- AC_REGION_TRIATT_START, AC_REGION_TRIATT_END, AC_REGION_PAIR_TRANSITION, AC_REGION_KINDS) = range(9)
+(AC_REGION_QKV, AC_REGION_ATTENTION, AC_REGION_OUT_PROJ, AC_REGION_FFN, AC_REGION_TRIMUL_OUT,
+ AC_REGION_TRIMUL_IN, AC_REGION_TRIATT_START, AC_REGION_TRIATT_END, AC_REGION_PAIR_TRANSITION,
+ AC_REGION_KINDS) = range(10)
 AC_DIM_BATCH, AC_DIM_SEQ, AC_DIM_FEATURE, AC_DIM_HEAD_DIM, AC_DIM_KEY = range(5)
 AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
 AC_FLAG_UNFUSED_ELEMENTWISE = 1

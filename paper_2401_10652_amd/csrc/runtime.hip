@@ -358,6 +358,7 @@ void Walk::transformer(const void* x, void* y) {
   void* qk = arena.push((uint64_t)T * (bf ? 2 : 3) * d * e);
   void* vt = bf ? arena.push((uint64_t)T * d * e) : nullptr;
   const int64_t ldqk = (bf ? 2 : 3) * d;
+  void* ctx_all = arena.push((uint64_t)T * d * e);   // whole context: output of the attention region
   void* hbuf = arena.push((uint64_t)T * d * e);
   void* tbuf = m.layers > 1 ? arena.push((uint64_t)T * d * e) : nullptr;
 
@@ -389,20 +390,24 @@ void Walk::transformer(const void* x, void* y) {
       }
     });
 
-    // ---- region 2: attention of a query segment over whole k, v; output projection; residual
+    // ---- region 2: attention of a query segment over whole k, v; writes its rows of the context
     seg_loop(token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION)), [&](const Seg& sg) {
-      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      void* ctx = arena.push((uint64_t)rows * d * e);
+      const int64_t r0 = sg.b0 * S + sg.s0;
       AttnArgs a{};
       a.q = at(qk, r0 * ldqk); a.ldq = ldqk; a.sq_b = S * ldqk;
       a.k = at(qk, sg.b0 * S * ldqk + d); a.ldk = ldqk; a.sk_b = S * ldqk;
       if (bf) { a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1; }
       else { a.v = at(qk, sg.b0 * S * ldqk + 2 * d); a.ldv = ldqk; a.sv_b = S * ldqk; a.v_transposed = 0; }
-      a.ctx = ctx; a.ldc = d; a.sc_b = sg.ns * d;
+      a.ctx = atw(ctx_all, r0 * d); a.ldc = d; a.sc_b = S * d;
       a.batch = sg.nb; a.sq = sg.ns; a.sk = S; a.heads = m.heads; a.head_dim = m.head_dim;
       a.causal = m.causal; a.q_offset = sg.s0;
       attention(a);
-      proj(ctx, d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
+    });
+
+    // ---- region 2b: output projection + residual
+    seg_loop(token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ)), [&](const Seg& sg) {
+      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
+      proj(at(ctx_all, r0 * d), d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
     });
 
     // ---- region 3: LayerNorm 2 + feed-forward + residual
@@ -643,6 +648,7 @@ static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
     switch (kind) {
       case AC_REGION_QKV: return T * d * b + 3 * T * d * b + (uint64_t)c * d * b;
       case AC_REGION_ATTENTION: return T * d * b + 3 * T * d * b + T * d * b + 2 * H * (uint64_t)c * S * b;
+      case AC_REGION_OUT_PROJ: return 3 * T * d * b + (uint64_t)c * d * b;   // x, ctx, h whole; projection before the residual
       case AC_REGION_FFN: return 2 * T * d * b + (uint64_t)c * d * b + 2 * (uint64_t)c * F * b;
       default: return 0;
     }
@@ -671,7 +677,7 @@ static int64_t model_rows(const ac_model_desc& m, const Setting& s, int64_t len)
 }
 
 static void region_kinds(const ac_model_desc& m, int& first, int& count) {
-  if (m.workload == AC_TRANSFORMER_STACK) { first = AC_REGION_QKV; count = 3; }
+  if (m.workload == AC_TRANSFORMER_STACK) { first = AC_REGION_QKV; count = 4; }
   else { first = AC_REGION_TRIMUL_OUT; count = 5; }
 }
 

@@ -27,7 +27,7 @@ def B():
 
 def tregions(B, c):
     return [(B.AC_REGION_QKV, B.AC_DIM_SEQ, c[0]), (B.AC_REGION_ATTENTION, B.AC_DIM_SEQ, c[1]),
-            (B.AC_REGION_FFN, B.AC_DIM_SEQ, c[2])]
+            (B.AC_REGION_OUT_PROJ, B.AC_DIM_SEQ, c[3] if len(c) > 3 else c[1]), (B.AC_REGION_FFN, B.AC_DIM_SEQ, c[2])]
 
 
 def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None):
@@ -50,8 +50,9 @@ def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None):
 def test_c2_gpt_full_stack(B):
     cfg = I.C2
     x, layers = I.transformer_inputs(cfg)
-    y, info, dw = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0)), cfg.act_budget)
+    y, info, dw = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget)
     assert info.regions[1].chunk_len == 1792 and info.peak_bytes_model <= cfg.act_budget
+    assert [r.n_segments for r in info.regions[:4]] == [1, 5, 1, 1]
     ref = O.transformer_stack(x, layers, cfg.heads, True, query_block=1024)
     err = rel_err(host(y), ref)
     print("C2 rel err", err)
@@ -67,7 +68,7 @@ def test_c3_vit_full_stack(B):
     cfg = I.C3
     x, layers = I.transformer_inputs(cfg)
     y, info, _ = run_transformer(B, cfg, x, layers, tregions(B, (512, 512, 512)))
-    assert [r.n_segments for r in info.regions[:3]] == [8, 8, 8]
+    assert [r.n_segments for r in info.regions[:4]] == [8, 8, 8, 8]
     ref = O.transformer_stack(x, layers, cfg.heads, False, query_block=1024)
     err = rel_err(host(y), ref)
     print("C3 rel err", err)
@@ -78,7 +79,7 @@ def test_c5_long_context(B):
     import torch
     cfg1 = dataclasses.replace(I.C5, layers=1)
     x, layers = I.transformer_inputs(cfg1)
-    y, info, dw = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0)), I.C5.act_budget)
+    y, info, dw = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0, 0)), I.C5.act_budget)
     assert info.regions[1].chunk_len == 640 and info.regions[1].n_segments == 103
     got = host(y)
     assert np.isfinite(got).all()
@@ -93,7 +94,7 @@ def test_c5_long_context(B):
     # two layers, budget plan vs another chunking: identical bits
     cfg = I.C5
     x2, layers2 = I.transformer_inputs(cfg)
-    ya, infa, dw2 = run_transformer(B, cfg, x2, layers2, tregions(B, (0, 0, 0)), cfg.act_budget)
+    ya, infa, dw2 = run_transformer(B, cfg, x2, layers2, tregions(B, (0, 0, 0, 0)), cfg.act_budget)
     yb, _, _ = run_transformer(B, cfg, x2, layers2, tregions(B, (8192, 2048, 4096)), dw=dw2)
     assert bool(torch.isfinite(ya.float()).all())
     assert rel_err(host(yb), host(ya)) <= 0.5 * TOL["bf16"]   # key splits differ: equal to rounding

@@ -18,9 +18,10 @@ def B():
     return binding
 
 
-def regions(B, c_qkv, c_attn, c_ffn, dim=None):
+def regions(B, c_qkv, c_attn, c_ffn, dim=None, c_out=None):
     dim = B.AC_DIM_SEQ if dim is None else dim
-    return [(B.AC_REGION_QKV, dim, c_qkv), (B.AC_REGION_ATTENTION, dim, c_attn), (B.AC_REGION_FFN, dim, c_ffn)]
+    return [(B.AC_REGION_QKV, dim, c_qkv), (B.AC_REGION_ATTENTION, dim, c_attn),
+            (B.AC_REGION_OUT_PROJ, dim, c_attn if c_out is None else c_out), (B.AC_REGION_FFN, dim, c_ffn)]
 
 
 class Runner:
@@ -63,7 +64,7 @@ def test_c1_block_fp32_chunked_and_unchunked(B):
     ref = r.oracle()
     y4, info4 = r.run(regions(B, 64, 64, 64))
     y1, info1 = r.run(regions(B, 256, 256, 256))
-    assert [x.n_segments for x in info4.regions[:3]] == [4, 4, 4]
+    assert [x.n_segments for x in info4.regions[:4]] == [4, 4, 4, 4]
     assert rel_err(host(y4), ref) <= TOL["f32"]
     assert rel_err(host(y1), ref) <= TOL["f32"]
     assert info4.peak_bytes_planned < info1.peak_bytes_planned
@@ -91,7 +92,7 @@ def test_bf16_stack_chunked_equals_oracle(B, causal, heads, act):
     ref = r.oracle()
     outs = []
     for c in ((640, 640, 640), (128, 128, 128), (256, 384, 512), (200, 136, 72), (640, 8, 640)):
-        y, info = r.run(regions(B, *c))
+        y, info = r.run(regions(B, *c, c_out=c[0]))
         assert rel_err(host(y), ref) <= TOL["bf16"], c
         outs.append(y)
     # the K loop and the key-tile order do not depend on the segment a row falls in:
@@ -109,7 +110,7 @@ def test_batch_and_batch_chunks(B):
     ref = r.oracle()
     ys, _ = r.run(regions(B, 64, 64, 64))
     yb, info = r.run(regions(B, 2, 1, 3, dim=B.AC_DIM_BATCH))
-    assert [x.n_segments for x in info.regions[:3]] == [2, 3, 1]
+    assert [x.n_segments for x in info.regions[:4]] == [2, 3, 3, 1]
     assert rel_err(host(ys), ref) <= TOL["bf16"] and rel_err(host(yb), ref) <= TOL["bf16"]
     assert torch.equal(ys, yb)
     cfg32 = I.TransformerConfig("tb32", 34, 1, 50, 32, 2, 64, False, "f32", None, batch=2)

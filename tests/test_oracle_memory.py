@@ -37,6 +37,9 @@ def test_ffn_and_qkv_hand_counts():
     assert M.ffn_region(8192, 1024, 4096, 2) == (16 + 16 + 16 + 128) * MIB
     assert M.ffn_region(8192, 1024, 4096, 2, 1024) == (16 + 16 + 2 + 16) * MIB
     assert M.qkv_region(8192, 1024, 2) == (16 + 48 + 16) * MIB
+    # output projection: x, ctx, h whole (16 MiB each) + the projection before the residual
+    assert M.out_proj_region(8192, 1024, 2) == (48 + 16) * MIB
+    assert M.out_proj_region(8192, 1024, 2, 1024) == (48 + 2) * MIB
     assert M.transformer_layer_peak(8192, 1024, 16, 4096, 2) == (16 + 48 + 16 + 4096) * MIB
 
 

@@ -26,8 +26,10 @@ def test_library_exports_every_declared_symbol():
     assert L.ac_status_string(B.AC_ERR_ILLEGAL_CHUNK_DIM) == b"illegal chunk dimension"
 
 
-def regions(c_qkv, c_attn, c_ffn, dim=B.AC_DIM_SEQ):
-    return [(B.AC_REGION_QKV, dim, c_qkv), (B.AC_REGION_ATTENTION, dim, c_attn), (B.AC_REGION_FFN, dim, c_ffn)]
+def regions(c_qkv, c_attn, c_ffn, dim=B.AC_DIM_SEQ, c_out=None):
+    """Four regions per layer; the output projection follows the attention's length unless given."""
+    return [(B.AC_REGION_QKV, dim, c_qkv), (B.AC_REGION_ATTENTION, dim, c_attn),
+            (B.AC_REGION_OUT_PROJ, dim, c_attn if c_out is None else c_out), (B.AC_REGION_FFN, dim, c_ffn)]
 
 
 def al(v):
@@ -45,24 +47,27 @@ def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
     return max(1, min(-(-768 // blocks), sk // 512, 16))
 
 
-def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1):
-    """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], h (Td), inter-layer t (Td if
-    layers > 1), plus the largest per-segment set: u (c d) | ctx (c d) + fp32 split partials
-    (ns c H (d_h + 2) floats) | u (c d) + hidden (c F)."""
+def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None):
+    """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], context (Td), h (Td),
+    inter-layer t (Td if layers > 1), plus the largest per-segment set: u (c d) | fp32 split
+    partials of the attention (ns c H (d_h + 2) floats) | nothing for the output projection
+    (its unfused form holds c d) | u (c d) + hidden (c F)."""
+    c_out = c_attn if c_out is None else c_out
     e = 2 if cfg.dtype == "bf16" else 4
     T, d, F = cfg.seq * cfg.batch, cfg.d_model, cfg.d_ffn
     whole = (al(T * 2 * d * e) + al(T * d * e)) if cfg.dtype == "bf16" else al(T * 3 * d * e)
-    whole += al(T * d * e)
+    whole += 2 * al(T * d * e)
     if cfg.layers > 1:
         whole += al(T * d * e)
     r1 = al(c_qkv * d * e)
     ns = key_splits_by_hand(c_attn, cfg.seq, cfg.heads, 1, cfg.head_dim, cfg.dtype)
     parts = (al(ns * c_attn * d * 4) + al(ns * c_attn * cfg.heads * 8)) if ns > 1 else 0
-    r2 = al(c_attn * d * e) + max(parts, al(c_attn * d * e) if unfused else 0)
+    r2 = parts
+    r2b = al(c_out * d * e) if unfused else 0
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
     # two segments in flight: a region with more than one segment holds two per-segment sets
     mult = lambda c: lanes if c < cfg.seq else 1
-    return whole + max(r1 * mult(c_qkv), r2 * mult(c_attn), r3 * mult(c_ffn))
+    return whole + max(r1 * mult(c_qkv), r2 * mult(c_attn), r2b * mult(c_out), r3 * mult(c_ffn))
 
 
 @pytest.mark.parametrize("cfg,c", [(I.C1, (64, 64, 64)), (I.C3, (512, 512, 512)), (I.C2, (1024, 1024, 1024)),
@@ -75,16 +80,17 @@ def test_planned_bytes_equal_the_arena_worked_by_hand(cfg, c):
     assert info.workspace_bytes == arena_by_hand(cfg, *c)
     assert info.peak_bytes_planned == info.io_bytes + info.workspace_bytes
     assert info.peak_bytes_unchunked_planned == info.io_bytes + arena_by_hand(cfg, cfg.seq, cfg.seq, cfg.seq)
-    assert info.n_weights == 12 * cfg.layers and info.n_regions == 3
-    for r, cl in zip(info.regions[:3], c):
+    assert info.n_weights == 12 * cfg.layers and info.n_regions == 4
+    for r, cl in zip(info.regions[:4], (c[0], c[1], c[1], c[2])):
         assert r.chunk_len == cl and r.n_segments == -(-cfg.seq // cl) and r.extent == cfg.seq
     # paper-style region bytes agree with the independent model in oracle/
     a = info.regions[1]
     assert a.model_bytes == M.attention_region(cfg.seq, cfg.d_model, cfg.heads, e, c[1])
     assert a.model_bytes_unchunked == M.attention_region(cfg.seq, cfg.d_model, cfg.heads, e)
     assert info.regions[0].model_bytes == M.qkv_region(cfg.seq, cfg.d_model, e, c[0])
-    assert info.regions[2].model_bytes == M.ffn_region(cfg.seq, cfg.d_model, cfg.d_ffn, e, c[2])
-    assert info.peak_bytes_model == M.transformer_layer_peak(cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, e, *c)
+    assert info.regions[3].model_bytes == M.ffn_region(cfg.seq, cfg.d_model, cfg.d_ffn, e, c[2])
+    assert info.regions[2].model_bytes == M.out_proj_region(cfg.seq, cfg.d_model, e, c[1])
+    assert info.peak_bytes_model == M.transformer_layer_peak(cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, e, *c, c_out=c[1])
     assert info.peak_bytes_model_unchunked == M.transformer_layer_peak(cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, e)
     p.close()
 
@@ -105,6 +111,11 @@ def test_two_segments_in_flight_doubles_the_per_segment_sets():
     for cfg, c in ((I.C3, (512, 512, 512)), (I.C2, (8192, 1792, 8192)), (I.C2, (1024, 1024, 1024))):
         p = B.Plan(B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(*c))
         assert p.ac_plan_query().workspace_bytes == arena_by_hand(cfg, *c, lanes=2)
+    # the output projection may be cut differently from the attention core
+    p = B.Plan(B.transformer_desc(I.C2), regions(8192, 1792, 8192, c_out=8192))
+    info = p.ac_plan_query()
+    assert [r.n_segments for r in info.regions[:4]] == [1, 5, 1, 1]
+    assert info.workspace_bytes == arena_by_hand(I.C2, 8192, 1792, 8192, c_out=8192)
 
 
 def test_unfused_flag_adds_the_temporaries():
@@ -125,6 +136,13 @@ def test_flops_are_the_algorithmic_counts():
         assert abs(info2.flops_per_execute - info.flops_per_execute) <= 1e-9 * info.flops_per_execute
 
 
+def expect(status, fn):
+    with pytest.raises(B.AcError) as ei:
+        fn()
+    assert ei.value.status == status, str(ei.value)
+    assert B.lib().ac_last_error() != b""
+
+
 def test_budget_sizes_the_chunk_lengths():
     # C2, 1 GiB: only the attention region exceeds it; largest multiple of 128 that fits is 1792
     p = B.Plan(B.transformer_desc(I.C2), regions(0, 0, 0), 1 * GIB)
@@ -133,7 +151,7 @@ def test_budget_sizes_the_chunk_lengths():
     fits = lambda c: M.attention_region(8192, 1024, 16, e, c) <= GIB
     assert info.regions[1].chunk_len == M.largest_chunk_len(8192, 128, fits) == 1792
     assert info.regions[1].n_segments == 5
-    assert info.regions[0].chunk_len == 8192 and info.regions[2].chunk_len == 8192
+    assert info.regions[0].chunk_len == 8192 and info.regions[2].chunk_len == 8192 and info.regions[3].chunk_len == 8192
     assert info.peak_bytes_model <= GIB < info.peak_bytes_model_unchunked
     assert info.peak_bytes_planned <= GIB
     # C5, 4 GiB: attention gets 640 rows, the other regions fit whole (multi-stage: each
@@ -144,11 +162,14 @@ def test_budget_sizes_the_chunk_lengths():
     assert info5.regions[1].n_segments == 103
     assert info5.peak_bytes_model <= 4 * GIB and info5.peak_bytes_planned <= 4 * GIB
     # a tighter budget makes the feed-forward chunk too
-    info5b = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 2 * GIB).ac_plan_query()
-    assert info5b.regions[2].chunk_len < 65536 and info5b.regions[1].chunk_len == 128
-    for r in info5b.regions[:3]:
-        assert r.model_bytes <= 2 * GIB
-    assert info5b.peak_bytes_planned <= 2 * GIB
+    tight = 5 * GIB // 2
+    info5b = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), tight).ac_plan_query()
+    assert info5b.regions[3].chunk_len < 65536 and info5b.regions[1].chunk_len == 256
+    for r in info5b.regions[:4]:
+        assert r.model_bytes <= tight
+    assert info5b.peak_bytes_planned <= tight
+    # at 2 GiB the whole tensors of the executor alone (x, y, q, k, v, context, h, t: 8 x 256 MiB) do not fit
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 2 * GIB))
     # monotone: more segments never need more bytes
     prev = None
     for c in (8192, 4096, 1024, 256, 64):
@@ -157,17 +178,10 @@ def test_budget_sizes_the_chunk_lengths():
         prev = w
 
 
-def expect(status, fn):
-    with pytest.raises(B.AcError) as ei:
-        fn()
-    assert ei.value.status == status, str(ei.value)
-    assert B.lib().ac_last_error() != b""
-
-
 def test_legality_and_errors():
     d = B.transformer_desc(I.C3)
     for dim in (B.AC_DIM_FEATURE, B.AC_DIM_HEAD_DIM, B.AC_DIM_KEY):
-        for kind in (B.AC_REGION_QKV, B.AC_REGION_ATTENTION, B.AC_REGION_FFN):
+        for kind in (B.AC_REGION_QKV, B.AC_REGION_ATTENTION, B.AC_REGION_OUT_PROJ, B.AC_REGION_FFN):
             expect(B.AC_ERR_ILLEGAL_CHUNK_DIM, lambda: B.Plan(d, [(kind, dim, 64)]))
     B.Plan(d, [(B.AC_REGION_ATTENTION, B.AC_DIM_BATCH, 1)]).close()
     expect(B.AC_ERR_ARG, lambda: B.Plan(d, [(B.AC_REGION_ATTENTION, 9, 64)]))
@@ -185,10 +199,10 @@ def test_legality_and_errors():
     expect(B.AC_ERR_ARG, lambda: B.Plan(bad))
     # the floor of the second activation equation: whole tensors alone exceed the budget
     expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 1 * GIB))
-    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C2), regions(0, 4096, 0), 1 * GIB))
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C2), regions(0, 4096, 0, c_out=0), 1 * GIB))
     # chunk_len larger than the extent means one segment
     info = B.Plan(d, regions(10 ** 9, 10 ** 9, 10 ** 9)).ac_plan_query()
-    assert all(r.n_segments == 1 for r in info.regions[:3])
+    assert all(r.n_segments == 1 for r in info.regions[:4])
     # query / bind / execute argument checks that need no device
     p = B.Plan(d)
     L = B.lib()
