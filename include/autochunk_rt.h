@@ -264,7 +264,7 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch,
  * keys each block of queries sees can be cut into n_splits runs that separate blocks
  * process; their fp32 partial results (unnormalised context, running maximum and sum) go to
  * split_workspace (device, 16-byte aligned, ac_attention_split_workspace_bytes large) and a
- * second kernel merges them.  n_splits <= 1 means one pass and no workspace.  Results for
+ * second kernel merges them.  n_splits <= 1 means one pass and no workspace; at most 16.  Results for
  * different n_splits agree to rounding, not bitwise.  ac_attention_key_splits is the count
  * the executor uses for a launch shape (1 when the launch already fills the GPU).
  */

@@ -405,18 +405,37 @@ __global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
   const int64_t br = rh / a.heads;
   const int64_t row = br % a.sq, b = br / a.sq;
   const int64_t stride = a.batch * a.sq * a.heads;   // (row, head) pairs per split
+  // all loads of a thread are issued before the first use (at most 16 splits), so their
+  // latencies overlap instead of adding up
+  constexpr int kMaxSplits = 16;
   const float* ml = (const float*)a.part_ml;
+  const float* po = (const float*)a.part_o;
+  f32x2 mls[kMaxSplits];
+  f32x4 os[kMaxSplits];
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    if (s < a.n_splits) {
+      mls[s] = *reinterpret_cast<const f32x2*>(ml + (s * stride + rh) * 2);
+      os[s] = *reinterpret_cast<const f32x4*>(po + (s * stride + rh) * a.head_dim + d);
+    } else {
+      mls[s] = f32x2{-INFINITY, 0.f};
+      os[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
   float M = -INFINITY;
-  for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, ml[(s * stride + rh) * 2]);
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) M = fmaxf(M, mls[s][0]);
   float L = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < a.n_splits; ++s) {
-    const float m = ml[(s * stride + rh) * 2];
-    if (m == -INFINITY) continue;              // that split saw no key of this row
-    const float w = __builtin_amdgcn_exp2f(m - M);
-    L += ml[(s * stride + rh) * 2 + 1] * w;
-    const f32x4 o = *reinterpret_cast<const f32x4*>((const float*)a.part_o + (s * stride + rh) * a.head_dim + d);
-    acc += o * w;
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    // a split that saw no key of this row reports m = -inf; its sum and context are not
+    // meaningful (the kernel may have formed inf - inf there) and must not be touched
+    if (mls[s][0] != -INFINITY) {
+      const float w = __builtin_amdgcn_exp2f(mls[s][0] - M);
+      L += mls[s][1] * w;
+      acc += os[s] * w;
+    }
   }
   const float inv = 1.0f / L;
   float v[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};

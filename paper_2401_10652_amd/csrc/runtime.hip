@@ -1089,7 +1089,7 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch, const vo
                     int64_t sq, int64_t sk, int heads, int head_dim, int causal, int64_t q_offset, int n_splits,
                     void* split_workspace, uint64_t split_workspace_bytes, int dtype, void* stream) {
   if (!q || !k || !v || !ctx || batch < 0 || sq < 0 || sk < 1 || heads < 1 || head_dim < 1 || q_offset < 0 ||
-      !dtype_ok(dtype) || n_splits < 0 || n_splits > 64)
+      !dtype_ok(dtype) || n_splits < 0 || n_splits > 16)
     return fail(AC_ERR_ARG, "ac_op_attention: bad argument");
   if (n_splits > 1) {
     const uint64_t need = attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits);
