@@ -377,7 +377,7 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
     // estimated time: tiles per CU (rounded up) x padded tile area / measured efficiency of
     // that tile shape.  The k order is the same for all of them.
     struct Cand { int bm, bn; double eff; };
-    static const Cand cands[5] = {{256, 256, 0.40}, {256, 128, 0.33}, {128, 128, 0.30}, {64, 256, 0.24}, {64, 64, 0.15}};
+    static const Cand cands[5] = {{256, 256, 0.41}, {256, 128, 0.376}, {128, 128, 0.36}, {64, 256, 0.26}, {64, 64, 0.253}};
     int best = 4;
     double best_t = 0;
     for (int c = 0; c < 5; ++c) {
