@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
                     help="segments of a region in flight at once (2: two streams, two per-segment workspaces)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sequential-only", action="store_true",
+                    help="skip the extra two-segments-in-flight timing (its overlapping kernels would "
+                         "distort per-kernel durations in a profiler trace)")
     ap.add_argument("--sweep", action="store_true", help="also time a sweep of chunk lengths")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB copy kernel --steps times (for scaling rocprofv3 byte counters)")
@@ -246,7 +249,7 @@ def main():
             "ratio_vs_unchunked_measured": round(peak / peak1, 4),
         },
     }
-    if args.in_flight == 1:
+    if args.in_flight == 1 and not args.sequential_only:
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
         import copy
