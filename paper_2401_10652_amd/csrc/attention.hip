@@ -519,16 +519,16 @@ static hipError_t generic_attn_dispatch(const AttnArgs& a, hipStream_t s) {
 }
 
 // Key splits for a launch that would leave most of the 256 CUs idle: as many as still give
-// at most three blocks per CU (what a CU holds at a time, so that all of them start at once:
-// a fourth block per CU would run alone after the others, at a fraction of the rate), each
-// split at least 512 keys long.  A pure function of the launch shape, so planning and
-// execution agree.
+// every block a place at once, which by register count is three blocks per CU, two with
+// 128-wide heads (a launch that spills into a second round leaves those blocks to run alone
+// at the end, at a fraction of the CU's rate), each split at least 512 keys long.  A pure
+// function of the launch shape, so planning and execution agree.
 int attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim, int dtype, int v_transposed) {
   if (dtype != AC_BF16 || !v_transposed) return 1;
   if (head_dim != 32 && head_dim != 64 && head_dim != 128) return 1;
   const int64_t blocks = ((sq + kQB - 1) / kQB) * heads * batch;
   if (blocks <= 0 || blocks >= 512 || sk < 1024) return 1;
-  int64_t want = 768 / blocks;
+  int64_t want = (head_dim > 64 ? 512 : 768) / blocks;
   const int64_t by_len = sk / 512;
   if (want > by_len) want = by_len;
   if (want > 16) want = 16;

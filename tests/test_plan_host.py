@@ -39,13 +39,14 @@ def al(v):
 def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
     """The executor cuts the keys of a launch with fewer than 512 blocks of 128 query rows into
     runs of at least 512 keys, as many as keep the launch within 768 blocks (three per compute
-    unit, all resident at once), at most 16 (bf16 matrix-core path)."""
+    unit, all resident at once; 512, two per unit, with 128-wide heads), at most 16 (bf16
+    matrix-core path)."""
     if dtype != "bf16" or dh not in (32, 64, 128):
         return 1
     blocks = -(-sq // 128) * heads * batch
     if blocks >= 512 or sk < 1024:
         return 1
-    return max(1, min(768 // blocks, sk // 512, 16))
+    return max(1, min((512 if dh > 64 else 768) // blocks, sk // 512, 16))
 
 
 def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None):
@@ -104,6 +105,7 @@ def test_key_split_rule():
         assert B.ac_attention_key_splits(sq, sk, h, b, dh, dt) == key_splits_by_hand(sq, sk, h, b, dh, dt)
     assert B.ac_attention_key_splits(1792, 8192, 16, 1, 64, "bf16") == 3
     assert B.ac_attention_key_splits(512, 4096, 12, 1, 64, "bf16") == 8
+    assert B.ac_attention_key_splits(640, 65536, 16, 1, 128, "bf16") == 6
     assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 3) == 3 * 2 * 100 * 4 * (64 + 2) * 4
     assert B.ac_attention_split_workspace_bytes(100, 4, 2, 64, 1) == 0
 
