@@ -101,28 +101,6 @@ __device__ __forceinline__ void tile_of_block(int64_t tiles_m, int64_t tiles_n, 
   tn = (t % width) / gsz;
 }
 
-// bias, activation, multiplier, residual for 4 consecutive columns of one row (fp32)
-template <int ACT>
-__device__ __forceinline__ void epilogue_math4(const LinearArgs& g, int64_t m, int64_t n, float (&v)[4]) {
-  if (g.bias) {
-    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + n);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) v[j] = apply_act<ACT>(v[j]);
-  if (g.mul) {
-    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.mul + m * g.ldmul + n);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] *= bf2f(b[j]);
-  }
-  if (g.resid) {
-    bf16x4 b = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.resid + m * g.ldr + n);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += bf2f(b[j]);
-  }
-}
-
 // The epilogue of one block.  A tile that lies wholly in the row-major part of the output
 // is rounded to bf16 into LDS (free after the k loop) and written out with 16-byte stores
 // whose lanes walk along rows; other tiles (strided store, narrow or misaligned outputs)
@@ -141,6 +119,14 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   const bool tstaged = !staged && n0 >= g.n_split && g.t_s2 == 1 && g.m % 8 == 0 && g.t_s1 % 8 == 0 && g.t_s3 % 8 == 0 &&
                        ((uintptr_t)g.out_t % 16) == 0 && (g.t_period == INT64_MAX || (g.t_period % BM == 0));
   if (staged || tstaged) __syncthreads();   // every wave is done reading the k-loop buffers
+  // Operand loads of the epilogue are issued in batches and from clamped, always valid
+  // addresses, so that a lane waits for memory once per batch and not once per group of four
+  // columns; only the stores are predicated.  A batch is a row of the wave's 32x32
+  // accumulator tiles in the 8-wave shapes and a single tile in the 4-wave shapes, which
+  // have no registers to spare.
+  constexpr int JB = WAVES_M * WAVES_N == 8 ? TN : 1;
+  const bf16x4 zero4 = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+  const int cl0 = wave_n * WN + 4 * half;      // this lane's first column of the tile
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int rl = wave_m * WM + i * 32 + l32;
@@ -150,26 +136,62 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
     // offset of row m in the strided ("transposed") output, if any
     const int64_t t_base = g.n_split < g.n ? (mc / g.t_period) * g.t_s1 + (mc % g.t_period) * g.t_s2 : 0;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int jb = 0; jb < TN; jb += JB) {
+      bf16x4 bias_v[JB][4], mul_v[JB][4], res_v[JB][4];
+      int64_t nc[JB][4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int cl = wave_n * WN + j * 32 + 8 * q + 4 * half;
-        const int64_t n = n0 + cl;
-        if (!row_ok || n >= g.n) continue;
-        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        epilogue_math4<ACT>(g, m, n, v);
-        const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
-        if (staged) {
-          *reinterpret_cast<bf16x4*>(lds + rl * CROW + cl) = o;
-        } else if (tstaged) {
+      for (int j = 0; j < JB; ++j)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) lds[(cl + jj) * TROW + rl] = o[jj];
-        } else if (n < g.n_split) {
-          *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
-        } else {
-          const int64_t base = t_base + (n - g.n_split) * g.t_s3;
+        for (int q = 0; q < 4; ++q) {
+          const int64_t n = n0 + cl0 + (jb + j) * 32 + 8 * q;
+          nc[j][q] = n < g.n ? n : g.n - 4;
+          bias_v[j][q] = g.bias ? *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + nc[j][q]) : zero4;
+        }
+      if (g.mul) {
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) ((bf16_t*)g.out_t)[base + jj * g.t_s3] = o[jj];
+        for (int j = 0; j < JB; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            mul_v[j][q] = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.mul + mc * g.ldmul + nc[j][q]);
+      }
+      if (g.resid) {
+#pragma unroll
+        for (int j = 0; j < JB; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            res_v[j][q] = *reinterpret_cast<const bf16x4*>((const bf16_t*)g.resid + mc * g.ldr + nc[j][q]);
+      }
+#pragma unroll
+      for (int j = 0; j < JB; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int cl = cl0 + (jb + j) * 32 + 8 * q;
+          const int64_t n = n0 + cl;
+          float v[4] = {acc[i][jb + j][4 * q], acc[i][jb + j][4 * q + 1], acc[i][jb + j][4 * q + 2], acc[i][jb + j][4 * q + 3]};
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) v[jj] = apply_act<ACT>(v[jj] + bf2f(bias_v[j][q][jj]));
+          if (g.mul) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) v[jj] *= bf2f(mul_v[j][q][jj]);
+          }
+          if (g.resid) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) v[jj] += bf2f(res_v[j][q][jj]);
+          }
+          const bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
+          if (!row_ok || n >= g.n) continue;
+          if (staged) {
+            *reinterpret_cast<bf16x4*>(lds + rl * CROW + cl) = o;
+          } else if (tstaged) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) lds[(cl + jj) * TROW + rl] = o[jj];
+          } else if (n < g.n_split) {
+            *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
+          } else {
+            const int64_t base = t_base + (n - g.n_split) * g.t_s3;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) ((bf16_t*)g.out_t)[base + jj * g.t_s3] = o[jj];
+          }
         }
       }
     }
