@@ -264,6 +264,33 @@ def main():
                                          "throughput_loss": round(1.0 - sec1 / sec2, 4), "peak_bytes_measured": peak2}
         plan2.close()
         del ws2
+    if not is_pair and not args.sequential_only:
+        # The same two plans with the attention core run as an unfused graph would (scores and
+        # probabilities stored in the workspace): here the workspace really holds the intermediate
+        # activations the paper's equations count, so the memory ratio of chunking is measured.
+        import copy
+        desc3 = copy.copy(desc)
+        desc3.flags = (desc.flags | B.AC_FLAG_MATERIALIZED_SCORES) & ~B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT
+        regs3 = [(k, dm, info.regions[i].chunk_len) for i, (k, dm, _) in enumerate(regs)]
+        stored = {}
+        for label, rg in (("chunked", regs3), ("one_segment", regs1)):
+            p3 = B.Plan(desc3, rg, 0)
+            i3 = p3.ac_plan_query()
+            entry = {"peak_bytes_planned": int(i3.peak_bytes_planned)}
+            if i3.workspace_bytes <= 48 << 30:      # the whole score tensor of a long sequence may not fit
+                p3.ac_plan_bind_weights(dw)
+                ws3 = B.empty_workspace(i3.workspace_bytes)
+                s3, pk3 = time_plan(B, torch, p3, dx, y, ws3, max(3, args.steps // 2), 1)
+                entry.update({"ms_per_step": round(s3 * 1e3, 4), "tokens_per_s": round(tokens / s3, 1),
+                              "peak_bytes_measured": pk3})
+                del ws3
+            stored[label] = entry
+            p3.close()
+        stored["peak_ratio_chunked_vs_one_segment"] = round(
+            stored["chunked"]["peak_bytes_planned"] / stored["one_segment"]["peak_bytes_planned"], 4)
+        if "ms_per_step" in stored["chunked"] and "ms_per_step" in stored["one_segment"]:
+            stored["throughput_loss"] = round(1.0 - stored["one_segment"]["ms_per_step"] / stored["chunked"]["ms_per_step"], 4)
+        out["stored_scores"] = stored
     if args.sweep:
         sweep = []
         c = cfg.n_res if is_pair else cfg.seq

@@ -88,9 +88,19 @@ enum {
                                       second stream owned by the plan, each with its own per-segment
                                       workspace (the plan's bytes account for both); all work is joined
                                       back into the caller's stream at the end of every region */
-  AC_FLAG_LISTED_REGIONS_ONLY = 2  /* pair stack only: the block consists of just the region kinds
+  AC_FLAG_LISTED_REGIONS_ONLY = 2, /* pair stack only: the block consists of just the region kinds
                                       listed in ac_plan_create (each maps z to z), in canonical
                                       order; weights of the others are still bound but unused */
+  AC_FLAG_MATERIALIZED_SCORES = 8  /* transformer stack only: the attention core runs as an unfused graph
+                                      would (AutoChunk section 2.1): scores = q k^T per head stored in the
+                                      workspace, probabilities = softmax(scores) stored beside them,
+                                      context = probabilities v.  The workspace then really holds the
+                                      intermediate activations the paper's equations count, mem(A) whole
+                                      or mem(A)/n per segment, so the effect of chunking on memory can be
+                                      measured and not only modelled.  Same result as the fused kernel up
+                                      to the rounding of the stored scores and probabilities.  With a
+                                      causal mask the masked half is computed and discarded;
+                                      flops_per_execute counts what is executed. */
 };
 
 typedef struct ac_model_desc {
@@ -280,6 +290,18 @@ int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_
 /* y = a + b  (op 0)  or  y = a * b  (op 1) over [rows, cols]. */
 int ac_op_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
                  int64_t rows, int64_t cols, int op, int dtype, void* stream);
+
+/*
+ * p = softmax(scale * s) over each of `rows` stored rows of `cols` scores (AutoChunk section
+ * 2.1 names the scores and probabilities of attention as the intermediate activations that
+ * dominate memory; this is the pass between them when they are stored).  Row r belongs to
+ * query r mod period, which stands at position q_offset + (r mod period); with causal != 0
+ * it sees columns j <= that position and the others get probability exactly 0.  s and p may
+ * be the same buffer.  scale > 0.
+ */
+int ac_op_softmax_rows(const void* s, int64_t lds, void* p, int64_t ldp, int64_t rows, int64_t cols,
+                       float scale, int causal, int64_t q_offset, int64_t period, int dtype,
+                       void* stream);
 
 /* dst[c * ldd + r] = src[r * lds + c] for a [rows, cols] matrix (e.g. values -> v_transposed). */
 int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows,

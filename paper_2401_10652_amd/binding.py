@@ -26,6 +26,7 @@ AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
 AC_FLAG_UNFUSED_ELEMENTWISE = 1
 AC_FLAG_LISTED_REGIONS_ONLY = 2
 AC_FLAG_TWO_SEGMENTS_IN_FLIGHT = 4
+AC_FLAG_MATERIALIZED_SCORES = 8
 
 ACTIVATIONS = {"none": AC_ACT_NONE, "gelu_erf": AC_ACT_GELU_ERF, "gelu_tanh": AC_ACT_GELU_TANH,
                "relu": AC_ACT_RELU, "sigmoid": AC_ACT_SIGMOID}
@@ -68,7 +69,7 @@ class ac_kernel_stat(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
-I64, U64, VP, INT = C.c_int64, C.c_uint64, C.c_void_p, C.c_int
+I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
 
 # name -> (restype, argtypes): every symbol include/autochunk_rt.h declares.
 SIGNATURES = {
@@ -91,6 +92,7 @@ SIGNATURES = {
     "ac_attention_split_workspace_bytes": (U64, [I64, INT, I64, INT, INT]),
     "ac_op_bias_act": (INT, [VP, I64, VP, VP, I64, I64, I64, INT, INT, VP]),
     "ac_op_binary": (INT, [VP, I64, VP, I64, VP, I64, I64, I64, INT, INT, VP]),
+    "ac_op_softmax_rows": (INT, [VP, I64, VP, I64, I64, I64, F32, INT, I64, I64, INT, VP]),
     "ac_op_transpose": (INT, [VP, I64, VP, I64, I64, I64, INT, VP]),
     "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose_square_inplace": (INT, [VP, I64, I64, I64, I64, INT, VP]),
@@ -285,6 +287,13 @@ def ac_op_bias_act(x, bias, y, activation):
     rows, cols = x.shape
     _check(lib().ac_op_bias_act(_ptr(x), x.stride(0), _ptr(bias), _ptr(y), y.stride(0), rows, cols,
                                 activation, _dt(x), _stream()), "ac_op_bias_act")
+
+
+def ac_op_softmax_rows(s, p, scale, causal=False, q_offset=0, period=None):
+    rows, cols = s.shape
+    _check(lib().ac_op_softmax_rows(_ptr(s), s.stride(0), _ptr(p), p.stride(0), rows, cols, float(scale),
+                                    int(causal), q_offset, rows if period is None else period, _dt(s), _stream()),
+           "ac_op_softmax_rows")
 
 
 def ac_op_binary(a, b, y, op):

@@ -97,6 +97,11 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
 // Sum over groups of G consecutive lanes (G a power of two <= 64).
 template <int G> __device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
@@ -153,6 +158,10 @@ hipError_t launch_bias_act(const void* x, int64_t ldx, const void* bias, void* y
 hipError_t launch_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
                          int64_t rows, int64_t cols, int op, int dtype, hipStream_t s);
 hipError_t launch_linear(const LinearArgs& g, hipStream_t s);
+// p = softmax(scale * s [causal]) over stored rows; row r is query r mod period at position
+// q_offset + (r mod period).
+hipError_t launch_softmax_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows, int64_t cols,
+                               float scale, int causal, int64_t q_offset, int64_t period, int dtype, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 int attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, int head_dim, int dtype, int v_transposed);
 uint64_t attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim, int n_splits);

@@ -374,4 +374,55 @@ hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, con
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------
+// Row softmax of a stored score matrix: p = softmax(scale * s [causal]).  One block per row;
+// the row is read three times (maximum, sum, write), which is what an unfused graph does
+// (AutoChunk section 2.1: the scores and the probabilities are separate activation tensors).
+// Row r is query i = r mod period, standing at position q_offset + i; with the causal mask it
+// sees keys j <= q_offset + i and the rest get probability exactly 0.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+softmax_rows(const T* __restrict__ src, int64_t lds_, T* __restrict__ dst, int64_t ldd, int64_t cols, float scale,
+             int causal, int64_t q_offset, int64_t period) {
+  __shared__ float red[4];
+  const int64_t r = blockIdx.x;
+  const T* in = src + r * lds_;
+  T* out = dst + r * ldd;
+  int64_t vis = cols;
+  if (causal) {
+    const int64_t last = q_offset + r % period;
+    if (last + 1 < vis) vis = last + 1;
+  }
+  const int tid = threadIdx.x;
+  float m = -INFINITY;
+  for (int64_t j = tid; j < vis; j += 256) m = fmaxf(m, Elem<T>::ld(in + j));
+  m = wave_max(m);
+  if (tid % 64 == 0) red[tid / 64] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * scale;      // scale > 0
+  __syncthreads();
+  float l = 0.f;
+  for (int64_t j = tid; j < vis; j += 256) l += __expf(Elem<T>::ld(in + j) * scale - m);
+  l = wave_sum(l);
+  if (tid % 64 == 0) red[tid / 64] = l;
+  __syncthreads();
+  const float inv = 1.0f / (red[0] + red[1] + red[2] + red[3]);
+  for (int64_t j = tid; j < cols; j += 256)
+    Elem<T>::st(out + j, j < vis ? __expf(Elem<T>::ld(in + j) * scale - m) * inv : 0.f);
+}
+
+hipError_t launch_softmax_rows(const void* src, int64_t lds_, void* dst, int64_t ldd, int64_t rows, int64_t cols,
+                               float scale, int causal, int64_t q_offset, int64_t period, int dtype, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (period <= 0 || !(scale > 0.f) || rows > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (dtype == AC_BF16)
+    hipLaunchKernelGGL((softmax_rows<bf16_t>), dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)src, lds_,
+                       (bf16_t*)dst, ldd, cols, scale, causal, q_offset, period);
+  else
+    hipLaunchKernelGGL((softmax_rows<float>), dim3((unsigned)rows), dim3(256), 0, s, (const float*)src, lds_,
+                       (float*)dst, ldd, cols, scale, causal, q_offset, period);
+  return hipGetLastError();
+}
+
 }  // namespace ac

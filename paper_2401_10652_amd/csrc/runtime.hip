@@ -243,6 +243,43 @@ struct Walk {
     run(K_ATTN, fl, by, "attention", [&] { return launch_attention(a, stream); });
     arena.release(mk);
   }
+  // The attention core as an unfused graph holds it (AC_FLAG_MATERIALIZED_SCORES): per problem
+  // scores[h] = q_h k_h^T and probabilities[h] = softmax(scores[h] / sqrt(d_h)) are stored
+  // tensors of the segment, then ctx_h = probabilities[h] v_h.  v is given transposed.
+  void attention_materialized(const AttnArgs& a) {
+    const int dt = p->m.dtype;
+    const int e = eb();
+    const int64_t c = a.sq, S = a.sk, H = a.heads, dh = a.head_dim;
+    const uint64_t mk = arena.mark();
+    uint8_t* scores = (uint8_t*)arena.push((uint64_t)a.batch * H * c * S * e);
+    uint8_t* probs = (uint8_t*)arena.push((uint64_t)a.batch * H * c * S * e);
+    const float scale = 1.0f / sqrtf((float)dh);
+    for (int64_t b = 0; b < a.batch && ok(); ++b) {
+      const uint64_t off = (uint64_t)b * H * c * S * e;
+      LinearArgs g1{};
+      g1.a = (const uint8_t*)a.q + b * a.sq_b * e; g1.lda = a.ldq; g1.sa_b = dh;
+      g1.w = (const uint8_t*)a.k + b * a.sk_b * e; g1.ldw = a.ldk; g1.sw_b = dh;
+      g1.out = dry ? nullptr : scores + off; g1.ldo = S; g1.so_b = c * S;
+      g1.m = c; g1.n = S; g1.k = dh; g1.n_split = S; g1.batch = H; g1.act = AC_ACT_NONE; g1.dtype = dt;
+      run(K_GEMM, 2.0 * c * S * dh * H, ((double)c * dh + (double)S * dh + (double)c * S) * H * e, "scores",
+          [&] { return launch_linear(g1, stream); });
+      const void* sp = dry ? nullptr : scores + off;
+      void* pp = dry ? nullptr : probs + off;
+      const int causal = a.causal;
+      const int64_t qo = a.q_offset;
+      hipStream_t st = stream;
+      run(K_ELEM, 5.0 * c * S * H, 4.0 * c * S * H * e, "softmax",
+          [&] { return launch_softmax_rows(sp, S, pp, S, H * c, S, scale, causal, qo, c, dt, st); });
+      LinearArgs g2{};
+      g2.a = pp; g2.lda = S; g2.sa_b = c * S;
+      g2.w = (const uint8_t*)a.v + b * a.sv_b * e; g2.ldw = a.ldv; g2.sw_b = dh * a.ldv;
+      g2.out = (uint8_t*)a.ctx + b * a.sc_b * e; g2.ldo = a.ldc; g2.so_b = dh;
+      g2.m = c; g2.n = dh; g2.k = S; g2.n_split = dh; g2.batch = H; g2.act = AC_ACT_NONE; g2.dtype = dt;
+      run(K_GEMM, 2.0 * c * S * dh * H, ((double)c * S + (double)S * dh + (double)c * dh) * H * e, "context",
+          [&] { return launch_linear(g2, stream); });
+    }
+    arena.release(mk);
+  }
   void bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy, int64_t rows, int64_t cols,
                 int act) {
     const int dt = p->m.dtype;
@@ -356,7 +393,10 @@ void Walk::transformer(const void* x, void* y) {
   // Whole tensors of a layer.  bf16: q,k row-major [T, 2d] and v transposed per batch
   // element [d, S]; fp32: q,k,v row-major [T, 3d].
   void* qk = arena.push((uint64_t)T * (bf ? 2 : 3) * d * e);
-  void* vt = bf ? arena.push((uint64_t)T * d * e) : nullptr;
+  const bool stored_scores = (m.flags & AC_FLAG_MATERIALIZED_SCORES) != 0;
+  // v transposed: written by the projection's strided store (bf16), or, for the stored-scores
+  // attention of an fp32 model, by a transpose after the projection region
+  void* vt = (bf || stored_scores) ? arena.push((uint64_t)T * d * e) : nullptr;
   const int64_t ldqk = (bf ? 2 : 3) * d;
   void* ctx_all = arena.push((uint64_t)T * d * e);   // whole context: output of the attention region
   void* hbuf = arena.push((uint64_t)T * d * e);
@@ -390,6 +430,14 @@ void Walk::transformer(const void* x, void* y) {
       }
     });
 
+    if (stored_scores && !bf) {
+      for (int64_t b = 0; b < m.batch && ok(); ++b) {
+        const void* src = at(qk, b * S * ldqk + 2 * d);
+        void* dst = atw(vt, b * d * S);
+        hipStream_t st = stream;
+        run(K_ELEM, 0.0, 2.0 * S * d * e, "transpose v", [&] { return launch_transpose(src, ldqk, dst, S, S, d, AC_F32, st); });
+      }
+    }
     // ---- region 2: attention of a query segment over whole k, v; writes its rows of the context
     seg_loop(token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0;
@@ -401,7 +449,12 @@ void Walk::transformer(const void* x, void* y) {
       a.ctx = atw(ctx_all, r0 * d); a.ldc = d; a.sc_b = S * d;
       a.batch = sg.nb; a.sq = sg.ns; a.sk = S; a.heads = m.heads; a.head_dim = m.head_dim;
       a.causal = m.causal; a.q_offset = sg.s0;
-      attention(a);
+      if (stored_scores) {
+        a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1;
+        attention_materialized(a);
+      } else {
+        attention(a);
+      }
     });
 
     // ---- region 2b: output projection + residual
@@ -771,6 +824,8 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
 
+  if ((m.flags & AC_FLAG_MATERIALIZED_SCORES) && m.workload != AC_TRANSFORMER_STACK)
+    return fail(AC_ERR_UNSUPPORTED, "AC_FLAG_MATERIALIZED_SCORES applies to the transformer stack only");
   if (m.flags & AC_FLAG_LISTED_REGIONS_ONLY) {
     if (m.workload != AC_PAIR_STACK) return fail(AC_ERR_ARG, "AC_FLAG_LISTED_REGIONS_ONLY applies to the pair stack only");
     if (n_regions < 1) return fail(AC_ERR_ARG, "AC_FLAG_LISTED_REGIONS_ONLY needs at least one region");
@@ -1137,6 +1192,15 @@ int ac_op_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y
       (op != 0 && op != 1))
     return fail(AC_ERR_ARG, "ac_op_binary: bad argument");
   return hip_status(launch_binary(a, lda, b, ldb, y, ldy, rows, cols, op, dtype, (hipStream_t)stream), "binary");
+}
+
+int ac_op_softmax_rows(const void* s, int64_t lds, void* p, int64_t ldp, int64_t rows, int64_t cols, float scale,
+                       int causal, int64_t q_offset, int64_t period, int dtype, void* stream) {
+  if (!s || !p || rows < 0 || cols < 1 || lds < cols || ldp < cols || !(scale > 0.f) || q_offset < 0 || period < 1 ||
+      !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_softmax_rows: bad argument");
+  return hip_status(launch_softmax_rows(s, lds, p, ldp, rows, cols, scale, causal != 0, q_offset, period, dtype,
+                                        (hipStream_t)stream), "softmax_rows");
 }
 
 int ac_op_transpose(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows, int64_t cols, int dtype,

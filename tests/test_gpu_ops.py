@@ -229,3 +229,31 @@ def test_bf16_store_rounds_to_nearest_even(B):
     torch.cuda.synchronize()
     want = I.round_to_bf16(hi.astype(np.float32) + lo.astype(np.float32))
     assert np.array_equal(y.float().cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols,period,q_offset,causal", [
+    (12, 100, 4, 0, False), (12, 100, 4, 96, True), (6, 1000, 3, 10, True), (8, 8, 8, 0, True),
+    (5, 4097, 5, 4000, True), (3, 1, 3, 0, True),
+])
+def test_softmax_rows(B, dtype, rows, cols, period, q_offset, causal):
+    """Stored scores -> stored probabilities; row r is query r mod period at position q_offset +
+    (r mod period); masked columns get exactly 0.  In place as well."""
+    import torch
+    s = draw((rows, cols), 70, dtype, 3.0)
+    scale = 0.37
+    ds = dev(B, s, dtype)
+    p = torch.full_like(ds, float("nan"))
+    B.ac_op_softmax_rows(ds, p, scale, causal=causal, q_offset=q_offset, period=period)
+    torch.cuda.synchronize()
+    z = s.astype(np.float64) * scale
+    if causal:
+        pos = q_offset + np.arange(rows) % period
+        z = np.where(np.arange(cols)[None, :] <= pos[:, None], z, -np.inf)
+    ref = O.softmax_rows(z)
+    got = host(p)
+    assert rel_err(got, ref) <= TOL[dtype]
+    assert (got[ref == 0] == 0).all()
+    B.ac_op_softmax_rows(ds, ds, scale, causal=causal, q_offset=q_offset, period=period)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(ds), got)

@@ -186,3 +186,33 @@ def test_two_segments_in_flight_equals_sequential(B):
     ya, _ = r32.run(regions(B, 33, 77, 50))
     yb, _ = r32.run(regions(B, 33, 77, 50), flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
     assert torch.equal(ya, yb)
+
+
+@pytest.mark.parametrize("dtype,causal", [("f32", False), ("f32", True), ("bf16", True), ("bf16", False)])
+def test_stored_scores_plans_equal_the_oracle(B, dtype, causal):
+    """AC_FLAG_MATERIALIZED_SCORES: scores and probabilities are stored tensors of the segment, as
+    in an unfused graph.  Same function as the fused kernel: oracle parity for one segment and
+    for ragged segments, batch chunks included; close to the fused plan's output; the measured
+    peak is the planned one and grows with the segment length as the paper's second activation
+    equation says."""
+    import torch
+    cfg = I.TransformerConfig("tss", 41, 2, 320, 128, 4, 256, causal, dtype, 0.05 if dtype == "bf16" else None, batch=2)
+    r = Runner(B, cfg, bias_std=0.1, ln_jitter=0.1)
+    ref = r.oracle()
+    flag = B.AC_FLAG_MATERIALIZED_SCORES
+    y_fused, _ = r.run(regions(B, 320, 320, 320))
+    peaks = []
+    for c in (320, 128, 72):
+        y, info = r.run(regions(B, 320, c, 320, c_out=320), flags=flag)
+        assert rel_err(host(y), ref) <= TOL[dtype]
+        assert rel_err(host(y), host(y_fused)) <= TOL[dtype]
+        peaks.append(info.workspace_bytes)
+    assert peaks[0] > peaks[1] > peaks[2]
+    e = 2 if dtype == "bf16" else 4
+    # whole minus 128-row segments: at least the scores + probabilities of (320 - 128) rows
+    assert peaks[0] - peaks[1] >= 2 * cfg.heads * (320 - 128) * 320 * e
+    # chunked along the batch: one problem per segment
+    y, info = r.run(regions(B, 1, 1, 1, dim=B.AC_DIM_BATCH), flags=flag)
+    assert rel_err(host(y), ref) <= TOL[dtype]
+    y2, _ = r.run(regions(B, 1, 1, 1, dim=B.AC_DIM_BATCH), flags=flag | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
+    assert torch.equal(y, y2)

@@ -49,7 +49,7 @@ def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
     return max(1, min((512 if dh > 64 else 768) // blocks, sk // 512, 16))
 
 
-def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None):
+def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None, stored_scores=False):
     """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], context (Td), h (Td),
     inter-layer t (Td if layers > 1), plus the largest per-segment set: u (c d) | fp32 split
     partials of the attention (ns c H (d_h + 2) floats) | nothing for the output projection
@@ -58,6 +58,8 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None)
     e = 2 if cfg.dtype == "bf16" else 4
     T, d, F = cfg.seq * cfg.batch, cfg.d_model, cfg.d_ffn
     whole = (al(T * 2 * d * e) + al(T * d * e)) if cfg.dtype == "bf16" else al(T * 3 * d * e)
+    if stored_scores and cfg.dtype != "bf16":
+        whole += al(T * d * e)             # v transposed, which the bf16 layout has anyway
     whole += 2 * al(T * d * e)
     if cfg.layers > 1:
         whole += al(T * d * e)
@@ -65,6 +67,8 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None)
     ns = key_splits_by_hand(c_attn, cfg.seq, cfg.heads, 1, cfg.head_dim, cfg.dtype)
     parts = (al(ns * c_attn * d * 4) + al(ns * c_attn * cfg.heads * 8)) if ns > 1 else 0
     r2 = parts
+    if stored_scores:                      # scores and probabilities of one segment, every head
+        r2 = 2 * al(cfg.heads * c_attn * cfg.seq * e)
     r2b = al(c_out * d * e) if unfused else 0
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
     # two segments in flight: a region with more than one segment holds two per-segment sets
@@ -119,6 +123,23 @@ def test_two_segments_in_flight_doubles_the_per_segment_sets():
     info = p.ac_plan_query()
     assert [r.n_segments for r in info.regions[:4]] == [1, 5, 1, 1]
     assert info.workspace_bytes == arena_by_hand(I.C2, 8192, 1792, 8192, c_out=8192)
+
+
+def test_stored_scores_hold_what_the_paper_counts():
+    """With AC_FLAG_MATERIALIZED_SCORES the attention core's share of the workspace is the
+    intermediate activation of the paper's equations: scores and probabilities, H c S elements
+    each, for the rows of one segment (AutoChunk section 2.1 and 2.2)."""
+    for cfg, c in ((I.C1, (256, 64, 256)), (I.C1, (256, 256, 256)), (I.C3, (4096, 512, 4096)), (I.C2, (8192, 1792, 8192))):
+        e = 2 if cfg.dtype == "bf16" else 4
+        p = B.Plan(B.transformer_desc(cfg, flags=B.AC_FLAG_MATERIALIZED_SCORES), regions(*c, c_out=cfg.seq))
+        info = p.ac_plan_query()
+        assert info.workspace_bytes == arena_by_hand(cfg, *c, c_out=cfg.seq, stored_scores=True)
+        a = M.attention_region(cfg.seq, cfg.d_model, cfg.heads, e, c[1]) - 5 * cfg.seq * cfg.d_model * e
+        assert a == 2 * cfg.heads * min(c[1], cfg.seq) * cfg.seq * e
+        # the model's peak and the chunk lengths a budget gives do not depend on the flag
+        q = B.Plan(B.transformer_desc(cfg), regions(*c, c_out=cfg.seq)).ac_plan_query()
+        assert info.peak_bytes_model == q.peak_bytes_model
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.pair_desc(I.C4, flags=B.AC_FLAG_MATERIALIZED_SCORES), []))
 
 
 def test_unfused_flag_adds_the_temporaries():
