@@ -16,12 +16,16 @@ when (rules 1 to 4 of section 3.3)
        by the per-op flow rules below; `run_chunked` checks it by brute force);
   3    the flow reaches at least one input of the region without interruption;
   4    every node of the region is passed by the flow, with one setting each
-       (a node reached twice must be reached in the same dimension).
+       (a node reached twice must be reached in the same dimension, and a node
+       that some consumer inside the region reads whole has no setting at all:
+       every segment would have to compute all of it).  An input of the region
+       may be read both ways, cut by one operand and whole by another.
 
 Section 3.3 also bounds the work: only regions inside a window of k nodes that
-holds the peak node are tried, and a region is searched in full only if a cheap
-first test passes (here: some input of the region has a dimension of the
-output dimension's extent).
+holds the peak node are tried, and a region is searched in full only if a
+cheaper first test passes: does any flow lead from the output dimension to an
+input of the region at all (followed without the checks of rule 4, and given up
+as soon as one input is reached).  A legal chunk always passes it.
 
 This module holds the op table (flow of a dimension through each op kind), the
 search, and a numpy executor that runs a region chunked, so that tests can
@@ -112,6 +116,18 @@ def granule(node: Node, c: int) -> int:
     return 1
 
 
+def chunk_granule(nodes, end: int, out_dim: int, node_dims, input_dims) -> int:
+    """Smallest chunk length along out_dim for which every tensor on the flow is cut between
+    whole elements: the cut dims all have extents proportional to the output's (a segment of
+    len elements of the output is len * ext / ext_out elements of a tensor whose cut dim has
+    extent ext), so len must make each of those an integer."""
+    ext_out = nodes[end].shape[out_dim]
+    g = 1
+    for i, d in list(node_dims.items()) + list(input_dims.items()):
+        g = math.lcm(g, ext_out // math.gcd(ext_out, nodes[i].shape[d]))
+    return g
+
+
 def trace(nodes, start: int, end: int, out_dim: int):
     """Chunk dims of every node of region [start, end] for a flow that leaves in `out_dim`
     of node `end`, or None when a rule is violated.  Returns (node_dims, input_dims) with
@@ -136,6 +152,8 @@ def trace(nodes, start: int, end: int, out_dim: int):
                 if kind == BROKEN:
                     return None                      # interrupted flow
                 if kind == WHOLE:
+                    if s in inside:
+                        return None                  # rule 4: that node would be needed whole by every segment
                     continue
                 if s in inside:
                     if s in dims:
@@ -156,6 +174,24 @@ def trace(nodes, start: int, end: int, out_dim: int):
     return dims, xin
 
 
+def some_flow_reaches_an_input(nodes, start: int, end: int, out_dim: int) -> bool:
+    """First stage of the two-stage search: is there any uninterrupted flow from `out_dim` of
+    node `end` to a node outside the region?  No rule is checked on the way."""
+    todo, seen = [(end, out_dim)], {(end, out_dim)}
+    while todo:
+        n, c = todo.pop()
+        for which, s in enumerate(nodes[n].inputs):
+            kind, d = flow_to_input(nodes[n], nodes, c, which)
+            if kind != FLOW:
+                continue
+            if s < start:
+                return True
+            if (s, d) not in seen:
+                seen.add((s, d))
+                todo.append((s, d))
+    return False
+
+
 def region_inputs(nodes, start, end):
     inside = set(range(start, end + 1))
     return sorted({s for i in inside for s in nodes[i].inputs if s not in inside})
@@ -172,12 +208,9 @@ def search(nodes, peak: int, window: int):
         for end in range(peak, min(len(nodes), start + window)):
             if any(nodes[i].op in (INPUT, PARAM) for i in range(start, end + 1)):
                 continue
-            ins = region_inputs(nodes, start, end)
             for d in range(len(nodes[end].shape)):
                 tried += 1
-                ext = nodes[end].shape[d]
-                # first stage: some input has a dimension of that extent
-                if not any(ext in nodes[s].shape for s in ins):
+                if not some_flow_reaches_an_input(nodes, start, end, d):
                     continue
                 passed += 1
                 t = trace(nodes, start, end, d)
@@ -237,7 +270,7 @@ def run(nodes, feeds):
     return val
 
 
-def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_len):
+def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_len, parts_too=False):
     """Output of region [start, end] computed segment by segment (section 2.2): the chunkable
     inputs are cut along their traced dims, the others are used whole, the parts of the
     output are concatenated along out_dim.  `val` holds the unchunked values of the inputs."""
@@ -246,17 +279,23 @@ def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_le
     for a in range(0, extent, chunk_len):
         b = min(extent, a + chunk_len)
         frac0, frac1 = a / extent, b / extent
-        local = {}
+        local, cut = {}, {}
         for s in region_inputs(nodes, start, end):
             x = val[s]
             if s in input_dims:
                 d = input_dims[s]
                 lo, hi = round(frac0 * x.shape[d]), round(frac1 * x.shape[d])
-                x = np.take(x, range(lo, hi), axis=d)
-            local[s] = x
+                cut[s] = np.take(x, range(lo, hi), axis=d)
         for i in range(start, end + 1):
             nd = nodes[i]
-            args = [local[s] for s in nd.inputs]
+            args = []
+            for which, s in enumerate(nd.inputs):
+                if s in local:
+                    args.append(local[s])
+                elif flow_to_input(nd, nodes, node_dims[i], which)[0] == FLOW:
+                    args.append(cut[s])         # X^c: this operand takes the segment's part
+                else:
+                    args.append(val[s])         # X^nc: this operand takes the input whole
             if nd.op == SPLIT_DIM:      # the cut dim's outer factor shrinks with the segment
                 p, outer = nd.attr
                 inner = nodes[nd.inputs[0]].shape[p] // outer
@@ -265,7 +304,8 @@ def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_le
             else:
                 local[i] = _apply(nd, args)
         parts.append(local[end])
-    return np.concatenate(parts, axis=out_dim)
+    whole = np.concatenate(parts, axis=out_dim)
+    return (whole, parts) if parts_too else whole
 
 
 # --------------------------------------------------------------------------------------
