@@ -75,8 +75,10 @@ typedef enum ac_region_kind {
  * [batch, sequence(query), feature, head_dim, key]; pair regions as [row i, column j,
  * channel, contraction index k].  Legal (section 3.3: no node of the region reduces over
  * the dim): batch and sequence for every transformer region; row and column for every
- * pair region.  Feature, head_dim, key, channel and contraction index are illegal.  Column
- * chunks are legal but not implemented (AC_ERR_UNSUPPORTED). */
+ * pair region; feature for the attention region (whole heads) and the output projection
+ * (blocks of output columns).  Otherwise feature, head_dim, key, channel and contraction
+ * index are illegal.  Column chunks and the two legal feature chunks are not implemented
+ * (AC_ERR_UNSUPPORTED). */
 enum { AC_DIM_BATCH = 0, AC_DIM_SEQ = 1, AC_DIM_FEATURE = 2, AC_DIM_HEAD_DIM = 3, AC_DIM_KEY = 4 };
 enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 };
 

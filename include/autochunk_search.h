@@ -1,0 +1,101 @@
+/*
+ * Chunk search on a small op graph: which runs of nodes can be executed segment by segment,
+ * and along which dimension (AutoChunk, section 3.3: chunk flow, the four rules, the
+ * bottom-up breadth-first search with its local window and first-stage filter).
+ *
+ * Host code only: no device memory, no HIP call.  Same library and status codes as
+ * autochunk_rt.h.  The executor of autochunk_rt.h works on fixed region kinds; this pass is
+ * the general form of its legality table (a region kind and a chunk dimension the executor
+ * accepts is a legal chunk of the corresponding graph here).
+ */
+#ifndef AUTOCHUNK_SEARCH_H
+#define AUTOCHUNK_SEARCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AC_GRAPH_MAX_RANK 6
+#define AC_GRAPH_MAX_INPUTS 3
+
+/*
+ * Op kinds and how a chunk flow passes them (output dimension c -> dimension of each input;
+ * "whole": the input has no such dimension and is used whole by every segment; "interrupted":
+ * the dimension is computed over, so no flow passes).
+ *   INPUT, PARAM       leaves (activations from outside, parameters); never inside a region
+ *   LINEAR             x [.., K], w [N, K], optional bias [N] -> [.., N].  c < last: x in c, w and
+ *                      bias whole.  c = last: x whole, w and bias in dim 0.
+ *   MATMUL_NT / _NN    a [.., M, K], b [.., N, K] / [.., K, N] -> [.., M, N].  Leading dims: both
+ *                      in c.  M: a in c, b whole.  N: a whole, b in its N dim.
+ *   ELEMENTWISE        any arity, trailing dims aligned, size-1 dims broadcast: an input is in
+ *                      the aligned dim, or whole where it lacks or broadcasts it
+ *   NORM_LAST, SOFTMAX_LAST   over the last dim: interrupted there, otherwise input 0 in c;
+ *                      inputs 1, 2 (gain, shift) whole
+ *   TRANSPOSE          attr = permutation: input in attr[c]
+ *   SPLIT_DIM          attr = {p, outer}: [.., A*B, ..] -> [.., A, B, ..].  c = p (outer factor):
+ *                      input in p; c = p + 1 (inner factor): interrupted; others shift
+ *   MERGE_DIMS         attr = {p, inner}: [.., A, B, ..] -> [.., A*B, ..].  c = p: input in p,
+ *                      chunk lengths must be multiples of B (the candidate's granule)
+ *   SLICE_LAST         attr = {first, past}: a fixed range of the last dim; interrupted along
+ *                      it, otherwise input in c
+ *   CONTRACT_IKC_JKC   a [I, K, C], b [J, K, C] -> [I, J, C] (the triangle update): c = 0: a in
+ *                      0, b whole; c = 1: a whole, b in 0; c = 2: both in 2
+ */
+typedef enum ac_graph_op {
+  AC_OP_INPUT = 0, AC_OP_PARAM = 1, AC_OP_LINEAR = 2, AC_OP_MATMUL_NT = 3, AC_OP_MATMUL_NN = 4,
+  AC_OP_ELEMENTWISE = 5, AC_OP_NORM_LAST = 6, AC_OP_SOFTMAX_LAST = 7, AC_OP_TRANSPOSE = 8,
+  AC_OP_SPLIT_DIM = 9, AC_OP_MERGE_DIMS = 10, AC_OP_SLICE_LAST = 11, AC_OP_CONTRACT_IKC_JKC = 12,
+  AC_OP_KINDS = 13
+} ac_graph_op;
+
+/* Nodes are listed in a topological order: inputs[] hold indices of earlier nodes. */
+typedef struct ac_graph_node {
+  int32_t op;
+  int32_t n_inputs;
+  int32_t inputs[AC_GRAPH_MAX_INPUTS];
+  int32_t rank;
+  int64_t shape[AC_GRAPH_MAX_RANK];
+  int64_t attr[AC_GRAPH_MAX_RANK];
+} ac_graph_node;
+
+typedef struct ac_chunk_candidate {
+  int32_t start, end;   /* the region: nodes start .. end of the list */
+  int32_t out_dim;      /* dimension of node `end` the segments are concatenated along */
+  int32_t granule;      /* chunk lengths must be multiples of this */
+} ac_chunk_candidate;
+
+/*
+ * Traces the chunk flow that leaves region [start, end] in dimension out_dim of node `end`
+ * (section 3.3, rules 1 to 4): the region's only value used outside must be node `end`'s; the
+ * flow must pass every node of the region, each in one dimension only (so no node of the
+ * region may be read whole by another), meet no interrupted dimension, and reach at least
+ * one input of the region.  An input may be cut for one operand and read whole by another.
+ * *legal = 1 or 0.  node_dims
+ * (n_nodes entries, caller's) receives, for a legal chunk, the chunk dimension of every node
+ * of the region and, for every node outside it that the region reads, the dimension in
+ * which that input is cut, or -1 (not part of the chunk; input used whole).
+ * Returns AC_OK, or AC_ERR_ARG for a malformed graph or region (then *legal is 0).
+ */
+int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
+                   int32_t* node_dims, int* legal);
+
+/*
+ * All legal chunks whose region holds node `peak` and spans at most `window` nodes (the
+ * local window of section 3.3, "complexity optimization").  A (region, dimension) pair is
+ * traced in full only if some uninterrupted flow leads from that dimension to an input of the
+ * region at all (first stage: no rule checked, stopped at the first input reached).  Candidates are written in order of start, end, out_dim; out (max_out entries)
+ * and node_dims (max_out * n_nodes entries, one ac_chunk_trace row per candidate) are the
+ * caller's; either may be NULL with max_out = 0 to count only.  *n_found counts all legal
+ * chunks even beyond max_out; n_tried / n_passed (may be NULL) count the pairs tried and
+ * those that passed the first stage.
+ */
+int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window,
+                    ac_chunk_candidate* out, int32_t* node_dims, int max_out,
+                    int* n_found, int* n_tried, int* n_passed);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -69,9 +69,25 @@ class ac_kernel_stat(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
-I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
+AC_GRAPH_MAX_RANK, AC_GRAPH_MAX_INPUTS = 6, 3
+(AC_OP_INPUT, AC_OP_PARAM, AC_OP_LINEAR, AC_OP_MATMUL_NT, AC_OP_MATMUL_NN, AC_OP_ELEMENTWISE, AC_OP_NORM_LAST,
+ AC_OP_SOFTMAX_LAST, AC_OP_TRANSPOSE, AC_OP_SPLIT_DIM, AC_OP_MERGE_DIMS, AC_OP_SLICE_LAST, AC_OP_CONTRACT_IKC_JKC,
+ AC_OP_KINDS) = range(14)
 
-# name -> (restype, argtypes): every symbol include/autochunk_rt.h declares.
+
+class ac_graph_node(C.Structure):
+    _fields_ = [("op", C.c_int32), ("n_inputs", C.c_int32), ("inputs", C.c_int32 * AC_GRAPH_MAX_INPUTS),
+                ("rank", C.c_int32), ("shape", C.c_int64 * AC_GRAPH_MAX_RANK), ("attr", C.c_int64 * AC_GRAPH_MAX_RANK)]
+
+
+class ac_chunk_candidate(C.Structure):
+    _fields_ = [("start", C.c_int32), ("end", C.c_int32), ("out_dim", C.c_int32), ("granule", C.c_int32)]
+
+
+I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
+I32P, INTP = C.POINTER(C.c_int32), C.POINTER(C.c_int)
+
+# name -> (restype, argtypes): every symbol the headers under include/ declare.
 SIGNATURES = {
     "ac_plan_create": (INT, [C.POINTER(ac_model_desc), C.POINTER(ac_region_desc), INT, U64, C.POINTER(VP)]),
     "ac_plan_query": (INT, [VP, C.POINTER(ac_plan_info)]),
@@ -97,6 +113,9 @@ SIGNATURES = {
     "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose_square_inplace": (INT, [VP, I64, I64, I64, I64, INT, VP]),
     "ac_op_layernorm_channel_major": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
+    "ac_chunk_trace": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, I32P, INTP]),
+    "ac_chunk_search": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, C.POINTER(ac_chunk_candidate), I32P, INT,
+                              INTP, INTP, INTP]),
 }
 
 _lib = None
@@ -345,3 +364,48 @@ def to_device(arr, dtype: str):
 def empty_workspace(nbytes: int):
     import torch
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+# ------------------------------------------------------------------------------------------
+# chunk search (host only)
+# ------------------------------------------------------------------------------------------
+
+def graph_nodes(spec):
+    """ac_graph_node array from a list of (op, inputs, shape, attr) tuples."""
+    arr = (ac_graph_node * len(spec))()
+    for nd, (op, inputs, shape, attr) in zip(arr, spec):
+        if len(inputs) > AC_GRAPH_MAX_INPUTS or len(shape) > AC_GRAPH_MAX_RANK or len(attr) > AC_GRAPH_MAX_RANK:
+            raise ValueError("node exceeds AC_GRAPH_MAX_INPUTS / AC_GRAPH_MAX_RANK")
+        nd.op, nd.n_inputs, nd.rank = op, len(inputs), len(shape)
+        for i, v in enumerate(inputs):
+            nd.inputs[i] = v
+        for i, v in enumerate(shape):
+            nd.shape[i] = v
+        for i, v in enumerate(attr):
+            nd.attr[i] = v
+    return arr
+
+
+def ac_chunk_trace(nodes, start, end, out_dim):
+    """Chunk dims per node (list, -1 = not cut) of a legal chunk, or None."""
+    row = (C.c_int32 * len(nodes))()
+    legal = C.c_int(0)
+    _check(lib().ac_chunk_trace(nodes, len(nodes), start, end, out_dim, row, C.byref(legal)), "ac_chunk_trace")
+    return list(row) if legal.value else None
+
+
+def ac_chunk_search(nodes, peak, window, max_out=None):
+    """(candidates, n_found, n_tried, n_passed); a candidate is (start, end, out_dim, granule, node_dims)."""
+    n = len(nodes)
+    found, tried, passed = C.c_int(0), C.c_int(0), C.c_int(0)
+    if max_out is None:
+        _check(lib().ac_chunk_search(nodes, n, peak, window, None, None, 0, C.byref(found), None, None),
+               "ac_chunk_search")
+        max_out = found.value
+    out = (ac_chunk_candidate * max(max_out, 1))()
+    rows = (C.c_int32 * (max(max_out, 1) * n))()
+    _check(lib().ac_chunk_search(nodes, n, peak, window, out, rows, max_out, C.byref(found), C.byref(tried),
+                                 C.byref(passed)), "ac_chunk_search")
+    cands = [(c.start, c.end, c.out_dim, c.granule, list(rows[i * n:(i + 1) * n]))
+             for i, c in enumerate(out[:min(max_out, found.value)])]
+    return cands, found.value, tried.value, passed.value

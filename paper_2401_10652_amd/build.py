@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libautochunk_rt.so"
 LIB_PATH = os.path.join(HERE, LIB_NAME)
 
-SOURCES = ["rowwise.hip", "linear.hip", "attention.hip", "runtime.hip"]
+SOURCES = ["rowwise.hip", "linear.hip", "attention.hip", "runtime.hip", "search.hip"]
 
 # Per-file extras.  attention.hip: keep MFMA results in VGPRs; the softmax reads every score
 # right after the matrix op, and accumulator-register copies would double its VALU work.

@@ -850,6 +850,13 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     }
     Setting& s = p->set[r.kind];
     if (s.present) { delete p; return fail(AC_ERR_ARG, "region kind %d listed twice (one chunk setting per region)", r.kind); }
+    // The feature dim of the context and of the output projection can be cut (whole heads;
+    // blocks of output columns): no node of those regions reduces over it.  No kernel here does.
+    if (m.workload == AC_TRANSFORMER_STACK && r.chunk_dim == AC_DIM_FEATURE &&
+        (r.kind == AC_REGION_ATTENTION || r.kind == AC_REGION_OUT_PROJ)) {
+      delete p;
+      return fail(AC_ERR_UNSUPPORTED, "feature chunks of region %d are legal but not implemented", r.kind);
+    }
     bool known;
     if (!dim_legal(m, r.chunk_dim, known)) {
       delete p;

@@ -1,0 +1,181 @@
+"""Chunk search of the library (ac_chunk_trace, ac_chunk_search; AutoChunk section 3.3) against
+the oracle's, candidate by candidate, on the transformer block graph and on seeded random
+graphs; plus brute-force pins of the oracle on those random graphs.  Host code only."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import chunk_search as S
+from paper_2401_10652_amd import binding as B
+from tests import graphs as G
+
+
+def oracle_nodes(spec):
+    return [S.Node(op, inputs, shape, attr, G.FNS.get(fn)) for op, inputs, shape, attr, fn in spec]
+
+
+def library_nodes(spec):
+    return B.graph_nodes([(op, inputs, shape, attr) for op, inputs, shape, attr, _ in spec])
+
+
+def block_spec(batch=2, seq=12, d=8, heads=2, f=16):
+    nodes, names = S.transformer_block_graph(batch, seq, d, heads, f)
+    return [(nd.op, nd.inputs, nd.shape, nd.attr, None) for nd in nodes], names
+
+
+def oracle_candidates(nodes, peak, window):
+    cands, tried, passed = S.search(nodes, peak, window)
+    out = []
+    for start, end, dim, node_dims, input_dims in cands:
+        row = [-1] * len(nodes)
+        for i, d in list(node_dims.items()) + list(input_dims.items()):
+            row[i] = d
+        out.append((start, end, dim, S.chunk_granule(nodes, end, dim, node_dims, input_dims), row))
+    return out, tried, passed
+
+
+def compare_everywhere(spec, windows):
+    on, ln = oracle_nodes(spec), library_nodes(spec)
+    total = 0
+    for peak in range(len(spec)):
+        for w in windows:
+            want, tried, passed = oracle_candidates(on, peak, w)
+            got, n_found, n_tried, n_passed = B.ac_chunk_search(ln, peak, w)
+            assert (n_tried, n_passed, n_found) == (tried, passed, len(want)), (peak, w)
+            assert got == want, (peak, w)
+            total += len(want)
+    return total
+
+
+def test_search_equals_the_oracle_on_the_transformer_block():
+    spec, _ = block_spec()
+    assert compare_everywhere(spec, (1, 4, 9, len(spec))) > 500
+
+
+def test_search_equals_the_oracle_on_random_graphs():
+    total = 0
+    for seed in range(80):
+        total += compare_everywhere(G.random_graph(seed, n_ops=8 + seed % 7), (1, 3, 6, 40))
+    assert total > 3000
+
+
+def test_trace_equals_the_oracle_on_every_region_and_dim():
+    for seed in (3, 11, 42):
+        spec = G.random_graph(seed, n_ops=9)
+        on, ln = oracle_nodes(spec), library_nodes(spec)
+        first = next(i for i, nd in enumerate(on) if nd.op not in (S.INPUT, S.PARAM))
+        n_legal = 0
+        for start in range(first, len(on)):
+            for end in range(start, len(on)):
+                for d in range(len(on[end].shape)):
+                    want = S.trace(on, start, end, d)
+                    got = B.ac_chunk_trace(ln, start, end, d)
+                    if want is None:
+                        assert got is None, (seed, start, end, d)
+                    else:
+                        assert S.some_flow_reaches_an_input(on, start, end, d)   # the first stage loses no chunk
+                        row = [-1] * len(on)
+                        for i, v in list(want[0].items()) + list(want[1].items()):
+                            row[i] = v
+                        assert got == row, (seed, start, end, d)
+                        n_legal += 1
+        assert n_legal > 10
+
+
+def test_oracle_chunks_of_random_graphs_reproduce_the_unchunked_output():
+    """Pins the oracle (flow table of every op kind, granule) by brute force: each chunk it calls
+    legal, run segment by segment at its granule, gives segments of exactly that length and the
+    unchunked values; a shorter length cuts some tensor inside an element."""
+    n_checked, n_coarse, kinds = 0, 0, set()
+    for seed in range(60):
+        spec = G.random_graph(seed, n_ops=8 + seed % 5)
+        nodes = oracle_nodes(spec)
+        val = S.run(nodes, S.random_feeds(nodes, seed))
+        seen = set()
+        for peak in range(len(nodes)):
+            if nodes[peak].op in (S.INPUT, S.PARAM):
+                continue
+            for start, end, dim, node_dims, input_dims in S.search(nodes, peak, 5)[0]:
+                if (start, end, dim) in seen:
+                    continue
+                seen.add((start, end, dim))
+                g = S.chunk_granule(nodes, end, dim, node_dims, input_dims)
+                extent = nodes[end].shape[dim]
+                assert extent % g == 0
+                for clen in {g, extent}:
+                    got, parts = S.run_chunked(nodes, val, start, end, dim, node_dims, input_dims, clen, parts_too=True)
+                    assert all(p.shape[dim] == clen for p in parts), (seed, start, end, dim, clen)
+                    assert np.allclose(got, val[end], rtol=0, atol=1e-9), (seed, start, end, dim, clen)
+                    n_checked += 1
+                if g > 1:
+                    n_coarse += 1
+                    # at the largest proper divisor of g some cut dim would get a fractional length
+                    small = max(k for k in range(1, g) if g % k == 0)
+                    exts = [nodes[i].shape[d] for i, d in list(node_dims.items()) + list(input_dims.items())]
+                    assert any(small * e % extent for e in exts)
+                kinds.update(nodes[i].op for i in range(start, end + 1))
+    assert n_checked > 1500 and n_coarse > 20
+    assert kinds == set(range(S.LINEAR, S.CONTRACT_IKC_JKC + 1))
+
+
+def test_granule_of_the_head_merge():
+    # context [B, S, H*dh] cut along its features: whole heads only
+    spec, nm = block_spec(heads=2, d=8)
+    ln = library_nodes(spec)
+    got, *_ = B.ac_chunk_search(ln, nm["ctx"], 3)
+    by_key = {(s, e, d): g for s, e, d, g, _ in got}
+    assert by_key[(nm["ctx_h"], nm["ctx"], 2)] == 4
+    assert by_key[(nm["ctx_h"], nm["ctx"], 1)] == 1
+
+
+def test_region_kinds_of_the_executor_are_chunks_of_the_block_graph():
+    """The executor's legality table (batch and sequence legal for every transformer region;
+    feature legal for the attention core and the output projection only, where it is not
+    implemented; head_dim and key never) read off the graph."""
+    spec, nm = block_spec()
+    ln = library_nodes(spec)
+
+    def dims(a, b):
+        return {d for d in range(len(spec[nm[b]][2])) if B.ac_chunk_trace(ln, nm[a], nm[b], d) is not None}
+
+    assert dims("u", "qkv") == {0, 1}
+    assert dims("scores", "ctx") == {0, 1, 2}      # query rows; features in whole heads
+    assert dims("scores", "ctx_h") == {0, 1, 2}    # [B, H, S, dh]: not the head dim
+    assert dims("scaled", "probs") == {0, 1, 2}    # [B, H, S, S]: not the key dim
+    assert dims("o", "h") == {0, 1, 2}
+    assert dims("u2", "y") == {0, 1}
+
+
+def test_count_only_truncation_and_errors():
+    spec, nm = block_spec()
+    ln = library_nodes(spec)
+    full, n_found, _, _ = B.ac_chunk_search(ln, nm["probs"], 6)
+    assert n_found == len(full) > 4
+    part, n_found2, _, _ = B.ac_chunk_search(ln, nm["probs"], 6, max_out=3)
+    assert n_found2 == n_found and part == full[:3]
+    L = B.lib()
+    found = C.c_int(-1)
+    assert L.ac_chunk_search(ln, len(ln), nm["probs"], 6, None, None, 2, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), len(ln), 6, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), 0, 0, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
+    # a peak that is an input: nothing to chunk, no error
+    assert L.ac_chunk_search(ln, len(ln), 0, 4, None, None, 0, C.byref(found), None, None) == B.AC_OK
+    assert found.value == 0
+    with pytest.raises(B.AcError):
+        B.ac_chunk_trace(ln, nm["x"], nm["u"], 0)       # region holds leaves
+    with pytest.raises(B.AcError):
+        B.ac_chunk_trace(ln, nm["u"], nm["qkv"], 3)     # no such dim
+    # malformed graphs: forward reference, bad permutation, shapes that do not fit the op
+    for breaker in ("forward", "perm", "shape", "rank"):
+        bad = library_nodes(spec)
+        if breaker == "forward":
+            bad[nm["u"]].inputs[0] = nm["y"]
+        elif breaker == "perm":
+            bad[nm["q_h"]].attr[1] = 0
+        elif breaker == "shape":
+            bad[nm["scores"]].shape[3] += 1
+        else:
+            bad[nm["probs"]].rank = 7
+        assert L.ac_chunk_search(bad, len(bad), nm["probs"], 6, None, None, 0, C.byref(found), None, None) == \
+            B.AC_ERR_ARG, breaker
