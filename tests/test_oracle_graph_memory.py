@@ -1,0 +1,239 @@
+"""Pins of the graph memory oracle (AutoChunk sections 2.1, 2.2, 3.2, 3.4): its per-node live
+bytes against an executor that really allocates, frees and counts numpy arrays; the closed
+forms M = X + Y + A and M = X + Y + A / n on the attention core; hand-counted costs; and the
+properties the pass loop must have (fits, legal, disjoint, no chunk shorter than needed)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import chunk_search as S
+from oracle import graph_memory as GM
+from tests import graphs as G
+
+
+def oracle_nodes(spec):
+    return [S.Node(op, inputs, shape, attr, G.FNS.get(fn)) for op, inputs, shape, attr, fn in spec]
+
+
+def owned(a):
+    return np.array(a, dtype=np.float64, order="C", copy=True)
+
+
+def counted_run(nodes, feeds, chunks=()):
+    """Runs the graph, chunked regions segment by segment, holding every tensor in a dict from
+    the moment it is made to the moment its last reader is done; returns, per node, the largest
+    number of bytes the dict held while that node ran (float64 arrays: 8 bytes an element)."""
+    n = len(nodes)
+    last = [-1] * n
+    for i, nd in enumerate(nodes):
+        for s in nd.inputs:
+            last[s] = i
+    live = {i: owned(feeds[i]) for i, nd in enumerate(nodes) if nd.op == S.INPUT and last[i] >= 0}
+    params = {i: feeds[i] for i, nd in enumerate(nodes) if nd.op == S.PARAM}
+    seen = [0] * n
+    region_at = {c[0]: c for c in chunks}
+
+    def get(i):
+        return params[i] if i in params else live[i]
+
+    def total(*dicts):
+        return sum(a.nbytes for d in dicts for a in d.values())
+
+    i = 0
+    while i < n:
+        nd = nodes[i]
+        if nd.op in (S.INPUT, S.PARAM):
+            i += 1
+            continue
+        if i not in region_at:
+            live[i] = owned(S._apply(nd, [get(s) for s in nd.inputs]))
+            seen[i] = total(live)
+            for j in [j for j in live if last[j] == i]:
+                del live[j]
+            i += 1
+            continue
+        start, end, dim, clen = region_at[i]
+        node_dims, input_dims = S.trace(nodes, start, end, dim)
+        extent = nodes[end].shape[dim]
+        live[end] = np.empty(nodes[end].shape)                    # Y, whole, written segment by segment
+        for a in range(0, extent, clen):
+            b = min(extent, a + clen)
+            seg = {}
+            for k in range(start, end + 1):
+                kd = nodes[k]
+                args = []
+                for which, s in enumerate(kd.inputs):
+                    if s in seg:
+                        args.append(seg[s])
+                    elif s in params or S.flow_to_input(kd, nodes, node_dims[k], which)[0] != S.FLOW:
+                        x = get(s)
+                        if s in params and S.flow_to_input(kd, nodes, node_dims[k], which)[0] == S.FLOW:
+                            d = input_dims[s]
+                            x = x[(slice(None),) * d + (slice(a * x.shape[d] // extent, b * x.shape[d] // extent),)]
+                        args.append(x)
+                    else:
+                        d = input_dims[s]
+                        x = live[s]
+                        args.append(x[(slice(None),) * d + (slice(a * x.shape[d] // extent, b * x.shape[d] // extent),)])
+                if kd.op == S.SPLIT_DIM:
+                    p, outer = kd.attr
+                    inner = nodes[kd.inputs[0]].shape[p] // outer
+                    sh = args[0].shape
+                    res = args[0].reshape(sh[:p] + (sh[p] // inner, inner) + sh[p + 1:])
+                else:
+                    res = S._apply(kd, args)
+                if k == end:
+                    live[end][(slice(None),) * dim + (slice(a, b),)] = res   # straight into Y
+                    del res
+                else:
+                    seg[k] = owned(res)
+                seen[k] = max(seen[k], total(live, seg))
+                for j in [j for j in seg if last[j] == k]:
+                    del seg[j]
+            assert not seg
+        for j in [j for j in live if start <= last[j] <= end]:
+            del live[j]
+        i = end + 1
+    return seen, live
+
+
+def some_chunks(nodes, rng, how_many=2):
+    """A few disjoint legal chunks with lengths that are granule multiples."""
+    chosen = []
+    peaks = [i for i, nd in enumerate(nodes) if nd.op not in (S.INPUT, S.PARAM)]
+    for _ in range(12):
+        cands = S.search(nodes, int(rng.choice(peaks)), 4)[0]
+        if not cands:
+            continue
+        start, end, dim, nd_, in_ = cands[int(rng.integers(len(cands)))]
+        if any(start <= c[1] and c[0] <= end for c in chosen):
+            continue
+        g = S.chunk_granule(nodes, end, dim, nd_, in_)
+        extent = nodes[end].shape[dim]
+        chosen.append((start, end, dim, g * int(rng.integers(1, extent // g + 1))))
+        if len(chosen) == how_many:
+            break
+    return chosen
+
+
+def test_live_bytes_equal_a_counting_executor():
+    n_regions = 0
+    for seed in range(40):
+        nodes = oracle_nodes(G.random_graph(seed, n_ops=9 + seed % 4))
+        feeds = S.random_feeds(nodes, seed)
+        rng = np.random.default_rng(seed)
+        for chunks in ([], some_chunks(nodes, rng)):
+            mem, peak, peak_node = GM.estimate(nodes, 8, chunks)
+            seen, left = counted_run(nodes, feeds, chunks)
+            assert mem == seen, (seed, chunks)
+            assert peak == max(seen) and peak_node == seen.index(peak)
+            val = S.run(nodes, feeds)
+            for j, a in left.items():           # what is left are the graph's outputs, and they are right
+                assert np.allclose(a, val[j], atol=1e-9)
+            n_regions += len(chunks)
+    assert n_regions > 40
+
+
+def test_attention_core_follows_the_two_activation_equations():
+    batch, seq, d, heads, f, e = 2, 12, 8, 2, 16, 2
+    nodes, nm = S.transformer_block_graph(batch, seq, d, heads, f)
+    dh = d // heads
+    score = batch * heads * seq * seq * e
+    row = batch * seq * d * e
+    mem, peak, peak_node = GM.estimate(nodes, e)
+    # at the softmax: x (for the residual), v_h, scaled and probs are live; q_h and k_h are done
+    assert mem[nm["probs"]] == row + row + 2 * score
+    # at the scaling: x, q.. no: q_h and k_h died at the scores; x, v_h, scores, scaled
+    assert mem[nm["scaled"]] == 2 * row + 2 * score
+    # at the scores: x, q_h, k_h, v_h and the scores
+    assert mem[nm["scores"]] == 4 * row + score
+    # M = X + Y + A with X = {x held for later, q_h, k_h, v_h}, Y = ctx_h, A = two score-sized tensors at most
+    region = (nm["scores"], nm["ctx_h"], 2)
+    whole = max(mem[region[0]:region[1] + 1])
+    assert whole == max(4 * row + score, 2 * row + 2 * score, 2 * row + score + row)
+    for n_seg in (2, 3, 4, 12):
+        clen = seq // n_seg
+        m2, _, _ = GM.estimate(nodes, e, [region + (clen,)])
+        got = max(m2[region[0]:region[1] + 1])
+        # X (x, q_h, k_h, v_h: all held to the region's end) + Y + A / n
+        assert got == 4 * row + row + 2 * score // n_seg
+    assert dh == 4
+
+
+def test_cost_terms_by_hand():
+    nodes, nm = S.transformer_block_graph(2, 12, 8, 2, 16)
+    B_, H, Sq, dh = 2, 2, 12, 4
+    s, e = nm["scores"], nm["ctx_h"]
+    flops = 2 * B_ * H * Sq * Sq * dh + B_ * H * Sq * Sq + 5 * B_ * H * Sq * Sq + 2 * B_ * H * Sq * dh * Sq
+    assert sum(GM.node_flops(nodes[i], nodes) for i in range(s, e + 1)) == flops
+    assert GM.chunk_cost(nodes, s, e, 2, (1, 0, 0, 0)) == 4                  # N_node
+    assert GM.chunk_cost(nodes, s, e, 2, (0, 1, 0, 0)) == flops              # N_flop
+    assert GM.chunk_cost(nodes, s, e, 2, (0, 0, 1, 0)) == flops / 4          # N_density
+    assert GM.chunk_cost(nodes, s, e, 2, (0, 0, 0, 1)) == dh                 # stride of the query dim of [B,H,S,dh]
+    assert GM.chunk_cost(nodes, s, e, 0, (0, 0, 0, 1)) == H * Sq * dh        # stride of the batch dim
+    assert GM.node_flops(nodes[nm["qkv"]], nodes) == 2 * B_ * Sq * 24 * 8
+    assert GM.node_flops(nodes[nm["u"]], nodes) == 8 * B_ * Sq * 8
+    assert GM.node_flops(nodes[nm["q_h"]], nodes) == 0
+
+
+def check_plan(nodes, e, budget, window, weights, feeds):
+    chunks, peak = GM.plan(nodes, e, budget, window, weights)
+    seen, _ = counted_run(nodes, feeds, chunks)
+    assert max(seen) * e // 8 == peak <= budget
+    for k, (start, end, dim, clen) in enumerate(chunks):
+        t = S.trace(nodes, start, end, dim)
+        assert t is not None
+        g = S.chunk_granule(nodes, end, dim, *t)
+        extent = nodes[end].shape[dim]
+        assert clen % g == 0 and 0 < clen < extent
+        assert all(end < c[0] or c[1] < start for c in chunks[:k])
+        # one granule longer and the region no longer fits (or the chunk would be no chunk)
+        if clen + g < extent:
+            longer = chunks[:k] + [(start, end, dim, clen + g)]
+            seen2, _ = counted_run(nodes, feeds, longer)
+            assert max(seen2[start:end + 1]) * e // 8 > budget
+    return chunks
+
+
+def test_pass_loop_on_the_block_graph():
+    # a block whose scores (and feed-forward hidden rows) dominate, as at long sequences
+    nodes, nm = S.transformer_block_graph(2, 32, 8, 2, 64)
+    feeds = S.random_feeds(nodes, 0)
+    e = 8
+    row, score, hidden = 2 * 32 * 8 * e, 2 * 2 * 32 * 32 * e, 2 * 32 * 64 * e
+    mem, whole, peak_node = GM.estimate(nodes, e)
+    assert (whole, peak_node) == (2 * row + 2 * score, nm["scaled"])
+    assert mem[nm["act"]] == row + 2 * hidden
+    assert GM.plan(nodes, e, whole, 8, (1, 0, 0, 0)) == ([], whole)           # fits: nothing to do
+    # 40000 bytes: the scores must be cut, then the hidden rows of the feed-forward: two passes,
+    # each around its own peak; by node count alone short regions win
+    chunks = check_plan(nodes, e, 40000, 8, (1, 0, 0, 0), feeds)
+    assert len(chunks) == 2
+    assert nm["scores"] <= chunks[0][0] and chunks[0][1] <= nm["ctx"] and chunks[0][0] <= nm["scaled"] <= chunks[0][1]
+    assert nm["u2"] <= chunks[1][0] and chunks[1][1] <= nm["y"] and chunks[1][0] <= nm["act"] <= chunks[1][1]
+    # the floor: x, the packed projection and the head views around k are live together outside any chunk
+    floor = mem[nm["k_split"]]
+    assert floor == 7 * row
+    check_plan(nodes, e, floor, 8, (1, 0, 0, 0), feeds)
+    with pytest.raises(ValueError):
+        GM.plan(nodes, e, floor - 1, 8, (1, 0, 0, 0))
+    # weights change the choice: a reward for stride alone prefers the batch dim while that fits
+    by_stride = check_plan(nodes, e, 60000, 8, (0, 0, 0, -1), feeds)
+    assert by_stride[0][2] == 0
+
+
+def test_pass_loop_on_random_graphs():
+    done = several = 0
+    for seed in range(80):
+        nodes = oracle_nodes(G.random_graph(seed, n_ops=10 + seed % 6))
+        feeds = S.random_feeds(nodes, seed)
+        _, whole, _ = GM.estimate(nodes, 8)
+        for frac in (0.9, 0.75, 0.6):
+            try:
+                chunks = check_plan(nodes, 8, int(whole * frac), 5, (1.0, 1e-3, -1e-3, -0.5), feeds)
+            except ValueError:
+                continue
+            done += len(chunks) > 0
+            several += len(chunks) > 1
+    assert done > 20 and several > 3
