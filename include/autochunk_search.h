@@ -3,6 +3,10 @@
  * and along which dimension (AutoChunk, section 3.3: chunk flow, the four rules, the
  * bottom-up breadth-first search with its local window and first-stage filter).
  *
+ * Also: the activation memory of such a graph with and without chunks, the selection cost
+ * of section 3.4, and the loop of passes of section 3.2 that chunks a graph until it fits
+ * a budget.
+ *
  * Host code only: no device memory, no HIP call.  Same library and status codes as
  * autochunk_rt.h.  The executor of autochunk_rt.h works on fixed region kinds; this pass is
  * the general form of its legality table (a region kind and a chunk dimension the executor
@@ -94,6 +98,60 @@ int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, 
 int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window,
                     ac_chunk_candidate* out, int32_t* node_dims, int max_out,
                     int* n_found, int* n_tried, int* n_passed);
+
+/* One chosen chunk: region [start, end], cut along out_dim of node `end` in segments of
+ * chunk_len (the last may be shorter).  reserved is 0. */
+typedef struct ac_graph_chunk {
+  int32_t start, end, out_dim, reserved;
+  int64_t chunk_len;
+} ac_graph_chunk;
+
+/*
+ * Activation bytes live at every node of the graph run with the given chunks (sections 2.1
+ * and 2.2, memory estimation of section 3.4).  Every node's result is a tensor of elem_bytes
+ * per element with storage of its own; parameters are not activations.  A tensor is live
+ * from its node (a graph input: from the start) to its last reader (none: to the end); the
+ * bytes at a node are all tensors live while it runs, M = mem(X) + mem(Y) + mem(A).  Inside
+ * a chunked region, M = mem(X) + mem(Y) + mem(A) / n: the region's result is held whole,
+ * everything live at the region's entry stays live to its end, and the region's own tensors
+ * have chunk_len / extent of their size.
+ * chunks: legal (else AC_ERR_ILLEGAL_CHUNK_DIM), apart from each other, chunk_len a multiple
+ * of the chunk's granule in 1..extent (else AC_ERR_ARG).  node_bytes (n_nodes entries, may
+ * be NULL) receives the bytes per node, 0 for inputs and parameters; *peak_node is the
+ * first node that reaches *peak_bytes.
+ */
+int ac_graph_estimate(const ac_graph_node* nodes, int n_nodes, int elem_bytes,
+                      const ac_graph_chunk* chunks, int n_chunks, uint64_t* node_bytes,
+                      uint64_t* peak_bytes, int* peak_node);
+
+/*
+ * Selection cost of a chunk (section 3.4): L = L_macro + L_micro with
+ * L_macro = weights[0] N_node + weights[1] N_flop, L_micro = weights[2] N_density +
+ * weights[3] N_stride.  N_node: nodes of the region; N_flop: their operations (2 per
+ * multiply-add of LINEAR, MATMUL and CONTRACT; 1 per element of ELEMENTWISE, 5 of
+ * SOFTMAX_LAST, 8 of NORM_LAST; none for the reshaping ops); N_density = N_flop / N_node;
+ * N_stride: elements between neighbours along out_dim in the contiguous result of `end`.
+ * The paper tunes the four weights and prints no values: they are the caller's.
+ */
+int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
+                        const double* weights, double* cost);
+
+/*
+ * Chunks the graph pass by pass until its estimated peak is at most budget_bytes (section
+ * 3.2: estimate, search around the peak node, select; repeated).  One pass: the legal chunks
+ * of ac_chunk_search(peak node, window) that touch no region chosen before get the longest
+ * chunk_len (multiple of the granule, below the extent) at which their region fits the
+ * budget; those with none are dropped; the one of least cost is taken (ties: fewer
+ * segments, then search order).  One candidate per pass, no look-ahead: the paper's search
+ * over whole strategies (dynamic programming with a beam) is not part of this call.
+ * out (max_out entries, caller's) receives the chunks in the order chosen, *n_out their
+ * number, *peak_bytes the estimate with them.  AC_ERR_BUDGET_INFEASIBLE when a pass finds
+ * no candidate (*n_out and *peak_bytes then describe the chunks chosen so far); AC_ERR_ARG
+ * when more than max_out chunks would be needed.
+ */
+int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
+                  int window, const double* weights, ac_graph_chunk* out, int max_out, int* n_out,
+                  uint64_t* peak_bytes);
 
 #ifdef __cplusplus
 }

@@ -67,7 +67,7 @@ def estimate(nodes, elem_bytes, chunks=()):
             continue
         start, end, out_dim, clen = region_of[i]
         extent = nodes[end].shape[out_dim]
-        held = sum(size[j] for j in range(start) if dies[j] >= start)        # X, and whatever lives across
+        held = sum(size[j] for j in range(n) if born[j] < start <= dies[j])   # X, and whatever lives across
         inside = sum(size[j] for j in range(start, i + 1) if j != end and dies[j] >= i)
         assert inside * clen % extent == 0
         mem[i] = held + size[end] + inside * clen // extent                  # X + Y + A / n

@@ -84,6 +84,11 @@ class ac_chunk_candidate(C.Structure):
     _fields_ = [("start", C.c_int32), ("end", C.c_int32), ("out_dim", C.c_int32), ("granule", C.c_int32)]
 
 
+class ac_graph_chunk(C.Structure):
+    _fields_ = [("start", C.c_int32), ("end", C.c_int32), ("out_dim", C.c_int32), ("reserved", C.c_int32),
+                ("chunk_len", C.c_int64)]
+
+
 I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
 I32P, INTP = C.POINTER(C.c_int32), C.POINTER(C.c_int)
 
@@ -116,6 +121,12 @@ SIGNATURES = {
     "ac_chunk_trace": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, I32P, INTP]),
     "ac_chunk_search": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, C.POINTER(ac_chunk_candidate), I32P, INT,
                               INTP, INTP, INTP]),
+    "ac_graph_estimate": (INT, [C.POINTER(ac_graph_node), INT, INT, C.POINTER(ac_graph_chunk), INT, C.POINTER(U64),
+                                C.POINTER(U64), INTP]),
+    "ac_graph_chunk_cost": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double)]),
+    "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double),
+                            C.POINTER(ac_graph_chunk), INT, INTP, C.POINTER(U64)]),
 }
 
 _lib = None
@@ -409,3 +420,36 @@ def ac_chunk_search(nodes, peak, window, max_out=None):
     cands = [(c.start, c.end, c.out_dim, c.granule, list(rows[i * n:(i + 1) * n]))
              for i, c in enumerate(out[:min(max_out, found.value)])]
     return cands, found.value, tried.value, passed.value
+
+
+def _chunks(chunks):
+    arr = (ac_graph_chunk * max(len(chunks), 1))()
+    for c, (start, end, dim, clen) in zip(arr, chunks):
+        c.start, c.end, c.out_dim, c.chunk_len = start, end, dim, clen
+    return arr
+
+
+def ac_graph_estimate(nodes, elem_bytes, chunks=()):
+    """(bytes per node, peak bytes, peak node) with chunks = [(start, end, out_dim, chunk_len)]."""
+    per_node = (C.c_uint64 * len(nodes))()
+    peak, peak_node = C.c_uint64(0), C.c_int(0)
+    _check(lib().ac_graph_estimate(nodes, len(nodes), elem_bytes, _chunks(chunks), len(chunks), per_node,
+                                   C.byref(peak), C.byref(peak_node)), "ac_graph_estimate")
+    return list(per_node), peak.value, peak_node.value
+
+
+def ac_graph_chunk_cost(nodes, start, end, out_dim, weights):
+    w = (C.c_double * 4)(*weights)
+    cost = C.c_double(0)
+    _check(lib().ac_graph_chunk_cost(nodes, len(nodes), start, end, out_dim, w, C.byref(cost)), "ac_graph_chunk_cost")
+    return cost.value
+
+
+def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, max_out=64):
+    """(chunks, peak bytes): chunks [(start, end, out_dim, chunk_len)] in the order chosen."""
+    w = (C.c_double * 4)(*weights)
+    out = (ac_graph_chunk * max_out)()
+    n_out, peak = C.c_int(0), C.c_uint64(0)
+    _check(lib().ac_graph_plan(nodes, len(nodes), elem_bytes, budget_bytes, window, w, out, max_out, C.byref(n_out),
+                               C.byref(peak)), "ac_graph_plan")
+    return [(c.start, c.end, c.out_dim, c.chunk_len) for c in out[:n_out.value]], peak.value

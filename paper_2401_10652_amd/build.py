@@ -14,7 +14,8 @@ SOURCES = ["rowwise.hip", "linear.hip", "attention.hip", "runtime.hip", "search.
 
 # Per-file extras.  attention.hip: keep MFMA results in VGPRs; the softmax reads every score
 # right after the matrix op, and accumulator-register copies would double its VALU work.
-EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+# search.hip (host only): its cost function is compared bit for bit, so no fused multiply-adds.
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"], "search.hip": ["-ffp-contract=off"]}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

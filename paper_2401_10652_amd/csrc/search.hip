@@ -251,7 +251,204 @@ struct Tracer {
     }
     return false;
   }
+
+  // Every legal chunk whose region holds `peak` and spans at most `window` nodes, in order of
+  // start, end, dimension (the local window and the two stages of section 3.3).
+  template <class F>
+  void candidates(int peak, int window, int* tried, int* passed, F&& on_chunk) {
+    std::vector<int32_t> row(n_nodes);
+    const int first = peak - window + 1 > 0 ? peak - window + 1 : 0;
+    for (int start = first; start <= peak; ++start) {
+      const int past = start + window < n_nodes ? start + window : n_nodes;
+      for (int end = peak; end < past; ++end) {
+        if (holds_leaf(start, end)) break;  // longer regions hold it too
+        for (int d = 0; d < g[end].rank; ++d) {
+          ++*tried;
+          if (!reaches_an_input(start, end, d)) continue;
+          ++*passed;
+          int64_t gran = 1;
+          if (trace(start, end, d, row.data(), &gran)) on_chunk(start, end, d, gran, row.data());
+        }
+      }
+    }
+  }
 };
+
+// -----------------------------------------------------------------------------------------
+// Activation memory of the graph (sections 2.1, 2.2) and the selection cost (section 3.4).
+//
+// Every node's result has storage of its own; parameters are not counted.  A tensor is live
+// from its node (a graph input: from the start) to its last reader (none: to the end).  The
+// bytes at a node are all tensors live while it runs.  Inside a chunked region the region's
+// result is held whole, tensors of the region shrink to chunk_len / extent of their size, and
+// everything live at the region's entry stays so until its last segment is done:
+// M = X + Y + A / n.
+// -----------------------------------------------------------------------------------------
+typedef unsigned __int128 u128;
+
+struct Memory {
+  const Tracer& t;
+  int n;
+  std::vector<uint64_t> size;   // bytes of each node's result (0 for parameters)
+  std::vector<int> dies;        // last reader; n - 1 for results nobody reads; -1 for unread leaves
+  std::vector<uint64_t> whole;  // live bytes at each node of the unchunked graph
+
+  Memory(const Tracer& tr, int elem_bytes) : t(tr), n(tr.n_nodes), size(n), dies(n), whole(n, 0) {
+    const ac_graph_node* g = t.g;
+    std::vector<int64_t> delta(n + 1, 0);
+    for (int i = 0; i < n; ++i) {
+      uint64_t elems = 1;
+      for (int d = 0; d < g[i].rank; ++d) elems *= (uint64_t)g[i].shape[d];
+      size[i] = g[i].op == AC_OP_PARAM ? 0 : elems * (uint64_t)elem_bytes;
+      dies[i] = t.last_use[i] >= 0 ? t.last_use[i] : (is_leaf(g[i]) ? -1 : n - 1);
+      if (dies[i] < 0) continue;
+      delta[is_leaf(g[i]) ? 0 : i] += (int64_t)size[i];
+      delta[dies[i] + 1] -= (int64_t)size[i];
+    }
+    int64_t live = 0;
+    for (int i = 0; i < n; ++i) {
+      live += delta[i];
+      whole[i] = is_leaf(g[i]) ? 0 : (uint64_t)live;
+    }
+  }
+
+  // What a region holds at any segment length: X and everything else alive at its entry, plus Y.
+  uint64_t held(int start, int end) const { return whole[start] - size[start] + size[end]; }
+
+  // Unchunked bytes of the region's own tensors live at each of its nodes (the A of each node).
+  void inside(int start, int end, std::vector<uint64_t>& a) const {
+    const ac_graph_node* g = t.g;
+    a.assign(end - start + 1, 0);
+    uint64_t cur = 0;
+    for (int i = start; i <= end; ++i) {
+      if (i != end) cur += size[i];
+      a[i - start] = cur;
+      for (int k = 0; k < g[i].n_inputs; ++k) {
+        const int s = g[i].inputs[k];
+        bool counted = false;
+        for (int q = 0; q < k; ++q) counted |= g[i].inputs[q] == s;
+        if (!counted && s >= start && t.last_use[s] == i) cur -= size[s];
+      }
+    }
+  }
+
+  // Longest chunk length (multiple of granule, below the extent) at which the region fits, or 0.
+  int64_t longest_len(int start, int end, int64_t extent, int64_t granule, uint64_t budget,
+                      std::vector<uint64_t>& scratch) const {
+    const uint64_t fixed = held(start, end);
+    if (fixed > budget) return 0;
+    inside(start, end, scratch);
+    uint64_t a_max = 0;
+    for (uint64_t v : scratch) a_max = v > a_max ? v : a_max;
+    int64_t len = (extent - 1) / granule * granule;
+    if (a_max > 0) {
+      const u128 fit = (u128)(budget - fixed) * (u128)extent / a_max;
+      if (fit < (u128)len) len = (int64_t)fit / granule * granule;
+    }
+    return len;
+  }
+};
+
+uint64_t node_flops(const ac_graph_node* g, const ac_graph_node& n) {
+  uint64_t out = 1;
+  for (int d = 0; d < n.rank; ++d) out *= (uint64_t)n.shape[d];
+  switch (n.op) {
+    case AC_OP_LINEAR:
+    case AC_OP_MATMUL_NT:
+    case AC_OP_MATMUL_NN: {
+      const ac_graph_node& x = g[n.inputs[0]];
+      return 2 * out * (uint64_t)x.shape[x.rank - 1];
+    }
+    case AC_OP_CONTRACT_IKC_JKC:
+      return 2 * out * (uint64_t)g[n.inputs[0]].shape[1];
+    case AC_OP_ELEMENTWISE:
+      return out;
+    case AC_OP_SOFTMAX_LAST:
+      return 5 * out;  // max, subtract, exponential, sum, divide
+    case AC_OP_NORM_LAST:
+      return 8 * out;  // mean; centre, square, sum; scale by the deviation; gain, shift
+    default:
+      return 0;
+  }
+}
+
+// L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride)
+double chunk_cost(const ac_graph_node* g, int start, int end, int out_dim, const double* w) {
+  uint64_t flops = 0;
+  for (int i = start; i <= end; ++i) flops += node_flops(g, g[i]);
+  uint64_t stride = 1;
+  for (int d = out_dim + 1; d < g[end].rank; ++d) stride *= (uint64_t)g[end].shape[d];
+  const double n_node = (double)(end - start + 1), n_flop = (double)flops;
+  const double n_density = n_flop / n_node, n_stride = (double)stride;
+  const double macro = w[0] * n_node + w[1] * n_flop;
+  const double micro = w[2] * n_density + w[3] * n_stride;
+  return macro + micro;
+}
+
+// Checks a caller's chunk list (legal, lengths on the granule, regions apart) and fills
+// region_of[i] = index of the chunk that holds node i, or -1.
+int check_chunks(Tracer& t, const ac_graph_chunk* chunks, int n_chunks, std::vector<int>& region_of) {
+  const int n = t.n_nodes;
+  region_of.assign(n, -1);
+  std::vector<int32_t> row(n);
+  for (int c = 0; c < n_chunks; ++c) {
+    const ac_graph_chunk& ch = chunks[c];
+    if (ch.start < 0 || ch.end < ch.start || ch.end >= n || t.holds_leaf(ch.start, ch.end) || ch.out_dim < 0 ||
+        ch.out_dim >= t.g[ch.end].rank) {
+      ac::set_error("chunk %d: region [%d, %d] or dim %d not in the graph", c, ch.start, ch.end, ch.out_dim);
+      return AC_ERR_ARG;
+    }
+    int64_t gran = 1;
+    if (!t.trace(ch.start, ch.end, ch.out_dim, row.data(), &gran)) {
+      ac::set_error("chunk %d: region [%d, %d] cannot be cut along dim %d", c, ch.start, ch.end, ch.out_dim);
+      return AC_ERR_ILLEGAL_CHUNK_DIM;
+    }
+    const int64_t extent = t.g[ch.end].shape[ch.out_dim];
+    if (ch.chunk_len < 1 || ch.chunk_len > extent || ch.chunk_len % gran != 0) {
+      ac::set_error("chunk %d: chunk_len %lld is not a multiple of %lld within 1..%lld", c, (long long)ch.chunk_len,
+                    (long long)gran, (long long)extent);
+      return AC_ERR_ARG;
+    }
+    for (int i = ch.start; i <= ch.end; ++i) {
+      if (region_of[i] >= 0) {
+        ac::set_error("chunks %d and %d overlap at node %d", region_of[i], c, i);
+        return AC_ERR_ARG;
+      }
+      region_of[i] = c;
+    }
+  }
+  return AC_OK;
+}
+
+// Live bytes at every node under the chunk list; returns the peak and its first node.
+uint64_t estimate(const Memory& m, const ac_graph_chunk* chunks, const std::vector<int>& region_of,
+                  std::vector<uint64_t>& bytes, int* peak_node) {
+  const int n = m.n;
+  bytes.assign(n, 0);
+  std::vector<uint64_t> a;
+  for (int i = 0; i < n;) {
+    if (region_of[i] < 0) {
+      bytes[i] = m.whole[i];
+      ++i;
+      continue;
+    }
+    const ac_graph_chunk& ch = chunks[region_of[i]];
+    const uint64_t fixed = m.held(ch.start, ch.end);
+    const uint64_t extent = (uint64_t)m.t.g[ch.end].shape[ch.out_dim];
+    m.inside(ch.start, ch.end, a);
+    for (int k = ch.start; k <= ch.end; ++k)
+      bytes[k] = fixed + (uint64_t)((u128)a[k - ch.start] * (u128)ch.chunk_len / extent);
+    i = ch.end + 1;
+  }
+  uint64_t peak = 0;
+  *peak_node = 0;
+  for (int i = 0; i < n; ++i)
+    if (bytes[i] > peak) {
+      peak = bytes[i];
+      *peak_node = i;
+    }
+  return peak;
+}
 
 template <class... A>
 int bad(const char* fmt, A... a) {
@@ -291,32 +488,102 @@ extern "C" int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak
     return bad("ac_chunk_search: peak %d, window %d or max_out %d out of range", peak, window, max_out);
   if (max_out > 0 && (!out || !node_dims)) return bad("ac_chunk_search: null output with max_out %d", max_out);
   Tracer t(nodes, n_nodes);
-  std::vector<int32_t> row(n_nodes);
   int found = 0, tried = 0, passed = 0;
-  const int first = peak - window + 1 > 0 ? peak - window + 1 : 0;
-  for (int start = first; start <= peak; ++start) {
-    const int past = start + window < n_nodes ? start + window : n_nodes;
-    for (int end = peak; end < past; ++end) {
-      if (t.holds_leaf(start, end)) break;  // longer regions hold it too
-      for (int d = 0; d < nodes[end].rank; ++d) {
-        ++tried;
-        if (!t.reaches_an_input(start, end, d)) continue;
-        ++passed;
-        int64_t gran = 1;
-        if (!t.trace(start, end, d, row.data(), &gran)) continue;
-        if (found < max_out) {
-          out[found].start = start;
-          out[found].end = end;
-          out[found].out_dim = d;
-          out[found].granule = (int32_t)gran;
-          for (int i = 0; i < n_nodes; ++i) node_dims[(size_t)found * n_nodes + i] = row[i];
-        }
-        ++found;
-      }
+  t.candidates(peak, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t* row) {
+    if (found < max_out) {
+      out[found].start = start;
+      out[found].end = end;
+      out[found].out_dim = d;
+      out[found].granule = (int32_t)gran;
+      for (int i = 0; i < n_nodes; ++i) node_dims[(size_t)found * n_nodes + i] = row[i];
     }
-  }
+    ++found;
+  });
   *n_found = found;
   if (n_tried) *n_tried = tried;
   if (n_passed) *n_passed = passed;
   return AC_OK;
+}
+
+extern "C" int ac_graph_estimate(const ac_graph_node* nodes, int n_nodes, int elem_bytes,
+                                 const ac_graph_chunk* chunks, int n_chunks, uint64_t* node_bytes,
+                                 uint64_t* peak_bytes, int* peak_node) {
+  if (!peak_bytes || !peak_node || (n_chunks > 0 && !chunks)) return bad("ac_graph_estimate: null argument");
+  if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_estimate: malformed graph");
+  if (elem_bytes < 1 || n_chunks < 0) return bad("ac_graph_estimate: elem_bytes %d or n_chunks %d out of range", elem_bytes, n_chunks);
+  Tracer t(nodes, n_nodes);
+  std::vector<int> region_of;
+  const int st = check_chunks(t, chunks, n_chunks, region_of);
+  if (st != AC_OK) return st;
+  Memory m(t, elem_bytes);
+  std::vector<uint64_t> bytes;
+  *peak_bytes = estimate(m, chunks, region_of, bytes, peak_node);
+  if (node_bytes)
+    for (int i = 0; i < n_nodes; ++i) node_bytes[i] = bytes[i];
+  return AC_OK;
+}
+
+extern "C" int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
+                                   const double* weights, double* cost) {
+  if (!weights || !cost) return bad("ac_graph_chunk_cost: null argument");
+  if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_chunk_cost: malformed graph");
+  if (start < 0 || end < start || end >= n_nodes || out_dim < 0 || out_dim >= nodes[end].rank)
+    return bad("ac_graph_chunk_cost: region [%d, %d] or dim %d not in the graph", start, end, out_dim);
+  *cost = chunk_cost(nodes, start, end, out_dim, weights);
+  return AC_OK;
+}
+
+extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
+                             int window, const double* weights, ac_graph_chunk* out, int max_out, int* n_out,
+                             uint64_t* peak_bytes) {
+  if (n_out) *n_out = 0;
+  if (!weights || !out || !n_out || !peak_bytes) return bad("ac_graph_plan: null argument");
+  if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_plan: malformed graph");
+  if (elem_bytes < 1 || window < 1 || max_out < 1)
+    return bad("ac_graph_plan: elem_bytes %d, window %d or max_out %d out of range", elem_bytes, window, max_out);
+  Tracer t(nodes, n_nodes);
+  Memory m(t, elem_bytes);
+  std::vector<int> region_of(n_nodes, -1);
+  std::vector<uint64_t> bytes, scratch;
+  int chosen = 0;
+  for (;;) {  // one pass per chunk: estimate, search around the peak, select
+    int peak_node = 0;
+    *peak_bytes = estimate(m, out, region_of, bytes, &peak_node);
+    *n_out = chosen;
+    if (*peak_bytes <= budget_bytes) return AC_OK;
+    if (region_of[peak_node] >= 0) {
+      ac::set_error("ac_graph_plan: the peak (%llu bytes at node %d) lies in a region already chunked",
+                    (unsigned long long)*peak_bytes, peak_node);
+      return AC_ERR_BUDGET_INFEASIBLE;
+    }
+    if (chosen == max_out) return bad("ac_graph_plan: more than max_out = %d chunks needed", max_out);
+    bool have = false;
+    double best_cost = 0;
+    int64_t best_segments = 0;
+    ac_graph_chunk best{};
+    int tried = 0, passed = 0;
+    t.candidates(peak_node, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t*) {
+      for (int i = start; i <= end; ++i)
+        if (region_of[i] >= 0) return;
+      const int64_t extent = nodes[end].shape[d];
+      const int64_t len = m.longest_len(start, end, extent, gran, budget_bytes, scratch);
+      if (len < gran) return;
+      const double cost = chunk_cost(nodes, start, end, d, weights);
+      const int64_t segments = (extent + len - 1) / len;
+      if (!have || cost < best_cost || (cost == best_cost && segments < best_segments)) {
+        have = true;
+        best_cost = cost;
+        best_segments = segments;
+        best = ac_graph_chunk{start, end, d, 0, len};
+      }
+    });
+    if (!have) {
+      ac::set_error("ac_graph_plan: no chunk around node %d brings its %llu bytes within %llu", peak_node,
+                    (unsigned long long)*peak_bytes, (unsigned long long)budget_bytes);
+      return AC_ERR_BUDGET_INFEASIBLE;
+    }
+    out[chosen] = best;
+    for (int i = best.start; i <= best.end; ++i) region_of[i] = chosen;
+    ++chosen;
+  }
 }

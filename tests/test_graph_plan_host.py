@@ -1,0 +1,115 @@
+"""Graph memory estimate, selection cost and pass loop of the library (ac_graph_estimate,
+ac_graph_chunk_cost, ac_graph_plan; AutoChunk sections 2.1, 2.2, 3.2, 3.4) against the
+oracle's, value by value.  Host code only."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import chunk_search as S
+from oracle import graph_memory as GM
+from paper_2401_10652_amd import binding as B
+from paper_2401_10652_amd import graphs as PG
+from tests import graphs as G
+from tests.test_oracle_graph_memory import some_chunks
+from tests.test_search_host import library_nodes, oracle_nodes
+
+WEIGHTS = ((1, 0, 0, 0), (0, 0, 0, -1), (1.0, 1e-3, -1e-3, -0.5), (0.3, 2e-7, -1e-7, 0.01))
+
+
+def test_estimate_equals_the_oracle():
+    n_chunked = 0
+    for seed in range(60):
+        spec = G.random_graph(seed, n_ops=9 + seed % 6)
+        on, ln = oracle_nodes(spec), library_nodes(spec)
+        rng = np.random.default_rng(seed)
+        for chunks in ([], some_chunks(on, rng, 3)):
+            for e in (2, 4):
+                assert B.ac_graph_estimate(ln, e, chunks) == GM.estimate(on, e, chunks), (seed, chunks)
+            n_chunked += len(chunks)
+    assert n_chunked > 60
+
+
+def test_cost_equals_the_oracle_bit_for_bit():
+    for seed in range(20):
+        spec = G.random_graph(seed, n_ops=10)
+        on, ln = oracle_nodes(spec), library_nodes(spec)
+        first = next(i for i, nd in enumerate(on) if nd.op not in (S.INPUT, S.PARAM))
+        for start in range(first, len(on)):
+            for end in range(start, min(len(on), start + 4)):
+                for d in range(len(on[end].shape)):
+                    for w in WEIGHTS:
+                        assert B.ac_graph_chunk_cost(ln, start, end, d, w) == GM.chunk_cost(on, start, end, d, w)
+
+
+def both_plans(on, ln, e, budget, window, w):
+    try:
+        want = GM.plan(on, e, budget, window, w)
+    except ValueError:
+        with pytest.raises(B.AcError) as err:
+            B.ac_graph_plan(ln, e, budget, window, w)
+        assert err.value.status == B.AC_ERR_BUDGET_INFEASIBLE
+        return None
+    assert B.ac_graph_plan(ln, e, budget, window, w) == want
+    return want
+
+
+def test_plan_equals_the_oracle_on_random_graphs():
+    planned = failed = 0
+    for seed in range(150):
+        spec = G.random_graph(seed, n_ops=10 + seed % 6)
+        on, ln = oracle_nodes(spec), library_nodes(spec)
+        _, whole, _ = GM.estimate(on, 2)
+        for frac in (1.0, 0.95, 0.85, 0.75, 0.6):
+            got = both_plans(on, ln, 2, int(whole * frac), 5, WEIGHTS[seed % len(WEIGHTS)])
+            planned += bool(got and got[0])
+            failed += got is None
+
+    assert planned > 40 and failed > 20
+
+
+def test_plan_equals_the_oracle_on_the_block_graph():
+    spec, nm = PG.transformer_stack_graph(2, 32, 8, 2, 64)
+    onodes, onm = S.transformer_block_graph(2, 32, 8, 2, 64)
+    # the library's builder and the oracle's describe the same graph
+    assert nm == onm and spec == [(nd.op, nd.inputs, nd.shape, nd.attr) for nd in onodes]
+    ln = B.graph_nodes(spec)
+    for budget in (73728, 60000, 40000, 30000, 28672, 28671):
+        for w in WEIGHTS:
+            both_plans(onodes, ln, 8, budget, 8, w)
+    chunks, peak = B.ac_graph_plan(ln, 8, 40000, 8, (1, 0, 0, 0))
+    assert len(chunks) == 2 and peak <= 40000
+
+
+def test_two_layers_take_one_pass_per_peak():
+    spec, nm = PG.transformer_stack_graph(1, 64, 16, 2, 32, layers=2)
+    ln = B.graph_nodes(spec)
+    per_node, whole, peak_node = B.ac_graph_estimate(ln, 2)
+    assert peak_node == nm["scaled"] and per_node[nm["l1.scaled"]] == whole
+    chunks, peak = B.ac_graph_plan(ln, 2, whole // 2, 8, (1, 0, 0, 0))
+    assert len(chunks) == 2 and peak <= whole // 2
+    assert nm["scores"] <= chunks[0][0] <= chunks[0][1] <= nm["ctx"]
+    assert nm["l1.scores"] <= chunks[1][0] <= chunks[1][1] <= nm["l1.ctx"]
+
+
+def test_errors():
+    spec, nm = PG.transformer_stack_graph(2, 32, 8, 2, 64)
+    ln = B.graph_nodes(spec)
+
+    def status(fn):
+        with pytest.raises(B.AcError) as err:
+            fn()
+        return err.value.status
+
+    s, c = nm["scores"], nm["ctx_h"]
+    assert status(lambda: B.ac_graph_estimate(ln, 2, [(s, c, 3, 1)])) == B.AC_ERR_ILLEGAL_CHUNK_DIM   # head dim
+    assert status(lambda: B.ac_graph_estimate(ln, 2, [(s, c, 2, 0)])) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_estimate(ln, 2, [(s, c, 2, 33)])) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_estimate(ln, 2, [(s, c, 2, 4), (c, c + 1, 1, 4)])) == B.AC_ERR_ARG   # overlap
+    assert status(lambda: B.ac_graph_estimate(ln, 2, [(nm["ctx_h"], nm["ctx"], 2, 3)])) == B.AC_ERR_ARG   # granule 4
+    assert status(lambda: B.ac_graph_estimate(ln, 0)) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 8, (1, 0, 0, 0), max_out=1)) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 0, (1, 0, 0, 0))) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_chunk_cost(ln, s, c, 4, (1, 0, 0, 0))) == B.AC_ERR_ARG
+    L = B.lib()
+    assert L.ac_graph_estimate(ln, len(ln), 2, None, 0, None, None, None) == B.AC_ERR_ARG
