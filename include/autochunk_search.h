@@ -138,20 +138,22 @@ int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int 
 
 /*
  * Chunks the graph pass by pass until its estimated peak is at most budget_bytes (section
- * 3.2: estimate, search around the peak node, select; repeated).  One pass: the legal chunks
- * of ac_chunk_search(peak node, window) that touch no region chosen before get the longest
- * chunk_len (multiple of the granule, below the extent) at which their region fits the
- * budget; those with none are dropped; the one of least cost is taken (ties: fewer
- * segments, then search order).  One candidate per pass, no look-ahead: the paper's search
- * over whole strategies (dynamic programming with a beam) is not part of this call.
+ * 3.2: estimate, search around the peak node, select; repeated), looking for the strategy
+ * S = [s_1 .. s_l] of least summed cost (section 3.4).  One pass extends a strategy by one
+ * chunk: the legal chunks of ac_chunk_search(peak node, window) that touch no region chosen
+ * before get the longest chunk_len (multiple of the granule, below the extent) at which
+ * their region fits the budget; those with none are dropped.  The `beam` strategies of least
+ * summed cost (ties: fewer segments in all, then the order they were made in) are kept from
+ * pass to pass; strategies that fit stay as they are; the call ends when all that are kept
+ * fit and returns the first.  beam = 1: every pass takes its cheapest candidate.
  * out (max_out entries, caller's) receives the chunks in the order chosen, *n_out their
- * number, *peak_bytes the estimate with them.  AC_ERR_BUDGET_INFEASIBLE when a pass finds
- * no candidate (*n_out and *peak_bytes then describe the chunks chosen so far); AC_ERR_ARG
- * when more than max_out chunks would be needed.
+ * number, *peak_bytes the estimate with them.  AC_ERR_BUDGET_INFEASIBLE when no strategy in
+ * the beam can be extended (*n_out = 0, *peak_bytes = the unchunked peak); AC_ERR_ARG when
+ * the strategy has more than max_out chunks.
  */
 int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
-                  int window, const double* weights, ac_graph_chunk* out, int max_out, int* n_out,
-                  uint64_t* peak_bytes);
+                  int window, const double* weights, int beam, ac_graph_chunk* out, int max_out,
+                  int* n_out, uint64_t* peak_bytes);
 
 #ifdef __cplusplus
 }

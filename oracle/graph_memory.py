@@ -23,7 +23,10 @@ Readings where the paper leaves the matter open:
     already chosen, give each the longest chunk length (a multiple of its granule, below
     the extent) at which the region fits the budget, drop those with none, take the one
     with the least L (ties: fewer segments, then search order).  The weights of L are the
-    caller's: the paper tunes them and prints no values.
+    caller's: the paper tunes them and prints no values;
+  * the search over whole strategies (section 3.4: minimise the sum of L subject to the
+    budget, by dynamic programming with a beam) keeps the `beam` cheapest strategies from
+    pass to pass; a beam of 1 is the loop above.
 """
 from __future__ import annotations
 
@@ -114,28 +117,53 @@ def longest_fitting_len(nodes, elem_bytes, chunks, cand, granule, budget):
     return 0
 
 
-def plan(nodes, elem_bytes, budget, window, weights):
+def feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node):
+    """One pass's choices: (cost, segments, (start, end, out_dim, chunk_len)) in search order."""
+    out = []
+    for start, end, dim, node_dims, input_dims in S.search(nodes, peak_node, window)[0]:
+        if any(start <= c[1] and c[0] <= end for c in chunks):
+            continue
+        g = S.chunk_granule(nodes, end, dim, node_dims, input_dims)
+        clen = longest_fitting_len(nodes, elem_bytes, chunks, (start, end, dim), g, budget)
+        if clen == 0:
+            continue
+        extent = nodes[end].shape[dim]
+        out.append((chunk_cost(nodes, start, end, dim, weights), -(-extent // clen), (start, end, dim, clen)))
+    return out
+
+
+def plan(nodes, elem_bytes, budget, window, weights, beam=1):
     """Chunks [(start, end, out_dim, chunk_len)] chosen pass by pass until the peak fits;
-    returns (chunks, peak) or raises ValueError when some pass finds no candidate."""
-    chunks = []
+    returns (chunks, peak) or raises ValueError when no strategy in the beam gets there.
+
+    The beam holds the `beam` strategies of least summed cost (ties: fewer segments in all,
+    then the order they were made in).  Every pass extends each strategy that does not fit yet
+    by each candidate around its own peak node; strategies that fit stay as they are.  With
+    beam = 1 this is: take the cheapest candidate of every pass."""
+    states = [(0.0, 0, [])]                               # (sum of L, segments in all, chunks)
     while True:
-        mem, peak, peak_node = estimate(nodes, elem_bytes, chunks)
-        if peak <= budget:
-            return chunks, peak
-        if any(c[0] <= peak_node <= c[1] for c in chunks):
-            raise ValueError("the peak lies in a region already chunked")
-        best = None
-        for start, end, dim, node_dims, input_dims in S.search(nodes, peak_node, window)[0]:
-            if any(start <= c[1] and c[0] <= end for c in chunks):
+        grown, all_fit = [], True
+        known = set()
+        for total, segments, chunks in states:
+            mem, peak, peak_node = estimate(nodes, elem_bytes, chunks)
+            if peak <= budget:
+                if tuple(sorted(chunks)) not in known:
+                    known.add(tuple(sorted(chunks)))
+                    grown.append((total, segments, chunks))
                 continue
-            g = S.chunk_granule(nodes, end, dim, node_dims, input_dims)
-            clen = longest_fitting_len(nodes, elem_bytes, chunks, (start, end, dim), g, budget)
-            if clen == 0:
-                continue
-            extent = nodes[end].shape[dim]
-            key = (chunk_cost(nodes, start, end, dim, weights), -(-extent // clen))
-            if best is None or key < best[0]:
-                best = (key, (start, end, dim, clen))
-        if best is None:
-            raise ValueError(f"no chunk around node {peak_node} brings its {peak} bytes within {budget}")
-        chunks.append(best[1])
+            all_fit = False
+            if any(c[0] <= peak_node <= c[1] for c in chunks):
+                continue                                  # the peak lies in a region already chunked
+            for cost, seg, cand in feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node):
+                new = chunks + [cand]
+                if tuple(sorted(new)) in known:
+                    continue                              # the same chunks, chosen in another order
+                known.add(tuple(sorted(new)))
+                grown.append((total + cost, segments + seg, new))
+        if all_fit:
+            chunks = states[0][2]
+            return chunks, estimate(nodes, elem_bytes, chunks)[1]
+        if not grown:
+            raise ValueError(f"no chunk strategy brings the peak within {budget}")
+        grown.sort(key=lambda st: st[:2])                 # stable: equal keys keep the order of making
+        states = grown[:beam]

@@ -125,7 +125,7 @@ SIGNATURES = {
                                 C.POINTER(U64), INTP]),
     "ac_graph_chunk_cost": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, C.POINTER(C.c_double),
                                   C.POINTER(C.c_double)]),
-    "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double),
+    "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double), INT,
                             C.POINTER(ac_graph_chunk), INT, INTP, C.POINTER(U64)]),
 }
 
@@ -445,11 +445,11 @@ def ac_graph_chunk_cost(nodes, start, end, out_dim, weights):
     return cost.value
 
 
-def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, max_out=64):
+def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, beam=1, max_out=64):
     """(chunks, peak bytes): chunks [(start, end, out_dim, chunk_len)] in the order chosen."""
     w = (C.c_double * 4)(*weights)
     out = (ac_graph_chunk * max_out)()
     n_out, peak = C.c_int(0), C.c_uint64(0)
-    _check(lib().ac_graph_plan(nodes, len(nodes), elem_bytes, budget_bytes, window, w, out, max_out, C.byref(n_out),
+    _check(lib().ac_graph_plan(nodes, len(nodes), elem_bytes, budget_bytes, window, w, beam, out, max_out, C.byref(n_out),
                                C.byref(peak)), "ac_graph_plan")
     return [(c.start, c.end, c.out_dim, c.chunk_len) for c in out[:n_out.value]], peak.value

@@ -4,8 +4,11 @@
 // flow of that dimension is followed from `end` towards the region's inputs: each op kind
 // says in which dimension of each operand the cut continues (a value >= 0), that the
 // operand is not cut (kWhole), or that the op computes over the dimension (kCut).
+#include <algorithm>
+#include <array>
 #include <cstdint>
 #include <numeric>
+#include <set>
 #include <vector>
 
 #include "../../include/autochunk_search.h"
@@ -533,57 +536,93 @@ extern "C" int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int 
   return AC_OK;
 }
 
+namespace {
+
+// One chunk strategy of the beam: its chunks in the order chosen, the sum of their costs and
+// of their segment counts.
+struct Strategy {
+  double total = 0;
+  int64_t segments = 0;
+  std::vector<ac_graph_chunk> chunks;
+};
+
+typedef std::vector<std::array<int64_t, 4>> StrategyKey;  // the chunks, sorted: order of choice does not matter
+
+StrategyKey key_of(const std::vector<ac_graph_chunk>& chunks) {
+  StrategyKey k;
+  for (const ac_graph_chunk& c : chunks) k.push_back({c.start, c.end, c.out_dim, c.chunk_len});
+  std::sort(k.begin(), k.end());
+  return k;
+}
+
+}  // namespace
+
 extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
-                             int window, const double* weights, ac_graph_chunk* out, int max_out, int* n_out,
-                             uint64_t* peak_bytes) {
+                             int window, const double* weights, int beam, ac_graph_chunk* out, int max_out,
+                             int* n_out, uint64_t* peak_bytes) {
   if (n_out) *n_out = 0;
   if (!weights || !out || !n_out || !peak_bytes) return bad("ac_graph_plan: null argument");
   if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_plan: malformed graph");
-  if (elem_bytes < 1 || window < 1 || max_out < 1)
-    return bad("ac_graph_plan: elem_bytes %d, window %d or max_out %d out of range", elem_bytes, window, max_out);
+  if (elem_bytes < 1 || window < 1 || beam < 1 || max_out < 1)
+    return bad("ac_graph_plan: elem_bytes %d, window %d, beam %d or max_out %d out of range", elem_bytes, window, beam,
+               max_out);
   Tracer t(nodes, n_nodes);
   Memory m(t, elem_bytes);
-  std::vector<int> region_of(n_nodes, -1);
+  std::vector<int> region_of(n_nodes);
   std::vector<uint64_t> bytes, scratch;
-  int chosen = 0;
-  for (;;) {  // one pass per chunk: estimate, search around the peak, select
-    int peak_node = 0;
-    *peak_bytes = estimate(m, out, region_of, bytes, &peak_node);
-    *n_out = chosen;
-    if (*peak_bytes <= budget_bytes) return AC_OK;
-    if (region_of[peak_node] >= 0) {
-      ac::set_error("ac_graph_plan: the peak (%llu bytes at node %d) lies in a region already chunked",
-                    (unsigned long long)*peak_bytes, peak_node);
-      return AC_ERR_BUDGET_INFEASIBLE;
-    }
-    if (chosen == max_out) return bad("ac_graph_plan: more than max_out = %d chunks needed", max_out);
-    bool have = false;
-    double best_cost = 0;
-    int64_t best_segments = 0;
-    ac_graph_chunk best{};
-    int tried = 0, passed = 0;
-    t.candidates(peak_node, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t*) {
-      for (int i = start; i <= end; ++i)
-        if (region_of[i] >= 0) return;
-      const int64_t extent = nodes[end].shape[d];
-      const int64_t len = m.longest_len(start, end, extent, gran, budget_bytes, scratch);
-      if (len < gran) return;
-      const double cost = chunk_cost(nodes, start, end, d, weights);
-      const int64_t segments = (extent + len - 1) / len;
-      if (!have || cost < best_cost || (cost == best_cost && segments < best_segments)) {
-        have = true;
-        best_cost = cost;
-        best_segments = segments;
-        best = ac_graph_chunk{start, end, d, 0, len};
+  auto estimate_of = [&](const std::vector<ac_graph_chunk>& chunks, int* peak_node) {
+    region_of.assign(n_nodes, -1);
+    for (size_t c = 0; c < chunks.size(); ++c)
+      for (int i = chunks[c].start; i <= chunks[c].end; ++i) region_of[i] = (int)c;
+    return estimate(m, chunks.data(), region_of, bytes, peak_node);
+  };
+  int peak_node = 0;
+  *peak_bytes = estimate_of({}, &peak_node);
+
+  std::vector<Strategy> states(1);
+  for (;;) {  // one pass: every strategy that does not fit yet grows by one chunk around its own peak
+    std::vector<Strategy> grown;
+    std::set<StrategyKey> known;
+    bool all_fit = true;
+    for (const Strategy& st : states) {
+      const uint64_t peak = estimate_of(st.chunks, &peak_node);  // also leaves region_of set for st
+      if (peak <= budget_bytes) {
+        if (known.insert(key_of(st.chunks)).second) grown.push_back(st);
+        continue;
       }
-    });
-    if (!have) {
-      ac::set_error("ac_graph_plan: no chunk around node %d brings its %llu bytes within %llu", peak_node,
+      all_fit = false;
+      if (region_of[peak_node] >= 0) continue;  // the peak lies in a region already chunked: a dead end
+      int tried = 0, passed = 0;
+      t.candidates(peak_node, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t*) {
+        for (int i = start; i <= end; ++i)
+          if (region_of[i] >= 0) return;
+        const int64_t extent = nodes[end].shape[d];
+        const int64_t len = m.longest_len(start, end, extent, gran, budget_bytes, scratch);
+        if (len < gran) return;
+        Strategy next = st;
+        next.chunks.push_back(ac_graph_chunk{start, end, d, 0, len});
+        if (!known.insert(key_of(next.chunks)).second) return;  // the same chunks, chosen in another order
+        next.total = st.total + chunk_cost(nodes, start, end, d, weights);
+        next.segments = st.segments + (extent + len - 1) / len;
+        grown.push_back(std::move(next));
+      });
+    }
+    if (all_fit) break;
+    if (grown.empty()) {
+      ac::set_error("ac_graph_plan: no chunk strategy brings the peak of %llu bytes within %llu",
                     (unsigned long long)*peak_bytes, (unsigned long long)budget_bytes);
       return AC_ERR_BUDGET_INFEASIBLE;
     }
-    out[chosen] = best;
-    for (int i = best.start; i <= best.end; ++i) region_of[i] = chosen;
-    ++chosen;
+    std::stable_sort(grown.begin(), grown.end(), [](const Strategy& a, const Strategy& b) {
+      return a.total < b.total || (a.total == b.total && a.segments < b.segments);
+    });
+    if ((int)grown.size() > beam) grown.resize(beam);
+    states.swap(grown);
   }
+  const Strategy& best = states[0];
+  if ((int)best.chunks.size() > max_out) return bad("ac_graph_plan: %d chunks needed, max_out is %d", (int)best.chunks.size(), max_out);
+  for (size_t c = 0; c < best.chunks.size(); ++c) out[c] = best.chunks[c];
+  *n_out = (int)best.chunks.size();
+  *peak_bytes = estimate_of(best.chunks, &peak_node);
+  return AC_OK;
 }

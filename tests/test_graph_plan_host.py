@@ -42,20 +42,20 @@ def test_cost_equals_the_oracle_bit_for_bit():
                         assert B.ac_graph_chunk_cost(ln, start, end, d, w) == GM.chunk_cost(on, start, end, d, w)
 
 
-def both_plans(on, ln, e, budget, window, w):
+def both_plans(on, ln, e, budget, window, w, beam=1):
     try:
-        want = GM.plan(on, e, budget, window, w)
+        want = GM.plan(on, e, budget, window, w, beam)
     except ValueError:
         with pytest.raises(B.AcError) as err:
-            B.ac_graph_plan(ln, e, budget, window, w)
+            B.ac_graph_plan(ln, e, budget, window, w, beam)
         assert err.value.status == B.AC_ERR_BUDGET_INFEASIBLE
         return None
-    assert B.ac_graph_plan(ln, e, budget, window, w) == want
+    assert B.ac_graph_plan(ln, e, budget, window, w, beam) == want
     return want
 
 
 def test_plan_equals_the_oracle_on_random_graphs():
-    planned = failed = 0
+    planned = failed = rescued = 0
     for seed in range(150):
         spec = G.random_graph(seed, n_ops=10 + seed % 6)
         on, ln = oracle_nodes(spec), library_nodes(spec)
@@ -64,8 +64,11 @@ def test_plan_equals_the_oracle_on_random_graphs():
             got = both_plans(on, ln, 2, int(whole * frac), 5, WEIGHTS[seed % len(WEIGHTS)])
             planned += bool(got and got[0])
             failed += got is None
+            for beam in (2, 5):
+                wide = both_plans(on, ln, 2, int(whole * frac), 5, WEIGHTS[seed % len(WEIGHTS)], beam)
+                rescued += got is None and wide is not None
 
-    assert planned > 40 and failed > 20
+    assert planned > 40 and failed > 20 and rescued > 5
 
 
 def test_plan_equals_the_oracle_on_the_block_graph():
@@ -109,6 +112,7 @@ def test_errors():
     assert status(lambda: B.ac_graph_estimate(ln, 2, [(nm["ctx_h"], nm["ctx"], 2, 3)])) == B.AC_ERR_ARG   # granule 4
     assert status(lambda: B.ac_graph_estimate(ln, 0)) == B.AC_ERR_ARG
     assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 8, (1, 0, 0, 0), max_out=1)) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 8, (1, 0, 0, 0), beam=0)) == B.AC_ERR_ARG
     assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 0, (1, 0, 0, 0))) == B.AC_ERR_ARG
     assert status(lambda: B.ac_graph_chunk_cost(ln, s, c, 4, (1, 0, 0, 0))) == B.AC_ERR_ARG
     L = B.lib()

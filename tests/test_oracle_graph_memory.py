@@ -237,3 +237,49 @@ def test_pass_loop_on_random_graphs():
             done += len(chunks) > 0
             several += len(chunks) > 1
     assert done > 20 and several > 3
+
+
+def cheapest_by_exhaustion(nodes, e, budget, window, weights):
+    """Least summed cost over every strategy the passes can build (all orders, all candidates)."""
+    best = [None]
+
+    def go(chunks, total):
+        _, peak, peak_node = GM.estimate(nodes, e, chunks)
+        if peak <= budget:
+            if best[0] is None or total < best[0]:
+                best[0] = total
+            return
+        if any(c[0] <= peak_node <= c[1] for c in chunks):
+            return
+        for cost, _, cand in GM.feasible_candidates(nodes, e, budget, window, weights, chunks, peak_node):
+            go(chunks + [cand], total + cost)
+
+    go([], 0.0)
+    return best[0]
+
+
+def test_a_wide_beam_finds_the_cheapest_strategy():
+    weights = (1.0, 1e-3, -1e-3, -0.5)
+    solved = rescued = 0
+    for seed in range(60):
+        nodes = oracle_nodes(G.random_graph(seed, n_ops=10 + seed % 4))
+        feeds = S.random_feeds(nodes, seed)
+        _, whole, _ = GM.estimate(nodes, 8)
+        for frac in (0.95, 0.85, 0.7):
+            budget = int(whole * frac)
+            least = cheapest_by_exhaustion(nodes, 8, budget, 4, weights)
+            try:
+                chunks, peak = GM.plan(nodes, 8, budget, 4, weights, beam=10 ** 6)
+            except ValueError:
+                assert least is None
+                continue
+            total = sum(GM.chunk_cost(nodes, c[0], c[1], c[2], weights) for c in chunks)
+            assert least is not None and abs(total - least) <= 1e-9 * max(1.0, abs(least)), (seed, frac)
+            seen, _ = counted_run(nodes, feeds, chunks)
+            assert max(seen) == peak <= budget
+            solved += 1
+            try:
+                GM.plan(nodes, 8, budget, 4, weights, beam=1)
+            except ValueError:
+                rescued += 1            # the cheapest candidate of some pass led into a dead end
+    assert solved > 40 and rescued > 2
