@@ -54,3 +54,43 @@ def transformer_stack_graph(batch, seq, d_model, heads, d_ffn, layers=1):
         g.add(n("down"), B.AC_OP_LINEAR, (n("act"), n("w2"), n("bf2")), bsd)
         src = g.add(n("y"), B.AC_OP_ELEMENTWISE, (n("h"), n("down")), bsd)
     return g.spec, g.names
+
+
+# What each dimension of a node of transformer_stack_graph means, by node name.
+_BSD = ("batch", "seq", "feature")
+_BHSD = ("batch", "heads", "seq", "head_dim")
+_BHSS = ("batch", "heads", "seq", "key")
+_BSHD = ("batch", "seq", "heads", "head_dim")
+_MEANING = {"u": _BSD, "qkv": _BSD, "scores": _BHSS, "scaled": _BHSS, "probs": _BHSS, "ctx_h": _BHSD, "ctx_t": _BSHD,
+            "ctx": _BSD, "o": _BSD, "h": _BSD, "u2": _BSD, "t": _BSD, "act": _BSD, "down": _BSD, "y": _BSD}
+for _t in "qkv":
+    _MEANING.update({_t + "_flat": _BSD, _t + "_split": _BSHD, _t + "_h": _BHSD})
+
+# Node spans of the executor's region kinds within a layer (first node, last node).
+_KIND_SPANS = ((B.AC_REGION_QKV, "u", "v_h"), (B.AC_REGION_ATTENTION, "scores", "ctx"),
+               (B.AC_REGION_OUT_PROJ, "o", "h"), (B.AC_REGION_FFN, "u2", "y"))
+
+
+def executor_regions(chunks, names):
+    """Region settings for ac_plan_create, [(kind, chunk_dim, chunk_len)], from chunks
+    [(start, end, out_dim, chunk_len)] of a transformer_stack_graph (as ac_graph_plan returns
+    them).  A chunk goes to the region kind whose nodes hold it; the executor cuts the whole
+    kind, in every layer, so one kind takes the shortest length asked for in any layer.
+    Raises ValueError for a chunk that spans two kinds, that is cut along a dimension the
+    executor has no kernel for, or when layers disagree on the dimension."""
+    by_index = {v: k for k, v in names.items()}
+    settings = {}
+    for start, end, out_dim, chunk_len in chunks:
+        prefix, _, last = by_index[end].rpartition(".")
+        where = (lambda nm: names[f"{prefix}.{nm}" if prefix else nm])
+        kind = next((k for k, a, b in _KIND_SPANS if where(a) <= start and end <= where(b)), None)
+        if kind is None:
+            raise ValueError(f"chunk [{by_index[start]}, {by_index[end]}] lies in no single region kind of the executor")
+        meaning = _MEANING[last][out_dim]
+        if meaning not in ("batch", "seq"):
+            raise ValueError(f"chunk [{by_index[start]}, {by_index[end]}] is cut along {meaning}: no kernel")
+        dim = B.AC_DIM_BATCH if meaning == "batch" else B.AC_DIM_SEQ
+        if kind in settings and settings[kind][0] != dim:
+            raise ValueError(f"layers disagree on the chunk dimension of region kind {kind}")
+        settings[kind] = (dim, min(chunk_len, settings.get(kind, (dim, chunk_len))[1]))
+    return [(kind, dim, clen) for kind, (dim, clen) in sorted(settings.items())]

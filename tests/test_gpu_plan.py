@@ -216,3 +216,28 @@ def test_stored_scores_plans_equal_the_oracle(B, dtype, causal):
     assert rel_err(host(y), ref) <= TOL[dtype]
     y2, _ = r.run(regions(B, 1, 1, 1, dim=B.AC_DIM_BATCH), flags=flag | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("dtype,batch", [("f32", 1), ("bf16", 2)])
+def test_chunks_planned_on_the_graph_run_in_the_executor(B, dtype, batch):
+    """The whole chain: the unfused graph of the stack is chunked to half its estimated peak by
+    ac_graph_plan (sections 3.2 to 3.4), the chunks are handed to the executor as region settings,
+    and the stored-scores plan they give equals the oracle and really needs less workspace."""
+    from paper_2401_10652_amd import graphs as PG
+    cfg = I.TransformerConfig("tgp", 43, 2, 384, 128, 4, 256, True, dtype, 0.05 if dtype == "bf16" else None, batch=batch)
+    e = 2 if dtype == "bf16" else 4
+    spec, names = PG.transformer_stack_graph(cfg.batch, cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, cfg.layers)
+    nodes = B.graph_nodes(spec)
+    _, whole, peak_node = B.ac_graph_estimate(nodes, e)
+    assert peak_node == names["scaled"]
+    chunks, peak = B.ac_graph_plan(nodes, e, whole // 2, 12, (1.0, 0.0, 0.0, 0.0), beam=2)
+    assert chunks and peak <= whole // 2
+    settings = PG.executor_regions(chunks, names)
+    assert [s[0] for s in settings] == [B.AC_REGION_ATTENTION] and settings[0][2] < cfg.seq
+    r = Runner(B, cfg, bias_std=0.1, ln_jitter=0.1)
+    flag = B.AC_FLAG_MATERIALIZED_SCORES
+    y, info = r.run(settings, flags=flag)
+    assert rel_err(host(y), r.oracle()) <= TOL[dtype]
+    assert info.regions[B.AC_REGION_ATTENTION].n_segments > 1
+    _, info_whole = r.run([], flags=flag)
+    assert info.workspace_bytes < info_whole.workspace_bytes
