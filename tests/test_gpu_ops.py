@@ -81,6 +81,35 @@ def test_linear(B, dtype, m, n, k, epi):
     assert rel_err(got, ref) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("m,n,k,epi", [(8184, 8168, 2048, "none"), (8184, 8168, 2048, "bias_gelu"),
+                                       (8184, 8168, 4096, "bias_resid"), (8192, 8192, 1024, "bias_gelu")])
+def test_linear_large_tiles_on_sampled_rows(B, m, n, k, epi):
+    """Shapes that take the 256x256 tiles (both kernels: k >= 2048 and below), with ragged last
+    tiles in both directions; the oracle computes every column of a sample of rows (the first
+    and the last tile's rows among them)."""
+    import torch
+    a = draw((m, k), 15, "bf16")
+    w = draw((n, k), 16, "bf16", 1 / math.sqrt(k))
+    bias = draw((n,), 17, "bf16", 0.5)
+    res = draw((m, n), 18, "bf16")
+    rows = np.unique(np.concatenate([np.arange(40), np.arange(m - 40, m), np.arange(0, m, 97), [255, 256, 4095, 4096]]))
+    da, dw = dev(B, a, "bf16"), dev(B, w, "bf16")
+    out = torch.full((m, n), float("nan"), device="cuda", dtype=da.dtype)
+    ref = O.linear(a[rows], w)
+    kw = {}
+    if epi == "bias_gelu":
+        kw = dict(bias=dev(B, bias, "bf16"), activation=B.AC_ACT_GELU_ERF)
+        ref = O.gelu_erf(ref + bias)
+    elif epi == "bias_resid":
+        kw = dict(bias=dev(B, bias, "bf16"), residual=dev(B, res, "bf16"))
+        ref = ref + bias + res[rows]
+    B.ac_op_linear(da, dw, out, **kw)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    got = host(out[torch.from_numpy(rows).cuda()])
+    assert rel_err(got, ref) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype,m,n,k,split", [("bf16", 384, 256, 128, 128), ("bf16", 200, 96, 64, 0),
                                                ("f32", 100, 48, 32, 16), ("bf16", 50, 30, 20, 10)])
 def test_linear_strided_store(B, dtype, m, n, k, split):
