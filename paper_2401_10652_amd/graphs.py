@@ -94,3 +94,81 @@ def executor_regions(chunks, names):
             raise ValueError(f"layers disagree on the chunk dimension of region kind {kind}")
         settings[kind] = (dim, min(chunk_len, settings.get(kind, (dim, chunk_len))[1]))
     return [(kind, dim, clen) for kind, (dim, clen) in sorted(settings.items())]
+
+
+def pair_block_graph(n_res, c_z, c_hidden, heads, head_dim, transition_factor):
+    """One pair-stack block on z [n_res, n_res, c_z] as an unfused graph: triangle
+    multiplicative update (outgoing "tmo", incoming "tmi"), triangle self-attention around the
+    starting ("tas") and ending ("tae") node, pair transition ("pt"); node names carry the
+    module's prefix.  The ending-node attention is the starting-node one on the transposed
+    pair tensor, transposed back.  Returns (spec, names)."""
+    g = GraphBuilder()
+    n, c, ch, hd = n_res, c_z, c_hidden, heads * head_dim
+    nnc = (n, n, c)
+    g.add("z", B.AC_OP_INPUT, shape=nnc)
+
+    def param(name, *shape):
+        return g.add(name, B.AC_OP_PARAM, shape=shape)
+
+    for p in ("tmo.", "tmi."):
+        for nm in ("ln_in_g", "ln_in_b"):
+            param(p + nm, c)
+        for nm in ("ag", "ap", "bg", "bp"):
+            param(p + "w_" + nm, ch, c)
+            param(p + "b_" + nm, ch)
+        param(p + "w_g", c, c), param(p + "b_g", c)
+        param(p + "ln_out_g", ch), param(p + "ln_out_b", ch)
+        param(p + "w_o", c, ch), param(p + "b_o", c)
+    for p in ("tas.", "tae."):
+        param(p + "ln_g", c), param(p + "ln_b", c)
+        for nm in ("q", "k", "v"):
+            param(p + "w_" + nm, hd, c)
+        param(p + "w_bias", heads, c)
+        param(p + "w_g", hd, c), param(p + "b_g", hd)
+        param(p + "w_o", c, hd), param(p + "b_o", c)
+    param("pt.ln_g", c), param("pt.ln_b", c)
+    param("pt.w_1", transition_factor * c, c), param("pt.b_1", transition_factor * c)
+    param("pt.w_2", c, transition_factor * c), param("pt.b_2", c)
+
+    src = "z"
+    for p, outgoing in (("tmo.", True), ("tmi.", False)):
+        g.add(p + "t", B.AC_OP_NORM_LAST, (src, p + "ln_in_g", p + "ln_in_b"), nnc)
+        for x in "ab":
+            g.add(p + x + "_gate", B.AC_OP_LINEAR, (p + "t", p + f"w_{x}g", p + f"b_{x}g"), (n, n, ch))
+            g.add(p + x + "_proj", B.AC_OP_LINEAR, (p + "t", p + f"w_{x}p", p + f"b_{x}p"), (n, n, ch))
+            g.add(p + x, B.AC_OP_ELEMENTWISE, (p + x + "_gate", p + x + "_proj"), (n, n, ch))
+            if not outgoing:     # o[i,j,c] = sum_k a[k,i,c] b[k,j,c]: bring the summed index to the middle
+                g.add(p + x + "_t", B.AC_OP_TRANSPOSE, (p + x,), (n, n, ch), (1, 0, 2))
+        ops = (p + "a", p + "b") if outgoing else (p + "a_t", p + "b_t")
+        g.add(p + "o", B.AC_OP_CONTRACT_IKC_JKC, ops, (n, n, ch))
+        g.add(p + "gate", B.AC_OP_LINEAR, (p + "t", p + "w_g", p + "b_g"), nnc)
+        g.add(p + "on", B.AC_OP_NORM_LAST, (p + "o", p + "ln_out_g", p + "ln_out_b"), (n, n, ch))
+        g.add(p + "ol", B.AC_OP_LINEAR, (p + "on", p + "w_o", p + "b_o"), nnc)
+        g.add(p + "upd", B.AC_OP_ELEMENTWISE, (p + "gate", p + "ol"), nnc)
+        src = g.add(p + "z", B.AC_OP_ELEMENTWISE, (src, p + "upd"), nnc)
+    for p, starting in (("tas.", True), ("tae.", False)):
+        zin = src if starting else g.add(p + "zt", B.AC_OP_TRANSPOSE, (src,), nnc, (1, 0, 2))
+        g.add(p + "t", B.AC_OP_NORM_LAST, (zin, p + "ln_g", p + "ln_b"), nnc)
+        for x in "qkv":
+            g.add(p + x, B.AC_OP_LINEAR, (p + "t", p + "w_" + x), (n, n, hd))
+            g.add(p + x + "_split", B.AC_OP_SPLIT_DIM, (p + x,), (n, n, heads, head_dim), (2, heads))
+            g.add(p + x + "_h", B.AC_OP_TRANSPOSE, (p + x + "_split",), (n, heads, n, head_dim), (0, 2, 1, 3))
+        g.add(p + "bias", B.AC_OP_LINEAR, (p + "t", p + "w_bias"), (n, n, heads))
+        g.add(p + "bias_t", B.AC_OP_TRANSPOSE, (p + "bias",), (heads, n, n), (2, 0, 1))
+        g.add(p + "gate", B.AC_OP_LINEAR, (p + "t", p + "w_g", p + "b_g"), (n, n, hd))
+        g.add(p + "scores", B.AC_OP_MATMUL_NT, (p + "q_h", p + "k_h"), (n, heads, n, n))
+        g.add(p + "biased", B.AC_OP_ELEMENTWISE, (p + "scores", p + "bias_t"), (n, heads, n, n))
+        g.add(p + "probs", B.AC_OP_SOFTMAX_LAST, (p + "biased",), (n, heads, n, n))
+        g.add(p + "ctx_h", B.AC_OP_MATMUL_NN, (p + "probs", p + "v_h"), (n, heads, n, head_dim))
+        g.add(p + "ctx_t", B.AC_OP_TRANSPOSE, (p + "ctx_h",), (n, n, heads, head_dim), (0, 2, 1, 3))
+        g.add(p + "ctx", B.AC_OP_MERGE_DIMS, (p + "ctx_t",), (n, n, hd), (2, head_dim))
+        g.add(p + "gated", B.AC_OP_ELEMENTWISE, (p + "gate", p + "ctx"), (n, n, hd))
+        g.add(p + "o", B.AC_OP_LINEAR, (p + "gated", p + "w_o", p + "b_o"), nnc)
+        upd = p + "o" if starting else g.add(p + "o_t", B.AC_OP_TRANSPOSE, (p + "o",), nnc, (1, 0, 2))
+        src = g.add(p + "z", B.AC_OP_ELEMENTWISE, (src, upd), nnc)
+    g.add("pt.u", B.AC_OP_NORM_LAST, (src, "pt.ln_g", "pt.ln_b"), nnc)
+    g.add("pt.t", B.AC_OP_LINEAR, ("pt.u", "pt.w_1", "pt.b_1"), (n, n, transition_factor * c))
+    g.add("pt.act", B.AC_OP_ELEMENTWISE, ("pt.t",), (n, n, transition_factor * c))
+    g.add("pt.down", B.AC_OP_LINEAR, ("pt.act", "pt.w_2", "pt.b_2"), nnc)
+    g.add("pt.z", B.AC_OP_ELEMENTWISE, (src, "pt.down"), nnc)
+    return g.spec, g.names

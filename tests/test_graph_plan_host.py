@@ -117,3 +117,23 @@ def test_errors():
     assert status(lambda: B.ac_graph_chunk_cost(ln, s, c, 4, (1, 0, 0, 0))) == B.AC_ERR_ARG
     L = B.lib()
     assert L.ac_graph_estimate(ln, len(ln), 2, None, 0, None, None, None) == B.AC_ERR_ARG
+
+
+def test_pair_block_plan_equals_the_oracle_and_chunks_the_triangle_attention():
+    from tests.test_search_host import pair_spec
+    spec, nm = pair_spec(n=8, c=4, ch=4, heads=2, dh=2, factor=2)
+    on, ln = oracle_nodes(spec), library_nodes(spec)
+    assert B.ac_graph_estimate(ln, 2) == GM.estimate(on, 2)
+    _, whole, peak_node = GM.estimate(on, 2)
+    assert peak_node == nm["tas.biased"]
+    for frac in (0.8, 0.6, 0.5):
+        for beam in (1, 3):
+            both_plans(on, ln, 2, int(whole * frac), 10, (1, 0, 0, 0), beam)
+    # at the size of the pair workload: 16.8 GiB unchunked, the scores of both triangle attentions cut along rows
+    spec, nm = PG.pair_block_graph(1024, 128, 128, 4, 32, 4)
+    big = B.graph_nodes(spec)
+    _, whole, peak_node = B.ac_graph_estimate(big, 2)
+    # two score-sized tensors, and z, the values, the gate (one pair tensor each) and the bias [H, N, N]
+    assert peak_node == nm["tas.biased"] and whole == 2 * (4 * 1024 ** 3) * 2 + (3 * 128 + 4) * 1024 * 1024 * 2
+    chunks, peak = B.ac_graph_plan(big, 2, 4 << 30, 16, (1, 0, 0, 0), beam=2)
+    assert peak <= 4 << 30 and [(c[0], c[2]) for c in chunks] == [(nm["tas.scores"], 0), (nm["tae.scores"], 0)]

@@ -179,3 +179,55 @@ def test_count_only_truncation_and_errors():
             bad[nm["probs"]].rank = 7
         assert L.ac_chunk_search(bad, len(bad), nm["probs"], 6, None, None, 0, C.byref(found), None, None) == \
             B.AC_ERR_ARG, breaker
+
+
+def pair_spec(n=6, c=4, ch=4, heads=2, dh=2, factor=2):
+    from paper_2401_10652_amd import graphs as PG
+    spec, names = PG.pair_block_graph(n, c, ch, heads, dh, factor)
+    # any elementwise function serves the legality checks: pick one by arity
+    fn = {1: "tanh", 2: "mul"}
+    return [(op, ins, shape, attr, fn[len(ins)] if op == S.ELEMENTWISE else None) for op, ins, shape, attr in spec], names
+
+
+def test_pair_block_chunks_equal_the_oracle_and_reproduce_the_unchunked_output():
+    spec, nm = pair_spec()
+    assert compare_everywhere(spec, (1, 5, 12)) > 2000
+    nodes = oracle_nodes(spec)
+    val = S.run(nodes, S.random_feeds(nodes, 5))
+    seen = set()
+    for peak in range(len(nodes)):
+        if nodes[peak].op in (S.INPUT, S.PARAM):
+            continue
+        for start, end, dim, node_dims, input_dims in S.search(nodes, peak, 7)[0]:
+            if (start, end, dim) in seen:
+                continue
+            seen.add((start, end, dim))
+            g = S.chunk_granule(nodes, end, dim, node_dims, input_dims)
+            got = S.run_chunked(nodes, val, start, end, dim, node_dims, input_dims, g)
+            assert np.allclose(got, val[end], rtol=0, atol=1e-10), (start, end, dim)
+    assert len(seen) > 400
+
+
+def test_region_kinds_of_the_pair_executor_are_chunks_of_the_pair_graph():
+    """Row and column chunks are legal for the chunked part of every pair module, channel chunks
+    are not; the projections that every segment reads whole (b of the triangle update; keys,
+    values and bias of the triangle attention) cannot be inside the region (rule 4)."""
+    spec, nm = pair_spec()
+    ln = library_nodes(spec)
+
+    def dims(a, b):
+        return {d for d in range(len(spec[nm[b]][2])) if B.ac_chunk_trace(ln, nm[a], nm[b], d) is not None}
+
+    for p in ("tmo.", "tmi."):
+        assert dims(p + "o", p + "z") == {0, 1}            # contraction .. residual: rows i, columns j
+        assert dims(p + "o", p + "o") == {0, 1, 2}         # the contraction alone: channels too
+        assert dims(p + "t", p + "z") == set()             # with the b projection inside: no chunk
+    for p in ("tas.", "tae."):
+        assert dims(p + "scores", p + "ctx") == {0, 1, 2}  # row, query column, whole heads
+        assert dims(p + "scores", p + "probs") == {0, 1, 2}
+        assert dims(p + "scores", p + "o") == {0, 1}
+        assert dims(p + "t", p + "z") == set()
+    assert dims("pt.u", "pt.z") == {0, 1}
+    # the ending-node module cut along rows of z: after its two transposes the cut runs along the query column
+    row = B.ac_chunk_trace(ln, nm["tae.scores"], nm["tae.z"], 0)
+    assert row is not None and row[nm["tae.o"]] == 1 and row[nm["tae.scores"]] == 2
