@@ -174,6 +174,67 @@ def trace(nodes, start: int, end: int, out_dim: int):
     return dims, xin
 
 
+def trace_hoisting(nodes, start: int, end: int, out_dim: int):
+    """Like `trace`, with the graph optimisation of section 3.3 applied: nodes of the region
+    that the chunk flow does not pass, or that some node reads whole, are moved ahead of the
+    region together with everything inside the region they depend on (they are computed once,
+    whole, and not again in every segment), and the rest is traced as a region of its own
+    whose inputs include the moved nodes.  Returns (node_dims, input_dims, moved) or None;
+    input_dims also names the moved nodes that the rest reads in slices.  A region whose first
+    node would be moved is left to the shorter region that starts behind it."""
+    inside = set(range(start, end + 1))
+    for i, nd in enumerate(nodes):
+        if i not in inside:
+            for s in nd.inputs:
+                if s in inside and s != end:
+                    return None
+    moved = set()
+    while True:
+        rest = inside - moved
+        dims, xin, whole = {end: out_dim}, {}, set()
+        frontier = [end]
+        while frontier:
+            nxt = []
+            for n in frontier:
+                nd = nodes[n]
+                for which, s in enumerate(nd.inputs):
+                    kind, d = flow_to_input(nd, nodes, dims[n], which)
+                    if kind == BROKEN:
+                        return None
+                    if kind == WHOLE:
+                        if s in rest:
+                            whole.add(s)
+                        continue
+                    if s in rest:
+                        if s in dims:
+                            if dims[s] != d:
+                                return None
+                            continue
+                        dims[s] = d
+                        nxt.append(s)
+                    else:
+                        if s in xin and xin[s] != d:
+                            return None
+                        xin[s] = d
+            frontier = nxt
+        # move what is read whole or not reached, with its ancestors inside the region
+        grow = {i for i in rest if i in whole or i not in dims}
+        todo = list(grow)
+        while todo:
+            for s in nodes[todo.pop()].inputs:
+                if s in rest and s not in grow:
+                    grow.add(s)
+                    todo.append(s)
+        if not grow:
+            break
+        if end in grow or start in grow:
+            return None
+        moved |= grow
+    if start in moved or not xin:
+        return None
+    return dims, xin, moved
+
+
 def some_flow_reaches_an_input(nodes, start: int, end: int, out_dim: int) -> bool:
     """First stage of the two-stage search: is there any uninterrupted flow from `out_dim` of
     node `end` to a node outside the region?  No rule is checked on the way."""
@@ -195,6 +256,26 @@ def some_flow_reaches_an_input(nodes, start: int, end: int, out_dim: int) -> boo
 def region_inputs(nodes, start, end):
     inside = set(range(start, end + 1))
     return sorted({s for i in inside for s in nodes[i].inputs if s not in inside})
+
+
+def search_hoisting(nodes, peak: int, window: int):
+    """`search` with `trace_hoisting`: candidates are (start, end, out_dim, node_dims, input_dims,
+    moved); a candidate whose peak node would be moved out of the region is dropped (chunking
+    it would not touch the peak)."""
+    out, tried, passed = [], 0, 0
+    for start in range(max(0, peak - window + 1), peak + 1):
+        for end in range(peak, min(len(nodes), start + window)):
+            if any(nodes[i].op in (INPUT, PARAM) for i in range(start, end + 1)):
+                break
+            for d in range(len(nodes[end].shape)):
+                tried += 1
+                if not some_flow_reaches_an_input(nodes, start, end, d):
+                    continue
+                passed += 1
+                t = trace_hoisting(nodes, start, end, d)
+                if t is not None and peak not in t[2]:
+                    out.append((start, end, d) + t)
+    return out, tried, passed
 
 
 def search(nodes, peak: int, window: int):
@@ -270,7 +351,7 @@ def run(nodes, feeds):
     return val
 
 
-def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_len, parts_too=False):
+def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_len, parts_too=False, moved=()):
     """Output of region [start, end] computed segment by segment (section 2.2): the chunkable
     inputs are cut along their traced dims, the others are used whole, the parts of the
     output are concatenated along out_dim.  `val` holds the unchunked values of the inputs."""
@@ -280,13 +361,15 @@ def run_chunked(nodes, val, start, end, out_dim, node_dims, input_dims, chunk_le
         b = min(extent, a + chunk_len)
         frac0, frac1 = a / extent, b / extent
         local, cut = {}, {}
-        for s in region_inputs(nodes, start, end):
+        for s in region_inputs(nodes, start, end) + sorted(moved):   # moved nodes: computed whole beforehand
             x = val[s]
             if s in input_dims:
                 d = input_dims[s]
                 lo, hi = round(frac0 * x.shape[d]), round(frac1 * x.shape[d])
                 cut[s] = np.take(x, range(lo, hi), axis=d)
         for i in range(start, end + 1):
+            if i in moved:
+                continue
             nd = nodes[i]
             args = []
             for which, s in enumerate(nd.inputs):

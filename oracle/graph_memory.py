@@ -24,6 +24,9 @@ Readings where the paper leaves the matter open:
     the extent) at which the region fits the budget, drop those with none, take the one
     with the least L (ties: fewer segments, then search order).  The weights of L are the
     caller's: the paper tunes them and prints no values;
+  * with the graph optimisation of section 3.3 (`hoist`), nodes of a region that are off the
+    chunk flow are computed whole and once ahead of the region's segments; N_node and N_flop
+    of L then count the nodes that run per segment;
   * the search over whole strategies (section 3.4: minimise the sum of L subject to the
     budget, by dynamic programming with a beam) keeps the `beam` cheapest strategies from
     pass to pass; a beam of 1 is the loop above.
@@ -53,10 +56,14 @@ def lifetimes(nodes):
 
 def estimate(nodes, elem_bytes, chunks=()):
     """Activation bytes live at every node (0 for leaves), the peak and the peak node.
-    chunks = [(start, end, out_dim, chunk_len)], disjoint legal regions."""
+    chunks = [(start, end, out_dim, chunk_len[, moved])], disjoint legal regions; `moved` lists
+    the nodes of the region that are computed whole, once, ahead of its segments (section 3.3,
+    graph optimisation): they run first, in order, and those the segments read stay live to
+    the region's end."""
     n = len(nodes)
     born, dies = lifetimes(nodes)
     size = [node_bytes(nd, elem_bytes) for nd in nodes]
+    read_at_all = {s for nd in nodes for s in nd.inputs}      # the others are results of the graph: kept to the end
     region_of = {}
     for ch in chunks:
         for i in range(ch[0], ch[1] + 1):
@@ -68,12 +75,19 @@ def estimate(nodes, elem_bytes, chunks=()):
         if i not in region_of:
             mem[i] = sum(size[j] for j in range(n) if born[j] <= i <= dies[j])
             continue
-        start, end, out_dim, clen = region_of[i]
+        start, end, out_dim, clen = region_of[i][:4]
+        moved = set(region_of[i][4]) if len(region_of[i]) > 4 else set()
+        rest = [j for j in range(start, end + 1) if j not in moved]
+        read_by_rest = {s for j in rest for s in nodes[j].inputs if s in moved}
         extent = nodes[end].shape[out_dim]
         held = sum(size[j] for j in range(n) if born[j] < start <= dies[j])   # X, and whatever lives across
-        inside = sum(size[j] for j in range(start, i + 1) if j != end and dies[j] >= i)
+        if i in moved:
+            mem[i] = held + sum(size[h] for h in moved if h <= i and (h in read_by_rest or dies[h] >= i))
+            continue
+        inside = sum(size[j] for j in rest if j <= i and j != end and dies[j] >= i)
         assert inside * clen % extent == 0
-        mem[i] = held + size[end] + inside * clen // extent                  # X + Y + A / n
+        kept = sum(size[h] for h in moved if h in read_by_rest or dies[h] > end or h not in read_at_all)   # still needed
+        mem[i] = held + kept + size[end] + inside * clen // extent                 # X + Y + A / n
     peak = max(mem)
     return mem, peak, mem.index(peak)
 
@@ -93,46 +107,51 @@ def node_flops(node, nodes):
     return 0                # views and leaves
 
 
-def chunk_cost(nodes, start, end, out_dim, weights):
-    """L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride), section 3.4."""
+def chunk_cost(nodes, start, end, out_dim, weights, moved=()):
+    """L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride), section 3.4,
+    over the nodes that run once per segment."""
     alpha, beta, gamma, lam = weights
-    n_node = end - start + 1
-    n_flop = float(sum(node_flops(nodes[i], nodes) for i in range(start, end + 1)))
+    rest = [i for i in range(start, end + 1) if i not in moved]
+    n_node = len(rest)
+    n_flop = float(sum(node_flops(nodes[i], nodes) for i in rest))
     n_density = n_flop / n_node
     n_stride = float(math.prod(nodes[end].shape[out_dim + 1:]))
     return (alpha * n_node + beta * n_flop) + (gamma * n_density + lam * n_stride)
 
 
-def longest_fitting_len(nodes, elem_bytes, chunks, cand, granule, budget):
+def longest_fitting_len(nodes, elem_bytes, chunks, cand, granule, budget, moved=()):
     """Longest chunk length (multiple of granule, below the extent) at which every node of the
     candidate region is within the budget, or 0."""
     start, end, out_dim = cand
     extent = nodes[end].shape[out_dim]
     clen = (extent - 1) // granule * granule
     while clen >= granule:
-        mem, _, _ = estimate(nodes, elem_bytes, list(chunks) + [(start, end, out_dim, clen)])
+        mem, _, _ = estimate(nodes, elem_bytes, list(chunks) + [(start, end, out_dim, clen, tuple(moved))])
         if max(mem[start:end + 1]) <= budget:
             return clen
         clen -= granule
     return 0
 
 
-def feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node):
-    """One pass's choices: (cost, segments, (start, end, out_dim, chunk_len)) in search order."""
+def feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node, hoist=False):
+    """One pass's choices: (cost, segments, (start, end, out_dim, chunk_len[, moved])) in search order."""
     out = []
-    for start, end, dim, node_dims, input_dims in S.search(nodes, peak_node, window)[0]:
+    found = S.search_hoisting(nodes, peak_node, window)[0] if hoist else \
+        [c + (set(),) for c in S.search(nodes, peak_node, window)[0]]
+    for start, end, dim, node_dims, input_dims, moved in found:
         if any(start <= c[1] and c[0] <= end for c in chunks):
             continue
         g = S.chunk_granule(nodes, end, dim, node_dims, input_dims)
-        clen = longest_fitting_len(nodes, elem_bytes, chunks, (start, end, dim), g, budget)
+        clen = longest_fitting_len(nodes, elem_bytes, chunks, (start, end, dim), g, budget, moved)
         if clen == 0:
             continue
         extent = nodes[end].shape[dim]
-        out.append((chunk_cost(nodes, start, end, dim, weights), -(-extent // clen), (start, end, dim, clen)))
+        chunk = (start, end, dim, clen, tuple(sorted(moved))) if hoist else (start, end, dim, clen)
+        out.append((chunk_cost(nodes, start, end, dim, weights, moved), -(-extent // clen), chunk))
     return out
 
 
-def plan(nodes, elem_bytes, budget, window, weights, beam=1):
+def plan(nodes, elem_bytes, budget, window, weights, beam=1, hoist=False):
     """Chunks [(start, end, out_dim, chunk_len)] chosen pass by pass until the peak fits;
     returns (chunks, peak) or raises ValueError when no strategy in the beam gets there.
 
@@ -154,7 +173,7 @@ def plan(nodes, elem_bytes, budget, window, weights, beam=1):
             all_fit = False
             if any(c[0] <= peak_node <= c[1] for c in chunks):
                 continue                                  # the peak lies in a region already chunked
-            for cost, seg, cand in feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node):
+            for cost, seg, cand in feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node, hoist):
                 new = chunks + [cand]
                 if tuple(sorted(new)) in known:
                     continue                              # the same chunks, chosen in another order

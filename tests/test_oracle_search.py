@@ -101,3 +101,42 @@ def test_window_bounds_the_regions():
         cands, tried, passed = S.search(nodes, peak, w)
         assert all(e - s < w and s <= peak <= e for s, e, *_ in cands)
     assert len(S.search(nodes, peak, 6)[0]) > len(S.search(nodes, peak, 3)[0]) > len(S.search(nodes, peak, 1)[0]) > 0
+
+
+def test_graph_optimisation_moves_nodes_off_the_flow_ahead_of_the_region():
+    """Section 3.3, graph optimisation.  Every candidate of the search with it, run with the moved
+    nodes computed once and whole, reproduces the unchunked output in segments of exactly the
+    chunk length; every strict candidate is found unchanged; the cases with a known answer."""
+    from tests import graphs as G
+    nodes, nm, val = small_block()
+    t = S.trace_hoisting(nodes, nm["q_flat"], nm["ctx"], 1)          # attention cut along the queries
+    assert t is not None and t[2] == {nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")}
+    assert t[1] == {nm["qkv"]: 1}
+    assert S.trace_hoisting(nodes, nm["u"], nm["ctx"], 1) is None     # the first node would have to move
+    assert S.trace_hoisting(nodes, nm["scores"], nm["ctx_h"], 3) is None   # the head dim: probabilities whole -> end's producer moves
+    n_checked = n_moved = 0
+    graphs = [nodes] + [[S.Node(op, i, sh, at, G.FNS.get(fn)) for op, i, sh, at, fn in G.random_graph(seed, 13)]
+                        for seed in range(40)]
+    for gi, gr in enumerate(graphs):
+        v = val if gi == 0 else S.run(gr, S.random_feeds(gr, gi))
+        seen = set()
+        for peak in range(len(gr)):
+            if gr[peak].op in (S.INPUT, S.PARAM):
+                continue
+            strict = {(c[0], c[1], c[2]): c for c in S.search(gr, peak, 10)[0]}
+            found = S.search_hoisting(gr, peak, 10)[0]
+            by_key = {(c[0], c[1], c[2]): c for c in found}
+            for key, c in strict.items():
+                assert by_key[key][3:] == (c[3], c[4], set())
+            for start, end, dim, node_dims, input_dims, moved in found:
+                if (start, end, dim) in seen:
+                    continue
+                seen.add((start, end, dim))
+                assert start not in moved and end not in moved and peak not in moved
+                g = S.chunk_granule(gr, end, dim, node_dims, input_dims)
+                got, parts = S.run_chunked(gr, v, start, end, dim, node_dims, input_dims, g, parts_too=True, moved=moved)
+                assert all(p.shape[dim] == g for p in parts)
+                assert np.allclose(got, v[end], rtol=0, atol=1e-9), (gi, start, end, dim)
+                n_checked += 1
+                n_moved += bool(moved)
+    assert n_checked > 1500 and n_moved > 60, (n_checked, n_moved)
