@@ -76,33 +76,43 @@ typedef struct ac_chunk_candidate {
  * flow must pass every node of the region, each in one dimension only (so no node of the
  * region may be read whole by another), meet no interrupted dimension, and reach at least
  * one input of the region.  An input may be cut for one operand and read whole by another.
- * *legal = 1 or 0.  node_dims
- * (n_nodes entries, caller's) receives, for a legal chunk, the chunk dimension of every node
- * of the region and, for every node outside it that the region reads, the dimension in
- * which that input is cut, or -1 (not part of the chunk; input used whole).
+ *
+ * hoist = 1 applies the graph optimisation of section 3.3 first: nodes of the region that the
+ * flow does not pass, or that another node reads whole, are taken out of it together with
+ * everything inside the region they depend on; they are computed whole, once, ahead of the
+ * segments and count as inputs of what remains, which must then satisfy the rules.  The
+ * region's first and last node must remain.  hoist = 0: such a region is illegal.
+ *
+ * *legal = 1 or 0.  node_dims (n_nodes entries, caller's) receives, for a legal chunk, the
+ * chunk dimension of every node that runs per segment and, for every input (a node outside
+ * the region, or a moved one) that is cut, the dimension in which it is cut; -1 otherwise.
+ * node_moved (n_nodes bytes, may be NULL) receives 1 for the moved nodes.
  * Returns AC_OK, or AC_ERR_ARG for a malformed graph or region (then *legal is 0).
  */
-int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
-                   int32_t* node_dims, int* legal);
+int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim, int hoist,
+                   int32_t* node_dims, uint8_t* node_moved, int* legal);
 
 /*
  * All legal chunks whose region holds node `peak` and spans at most `window` nodes (the
  * local window of section 3.3, "complexity optimization").  A (region, dimension) pair is
  * traced in full only if some uninterrupted flow leads from that dimension to an input of the
- * region at all (first stage: no rule checked, stopped at the first input reached).  Candidates are written in order of start, end, out_dim; out (max_out entries)
- * and node_dims (max_out * n_nodes entries, one ac_chunk_trace row per candidate) are the
- * caller's; either may be NULL with max_out = 0 to count only.  *n_found counts all legal
- * chunks even beyond max_out; n_tried / n_passed (may be NULL) count the pairs tried and
- * those that passed the first stage.
+ * region at all (first stage: no rule checked, stopped at the first input reached).  With
+ * hoist = 1 a chunk that would move `peak` itself out of the region is not reported.
+ * Candidates are written in order of start, end, out_dim; out (max_out entries), node_dims
+ * and node_moved (max_out * n_nodes entries each, one ac_chunk_trace row per candidate;
+ * node_moved may be NULL) are the caller's; out and node_dims may be NULL with max_out = 0
+ * to count only.  *n_found counts all legal chunks even beyond max_out; n_tried / n_passed
+ * (may be NULL) count the pairs tried and those that passed the first stage.
  */
-int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window,
-                    ac_chunk_candidate* out, int32_t* node_dims, int max_out,
+int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window, int hoist,
+                    ac_chunk_candidate* out, int32_t* node_dims, uint8_t* node_moved, int max_out,
                     int* n_found, int* n_tried, int* n_passed);
 
 /* One chosen chunk: region [start, end], cut along out_dim of node `end` in segments of
- * chunk_len (the last may be shorter).  reserved is 0. */
+ * chunk_len (the last may be shorter); hoist as in ac_chunk_trace (the moved nodes follow
+ * from the region and are not stored). */
 typedef struct ac_graph_chunk {
-  int32_t start, end, out_dim, reserved;
+  int32_t start, end, out_dim, hoist;
   int64_t chunk_len;
 } ac_graph_chunk;
 
@@ -114,7 +124,8 @@ typedef struct ac_graph_chunk {
  * bytes at a node are all tensors live while it runs, M = mem(X) + mem(Y) + mem(A).  Inside
  * a chunked region, M = mem(X) + mem(Y) + mem(A) / n: the region's result is held whole,
  * everything live at the region's entry stays live to its end, and the region's own tensors
- * have chunk_len / extent of their size.
+ * have chunk_len / extent of their size.  Moved nodes (hoist) run first, in order and whole;
+ * those the segments read stay live to the region's end and count with X.
  * chunks: legal (else AC_ERR_ILLEGAL_CHUNK_DIM), apart from each other, chunk_len a multiple
  * of the chunk's granule in 1..extent (else AC_ERR_ARG).  node_bytes (n_nodes entries, may
  * be NULL) receives the bytes per node, 0 for inputs and parameters; *peak_node is the
@@ -127,33 +138,35 @@ int ac_graph_estimate(const ac_graph_node* nodes, int n_nodes, int elem_bytes,
 /*
  * Selection cost of a chunk (section 3.4): L = L_macro + L_micro with
  * L_macro = weights[0] N_node + weights[1] N_flop, L_micro = weights[2] N_density +
- * weights[3] N_stride.  N_node: nodes of the region; N_flop: their operations (2 per
- * multiply-add of LINEAR, MATMUL and CONTRACT; 1 per element of ELEMENTWISE, 5 of
- * SOFTMAX_LAST, 8 of NORM_LAST; none for the reshaping ops); N_density = N_flop / N_node;
- * N_stride: elements between neighbours along out_dim in the contiguous result of `end`.
- * The paper tunes the four weights and prints no values: they are the caller's.
+ * weights[3] N_stride.  N_node: nodes of the region that run per segment (all of them, or
+ * those not moved when hoist = 1; the chunk must then be legal, else
+ * AC_ERR_ILLEGAL_CHUNK_DIM); N_flop: their operations (2 per multiply-add of LINEAR, MATMUL
+ * and CONTRACT; 1 per element of ELEMENTWISE, 5 of SOFTMAX_LAST, 8 of NORM_LAST; none for the
+ * reshaping ops); N_density = N_flop / N_node; N_stride: elements between neighbours along
+ * out_dim in the contiguous result of `end`.  The paper tunes the four weights and prints
+ * no values: they are the caller's.
  */
-int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
+int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim, int hoist,
                         const double* weights, double* cost);
 
 /*
  * Chunks the graph pass by pass until its estimated peak is at most budget_bytes (section
  * 3.2: estimate, search around the peak node, select; repeated), looking for the strategy
  * S = [s_1 .. s_l] of least summed cost (section 3.4).  One pass extends a strategy by one
- * chunk: the legal chunks of ac_chunk_search(peak node, window) that touch no region chosen
- * before get the longest chunk_len (multiple of the granule, below the extent) at which
- * their region fits the budget; those with none are dropped.  The `beam` strategies of least
- * summed cost (ties: fewer segments in all, then the order they were made in) are kept from
- * pass to pass; strategies that fit stay as they are; the call ends when all that are kept
- * fit and returns the first.  beam = 1: every pass takes its cheapest candidate.
+ * chunk: the legal chunks of ac_chunk_search(peak node, window, hoist) that touch no region
+ * chosen before get the longest chunk_len (multiple of the granule, below the extent) at
+ * which their region fits the budget; those with none are dropped.  The `beam` strategies of
+ * least summed cost (ties: fewer segments in all, then the order they were made in) are kept
+ * from pass to pass; strategies that fit stay as they are; the call ends when all that are
+ * kept fit and returns the first.  beam = 1: every pass takes its cheapest candidate.
  * out (max_out entries, caller's) receives the chunks in the order chosen, *n_out their
  * number, *peak_bytes the estimate with them.  AC_ERR_BUDGET_INFEASIBLE when no strategy in
  * the beam can be extended (*n_out = 0, *peak_bytes = the unchunked peak); AC_ERR_ARG when
  * the strategy has more than max_out chunks.
  */
 int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
-                  int window, const double* weights, int beam, ac_graph_chunk* out, int max_out,
-                  int* n_out, uint64_t* peak_bytes);
+                  int window, const double* weights, int beam, int hoist, ac_graph_chunk* out,
+                  int max_out, int* n_out, uint64_t* peak_bytes);
 
 #ifdef __cplusplus
 }

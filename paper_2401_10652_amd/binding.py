@@ -85,12 +85,12 @@ class ac_chunk_candidate(C.Structure):
 
 
 class ac_graph_chunk(C.Structure):
-    _fields_ = [("start", C.c_int32), ("end", C.c_int32), ("out_dim", C.c_int32), ("reserved", C.c_int32),
+    _fields_ = [("start", C.c_int32), ("end", C.c_int32), ("out_dim", C.c_int32), ("hoist", C.c_int32),
                 ("chunk_len", C.c_int64)]
 
 
 I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
-I32P, INTP = C.POINTER(C.c_int32), C.POINTER(C.c_int)
+I32P, INTP, U8P = C.POINTER(C.c_int32), C.POINTER(C.c_int), C.POINTER(C.c_uint8)
 
 # name -> (restype, argtypes): every symbol the headers under include/ declare.
 SIGNATURES = {
@@ -118,14 +118,14 @@ SIGNATURES = {
     "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose_square_inplace": (INT, [VP, I64, I64, I64, I64, INT, VP]),
     "ac_op_layernorm_channel_major": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
-    "ac_chunk_trace": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, I32P, INTP]),
-    "ac_chunk_search": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, C.POINTER(ac_chunk_candidate), I32P, INT,
-                              INTP, INTP, INTP]),
+    "ac_chunk_trace": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, INT, I32P, U8P, INTP]),
+    "ac_chunk_search": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, C.POINTER(ac_chunk_candidate), I32P, U8P,
+                              INT, INTP, INTP, INTP]),
     "ac_graph_estimate": (INT, [C.POINTER(ac_graph_node), INT, INT, C.POINTER(ac_graph_chunk), INT, C.POINTER(U64),
                                 C.POINTER(U64), INTP]),
-    "ac_graph_chunk_cost": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, C.POINTER(C.c_double),
+    "ac_graph_chunk_cost": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, INT, C.POINTER(C.c_double),
                                   C.POINTER(C.c_double)]),
-    "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double), INT,
+    "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double), INT, INT,
                             C.POINTER(ac_graph_chunk), INT, INTP, C.POINTER(U64)]),
 }
 
@@ -397,40 +397,53 @@ def graph_nodes(spec):
     return arr
 
 
-def ac_chunk_trace(nodes, start, end, out_dim):
-    """Chunk dims per node (list, -1 = not cut) of a legal chunk, or None."""
+def ac_chunk_trace(nodes, start, end, out_dim, hoist=False):
+    """Chunk dims per node (list, -1 = not cut) of a legal chunk, or None; with hoist, a pair
+    (dims, sorted list of the nodes moved ahead of the region)."""
     row = (C.c_int32 * len(nodes))()
+    moved = (C.c_uint8 * len(nodes))()
     legal = C.c_int(0)
-    _check(lib().ac_chunk_trace(nodes, len(nodes), start, end, out_dim, row, C.byref(legal)), "ac_chunk_trace")
-    return list(row) if legal.value else None
+    _check(lib().ac_chunk_trace(nodes, len(nodes), start, end, out_dim, int(hoist), row, moved, C.byref(legal)),
+           "ac_chunk_trace")
+    if not legal.value:
+        return None
+    return (list(row), [i for i, m in enumerate(moved) if m]) if hoist else list(row)
 
 
-def ac_chunk_search(nodes, peak, window, max_out=None):
-    """(candidates, n_found, n_tried, n_passed); a candidate is (start, end, out_dim, granule, node_dims)."""
+def ac_chunk_search(nodes, peak, window, max_out=None, hoist=False):
+    """(candidates, n_found, n_tried, n_passed); a candidate is (start, end, out_dim, granule,
+    node_dims), with hoist followed by the sorted list of its moved nodes."""
     n = len(nodes)
     found, tried, passed = C.c_int(0), C.c_int(0), C.c_int(0)
     if max_out is None:
-        _check(lib().ac_chunk_search(nodes, n, peak, window, None, None, 0, C.byref(found), None, None),
+        _check(lib().ac_chunk_search(nodes, n, peak, window, int(hoist), None, None, None, 0, C.byref(found), None, None),
                "ac_chunk_search")
         max_out = found.value
     out = (ac_chunk_candidate * max(max_out, 1))()
     rows = (C.c_int32 * (max(max_out, 1) * n))()
-    _check(lib().ac_chunk_search(nodes, n, peak, window, out, rows, max_out, C.byref(found), C.byref(tried),
-                                 C.byref(passed)), "ac_chunk_search")
-    cands = [(c.start, c.end, c.out_dim, c.granule, list(rows[i * n:(i + 1) * n]))
-             for i, c in enumerate(out[:min(max_out, found.value)])]
+    moved = (C.c_uint8 * (max(max_out, 1) * n))()
+    _check(lib().ac_chunk_search(nodes, n, peak, window, int(hoist), out, rows, moved, max_out, C.byref(found),
+                                 C.byref(tried), C.byref(passed)), "ac_chunk_search")
+    cands = []
+    for i, c in enumerate(out[:min(max_out, found.value)]):
+        cand = (c.start, c.end, c.out_dim, c.granule, list(rows[i * n:(i + 1) * n]))
+        if hoist:
+            cand += ([j for j in range(n) if moved[i * n + j]],)
+        cands.append(cand)
     return cands, found.value, tried.value, passed.value
 
 
 def _chunks(chunks):
+    """ac_graph_chunk array from (start, end, out_dim, chunk_len[, hoist]) tuples."""
     arr = (ac_graph_chunk * max(len(chunks), 1))()
-    for c, (start, end, dim, clen) in zip(arr, chunks):
-        c.start, c.end, c.out_dim, c.chunk_len = start, end, dim, clen
+    for c, ch in zip(arr, chunks):
+        c.start, c.end, c.out_dim, c.chunk_len = ch[:4]
+        c.hoist = int(bool(ch[4])) if len(ch) > 4 else 0
     return arr
 
 
 def ac_graph_estimate(nodes, elem_bytes, chunks=()):
-    """(bytes per node, peak bytes, peak node) with chunks = [(start, end, out_dim, chunk_len)]."""
+    """(bytes per node, peak bytes, peak node) with chunks = [(start, end, out_dim, chunk_len[, hoist])]."""
     per_node = (C.c_uint64 * len(nodes))()
     peak, peak_node = C.c_uint64(0), C.c_int(0)
     _check(lib().ac_graph_estimate(nodes, len(nodes), elem_bytes, _chunks(chunks), len(chunks), per_node,
@@ -438,18 +451,19 @@ def ac_graph_estimate(nodes, elem_bytes, chunks=()):
     return list(per_node), peak.value, peak_node.value
 
 
-def ac_graph_chunk_cost(nodes, start, end, out_dim, weights):
+def ac_graph_chunk_cost(nodes, start, end, out_dim, weights, hoist=False):
     w = (C.c_double * 4)(*weights)
     cost = C.c_double(0)
-    _check(lib().ac_graph_chunk_cost(nodes, len(nodes), start, end, out_dim, w, C.byref(cost)), "ac_graph_chunk_cost")
+    _check(lib().ac_graph_chunk_cost(nodes, len(nodes), start, end, out_dim, int(hoist), w, C.byref(cost)),
+           "ac_graph_chunk_cost")
     return cost.value
 
 
-def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, beam=1, max_out=64):
-    """(chunks, peak bytes): chunks [(start, end, out_dim, chunk_len)] in the order chosen."""
+def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, beam=1, max_out=64, hoist=False):
+    """(chunks, peak bytes): chunks (start, end, out_dim, chunk_len), with hoist (.., 1), in the order chosen."""
     w = (C.c_double * 4)(*weights)
     out = (ac_graph_chunk * max_out)()
     n_out, peak = C.c_int(0), C.c_uint64(0)
-    _check(lib().ac_graph_plan(nodes, len(nodes), elem_bytes, budget_bytes, window, w, beam, out, max_out, C.byref(n_out),
-                               C.byref(peak)), "ac_graph_plan")
-    return [(c.start, c.end, c.out_dim, c.chunk_len) for c in out[:n_out.value]], peak.value
+    _check(lib().ac_graph_plan(nodes, len(nodes), elem_bytes, budget_bytes, window, w, beam, int(hoist), out, max_out,
+                               C.byref(n_out), C.byref(peak)), "ac_graph_plan")
+    return [(c.start, c.end, c.out_dim, c.chunk_len) + ((1,) if hoist else ()) for c in out[:n_out.value]], peak.value

@@ -172,9 +172,9 @@ struct Tracer {
   std::vector<int> last_use;   // highest index of a node that reads node i, -1 if none
   std::vector<int> leaves_upto;  // number of INPUT/PARAM nodes among 0..i-1
   std::vector<int> queue;
-  std::vector<uint8_t> seen;
+  std::vector<uint8_t> seen, read_whole;
 
-  Tracer(const ac_graph_node* nodes, int n) : g(nodes), n_nodes(n), last_use(n, -1), leaves_upto(n + 1, 0), seen(n, 0) {
+  Tracer(const ac_graph_node* nodes, int n) : g(nodes), n_nodes(n), last_use(n, -1), leaves_upto(n + 1, 0), seen(n, 0), read_whole(n, 0) {
     for (int i = 0; i < n; ++i) {
       for (int k = 0; k < g[i].n_inputs; ++k) last_use[g[i].inputs[k]] = i;
       leaves_upto[i + 1] = leaves_upto[i] + (is_leaf(g[i]) ? 1 : 0);
@@ -184,49 +184,76 @@ struct Tracer {
 
   bool holds_leaf(int start, int end) const { return leaves_upto[end + 1] != leaves_upto[start]; }
 
-  // Rules 1 to 4 for one candidate; fills row (n_nodes entries) and the granule.
-  bool trace(int start, int end, int out_dim, int32_t* row, int64_t* granule) {
+  // Rules 1 to 4 for one candidate; fills row (n_nodes entries: chunk dim of every node of the
+  // region and of every input that is cut, else -1) and the granule.
+  //
+  // With hoist (the graph optimisation of section 3.3) nodes of the region that the flow does
+  // not pass, or that another node reads whole, do not make the chunk illegal: they are marked
+  // in moved[] together with everything inside the region they depend on (to be computed whole,
+  // once, ahead of the segments) and the rest is traced again with them as inputs, until
+  // nothing more has to move.  The first and the last node must stay.
+  bool trace(int start, int end, int out_dim, bool hoist, int32_t* row, uint8_t* moved, int64_t* granule) {
     // Form Y^c = F(X^c, X^nc): no intermediate of the region is read after `end`.
     for (int i = start; i < end; ++i)
       if (last_use[i] > end) return false;
-    for (int i = 0; i < n_nodes; ++i) row[i] = -1;
-    row[end] = out_dim;
-    queue.clear();
-    queue.push_back(end);
+    for (int i = start; i <= end; ++i) moved[i] = 0;
     const int64_t ext_out = g[end].shape[out_dim];
-    int64_t gran = 1;
-    int reached_inputs = 0, passed = 1;
-    for (size_t head = 0; head < queue.size(); ++head) {
-      const ac_graph_node& n = g[queue[head]];
-      const int c = row[queue[head]];
-      for (int k = 0; k < n.n_inputs; ++k) {
-        const int d = step(g, n, c, k);
-        if (d == kCut) return false;   // the flow is interrupted
-        const int s = n.inputs[k];
-        if (d == kWhole) {
-          if (s >= start) return false;  // a node of the region read whole: every segment would compute all of it
-          continue;
-        }
-        if (row[s] >= 0) {
-          if (row[s] != d) return false;  // one node (or input), two chunk dimensions
-          continue;
-        }
-        row[s] = d;
-        // a segment of len elements of the output covers len * ext / ext_out elements here
-        const int64_t ext = g[s].shape[d];
-        gran = std::lcm(gran, ext_out / std::gcd(ext_out, ext));
-        if (s >= start) {
-          queue.push_back(s);
-          ++passed;
-        } else {
-          ++reached_inputs;
+    for (;;) {
+      for (int i = 0; i < n_nodes; ++i) row[i] = -1;
+      for (int i = start; i <= end; ++i) read_whole[i] = 0;
+      row[end] = out_dim;
+      queue.clear();
+      queue.push_back(end);
+      int64_t gran = 1;
+      int reached_inputs = 0;
+      for (size_t head = 0; head < queue.size(); ++head) {
+        const ac_graph_node& n = g[queue[head]];
+        const int c = row[queue[head]];
+        for (int k = 0; k < n.n_inputs; ++k) {
+          const int d = step(g, n, c, k);
+          if (d == kCut) return false;   // the flow is interrupted
+          const int s = n.inputs[k];
+          const bool in_rest = s >= start && !moved[s];
+          if (d == kWhole) {
+            // a node of the region read whole: every segment would compute all of it
+            if (in_rest) {
+              if (!hoist) return false;
+              read_whole[s] = 1;
+            }
+            continue;
+          }
+          if (row[s] >= 0) {
+            if (row[s] != d) return false;  // one node (or input), two chunk dimensions
+            continue;
+          }
+          row[s] = d;
+          // a segment of len elements of the output covers len * ext / ext_out elements here
+          const int64_t ext = g[s].shape[d];
+          gran = std::lcm(gran, ext_out / std::gcd(ext_out, ext));
+          if (in_rest) queue.push_back(s);
+          else ++reached_inputs;
         }
       }
+      // nodes on no flow, or read whole: illegal, or (hoist) moved with their ancestors in the region
+      bool grew = false;
+      for (int i = end; i >= start; --i) {
+        if (moved[i]) continue;
+        bool go = row[i] < 0 || read_whole[i];
+        if (go && !hoist) return false;
+        if (go) {
+          if (i == start || i == end) return false;
+          moved[i] = 1;
+          grew = true;
+          // descending order: inputs of a moved node are visited later in this loop
+          for (int k = 0; k < g[i].n_inputs; ++k)
+            if (g[i].inputs[k] >= start) read_whole[g[i].inputs[k]] = 1;
+        }
+      }
+      if (grew) continue;
+      if (reached_inputs == 0) return false;        // no input can be cut
+      *granule = gran;
+      return true;
     }
-    if (passed != end - start + 1) return false;  // some node is on no flow
-    if (reached_inputs == 0) return false;        // no input can be cut
-    *granule = gran;
-    return true;
   }
 
   // First stage of the two-stage search: does any uninterrupted flow lead from the output
@@ -258,8 +285,9 @@ struct Tracer {
   // Every legal chunk whose region holds `peak` and spans at most `window` nodes, in order of
   // start, end, dimension (the local window and the two stages of section 3.3).
   template <class F>
-  void candidates(int peak, int window, int* tried, int* passed, F&& on_chunk) {
+  void candidates(int peak, int window, bool hoist, int* tried, int* passed, F&& on_chunk) {
     std::vector<int32_t> row(n_nodes);
+    std::vector<uint8_t> moved(n_nodes, 0);
     const int first = peak - window + 1 > 0 ? peak - window + 1 : 0;
     for (int start = first; start <= peak; ++start) {
       const int past = start + window < n_nodes ? start + window : n_nodes;
@@ -270,7 +298,9 @@ struct Tracer {
           if (!reaches_an_input(start, end, d)) continue;
           ++*passed;
           int64_t gran = 1;
-          if (trace(start, end, d, row.data(), &gran)) on_chunk(start, end, d, gran, row.data());
+          // a chunk that moves the peak node out of the region does nothing for the peak
+          if (trace(start, end, d, hoist, row.data(), moved.data(), &gran) && !moved[peak])
+            on_chunk(start, end, d, gran, row.data(), moved.data());
         }
       }
     }
@@ -295,6 +325,7 @@ struct Memory {
   std::vector<uint64_t> size;   // bytes of each node's result (0 for parameters)
   std::vector<int> dies;        // last reader; n - 1 for results nobody reads; -1 for unread leaves
   std::vector<uint64_t> whole;  // live bytes at each node of the unchunked graph
+  mutable std::vector<uint8_t> keep_scratch;
 
   Memory(const Tracer& tr, int elem_bytes) : t(tr), n(tr.n_nodes), size(n), dies(n), whole(n, 0) {
     const ac_graph_node* g = t.g;
@@ -315,37 +346,66 @@ struct Memory {
     }
   }
 
-  // What a region holds at any segment length: X and everything else alive at its entry, plus Y.
-  uint64_t held(int start, int end) const { return whole[start] - size[start] + size[end]; }
-
-  // Unchunked bytes of the region's own tensors live at each of its nodes (the A of each node).
-  void inside(int start, int end, std::vector<uint64_t>& a) const {
+  // Bytes live at every node of a chunked region, as fixed part + part that scales with the
+  // segment length: bytes(i) = fixed[i] + scaled[i] * len / extent.  moved[] marks the nodes
+  // computed whole ahead of the segments: they run first, in order, with ordinary lifetimes,
+  // except that those the segments read stay live to the region's end.
+  void region(int start, int end, const uint8_t* moved, std::vector<uint64_t>& fixed,
+              std::vector<uint64_t>& scaled) const {
     const ac_graph_node* g = t.g;
-    a.assign(end - start + 1, 0);
+    const int count = end - start + 1;
+    fixed.assign(count, 0);
+    scaled.assign(count, 0);
+    const uint64_t entry = whole[start] - size[start];   // X and everything else alive at the region's entry
+    // moved nodes the segments read, and moved results that outlive the region
+    uint64_t kept = 0;
+    std::vector<uint8_t>& keep = keep_scratch;
+    keep.assign(count, 0);
+    for (int i = start; i <= end; ++i) {
+      if (moved[i]) continue;
+      for (int k = 0; k < g[i].n_inputs; ++k) {
+        const int s = g[i].inputs[k];
+        if (s >= start && moved[s]) keep[s - start] = 1;
+      }
+    }
+    for (int h = start; h <= end; ++h)
+      if (moved[h] && (keep[h - start] || t.last_use[h] < 0 || t.last_use[h] > end)) {
+        keep[h - start] = 1;
+        kept += size[h];
+      }
+    // ahead of the segments: the moved nodes in order
+    for (int i = start; i <= end; ++i) {
+      if (!moved[i]) continue;
+      uint64_t live = entry;
+      for (int h = start; h <= i; ++h)
+        if (moved[h] && (keep[h - start] || t.last_use[h] >= i)) live += size[h];
+      fixed[i - start] = live;
+    }
+    // the segments: Y whole, the region's own tensors at their segment's share
     uint64_t cur = 0;
     for (int i = start; i <= end; ++i) {
+      if (moved[i]) continue;
       if (i != end) cur += size[i];
-      a[i - start] = cur;
+      fixed[i - start] = entry + kept + size[end];
+      scaled[i - start] = cur;
       for (int k = 0; k < g[i].n_inputs; ++k) {
         const int s = g[i].inputs[k];
         bool counted = false;
         for (int q = 0; q < k; ++q) counted |= g[i].inputs[q] == s;
-        if (!counted && s >= start && t.last_use[s] == i) cur -= size[s];
+        if (!counted && s >= start && !moved[s] && t.last_use[s] == i) cur -= size[s];
       }
     }
   }
 
   // Longest chunk length (multiple of granule, below the extent) at which the region fits, or 0.
-  int64_t longest_len(int start, int end, int64_t extent, int64_t granule, uint64_t budget,
-                      std::vector<uint64_t>& scratch) const {
-    const uint64_t fixed = held(start, end);
-    if (fixed > budget) return 0;
-    inside(start, end, scratch);
-    uint64_t a_max = 0;
-    for (uint64_t v : scratch) a_max = v > a_max ? v : a_max;
+  int64_t longest_len(int start, int end, const uint8_t* moved, int64_t extent, int64_t granule, uint64_t budget,
+                      std::vector<uint64_t>& fixed, std::vector<uint64_t>& scaled) const {
+    region(start, end, moved, fixed, scaled);
     int64_t len = (extent - 1) / granule * granule;
-    if (a_max > 0) {
-      const u128 fit = (u128)(budget - fixed) * (u128)extent / a_max;
+    for (size_t i = 0; i < fixed.size(); ++i) {
+      if (fixed[i] > budget) return 0;
+      if (scaled[i] == 0) continue;
+      const u128 fit = (u128)(budget - fixed[i]) * (u128)extent / scaled[i];
       if (fit < (u128)len) len = (int64_t)fit / granule * granule;
     }
     return len;
@@ -375,34 +435,44 @@ uint64_t node_flops(const ac_graph_node* g, const ac_graph_node& n) {
   }
 }
 
-// L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride)
-double chunk_cost(const ac_graph_node* g, int start, int end, int out_dim, const double* w) {
+// L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride), over the nodes that
+// run once per segment (moved may be null: all of the region).
+double chunk_cost(const ac_graph_node* g, int start, int end, int out_dim, const uint8_t* moved, const double* w) {
   uint64_t flops = 0;
-  for (int i = start; i <= end; ++i) flops += node_flops(g, g[i]);
+  int count = 0;
+  for (int i = start; i <= end; ++i) {
+    if (moved && moved[i]) continue;
+    flops += node_flops(g, g[i]);
+    ++count;
+  }
   uint64_t stride = 1;
   for (int d = out_dim + 1; d < g[end].rank; ++d) stride *= (uint64_t)g[end].shape[d];
-  const double n_node = (double)(end - start + 1), n_flop = (double)flops;
+  const double n_node = (double)count, n_flop = (double)flops;
   const double n_density = n_flop / n_node, n_stride = (double)stride;
   const double macro = w[0] * n_node + w[1] * n_flop;
   const double micro = w[2] * n_density + w[3] * n_stride;
   return macro + micro;
 }
 
-// Checks a caller's chunk list (legal, lengths on the granule, regions apart) and fills
-// region_of[i] = index of the chunk that holds node i, or -1.
-int check_chunks(Tracer& t, const ac_graph_chunk* chunks, int n_chunks, std::vector<int>& region_of) {
+// Checks a caller's chunk list (legal, lengths on the granule, regions apart), fills
+// region_of[i] = index of the chunk that holds node i, or -1, and moved[c] = the nodes chunk c
+// computes ahead of its segments (all zero without hoist).
+int check_chunks(Tracer& t, const ac_graph_chunk* chunks, int n_chunks, std::vector<int>& region_of,
+                 std::vector<std::vector<uint8_t>>& moved) {
   const int n = t.n_nodes;
   region_of.assign(n, -1);
+  moved.assign(n_chunks, std::vector<uint8_t>(n, 0));
   std::vector<int32_t> row(n);
   for (int c = 0; c < n_chunks; ++c) {
     const ac_graph_chunk& ch = chunks[c];
     if (ch.start < 0 || ch.end < ch.start || ch.end >= n || t.holds_leaf(ch.start, ch.end) || ch.out_dim < 0 ||
-        ch.out_dim >= t.g[ch.end].rank) {
-      ac::set_error("chunk %d: region [%d, %d] or dim %d not in the graph", c, ch.start, ch.end, ch.out_dim);
+        ch.out_dim >= t.g[ch.end].rank || (ch.hoist != 0 && ch.hoist != 1)) {
+      ac::set_error("chunk %d: region [%d, %d], dim %d or hoist %d not valid for the graph", c, ch.start, ch.end,
+                    ch.out_dim, ch.hoist);
       return AC_ERR_ARG;
     }
     int64_t gran = 1;
-    if (!t.trace(ch.start, ch.end, ch.out_dim, row.data(), &gran)) {
+    if (!t.trace(ch.start, ch.end, ch.out_dim, ch.hoist != 0, row.data(), moved[c].data(), &gran)) {
       ac::set_error("chunk %d: region [%d, %d] cannot be cut along dim %d", c, ch.start, ch.end, ch.out_dim);
       return AC_ERR_ILLEGAL_CHUNK_DIM;
     }
@@ -424,23 +494,23 @@ int check_chunks(Tracer& t, const ac_graph_chunk* chunks, int n_chunks, std::vec
 }
 
 // Live bytes at every node under the chunk list; returns the peak and its first node.
-uint64_t estimate(const Memory& m, const ac_graph_chunk* chunks, const std::vector<int>& region_of,
-                  std::vector<uint64_t>& bytes, int* peak_node) {
+uint64_t estimate(const Memory& m, const ac_graph_chunk* chunks, const std::vector<std::vector<uint8_t>>& moved,
+                  const std::vector<int>& region_of, std::vector<uint64_t>& bytes, int* peak_node) {
   const int n = m.n;
   bytes.assign(n, 0);
-  std::vector<uint64_t> a;
+  std::vector<uint64_t> fixed, scaled;
   for (int i = 0; i < n;) {
     if (region_of[i] < 0) {
       bytes[i] = m.whole[i];
       ++i;
       continue;
     }
-    const ac_graph_chunk& ch = chunks[region_of[i]];
-    const uint64_t fixed = m.held(ch.start, ch.end);
+    const int c = region_of[i];
+    const ac_graph_chunk& ch = chunks[c];
     const uint64_t extent = (uint64_t)m.t.g[ch.end].shape[ch.out_dim];
-    m.inside(ch.start, ch.end, a);
+    m.region(ch.start, ch.end, moved[c].data(), fixed, scaled);
     for (int k = ch.start; k <= ch.end; ++k)
-      bytes[k] = fixed + (uint64_t)((u128)a[k - ch.start] * (u128)ch.chunk_len / extent);
+      bytes[k] = fixed[k - ch.start] + (uint64_t)((u128)scaled[k - ch.start] * (u128)ch.chunk_len / extent);
     i = ch.end + 1;
   }
   uint64_t peak = 0;
@@ -461,44 +531,52 @@ int bad(const char* fmt, A... a) {
 
 }  // namespace
 
-extern "C" int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
-                              int32_t* node_dims, int* legal) {
+extern "C" int ac_chunk_trace(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim, int hoist,
+                              int32_t* node_dims, uint8_t* node_moved, int* legal) {
   if (legal) *legal = 0;
   if (!legal || !node_dims) return bad("ac_chunk_trace: null argument");
   if (!graph_ok(nodes, n_nodes)) return bad("ac_chunk_trace: malformed graph");
   if (start < 0 || end < start || end >= n_nodes) return bad("ac_chunk_trace: region [%d, %d] outside the graph", start, end);
   if (out_dim < 0 || out_dim >= nodes[end].rank) return bad("ac_chunk_trace: node %d has no dim %d", end, out_dim);
+  if (hoist != 0 && hoist != 1) return bad("ac_chunk_trace: hoist must be 0 or 1");
   Tracer t(nodes, n_nodes);
   if (t.holds_leaf(start, end)) return bad("ac_chunk_trace: region [%d, %d] holds an input or parameter node", start, end);
   int64_t gran = 1;
-  if (t.trace(start, end, out_dim, node_dims, &gran)) {
+  std::vector<uint8_t> moved(n_nodes, 0);
+  if (t.trace(start, end, out_dim, hoist != 0, node_dims, moved.data(), &gran)) {
     *legal = 1;
   } else {
     for (int i = 0; i < n_nodes; ++i) node_dims[i] = -1;
+    moved.assign(n_nodes, 0);
   }
+  if (node_moved)
+    for (int i = 0; i < n_nodes; ++i) node_moved[i] = moved[i];
   return AC_OK;
 }
 
-extern "C" int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window,
-                               ac_chunk_candidate* out, int32_t* node_dims, int max_out,
+extern "C" int ac_chunk_search(const ac_graph_node* nodes, int n_nodes, int peak, int window, int hoist,
+                               ac_chunk_candidate* out, int32_t* node_dims, uint8_t* node_moved, int max_out,
                                int* n_found, int* n_tried, int* n_passed) {
   if (n_found) *n_found = 0;
   if (n_tried) *n_tried = 0;
   if (n_passed) *n_passed = 0;
   if (!n_found) return bad("ac_chunk_search: null argument");
   if (!graph_ok(nodes, n_nodes)) return bad("ac_chunk_search: malformed graph");
-  if (peak < 0 || peak >= n_nodes || window < 1 || max_out < 0)
-    return bad("ac_chunk_search: peak %d, window %d or max_out %d out of range", peak, window, max_out);
+  if (peak < 0 || peak >= n_nodes || window < 1 || max_out < 0 || (hoist != 0 && hoist != 1))
+    return bad("ac_chunk_search: peak %d, window %d, hoist %d or max_out %d out of range", peak, window, hoist, max_out);
   if (max_out > 0 && (!out || !node_dims)) return bad("ac_chunk_search: null output with max_out %d", max_out);
   Tracer t(nodes, n_nodes);
   int found = 0, tried = 0, passed = 0;
-  t.candidates(peak, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t* row) {
+  t.candidates(peak, window, hoist != 0, &tried, &passed,
+               [&](int start, int end, int d, int64_t gran, const int32_t* row, const uint8_t* moved) {
     if (found < max_out) {
       out[found].start = start;
       out[found].end = end;
       out[found].out_dim = d;
       out[found].granule = (int32_t)gran;
       for (int i = 0; i < n_nodes; ++i) node_dims[(size_t)found * n_nodes + i] = row[i];
+      if (node_moved)
+        for (int i = 0; i < n_nodes; ++i) node_moved[(size_t)found * n_nodes + i] = (i >= start && i <= end) ? moved[i] : 0;
     }
     ++found;
   });
@@ -516,41 +594,56 @@ extern "C" int ac_graph_estimate(const ac_graph_node* nodes, int n_nodes, int el
   if (elem_bytes < 1 || n_chunks < 0) return bad("ac_graph_estimate: elem_bytes %d or n_chunks %d out of range", elem_bytes, n_chunks);
   Tracer t(nodes, n_nodes);
   std::vector<int> region_of;
-  const int st = check_chunks(t, chunks, n_chunks, region_of);
+  std::vector<std::vector<uint8_t>> moved;
+  const int st = check_chunks(t, chunks, n_chunks, region_of, moved);
   if (st != AC_OK) return st;
   Memory m(t, elem_bytes);
   std::vector<uint64_t> bytes;
-  *peak_bytes = estimate(m, chunks, region_of, bytes, peak_node);
+  *peak_bytes = estimate(m, chunks, moved, region_of, bytes, peak_node);
   if (node_bytes)
     for (int i = 0; i < n_nodes; ++i) node_bytes[i] = bytes[i];
   return AC_OK;
 }
 
-extern "C" int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim,
+extern "C" int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int end, int out_dim, int hoist,
                                    const double* weights, double* cost) {
   if (!weights || !cost) return bad("ac_graph_chunk_cost: null argument");
   if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_chunk_cost: malformed graph");
-  if (start < 0 || end < start || end >= n_nodes || out_dim < 0 || out_dim >= nodes[end].rank)
-    return bad("ac_graph_chunk_cost: region [%d, %d] or dim %d not in the graph", start, end, out_dim);
-  *cost = chunk_cost(nodes, start, end, out_dim, weights);
+  if (start < 0 || end < start || end >= n_nodes || out_dim < 0 || out_dim >= nodes[end].rank || (hoist != 0 && hoist != 1))
+    return bad("ac_graph_chunk_cost: region [%d, %d], dim %d or hoist %d not valid for the graph", start, end, out_dim, hoist);
+  if (!hoist) {
+    *cost = chunk_cost(nodes, start, end, out_dim, nullptr, weights);
+    return AC_OK;
+  }
+  Tracer t(nodes, n_nodes);
+  if (t.holds_leaf(start, end)) return bad("ac_graph_chunk_cost: region [%d, %d] holds an input or parameter node", start, end);
+  std::vector<int32_t> row(n_nodes);
+  std::vector<uint8_t> moved(n_nodes, 0);
+  int64_t gran = 1;
+  if (!t.trace(start, end, out_dim, true, row.data(), moved.data(), &gran)) {
+    ac::set_error("ac_graph_chunk_cost: region [%d, %d] cannot be cut along dim %d", start, end, out_dim);
+    return AC_ERR_ILLEGAL_CHUNK_DIM;
+  }
+  *cost = chunk_cost(nodes, start, end, out_dim, moved.data(), weights);
   return AC_OK;
 }
 
 namespace {
 
-// One chunk strategy of the beam: its chunks in the order chosen, the sum of their costs and
-// of their segment counts.
+// One chunk strategy of the beam: its chunks in the order chosen (each with the nodes it
+// moves ahead of its segments), the sum of their costs and of their segment counts.
 struct Strategy {
   double total = 0;
   int64_t segments = 0;
   std::vector<ac_graph_chunk> chunks;
+  std::vector<std::vector<uint8_t>> moved;
 };
 
-typedef std::vector<std::array<int64_t, 4>> StrategyKey;  // the chunks, sorted: order of choice does not matter
+typedef std::vector<std::array<int64_t, 5>> StrategyKey;  // the chunks, sorted: order of choice does not matter
 
 StrategyKey key_of(const std::vector<ac_graph_chunk>& chunks) {
   StrategyKey k;
-  for (const ac_graph_chunk& c : chunks) k.push_back({c.start, c.end, c.out_dim, c.chunk_len});
+  for (const ac_graph_chunk& c : chunks) k.push_back({c.start, c.end, c.out_dim, c.chunk_len, c.hoist});
   std::sort(k.begin(), k.end());
   return k;
 }
@@ -558,34 +651,33 @@ StrategyKey key_of(const std::vector<ac_graph_chunk>& chunks) {
 }  // namespace
 
 extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
-                             int window, const double* weights, int beam, ac_graph_chunk* out, int max_out,
+                             int window, const double* weights, int beam, int hoist, ac_graph_chunk* out, int max_out,
                              int* n_out, uint64_t* peak_bytes) {
   if (n_out) *n_out = 0;
   if (!weights || !out || !n_out || !peak_bytes) return bad("ac_graph_plan: null argument");
   if (!graph_ok(nodes, n_nodes)) return bad("ac_graph_plan: malformed graph");
-  if (elem_bytes < 1 || window < 1 || beam < 1 || max_out < 1)
-    return bad("ac_graph_plan: elem_bytes %d, window %d, beam %d or max_out %d out of range", elem_bytes, window, beam,
-               max_out);
+  if (elem_bytes < 1 || window < 1 || beam < 1 || max_out < 1 || (hoist != 0 && hoist != 1))
+    return bad("ac_graph_plan: elem_bytes %d, window %d, beam %d, hoist %d or max_out %d out of range", elem_bytes, window,
+               beam, hoist, max_out);
   Tracer t(nodes, n_nodes);
   Memory m(t, elem_bytes);
   std::vector<int> region_of(n_nodes);
-  std::vector<uint64_t> bytes, scratch;
-  auto estimate_of = [&](const std::vector<ac_graph_chunk>& chunks, int* peak_node) {
+  std::vector<uint64_t> bytes, fixed, scaled;
+  auto estimate_of = [&](const Strategy& st, int* peak_node) {
     region_of.assign(n_nodes, -1);
-    for (size_t c = 0; c < chunks.size(); ++c)
-      for (int i = chunks[c].start; i <= chunks[c].end; ++i) region_of[i] = (int)c;
-    return estimate(m, chunks.data(), region_of, bytes, peak_node);
+    for (size_t c = 0; c < st.chunks.size(); ++c)
+      for (int i = st.chunks[c].start; i <= st.chunks[c].end; ++i) region_of[i] = (int)c;
+    return estimate(m, st.chunks.data(), st.moved, region_of, bytes, peak_node);
   };
   int peak_node = 0;
-  *peak_bytes = estimate_of({}, &peak_node);
-
   std::vector<Strategy> states(1);
+  *peak_bytes = estimate_of(states[0], &peak_node);
   for (;;) {  // one pass: every strategy that does not fit yet grows by one chunk around its own peak
     std::vector<Strategy> grown;
     std::set<StrategyKey> known;
     bool all_fit = true;
     for (const Strategy& st : states) {
-      const uint64_t peak = estimate_of(st.chunks, &peak_node);  // also leaves region_of set for st
+      const uint64_t peak = estimate_of(st, &peak_node);  // also leaves region_of set for st
       if (peak <= budget_bytes) {
         if (known.insert(key_of(st.chunks)).second) grown.push_back(st);
         continue;
@@ -593,16 +685,20 @@ extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_b
       all_fit = false;
       if (region_of[peak_node] >= 0) continue;  // the peak lies in a region already chunked: a dead end
       int tried = 0, passed = 0;
-      t.candidates(peak_node, window, &tried, &passed, [&](int start, int end, int d, int64_t gran, const int32_t*) {
+      t.candidates(peak_node, window, hoist != 0, &tried, &passed,
+                   [&](int start, int end, int d, int64_t gran, const int32_t*, const uint8_t* moved) {
         for (int i = start; i <= end; ++i)
           if (region_of[i] >= 0) return;
         const int64_t extent = nodes[end].shape[d];
-        const int64_t len = m.longest_len(start, end, extent, gran, budget_bytes, scratch);
+        const int64_t len = m.longest_len(start, end, moved, extent, gran, budget_bytes, fixed, scaled);
         if (len < gran) return;
         Strategy next = st;
-        next.chunks.push_back(ac_graph_chunk{start, end, d, 0, len});
+        next.chunks.push_back(ac_graph_chunk{start, end, d, hoist, len});
         if (!known.insert(key_of(next.chunks)).second) return;  // the same chunks, chosen in another order
-        next.total = st.total + chunk_cost(nodes, start, end, d, weights);
+        next.moved.emplace_back(moved, moved + n_nodes);
+        for (int i = 0; i < n_nodes; ++i)
+          if (i < start || i > end) next.moved.back()[i] = 0;
+        next.total = st.total + chunk_cost(nodes, start, end, d, moved, weights);
         next.segments = st.segments + (extent + len - 1) / len;
         grown.push_back(std::move(next));
       });
@@ -623,6 +719,6 @@ extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_b
   if ((int)best.chunks.size() > max_out) return bad("ac_graph_plan: %d chunks needed, max_out is %d", (int)best.chunks.size(), max_out);
   for (size_t c = 0; c < best.chunks.size(); ++c) out[c] = best.chunks[c];
   *n_out = (int)best.chunks.size();
-  *peak_bytes = estimate_of(best.chunks, &peak_node);
+  *peak_bytes = estimate_of(best, &peak_node);
   return AC_OK;
 }

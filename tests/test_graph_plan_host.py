@@ -11,7 +11,7 @@ from oracle import graph_memory as GM
 from paper_2401_10652_amd import binding as B
 from paper_2401_10652_amd import graphs as PG
 from tests import graphs as G
-from tests.test_oracle_graph_memory import some_chunks
+from tests.test_oracle_graph_memory import hoisting_chunks, some_chunks
 from tests.test_search_host import library_nodes, oracle_nodes
 
 WEIGHTS = ((1, 0, 0, 0), (0, 0, 0, -1), (1.0, 1e-3, -1e-3, -0.5), (0.3, 2e-7, -1e-7, 0.01))
@@ -30,6 +30,24 @@ def test_estimate_equals_the_oracle():
     assert n_chunked > 60
 
 
+def test_estimate_with_moved_nodes_equals_the_oracle():
+    n_moved = 0
+    block, nm = S.transformer_block_graph(2, 12, 8, 2, 16)
+    kv = tuple(sorted(nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")))
+    cases = [([(nd.op, nd.inputs, nd.shape, nd.attr, None) for nd in block], [(nm["q_flat"], nm["ctx"], 1, 4, kv)])]
+    cases += [(G.random_graph(seed, n_ops=12 + seed % 6), None) for seed in range(150)]
+    for seed, (spec, chunks) in enumerate(cases):
+        on, ln = oracle_nodes(spec), library_nodes(spec)
+        if chunks is None:
+            chunks = hoisting_chunks(on, np.random.default_rng(seed))
+        assert B.ac_graph_estimate(ln, 2, [c[:4] + (1,) for c in chunks]) == GM.estimate(on, 2, chunks), (seed, chunks)
+        for c in chunks:
+            for w in WEIGHTS:
+                assert B.ac_graph_chunk_cost(ln, c[0], c[1], c[2], w, hoist=True) == GM.chunk_cost(on, c[0], c[1], c[2], w, c[4])
+        n_moved += sum(len(c[4]) > 0 for c in chunks)
+    assert n_moved > 20
+
+
 def test_cost_equals_the_oracle_bit_for_bit():
     for seed in range(20):
         spec = G.random_graph(seed, n_ops=10)
@@ -42,15 +60,16 @@ def test_cost_equals_the_oracle_bit_for_bit():
                         assert B.ac_graph_chunk_cost(ln, start, end, d, w) == GM.chunk_cost(on, start, end, d, w)
 
 
-def both_plans(on, ln, e, budget, window, w, beam=1):
+def both_plans(on, ln, e, budget, window, w, beam=1, hoist=False):
     try:
-        want = GM.plan(on, e, budget, window, w, beam)
+        want = GM.plan(on, e, budget, window, w, beam, hoist)
     except ValueError:
         with pytest.raises(B.AcError) as err:
-            B.ac_graph_plan(ln, e, budget, window, w, beam)
+            B.ac_graph_plan(ln, e, budget, window, w, beam, hoist=hoist)
         assert err.value.status == B.AC_ERR_BUDGET_INFEASIBLE
         return None
-    assert B.ac_graph_plan(ln, e, budget, window, w, beam) == want
+    got = B.ac_graph_plan(ln, e, budget, window, w, beam, hoist=hoist)
+    assert got == ([c[:4] + (1,) for c in want[0]] if hoist else want[0], want[1])
     return want
 
 
@@ -67,6 +86,7 @@ def test_plan_equals_the_oracle_on_random_graphs():
             for beam in (2, 5):
                 wide = both_plans(on, ln, 2, int(whole * frac), 5, WEIGHTS[seed % len(WEIGHTS)], beam)
                 rescued += got is None and wide is not None
+            both_plans(on, ln, 2, int(whole * frac), 7, WEIGHTS[seed % len(WEIGHTS)], 2, hoist=True)
 
     assert planned > 40 and failed > 20 and rescued > 5
 
@@ -115,6 +135,7 @@ def test_errors():
     assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 8, (1, 0, 0, 0), beam=0)) == B.AC_ERR_ARG
     assert status(lambda: B.ac_graph_plan(ln, 8, 40000, 0, (1, 0, 0, 0))) == B.AC_ERR_ARG
     assert status(lambda: B.ac_graph_chunk_cost(ln, s, c, 4, (1, 0, 0, 0))) == B.AC_ERR_ARG
+    assert status(lambda: B.ac_graph_chunk_cost(ln, s, c, 3, (1, 0, 0, 0), hoist=True)) == B.AC_ERR_ILLEGAL_CHUNK_DIM
     L = B.lib()
     assert L.ac_graph_estimate(ln, len(ln), 2, None, 0, None, None, None) == B.AC_ERR_ARG
 
@@ -129,6 +150,7 @@ def test_pair_block_plan_equals_the_oracle_and_chunks_the_triangle_attention():
     for frac in (0.8, 0.6, 0.5):
         for beam in (1, 3):
             both_plans(on, ln, 2, int(whole * frac), 10, (1, 0, 0, 0), beam)
+        both_plans(on, ln, 2, int(whole * frac), 12, (-1, 0, 0, 0), 2, hoist=True)
     # at the size of the pair workload: 16.8 GiB unchunked, the scores of both triangle attentions cut along rows
     spec, nm = PG.pair_block_graph(1024, 128, 128, 4, 32, 4)
     big = B.graph_nodes(spec)

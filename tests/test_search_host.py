@@ -35,17 +35,49 @@ def oracle_candidates(nodes, peak, window):
     return out, tried, passed
 
 
-def compare_everywhere(spec, windows):
+def oracle_candidates_hoisting(nodes, peak, window):
+    cands, tried, passed = S.search_hoisting(nodes, peak, window)
+    out = []
+    for start, end, dim, node_dims, input_dims, moved in cands:
+        row = [-1] * len(nodes)
+        for i, d in list(node_dims.items()) + list(input_dims.items()):
+            row[i] = d
+        out.append((start, end, dim, S.chunk_granule(nodes, end, dim, node_dims, input_dims), row, sorted(moved)))
+    return out, tried, passed
+
+
+def compare_everywhere(spec, windows, hoist=False):
     on, ln = oracle_nodes(spec), library_nodes(spec)
     total = 0
     for peak in range(len(spec)):
         for w in windows:
-            want, tried, passed = oracle_candidates(on, peak, w)
-            got, n_found, n_tried, n_passed = B.ac_chunk_search(ln, peak, w)
+            want, tried, passed = (oracle_candidates_hoisting if hoist else oracle_candidates)(on, peak, w)
+            got, n_found, n_tried, n_passed = B.ac_chunk_search(ln, peak, w, hoist=hoist)
             assert (n_tried, n_passed, n_found) == (tried, passed, len(want)), (peak, w)
             assert got == want, (peak, w)
-            total += len(want)
+            total += sum(bool(c[5]) for c in want) if hoist else len(want)
     return total
+
+
+def test_search_with_the_graph_optimisation_equals_the_oracle():
+    """hoist = 1: candidates, dims and moved nodes, on the block graph, the pair block and random graphs."""
+    spec, nm = block_spec()
+    assert compare_everywhere(spec, (6, 12, 20), hoist=True) > 50            # counts candidates with moved nodes
+    ln = library_nodes(spec)
+    dims, moved = B.ac_chunk_trace(ln, nm["q_flat"], nm["ctx"], 1, hoist=True)
+    assert moved == sorted(nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")) and dims[nm["qkv"]] == 1
+    assert B.ac_chunk_trace(ln, nm["q_flat"], nm["ctx"], 1) is None          # without it: k and v are read whole
+    assert B.ac_chunk_trace(ln, nm["u"], nm["ctx"], 1, hoist=True) is None   # the first node would move
+    pair, pnm = pair_spec()
+    assert compare_everywhere(pair, (8, 14), hoist=True) > 300
+    pl = library_nodes(pair)
+    # the triangle update from the a projection on, cut along rows: the b projection moves ahead
+    dims, moved = B.ac_chunk_trace(pl, pnm["tmo.a_gate"], pnm["tmo.z"], 0, hoist=True)
+    assert moved == sorted(pnm["tmo." + x] for x in ("b_gate", "b_proj", "b"))
+    total = 0
+    for seed in range(40):
+        total += compare_everywhere(G.random_graph(seed, n_ops=13), (5, 10), hoist=True)
+    assert total > 100
 
 
 def test_search_equals_the_oracle_on_the_transformer_block():
@@ -156,11 +188,12 @@ def test_count_only_truncation_and_errors():
     assert n_found2 == n_found and part == full[:3]
     L = B.lib()
     found = C.c_int(-1)
-    assert L.ac_chunk_search(ln, len(ln), nm["probs"], 6, None, None, 2, C.byref(found), None, None) == B.AC_ERR_ARG
-    assert L.ac_chunk_search(ln, len(ln), len(ln), 6, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
-    assert L.ac_chunk_search(ln, len(ln), 0, 0, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), nm["probs"], 6, 0, None, None, None, 2, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), len(ln), 6, 0, None, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), nm["probs"], 6, 2, None, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
+    assert L.ac_chunk_search(ln, len(ln), 0, 0, 0, None, None, None, 0, C.byref(found), None, None) == B.AC_ERR_ARG
     # a peak that is an input: nothing to chunk, no error
-    assert L.ac_chunk_search(ln, len(ln), 0, 4, None, None, 0, C.byref(found), None, None) == B.AC_OK
+    assert L.ac_chunk_search(ln, len(ln), 0, 4, 0, None, None, None, 0, C.byref(found), None, None) == B.AC_OK
     assert found.value == 0
     with pytest.raises(B.AcError):
         B.ac_chunk_trace(ln, nm["x"], nm["u"], 0)       # region holds leaves
@@ -177,7 +210,7 @@ def test_count_only_truncation_and_errors():
             bad[nm["scores"]].shape[3] += 1
         else:
             bad[nm["probs"]].rank = 7
-        assert L.ac_chunk_search(bad, len(bad), nm["probs"], 6, None, None, 0, C.byref(found), None, None) == \
+        assert L.ac_chunk_search(bad, len(bad), nm["probs"], 6, 0, None, None, None, 0, C.byref(found), None, None) == \
             B.AC_ERR_ARG, breaker
 
 
