@@ -54,7 +54,10 @@ typedef enum ac_graph_op {
   AC_OP_KINDS = 13
 } ac_graph_op;
 
-/* Nodes are listed in a topological order: inputs[] hold indices of earlier nodes. */
+/* Nodes are listed in a topological order: inputs[] hold indices of earlier nodes.  rank is
+ * 1..AC_GRAPH_MAX_RANK, every extent at least 1, and a tensor has at most 2^40 elements (so
+ * that byte and operation counts stay within 64 bits); shapes must fit the op kind.  A graph
+ * that breaks any of this is refused with AC_ERR_ARG by every call below. */
 typedef struct ac_graph_node {
   int32_t op;
   int32_t n_inputs;

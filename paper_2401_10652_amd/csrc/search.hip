@@ -78,8 +78,13 @@ bool graph_ok(const ac_graph_node* g, int n_nodes) {
     const ac_graph_node& n = g[i];
     if (n.op < 0 || n.op >= AC_OP_KINDS) return false;
     if (n.rank < 1 || n.rank > AC_GRAPH_MAX_RANK) return false;
-    for (int d = 0; d < n.rank; ++d)
-      if (n.shape[d] < 1) return false;
+    // element and byte counts are kept in 64 bits: cap a tensor at 2^40 elements so that the sum
+    // over a graph of up to 2^20 such tensors of 8-byte elements cannot wrap
+    int64_t elems = 1;
+    for (int d = 0; d < n.rank; ++d) {
+      if (n.shape[d] < 1 || n.shape[d] > (int64_t(1) << 40) / elems) return false;
+      elems *= n.shape[d];
+    }
     if (n.n_inputs < 0 || n.n_inputs > AC_GRAPH_MAX_INPUTS) return false;
     for (int k = 0; k < n.n_inputs; ++k)
       if (n.inputs[k] < 0 || n.inputs[k] >= i) return false;
@@ -412,18 +417,19 @@ struct Memory {
   }
 };
 
-uint64_t node_flops(const ac_graph_node* g, const ac_graph_node& n) {
-  uint64_t out = 1;
-  for (int d = 0; d < n.rank; ++d) out *= (uint64_t)n.shape[d];
+// Operations of one node (128 bits: 2^40 elements times a contraction length can pass 2^64).
+u128 node_flops(const ac_graph_node* g, const ac_graph_node& n) {
+  u128 out = 1;
+  for (int d = 0; d < n.rank; ++d) out *= (u128)n.shape[d];
   switch (n.op) {
     case AC_OP_LINEAR:
     case AC_OP_MATMUL_NT:
     case AC_OP_MATMUL_NN: {
       const ac_graph_node& x = g[n.inputs[0]];
-      return 2 * out * (uint64_t)x.shape[x.rank - 1];
+      return 2 * out * (u128)x.shape[x.rank - 1];
     }
     case AC_OP_CONTRACT_IKC_JKC:
-      return 2 * out * (uint64_t)g[n.inputs[0]].shape[1];
+      return 2 * out * (u128)g[n.inputs[0]].shape[1];
     case AC_OP_ELEMENTWISE:
       return out;
     case AC_OP_SOFTMAX_LAST:
@@ -438,7 +444,7 @@ uint64_t node_flops(const ac_graph_node* g, const ac_graph_node& n) {
 // L = (alpha N_node + beta N_flop) + (gamma N_density + lambda N_stride), over the nodes that
 // run once per segment (moved may be null: all of the region).
 double chunk_cost(const ac_graph_node* g, int start, int end, int out_dim, const uint8_t* moved, const double* w) {
-  uint64_t flops = 0;
+  u128 flops = 0;
   int count = 0;
   for (int i = start; i <= end; ++i) {
     if (moved && moved[i]) continue;

@@ -200,7 +200,7 @@ def test_count_only_truncation_and_errors():
     with pytest.raises(B.AcError):
         B.ac_chunk_trace(ln, nm["u"], nm["qkv"], 3)     # no such dim
     # malformed graphs: forward reference, bad permutation, shapes that do not fit the op
-    for breaker in ("forward", "perm", "shape", "rank"):
+    for breaker in ("forward", "perm", "shape", "rank", "huge"):
         bad = library_nodes(spec)
         if breaker == "forward":
             bad[nm["u"]].inputs[0] = nm["y"]
@@ -208,6 +208,8 @@ def test_count_only_truncation_and_errors():
             bad[nm["q_h"]].attr[1] = 0
         elif breaker == "shape":
             bad[nm["scores"]].shape[3] += 1
+        elif breaker == "huge":
+            bad[nm["x"]].shape[0] = 1 << 41
         else:
             bad[nm["probs"]].rank = 7
         assert L.ac_chunk_search(bad, len(bad), nm["probs"], 6, 0, None, None, None, 0, C.byref(found), None, None) == \
