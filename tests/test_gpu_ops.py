@@ -286,3 +286,47 @@ def test_softmax_rows(B, dtype, rows, cols, period, q_offset, causal):
     B.ac_op_softmax_rows(ds, ds, scale, causal=causal, q_offset=q_offset, period=period)
     torch.cuda.synchronize()
     assert np.array_equal(host(ds), got)
+
+
+def test_random_shapes_of_linear_and_attention(B):
+    """Seeded random shapes around the tile and split boundaries of both matrix kernels (ragged
+    tails in every direction, every epilogue, query segments at random absolute positions),
+    each against the oracle."""
+    import torch
+    rng = np.random.default_rng(2401)
+    worst = 0.0
+    for case in range(24):
+        m = int(rng.choice([1, 31, 64, 65, 127, 128, 129, 255, 257, 300, 513, 700]))
+        n = 4 * int(rng.integers(1, 160))
+        k = 64 * int(rng.integers(1, 9)) if case % 4 else 8 * int(rng.integers(1, 40))
+        epi = ["plain", "bias_gelu", "bias_resid", "relu"][case % 4]
+        a, w = draw((m, k), 100 + case, "bf16"), draw((n, k), 200 + case, "bf16", 1 / math.sqrt(k))
+        bias, res = draw((n,), 300 + case, "bf16", 0.5), draw((m, n), 400 + case, "bf16")
+        out = torch.full((m, n), float("nan"), device="cuda", dtype=torch.bfloat16)
+        ref = O.linear(a, w)
+        kw = {}
+        if epi == "bias_gelu":
+            kw, ref = dict(bias=dev(B, bias, "bf16"), activation=B.AC_ACT_GELU_ERF), O.gelu_erf(ref + bias)
+        elif epi == "bias_resid":
+            kw, ref = dict(bias=dev(B, bias, "bf16"), residual=dev(B, res, "bf16")), ref + bias + res
+        elif epi == "relu":
+            kw, ref = dict(activation=B.AC_ACT_RELU), O.relu(ref)
+        B.ac_op_linear(dev(B, a, "bf16"), dev(B, w, "bf16"), out, **kw)
+        torch.cuda.synchronize()
+        got = host(out)
+        assert np.isfinite(got).all(), (m, n, k, epi)
+        err = rel_err(got, ref)
+        assert err <= TOL["bf16"], (m, n, k, epi, err)
+        worst = max(worst, err)
+    for case in range(24):
+        dh = int(rng.choice([32, 64, 128]))
+        heads = int(rng.integers(1, 5))
+        sk = int(rng.integers(1, 1400))
+        causal = bool(case % 2)
+        sq = int(rng.integers(1, min(sk, 400) + 1)) if causal else int(rng.integers(1, 400))
+        q_offset = sk - sq if causal else 0          # the segment's rows end at the last key
+        n_splits = int(rng.choice([1, 1, 2, 5])) if sk >= 64 else 1
+        err = _attn_case(B, "bf16", sq, sk, heads, dh, causal, q_offset, case % 3 == 0, case % 5 == 0, True, n_splits)
+        assert err <= TOL["bf16"], (sq, sk, heads, dh, causal, q_offset, n_splits, err)
+        worst = max(worst, err)
+    assert worst > 0
