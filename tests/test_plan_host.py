@@ -259,3 +259,17 @@ def test_legality_and_errors():
     assert L.ac_plan_weight_info(p._h, n, C.byref(wi)) == B.AC_ERR_ARG
     assert L.ac_plan_read_profile(p._h, None, 0, None) == B.AC_ERR_ARG
     L.ac_plan_destroy(None)
+
+
+def test_public_headers_are_plain_c(tmp_path):
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "headers.c"
+    src.write_text("".join(f'#include "{f}"\n' for f in sorted(os.listdir(inc)) if f.endswith(".h")) + "int main(void) { return 0; }\n")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
