@@ -291,6 +291,33 @@ def main():
         if "ms_per_step" in stored["chunked"] and "ms_per_step" in stored["one_segment"]:
             stored["throughput_loss"] = round(1.0 - stored["one_segment"]["ms_per_step"] / stored["chunked"]["ms_per_step"], 4)
         out["stored_scores"] = stored
+        if budget:
+            # The planning passes on the unfused graph of the same stack at the same budget (host
+            # code: estimate, search around the peak, select, repeated), and the stored-scores
+            # executor run with the chunks they choose.
+            from paper_2401_10652_amd import graphs as PG
+            spec, names = PG.transformer_stack_graph(cfg.batch, cfg.seq, cfg.d_model, cfg.heads, cfg.d_ffn, cfg.layers)
+            nodes = B.graph_nodes(spec)
+            e = 2 if cfg.dtype == "bf16" else 4
+            _, whole, _ = B.ac_graph_estimate(nodes, e)
+            t0 = time.perf_counter()
+            chunks, planned = B.ac_graph_plan(nodes, e, budget, 12, (1.0, 0.0, 0.0, 0.0), beam=2, max_out=4 * cfg.layers)
+            plan_ms = (time.perf_counter() - t0) * 1e3
+            settings = PG.executor_regions(chunks, names)
+            p4 = B.Plan(desc3, settings, 0)
+            i4 = p4.ac_plan_query()
+            entry = {"graph_nodes": len(spec), "estimate_unchunked_bytes": whole, "estimate_planned_bytes": planned,
+                     "planning_ms": round(plan_ms, 3), "chunks": len(chunks), "window": 12, "beam": 2,
+                     "weights": [1.0, 0.0, 0.0, 0.0], "executor_regions": [list(s) for s in settings],
+                     "executor_peak_bytes_planned": int(i4.peak_bytes_planned)}
+            if i4.workspace_bytes <= 48 << 30:
+                p4.ac_plan_bind_weights(dw)
+                ws4 = B.empty_workspace(i4.workspace_bytes)
+                s4, pk4 = time_plan(B, torch, p4, dx, y, ws4, max(3, args.steps // 2), 1)
+                entry.update({"ms_per_step": round(s4 * 1e3, 4), "executor_peak_bytes_measured": pk4})
+                del ws4
+            p4.close()
+            out["planned_on_the_graph"] = entry
     if args.sweep:
         sweep = []
         c = cfg.n_res if is_pair else cfg.seq
