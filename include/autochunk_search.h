@@ -46,12 +46,19 @@ extern "C" {
  *                      it, otherwise input in c
  *   CONTRACT_IKC_JKC   a [I, K, C], b [J, K, C] -> [I, J, C] (the triangle update): c = 0: a in
  *                      0, b whole; c = 1: a whole, b in 0; c = 2: both in 2
+ *   CONV2D             x [B, Ci, H, W], w [Co, Ci, kh, kw] (kh, kw odd), optional bias [Co] ->
+ *                      [B, Co, H, W], stride 1, same padding.  c = 0: x in 0, w and bias whole;
+ *                      c = 1: x whole, w and bias in 0; c = 2, 3: x in c where the window has
+ *                      one element along it, else interrupted (a wider window reads across any cut)
+ *   GROUP_NORM         attr = {groups}: x [B, C, H, W] normalised over (C / groups, H, W); gain,
+ *                      shift [C] whole.  c = 0: x in 0; otherwise interrupted (cuts of the
+ *                      channels in whole groups would be legal; they are not expressed)
  */
 typedef enum ac_graph_op {
   AC_OP_INPUT = 0, AC_OP_PARAM = 1, AC_OP_LINEAR = 2, AC_OP_MATMUL_NT = 3, AC_OP_MATMUL_NN = 4,
   AC_OP_ELEMENTWISE = 5, AC_OP_NORM_LAST = 6, AC_OP_SOFTMAX_LAST = 7, AC_OP_TRANSPOSE = 8,
   AC_OP_SPLIT_DIM = 9, AC_OP_MERGE_DIMS = 10, AC_OP_SLICE_LAST = 11, AC_OP_CONTRACT_IKC_JKC = 12,
-  AC_OP_KINDS = 13
+  AC_OP_CONV2D = 13, AC_OP_GROUP_NORM = 14, AC_OP_KINDS = 15
 } ac_graph_op;
 
 /* Nodes are listed in a topological order: inputs[] hold indices of earlier nodes.  rank is
@@ -143,9 +150,9 @@ int ac_graph_estimate(const ac_graph_node* nodes, int n_nodes, int elem_bytes,
  * L_macro = weights[0] N_node + weights[1] N_flop, L_micro = weights[2] N_density +
  * weights[3] N_stride.  N_node: nodes of the region that run per segment (all of them, or
  * those not moved when hoist = 1; the chunk must then be legal, else
- * AC_ERR_ILLEGAL_CHUNK_DIM); N_flop: their operations (2 per multiply-add of LINEAR, MATMUL
- * and CONTRACT; 1 per element of ELEMENTWISE, 5 of SOFTMAX_LAST, 8 of NORM_LAST; none for the
- * reshaping ops); N_density = N_flop / N_node; N_stride: elements between neighbours along
+ * AC_ERR_ILLEGAL_CHUNK_DIM); N_flop: their operations (2 per multiply-add of LINEAR, MATMUL,
+ * CONTRACT and CONV2D; 1 per element of ELEMENTWISE, 5 of SOFTMAX_LAST, 8 of NORM_LAST and
+ * GROUP_NORM; none for the reshaping ops); N_density = N_flop / N_node; N_stride: elements between neighbours along
  * out_dim in the contiguous result of `end`.  The paper tunes the four weights and prints
  * no values: they are the caller's.
  */

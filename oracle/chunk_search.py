@@ -40,7 +40,7 @@ import numpy as np
 
 # op kinds (shared numbering with the C interface; a format, not arithmetic)
 INPUT, PARAM, LINEAR, MATMUL_NT, MATMUL_NN, ELEMENTWISE, NORM_LAST, SOFTMAX_LAST, TRANSPOSE, SPLIT_DIM, MERGE_DIMS, \
-    SLICE_LAST, CONTRACT_IKC_JKC = range(13)
+    SLICE_LAST, CONTRACT_IKC_JKC, CONV2D, GROUP_NORM = range(15)
 
 FLOW, WHOLE, BROKEN = 0, 1, 2
 
@@ -50,7 +50,8 @@ class Node:
     op: int
     inputs: tuple = ()
     shape: tuple = ()
-    attr: tuple = ()        # TRANSPOSE: perm; SPLIT_DIM: (dim, outer); MERGE_DIMS: (dim,); SLICE_LAST: (start, stop)
+    attr: tuple = ()        # TRANSPOSE: perm; SPLIT_DIM: (dim, outer); MERGE_DIMS: (dim, inner); SLICE_LAST: (start, stop);
+                            # GROUP_NORM: (groups,)
     fn: object = None       # ELEMENTWISE: numpy callable of its inputs (executor only)
 
 
@@ -106,6 +107,19 @@ def flow_to_input(node: Node, nodes, c: int, which: int):
         if c == 1:
             return (WHOLE, -1) if which == 0 else (FLOW, 0)
         return FLOW, 2
+    if node.op == CONV2D:               # x [B, Ci, H, W], w [Co, Ci, kh, kw], bias [Co] -> [B, Co, H, W], same padding
+        w = nodes[node.inputs[1]]
+        if c == 0:
+            return (FLOW, 0) if which == 0 else (WHOLE, -1)
+        if c == 1:
+            return (WHOLE, -1) if which == 0 else (FLOW, 0)
+        if w.shape[c] != 1:
+            return BROKEN, -1           # a window wider than one element reads its neighbours across any cut
+        return (FLOW, c) if which == 0 else (WHOLE, -1)
+    if node.op == GROUP_NORM:           # x [B, C, H, W] normalised over (C / groups, H, W); gain, shift [C]
+        if which > 0:
+            return WHOLE, -1
+        return (FLOW, 0) if c == 0 else (BROKEN, -1)    # channel chunks in whole groups would be legal: not expressed
     raise ValueError(f"no flow rule for op {node.op}")
 
 
@@ -338,6 +352,24 @@ def _apply(nd: Node, args):
         return args[0][..., nd.attr[0]:nd.attr[1]]
     if nd.op == CONTRACT_IKC_JKC:
         return np.einsum("ikc,jkc->ijc", args[0], args[1])
+    if nd.op == CONV2D:
+        x, w = args[0], args[1]
+        kh, kw = w.shape[2], w.shape[3]
+        xp = np.pad(x, ((0, 0), (0, 0), (kh // 2, kh // 2), (kw // 2, kw // 2)))
+        y = np.zeros((x.shape[0], w.shape[0], x.shape[2], x.shape[3]))
+        for a in range(kh):
+            for b in range(kw):
+                y += np.einsum("bchw,oc->bohw", xp[:, :, a:a + x.shape[2], b:b + x.shape[3]], w[:, :, a, b])
+        return y + args[2][None, :, None, None] if len(args) > 2 else y
+    if nd.op == GROUP_NORM:
+        x = args[0]
+        b, c, h, w_ = x.shape
+        g = x.reshape(b, nd.attr[0], -1)
+        mu = g.mean(-1, keepdims=True)
+        y = ((g - mu) / np.sqrt(((g - mu) ** 2).mean(-1, keepdims=True) + 1e-5)).reshape(x.shape)
+        if len(args) > 1:
+            y = y * args[1][None, :, None, None] + args[2][None, :, None, None]
+        return y
     raise ValueError(nd.op)
 
 

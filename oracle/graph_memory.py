@@ -102,8 +102,11 @@ def node_flops(node, nodes):
         return out
     if node.op == S.SOFTMAX_LAST:
         return 5 * out      # max, subtract, exponential, sum, divide
-    if node.op == S.NORM_LAST:
+    if node.op in (S.NORM_LAST, S.GROUP_NORM):
         return 8 * out      # mean; centre, square, sum; scale by the deviation; gain, shift
+    if node.op == S.CONV2D:
+        w = nodes[node.inputs[1]].shape
+        return 2 * out * w[1] * w[2] * w[3]
     return 0                # views and leaves
 
 

@@ -72,7 +72,7 @@ class ac_kernel_stat(C.Structure):
 AC_GRAPH_MAX_RANK, AC_GRAPH_MAX_INPUTS = 6, 3
 (AC_OP_INPUT, AC_OP_PARAM, AC_OP_LINEAR, AC_OP_MATMUL_NT, AC_OP_MATMUL_NN, AC_OP_ELEMENTWISE, AC_OP_NORM_LAST,
  AC_OP_SOFTMAX_LAST, AC_OP_TRANSPOSE, AC_OP_SPLIT_DIM, AC_OP_MERGE_DIMS, AC_OP_SLICE_LAST, AC_OP_CONTRACT_IKC_JKC,
- AC_OP_KINDS) = range(14)
+ AC_OP_CONV2D, AC_OP_GROUP_NORM, AC_OP_KINDS) = range(16)
 
 
 class ac_graph_node(C.Structure):

@@ -60,6 +60,14 @@ int step(const ac_graph_node* g, const ac_graph_node& n, int c, int k) {
     case AC_OP_CONTRACT_IKC_JKC:
       if (c == 2) return 2;
       return (c == 0) == (k == 0) ? 0 : kWhole;
+    case AC_OP_CONV2D:
+      if (c == 0) return k == 0 ? 0 : kWhole;
+      if (c == 1) return k == 0 ? kWhole : 0;
+      if (g[n.inputs[1]].shape[c] != 1) return kCut;  // a window wider than one element reads across any cut
+      return k == 0 ? c : kWhole;
+    case AC_OP_GROUP_NORM:
+      if (k != 0) return kWhole;
+      return c == 0 ? 0 : kCut;
     default:
       return kCut;
   }
@@ -161,6 +169,19 @@ bool graph_ok(const ac_graph_node* g, int n_nodes) {
         if (a < 0 || b <= a || b > x->shape[n.rank - 1] || n.shape[n.rank - 1] != b - a) return false;
         break;
       }
+      case AC_OP_CONV2D: {
+        if (n.n_inputs < 2 || n.rank != 4 || x->rank != 4 || y->rank != 4) return false;
+        if (y->shape[1] != x->shape[1] || y->shape[0] != n.shape[1] || y->shape[2] % 2 != 1 || y->shape[3] % 2 != 1) return false;
+        if (n.shape[0] != x->shape[0] || n.shape[2] != x->shape[2] || n.shape[3] != x->shape[3]) return false;
+        if (n.n_inputs == 3 && (g[n.inputs[2]].rank != 1 || g[n.inputs[2]].shape[0] != n.shape[1])) return false;
+        break;
+      }
+      case AC_OP_GROUP_NORM:
+        if (n.n_inputs < 1 || n.rank != 4 || x->rank != 4 || !same_shape_but(n, *x, 4)) return false;
+        if (n.attr[0] < 1 || n.shape[1] % n.attr[0] != 0) return false;
+        for (int k = 1; k < n.n_inputs; ++k)
+          if (g[n.inputs[k]].rank != 1 || g[n.inputs[k]].shape[0] != n.shape[1]) return false;
+        break;
       case AC_OP_CONTRACT_IKC_JKC:
         if (n.n_inputs != 2 || n.rank != 3 || x->rank != 3 || y->rank != 3) return false;
         if (x->shape[1] != y->shape[1] || x->shape[2] != y->shape[2]) return false;
@@ -435,7 +456,12 @@ u128 node_flops(const ac_graph_node* g, const ac_graph_node& n) {
     case AC_OP_SOFTMAX_LAST:
       return 5 * out;  // max, subtract, exponential, sum, divide
     case AC_OP_NORM_LAST:
+    case AC_OP_GROUP_NORM:
       return 8 * out;  // mean; centre, square, sum; scale by the deviation; gain, shift
+    case AC_OP_CONV2D: {
+      const ac_graph_node& w = g[n.inputs[1]];
+      return 2 * out * (u128)w.shape[1] * (u128)w.shape[2] * (u128)w.shape[3];
+    }
     default:
       return 0;
   }

@@ -172,3 +172,75 @@ def pair_block_graph(n_res, c_z, c_hidden, heads, head_dim, transition_factor):
     g.add("pt.down", B.AC_OP_LINEAR, ("pt.act", "pt.w_2", "pt.b_2"), nnc)
     g.add("pt.z", B.AC_OP_ELEMENTWISE, (src, "pt.down"), nnc)
     return g.spec, g.names
+
+
+def unet_stage_graph(batch, channels, height, width, heads, context_tokens, context_dim, groups=32):
+    """One stage of a latent-diffusion UNet at a fixed resolution, as an unfused graph: a residual
+    block (group norm, SiLU, 3x3 convolution, time embedding added, again, skip) and a spatial
+    transformer (group norm, 1x1 convolution in, tokens [B, H*W, C]: self-attention,
+    cross-attention to a context [B, T, D], gated feed-forward, each behind a layer norm and
+    with a residual; 1x1 convolution out, skip).  Prefixes: "res." and "tr.".  Returns (spec, names)."""
+    g = GraphBuilder()
+    b, c, hh, ww = batch, channels, height, width
+    n, dh = hh * ww, channels // heads
+    img, tok = (b, c, hh, ww), (b, n, c)
+    g.add("x", B.AC_OP_INPUT, shape=img)
+    g.add("temb", B.AC_OP_INPUT, shape=(b, c, 1, 1))
+    g.add("context", B.AC_OP_INPUT, shape=(b, context_tokens, context_dim))
+
+    def param(name, *shape):
+        return g.add(name, B.AC_OP_PARAM, shape=shape)
+
+    for i in (1, 2):
+        param(f"res.gn{i}_g", c), param(f"res.gn{i}_b", c), param(f"res.w{i}", c, c, 3, 3), param(f"res.b{i}", c)
+    param("tr.gn_g", c), param("tr.gn_b", c), param("tr.w_in", c, c, 1, 1), param("tr.b_in", c)
+    for a, kv_dim in (("sa", c), ("ca", context_dim)):
+        param(f"tr.{a}.ln_g", c), param(f"tr.{a}.ln_b", c), param(f"tr.{a}.wq", c, c)
+        param(f"tr.{a}.wk", c, kv_dim), param(f"tr.{a}.wv", c, kv_dim), param(f"tr.{a}.wo", c, c), param(f"tr.{a}.bo", c)
+    param("tr.ff.ln_g", c), param("tr.ff.ln_b", c), param("tr.ff.w1", 8 * c, c), param("tr.ff.b1", 8 * c)
+    param("tr.ff.w2", c, 4 * c), param("tr.ff.b2", c)
+    param("tr.w_out", c, c, 1, 1), param("tr.b_out", c)
+
+    # residual block
+    g.add("res.n1", B.AC_OP_GROUP_NORM, ("x", "res.gn1_g", "res.gn1_b"), img, (groups,))
+    g.add("res.a1", B.AC_OP_ELEMENTWISE, ("res.n1",), img)
+    g.add("res.c1", B.AC_OP_CONV2D, ("res.a1", "res.w1", "res.b1"), img)
+    g.add("res.t", B.AC_OP_ELEMENTWISE, ("res.c1", "temb"), img)
+    g.add("res.n2", B.AC_OP_GROUP_NORM, ("res.t", "res.gn2_g", "res.gn2_b"), img, (groups,))
+    g.add("res.a2", B.AC_OP_ELEMENTWISE, ("res.n2",), img)
+    g.add("res.c2", B.AC_OP_CONV2D, ("res.a2", "res.w2", "res.b2"), img)
+    g.add("res.y", B.AC_OP_ELEMENTWISE, ("x", "res.c2"), img)
+    # spatial transformer: image -> tokens
+    g.add("tr.n", B.AC_OP_GROUP_NORM, ("res.y", "tr.gn_g", "tr.gn_b"), img, (groups,))
+    g.add("tr.in", B.AC_OP_CONV2D, ("tr.n", "tr.w_in", "tr.b_in"), img)
+    g.add("tr.flat", B.AC_OP_MERGE_DIMS, ("tr.in",), (b, c, n), (2, ww))
+    src = g.add("tr.tok", B.AC_OP_TRANSPOSE, ("tr.flat",), tok, (0, 2, 1))
+    for a, kv_src, kv_len in (("sa", None, n), ("ca", "context", context_tokens)):
+        p = f"tr.{a}."
+        g.add(p + "u", B.AC_OP_NORM_LAST, (src, p + "ln_g", p + "ln_b"), tok)
+        kv = kv_src or p + "u"
+        for t, inp, w, length in (("q", p + "u", "wq", n), ("k", kv, "wk", kv_len), ("v", kv, "wv", kv_len)):
+            g.add(p + t, B.AC_OP_LINEAR, (inp, p + w), (b, length, c))
+            g.add(p + t + "_split", B.AC_OP_SPLIT_DIM, (p + t,), (b, length, heads, dh), (2, heads))
+            g.add(p + t + "_h", B.AC_OP_TRANSPOSE, (p + t + "_split",), (b, heads, length, dh), (0, 2, 1, 3))
+        g.add(p + "scores", B.AC_OP_MATMUL_NT, (p + "q_h", p + "k_h"), (b, heads, n, kv_len))
+        g.add(p + "scaled", B.AC_OP_ELEMENTWISE, (p + "scores",), (b, heads, n, kv_len))
+        g.add(p + "probs", B.AC_OP_SOFTMAX_LAST, (p + "scaled",), (b, heads, n, kv_len))
+        g.add(p + "ctx_h", B.AC_OP_MATMUL_NN, (p + "probs", p + "v_h"), (b, heads, n, dh))
+        g.add(p + "ctx_t", B.AC_OP_TRANSPOSE, (p + "ctx_h",), (b, n, heads, dh), (0, 2, 1, 3))
+        g.add(p + "ctx", B.AC_OP_MERGE_DIMS, (p + "ctx_t",), tok, (2, dh))
+        g.add(p + "o", B.AC_OP_LINEAR, (p + "ctx", p + "wo", p + "bo"), tok)
+        src = g.add(p + "h", B.AC_OP_ELEMENTWISE, (src, p + "o"), tok)
+    g.add("tr.ff.u", B.AC_OP_NORM_LAST, (src, "tr.ff.ln_g", "tr.ff.ln_b"), tok)
+    g.add("tr.ff.t", B.AC_OP_LINEAR, ("tr.ff.u", "tr.ff.w1", "tr.ff.b1"), (b, n, 8 * c))
+    g.add("tr.ff.val", B.AC_OP_SLICE_LAST, ("tr.ff.t",), (b, n, 4 * c), (0, 4 * c))
+    g.add("tr.ff.gate", B.AC_OP_SLICE_LAST, ("tr.ff.t",), (b, n, 4 * c), (4 * c, 8 * c))
+    g.add("tr.ff.act", B.AC_OP_ELEMENTWISE, ("tr.ff.val", "tr.ff.gate"), (b, n, 4 * c))
+    g.add("tr.ff.down", B.AC_OP_LINEAR, ("tr.ff.act", "tr.ff.w2", "tr.ff.b2"), tok)
+    g.add("tr.ff.h", B.AC_OP_ELEMENTWISE, (src, "tr.ff.down"), tok)
+    # tokens -> image
+    g.add("tr.back", B.AC_OP_TRANSPOSE, ("tr.ff.h",), (b, c, n), (0, 2, 1))
+    g.add("tr.img", B.AC_OP_SPLIT_DIM, ("tr.back",), img, (2, hh))
+    g.add("tr.out", B.AC_OP_CONV2D, ("tr.img", "tr.w_out", "tr.b_out"), img)
+    g.add("tr.y", B.AC_OP_ELEMENTWISE, ("res.y", "tr.out"), img)
+    return g.spec, g.names

@@ -3,7 +3,12 @@ tuples with the op numbering of include/autochunk_search.h, leaves first.  No se
 import numpy as np
 
 (INPUT, PARAM, LINEAR, MATMUL_NT, MATMUL_NN, ELEMENTWISE, NORM_LAST, SOFTMAX_LAST, TRANSPOSE, SPLIT_DIM, MERGE_DIMS,
- SLICE_LAST, CONTRACT_IKC_JKC) = range(13)
+ SLICE_LAST, CONTRACT_IKC_JKC, CONV2D, GROUP_NORM) = range(15)
+
+def close(got, want):
+    """Equal up to fp64 rounding of sums taken in another order (values of a random graph can be large)."""
+    return np.allclose(got, want, rtol=0, atol=1e-9 * max(1.0, float(np.abs(want).max())))
+
 
 FNS = {"tanh": np.tanh, "add": lambda a, b: a + b, "mul": lambda a, b: a * b, "add3": lambda a, b, c: a + b * c}
 
@@ -27,7 +32,7 @@ def random_graph(seed, n_ops=10):
         shp = nodes[x][2]
         r = len(shp)
         op = int(rng.choice([LINEAR, MATMUL_NT, MATMUL_NN, ELEMENTWISE, ELEMENTWISE, NORM_LAST, SOFTMAX_LAST, TRANSPOSE,
-                             SPLIT_DIM, MERGE_DIMS, SLICE_LAST, CONTRACT_IKC_JKC]))
+                             SPLIT_DIM, MERGE_DIMS, SLICE_LAST, CONTRACT_IKC_JKC, CONV2D, GROUP_NORM]))
         if op == LINEAR:
             n = int(rng.choice(sizes))
             w = add(PARAM, shape=(n, shp[-1]))
@@ -90,6 +95,19 @@ def random_graph(seed, n_ops=10):
             a = int(rng.integers(0, shp[-1] - 1))
             b = int(rng.integers(a + 1, shp[-1] + 1))
             add(SLICE_LAST, [x], shp[:-1] + (b - a,), (a, b))
+        elif op == CONV2D:
+            if r != 4:
+                continue
+            co = int(rng.choice(sizes))
+            kh, kw = (int(v) for v in rng.choice([1, 3], size=2))
+            ins = [x, add(PARAM, shape=(co, shp[1], kh, kw))] + ([add(PARAM, shape=(co,))] if rng.random() < 0.5 else [])
+            add(CONV2D, ins, (shp[0], co) + shp[2:])
+        elif op == GROUP_NORM:
+            if r != 4:
+                continue
+            groups = int(rng.choice([g for g in (1, 2, 3) if shp[1] % g == 0]))
+            ins = [x] + ([add(PARAM, shape=(shp[1],)), add(PARAM, shape=(shp[1],))] if rng.random() < 0.5 else [])
+            add(GROUP_NORM, ins, shp, (groups,))
         elif op == CONTRACT_IKC_JKC:
             if r != 3:
                 continue

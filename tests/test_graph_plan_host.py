@@ -35,7 +35,7 @@ def test_estimate_with_moved_nodes_equals_the_oracle():
     block, nm = S.transformer_block_graph(2, 12, 8, 2, 16)
     kv = tuple(sorted(nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")))
     cases = [([(nd.op, nd.inputs, nd.shape, nd.attr, None) for nd in block], [(nm["q_flat"], nm["ctx"], 1, 4, kv)])]
-    cases += [(G.random_graph(seed, n_ops=12 + seed % 6), None) for seed in range(150)]
+    cases += [(G.random_graph(seed, n_ops=12 + seed % 6), None) for seed in range(220)]
     for seed, (spec, chunks) in enumerate(cases):
         on, ln = oracle_nodes(spec), library_nodes(spec)
         if chunks is None:

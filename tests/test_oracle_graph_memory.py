@@ -141,7 +141,7 @@ def test_live_bytes_equal_a_counting_executor():
             assert peak == max(seen) and peak_node == seen.index(peak)
             val = S.run(nodes, feeds)
             for j, a in left.items():           # what is left are the graph's outputs, and they are right
-                assert np.allclose(a, val[j], atol=1e-9)
+                assert G.close(a, val[j])
             n_regions += len(chunks)
     assert n_regions > 40
 
@@ -272,7 +272,7 @@ def cheapest_by_exhaustion(nodes, e, budget, window, weights):
 def test_a_wide_beam_finds_the_cheapest_strategy():
     weights = (1.0, 1e-3, -1e-3, -0.5)
     solved = rescued = 0
-    for seed in range(60):
+    for seed in range(100):
         nodes = oracle_nodes(G.random_graph(seed, n_ops=10 + seed % 4))
         feeds = S.random_feeds(nodes, seed)
         _, whole, _ = GM.estimate(nodes, 8)
@@ -322,7 +322,7 @@ def test_live_bytes_with_moved_nodes_equal_the_counting_executor():
     block, nm = S.transformer_block_graph(2, 12, 8, 2, 16)
     cases = [(block, [(nm["q_flat"], nm["ctx"], 1, 4, tuple(sorted(nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")))),
                       (nm["t"], nm["down"], 0, 1, ())])]
-    cases += [(oracle_nodes(G.random_graph(seed, n_ops=12 + seed % 6)), None) for seed in range(150)]
+    cases += [(oracle_nodes(G.random_graph(seed, n_ops=12 + seed % 6)), None) for seed in range(220)]
     for seed, (nodes, chunks) in enumerate(cases):
         feeds = S.random_feeds(nodes, seed)
         if chunks is None:
@@ -332,7 +332,7 @@ def test_live_bytes_with_moved_nodes_equal_the_counting_executor():
         assert mem == seen, (seed, chunks)
         val = S.run(nodes, feeds)
         for j, a in left.items():
-            assert np.allclose(a, val[j], atol=1e-9)
+            assert G.close(a, val[j])
         n_moved += sum(len(c[4]) > 0 for c in chunks)
     assert n_moved > 20
 

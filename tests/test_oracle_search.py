@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import chunk_search as S
+from tests import graphs as G
 
 
 def small_block(batch=2, seq=12, d=8, heads=2, f=16):
@@ -33,7 +34,7 @@ def test_every_legal_chunk_reproduces_the_unchunked_output():
             extent = nodes[end].shape[dim]
             for clen in {g, 2 * g, (extent // g // 2 + 1) * g, extent}:     # incl. a ragged last segment
                 got = S.run_chunked(nodes, val, start, end, dim, node_dims, input_dims, clen)
-                assert np.allclose(got, val[end], rtol=0, atol=1e-11), (start, end, dim, clen)
+                assert G.close(got, val[end]), (start, end, dim, clen)
                 n_checked += 1
     assert n_checked > 200 and len(seen) > 60
 
@@ -107,7 +108,6 @@ def test_graph_optimisation_moves_nodes_off_the_flow_ahead_of_the_region():
     """Section 3.3, graph optimisation.  Every candidate of the search with it, run with the moved
     nodes computed once and whole, reproduces the unchunked output in segments of exactly the
     chunk length; every strict candidate is found unchanged; the cases with a known answer."""
-    from tests import graphs as G
     nodes, nm, val = small_block()
     t = S.trace_hoisting(nodes, nm["q_flat"], nm["ctx"], 1)          # attention cut along the queries
     assert t is not None and t[2] == {nm[x + s] for x in "kv" for s in ("_flat", "_split", "_h")}
@@ -136,7 +136,7 @@ def test_graph_optimisation_moves_nodes_off_the_flow_ahead_of_the_region():
                 g = S.chunk_granule(gr, end, dim, node_dims, input_dims)
                 got, parts = S.run_chunked(gr, v, start, end, dim, node_dims, input_dims, g, parts_too=True, moved=moved)
                 assert all(p.shape[dim] == g for p in parts)
-                assert np.allclose(got, v[end], rtol=0, atol=1e-9), (gi, start, end, dim)
+                assert G.close(got, v[end]), (gi, start, end, dim)
                 n_checked += 1
                 n_moved += bool(moved)
     assert n_checked > 1500 and n_moved > 60, (n_checked, n_moved)
