@@ -159,3 +159,13 @@ def test_pair_block_plan_equals_the_oracle_and_chunks_the_triangle_attention():
     assert peak_node == nm["tas.biased"] and whole == 2 * (4 * 1024 ** 3) * 2 + (3 * 128 + 4) * 1024 * 1024 * 2
     chunks, peak = B.ac_graph_plan(big, 2, 4 << 30, 16, (1, 0, 0, 0), beam=2)
     assert peak <= 4 << 30 and [(c[0], c[2]) for c in chunks] == [(nm["tas.scores"], 0), (nm["tae.scores"], 0)]
+
+
+def test_calibration_reads_the_four_terms_of_the_cost():
+    from paper_2401_10652_amd import calibrate
+    spec, nm = PG.transformer_stack_graph(2, 12, 8, 2, 16)
+    ln = B.graph_nodes(spec)
+    b, h, sq, dh = 2, 2, 12, 4
+    flops = 2 * b * h * sq * sq * dh + b * h * sq * sq + 5 * b * h * sq * sq + 2 * b * h * sq * dh * sq
+    assert calibrate.terms(ln, nm["scores"], nm["ctx_h"], 2) == [4.0, float(flops), flops / 4, float(dh)]
+    assert list(calibrate.ranks(np.array([0.3, -1.0, 2.0]))) == [1.0, 0.0, 2.0]
