@@ -1,4 +1,7 @@
-// Chunk search on an op graph (AutoChunk, section 3.3).  Host code only.
+// The passes that decide a chunk plan, on an op graph (AutoChunk sections 3.2 to 3.4): chunk
+// flow and the four rules, the graph optimisation, the windowed two-stage search, activation
+// memory with and without chunks, the selection cost, and the loop of passes with a beam.
+// Host code only.
 //
 // A chunk is a run [start, end] of the node list plus one dimension of node `end`.  The
 // flow of that dimension is followed from `end` towards the region's inputs: each op kind
