@@ -163,6 +163,8 @@ def main():
     from paper_2401_10652_amd import binding as B
     from paper_2401_10652_amd import inputs as I
 
+    from paper_2401_10652_amd.build import ensure_built
+    ensure_built()      # loads what is built; compiles only when nothing is
     B.lib()
     torch.cuda.set_device(0)
     if args.copy_calibration:

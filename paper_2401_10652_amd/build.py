@@ -56,5 +56,11 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """The library's path, compiling it first only if no built library is there (for the test
+    suite, the smoke run and the benchmark; the binding itself never builds and raises)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """The suite loads the built library; it compiles it only when none is there."""
+    from paper_2401_10652_amd.build import ensure_built
+    ensure_built()
+
+
 def pytest_collection_modifyitems(config, items):
     """GPU tests are skipped (not failed) when no device is visible."""
     need_gpu = [it for it in items if "gpu" in it.keywords]
