@@ -319,3 +319,52 @@ def test_unet_stage_plan_at_a_latent_diffusion_size():
     chunks, peak = B.ac_graph_plan(ln, 2, whole // 4, 16, (1, 0, 0, 0), beam=2)
     assert peak <= whole // 4 and len(chunks) == 1
     assert nm["tr.sa.scores"] <= chunks[0][0] <= chunks[0][1] <= nm["tr.sa.ctx"]
+
+
+def test_corrupted_graphs_are_refused_or_handled_never_trusted():
+    """Valid random graphs with a few fields overwritten by arbitrary values: every entry point
+    must come back with a status (AC_OK or an error), whatever it is handed."""
+    rng = np.random.default_rng(77)
+    L = B.lib()
+    statuses = set()
+    for case in range(1500):
+        spec = G.random_graph(case % 40, n_ops=9)
+        ln = library_nodes(spec)
+        n = len(ln)
+        for _ in range(int(rng.integers(1, 4))):
+            nd = ln[int(rng.integers(n))]
+            field = int(rng.integers(6))
+            value = int(rng.choice([-(1 << 31), -7, -1, 0, 1, 2, 5, 6, 7, 100, (1 << 31) - 1]))
+            if field == 0:
+                nd.op = value
+            elif field == 1:
+                nd.n_inputs = value
+            elif field == 2:
+                nd.inputs[int(rng.integers(3))] = value
+            elif field == 3:
+                nd.rank = value
+            elif field == 4:
+                nd.shape[int(rng.integers(6))] = int(rng.choice([-(1 << 62), -1, 0, 1, 3, 1 << 20, 1 << 41, (1 << 63) - 1]))
+            else:
+                nd.attr[int(rng.integers(6))] = int(rng.choice([-(1 << 62), -1, 0, 1, 2, 5, 6, 1 << 40]))
+        found, legal, peak_node = C.c_int(0), C.c_int(0), C.c_int(0)
+        peak = C.c_uint64(0)
+        row = (C.c_int32 * n)()
+        moved = (C.c_uint8 * n)()
+        out = (B.ac_chunk_candidate * 64)()
+        rows = (C.c_int32 * (64 * n))()
+        chunks = (B.ac_graph_chunk * 8)()
+        w = (C.c_double * 4)(1.0, 1e-9, -1e-9, 0.5)
+        cost = C.c_double(0)
+        n_out = C.c_int(0)
+        hoist = case % 2
+        start, end = sorted(int(v) for v in rng.integers(-1, n + 1, size=2))
+        statuses.add(L.ac_chunk_search(ln, n, int(rng.integers(-1, n + 1)), int(rng.integers(0, 12)), hoist, out, rows, None,
+                                       64, C.byref(found), None, None))
+        statuses.add(L.ac_chunk_trace(ln, n, start, end, int(rng.integers(-1, 7)), hoist, row, moved, C.byref(legal)))
+        statuses.add(L.ac_graph_estimate(ln, n, 2, None, 0, None, C.byref(peak), C.byref(peak_node)))
+        statuses.add(L.ac_graph_chunk_cost(ln, n, start, end, int(rng.integers(-1, 7)), hoist, w, C.byref(cost)))
+        statuses.add(L.ac_graph_plan(ln, n, 2, int(rng.integers(0, 4000)), 6, w, 2, hoist, chunks, 8, C.byref(n_out),
+                                     C.byref(peak)))
+    assert statuses <= {B.AC_OK, B.AC_ERR_ARG, B.AC_ERR_BUDGET_INFEASIBLE, B.AC_ERR_ILLEGAL_CHUNK_DIM}
+    assert B.AC_OK in statuses and B.AC_ERR_ARG in statuses
