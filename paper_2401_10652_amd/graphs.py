@@ -80,7 +80,7 @@ def executor_regions(chunks, names):
     executor has no kernel for, or when layers disagree on the dimension."""
     by_index = {v: k for k, v in names.items()}
     settings = {}
-    for start, end, out_dim, chunk_len in chunks:
+    for start, end, out_dim, chunk_len in (c[:4] for c in chunks):     # a fifth entry (hoist) changes nothing here
         prefix, _, last = by_index[end].rpartition(".")
         where = (lambda nm: names[f"{prefix}.{nm}" if prefix else nm])
         kind = next((k for k, a, b in _KIND_SPANS if where(a) <= start and end <= where(b)), None)

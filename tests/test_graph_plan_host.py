@@ -169,3 +169,16 @@ def test_calibration_reads_the_four_terms_of_the_cost():
     flops = 2 * b * h * sq * sq * dh + b * h * sq * sq + 5 * b * h * sq * sq + 2 * b * h * sq * dh * sq
     assert calibrate.terms(ln, nm["scores"], nm["ctx_h"], 2) == [4.0, float(flops), flops / 4, float(dh)]
     assert list(calibrate.ranks(np.array([0.3, -1.0, 2.0]))) == [1.0, 0.0, 2.0]
+
+
+def test_chunks_map_to_executor_region_settings():
+    spec, nm = PG.transformer_stack_graph(1, 64, 16, 2, 32, layers=2)
+    regs = PG.executor_regions([(nm["scores"], nm["ctx_h"], 2, 24), (nm["l1.scores"], nm["l1.ctx"], 1, 16, 1),
+                                (nm["l1.t"], nm["l1.down"], 1, 32)], nm)
+    assert regs == [(B.AC_REGION_ATTENTION, B.AC_DIM_SEQ, 16), (B.AC_REGION_FFN, B.AC_DIM_SEQ, 32)]
+    assert PG.executor_regions([(nm["u"], nm["qkv"], 0, 1)], nm) == [(B.AC_REGION_QKV, B.AC_DIM_BATCH, 1)]
+    for bad in ([(nm["scores"], nm["ctx_h"], 1, 1)],                       # along the heads: no kernel
+                [(nm["ctx"], nm["h"], 1, 8)],                              # spans attention and output projection
+                [(nm["scores"], nm["ctx_h"], 2, 8), (nm["l1.scores"], nm["l1.ctx_h"], 0, 1)]):   # layers disagree
+        with pytest.raises(ValueError):
+            PG.executor_regions(bad, nm)
