@@ -93,7 +93,7 @@ enum {
   AC_FLAG_LISTED_REGIONS_ONLY = 2, /* pair stack only: the block consists of just the region kinds
                                       listed in ac_plan_create (each maps z to z), in canonical
                                       order; weights of the others are still bound but unused */
-  AC_FLAG_MATERIALIZED_SCORES = 8  /* transformer stack only: the attention core runs as an unfused graph
+  AC_FLAG_MATERIALIZED_SCORES = 8, /* transformer stack only: the attention core runs as an unfused graph
                                       would (AutoChunk section 2.1): scores = q k^T per head stored in the
                                       workspace, probabilities = softmax(scores) stored beside them,
                                       context = probabilities v.  The workspace then really holds the
@@ -103,6 +103,13 @@ enum {
                                       to the rounding of the stored scores and probabilities.  With a
                                       causal mask the masked half is computed and discarded;
                                       flops_per_execute counts what is executed. */
+  AC_FLAG_BUDGET_PAPER_MODEL = 16  /* act_budget_bytes additionally bounds, for every region, the bytes
+                                      the paper's two activation equations give for an unfused graph in
+                                      which every op output is a tensor (ac_region_info.model_bytes:
+                                      scores and probabilities of a segment included), as a planner that
+                                      sees such a graph would size it (AutoChunk section 3.2, 3.4).
+                                      Without the flag the budget bounds what this executor really
+                                      holds, where the scores never reach memory. */
 };
 
 typedef struct ac_model_desc {
@@ -171,25 +178,35 @@ typedef struct ac_plan ac_plan;
  * Build a chunk plan (host only; touches no device).  Section 3.1/3.2: regions, their
  * chunk settings, and a memory budget in; a plan out.  `regions` lists at most one entry
  * per region kind of the workload; a kind not listed runs as one segment.  The same
- * settings apply to every layer.  `act_budget_bytes` (0 = none) bounds, per layer, both
- * the planned executor bytes and the paper-style model bytes of every region; it sizes the
- * regions whose chunk_len is 0 and is checked (AC_ERR_BUDGET_INFEASIBLE) for the others.
+ * settings apply to every layer.  `act_budget_bytes` (0 = none) is the paper's memory_budget
+ * (section 3.2): it bounds the activation memory this executor really needs, mem(X) + mem(Y) +
+ * the workspace's high-water mark (peak_bytes_planned).  Every region whose chunk_len is 0 gets
+ * the largest length (its extent, else a multiple of 128 rows for bf16 / 64 for fp32 / 1 for
+ * batch elements and pair rows) at which its own peak fits; regions with an explicit length are
+ * checked (AC_ERR_BUDGET_INFEASIBLE).  With AC_FLAG_BUDGET_PAPER_MODEL the paper-style bytes of
+ * every region are bounded as well.
  * Errors: AC_ERR_ARG, AC_ERR_ILLEGAL_CHUNK_DIM, AC_ERR_UNSUPPORTED, AC_ERR_BUDGET_INFEASIBLE.
  * On success *out owns host memory only; release it with ac_plan_destroy.
  */
 int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, int n_regions,
                    uint64_t act_budget_bytes, ac_plan** out);
 
-/* Sizes and byte counts of a plan (host only).  `out` is host memory of the caller. */
+/* Sizes and byte counts of a plan (host only).  `out` is host memory of the caller.  The byte
+ * counts are those of section 2.1 / 2.2: mem(X) + mem(Y) + mem(A) for one segment per region,
+ * mem(X) + mem(Y) + mem(A)/n for the plan, once as this executor holds them and once as the
+ * unfused graph of the paper's model would. */
 int ac_plan_query(const ac_plan* plan, ac_plan_info* out);
 
 /* Name, shape and dtype of weight tensor `index` (0 <= index < n_weights), in bind order. */
 int ac_plan_weight_info(const ac_plan* plan, int index, ac_weight_info* out);
 
 /*
- * Hand the plan the device addresses of its weights, in ac_plan_weight_info order.  The
- * pointers stay owned by the caller and must outlive every ac_execute of this plan.  Each
- * must be 256-byte aligned (AC_ERR_ALIGN); n_ptrs must equal n_weights (AC_ERR_ARG).
+ * Hand the plan the device addresses of its weights, in ac_plan_weight_info order (section 3.1:
+ * the weights are non-chunkable inputs X^nc, seen whole by every segment).  The pointers stay
+ * owned by the caller and must outlive every ac_execute of this plan.  Each must be 256-byte
+ * aligned (AC_ERR_ALIGN); n_ptrs must equal n_weights (AC_ERR_ARG).  This is the first call of a
+ * plan that touches the device: a plan with AC_FLAG_TWO_SEGMENTS_IN_FLIGHT creates its second
+ * stream here (AC_ERR_HIP if that fails), so that ac_execute creates nothing.
  */
 int ac_plan_bind_weights(ac_plan* plan, const void* const* dev_ptrs, int n_ptrs);
 
@@ -206,7 +223,8 @@ int ac_plan_bind_weights(ac_plan* plan, const void* const* dev_ptrs, int n_ptrs)
 int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_dev,
                uint64_t workspace_bytes, void* stream, uint64_t* measured_peak_bytes);
 
-/* Free the plan's host memory (and its profiling events, if any).  NULL is allowed. */
+/* Free the plan's host memory, its second stream and its events, if any (the plan of section
+ * 3.2 holds no device memory).  NULL is allowed. */
 void ac_plan_destroy(ac_plan* plan);
 
 /*

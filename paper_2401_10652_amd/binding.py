@@ -27,6 +27,7 @@ AC_FLAG_UNFUSED_ELEMENTWISE = 1
 AC_FLAG_LISTED_REGIONS_ONLY = 2
 AC_FLAG_TWO_SEGMENTS_IN_FLIGHT = 4
 AC_FLAG_MATERIALIZED_SCORES = 8
+AC_FLAG_BUDGET_PAPER_MODEL = 16
 
 ACTIVATIONS = {"none": AC_ACT_NONE, "gelu_erf": AC_ACT_GELU_ERF, "gelu_tanh": AC_ACT_GELU_TANH,
                "relu": AC_ACT_RELU, "sigmoid": AC_ACT_SIGMOID}

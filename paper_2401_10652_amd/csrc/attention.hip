@@ -452,13 +452,9 @@ template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED, NW>;
   constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t nqb = (a.sq + 32 * NW - 1) / (32 * NW);
   const int ns = a.n_splits > 1 ? a.n_splits : 1;
   const int64_t blocks = nqb * a.heads * a.batch * ns;

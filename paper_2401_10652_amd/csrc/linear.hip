@@ -383,14 +383,11 @@ constexpr size_t mfma_lds_bytes() { return (size_t)2 * (BM + BN) * kLdsRow * siz
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
   auto kern = linear_mfma_bf16<BM, BN, WAVES_M, WAVES_N>;
-  static bool attr_set = false;   // the attribute is per function; set once per process
   constexpr size_t lds = mfma_lds_bytes<BM, BN>();
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // the attribute is per function; set once per process (the initialiser runs once, thread-safe)
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t tiles = ((g.m + BM - 1) / BM) * ((g.n + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)g.batch), dim3(64 * WAVES_M * WAVES_N), lds, s, g);
   return hipGetLastError();

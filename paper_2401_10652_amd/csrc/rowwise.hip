@@ -129,9 +129,11 @@ hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const 
 // y = act(x + bias[col]);  y = a (+|*) b.   Grid-stride over 16-byte vectors of a
 // [rows, cols] view with row strides; cols % kVec == 0 takes the vector path.
 // ------------------------------------------------------------------------------------
+// x and y may be the same buffer (the executor applies bias + activation in place), so the
+// pointers carry no restrict qualifier.
 template <typename T>
 __global__ void __launch_bounds__(256)
-bias_act_vec(const T* __restrict__ x, int64_t ldx, const T* __restrict__ bias, T* __restrict__ y,
+bias_act_vec(const T* x, int64_t ldx, const T* bias, T* y,
              int64_t ldy, int64_t rows, int64_t vec_per_row, int act) {
   constexpr int V = Elem<T>::kVec;
   const int64_t total = rows * vec_per_row;
@@ -152,7 +154,7 @@ bias_act_vec(const T* __restrict__ x, int64_t ldx, const T* __restrict__ bias, T
 
 template <typename T>
 __global__ void __launch_bounds__(256)
-bias_act_scalar(const T* __restrict__ x, int64_t ldx, const T* __restrict__ bias, T* __restrict__ y,
+bias_act_scalar(const T* x, int64_t ldx, const T* bias, T* y,
                 int64_t ldy, int64_t rows, int64_t cols, int act) {
   const int64_t total = rows * cols;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
@@ -383,7 +385,7 @@ hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, con
 // ------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256)
-softmax_rows(const T* __restrict__ src, int64_t lds_, T* __restrict__ dst, int64_t ldd, int64_t cols, float scale,
+softmax_rows(const T* src, int64_t lds_, T* dst, int64_t ldd, int64_t cols, float scale,
              int causal, int64_t q_offset, int64_t period) {
   __shared__ float red[4];
   const int64_t r = blockIdx.x;

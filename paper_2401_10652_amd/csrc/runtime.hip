@@ -48,10 +48,12 @@ static const char* const kClassName[K_CLASSES] = {"gemm", "attention", "layernor
 struct Arena {
   uint8_t* base = nullptr;   // null during planning
   uint64_t top = 0, high = 0;
+  uint64_t* watch = nullptr;   // high-water mark of the region being walked (planning)
   void* push(uint64_t bytes) {
     const uint64_t off = align_up(top, 256);
     top = off + bytes;
     high = std::max(high, top);
+    if (watch) *watch = std::max(*watch, top);
     // during planning the "pointer" is only an offset and is never dereferenced
     return base ? (void*)(base + off) : (void*)(uintptr_t)(off + 256);
   }
@@ -92,6 +94,7 @@ struct ac_plan {
   hipStream_t aux_stream = nullptr;
   std::vector<hipEvent_t> sync_pool;
   size_t sync_used = 0;
+  int sync_needed = 0;
 };
 
 namespace ac {
@@ -114,8 +117,14 @@ struct Walk {
   int lanes = 1;
   hipStream_t lane_stream[2] = {nullptr, nullptr};
   bool measuring = false;  // sizing pass of a segment loop: pushes only, no launches, no counts
+  // highest arena offset reached while each region kind was being walked: a region's own peak,
+  // which depends on its own chunk length only (the whole tensors around it are fixed)
+  uint64_t region_high[AC_REGION_KINDS] = {};
+  void enter(int kind) { arena.watch = &region_high[kind]; }
 
+  int sync_events = 0;     // planning: events one execute needs for its forks and joins
   void fork() {
+    if (dry && lanes == 2) ++sync_events;
     if (dry || lanes != 2 || !ok()) return;
     hipEvent_t e = next_sync_event();
     if (!e) return;
@@ -125,6 +134,7 @@ struct Walk {
   }
   void join() {
     stream = lane_stream[0];
+    if (dry && lanes == 2) ++sync_events;
     if (dry || lanes != 2 || !ok()) return;
     hipEvent_t e = next_sync_event();
     if (!e) return;
@@ -230,7 +240,11 @@ struct Walk {
       pairs = (double)a.sq * a.sk;
     }
     const double fl = 4.0 * pairs * a.head_dim * a.heads * a.batch;
-    const double by = ((double)a.sq * 2 + (double)a.sk * 2) * a.heads * a.head_dim * a.batch * eb();
+    // q and ctx rows of the segment, k and v rows any of them sees (causal: keys up to the last row)
+    const int64_t keys_seen = a.causal ? std::min<int64_t>(a.sk, a.q_offset + a.sq) : a.sk;
+    double by = ((double)a.sq * 2 + (double)keys_seen * 2) * a.heads * a.head_dim * a.batch * eb();
+    if (a.gate) by += (double)a.sq * a.heads * a.head_dim * a.batch * eb();
+    if (a.bias) by += (double)a.sq * a.sk * a.heads * eb();
     // few query rows: cut the keys into runs so that every CU gets blocks; the fp32 partial
     // results live in the arena for the duration of this call
     const uint64_t mk = arena.mark();
@@ -352,14 +366,11 @@ struct Walk {
   void transition(const void* const* W, const void* zin, void* zout);
 };
 
+// Events of the forks and joins: all created when the weights are bound (the dry run counted them).
 hipEvent_t Walk::next_sync_event() {
   if (p->sync_used == p->sync_pool.size()) {
-    hipEvent_t e;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
-      err = hipGetLastError(); err_where = "hipEventCreate";
-      return nullptr;
-    }
-    p->sync_pool.push_back(e);
+    err = hipErrorInvalidResourceHandle; err_where = "fork/join event pool";
+    return nullptr;
   }
   return p->sync_pool[p->sync_used++];
 }
@@ -408,6 +419,7 @@ void Walk::transformer(const void* x, void* y) {
     auto W = [&](int slot) { return w(l, slot, 12); };
 
     // ---- region 1: LayerNorm 1 + packed projection, writes whole q, k, v
+    enter(AC_REGION_QKV);
     seg_loop(token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
       void* u = arena.push((uint64_t)rows * d * e);
@@ -439,6 +451,7 @@ void Walk::transformer(const void* x, void* y) {
       }
     }
     // ---- region 2: attention of a query segment over whole k, v; writes its rows of the context
+    enter(AC_REGION_ATTENTION);
     seg_loop(token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0;
       AttnArgs a{};
@@ -458,12 +471,14 @@ void Walk::transformer(const void* x, void* y) {
     });
 
     // ---- region 2b: output projection + residual
+    enter(AC_REGION_OUT_PROJ);
     seg_loop(token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
       proj(at(ctx_all, r0 * d), d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
     });
 
     // ---- region 3: LayerNorm 2 + feed-forward + residual
+    enter(AC_REGION_FFN);
     seg_loop(token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN)), [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
       void* u = arena.push((uint64_t)rows * d * e);
@@ -506,6 +521,7 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t mk0 = arena.mark();
+  enter(kind);
   void* a_t = arena.push((uint64_t)ch * R * e);   // [c][i][k]
   void* b_t = arena.push((uint64_t)ch * R * e);   // [c][j][k]
   const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
@@ -564,6 +580,7 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t mk0 = arena.mark();
+  enter(kind);
   const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
   // ---- whole operands.  Starting node: the pair bias [h][j][k].  Ending node: the bias as
   // [h][i][k] (= projection at position (k, i)), all keys [(k, j)][h*d] and all values
@@ -651,6 +668,7 @@ void Walk::transition(const void* const* W, const void* zin, void* zout) {
   const int e = eb();
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  enter(AC_REGION_PAIR_TRANSITION);
   seg_loop(row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION)), [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
     void* u = arena.push((uint64_t)rows * cz * e);
@@ -747,13 +765,16 @@ static bool dim_legal(const ac_model_desc& m, int dim, bool& known) {
   return false;
 }
 
-static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& flops) {
+static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& flops,
+                    uint64_t* region_high = nullptr) {
   Walk wk{p, true, unchunked, nullptr};
   wk.lanes = (p->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) ? 2 : 1;
   if (p->m.workload == AC_TRANSFORMER_STACK) wk.transformer(nullptr, nullptr);
   else wk.pair(nullptr, nullptr);
   arena_bytes = wk.arena.high;
   flops = wk.flops;
+  if (region_high) memcpy(region_high, wk.region_high, sizeof(wk.region_high));
+  if (!unchunked) p->sync_needed = wk.sync_events;
 }
 
 static uint64_t io_bytes(const ac_model_desc& m) {
@@ -881,16 +902,20 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     }
   }
 
-  // ---- size the regions left open from the budget: largest length (the extent itself, or
-  // a multiple of the row granule below it) whose paper-style region bytes fit.
-  const int64_t granule = m.workload == AC_PAIR_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
+  // ---- paper-style model bytes as an additional bound (AC_FLAG_BUDGET_PAPER_MODEL): largest
+  // length (the extent itself, or a multiple of the region's granule below it) whose unfused
+  // region bytes fit; explicit lengths are checked against the same bound.
+  const int64_t row_granule = m.workload == AC_PAIR_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
+  auto granule_of = [&](const Setting& s) -> int64_t {
+    return (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_BATCH) ? 1 : row_granule;
+  };
   auto rows_of = [&](const Setting& s, int64_t len) { return model_rows(m, s, len); };
-  if (act_budget_bytes > 0) {
+  if (act_budget_bytes > 0 && (m.flags & AC_FLAG_BUDGET_PAPER_MODEL)) {
     for (int k = first; k < first + count; ++k) {
       Setting& s = p->set[k];
       if (s.sized_by_budget) {
         int64_t c = s.extent;
-        const int64_t g = s.chunk_dim == AC_DIM_BATCH && m.workload == AC_TRANSFORMER_STACK ? 1 : granule;
+        const int64_t g = granule_of(s);
         if (model_bytes(m, k, rows_of(s, c)) > act_budget_bytes) {
           c = (s.extent - 1) / g * g;
           while (c >= g && model_bytes(m, k, rows_of(s, c)) > act_budget_bytes) c -= g;
@@ -956,27 +981,50 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
   }
   p->wptr.assign(p->weights.size(), nullptr);
 
-  // ---- plan = dry run of the walk; shrink budget-sized regions while the executor's own
-  // bytes exceed the budget (they are a subset of the model's tensors, so this rarely bites).
+  // ---- plan = dry run of the walk.  The budget bounds the executor's own bytes, mem(X) + mem(Y)
+  // + the arena's high-water mark.  A region's own peak (the highest arena offset reached while
+  // it is walked) depends on its own chunk length only, so every region left open is sized on
+  // its own: the largest length, the extent or a multiple of its granule, whose peak fits.
   ac_plan_info& inf = p->info;
   memset(&inf, 0, sizeof(inf));
   uint64_t arena = 0;
   double flops = 0;
-  for (;;) {
-    dry_run(p, false, arena, flops);
-    if (act_budget_bytes == 0 || io_bytes(m) + arena <= act_budget_bytes) break;
-    int victim = -1;
-    for (int k = first; k < first + count; ++k)
-      if (p->set[k].sized_by_budget && p->set[k].chunk_len > granule &&
-          (victim < 0 || p->set[k].chunk_len > p->set[victim].chunk_len))
-        victim = k;
-    if (victim < 0) {
+  uint64_t rhigh[AC_REGION_KINDS];
+  const uint64_t io = io_bytes(m);
+  dry_run(p, false, arena, flops, rhigh);
+  if (act_budget_bytes > 0 && io + arena > act_budget_bytes) {
+    for (int k = first; k < first + count; ++k) {
+      Setting& s = p->set[k];
+      if (!s.sized_by_budget || io + rhigh[k] <= act_budget_bytes) continue;
+      const int64_t g = granule_of(s);
+      auto fits = [&](int64_t len) {
+        s.chunk_len = len;
+        dry_run(p, false, arena, flops, rhigh);
+        return io + rhigh[k] <= act_budget_bytes;
+      };
+      // lengths tried: g, 2g, ... below the current one (an upper bound already set by the
+      // paper-style model, or the extent); bisection, then a downward walk in case the peak is
+      // not monotone in the length (attention key splits grow as the segment shrinks)
+      int64_t hi = (s.chunk_len - 1) / g, lo = 1;   // in granules
+      if (hi < 1 || !fits(g)) {
+        const uint64_t need = io + rhigh[k];
+        delete p;
+        return fail(AC_ERR_BUDGET_INFEASIBLE, "region %d needs %llu bytes even at chunk_len %lld; budget is %llu", k,
+                    (unsigned long long)need, (long long)g, (unsigned long long)act_budget_bytes);
+      }
+      while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (fits(mid * g)) lo = mid; else hi = mid - 1;
+      }
+      while (lo > 1 && !fits(lo * g)) --lo;
+      s.chunk_len = lo * g;
+    }
+    dry_run(p, false, arena, flops, rhigh);
+    if (io + arena > act_budget_bytes) {
       delete p;
       return fail(AC_ERR_BUDGET_INFEASIBLE, "executor needs %llu bytes; budget is %llu",
-                  (unsigned long long)(io_bytes(m) + arena), (unsigned long long)act_budget_bytes);
+                  (unsigned long long)(io + arena), (unsigned long long)act_budget_bytes);
     }
-    Setting& s = p->set[victim];
-    s.chunk_len = std::max<int64_t>(granule, (s.chunk_len / 2 + granule - 1) / granule * granule);
   }
   inf.workspace_bytes = arena;
   inf.io_bytes = io_bytes(m);
@@ -1033,6 +1081,15 @@ int ac_plan_bind_weights(ac_plan* plan, const void* const* dev_ptrs, int n_ptrs)
     if (!dev_ptrs[i]) return fail(AC_ERR_ARG, "weight %d (%s) is null", i, plan->weights[i].name.c_str());
     if (!aligned256(dev_ptrs[i])) return fail(AC_ERR_ALIGN, "weight %d (%s) is not 256-byte aligned", i, plan->weights[i].name.c_str());
   }
+  if ((plan->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) && !plan->aux_stream &&
+      hipStreamCreateWithFlags(&plan->aux_stream, hipStreamNonBlocking) != hipSuccess)
+    return fail(AC_ERR_HIP, "hipStreamCreate: %s", hipGetErrorString(hipGetLastError()));
+  while ((int)plan->sync_pool.size() < plan->sync_needed) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+      return fail(AC_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(hipGetLastError()));
+    plan->sync_pool.push_back(e);
+  }
   plan->wptr.assign(dev_ptrs, dev_ptrs + n_ptrs);
   plan->bound = true;
   return AC_OK;
@@ -1055,8 +1112,7 @@ int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_de
   wk.arena.base = (uint8_t*)workspace_dev;
   wk.lane_stream[0] = (hipStream_t)stream;
   if (plan->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) {
-    if (!plan->aux_stream && hipStreamCreateWithFlags(&plan->aux_stream, hipStreamNonBlocking) != hipSuccess)
-      return fail(AC_ERR_HIP, "hipStreamCreate: %s", hipGetErrorString(hipGetLastError()));
+    if (!plan->aux_stream) return fail(AC_ERR_STATE, "the plan's second stream does not exist");
     wk.lanes = 2;
     wk.lane_stream[1] = plan->aux_stream;
     plan->sync_used = 0;

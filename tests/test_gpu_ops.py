@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import transformer as O
-from util import TOL, draw, host, rel_err
+from util import TOL, check, draw, host, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,7 @@ def test_layernorm(B, dtype, rows, cols):
     B.ac_op_layernorm(dx, dg, db, y, 1e-5)
     torch.cuda.synchronize()
     ref = O.layer_norm(x, g, b, 1e-5)
-    assert rel_err(host(y), ref) <= TOL[dtype]
+    check(host(y), ref, dtype)
 
 
 @pytest.mark.parametrize("dtype,m,n,k", [
@@ -78,7 +78,7 @@ def test_linear(B, dtype, m, n, k, epi):
     torch.cuda.synchronize()
     got = host(out)
     assert np.isfinite(got).all()
-    assert rel_err(got, ref) <= TOL[dtype]
+    check(got, ref, dtype)
 
 
 @pytest.mark.parametrize("m,n,k,epi", [(8184, 8168, 2048, "none"), (8184, 8168, 2048, "bias_gelu"),
@@ -107,7 +107,7 @@ def test_linear_large_tiles_on_sampled_rows(B, m, n, k, epi):
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out.float()).all())
     got = host(out[torch.from_numpy(rows).cuda()])
-    assert rel_err(got, ref) <= TOL["bf16"]
+    check(got, ref, "bf16")
 
 
 @pytest.mark.parametrize("dtype,m,n,k,split", [("bf16", 384, 256, 128, 128), ("bf16", 200, 96, 64, 0),
@@ -126,8 +126,8 @@ def test_linear_strided_store(B, dtype, m, n, k, split):
     B.ac_op_linear(da, dw, out if split else None, bias=dbias, out_t=out_t, n_split=split, t_s2=1, t_s3=m)
     torch.cuda.synchronize()
     if split:
-        assert rel_err(host(out)[:, :split], ref[:, :split]) <= TOL[dtype]
-    assert rel_err(host(out_t), ref[:, split:].T) <= TOL[dtype]
+        check(host(out)[:, :split], ref[:, :split], dtype)
+    check(host(out_t), ref[:, split:].T, dtype)
     # periodic form: m = p * P + r  ->  out_t[p][n][r]
     if m % 50 == 0:
         P = 50
@@ -136,7 +136,7 @@ def test_linear_strided_store(B, dtype, m, n, k, split):
                        t_period=P, t_s1=(n - split) * P, t_s2=1, t_s3=P)
         torch.cuda.synchronize()
         want = ref[:, split:].reshape(m // P, P, n - split).transpose(0, 2, 1)
-        assert rel_err(host(out_p), want) <= TOL[dtype]
+        check(host(out_p), want, dtype)
 
 
 def _attn_case(B, dtype, sq, sk, heads, dh, causal, q_offset, use_bias, use_gate, v_t, n_splits=1):
@@ -232,16 +232,16 @@ def test_elementwise(B, dtype, rows, cols):
                     (B.AC_ACT_SIGMOID, lambda t: 1 / (1 + np.exp(-t))), (B.AC_ACT_NONE, lambda t: t)):
         B.ac_op_bias_act(dx, dbias, y, act)
         torch.cuda.synchronize()
-        assert rel_err(host(y), fn(x.astype(np.float64) + bias)) <= TOL[dtype]
+        check(host(y), fn(x.astype(np.float64) + bias), dtype)
     B.ac_op_bias_act(dx, None, y, B.AC_ACT_GELU_ERF)
     torch.cuda.synchronize()
-    assert rel_err(host(y), O.gelu_erf(x)) <= TOL[dtype]
+    check(host(y), O.gelu_erf(x), dtype)
     B.ac_op_binary(dx, dr, y, 0)
     torch.cuda.synchronize()
-    assert rel_err(host(y), x.astype(np.float64) + r) <= TOL[dtype]
+    check(host(y), x.astype(np.float64) + r, dtype)
     B.ac_op_binary(dx, dr, y, 1)
     torch.cuda.synchronize()
-    assert rel_err(host(y), x.astype(np.float64) * r) <= TOL[dtype]
+    check(host(y), x.astype(np.float64) * r, dtype)
 
 
 def test_bf16_store_rounds_to_nearest_even(B):
@@ -281,7 +281,7 @@ def test_softmax_rows(B, dtype, rows, cols, period, q_offset, causal):
         z = np.where(np.arange(cols)[None, :] <= pos[:, None], z, -np.inf)
     ref = O.softmax_rows(z)
     got = host(p)
-    assert rel_err(got, ref) <= TOL[dtype]
+    check(got, ref, dtype)
     assert (got[ref == 0] == 0).all()
     B.ac_op_softmax_rows(ds, ds, scale, causal=causal, q_offset=q_offset, period=period)
     torch.cuda.synchronize()

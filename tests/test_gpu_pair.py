@@ -5,7 +5,7 @@ import pytest
 from oracle import pairstack as P
 from oracle import transformer as O
 from paper_2401_10652_amd import inputs as I
-from util import TOL, draw, host, rel_err
+from util import TOL, check, draw, host, rel_err
 
 pytestmark = pytest.mark.gpu
 CANARY = 0x5A
@@ -29,7 +29,7 @@ def test_triangle_contract(B, dtype, ch, ni, nj, nk):
     B.ac_op_triangle_contract(B.to_device(a, dtype), B.to_device(b, dtype), out)
     torch.cuda.synchronize()
     ref = np.einsum("cik,cjk->cij", a.astype(np.float64), b.astype(np.float64))
-    assert rel_err(host(out), ref) <= TOL[dtype]
+    check(host(out), ref, dtype)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -55,7 +55,7 @@ def test_layernorm_channel_major(B, dtype, ch, pos):
                      dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
     B.ac_op_layernorm_channel_major(B.to_device(x, dtype), B.to_device(g, dtype), B.to_device(b, dtype), dst)
     torch.cuda.synchronize()
-    assert rel_err(host(dst), O.layer_norm(x.T, g, b)) <= TOL[dtype]
+    check(host(dst), O.layer_norm(x.T, g, b), dtype)
 
 
 def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, flags=0):
@@ -93,7 +93,7 @@ def test_pair_block_chunked_equals_oracle(B, dtype, n, cz, ch, heads, dh):
         if ref is None:
             ref = P.pair_block(z, w, heads, cfg.activation, cfg.ln_eps)
         assert np.isfinite(host(y)).all()
-        assert rel_err(host(y), ref) <= TOL[dtype], chunk
+        check(host(y), ref, dtype, what=str(chunk))
         outs.append(y)
     for y in outs[1:]:
         assert torch.equal(y, outs[0])

@@ -168,9 +168,65 @@ def expect(status, fn):
     assert B.lib().ac_last_error() != b""
 
 
-def test_budget_sizes_the_chunk_lengths():
+def test_budget_bounds_the_executor_bytes():
+    """Reading: the budget is the paper's memory_budget (section 3.2) applied to what the executor
+    really holds, mem(X) + mem(Y) + the workspace's high-water mark.  The fused attention keeps no
+    scores in memory, so C2 at 1 GiB and C5 at 4 GiB run every region as one segment."""
+    for cfg, budget in ((I.C2, 1 * GIB), (I.C5, 4 * GIB)):
+        info = B.Plan(B.transformer_desc(cfg), regions(0, 0, 0, c_out=0), budget).ac_plan_query()
+        assert [r.n_segments for r in info.regions[:4]] == [1, 1, 1, 1]
+        assert info.peak_bytes_planned == info.peak_bytes_unchunked_planned <= budget
+    # C5, 3 GiB: only the feed-forward region (LayerNorm output + hidden tensor of a segment on
+    # top of the whole tensors) exceeds it; it gets the largest multiple of 128 rows that fits
+    e = 2
+    S, d, F = I.C5.seq, I.C5.d_model, I.C5.d_ffn
+    whole = 2 * S * d * e + 6 * S * d * e          # x, y; q, k, v, context, h, inter-layer buffer
+    info3 = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0, c_out=0), 3 * GIB).ac_plan_query()
+    fits = lambda c: whole + c * (d + F) * e <= 3 * GIB
+    assert [r.n_segments for r in info3.regions[:3]] == [1, 1, 1]
+    assert info3.regions[3].chunk_len == M.largest_chunk_len(S, 128, fits) == 52352
+    assert info3.peak_bytes_planned <= 3 * GIB < info3.peak_bytes_unchunked_planned
+    assert info3.peak_bytes_planned == arena_by_hand(I.C5, S, S, 52352, c_out=S) + 2 * S * d * e
+    # one granule more would not fit
+    over = B.Plan(B.transformer_desc(I.C5), regions(S, S, 52352 + 128, c_out=S)).ac_plan_query()
+    assert over.peak_bytes_planned > 3 * GIB
+    # an explicit length that does not fit is an error, as is a budget below the whole tensors
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, S, c_out=0), 3 * GIB))
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0, c_out=0), 2 * GIB))
+    # two segments in flight: the budget bounds the doubled per-segment sets too
+    info2 = B.Plan(B.transformer_desc(I.C5, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(0, 0, 0, c_out=0),
+                   3 * GIB).ac_plan_query()
+    assert info2.peak_bytes_planned <= 3 * GIB and info2.regions[3].chunk_len <= 52352 // 2 + 128
+
+
+def test_budget_sizes_batch_chunks():
+    """Batch chunks are sized in whole batch elements (granule 1), with and without stored scores."""
+    cfg = I.TransformerConfig("b8", 91, 2, 1024, 1024, 16, 4096, True, "bf16", 0.02, batch=8)
+    kinds = (B.AC_REGION_QKV, B.AC_REGION_ATTENTION, B.AC_REGION_OUT_PROJ, B.AC_REGION_FFN)
+    regs = [(k, B.AC_DIM_BATCH, 0) for k in kinds]
+    for flags, budget in ((B.AC_FLAG_MATERIALIZED_SCORES, 400000000), (0, 200000000),
+                          (B.AC_FLAG_MATERIALIZED_SCORES | B.AC_FLAG_BUDGET_PAPER_MODEL, 400000000)):
+        info = B.Plan(B.transformer_desc(cfg, flags=flags), regs, budget).ac_plan_query()
+        assert info.peak_bytes_planned <= budget < info.peak_bytes_unchunked_planned
+        assert any(1 <= r.chunk_len < 8 for r in info.regions[:4])
+        # the lengths chosen are the largest that fit: one more batch element in the region that
+        # holds the peak does not
+        worst = max(range(4), key=lambda i: B.Plan(
+            B.transformer_desc(cfg, flags=flags & ~B.AC_FLAG_BUDGET_PAPER_MODEL),
+            [(k, B.AC_DIM_BATCH, info.regions[j].chunk_len if j == i else 8) for j, k in enumerate(kinds)]
+        ).ac_plan_query().peak_bytes_planned)
+        r = info.regions[worst]
+        if r.chunk_len < 8 and not flags & B.AC_FLAG_BUDGET_PAPER_MODEL:
+            more = [(k, B.AC_DIM_BATCH, info.regions[j].chunk_len + (1 if j == worst else 0)) for j, k in enumerate(kinds)]
+            assert B.Plan(B.transformer_desc(cfg, flags=flags), more).ac_plan_query().peak_bytes_planned > budget
+
+
+def test_budget_under_the_paper_model_sizes_the_chunk_lengths():
+    """AC_FLAG_BUDGET_PAPER_MODEL: the budget also bounds the bytes the two activation equations give
+    for the unfused graph of a region (scores and probabilities stored)."""
+    pm = B.AC_FLAG_BUDGET_PAPER_MODEL
     # C2, 1 GiB: only the attention region exceeds it; largest multiple of 128 that fits is 1792
-    p = B.Plan(B.transformer_desc(I.C2), regions(0, 0, 0), 1 * GIB)
+    p = B.Plan(B.transformer_desc(I.C2, flags=pm), regions(0, 0, 0), 1 * GIB)
     info = p.ac_plan_query()
     e = 2
     fits = lambda c: M.attention_region(8192, 1024, 16, e, c) <= GIB
@@ -181,20 +237,20 @@ def test_budget_sizes_the_chunk_lengths():
     assert info.peak_bytes_planned <= GIB
     # C5, 4 GiB: attention gets 640 rows, the other regions fit whole (multi-stage: each
     # region is sized on its own until the layer's peak is under the budget)
-    info5 = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 4 * GIB).ac_plan_query()
+    info5 = B.Plan(B.transformer_desc(I.C5, flags=pm), regions(0, 0, 0), 4 * GIB).ac_plan_query()
     fits5 = lambda c: M.attention_region(65536, 2048, 16, e, c) <= 4 * GIB
     assert info5.regions[1].chunk_len == M.largest_chunk_len(65536, 128, fits5) == 640
     assert info5.regions[1].n_segments == 103
     assert info5.peak_bytes_model <= 4 * GIB and info5.peak_bytes_planned <= 4 * GIB
     # a tighter budget makes the feed-forward chunk too
     tight = 5 * GIB // 2
-    info5b = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), tight).ac_plan_query()
+    info5b = B.Plan(B.transformer_desc(I.C5, flags=pm), regions(0, 0, 0), tight).ac_plan_query()
     assert info5b.regions[3].chunk_len < 65536 and info5b.regions[1].chunk_len == 256
     for r in info5b.regions[:4]:
         assert r.model_bytes <= tight
     assert info5b.peak_bytes_planned <= tight
     # at 2 GiB the whole tensors of the executor alone (x, y, q, k, v, context, h, t: 8 x 256 MiB) do not fit
-    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 2 * GIB))
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5, flags=pm), regions(0, 0, 0), 2 * GIB))
     # monotone: more segments never need more bytes
     prev = None
     for c in (8192, 4096, 1024, 256, 64):
@@ -227,7 +283,8 @@ def test_legality_and_errors():
     expect(B.AC_ERR_ARG, lambda: B.Plan(bad))
     # the floor of the second activation equation: whole tensors alone exceed the budget
     expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0), 1 * GIB))
-    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C2), regions(0, 4096, 0, c_out=0), 1 * GIB))
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C2, flags=B.AC_FLAG_BUDGET_PAPER_MODEL),
+                                                      regions(0, 4096, 0, c_out=0), 1 * GIB))
     # chunk_len larger than the extent means one segment
     info = B.Plan(d, regions(10 ** 9, 10 ** 9, 10 ** 9)).ac_plan_query()
     assert all(r.n_segments == 1 for r in info.regions[:4])

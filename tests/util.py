@@ -11,6 +11,28 @@ def rel_err(got, ref):
     return float(np.abs(got - ref).max() / (denom if denom > 0 else 1.0))
 
 
+def mixed_err(got, ref, rtol):
+    """Largest |got - ref| / (rtol |ref| + rtol RMS(ref)) over the elements: <= 1 means every
+    element is within rtol of its own magnitude plus rtol of the tensor's typical magnitude.
+    (A purely elementwise relative error is meaningless at the zero crossings of an N(0, .)
+    output, and a purely global one lets a small element be far off; this gate sits between.)"""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    den = rtol * np.abs(ref) + rtol * (rms if rms > 0 else 1.0)
+    return float((np.abs(got - ref) / den).max()) if ref.size else 0.0
+
+
+def check(got, ref, dtype, what="", mixed_factor=1.0):
+    """The parity bar of a single kernel or short chain: both gates at the dtype's tolerance.
+    Returns (global relative error, mixed-gate ratio)."""
+    tol = TOL[dtype]
+    e, m = rel_err(got, ref), mixed_err(got, ref, tol)
+    assert e <= tol, f"{what}: max|d|/max|ref| = {e:.3e} > {tol}"
+    assert m <= mixed_factor, f"{what}: mixed gate ratio {m:.3f} > {mixed_factor} (rtol {tol})"
+    return e, m
+
+
 def host(t):
     """Device tensor -> fp64 numpy."""
     return t.detach().float().cpu().numpy().astype(np.float64)
