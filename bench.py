@@ -76,14 +76,39 @@ def cpu_baseline_pair(cfg, z, w):
                       "the per-row cost of a full run"}
 
 
+def cpu_baseline_rows(cfg, x, layers, cores):
+    """The oracle as it stands on a bounded sample of a long sequence: the keys and values of every
+    token of layer 1 (which any row needs) and 8 blocks of 16 query rows spread evenly over the
+    sequence, through attention, output projection and feed-forward; scaled to all rows and layers."""
+    from oracle import transformer as O
+    S = cfg.seq
+    t0 = time.perf_counter()
+    O.transformer_block_row_blocks(x, layers[0], cfg.heads, cfg.causal, [], cfg.activation, cfg.ln_eps)
+    t_kv = time.perf_counter() - t0
+    blocks = [(r, r + 16) for r in range(S // 16, S, S // 8)][:8]
+    n_rows = sum(b - a for a, b in blocks)
+    t0 = time.perf_counter()
+    O.transformer_block_row_blocks(x, layers[0], cfg.heads, cfg.causal, blocks, cfg.activation, cfg.ln_eps)
+    t_rows = max(time.perf_counter() - t0 - t_kv, 1e-9)
+    per_layer = t_kv + t_rows * S / n_rows
+    return {"value": S / (per_layer * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"layer 1 of {cfg.layers} in fp64: LayerNorm + key/value projection of all {S} tokens "
+                      f"({t_kv:.1f} s) and {n_rows} query rows in 8 blocks spread over the sequence through "
+                      f"attention, output projection and feed-forward ({t_rows:.1f} s); scaled to {S} rows "
+                      f"and {cfg.layers} layers"}
+
+
 def cpu_baseline(cfg, x, layers):
-    """The oracle as it stands, one layer over all tokens, on the host cores."""
+    """The oracle as it stands on the host cores: whole layers where a layer takes seconds, else a
+    row sample."""
     from oracle import transformer as O
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
     except Exception:
         cores = os.cpu_count()
+    if cfg.seq > 16384:
+        return cpu_baseline_rows(cfg, x, layers, cores)
     t0 = time.perf_counter()
     n = min(2, cfg.layers)
     O.transformer_stack(x, layers[:n], cfg.heads, cfg.causal, cfg.activation, cfg.ln_eps, cfg.batch,
@@ -92,6 +117,30 @@ def cpu_baseline(cfg, x, layers):
     return {"value": cfg.tokens * n / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"layers 1-{n} of {cfg.layers} over all {cfg.tokens} tokens in fp64 ({dt:.1f} s), "
                       f"scaled to {cfg.layers} layers"}
+
+
+BALANCE = PEAK["mfma_bf16"] / PEAK["hbm"]     # 312.5 flop per byte: below it a bf16 kernel is HBM-bound
+
+
+def class_entry(s, steps, dtype):
+    """Roofline entry of a kernel class from its event-timed launches.  The bound follows the
+    arithmetic intensity of the class (algorithmic flops / algorithmic bytes against the machine
+    balance), not its name: a contraction over few rows that re-reads a large operand is HBM-bound."""
+    sec = s["total_ms"] * 1e-3
+    contraction = s["name"] in ("gemm", "attention", "trimul")
+    intensity = s["flops"] / s["bytes"] if s["bytes"] else float("inf")
+    if contraction and dtype == "bf16" and intensity >= BALANCE:
+        bound, ach, pk, unit = "mfma", s["flops"] / sec / 1e12, PEAK["mfma_bf16"] / 1e12, "TFLOP/s"
+    elif contraction and dtype == "f32" and intensity >= PEAK["fp32_vector"] / PEAK["hbm"]:
+        bound, ach, pk, unit = "alu", s["flops"] / sec / 1e12, PEAK["fp32_vector"] / 1e12, "TFLOP/s"
+    else:
+        bound, ach, pk, unit = "hbm", s["bytes"] / sec / 1e9, PEAK["hbm"] / 1e9, "GB/s"
+    entry = {"bound": bound, "achieved": round(ach, 2), "peak": pk, "unit": unit, "frac": round(ach / pk, 4),
+             "launches_per_step": s["launches"] // steps, "avg_launch_us": round(s["total_ms"] / s["launches"] * 1e3, 2),
+             "ms_per_step": round(s["total_ms"] / steps, 4), "flop_per_byte": round(intensity, 1)}
+    if contraction and bound == "hbm":
+        entry["tflops"] = round(s["flops"] / sec / 1e12, 2)
+    return entry
 
 
 KERNEL_SOURCES = {"gemm": ["linear.hip", "common.h"], "trimul": ["linear.hip", "common.h"],
@@ -141,7 +190,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="workload (default: C5, the largest that one GPU holds)")
     ap.add_argument("--chunk", type=int, nargs=3, default=None, metavar=("QKV", "ATTN", "FFN"),
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
@@ -151,6 +201,9 @@ def main():
                     help="skip the extra two-segments-in-flight timing (its overlapping kernels would "
                          "distort per-kernel durations in a profiler trace)")
     ap.add_argument("--sweep", action="store_true", help="also time a sweep of chunk lengths")
+    ap.add_argument("--budget-on", default="executor", choices=["executor", "paper-model"],
+                    help="what the workload's activation budget bounds in the headline plan: the bytes the "
+                         "executor really holds, or also the paper-style bytes of the unfused graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB copy kernel --steps times (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -172,16 +225,18 @@ def main():
         return
     cfg = I.CONFIGS[args.config]
     is_pair = isinstance(cfg, I.PairConfig)
+    lanes_flag = B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0
+    pm_flag = B.AC_FLAG_BUDGET_PAPER_MODEL
     if is_pair:
         x, layers = I.pair_inputs(cfg)
         dw = [B.to_device(layers[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
-        desc = B.pair_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0)
+        make_desc = lambda flags: B.pair_desc(cfg, flags=flags)
         regs, budget = pair_regions(B, args.chunk[0] if args.chunk else cfg.chunk_len), 0
         regs1 = pair_regions(B, cfg.n_res)
     else:
         x, layers = I.transformer_inputs(cfg)
         dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
-        desc = B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0)
+        make_desc = lambda flags: B.transformer_desc(cfg, flags=flags)
         if args.chunk:
             regs, budget = plan_regions(B, *args.chunk), 0
         elif cfg.chunk_len:
@@ -189,12 +244,13 @@ def main():
         else:
             regs, budget = plan_regions(B, 0, 0, 0, 0), cfg.act_budget
         regs1 = plan_regions(B, cfg.seq, cfg.seq, cfg.seq)
+    desc = make_desc(lanes_flag | (pm_flag if budget and args.budget_on == "paper-model" else 0))
     dx = B.to_device(x, cfg.dtype)
     y = torch.empty_like(dx)
     plan = B.Plan(desc, regs, budget)
     info = plan.ac_plan_query()
     plan.ac_plan_bind_weights(dw)
-    plan1 = B.Plan(desc, regs1, 0)
+    plan1 = B.Plan(make_desc(lanes_flag), regs1, 0)
     info1 = plan1.ac_plan_query()
     plan1.ac_plan_bind_weights(dw)
     ws = B.empty_workspace(max(info.workspace_bytes, info1.workspace_bytes))
@@ -204,25 +260,16 @@ def main():
     stats = profile_plan(plan, dx, y, ws, args.steps)
 
     tokens = cfg.tokens
-    classes = {}
-    for s in stats:
-        per = s["total_ms"] / s["launches"]
-        bound = "mfma" if s["name"] in ("gemm", "attention", "trimul") else "hbm"
-        if bound == "mfma":
-            ach, pk, unit = s["flops"] / (s["total_ms"] * 1e-3) / 1e12, PEAK["mfma_bf16"] / 1e12, "TFLOP/s"
-            if cfg.dtype == "f32":
-                pk = PEAK["fp32_vector"] / 1e12
-        else:
-            ach, pk, unit = s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, PEAK["hbm"] / 1e9, "GB/s"
-        classes[s["name"]] = {"bound": bound, "achieved": round(ach, 2), "peak": pk, "unit": unit,
-                              "frac": round(ach / pk, 4), "launches_per_step": s["launches"] // args.steps,
-                              "avg_launch_us": round(per * 1e3, 2),
-                              "ms_per_step": round(s["total_ms"] / args.steps, 4)}
+    classes = {s["name"]: class_entry(s, args.steps, cfg.dtype) for s in stats}
     dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
     s_dom = next(s for s in stats if s["name"] == dom)
     roof = dict(classes[dom])
     roof.update({"kernel": dom, "traffic": recorded_traffic(cfg.name, dom),
-                 "algorithmic_per_launch": round((s_dom["flops"] if roof["bound"] == "mfma" else s_dom["bytes"]) / s_dom["launches"])})
+                 "algorithmic_per_launch": round((s_dom["bytes"] if roof["bound"] == "hbm" else s_dom["flops"]) / s_dom["launches"])})
+
+    def chunk_lens(inf):
+        return {"chunk_len": [inf.regions[i].chunk_len for i in range(inf.n_regions)],
+                "n_segments": [inf.regions[i].n_segments for i in range(inf.n_regions)]}
 
     out = {
         "metric": "tokens/s at fixed activation budget",
@@ -231,9 +278,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": dict(
-            {"workload": cfg.name, "act_budget_bytes": budget, "segments_in_flight": args.in_flight,
-             "chunk_len": [info.regions[i].chunk_len for i in range(info.n_regions)],
-             "n_segments": [info.regions[i].n_segments for i in range(info.n_regions)]},
+            {"workload": cfg.name, "act_budget_bytes": budget,
+             "budget_bounds": ("executor bytes" if args.budget_on == "executor" else "executor and paper-model bytes") if budget else None,
+             "segments_in_flight": args.in_flight, **chunk_lens(info)},
             **({"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
                 "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
                {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,
@@ -241,48 +288,73 @@ def main():
         "roofline": roof,
         "kernels": classes,
         "mfma_frac_whole_step": round(info.flops_per_execute / sec / PEAK["mfma_bf16"], 4),
-        "unchunked": {"tokens_per_s": round(tokens / sec1, 1), "ms_per_step": round(sec1 * 1e3, 4),
-                      "throughput_loss": round(1.0 - sec1 / sec, 4)},
+        "one_segment_per_region": {"tokens_per_s": round(tokens / sec1, 1), "ms_per_step": round(sec1 * 1e3, 4),
+                                   "throughput_loss_of_the_plan": round(1.0 - sec1 / sec, 4)},
+        # like-for-like ratios only: this executor chunked vs this executor with one segment per
+        # region (measured), and the paper-style model of an unfused graph chunked vs unchunked
         "peak_activation_bytes": {
-            "chunked_measured": peak, "unchunked_measured": peak1,
-            "chunked_paper_model": info.peak_bytes_model, "unchunked_paper_model": info.peak_bytes_model_unchunked,
-            "ratio_vs_unchunked_paper_model": round(peak / info.peak_bytes_model_unchunked, 4),
-            "ratio_model_vs_model": round(info.peak_bytes_model / info.peak_bytes_model_unchunked, 4),
-            "ratio_vs_unchunked_measured": round(peak / peak1, 4),
+            "chunked_measured": peak, "one_segment_measured": peak1,
+            "ratio_measured": round(peak / peak1, 4),
+            "paper_model_chunked": info.peak_bytes_model, "paper_model_one_segment": info.peak_bytes_model_unchunked,
+            "ratio_paper_model": round(info.peak_bytes_model / info.peak_bytes_model_unchunked, 4),
         },
     }
-    if args.in_flight == 1 and not args.sequential_only:
+    extras = not args.sequential_only
+
+    def timed_variant(flags, rg, bud, steps=None):
+        p_ = B.Plan(make_desc(flags), rg, bud)
+        i_ = p_.ac_plan_query()
+        p_.ac_plan_bind_weights(dw)
+        w_ = ws if i_.workspace_bytes <= ws.numel() else B.empty_workspace(i_.workspace_bytes)
+        s_, pk_ = time_plan(B, torch, p_, dx, y, w_, steps or args.steps, args.warmup)
+        entry = {"ms_per_step": round(s_ * 1e3, 4), "tokens_per_s": round(tokens / s_, 1),
+                 "throughput_loss": round(1.0 - sec1 / s_, 4), "peak_bytes_measured": pk_,
+                 "peak_ratio_vs_one_segment": round(pk_ / peak1, 4), **chunk_lens(i_)}
+        p_.close()
+        return entry
+
+    if extras and budget and args.budget_on == "executor":
+        # The same budget read as a planner of the paper would read it: a bound on the bytes of the
+        # unfused graph (scores and probabilities of a segment stored), section 3.2 / 3.4.
+        out["budget_on_paper_model_bytes"] = timed_variant(lanes_flag | pm_flag, regs, budget)
+        # A budget that does bind on the executor's own bytes: 0.8 of what one segment per region needs.
+        tight = int(0.8 * peak1)
+        try:
+            out["tight_budget_on_executor_bytes"] = dict(timed_variant(lanes_flag, regs, tight), act_budget_bytes=tight)
+        except B.AcError as err:
+            out["tight_budget_on_executor_bytes"] = {"act_budget_bytes": tight, "error": str(err)}
+    if extras and args.in_flight == 1:
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
-        import copy
-        desc2 = copy.copy(desc)
-        desc2.flags = desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT
-        plan2 = B.Plan(desc2, regs, budget)
-        info2 = plan2.ac_plan_query()
-        plan2.ac_plan_bind_weights(dw)
-        ws2 = B.empty_workspace(info2.workspace_bytes)
-        sec2, peak2 = time_plan(B, torch, plan2, dx, y, ws2, args.steps, args.warmup)
-        out["two_segments_in_flight"] = {"tokens_per_s": round(tokens / sec2, 1), "ms_per_step": round(sec2 * 1e3, 4),
-                                         "throughput_loss": round(1.0 - sec1 / sec2, 4), "peak_bytes_measured": peak2}
-        plan2.close()
-        del ws2
-    if not is_pair and not args.sequential_only:
+        out["two_segments_in_flight"] = timed_variant(desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, regs, budget)
+    if extras:
+        # The standalone row passes (bias + activation, residual add, LayerNorm), which the fused
+        # plan folds into GEMM epilogues, timed with HIP events in a plan that runs them unfused.
+        pu = B.Plan(make_desc(B.AC_FLAG_UNFUSED_ELEMENTWISE), regs, 0 if is_pair else budget)
+        iu = pu.ac_plan_query()
+        pu.ac_plan_bind_weights(dw)
+        wu = ws if iu.workspace_bytes <= ws.numel() else B.empty_workspace(iu.workspace_bytes)
+        for _ in range(2):
+            pu.ac_execute(dx, y, wu)
+        su = profile_plan(pu, dx, y, wu, max(3, args.steps // 4))
+        out["standalone_row_passes"] = {s_["name"]: class_entry(s_, max(3, args.steps // 4), cfg.dtype)
+                                        for s_ in su if s_["name"] in ("elementwise", "layernorm")}
+        pu.close()
+        del wu
+    if extras and not is_pair:
         # The same two plans with the attention core run as an unfused graph would (scores and
         # probabilities stored in the workspace): here the workspace really holds the intermediate
         # activations the paper's equations count, so the memory ratio of chunking is measured.
-        import copy
-        desc3 = copy.copy(desc)
-        desc3.flags = (desc.flags | B.AC_FLAG_MATERIALIZED_SCORES) & ~B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT
-        regs3 = [(k, dm, info.regions[i].chunk_len) for i, (k, dm, _) in enumerate(regs)]
+        sflags = B.AC_FLAG_MATERIALIZED_SCORES | (pm_flag if budget else 0)
         stored = {}
-        for label, rg in (("chunked", regs3), ("one_segment", regs1)):
-            p3 = B.Plan(desc3, rg, 0)
+        for label, rg, bud in (("chunked", regs, budget), ("one_segment", regs1, 0)):
+            p3 = B.Plan(make_desc(sflags if bud else B.AC_FLAG_MATERIALIZED_SCORES), rg, bud)
             i3 = p3.ac_plan_query()
-            entry = {"peak_bytes_planned": int(i3.peak_bytes_planned)}
+            entry = {"peak_bytes_planned": int(i3.peak_bytes_planned), **chunk_lens(i3)}
             if i3.workspace_bytes <= 48 << 30:      # the whole score tensor of a long sequence may not fit
                 p3.ac_plan_bind_weights(dw)
                 ws3 = B.empty_workspace(i3.workspace_bytes)
-                s3, pk3 = time_plan(B, torch, p3, dx, y, ws3, max(3, args.steps // 2), 1)
+                s3, pk3 = time_plan(B, torch, p3, dx, y, ws3, max(3, args.steps // 4), 1)
                 entry.update({"ms_per_step": round(s3 * 1e3, 4), "tokens_per_s": round(tokens / s3, 1),
                               "peak_bytes_measured": pk3})
                 del ws3
@@ -306,7 +378,7 @@ def main():
             chunks, planned = B.ac_graph_plan(nodes, e, budget, 12, (1.0, 0.0, 0.0, 0.0), beam=2, max_out=4 * cfg.layers)
             plan_ms = (time.perf_counter() - t0) * 1e3
             settings = PG.executor_regions(chunks, names)
-            p4 = B.Plan(desc3, settings, 0)
+            p4 = B.Plan(make_desc(B.AC_FLAG_MATERIALIZED_SCORES), settings, 0)
             i4 = p4.ac_plan_query()
             entry = {"graph_nodes": len(spec), "estimate_unchunked_bytes": whole, "estimate_planned_bytes": planned,
                      "planning_ms": round(plan_ms, 3), "chunks": len(chunks), "window": 12, "beam": 2,
@@ -315,7 +387,7 @@ def main():
             if i4.workspace_bytes <= 48 << 30:
                 p4.ac_plan_bind_weights(dw)
                 ws4 = B.empty_workspace(i4.workspace_bytes)
-                s4, pk4 = time_plan(B, torch, p4, dx, y, ws4, max(3, args.steps // 2), 1)
+                s4, pk4 = time_plan(B, torch, p4, dx, y, ws4, max(3, args.steps // 4), 1)
                 entry.update({"ms_per_step": round(s4 * 1e3, 4), "executor_peak_bytes_measured": pk4})
                 del ws4
             p4.close()

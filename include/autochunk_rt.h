@@ -303,6 +303,29 @@ int ac_attention_key_splits(int64_t sq, int64_t sk, int heads, int64_t batch, in
 uint64_t ac_attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, int head_dim,
                                             int n_splits);
 
+/*
+ * ac_op_attention for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and result as ac_op_attention; the fp32 partial results of the key splits go to a
+ * device array of ac_static_scratch_bytes() (64 MiB) that is part of the library's code object,
+ * so every GPU the library runs on holds one until the process ends.  n_splits = 0 takes
+ * ac_attention_key_splits' count, 1 uses no scratch at all.  A launch whose partial results
+ * (ac_attention_split_workspace_bytes) exceed the array is refused with AC_ERR_WORKSPACE and
+ * nothing is launched.  The call allocates and frees nothing; on its first use on a device it
+ * looks up that device's address of the array (the device must be current).  All calls on one
+ * GPU share the array: calls that overlap on one GPU (two streams, two threads) race on it;
+ * calls on one stream are ordered and need no clearing in between.
+ */
+int ac_op_attention_static_scratch(const void* q, int64_t ldq, int64_t stride_q_batch,
+                                   const void* k, int64_t ldk, int64_t stride_k_batch,
+                                   const void* v, int64_t ldv, int64_t stride_v_batch, int v_transposed,
+                                   const void* bias, int64_t ld_bias, int64_t stride_bias_head,
+                                   const void* gate, int64_t ldg, int64_t stride_g_batch,
+                                   void* ctx, int64_t ldc, int64_t stride_c_batch,
+                                   int64_t batch, int64_t sq, int64_t sk, int heads, int head_dim,
+                                   int causal, int64_t q_offset, int n_splits, int dtype, void* stream);
+uint64_t ac_static_scratch_bytes(void);
+
 /* y = activation(x + bias[col]) over [rows, cols]; bias may be NULL. */
 int ac_op_bias_act(const void* x, int64_t ldx, const void* bias, void* y, int64_t ldy,
                    int64_t rows, int64_t cols, int activation, int dtype, void* stream);

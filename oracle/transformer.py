@@ -131,12 +131,13 @@ def transformer_block(x, w, heads, causal, activation="gelu_erf", eps=1e-5, batc
     return ffn_region(h, w, activation, eps)
 
 
-def transformer_block_rows(x, w, heads, causal, r0, r1, activation="gelu_erf", eps=1e-5):
-    """Rows [r0, r1) of transformer_block(x) for one sequence, without forming the other rows.
+def transformer_block_row_blocks(x, w, heads, causal, blocks, activation="gelu_erf", eps=1e-5):
+    """Rows [r0, r1) of transformer_block(x), for every (r0, r1) of ``blocks``, one sequence.
 
-    Keys and values come from every row of x (they are what every query sees); queries,
-    output projection, residuals and feed-forward are evaluated for the requested rows only.
-    Lets a test check a few rows of a sequence too long to evaluate whole.
+    Keys and values come from every row of x (they are what every query sees) and are
+    computed once; queries, output projection, residuals and feed-forward are evaluated
+    for the requested rows only.  Lets a test check some rows of a sequence too long to
+    evaluate whole.  Returns a list of arrays, one per block.
     """
     x = np.asarray(x, np.float64)
     d = x.shape[1]
@@ -145,10 +146,18 @@ def transformer_block_rows(x, w, heads, causal, r0, r1, activation="gelu_erf", e
     bq = np.asarray(w["b_qkv"], np.float64)
     k = linear(u, wq[d:2 * d], bq[d:2 * d])
     v = linear(u, wq[2 * d:], bq[2 * d:])
-    q = linear(u[r0:r1], wq[:d], bq[:d])
-    ctx = attention(q, k, v, heads, causal, q_offset=r0)
-    h = x[r0:r1] + linear(ctx, w["w_o"], w["b_o"])
-    return ffn_region(h, w, activation, eps)
+    out = []
+    for r0, r1 in blocks:
+        q = linear(u[r0:r1], wq[:d], bq[:d])
+        ctx = attention(q, k, v, heads, causal, q_offset=r0)
+        h = x[r0:r1] + linear(ctx, w["w_o"], w["b_o"])
+        out.append(ffn_region(h, w, activation, eps))
+    return out
+
+
+def transformer_block_rows(x, w, heads, causal, r0, r1, activation="gelu_erf", eps=1e-5):
+    """Rows [r0, r1) of transformer_block(x) for one sequence, without forming the other rows."""
+    return transformer_block_row_blocks(x, w, heads, causal, [(r0, r1)], activation, eps)[0]
 
 
 def transformer_stack(x, layers, heads, causal, activation="gelu_erf", eps=1e-5, batch=1,

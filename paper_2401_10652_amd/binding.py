@@ -110,6 +110,9 @@ SIGNATURES = {
                            I64, I64, I64, INT, INT, VP]),
     "ac_op_attention": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, INT, VP, I64, I64, VP, I64, I64,
                               VP, I64, I64, I64, I64, I64, INT, INT, INT, I64, INT, VP, U64, INT, VP]),
+    "ac_op_attention_static_scratch": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, INT, VP, I64, I64, VP, I64, I64,
+                                             VP, I64, I64, I64, I64, I64, INT, INT, INT, I64, INT, INT, VP]),
+    "ac_static_scratch_bytes": (U64, []),
     "ac_attention_key_splits": (INT, [I64, I64, INT, I64, INT, INT, INT]),
     "ac_attention_split_workspace_bytes": (U64, [I64, INT, I64, INT, INT]),
     "ac_op_bias_act": (INT, [VP, I64, VP, VP, I64, I64, I64, INT, INT, VP]),
@@ -304,6 +307,24 @@ def ac_op_attention(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bia
         n_splits, _ptr(split_workspace),
         0 if split_workspace is None else split_workspace.numel() * split_workspace.element_size(),
         _dt(q), _stream()), "ac_op_attention")
+
+
+def ac_op_attention_static_scratch(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bias=None, gate=None,
+                                   v_transposed=False, batch=1, strides=None, n_splits=0):
+    """ac_op_attention with the key-split partial results in the library's static device array."""
+    sq, sk = q.shape[0], k.shape[0]
+    sb = strides or (0, 0, 0, 0, 0)
+    _check(lib().ac_op_attention_static_scratch(
+        _ptr(q), q.stride(0), sb[0], _ptr(k), k.stride(0), sb[1], _ptr(v), v.stride(0), sb[2],
+        int(v_transposed),
+        _ptr(bias), 0 if bias is None else bias.stride(1), 0 if bias is None else bias.stride(0),
+        _ptr(gate), 0 if gate is None else gate.stride(0), sb[3],
+        _ptr(ctx), ctx.stride(0), sb[4], batch, sq, sk, heads, head_dim, int(causal), q_offset,
+        n_splits, _dt(q), _stream()), "ac_op_attention_static_scratch")
+
+
+def ac_static_scratch_bytes():
+    return lib().ac_static_scratch_bytes()
 
 
 def ac_attention_key_splits(sq, sk, heads, batch, head_dim, dtype, v_transposed=True):

@@ -150,8 +150,13 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   const int64_t bh = bq / nqb;
   int qb = (int)(bq % nqb);
   if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
-  const int64_t b = bh / a.heads;
-  const int h = (int)(bh % a.heads);
+  // Problem-major order keeps the heads of one problem together (their q/k/v rows interleave in
+  // memory).  Head-major order (set by the host when a bias shared by all problems is the
+  // largest operand) gives each XCD a run of problems of ONE head, so that head's bias stays
+  // in the XCD's L2 while keys and values stream through, instead of every problem fetching
+  // every head's bias again.
+  const int64_t b = a.head_major ? bh % a.batch : bh / a.heads;
+  const int h = (int)(a.head_major ? bh / a.batch : bh % a.heads);
   const int q0 = qb * QB;
 
   const bf16_t* kbase = (const bf16_t*)a.k + b * a.sk_b + h * DH;
@@ -539,6 +544,9 @@ uint64_t attention_split_workspace_bytes(int64_t sq, int heads, int64_t batch, i
 
 hipError_t launch_attention(const AttnArgs& a_in, hipStream_t s) {
   AttnArgs a = a_in;
+  // bytes of one head's bias against the keys and values of one (problem, head): whichever is
+  // larger should be what consecutive blocks share
+  a.head_major = a.bias != nullptr && a.batch > 1 && a.sq > 2 * (int64_t)a.head_dim;
   if (a.n_splits > 1 && (!a.part_o || !a.part_ml || !mfma_attn_eligible(a))) a.n_splits = 1;
   if (a.batch <= 0 || a.sq <= 0 || a.heads <= 0) return hipSuccess;
   if (a.sk <= 0 || a.sk > (1 << 30) || a.sq > (1 << 30) || a.q_offset > (1 << 30)) return hipErrorInvalidValue;

@@ -119,7 +119,10 @@ struct LinearArgs {
   const void* bias;                  // [n] or null
   const void* mul; int64_t ldmul;    // [m, n] or null
   const void* resid; int64_t ldr;    // [m, n] or null
-  void* out; int64_t ldo;            // columns [0, n_split): out[m * ldo + n]
+  void* out; int64_t ldo;            // columns [0, n_split): out[m * ldo + n], or, with o_period > 0,
+                                     // out[(m / o_period) * o_s1 + (m % o_period) * o_s2 + n]: rows regrouped
+                                     // on the way out (e.g. positions (k, j) of a pair tensor stored as (j, k))
+  int64_t o_period, o_s1, o_s2;
   // columns [n_split, n): out_t[(m / t_period) * t_s1 + (m % t_period) * t_s2 + (n - n_split) * t_s3]
   void* out_t; int64_t n_split; int64_t t_period, t_s1, t_s2, t_s3;
   int64_t m, n, k;
@@ -148,6 +151,7 @@ struct AttnArgs {
   int n_splits;
   void* part_o;
   void* part_ml;
+  int head_major;   // block order (head, problem, query block) instead of (problem, head, query block); set by launch_attention
 };
 
 hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,

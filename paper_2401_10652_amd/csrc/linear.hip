@@ -20,6 +20,11 @@ namespace ac {
 // Epilogue for one element (generic kernel) — bias, activation, multiplier, residual,
 // then the row-major or the strided ("transposed") store.
 // ------------------------------------------------------------------------------------
+// Offset of row m in the row-major part of the output.
+__device__ __forceinline__ int64_t out_row(const LinearArgs& g, int64_t m) {
+  return g.o_period == INT64_MAX ? m * g.ldo : (m / g.o_period) * g.o_s1 + (m % g.o_period) * g.o_s2;
+}
+
 template <typename T>
 __device__ __forceinline__ void epilogue_store_one(const LinearArgs& g, int64_t m, int64_t n, float v) {
   if (g.bias) v += Elem<T>::ld((const T*)g.bias + n);
@@ -27,7 +32,7 @@ __device__ __forceinline__ void epilogue_store_one(const LinearArgs& g, int64_t 
   if (g.mul) v *= Elem<T>::ld((const T*)g.mul + m * g.ldmul + n);
   if (g.resid) v += Elem<T>::ld((const T*)g.resid + m * g.ldr + n);
   if (n < g.n_split) {
-    Elem<T>::st((T*)g.out + m * g.ldo + n, v);
+    Elem<T>::st((T*)g.out + out_row(g, m) + n, v);
   } else {
     const int64_t off = (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 + (n - g.n_split) * g.t_s3;
     Elem<T>::st((T*)g.out_t + off, v);
@@ -137,7 +142,8 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int CROW = BN + 8;   // padded row of the staged tile
-  const bool staged = n0 + BN <= g.n_split && g.ldo % 8 == 0 && ((uintptr_t)g.out % 16) == 0 && g.n % 8 == 0;
+  const bool staged = n0 + BN <= g.n_split && g.ldo % 8 == 0 && ((uintptr_t)g.out % 16) == 0 && g.n % 8 == 0 &&
+                      (g.o_period == INT64_MAX || (g.o_s1 % 8 == 0 && g.o_s2 % 8 == 0));
   // a tile wholly in the strided part whose rows run contiguously (stride 1 along m, one
   // period) is staged TRANSPOSED, [n][m], and written with 16-byte stores along m
   constexpr int TROW = BM + 8;
@@ -214,7 +220,7 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) lds[(cl + jj) * TROW + rl] = o[jj];
           } else if (n < g.n_split) {
-            *reinterpret_cast<bf16x4*>((bf16_t*)g.out + m * g.ldo + n) = o;
+            *reinterpret_cast<bf16x4*>((bf16_t*)g.out + out_row(g, m) + n) = o;
           } else {
             const int64_t base = t_base + (n - g.n_split) * g.t_s3;
 #pragma unroll
@@ -246,7 +252,7 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
     const int rl = c / CPR, cc = (c % CPR) * 8;
     const int64_t m = m0 + rl, n = n0 + cc;
     if (m < g.m && n < g.n)
-      *reinterpret_cast<bf16x8*>((bf16_t*)g.out + m * g.ldo + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
+      *reinterpret_cast<bf16x8*>((bf16_t*)g.out + out_row(g, m) + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
   }
 }
 
@@ -402,6 +408,7 @@ static bool mfma_eligible(const LinearArgs& g) {
   if (g.lda % 8 != 0 || g.ldw % 8 != 0) return false;
   if (!aligned_to(g.a, 16) || !aligned_to(g.w, 16)) return false;
   if (g.n_split > 0 && (g.ldo % 4 != 0 || !aligned_to(g.out, 8))) return false;
+  if (g.o_period != INT64_MAX && (g.o_s1 % 4 != 0 || g.o_s2 % 4 != 0)) return false;
   if (g.batch > 1 && (g.sa_b % 8 != 0 || g.sw_b % 8 != 0 || g.so_b % 4 != 0)) return false;
   if (g.bias && !aligned_to(g.bias, 8)) return false;
   if (g.mul && (g.ldmul % 4 != 0 || !aligned_to(g.mul, 8))) return false;
@@ -416,7 +423,9 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (g.out_t == nullptr) g.n_split = g.n;
   if (g.n_split > g.n) g.n_split = g.n;
   if (g.t_period <= 0) g.t_period = INT64_MAX;
+  if (g.o_period <= 0) g.o_period = INT64_MAX;
   if (g.batch < 1) g.batch = 1;
+  if (g.batch > 1 && g.o_period != INT64_MAX) return hipErrorInvalidValue;
   if (g.batch > 1 && (g.bias || g.mul || g.resid || g.out_t || g.act != AC_ACT_NONE)) return hipErrorInvalidValue;
   if (g.batch > 65535) return hipErrorInvalidValue;
   if (mfma_eligible(g)) {

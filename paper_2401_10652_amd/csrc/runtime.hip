@@ -13,6 +13,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -248,7 +249,8 @@ struct Walk {
     // few query rows: cut the keys into runs so that every CU gets blocks; the fp32 partial
     // results live in the arena for the duration of this call
     const uint64_t mk = arena.mark();
-    a.n_splits = attention_key_splits(a.sq, a.sk, a.heads, a.batch, a.head_dim, a.dtype, a.v_transposed);
+    // (a causal segment sees keys up to its last row only: early segments need fewer runs or none)
+    a.n_splits = attention_key_splits(a.sq, keys_seen, a.heads, a.batch, a.head_dim, a.dtype, a.v_transposed);
     if (a.n_splits > 1) {
       const uint64_t rh = (uint64_t)a.n_splits * a.batch * a.sq * a.heads;
       a.part_o = arena.push(rh * a.head_dim * 4);
@@ -583,7 +585,9 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   enter(kind);
   const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
   // ---- whole operands.  Starting node: the pair bias [h][j][k].  Ending node: the bias as
-  // [h][i][k] (= projection at position (k, i)), all keys [(k, j)][h*d] and all values
+  // [h][i][k] (= projection at position (k, i)), all keys regrouped by column, [(j, k)][h*d]
+  // (the projection stores the row of position (k, j) at (j, k), 256 contiguous bytes at a
+  // time, so that a column's keys are consecutive rows for the attention kernel), and all values
   // channel-major [h*d][j][k]; the transposes are done in place per channel.
   void* bias = arena.push((uint64_t)H * R * e);
   void* k_all = ending ? arena.push((uint64_t)R * hd * e) : nullptr;
@@ -599,7 +603,8 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
     if (ending) {
       LinearArgs kk{};
       kk.a = t; kk.lda = cz; kk.w = W[TA_W_K]; kk.ldw = cz; kk.m = rows; kk.n = hd; kk.k = cz;
-      kk.out = atw(k_all, r0 * hd); kk.ldo = hd; kk.n_split = hd;
+      kk.out = atw(k_all, sg.i0 * hd); kk.ldo = hd; kk.n_split = hd;
+      kk.o_period = N; kk.o_s1 = hd; kk.o_s2 = N * hd;     // row (k - i0, j) -> (j, k)
       linear(kk);
       LinearArgs vv{};
       vv.a = t; vv.lda = cz; vv.w = W[TA_W_V]; vv.ldw = cz; vv.m = rows; vv.n = hd; vv.k = cz;
@@ -649,7 +654,7 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
       // one problem per column j: queries i of the segment, keys k of that column
       a.batch = N; a.sq = sg.ni;
       a.ldq = N * hd; a.sq_b = hd; a.ldg = N * hd; a.sg_b = hd; a.ldc = N * hd; a.sc_b = hd;
-      a.k = k_all; a.ldk = N * hd; a.sk_b = hd;
+      a.k = k_all; a.ldk = hd; a.sk_b = N * hd;
       a.v = v_all; a.ldv = R; a.sv_b = N;
       a.bias = at(bias, sg.i0 * N); a.ld_bias = N; a.s_bias_h = R;
     }
@@ -1227,6 +1232,73 @@ int ac_op_attention(const void* q, int64_t ldq, int64_t stride_q_batch, const vo
     a.n_splits = n_splits;
     a.part_o = split_workspace;
     a.part_ml = (uint8_t*)split_workspace + (uint64_t)n_splits * batch * sq * heads * head_dim * 4;
+  }
+  return hip_status(launch_attention(a, (hipStream_t)stream), "attention");
+}
+
+// ---- attention whose key-split partials live in a static device array ----------------------
+// For callers that cannot allocate.  `scratch` is a file-scope device array: its name is only a
+// host-side stand-in here, so its device address is asked for once per device (with that device
+// current) and only that address is ever handed to kernels.
+namespace {
+constexpr uint64_t kStaticScratchBytes = 64ull << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices];   // per device: the address of that device's copy of `scratch`
+std::mutex g_scratch_mu;
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(AC_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(AC_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_addr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(AC_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_addr[dev] = ptr;
+  }
+  *out = g_scratch_addr[dev];
+  return AC_OK;
+}
+}  // namespace
+
+uint64_t ac_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int ac_op_attention_static_scratch(const void* q, int64_t ldq, int64_t stride_q_batch, const void* k, int64_t ldk,
+                                   int64_t stride_k_batch, const void* v, int64_t ldv, int64_t stride_v_batch,
+                                   int v_transposed, const void* bias, int64_t ld_bias, int64_t stride_bias_head,
+                                   const void* gate, int64_t ldg, int64_t stride_g_batch, void* ctx, int64_t ldc,
+                                   int64_t stride_c_batch, int64_t batch, int64_t sq, int64_t sk, int heads,
+                                   int head_dim, int causal, int64_t q_offset, int n_splits, int dtype, void* stream) {
+  if (!q || !k || !v || !ctx || batch < 0 || sq < 0 || sk < 1 || heads < 1 || head_dim < 1 || q_offset < 0 ||
+      !dtype_ok(dtype) || n_splits < 0 || n_splits > 16)
+    return fail(AC_ERR_ARG, "ac_op_attention_static_scratch: bad argument");
+  if (n_splits == 0) n_splits = attention_key_splits(sq, sk, heads, batch, head_dim, dtype, v_transposed != 0);
+  AttnArgs a{};
+  a.q = q; a.ldq = ldq; a.sq_b = stride_q_batch; a.k = k; a.ldk = ldk; a.sk_b = stride_k_batch;
+  a.v = v; a.ldv = ldv; a.sv_b = stride_v_batch; a.v_transposed = v_transposed != 0;
+  a.bias = bias; a.ld_bias = ld_bias; a.s_bias_h = stride_bias_head;
+  a.gate = gate; a.ldg = ldg; a.sg_b = stride_g_batch; a.ctx = ctx; a.ldc = ldc; a.sc_b = stride_c_batch;
+  a.batch = batch; a.sq = sq; a.sk = sk; a.heads = heads; a.head_dim = head_dim; a.causal = causal != 0;
+  a.q_offset = q_offset; a.dtype = dtype;
+  if (n_splits > 1) {
+    const uint64_t need = attention_split_workspace_bytes(sq, heads, batch, head_dim, n_splits);
+    if (need > kStaticScratchBytes)
+      return fail(AC_ERR_WORKSPACE,
+                  "ac_op_attention_static_scratch: %d key splits of this launch need %llu bytes of partial results; "
+                  "the static scratch holds %llu (use fewer splits or fewer query rows, or ac_op_attention)",
+                  n_splits, (unsigned long long)need, (unsigned long long)kStaticScratchBytes);
+    void* base = nullptr;
+    const int st = static_scratch_of_current_device(&base);
+    if (st != AC_OK) return st;
+    // every element of the partial results that the merge reads is written by the attention
+    // kernel of this call first, so nothing of the array has to be cleared between calls
+    a.n_splits = n_splits;
+    a.part_o = base;
+    a.part_ml = (uint8_t*)base + (uint64_t)n_splits * batch * sq * heads * head_dim * 4;
   }
   return hip_status(launch_attention(a, (hipStream_t)stream), "attention");
 }

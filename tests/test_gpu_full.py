@@ -1,9 +1,14 @@
-"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+"""Parity at the full sizes of the five workloads, in the launch configurations bench.py times.
 
-C1-C3: the whole stack against the whole fp64 oracle.  C4: each pair-stack module at
-N_res = 1024 against oracle rows evaluated one by one, and the whole block chunked vs
-unchunked.  C5: one layer at S = 65536 against oracle row blocks, and the two-layer stack
-chunked two ways (properties that hold at any size: finite, equal to rounding for every chunk length).
+C1-C3: the whole stack against the whole fp64 oracle (C3 also layer by layer).  C4: the pair
+block at N_res = 1024 link by link: each module runs on the device output of the module before
+it and is compared, on 64 output rows spread over all 16 segments, with the oracle fed that same
+device output; the chain equals the block run as one plan bit for bit; plus a whole block at
+N_res = 256 against the whole oracle.  C5 (S = 65536): layer 1 against 1024 oracle rows that lie
+at the start, on both sides of two segment boundaries and at the end; layer 2 of the two-layer
+stack against the oracle's layer 2 evaluated on the device's own layer-1 output (read back; the
+fp64 oracle cannot carry 65536 x 2048 activations through two full layers in a test's time, and
+feeding it the device's layer-1 output isolates layer 2 exactly as the chain of C4 does).
 """
 import dataclasses
 
@@ -13,7 +18,7 @@ import pytest
 from oracle import pairstack as P
 from oracle import transformer as O
 from paper_2401_10652_amd import inputs as I
-from util import TOL, host, rel_err
+from util import TOL, check, host, mixed_err, rel_err
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
@@ -30,14 +35,15 @@ def tregions(B, c):
             (B.AC_REGION_OUT_PROJ, B.AC_DIM_SEQ, c[3] if len(c) > 3 else c[1]), (B.AC_REGION_FFN, B.AC_DIM_SEQ, c[2])]
 
 
-def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None):
+def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None, flags=0, dx=None):
     import torch
-    dx = B.to_device(x, cfg.dtype)
+    if dx is None:
+        dx = B.to_device(x, cfg.dtype)
     if dw is None:
         dw = [B.to_device(w[n], cfg.dtype) for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
-    p = B.Plan(B.transformer_desc(cfg), regs, budget)
+    p = B.Plan(B.transformer_desc(cfg, flags=flags), regs, budget)
     info = p.ac_plan_query()
-    p.ac_plan_bind_weights(dw)
+    p.ac_plan_bind_weights(dw[:12 * cfg.layers])
     ws = B.empty_workspace(info.workspace_bytes)
     y = torch.full_like(dx, float("nan"))
     peak = p.ac_execute(dx, y, ws)
@@ -47,60 +53,152 @@ def run_transformer(B, cfg, x, layers, regs, budget=0, dw=None):
     return y, info, dw
 
 
+def report(name, got, ref, dtype="bf16"):
+    """Both gates at the dtype's tolerance, printed; returns (global, mixed)."""
+    e, m = rel_err(got, ref), mixed_err(got, ref, TOL[dtype])
+    print(f"{name}: max|d|/max|ref| = {e:.3e}, mixed-gate ratio = {m:.3f}", flush=True)
+    return e, m
+
+
 def test_c2_gpt_full_stack(B):
     cfg = I.C2
     x, layers = I.transformer_inputs(cfg)
-    y, info, dw = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget)
+    ref = O.transformer_stack(x, layers, cfg.heads, True, query_block=1024)
+    # the workload's plan: 1 GiB per layer bounds what the executor holds; everything fits whole
+    y0, info0, dw = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget)
+    assert [r.n_segments for r in info0.regions[:4]] == [1, 1, 1, 1] and info0.peak_bytes_planned <= cfg.act_budget
+    e, m = report("C2 one segment per region", host(y0), ref)
+    assert e <= TOL["bf16"] and m <= 1.0
+    # the same budget applied to the paper-style bytes of the unfused graph: attention in 5 segments
+    y, info, _ = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget, dw=dw,
+                                 flags=B.AC_FLAG_BUDGET_PAPER_MODEL)
     assert info.regions[1].chunk_len == 1792 and info.peak_bytes_model <= cfg.act_budget
     assert [r.n_segments for r in info.regions[:4]] == [1, 5, 1, 1]
-    ref = O.transformer_stack(x, layers, cfg.heads, True, query_block=1024)
-    err = rel_err(host(y), ref)
-    print("C2 rel err", err)
-    assert err <= TOL["bf16"]
+    e, m = report("C2 attention in 5 segments", host(y), ref)
+    assert e <= TOL["bf16"] and m <= 1.0
     # another chunking cuts the keys of the attention launches differently (key splits), so the
-    # two results agree to rounding, not bitwise
+    # results agree to rounding, not bitwise
     y2, _, _ = run_transformer(B, cfg, x, layers, tregions(B, (1024, 1024, 1024)), dw=dw)
-    assert rel_err(host(y2), ref) <= TOL["bf16"]
+    e, m = report("C2 every region in 8 segments", host(y2), ref)
+    assert e <= TOL["bf16"] and m <= 1.0
     assert rel_err(host(y2), host(y)) <= 0.5 * TOL["bf16"]
+    assert rel_err(host(y0), host(y)) <= 0.5 * TOL["bf16"]
 
 
 def test_c3_vit_full_stack(B):
+    """The 12-layer stack against the oracle, and where its error comes from: the device run cut
+    after k layers against the oracle after k layers (what accumulates in the stream), and layer k
+    alone on the oracle's layer k-1 output rounded to storage (what one layer adds)."""
     cfg = I.C3
     x, layers = I.transformer_inputs(cfg)
-    y, info, _ = run_transformer(B, cfg, x, layers, tregions(B, (512, 512, 512)))
+    refs = [np.asarray(x, np.float64)]
+    for w in layers:
+        refs.append(O.transformer_block(refs[-1], w, cfg.heads, False, query_block=1024))
+    y, info, dw = run_transformer(B, cfg, x, layers, tregions(B, (512, 512, 512)))
     assert [r.n_segments for r in info.regions[:4]] == [8, 8, 8, 8]
-    ref = O.transformer_stack(x, layers, cfg.heads, False, query_block=1024)
-    err = rel_err(host(y), ref)
-    print("C3 rel err", err)
-    assert err <= TOL["bf16"]
+    e, m = report("C3 12 layers", host(y), refs[-1])
+    assert e <= TOL["bf16"]
+    # reading of the bar for a deep stack: the global gate is the stated one; the mixed gate is
+    # asserted at the tolerance for every prefix of up to 4 layers and reported beyond
+    for k in (1, 2, 4, 8, 12):
+        ck = dataclasses.replace(cfg, layers=k)
+        yk, _, _ = run_transformer(B, ck, x, layers[:k], tregions(B, (512, 512, 512)), dw=dw)
+        ek, mk = report(f"C3 first {k} layers", host(yk), refs[k])
+        assert ek <= TOL["bf16"]
+        if k <= 4:
+            assert mk <= 1.0
+    c1 = dataclasses.replace(cfg, layers=1)
+    for k in (1, 6, 12):
+        xin = I.round_to_storage(refs[k - 1], "bf16")
+        y1, _, _ = run_transformer(B, c1, xin, [layers[k - 1]], tregions(B, (512, 512, 512)), dw=dw[12 * (k - 1):12 * k])
+        check(host(y1), O.transformer_block(xin, layers[k - 1], cfg.heads, False, query_block=1024), "bf16",
+              what=f"C3 layer {k} alone")
 
 
-def test_c5_long_context(B):
+# ---------------------------------------------------------------------------------------
+# C5
+# ---------------------------------------------------------------------------------------
+# 1024 rows: the first 128, 192 on each side of the boundaries 51 * 640 and 102 * 640 of the
+# 640-row plan (the second also straddles a boundary of the 2048- and 8192-row plans' last
+# segments), and the last 128.
+C5_BLOCKS = [(0, 128), (32640 - 192, 32640 + 192), (65280 - 192, 65280 + 192), (65536 - 128, 65536)]
+
+
+@pytest.fixture(scope="module")
+def c5(B):
+    x, layers = I.transformer_inputs(I.C5)
+    dw = [B.to_device(w[n], "bf16") for w in layers for n in I.TRANSFORMER_LAYER_TENSORS]
+    return {"x": x, "layers": layers, "dw": dw, "dx": B.to_device(x, "bf16")}
+
+
+def check_blocks(name, y, refs, blocks=C5_BLOCKS):
+    scale = float(y.float().abs().max())
+    worst = 0.0
+    for (r0, r1), ref in zip(blocks, refs):
+        got = host(y[r0:r1])
+        err = np.abs(got - ref).max() / max(scale, np.abs(ref).max())
+        m = mixed_err(got, ref, TOL["bf16"])
+        print(f"{name} rows [{r0}, {r1}): max|d|/max|ref| = {err:.3e}, mixed-gate ratio = {m:.3f}", flush=True)
+        assert err <= TOL["bf16"] and m <= 1.0, (name, r0, r1)
+        worst = max(worst, err)
+    return worst
+
+
+def test_c5_layer_1(B, c5):
     import torch
     cfg1 = dataclasses.replace(I.C5, layers=1)
-    x, layers = I.transformer_inputs(cfg1)
-    y, info, dw = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0, 0)), I.C5.act_budget)
+    x, layers, dw, dx = c5["x"], c5["layers"], c5["dw"], c5["dx"]
+    refs = O.transformer_block_row_blocks(x, layers[0], cfg1.heads, True, C5_BLOCKS)
+    # 4 GiB on the paper-style bytes: the attention core in 103 segments of 640 rows
+    y, info, _ = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0, 0)), I.C5.act_budget, dw=dw, dx=dx,
+                                 flags=B.AC_FLAG_BUDGET_PAPER_MODEL)
     assert info.regions[1].chunk_len == 640 and info.regions[1].n_segments == 103
-    got = host(y)
-    assert np.isfinite(got).all()
-    scale = np.abs(got).max()
-    # row blocks: the first rows, both sides of a segment boundary (640 * 51 = 32640), the last rows
-    for r0, r1 in ((0, 64), (32608, 32672), (65472, 65536)):
-        ref = O.transformer_block_rows(x, layers[0], cfg1.heads, True, r0, r1)
-        err = np.abs(got[r0:r1] - ref).max() / max(scale, np.abs(ref).max())
-        print("C5 rows", r0, r1, "rel err", err)
-        assert err <= TOL["bf16"]
-    del got
-    # two layers, budget plan vs another chunking: identical bits
+    assert bool(torch.isfinite(y.float()).all())
+    check_blocks("C5 layer 1, attention 103 x 640", y, refs)
+    c5["y1"] = y
+    # multi-stage plan with explicit lengths: projections and feed-forward in 8192-row segments,
+    # attention in 2048-row segments
+    yb, infb, _ = run_transformer(B, cfg1, x, layers, tregions(B, (8192, 2048, 8192, 8192)), dw=dw, dx=dx)
+    assert [r.n_segments for r in infb.regions[:4]] == [8, 32, 8, 8]
+    check_blocks("C5 layer 1, 8192 / 2048 / 8192", yb, refs)
+    assert rel_err(host(yb[65000:]), host(y[65000:])) <= 0.5 * TOL["bf16"]   # key splits differ: equal to rounding
+    # 4 GiB on the executor's own bytes: one segment per region
+    yc, infc, _ = run_transformer(B, cfg1, x, layers, tregions(B, (0, 0, 0, 0)), I.C5.act_budget, dw=dw, dx=dx)
+    assert [r.n_segments for r in infc.regions[:4]] == [1, 1, 1, 1]
+    check_blocks("C5 layer 1, one segment per region", yc, refs)
+
+
+def test_c5_layer_2_on_the_device_output_of_layer_1(B, c5):
+    import torch
     cfg = I.C5
-    x2, layers2 = I.transformer_inputs(cfg)
-    ya, infa, dw2 = run_transformer(B, cfg, x2, layers2, tregions(B, (0, 0, 0, 0)), cfg.act_budget)
-    yb, _, _ = run_transformer(B, cfg, x2, layers2, tregions(B, (8192, 2048, 4096)), dw=dw2)
+    x, layers, dw, dx = c5["x"], c5["layers"], c5["dw"], c5["dx"]
+    pm = B.AC_FLAG_BUDGET_PAPER_MODEL
+    if "y1" not in c5:
+        c5["y1"], _, _ = run_transformer(B, dataclasses.replace(cfg, layers=1), x, layers, tregions(B, (0, 0, 0, 0)),
+                                         cfg.act_budget, dw=dw, dx=dx, flags=pm)
+    # the same plan over both layers: its first layer runs the launches that produced y1
+    ya, infa, _ = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget, dw=dw, dx=dx, flags=pm)
+    assert infa.regions[1].n_segments == 103 and infa.peak_bytes_planned <= cfg.act_budget
     assert bool(torch.isfinite(ya.float()).all())
-    assert rel_err(host(yb), host(ya)) <= 0.5 * TOL["bf16"]   # key splits differ: equal to rounding
-    assert infa.peak_bytes_planned <= cfg.act_budget
+    y1 = host(c5["y1"])
+    refs = O.transformer_block_row_blocks(y1, layers[1], cfg.heads, True, C5_BLOCKS)
+    del y1
+    check_blocks("C5 layer 2 (103 x 640) on the device's layer 1", ya, refs)
+    # a multi-stage plan over both layers against the same rows: its layer 1 differs from y1 only by
+    # the rounding order of the key splits, which the looser factor below allows for
+    yb, _, _ = run_transformer(B, cfg, x, layers, tregions(B, (8192, 2048, 4096, 8192)), dw=dw, dx=dx)
+    assert rel_err(host(yb[:4096]), host(ya[:4096])) <= 0.5 * TOL["bf16"]
+    assert rel_err(host(yb[61440:]), host(ya[61440:])) <= 0.5 * TOL["bf16"]
+    check_blocks("C5 layer 2 (8192 / 2048 / 4096)", yb, refs)
+    # and the plan the 4 GiB budget gives on the executor's own bytes
+    yc, infc, _ = run_transformer(B, cfg, x, layers, tregions(B, (0, 0, 0, 0)), cfg.act_budget, dw=dw, dx=dx)
+    assert infc.peak_bytes_planned <= cfg.act_budget
+    check_blocks("C5 layer 2 (budget on executor bytes)", yc, refs)
 
 
+# ---------------------------------------------------------------------------------------
+# C4
+# ---------------------------------------------------------------------------------------
 def run_pair(B, cfg, z, w, kinds, chunk, flags=0, dz=None, dw=None):
     import torch
     if dz is None:
@@ -119,25 +217,35 @@ def run_pair(B, cfg, z, w, kinds, chunk, flags=0, dz=None, dw=None):
     return y, info, dz, dw
 
 
-def test_c4_pair_modules_full_size(B):
+def test_c4_pair_block_link_by_link(B):
     import torch
     cfg = I.C4
     z, w = I.pair_inputs(cfg)
-    rows = np.array([0, 63, 64, 517, 1023])
-    dz = dw = None
+    n, c = cfg.n_res, cfg.chunk_len
+    # first and last row of each of the 16 segments, and 32 more rows drawn with a fixed seed
+    edge = np.concatenate([np.arange(0, n, c), np.arange(c - 1, n, c)])
+    rest = np.setdiff1d(np.arange(n), edge)
+    rows = np.sort(np.concatenate([edge, np.random.default_rng(4).choice(rest, 32, replace=False)]))
+    assert len(rows) == 64
+    rows_dev = torch.as_tensor(rows, device="cuda")
+    dw = None
+    cur = B.to_device(z, cfg.dtype)
+    cur_host = np.asarray(z, np.float64)
     for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
-        y, info, dz, dw = run_pair(B, cfg, z, w, [k], cfg.chunk_len, flags=B.AC_FLAG_LISTED_REGIONS_ONLY,
-                                   dz=dz, dw=dw)
-        got = host(y[torch.as_tensor(rows, device="cuda")])
-        ref = P.pair_module(name, z, w, cfg.heads, cfg.activation, cfg.ln_eps, rows=rows)
-        err = rel_err(got, ref)
-        print("C4", name, "rel err", err)
-        assert err <= TOL["bf16"], name
+        y, info, _, dw = run_pair(B, cfg, None, w, [k], c, flags=B.AC_FLAG_LISTED_REGIONS_ONLY, dz=cur, dw=dw)
+        assert info.regions[k - B.AC_REGION_TRIMUL_OUT].n_segments == 16
         assert bool(torch.isfinite(y.float()).all())
+        ref = P.pair_module(name, cur_host, w, cfg.heads, cfg.activation, cfg.ln_eps, rows=rows)
+        e, m = report(f"C4 {name} on the device output before it, 64 rows", host(y[rows_dev]), ref)
+        assert e <= TOL["bf16"] and m <= 1.0, name
+        cur = y
+        cur_host = host(y)
+    del cur_host
     kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
-    ya, infa, _, _ = run_pair(B, cfg, z, w, kinds, cfg.chunk_len, dz=dz, dw=dw)
-    yb, infb, _, _ = run_pair(B, cfg, z, w, kinds, cfg.n_res, dz=dz, dw=dw)
-    assert torch.equal(ya, yb) and bool(torch.isfinite(ya.float()).all())
+    ya, infa, dz, _ = run_pair(B, cfg, z, w, kinds, c, dw=dw)
+    assert torch.equal(ya, cur)          # the chain of single-module plans is the block
+    yb, infb, _, _ = run_pair(B, cfg, z, w, kinds, n, dz=dz, dw=dw)
+    assert torch.equal(ya, yb)           # and the chunk length does not change a bit
     assert infa.peak_bytes_planned < infb.peak_bytes_planned
 
 
@@ -147,6 +255,5 @@ def test_c4_pair_block_half_size_against_whole_oracle(B):
     kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
     y, _, _, _ = run_pair(B, cfg, z, w, kinds, 64)
     ref = P.pair_block(z, w, cfg.heads, cfg.activation, cfg.ln_eps)
-    err = rel_err(host(y), ref)
-    print("C4 block N=256 rel err", err)
-    assert err <= TOL["bf16"]
+    e, m = report("C4 block N=256", host(y), ref)
+    assert e <= TOL["bf16"] and m <= 1.0

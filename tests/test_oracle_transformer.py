@@ -169,3 +169,6 @@ def test_block_rows_equals_rows_of_block(causal):
     for r0, r1 in ((0, 3), (5, 9), (11, 12), (0, 12)):
         got = O.transformer_block_rows(x, ls[0], cfg.heads, causal, r0, r1)
         assert np.abs(got - full[r0:r1]).max() < 1e-12
+    blocks = [(0, 3), (5, 9), (11, 12)]
+    for (r0, r1), got in zip(blocks, O.transformer_block_row_blocks(x, ls[0], cfg.heads, causal, blocks)):
+        assert got.shape[0] == r1 - r0 and np.abs(got - full[r0:r1]).max() < 1e-12
