@@ -266,6 +266,34 @@ int ac_op_linear(const void* a, int64_t lda, const void* w, int64_t ldw, const v
                  void* stream);
 
 /*
+ * LayerNorm of `rows` short rows (k = 64 or 128 columns, bf16) followed by up to 5 projections of
+ * the normalised rows t = LN(x), in one kernel: t never reaches memory.  The pair-stack modules
+ * project each LayerNorm output several times (gated operands a and b of the triangle update;
+ * q, k, v, gate and pair bias of the triangle attention; the transition's first layer); as separate
+ * launches each would re-read t.  Part p computes
+ *   plain:  out = activation(t w^T + bias)                      (w [n, k], bias [n] or NULL)
+ *   gated:  out = sigmoid(t w_gate^T + bias_gate) * (t w^T + bias)   (the gate stays in registers)
+ * and stores it either row-major, out[row_offset(m) + col] with row_offset(m) = m * ldo or, if
+ * o_period > 0, (m / o_period) * o_s1 + (m % o_period) * o_s2 (rows regrouped on the way out), or,
+ * if out_t != NULL, strided like ac_op_linear's second output:
+ *   out_t[(m / t_period) * t_s1 + (m % t_period) * t_s2 + col * t_s3]   (t_period <= 0: no period).
+ * n must be a multiple of 4.  Shapes outside these return AC_ERR_UNSUPPORTED (use ac_op_layernorm
+ * and ac_op_linear).  A row's result does not depend on which launch or block computes it.
+ */
+typedef struct ac_proj_part {
+  const void* w; const void* bias;
+  const void* w_gate; const void* bias_gate;
+  int32_t gated;            /* 1: gated pair */
+  int32_t activation;       /* ac_activation of a plain part */
+  int64_t n;
+  void* out; int64_t ldo, o_period, o_s1, o_s2;
+  void* out_t; int64_t t_period, t_s1, t_s2, t_s3;
+} ac_proj_part;
+int ac_op_ln_linear(const void* x, int64_t ldx, const void* gain, const void* shift, float eps,
+                    int64_t rows, int64_t k, const ac_proj_part* parts, int n_parts, int dtype,
+                    void* stream);
+
+/*
  * Attention of `sq` query rows over `sk` keys, `heads` heads of `head_dim`, `batch`
  * independent problems: ctx = softmax(q k^T / sqrt(head_dim) + bias [causal mask]) v
  * [* gate].  q/k/v/ctx/gate rows of one problem are ld* apart, heads are contiguous

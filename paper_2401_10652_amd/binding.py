@@ -65,6 +65,14 @@ class ac_weight_info(C.Structure):
                 ("dtype", C.c_int32), ("index", C.c_int32)]
 
 
+class ac_proj_part(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("bias", C.c_void_p), ("w_gate", C.c_void_p), ("bias_gate", C.c_void_p),
+                ("gated", C.c_int32), ("activation", C.c_int32), ("n", C.c_int64),
+                ("out", C.c_void_p), ("ldo", C.c_int64), ("o_period", C.c_int64), ("o_s1", C.c_int64),
+                ("o_s2", C.c_int64), ("out_t", C.c_void_p), ("t_period", C.c_int64), ("t_s1", C.c_int64),
+                ("t_s2", C.c_int64), ("t_s3", C.c_int64)]
+
+
 class ac_kernel_stat(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("total_ms", C.c_double),
                 ("flops", C.c_double), ("bytes", C.c_double)]
@@ -106,6 +114,7 @@ SIGNATURES = {
     "ac_status_string": (C.c_char_p, [INT]),
     "ac_last_error": (C.c_char_p, []),
     "ac_op_layernorm": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
+    "ac_op_ln_linear": (INT, [VP, I64, VP, VP, C.c_float, I64, I64, C.POINTER(ac_proj_part), INT, INT, VP]),
     "ac_op_linear": (INT, [VP, I64, VP, I64, VP, VP, I64, VP, I64, VP, I64, VP, I64, I64, I64, I64, I64,
                            I64, I64, I64, INT, INT, VP]),
     "ac_op_attention": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, INT, VP, I64, I64, VP, I64, I64,
@@ -290,6 +299,28 @@ def ac_op_linear(a, w, out, bias=None, mul=None, residual=None, activation=AC_AC
         _ptr(out), 0 if out is None else out.stride(0),
         _ptr(out_t), n_split, t_period, t_s1, t_s2, t_s3, m, n, k, activation, _dt(a), _stream()),
         "ac_op_linear")
+
+
+def ac_op_ln_linear(x, gain, shift, parts, eps=1e-5):
+    """parts: dicts with w, n (default w.shape[0]) and either out (row-major tensor, optional o_period / o_s1 /
+    o_s2) or out_t (+ t_period, t_s1, t_s2, t_s3); optional bias, activation, w_gate, bias_gate."""
+    arr = (ac_proj_part * len(parts))()
+    for i, d in enumerate(parts):
+        a = arr[i]
+        addr = lambda t: None if t is None else t.data_ptr()
+        a.w, a.bias = addr(d["w"]), addr(d.get("bias"))
+        a.w_gate, a.bias_gate = addr(d.get("w_gate")), addr(d.get("bias_gate"))
+        a.gated = int(d.get("w_gate") is not None)
+        a.activation = d.get("activation", AC_ACT_NONE)
+        a.n = d.get("n", d["w"].shape[0])
+        out = d.get("out")
+        a.out = addr(out)
+        a.ldo = 0 if out is None else d.get("ldo", out.stride(0))
+        a.o_period, a.o_s1, a.o_s2 = d.get("o_period", 0), d.get("o_s1", 0), d.get("o_s2", 0)
+        a.out_t = addr(d.get("out_t"))
+        a.t_period, a.t_s1, a.t_s2, a.t_s3 = d.get("t_period", 0), d.get("t_s1", 0), d.get("t_s2", 0), d.get("t_s3", 0)
+    _check(lib().ac_op_ln_linear(_ptr(x), x.stride(0), _ptr(gain), _ptr(shift), eps, x.shape[0], x.shape[1],
+                                 arr, len(parts), _dt(x), _stream()), "ac_op_ln_linear")
 
 
 def ac_op_attention(q, k, v, ctx, heads, head_dim, causal=False, q_offset=0, bias=None, gate=None,

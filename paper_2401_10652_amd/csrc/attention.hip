@@ -138,6 +138,13 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);     // [2][kKB][KROW]
   bf16_t* sV = sK + 2 * kKB * KROW;                      // [2][DH][VROW]
+  // The bias tile [QB query rows][64 keys] of the block goes through LDS too: a lane needs 4
+  // consecutive keys of ITS row, so direct loads touch 64 cache lines per instruction and the
+  // kernel ends up bound by the L1's tag lookups; staged, a row's 128 bytes are one line read by
+  // 8 lanes.
+  constexpr int BROW = kKB + 4;                          // padded bias row (elements)
+  constexpr int B_CHUNKS = BIAS ? QB * (kKB / 8) / NT : 1;
+  bf16_t* sB = sV + 2 * DH * VROW;                       // [2][QB][BROW] (BIAS only)
 
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int l32 = lane % 32, half = lane / 32;
@@ -172,7 +179,19 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
-  const bf16_t* bias_row = BIAS ? (const bf16_t*)a.bias + h * a.s_bias_h + (int64_t)rowc * a.ld_bias : nullptr;
+  // bias chunk i of this thread: row b_row[i] of the block's query rows, keys b_col[i] .. +8 of the tile
+  const bf16_t* b_src[B_CHUNKS];
+  int b_dst[B_CHUNKS], b_col[B_CHUNKS];
+  if (BIAS) {
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      const int c = tid + NT * i, br = c / (kKB / 8);
+      b_col[i] = (c % (kKB / 8)) * 8;
+      int gr = q0 + br; if (gr > sq - 1) gr = sq - 1;
+      b_src[i] = (const bf16_t*)a.bias + h * a.s_bias_h + (int64_t)gr * a.ld_bias + b_col[i];
+      b_dst[i] = br * BROW + b_col[i];
+    }
+  }
 
   int kv_end = sk;
   if (CAUSAL) {
@@ -214,7 +233,7 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
     v_src[i] = vbase + (int64_t)v_row[i] * a.ldv + v_col[i];
     v_dst[i] = v_row[i] * VROW + (ch / 2) * 16 + (ch % 2) * 4;
   }
-  bf16x8 k_reg[K_CHUNKS], v_reg[V_CHUNKS];
+  bf16x8 k_reg[K_CHUNKS], v_reg[V_CHUNKS], b_reg[B_CHUNKS];
 
   auto load_tile = [&](int k0) {
 #pragma unroll
@@ -237,6 +256,19 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
         for (int j = 0; j < 8; ++j) v_reg[i][j] = key + j < sk ? src[j] : (bf16_t)0.0f;
       }
     }
+    if (BIAS) {
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) {
+        const bf16_t* src = b_src[i] + k0;
+        if (!RAGGED) {
+          b_reg[i] = *reinterpret_cast<const bf16x8*>(src);
+        } else {   // keys past the end are masked later; stage zeros for them
+          const int key = k0 + b_col[i];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) b_reg[i][j] = key + j < sk ? src[j] : (bf16_t)0.0f;
+        }
+      }
+    }
   };
   auto store_tile = [&](int buf) {
     bf16_t* dk = sK + buf * kKB * KROW;
@@ -249,6 +281,16 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
       const bf16x4 hi = {v_reg[i][4], v_reg[i][5], v_reg[i][6], v_reg[i][7]};
       *reinterpret_cast<bf16x4*>(dv + v_dst[i]) = lo;
       *reinterpret_cast<bf16x4*>(dv + v_dst[i] + 8) = hi;
+    }
+    if (BIAS) {
+      bf16_t* db = sB + buf * QB * BROW;
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) {
+        const bf16x4 lo = {b_reg[i][0], b_reg[i][1], b_reg[i][2], b_reg[i][3]};
+        const bf16x4 hi = {b_reg[i][4], b_reg[i][5], b_reg[i][6], b_reg[i][7]};
+        *reinterpret_cast<bf16x4*>(db + b_dst[i]) = lo;       // (rows are 8-byte aligned, not 16)
+        *reinterpret_cast<bf16x4*>(db + b_dst[i] + 4) = hi;
+      }
     }
   };
 
@@ -287,13 +329,12 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
       // ---- lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4.  Scores go to the log2 domain
       // only where needed: with a bias right away, otherwise folded into the exponent below.
       if (BIAS) {
+        const bf16_t* cb = sB + buf * QB * BROW + (wave * 32 + l32) * BROW + 4 * half;
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
           for (int g4 = 0; g4 < 4; ++g4) {
-            const int key = k0 + tt * 32 + 8 * g4 + 4 * half;
-            bf16x4 bb = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
-            if (!RAGGED || key < sk) bb = *reinterpret_cast<const bf16x4*>(bias_row + key);
+            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(cb + tt * 32 + 8 * g4);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
               acc_s[tt][4 * g4 + j] = fmaf(acc_s[tt][4 * g4 + j], scale2, bf2f(bb[j]) * kLog2e);
@@ -456,7 +497,7 @@ __global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
 template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED, NW>;
-  constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8) + (BIAS ? 32 * NW * (kKB + 4) : 0)) * sizeof(bf16_t);
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (attr_status != hipSuccess) return attr_status;
@@ -500,7 +541,7 @@ static bool mfma_attn_eligible(const AttnArgs& a) {
   if (a.ldq % 8 || a.ldk % 8 || a.ldv % 8 || a.sq_b % 8 || a.sk_b % 8 || a.sv_b % 8) return false;
   if (a.ldc % 4 || a.sc_b % 4) return false;
   if (!al(a.q, 16) || !al(a.k, 16) || !al(a.v, 16) || !al(a.ctx, 8)) return false;
-  if (a.bias && (a.sk % 4 || a.ld_bias % 4 || a.s_bias_h % 4 || !al(a.bias, 8))) return false;
+  if (a.bias && (a.sk % 4 || a.ld_bias % 8 || a.s_bias_h % 8 || !al(a.bias, 16))) return false;   // 16-byte bias chunks
   if (a.gate && (a.ldg % 4 || a.sg_b % 4 || !al(a.gate, 8))) return false;
   return true;
 }

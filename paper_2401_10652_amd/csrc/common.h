@@ -154,6 +154,32 @@ struct AttnArgs {
   int head_major;   // block order (head, problem, query block) instead of (problem, head, query block); set by launch_attention
 };
 
+// LayerNorm of short rows followed by several projections of the normalised rows, in one
+// kernel: t = LN(x) stays on chip and every part computes act(t w^T + bias) or, for a gated
+// pair, sigmoid(t w_gate^T + bias_gate) * (t w^T + bias), each with its own output layout.
+constexpr int kMaxProjParts = 5;
+constexpr int kMaxProjTiles = 24;
+struct ProjPart {
+  const void* w; const void* bias;             // [n, K], [n] or null
+  const void* w_gate; const void* bias_gate;   // of a gated pair
+  int gated;                                   // 1: out = sigmoid(t w_gate^T + bias_gate) * (t w^T + bias)
+  int act;                                     // of a plain part
+  int64_t n;
+  void* out; int64_t ldo, o_period, o_s1, o_s2;            // row-major store (rows regrouped if o_period > 0), or
+  void* out_t; int64_t t_period, t_s1, t_s2, t_s3;          // strided store of the whole part (see LinearArgs)
+};
+struct LnProjArgs {
+  const void* x; int64_t ldx;      // [rows, K]
+  const void* gain; const void* shift; float eps;
+  int64_t rows; int64_t k;
+  int n_parts;
+  ProjPart part[kMaxProjParts];
+};
+// Shapes the kernel covers (bf16, K = 64 or 128, every n a multiple of 4); a pure function of the
+// shapes so that planning and execution take the same path.
+bool ln_proj_shapes_ok(int dtype, int64_t k, const int64_t* n, int n_parts);
+hipError_t launch_ln_proj(const LnProjArgs& p, hipStream_t s);
+
 hipError_t launch_layernorm(const void* x, int64_t ldx, const void* gain, const void* shift, void* y,
                             int64_t ldy, int64_t rows, int64_t cols, float eps, int dtype,
                             hipStream_t s);

@@ -20,9 +20,27 @@ namespace ac {
 // Epilogue for one element (generic kernel) — bias, activation, multiplier, residual,
 // then the row-major or the strided ("transposed") store.
 // ------------------------------------------------------------------------------------
+// m = q * period + r for a row index m < 2^31 (the launchers refuse more rows): a 32-bit division,
+// a fraction of the instructions and registers of the 64-bit one.  A period of 2^31 or more (the
+// "no period" value) gives q = 0, r = m.
+__device__ __forceinline__ void split_row(int64_t m, int64_t period, int64_t& q, int64_t& r) {
+  if (period > 0x7fffffffLL) { q = 0; r = m; return; }
+  const uint32_t qq = (uint32_t)m / (uint32_t)period;
+  q = qq;
+  r = (int64_t)((uint32_t)m - qq * (uint32_t)period);
+}
 // Offset of row m in the row-major part of the output.
 __device__ __forceinline__ int64_t out_row(const LinearArgs& g, int64_t m) {
-  return g.o_period == INT64_MAX ? m * g.ldo : (m / g.o_period) * g.o_s1 + (m % g.o_period) * g.o_s2;
+  if (g.o_period == INT64_MAX) return m * g.ldo;
+  int64_t q, r;
+  split_row(m, g.o_period, q, r);
+  return q * g.o_s1 + r * g.o_s2;
+}
+// Offset of row m in the strided ("transposed") part of the output.
+__device__ __forceinline__ int64_t out_t_row(const LinearArgs& g, int64_t m) {
+  int64_t q, r;
+  split_row(m, g.t_period, q, r);
+  return q * g.t_s1 + r * g.t_s2;
 }
 
 template <typename T>
@@ -34,7 +52,7 @@ __device__ __forceinline__ void epilogue_store_one(const LinearArgs& g, int64_t 
   if (n < g.n_split) {
     Elem<T>::st((T*)g.out + out_row(g, m) + n, v);
   } else {
-    const int64_t off = (m / g.t_period) * g.t_s1 + (m % g.t_period) * g.t_s2 + (n - g.n_split) * g.t_s3;
+    const int64_t off = out_t_row(g, m) + (n - g.n_split) * g.t_s3;
     Elem<T>::st((T*)g.out_t + off, v);
   }
 }
@@ -106,6 +124,13 @@ __device__ __forceinline__ void tile_of_block(int64_t tiles_m, int64_t tiles_n, 
   tn = (t % width) / gsz;
 }
 
+// Block id -> position in a 1-D list of work items such that each XCD gets a contiguous run.
+__device__ __forceinline__ int64_t xcd_run(int64_t pid, int64_t nb) {
+  const int64_t q = nb / kXcds, r = nb % kXcds;
+  const int64_t x = pid % kXcds, idx = pid / kXcds;
+  return x * q + (x < r ? x : r) + idx;
+}
+
 // GELU (erf form) from a table in LDS.  gelu(x) = x/2 + |x| h(|x|) with h(a) = erf(a / sqrt 2) / 2,
 // and h is read from 385 entries (value, step to the next) at a spacing of 1/64, interpolated
 // linearly: |error of h| <= (1/64)^2 / 8 * max|h''| = 7.4e-6, and from |x| = 6 on h is 1/2 to
@@ -165,7 +190,7 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
     const bool row_ok = m < g.m;
     const int64_t mc = row_ok ? m : g.m - 1;
     // offset of row m in the strided ("transposed") output, if any
-    const int64_t t_base = g.n_split < g.n ? (mc / g.t_period) * g.t_s1 + (mc % g.t_period) * g.t_s2 : 0;
+    const int64_t t_base = g.n_split < g.n ? out_t_row(g, mc) : 0;
 #pragma unroll
     for (int jb = 0; jb < TN; jb += JB) {
       bf16x4 bias_v[JB][4], mul_v[JB][4], res_v[JB][4];
@@ -233,7 +258,9 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   if (tstaged) {
     __syncthreads();
     constexpr int CPT = BM / 8;   // 16-byte chunks per staged row (one output column n)
-    const int64_t t_tile = (m0 / g.t_period) * g.t_s1 + (m0 % g.t_period);   // the tile's rows share a period
+    int64_t tq, tr;
+    split_row(m0, g.t_period, tq, tr);
+    const int64_t t_tile = tq * g.t_s1 + tr;   // the tile's rows share a period (and t_s2 == 1 here)
 #pragma unroll 4
     for (int c = tid; c < BN * CPT; c += NT) {
       const int nl = c / CPT, mm = (c % CPT) * 8;
@@ -247,12 +274,22 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   if (!staged) return;
   __syncthreads();
   constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
+  if (g.o_period == INT64_MAX) {   // (two loops: the common one carries no trace of the regrouping arithmetic)
 #pragma unroll 4
-  for (int c = tid; c < BM * CPR; c += NT) {
-    const int rl = c / CPR, cc = (c % CPR) * 8;
-    const int64_t m = m0 + rl, n = n0 + cc;
-    if (m < g.m && n < g.n)
-      *reinterpret_cast<bf16x8*>((bf16_t*)g.out + out_row(g, m) + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
+    for (int c = tid; c < BM * CPR; c += NT) {
+      const int rl = c / CPR, cc = (c % CPR) * 8;
+      const int64_t m = m0 + rl, n = n0 + cc;
+      if (m < g.m && n < g.n)
+        *reinterpret_cast<bf16x8*>((bf16_t*)g.out + m * g.ldo + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
+    }
+  } else {
+#pragma unroll 2
+    for (int c = tid; c < BM * CPR; c += NT) {
+      const int rl = c / CPR, cc = (c % CPR) * 8;
+      const int64_t m = m0 + rl, n = n0 + cc;
+      if (m < g.m && n < g.n)
+        *reinterpret_cast<bf16x8*>((bf16_t*)g.out + out_row(g, m) + n) = *reinterpret_cast<const bf16x8*>(lds + rl * CROW + cc);
+    }
   }
 }
 
@@ -399,6 +436,295 @@ static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------
+// LayerNorm + several projections of the same short rows in one kernel.
+// The pair-stack modules project every LayerNorm output four or five times with K = c_z
+// (gated a and b of the triangle update; q, k, v, gate and pair bias of the triangle attention;
+// the transition's first layer).  Separate launches re-read the normalised rows each time and
+// are bound by that traffic, not by the matrix cores.  Here a block normalises 64 rows once
+// (the whole row is one k tile), keeps them in LDS as the matrix operand, and walks a list of
+// 128-column weight tiles (64 rows keep the accumulators small enough for two or three blocks per CU,
+// whose phases interleave: while one waits for its rows another multiplies and a third stores): each tile is prefetched into registers while the previous one is
+// multiplied, and leaves through the same epilogue as the GEMM above (row-major, regrouped
+// or strided store).  A gated pair keeps sigmoid(gate) in registers and multiplies the
+// projection by it, so the gate never reaches memory.  Per-row arithmetic does not depend on
+// the block a row falls in, so results are bitwise independent of the chunk length.
+// ------------------------------------------------------------------------------------
+struct LnProjKernelArgs {
+  LnProjArgs a;
+  int n_tiles;
+  int tile_part[kMaxProjTiles];
+  int tile_n0[kMaxProjTiles];
+  int any_gelu;
+};
+
+constexpr int kLnProjRows = 64;   // rows per block
+
+template <int K>
+__global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka) {
+  constexpr int BM = kLnProjRows, BN = 128, NT = 256;
+  constexpr int AROW = K + 8;                 // padded LDS row (elements)
+  constexpr int G = K / 8;                    // lanes per row in the LayerNorm pass (16-byte chunks per row)
+  constexpr int RPP = NT / G;                 // rows per pass
+  constexpr int PASSES = BM / RPP;
+  constexpr int KSTEPS = K / 16;
+  constexpr int W_CHUNKS = BN * G / NT;       // 16-byte chunks of a weight tile per thread
+  constexpr int STAGE = BN * (BM + 8);        // elements the epilogue's staging tile needs (the transposed form is the larger)
+  constexpr int WBUF = BN * AROW > STAGE ? BN * AROW : STAGE;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);     // [BM][AROW]: the normalised rows
+  bf16_t* sW = sA + BM * AROW;                          // [BN][AROW]: weight tile; then the epilogue's staging tile
+  float* gelu_tab = reinterpret_cast<float*>(sW + WBUF);
+  const LnProjArgs& p = ka.a;
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int wave_m = wave / 2, wave_n = wave % 2;
+  const int l32 = lane % 32, half = lane / 32;
+  // consecutive row tiles go to one XCD, so that neighbouring runs of a strided output meet in one L2
+  const int64_t m0 = xcd_run(blockIdx.x, gridDim.x) * BM;
+  if (ka.any_gelu) gelu_table_fill(gelu_tab, tid, NT);
+
+  // ---- LayerNorm of the block's rows (G lanes per row, the row in registers, fp32 statistics)
+  {
+    const int lg = tid % G, rg = tid / G;
+    const bf16_t* x = (const bf16_t*)p.x;
+    float v[PASSES][8];
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      int64_t r = m0 + ps * RPP + rg;
+      if (r > p.rows - 1) r = p.rows - 1;     // rows past the end shadow the last row; never stored
+      load_vec(x + r * p.ldx + lg * 8, v[ps]);
+    }
+    float gn[8], sh[8];
+    load_vec((const bf16_t*)p.gain + lg * 8, gn);
+    load_vec((const bf16_t*)p.shift + lg * 8, sh);
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += v[ps][j];
+      const float mean = group_sum<G>(sum) * (1.0f / K);
+      float sq = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float d = v[ps][j] - mean; sq += d * d; }
+      const float rstd = rsqrtf(group_sum<G>(sq) * (1.0f / K) + p.eps);
+      float o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = (v[ps][j] - mean) * rstd * gn[j] + sh[j];
+      store_vec(sA + (ps * RPP + rg) * AROW + lg * 8, o);
+    }
+  }
+
+  bf16x8 wreg[W_CHUNKS];
+  auto store_w = [&](int tid) {
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+      const int c = tid + NT * i, row = c / G, ch = c % G;
+      *reinterpret_cast<bf16x8*>(sW + row * AROW + ch * 8) = wreg[i];
+    }
+  };
+
+  auto load_w = [&](const void* wbase, int64_t n_rows, int64_t n0, int tid) {
+    const bf16_t* w = (const bf16_t*)wbase;
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+      const int c = tid + NT * i, row = c / G, ch = c % G;
+      int64_t gr = n0 + row; if (gr > n_rows - 1) gr = n_rows - 1;
+      wreg[i] = *reinterpret_cast<const bf16x8*>(w + gr * K + ch * 8);
+    }
+  };
+  // first weight tile of entry t: the gate's for a gated pair
+  auto load_first = [&](int t, int tid) {
+    const ProjPart& q = p.part[ka.tile_part[t]];
+    load_w(q.gated ? q.w_gate : q.w, q.n, ka.tile_n0[t], tid);
+  };
+  f32x16 acc[1][2];
+  const bf16_t* cA = sA + (wave_m * 32 + l32) * AROW + half * 8;
+  const bf16_t* cW = sW + (wave_n * 64 + l32) * AROW + half * 8;
+  auto multiply = [&]() {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[0][j][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 fa = *reinterpret_cast<const bf16x8*>(cA + ks * 16);
+      bf16x8 fw[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(cW + j * 32 * AROW + ks * 16);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fa, acc[0][j], 0, 0, 0);
+    }
+  };
+  // this lane's 4 consecutive columns of group q in 32-column tile j: acc[i][j][4q .. 4q+3]
+  auto lane_bias = [&](const void* bias, int64_t n_total, int64_t n0, int j, int q) {
+    int64_t n = n0 + wave_n * 64 + j * 32 + 8 * q + 4 * half;
+    if (n > n_total - 4) n = n_total - 4;
+    bf16x4 bv = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+    if (bias) bv = *reinterpret_cast<const bf16x4*>((const bf16_t*)bias + n);
+    return bv;
+  };
+
+  load_first(0, tid);
+  for (int t = 0; t < ka.n_tiles; ++t) {
+    const ProjPart& pp = p.part[ka.tile_part[t]];
+    const int64_t n0 = ka.tile_n0[t];
+    const bool gated = pp.gated != 0;
+    // (opaque copy of the thread index: see the note at the epilogue below)
+    int w_tid = tid;
+    asm volatile("" : "+v"(w_tid));
+    store_w(w_tid);
+    __syncthreads();                         // the tile (and, the first time, the normalised rows) is in LDS
+    // the next weight tile is in flight while this one is multiplied and stored
+    if (gated) load_w(pp.w, pp.n, n0, w_tid);
+    else if (t + 1 < ka.n_tiles) load_first(t + 1, w_tid);
+    multiply();
+    __syncthreads();                         // every wave is done reading the weight tile
+    if (gated) {
+      // sigmoid(gate) stays in registers; the projection tile of the pair follows at once
+      f32x16 sg[1][2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bf16x4 bv = lane_bias(pp.bias_gate, pp.n, n0, j, q);
+#pragma unroll
+          for (int i = 0; i < 1; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) sg[i][j][4 * q + jj] = sigmoidf(acc[i][j][4 * q + jj] + bf2f(bv[jj]));
+        }
+      store_w(w_tid);
+      __syncthreads();
+      if (t + 1 < ka.n_tiles) load_first(t + 1, w_tid);
+      multiply();
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bf16x4 bv = lane_bias(pp.bias, pp.n, n0, j, q);
+#pragma unroll
+          for (int i = 0; i < 1; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+              acc[i][j][4 * q + jj] = (acc[i][j][4 * q + jj] + bf2f(bv[jj])) * sg[i][j][4 * q + jj];
+        }
+    }
+    if (!gated) {
+      // bias and activation here, one uniform branch per tile, so that the epilogue below exists once
+      const int act = pp.act;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bf16x4 bv = lane_bias(pp.bias, pp.n, n0, j, q);
+#pragma unroll
+          for (int i = 0; i < 1; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) acc[i][j][4 * q + jj] += bf2f(bv[jj]);
+        }
+      if (act == AC_ACT_GELU_ERF) {
+#pragma unroll
+        for (int i = 0; i < 1; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_table(acc[i][j][r], gelu_tab);
+      } else if (act == AC_ACT_SIGMOID) {
+#pragma unroll
+        for (int i = 0; i < 1; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = sigmoidf(acc[i][j][r]);
+      } else if (act == AC_ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < 1; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = fmaxf(acc[i][j][r], 0.f);
+      } else if (act == AC_ACT_GELU_TANH) {
+#pragma unroll
+        for (int i = 0; i < 1; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_tanh(acc[i][j][r]);
+      }
+    }
+    LinearArgs g{};
+    g.out = pp.out; g.ldo = pp.ldo; g.o_period = pp.o_period; g.o_s1 = pp.o_s1; g.o_s2 = pp.o_s2;
+    g.out_t = pp.out_t; g.n_split = pp.out_t ? 0 : pp.n;
+    g.t_period = pp.t_period; g.t_s1 = pp.t_s1; g.t_s2 = pp.t_s2; g.t_s3 = pp.t_s3;
+    g.m = p.rows; g.n = pp.n;
+    // The epilogue's many per-lane addresses do not depend on the tile; hoisted out of this loop
+    // they would occupy registers for the whole kernel (and spill).  Opaque copies of the lane
+    // coordinates make them values of this iteration, recomputed per tile with a few ALU ops.
+    int e_tid = tid, e_l32 = l32, e_half = half, e_wm = wave_m, e_wn = wave_n;
+    asm volatile("" : "+v"(e_tid), "+v"(e_l32), "+v"(e_half), "+v"(e_wm), "+v"(e_wn));
+    epilogue_tile<AC_ACT_NONE, BM, BN, 2, 2>(g, acc, sW, gelu_tab, m0, n0, e_wm, e_wn, e_l32, e_half, e_tid);
+    __syncthreads();                         // the staging tile has been read out; sW is free for the next tile
+  }
+}
+
+bool ln_proj_shapes_ok(int dtype, int64_t k, const int64_t* n, int n_parts) {
+  if (dtype != AC_BF16 || (k != 64 && k != 128)) return false;
+  if (n_parts < 1 || n_parts > kMaxProjParts) return false;
+  int64_t tiles = 0;
+  for (int i = 0; i < n_parts; ++i) {
+    if (n[i] < 4 || n[i] % 4 != 0) return false;
+    tiles += (n[i] + 127) / 128;
+  }
+  return tiles <= kMaxProjTiles;
+}
+
+template <int K>
+static hipError_t ln_proj_launch(const LnProjKernelArgs& ka, hipStream_t s) {
+  auto kern = ln_multi_proj_bf16<K>;
+  constexpr int AROW = K + 8, STAGE = 128 * (kLnProjRows + 8);
+  constexpr int WBUF = 128 * AROW > STAGE ? 128 * AROW : STAGE;
+  constexpr size_t lds_max = (size_t)(kLnProjRows * AROW + WBUF) * sizeof(bf16_t) + kGeluTableBytes;
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+  if (attr_status != hipSuccess) return attr_status;
+  // the GELU table is only there when a part needs it: without it three blocks fit a CU's LDS
+  const size_t lds = lds_max - (ka.any_gelu ? 0 : kGeluTableBytes);
+  const int64_t blocks = (ka.a.rows + kLnProjRows - 1) / kLnProjRows;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, ka);
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_proj(const LnProjArgs& p_in, hipStream_t s) {
+  if (p_in.rows <= 0) return hipSuccess;
+  LnProjKernelArgs ka{};
+  ka.a = p_in;
+  LnProjArgs& p = ka.a;
+  int64_t ns[kMaxProjParts];
+  if (p.n_parts < 1 || p.n_parts > kMaxProjParts) return hipErrorInvalidValue;
+  for (int i = 0; i < p.n_parts; ++i) ns[i] = p.part[i].n;
+  if (!ln_proj_shapes_ok(AC_BF16, p.k, ns, p.n_parts)) return hipErrorNotSupported;
+  if (p.ldx % 8 != 0 || ((uintptr_t)p.x % 16) != 0 || ((uintptr_t)p.gain % 16) != 0 || ((uintptr_t)p.shift % 16) != 0)
+    return hipErrorNotSupported;
+  if (p.rows > 0x7fffffffLL) return hipErrorInvalidValue;
+  for (int i = 0; i < p.n_parts; ++i) {
+    ProjPart& pp = p.part[i];
+    if (!pp.w || ((uintptr_t)pp.w % 16) != 0 || ((uintptr_t)pp.w_gate % 16) != 0) return hipErrorNotSupported;
+    if (pp.gated && !pp.w_gate) return hipErrorInvalidValue;
+    if (((uintptr_t)pp.bias % 8) != 0 || ((uintptr_t)pp.bias_gate % 8) != 0) return hipErrorNotSupported;
+    if (pp.out_t == nullptr && (pp.out == nullptr || pp.ldo % 4 != 0 || ((uintptr_t)pp.out % 8) != 0)) return hipErrorNotSupported;
+    if (pp.t_period <= 0) pp.t_period = INT64_MAX;
+    if (pp.o_period <= 0) pp.o_period = INT64_MAX;
+    if (pp.o_period != INT64_MAX && (pp.o_s1 % 4 != 0 || pp.o_s2 % 4 != 0)) return hipErrorNotSupported;
+    if (pp.act == AC_ACT_GELU_ERF && !pp.gated) ka.any_gelu = 1;
+    for (int64_t n0 = 0; n0 < pp.n; n0 += 128) {   // a gated pair is one entry: two weight tiles, one output tile
+      ka.tile_part[ka.n_tiles] = i;
+      ka.tile_n0[ka.n_tiles++] = (int)n0;
+    }
+  }
+  return p.k == 128 ? ln_proj_launch<128>(ka, s) : ln_proj_launch<64>(ka, s);
+}
+
 static bool aligned_to(const void* p, uintptr_t a) { return p == nullptr || ((uintptr_t)p % a) == 0; }
 
 static bool mfma_eligible(const LinearArgs& g) {
@@ -427,7 +753,7 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (g.batch < 1) g.batch = 1;
   if (g.batch > 1 && g.o_period != INT64_MAX) return hipErrorInvalidValue;
   if (g.batch > 1 && (g.bias || g.mul || g.resid || g.out_t || g.act != AC_ACT_NONE)) return hipErrorInvalidValue;
-  if (g.batch > 65535) return hipErrorInvalidValue;
+  if (g.batch > 65535 || g.m > 0x7fffffffLL) return hipErrorInvalidValue;
   if (mfma_eligible(g)) {
     // A CU takes in at most 64 bytes per clock from L2 while its matrix cores retire 4096
     // flops per clock, so a tile needs >= 64 flops per loaded byte just to break even: 128x128

@@ -359,6 +359,28 @@ struct Walk {
     run(K_TRI, 2.0 * ni * nj * nk * channels, by, "triangle_contract", [&] { return launch_linear(g, stream); });
   }
 
+  // LayerNorm of `rows` rows of width k and every projection of `parts` in one kernel (the
+  // normalised rows never reach memory).  Callers ask fuses_ln_proj first; planning and
+  // execution take the same answer from the shapes alone.
+  bool fuses_ln_proj(int64_t k, std::initializer_list<int64_t> ns) const {
+    if (p->m.flags & AC_FLAG_UNFUSED_ELEMENTWISE) return false;
+    std::vector<int64_t> v(ns);
+    return ln_proj_shapes_ok(p->m.dtype, k, v.data(), (int)v.size());
+  }
+  void ln_proj(const void* x, int64_t ldx, const void* g, const void* b, int64_t rows, int64_t k,
+               std::initializer_list<ProjPart> parts) {
+    LnProjArgs a{};
+    a.x = x; a.ldx = ldx; a.gain = g; a.shift = b; a.eps = p->m.ln_eps; a.rows = rows; a.k = k;
+    double fl = 8.0 * rows * k, by = (double)rows * k * eb();
+    for (const ProjPart& pp : parts) {
+      a.part[a.n_parts++] = pp;
+      const double mult = pp.gated ? 2.0 : 1.0;
+      fl += 2.0 * rows * k * pp.n * mult;
+      by += ((double)rows * pp.n + (double)pp.n * k * mult) * eb();
+    }
+    run(K_GEMM, fl, by, "ln_proj", [&] { return launch_ln_proj(a, stream); });
+  }
+
   int64_t seg_len(int kind) const { return unchunked ? p->set[kind].extent : p->set[kind].chunk_len; }
 
   void transformer(const void* x, void* y);
@@ -530,8 +552,18 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   // ---- whole operands: a and b of every position, channel-major.  Row r = (i, k) of z lands
   // at [c][r]; for the incoming form r = (k, i), and the per-channel matrices are transposed
   // in place afterwards.
+  const bool fuse_ab = fuses_ln_proj(cz, {ch, ch}), fuse_g = fuses_ln_proj(cz, {cz});
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    if (fuse_ab) {   // LayerNorm and the four projections in one kernel; the gates stay in registers
+      ProjPart pa{}, pb{};
+      pa.w = W[TM_W_AP]; pa.bias = W[TM_B_AP]; pa.w_gate = W[TM_W_AG]; pa.bias_gate = W[TM_B_AG]; pa.gated = 1;
+      pa.n = ch; pa.out_t = atw(a_t, r0); pa.t_s2 = 1; pa.t_s3 = R;
+      pb.w = W[TM_W_BP]; pb.bias = W[TM_B_BP]; pb.w_gate = W[TM_W_BG]; pb.bias_gate = W[TM_B_BG]; pb.gated = 1;
+      pb.n = ch; pb.out_t = atw(b_t, r0); pb.t_s2 = 1; pb.t_s3 = R;
+      ln_proj(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], rows, cz, {pa, pb});
+      return;
+    }
     void* t = arena.push((uint64_t)rows * cz * e);
     void* gate = arena.push((uint64_t)rows * ch * e);
     ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
@@ -554,15 +586,21 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   // ---- chunked part: rows i of the output
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    void* t = arena.push((uint64_t)rows * cz * e);
+    void* t = fuse_g ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* gate = arena.push((uint64_t)rows * cz * e);
     void* o_c = arena.push((uint64_t)ch * rows * e);   // [c][i][j]
     void* lo = arena.push((uint64_t)rows * ch * e);
-    ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
-    LinearArgs g{};
-    g.a = t; g.lda = cz; g.w = W[TM_W_G]; g.ldw = cz; g.bias = W[TM_B_G]; g.act = AC_ACT_SIGMOID;
-    g.out = gate; g.ldo = cz; g.m = rows; g.n = cz; g.k = cz; g.n_split = cz;
-    linear(g);
+    if (fuse_g) {
+      ProjPart pg{};
+      pg.w = W[TM_W_G]; pg.bias = W[TM_B_G]; pg.act = AC_ACT_SIGMOID; pg.n = cz; pg.out = gate; pg.ldo = cz;
+      ln_proj(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], rows, cz, {pg});
+    } else {
+      ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
+      LinearArgs g{};
+      g.a = t; g.lda = cz; g.w = W[TM_W_G]; g.ldw = cz; g.bias = W[TM_B_G]; g.act = AC_ACT_SIGMOID;
+      g.out = gate; g.ldo = cz; g.m = rows; g.n = cz; g.k = cz; g.n_split = cz;
+      linear(g);
+    }
     contract(at(a_t, sg.i0 * N), N, R, b_t, N, R, o_c, N, rows, sg.ni, N, N, ch);
     ln_channel_major(o_c, rows, W[TM_LN_OUT_G], W[TM_LN_OUT_B], lo, ch, rows, ch);
     LinearArgs o{};
@@ -592,8 +630,20 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   void* bias = arena.push((uint64_t)H * R * e);
   void* k_all = ending ? arena.push((uint64_t)R * hd * e) : nullptr;
   void* v_all = ending ? arena.push((uint64_t)hd * R * e) : nullptr;
+  const bool fuse_a = ending ? fuses_ln_proj(cz, {H, hd, hd}) : fuses_ln_proj(cz, {H});
+  const bool fuse_b = ending ? fuses_ln_proj(cz, {hd, hd}) : fuses_ln_proj(cz, {hd, hd, hd, hd});
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    if (fuse_a) {
+      ProjPart pb{}, pk{}, pv{};
+      pb.w = W[TA_W_BIAS]; pb.n = H; pb.out_t = atw(bias, r0); pb.t_s2 = 1; pb.t_s3 = R;
+      pk.w = W[TA_W_K]; pk.n = hd; pk.out = k_all ? atw(k_all, sg.i0 * hd) : nullptr; pk.ldo = hd;
+      pk.o_period = N; pk.o_s1 = hd; pk.o_s2 = N * hd;     // row (k - i0, j) -> (j, k)
+      pv.w = W[TA_W_V]; pv.n = hd; pv.out_t = v_all ? atw(v_all, r0) : nullptr; pv.t_s2 = 1; pv.t_s3 = R;
+      if (ending) ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pb, pk, pv});
+      else ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pb});
+      return;
+    }
     void* t = arena.push((uint64_t)rows * cz * e);
     ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
     LinearArgs b{};
@@ -619,31 +669,43 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   // ---- chunked part
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    void* t = arena.push((uint64_t)rows * cz * e);
+    void* t = fuse_b ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* q = arena.push((uint64_t)rows * hd * e);
     void* gate = arena.push((uint64_t)rows * hd * e);
     void* ctx = arena.push((uint64_t)rows * hd * e);
     void* k_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);
     void* v_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);   // [i][h*d][k]
-    ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
     LinearArgs lq{};
     lq.a = t; lq.lda = cz; lq.w = W[TA_W_Q]; lq.ldw = cz; lq.m = rows; lq.n = hd; lq.k = cz;
     lq.out = q; lq.ldo = hd; lq.n_split = hd;
-    linear(lq);
-    LinearArgs lg = lq;
-    lg.w = W[TA_W_G]; lg.bias = W[TA_B_G]; lg.act = AC_ACT_SIGMOID; lg.out = gate;
-    linear(lg);
+    if (fuse_b) {   // LayerNorm, q, gate (and k, v of the row for the starting node) in one kernel
+      ProjPart pq{}, pg{}, pk{}, pv{};
+      pq.w = W[TA_W_Q]; pq.n = hd; pq.out = q; pq.ldo = hd;
+      pg.w = W[TA_W_G]; pg.bias = W[TA_B_G]; pg.act = AC_ACT_SIGMOID; pg.n = hd; pg.out = gate; pg.ldo = hd;
+      pk.w = W[TA_W_K]; pk.n = hd; pk.out = k_seg; pk.ldo = hd;
+      pv.w = W[TA_W_V]; pv.n = hd; pv.out_t = v_seg; pv.t_period = N; pv.t_s1 = hd * N; pv.t_s2 = 1; pv.t_s3 = N;
+      if (ending) ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg});
+      else ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg, pk, pv});
+    } else {
+      ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
+      linear(lq);
+      LinearArgs lg = lq;
+      lg.w = W[TA_W_G]; lg.bias = W[TA_B_G]; lg.act = AC_ACT_SIGMOID; lg.out = gate;
+      linear(lg);
+    }
     AttnArgs a{};
     a.heads = (int)H; a.head_dim = (int)dh; a.causal = 0; a.q_offset = 0; a.v_transposed = 1; a.sk = N;
     a.q = q; a.gate = gate; a.ctx = ctx;
     if (!ending) {
-      LinearArgs lk = lq;
-      lk.w = W[TA_W_K]; lk.out = k_seg;
-      linear(lk);
-      LinearArgs lv{};
-      lv.a = t; lv.lda = cz; lv.w = W[TA_W_V]; lv.ldw = cz; lv.m = rows; lv.n = hd; lv.k = cz;
-      lv.out_t = v_seg; lv.n_split = 0; lv.t_period = N; lv.t_s1 = hd * N; lv.t_s2 = 1; lv.t_s3 = N;
-      linear(lv);
+      if (!fuse_b) {
+        LinearArgs lk = lq;
+        lk.w = W[TA_W_K]; lk.out = k_seg;
+        linear(lk);
+        LinearArgs lv{};
+        lv.a = t; lv.lda = cz; lv.w = W[TA_W_V]; lv.ldw = cz; lv.m = rows; lv.n = hd; lv.k = cz;
+        lv.out_t = v_seg; lv.n_split = 0; lv.t_period = N; lv.t_s1 = hd * N; lv.t_s2 = 1; lv.t_s3 = N;
+        linear(lv);
+      }
       // one problem per row i: queries j, keys k of the same row
       a.batch = sg.ni; a.sq = N;
       a.ldq = hd; a.sq_b = N * hd; a.ldg = hd; a.sg_b = N * hd; a.ldc = hd; a.sc_b = N * hd;
@@ -676,10 +738,17 @@ void Walk::transition(const void* const* W, const void* zin, void* zout) {
   enter(AC_REGION_PAIR_TRANSITION);
   seg_loop(row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION)), [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
-    void* u = arena.push((uint64_t)rows * cz * e);
+    const bool fuse_up = fuses_ln_proj(cz, {F});
+    void* u = fuse_up ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* hid = arena.push((uint64_t)rows * F * e);
-    ln(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
-    proj(u, cz, W[PT_W_1], cz, W[PT_B_1], m.activation, nullptr, 0, hid, F, rows, F);
+    if (fuse_up) {
+      ProjPart pu{};
+      pu.w = W[PT_W_1]; pu.bias = W[PT_B_1]; pu.act = m.activation; pu.n = F; pu.out = hid; pu.ldo = F;
+      ln_proj(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], rows, cz, {pu});
+    } else {
+      ln(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
+      proj(u, cz, W[PT_W_1], cz, W[PT_B_1], m.activation, nullptr, 0, hid, F, rows, F);
+    }
     proj(hid, F, W[PT_W_2], F, W[PT_B_2], AC_ACT_NONE, at(zin, r0 * cz), cz, atw(zout, r0 * cz), cz, rows, cz);
   });
 }
@@ -1185,6 +1254,30 @@ int ac_op_layernorm(const void* x, int64_t ldx, const void* gain, const void* sh
     return fail(AC_ERR_ARG, "ac_op_layernorm: bad argument");
   return hip_status(launch_layernorm(x, ldx, gain, shift, y, ldy, rows, cols, eps, dtype, (hipStream_t)stream),
                     "layernorm");
+}
+
+int ac_op_ln_linear(const void* x, int64_t ldx, const void* gain, const void* shift, float eps, int64_t rows,
+                    int64_t k, const ac_proj_part* parts, int n_parts, int dtype, void* stream) {
+  if (!x || !gain || !shift || !parts || rows < 0 || k < 1 || ldx < k || n_parts < 1 || !(eps > 0.f) || !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_ln_linear: bad argument");
+  if (n_parts > kMaxProjParts) return fail(AC_ERR_UNSUPPORTED, "ac_op_ln_linear: at most %d parts", kMaxProjParts);
+  LnProjArgs a{};
+  a.x = x; a.ldx = ldx; a.gain = gain; a.shift = shift; a.eps = eps; a.rows = rows; a.k = k; a.n_parts = n_parts;
+  int64_t ns[kMaxProjParts];
+  for (int i = 0; i < n_parts; ++i) {
+    const ac_proj_part& s = parts[i];
+    if (!s.w || s.n < 1 || (s.gated && !s.w_gate) || (!s.out && !s.out_t) || s.activation < 0 ||
+        s.activation > AC_ACT_SIGMOID || (s.out && !s.out_t && s.o_period <= 0 && s.ldo < s.n))
+      return fail(AC_ERR_ARG, "ac_op_ln_linear: bad part %d", i);
+    ProjPart& d = a.part[i];
+    d.w = s.w; d.bias = s.bias; d.w_gate = s.w_gate; d.bias_gate = s.bias_gate; d.gated = s.gated != 0;
+    d.act = s.activation; d.n = s.n; d.out = s.out; d.ldo = s.ldo; d.o_period = s.o_period; d.o_s1 = s.o_s1;
+    d.o_s2 = s.o_s2; d.out_t = s.out_t; d.t_period = s.t_period; d.t_s1 = s.t_s1; d.t_s2 = s.t_s2; d.t_s3 = s.t_s3;
+    ns[i] = s.n;
+  }
+  if (!ln_proj_shapes_ok(dtype, k, ns, n_parts))
+    return fail(AC_ERR_UNSUPPORTED, "ac_op_ln_linear: bf16, k = 64 or 128 and n %% 4 == 0 only");
+  return hip_status(launch_ln_proj(a, (hipStream_t)stream), "ln_linear");
 }
 
 int ac_op_linear(const void* a, int64_t lda, const void* w, int64_t ldw, const void* bias, const void* mul,

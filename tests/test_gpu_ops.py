@@ -330,3 +330,56 @@ def test_random_shapes_of_linear_and_attention(B):
         assert err <= TOL["bf16"], (sq, sk, heads, dh, causal, q_offset, n_splits, err)
         worst = max(worst, err)
     assert worst > 0
+
+
+@pytest.mark.parametrize("rows,k", [(300, 128), (384, 128), (200, 64), (1, 128)])
+def test_ln_linear_parts(B, rows, k):
+    """LayerNorm + several projections in one kernel against the oracle's separate steps: a plain part
+    with bias and ReLU stored row-major, a gated pair stored channel-major, a 4-column part stored
+    strided, a GELU part with its rows regrouped on the way out, a sigmoid part."""
+    import torch
+    x = draw((rows, k), 400, "bf16")
+    g = 1.0 + draw((k,), 401, "bf16", 0.1)
+    b = draw((k,), 402, "bf16", 0.1)
+    w = {n: draw((c, k), 403 + i, "bf16", k ** -0.5) for i, (n, c) in
+         enumerate((("p", 128), ("gw", 64), ("gp", 64), ("s", 4), ("r", 256), ("sg", 72)))}
+    bias = {n: draw((w[n].shape[0],), 420 + i, "bf16", 0.2) for i, n in enumerate(w)}
+    dev_w = {n: dev(B, v, "bf16") for n, v in w.items()}
+    dev_b = {n: dev(B, v, "bf16") for n, v in bias.items()}
+    t = O.layer_norm(x, g, b)
+    sig = lambda v: 1.0 / (1.0 + np.exp(-v))
+    ref_p = O.relu(O.linear(t, w["p"], bias["p"]))
+    ref_g = sig(O.linear(t, w["gw"], bias["gw"])) * O.linear(t, w["gp"], bias["gp"])
+    ref_s = O.linear(t, w["s"])
+    ref_r = O.gelu_erf(O.linear(t, w["r"], bias["r"]))
+    ref_sg = sig(O.linear(t, w["sg"], bias["sg"]))
+    bf = torch.bfloat16
+    out_p = torch.full((rows, 128), float("nan"), dtype=bf, device="cuda")
+    out_g = torch.full((64, rows), float("nan"), dtype=bf, device="cuda")        # channel-major
+    out_s = torch.full((4, rows), float("nan"), dtype=bf, device="cuda")
+    # rows regrouped: row m = (a, c) with c < period lands at (c, a); pad the row count to the period
+    period = 8 if rows % 8 == 0 else 1
+    out_r = torch.full((rows, 256), float("nan"), dtype=bf, device="cuda")
+    out_sg = torch.full((rows, 72), float("nan"), dtype=bf, device="cuda")
+    parts = [
+        dict(w=dev_w["p"], bias=dev_b["p"], activation=B.AC_ACT_RELU, out=out_p),
+        dict(w=dev_w["gp"], bias=dev_b["gp"], w_gate=dev_w["gw"], bias_gate=dev_b["gw"], out_t=out_g, t_s2=1, t_s3=rows),
+        dict(w=dev_w["s"], out_t=out_s, t_s2=1, t_s3=rows),
+        dict(w=dev_w["r"], bias=dev_b["r"], activation=B.AC_ACT_GELU_ERF, out=out_r, o_period=period,
+             o_s1=256, o_s2=(rows // period) * 256),
+        dict(w=dev_w["sg"], bias=dev_b["sg"], activation=B.AC_ACT_SIGMOID, out=out_sg),
+    ]
+    B.ac_op_ln_linear(dev(B, x, "bf16"), dev(B, g, "bf16"), dev(B, b, "bf16"), parts)
+    torch.cuda.synchronize()
+    check(host(out_p), ref_p, "bf16", what="plain")
+    check(host(out_g).T, ref_g, "bf16", what="gated")
+    check(host(out_s).T, ref_s, "bf16", what="narrow")
+    # row m of the result sits at (m % period) * (rows / period) + m / period
+    m = np.arange(rows)
+    check(host(out_r)[(m % period) * (rows // period) + m // period], ref_r, "bf16", what="regrouped")
+    check(host(out_sg), ref_sg, "bf16", what="sigmoid")
+    # shapes the kernel does not cover are refused
+    with pytest.raises(B.AcError) as ei:
+        B.ac_op_ln_linear(dev(B, draw((8, 96), 1, "bf16"), "bf16"), dev(B, g[:96], "bf16"), dev(B, b[:96], "bf16"),
+                          [dict(w=dev(B, draw((8, 96), 2, "bf16"), "bf16"), out=out_p)])
+    assert ei.value.status == B.AC_ERR_UNSUPPORTED

@@ -82,7 +82,8 @@ def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, 
 
 
 @pytest.mark.parametrize("dtype,n,cz,ch,heads,dh", [("f32", 40, 32, 16, 2, 16), ("bf16", 40, 32, 16, 2, 16),
-                                                    ("bf16", 192, 64, 64, 2, 32)])
+                                                    ("bf16", 192, 64, 64, 2, 32), ("bf16", 72, 128, 128, 4, 32),
+                                                    ("bf16", 136, 128, 64, 4, 32)])
 def test_pair_block_chunked_equals_oracle(B, dtype, n, cz, ch, heads, dh):
     import torch
     cfg = I.PairConfig("tp", 41, n, cz, ch, heads, dh, 4, dtype)
@@ -93,11 +94,40 @@ def test_pair_block_chunked_equals_oracle(B, dtype, n, cz, ch, heads, dh):
         if ref is None:
             ref = P.pair_block(z, w, heads, cfg.activation, cfg.ln_eps)
         assert np.isfinite(host(y)).all()
-        check(host(y), ref, dtype, what=str(chunk))
+        check(host(y), ref, dtype, what=str(chunk), depth=5)
         outs.append(y)
     for y in outs[1:]:
         assert torch.equal(y, outs[0])
     assert info.n_regions == 5 and info.n_weights == 58
+
+
+def test_pair_fused_projections_equal_the_separate_kernels(B):
+    """c_z = 128 (and 64) take the kernel that normalises a block of rows once and applies every
+    projection of the module to it; AC_FLAG_UNFUSED_ELEMENTWISE keeps LayerNorm and each projection a
+    launch of its own.  Both must meet the oracle; they differ from each other by the rounding of
+    the gates (kept in fp32 registers by the fused kernel, stored as bf16 by the separate ones)."""
+    cfg = I.PairConfig("tpf", 43, 72, 128, 128, 4, 32, 4, "bf16")
+    z, w, y, info = run_pair(B, cfg, (16, 8, 72, 40, 24))
+    _, _, yu, infu = run_pair(B, cfg, (16, 8, 72, 40, 24), flags=B.AC_FLAG_UNFUSED_ELEMENTWISE)
+    ref = P.pair_block(z, w, cfg.heads, cfg.activation, cfg.ln_eps)
+    check(host(y), ref, "bf16", what="fused", depth=5)
+    check(host(yu), ref, "bf16", what="separate", depth=5)
+    check(host(y), host(yu), "bf16", what="fused vs separate", depth=5)
+    assert info.workspace_bytes < infu.workspace_bytes      # no normalised rows, no gates in memory
+    # every module on its own against the oracle (one stage: the mixed gate at the tolerance itself)
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+        import torch
+        dz = B.to_device(z, "bf16")
+        names = [n for n, _ in I.pair_tensor_shapes(cfg)]
+        dw = [B.to_device(w[n], "bf16") for n in names]
+        p = B.Plan(B.pair_desc(cfg, flags=B.AC_FLAG_LISTED_REGIONS_ONLY), [(k, B.AC_DIM_ROW, 24)])
+        p.ac_plan_bind_weights(dw)
+        ws = B.empty_workspace(p.ac_plan_query().workspace_bytes)
+        ym = torch.full_like(dz, float("nan"))
+        p.ac_execute(dz, ym, ws)
+        torch.cuda.synchronize()
+        p.close()
+        check(host(ym), P.pair_module(name, z, w, cfg.heads, cfg.activation, cfg.ln_eps), "bf16", what=name)
 
 
 def test_pair_legality(B):

@@ -78,10 +78,10 @@ def test_fp32_every_epilogue_and_ragged_lengths(B):
     outs = []
     for c in ((200, 200, 200), (64, 64, 64), (33, 77, 50), (1, 200, 7)):
         y, _ = r.run(regions(B, *c))
-        check(host(y), ref, "f32", what=str(c))
+        check(host(y), ref, "f32", what=str(c), depth=2)
         outs.append(y)
     yu, _ = r.run(regions(B, 64, 64, 64), flags=B.AC_FLAG_UNFUSED_ELEMENTWISE)
-    check(host(yu), ref, "f32")
+    check(host(yu), ref, "f32", depth=2)
 
 
 @pytest.mark.parametrize("causal,heads,act", [(True, 4, "gelu_erf"), (False, 8, "relu"), (False, 2, "gelu_tanh")])
@@ -93,14 +93,14 @@ def test_bf16_stack_chunked_equals_oracle(B, causal, heads, act):
     outs = []
     for c in ((640, 640, 640), (128, 128, 128), (256, 384, 512), (200, 136, 72), (640, 8, 640)):
         y, info = r.run(regions(B, *c, c_out=c[0]))
-        check(host(y), ref, "bf16", what=str(c))
+        check(host(y), ref, "bf16", what=str(c), depth=2)
         outs.append(y)
     # the K loop and the key-tile order do not depend on the segment a row falls in:
     # every chunk length gives bit-identical output
     for y in outs[1:]:
         assert torch.equal(y, outs[0])
     yu, _ = r.run(regions(B, 128, 128, 128), flags=B.AC_FLAG_UNFUSED_ELEMENTWISE)
-    check(host(yu), ref, "bf16")
+    check(host(yu), ref, "bf16", depth=2)
 
 
 def test_batch_and_batch_chunks(B):
@@ -179,7 +179,7 @@ def test_two_segments_in_flight_equals_sequential(B):
         y2, i2 = r.run(regions(B, *c), flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
         assert torch.equal(y1, y2), c
         assert i2.workspace_bytes >= i1.workspace_bytes
-        check(host(y2), ref, "bf16")
+        check(host(y2), ref, "bf16", depth=3)
     # repeated executes of one plan reuse its second stream and events
     p = B.Plan(B.transformer_desc(cfg, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(B, 128, 128, 128))
     p.ac_plan_bind_weights(r.dw)
@@ -214,8 +214,8 @@ def test_stored_scores_plans_equal_the_oracle(B, dtype, causal):
     peaks = []
     for c in (320, 128, 72):
         y, info = r.run(regions(B, 320, c, 320, c_out=320), flags=flag)
-        check(host(y), ref, dtype)
-        check(host(y), host(y_fused), dtype)
+        check(host(y), ref, dtype, depth=2)
+        check(host(y), host(y_fused), dtype, depth=2)
         peaks.append(info.workspace_bytes)
     assert peaks[0] > peaks[1] > peaks[2]
     e = 2 if dtype == "bf16" else 4
@@ -223,7 +223,7 @@ def test_stored_scores_plans_equal_the_oracle(B, dtype, causal):
     assert peaks[0] - peaks[1] >= 2 * cfg.heads * (320 - 128) * 320 * e
     # chunked along the batch: one problem per segment
     y, info = r.run(regions(B, 1, 1, 1, dim=B.AC_DIM_BATCH), flags=flag)
-    check(host(y), ref, dtype)
+    check(host(y), ref, dtype, depth=2)
     y2, _ = r.run(regions(B, 1, 1, 1, dim=B.AC_DIM_BATCH), flags=flag | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT)
     assert torch.equal(y, y2)
 
@@ -247,7 +247,7 @@ def test_chunks_planned_on_the_graph_run_in_the_executor(B, dtype, batch):
     r = Runner(B, cfg, bias_std=0.1, ln_jitter=0.1)
     flag = B.AC_FLAG_MATERIALIZED_SCORES
     y, info = r.run(settings, flags=flag)
-    check(host(y), r.oracle(), dtype)
+    check(host(y), r.oracle(), dtype, depth=2)
     assert info.regions[B.AC_REGION_ATTENTION].n_segments > 1
     _, info_whole = r.run([], flags=flag)
     assert info.workspace_bytes < info_whole.workspace_bytes
