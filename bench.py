@@ -31,8 +31,12 @@ def plan_regions(B, c_qkv, c_attn, c_ffn, c_out=None):
             (B.AC_REGION_FFN, B.AC_DIM_SEQ, c_ffn)]
 
 
+PAIR_DIM = "row"     # --pair-dim: the chunk dimension of the pair-stack regions
+
+
 def pair_regions(B, c):
-    return [(k, B.AC_DIM_ROW, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)]
+    dim = B.AC_DIM_COL if PAIR_DIM == "col" else B.AC_DIM_ROW
+    return [(k, dim, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)]
 
 
 def time_plan(B, torch, plan, dx, y, ws, steps, warmup):
@@ -196,6 +200,8 @@ def main():
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
                     help="segments of a region in flight at once (2: two streams, two per-segment workspaces)")
+    ap.add_argument("--pair-dim", default="row", choices=["row", "col"],
+                    help="pair stack: chunk along rows (the workload's plan) or columns of z")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sequential-only", action="store_true",
                     help="skip the extra two-segments-in-flight timing (its overlapping kernels would "
@@ -207,6 +213,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB copy kernel --steps times (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
+    global PAIR_DIM
+    PAIR_DIM = args.pair_dim
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -280,7 +288,8 @@ def main():
         "config": dict(
             {"workload": cfg.name, "act_budget_bytes": budget,
              "budget_bounds": ("executor bytes" if args.budget_on == "executor" else "executor and paper-model bytes") if budget else None,
-             "segments_in_flight": args.in_flight, **chunk_lens(info)},
+             "segments_in_flight": args.in_flight, **chunk_lens(info),
+             **({"chunk_dim": args.pair_dim} if is_pair else {})},
             **({"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
                 "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
                {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,
@@ -327,7 +336,7 @@ def main():
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
         out["two_segments_in_flight"] = timed_variant(desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, regs, budget)
-    if extras:
+    if extras and not (is_pair and args.pair_dim == "col"):
         # The standalone row passes (bias + activation, residual add, LayerNorm), which the fused
         # plan folds into GEMM epilogues, timed with HIP events in a plan that runs them unfused.
         pu = B.Plan(make_desc(B.AC_FLAG_UNFUSED_ELEMENTWISE), regs, 0 if is_pair else budget)

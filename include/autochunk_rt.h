@@ -77,7 +77,9 @@ typedef enum ac_region_kind {
  * the dim): batch and sequence for every transformer region; row and column for every
  * pair region; feature for the attention region (whole heads) and the output projection
  * (blocks of output columns).  Otherwise feature, head_dim, key, channel and contraction
- * index are illegal.  Column chunks and the two legal feature chunks are not implemented
+ * index are illegal.  A column chunk of a pair region gathers its positions with the two
+ * indices swapped (a copy that counts as activation memory, section 3.4) and runs the module's
+ * transposed form on them.  The two legal feature chunks are not implemented
  * (AC_ERR_UNSUPPORTED). */
 enum { AC_DIM_BATCH = 0, AC_DIM_SEQ = 1, AC_DIM_FEATURE = 2, AC_DIM_HEAD_DIM = 3, AC_DIM_KEY = 4 };
 enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 };

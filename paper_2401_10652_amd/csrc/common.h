@@ -202,6 +202,9 @@ hipError_t launch_transpose(const void* src, int64_t lds, void* dst, int64_t ldd
 // In-place transpose of `batch` square [n, n] matrices (row stride ld, `stride_b` apart).
 hipError_t launch_transpose_square_inplace(void* data, int64_t ld, int64_t stride_b, int64_t n,
                                            int64_t batch, int dtype, hipStream_t s);
+// dst[jj][i][:] = z[i][j0 + jj][:] for a pair tensor z[n][n][c] (the copy behind a column chunk).
+hipError_t launch_gather_columns(const void* src, void* dst, int64_t n, int64_t c, int64_t j0, int64_t nj, int dtype,
+                                 hipStream_t s);
 // LayerNorm over channels of a channel-major tensor: src[c * stride_c + p] -> dst[p * ldd + c].
 hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain,
                                           const void* shift, void* dst, int64_t ldd, int64_t positions,

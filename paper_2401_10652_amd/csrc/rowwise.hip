@@ -281,6 +281,43 @@ hipError_t launch_transpose(const void* src, int64_t lds_, void* dst, int64_t ld
 }
 
 // ------------------------------------------------------------------------------------
+// Columns [j0, j0 + nj) of a pair tensor z[n][n][c], gathered with the two position indices
+// swapped: dst[jj][i][:] = z[i][j0 + jj][:].  This is the copy a chunk along the second
+// dimension pays for (AutoChunk section 3.4 counts such "continuous operation" copies as
+// activation memory and penalises chunk dimensions with a small stride): after it the segment
+// is a contiguous block of rows of the transposed tensor.  16-byte accesses; a position's c
+// channels are contiguous on both sides.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+gather_columns(const T* src, T* dst, int64_t n, int64_t j0, int64_t nj, int64_t vec_per_pos, int64_t c) {
+  constexpr int V = Elem<T>::kVec;
+  const int64_t total = n * nj * vec_per_pos;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    const int64_t v = idx % vec_per_pos, pos = idx / vec_per_pos;
+    const int64_t jj = pos % nj, i = pos / nj;            // source order: runs of nj positions are contiguous
+    float t[V];
+    load_vec(src + ((i * n + j0 + jj) * c + v * V), t);
+    store_vec(dst + ((jj * n + i) * c + v * V), t);
+  }
+}
+
+hipError_t launch_gather_columns(const void* src, void* dst, int64_t n, int64_t c, int64_t j0, int64_t nj, int dtype,
+                                 hipStream_t s) {
+  if (n <= 0 || nj <= 0 || c <= 0) return hipSuccess;
+  const int V = dtype == AC_BF16 ? 8 : 4;
+  if (c % V != 0) return hipErrorNotSupported;
+  const int64_t items = n * nj * (c / V);
+  if (dtype == AC_BF16)
+    hipLaunchKernelGGL((gather_columns<bf16_t>), dim3(stream_grid(items)), dim3(256), 0, s, (const bf16_t*)src,
+                       (bf16_t*)dst, n, j0, nj, c / V, c);
+  else
+    hipLaunchKernelGGL((gather_columns<float>), dim3(stream_grid(items)), dim3(256), 0, s, (const float*)src,
+                       (float*)dst, n, j0, nj, c / V, c);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
 // In-place transpose of square matrices, by pairs of 64x64 tiles (bi <= bj): both tiles go
 // to LDS, each is written transposed into the other's place.  grid.x enumerates the tile
 // pairs of the upper triangle, grid.y the matrices.

@@ -102,6 +102,9 @@ namespace ac {
 
 static int elem_bytes(int dtype) { return dtype == AC_BF16 ? 2 : 4; }
 
+// A run [i0, i0 + ni) of rows (or columns) of a pair tensor.
+struct RowSeg { int64_t i0, ni; };
+
 // One walk of the plan: either a dry run (planning) or the real thing.
 struct Walk {
   ac_plan* p;
@@ -385,6 +388,8 @@ struct Walk {
 
   void transformer(const void* x, void* y);
   void pair(const void* x, void* y);
+  const void* pair_segment(const void* zin, const RowSeg& sg, bool col);
+  void pair_store(LinearArgs& o, void* zout, const RowSeg& sg, bool col);
   void tri_mul(int kind, const void* const* W, const void* zin, void* zout);
   void tri_att(int kind, const void* const* W, const void* zin, void* zout);
   void transition(const void* const* W, const void* zin, void* zout);
@@ -530,11 +535,39 @@ static const char* const kTmName[TM_COUNT] = {"ln_in_g", "ln_in_b", "w_ap", "b_a
 static const char* const kTaName[TA_COUNT] = {"ln_g", "ln_b", "w_q", "w_k", "w_v", "w_bias", "w_g", "b_g", "w_o", "b_o"};
 static const char* const kPtName[PT_COUNT] = {"ln_g", "ln_b", "w_1", "b_1", "w_2", "b_2"};
 
-struct RowSeg { int64_t i0, ni; };
 static std::vector<RowSeg> row_segments(int64_t n, int64_t len) {
   std::vector<RowSeg> v;
   for (int64_t i = 0; i < n; i += len) v.push_back(RowSeg{i, std::min<int64_t>(len, n - i)});
   return v;
+}
+
+// Input positions of one segment as a compact [ns * N, c_z] block.  A row chunk is a contiguous
+// run of rows of z already.  A column chunk (section 3.3 makes both legal; section 3.4 charges the
+// smaller stride) is gathered with the position indices swapped, (jj, i) <- z[i, j0 + jj]: from
+// there on the segment is a row segment of the transposed tensor, every module below runs its
+// transposed form on it, and the result rows (jj, i) are stored back to z'[i, j0 + jj].
+const void* Walk::pair_segment(const void* zin, const RowSeg& sg, bool col) {
+  const ac_model_desc& m = p->m;
+  const int64_t N = m.n_res, cz = m.c_z;
+  if (!col) return (const uint8_t*)zin + sg.i0 * N * cz * eb();
+  void* zc = arena.push((uint64_t)sg.ni * N * cz * eb());
+  const int dt = m.dtype;
+  run(K_ELEM, 0.0, 2.0 * sg.ni * N * cz * eb(), "gather_columns",
+      [&] { return launch_gather_columns(zin, zc, N, cz, sg.i0, sg.ni, dt, stream); });
+  return zc;
+}
+
+// Where the rows of a segment's result go: rows of z' (row chunk), or, for a column chunk whose
+// rows are (jj, i), position (i, j0 + jj).
+void Walk::pair_store(LinearArgs& o, void* zout, const RowSeg& sg, bool col) {
+  const ac_model_desc& m = p->m;
+  const int64_t N = m.n_res, cz = m.c_z;
+  if (!col) {
+    o.out = (uint8_t*)zout + sg.i0 * N * cz * eb(); o.ldo = cz;
+  } else {
+    o.out = (uint8_t*)zout + sg.i0 * cz * eb(); o.ldo = cz;
+    o.o_period = N; o.o_s1 = cz; o.o_s2 = N * cz;     // row jj * N + i -> (i * N + j0 + jj) * c_z
+  }
 }
 
 void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) {
@@ -542,6 +575,7 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   const int64_t N = m.n_res, cz = m.c_z, ch = m.c_hidden, R = N * N;
   const int e = eb();
   const bool incoming = kind == AC_REGION_TRIMUL_IN;
+  const bool col = p->set[kind].chunk_dim == AC_DIM_COL;
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t mk0 = arena.mark();
@@ -551,7 +585,7 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
   // ---- whole operands: a and b of every position, channel-major.  Row r = (i, k) of z lands
   // at [c][r]; for the incoming form r = (k, i), and the per-channel matrices are transposed
-  // in place afterwards.
+  // in place afterwards.  (Built in runs of rows of the segment length whatever the chunk dim.)
   const bool fuse_ab = fuses_ln_proj(cz, {ch, ch}), fuse_g = fuses_ln_proj(cz, {cz});
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
@@ -583,64 +617,79 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
     transpose_inplace(a_t, N, R, N, ch);
     transpose_inplace(b_t, N, R, N, ch);
   }
-  // ---- chunked part: rows i of the output
+  // ---- chunked part: rows i (or columns j) of the output.  For columns the contraction runs
+  // with the operands exchanged, out^T[j, i] = sum_k b[j, k] a[i, k], on the gathered segment.
   seg_loop(segs, [&](const RowSeg& sg) {
-    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const int64_t rows = sg.ni * N;
+    const void* zs = pair_segment(zin, sg, col);
     void* t = fuse_g ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* gate = arena.push((uint64_t)rows * cz * e);
-    void* o_c = arena.push((uint64_t)ch * rows * e);   // [c][i][j]
+    void* o_c = arena.push((uint64_t)ch * rows * e);   // [c][segment index][other index]
     void* lo = arena.push((uint64_t)rows * ch * e);
     if (fuse_g) {
       ProjPart pg{};
       pg.w = W[TM_W_G]; pg.bias = W[TM_B_G]; pg.act = AC_ACT_SIGMOID; pg.n = cz; pg.out = gate; pg.ldo = cz;
-      ln_proj(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], rows, cz, {pg});
+      ln_proj(zs, cz, W[TM_LN_IN_G], W[TM_LN_IN_B], rows, cz, {pg});
     } else {
-      ln(at(zin, r0 * cz), cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
+      ln(zs, cz, W[TM_LN_IN_G], W[TM_LN_IN_B], t, cz, rows, cz);
       LinearArgs g{};
       g.a = t; g.lda = cz; g.w = W[TM_W_G]; g.ldw = cz; g.bias = W[TM_B_G]; g.act = AC_ACT_SIGMOID;
       g.out = gate; g.ldo = cz; g.m = rows; g.n = cz; g.k = cz; g.n_split = cz;
       linear(g);
     }
-    contract(at(a_t, sg.i0 * N), N, R, b_t, N, R, o_c, N, rows, sg.ni, N, N, ch);
+    contract(at(col ? b_t : a_t, sg.i0 * N), N, R, col ? a_t : b_t, N, R, o_c, N, rows, sg.ni, N, N, ch);
     ln_channel_major(o_c, rows, W[TM_LN_OUT_G], W[TM_LN_OUT_B], lo, ch, rows, ch);
     LinearArgs o{};
     o.a = lo; o.lda = ch; o.w = W[TM_W_O]; o.ldw = ch; o.bias = W[TM_B_O]; o.mul = gate; o.ldmul = cz;
-    o.resid = at(zin, r0 * cz); o.ldr = cz; o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = ch;
-    o.n_split = cz;
+    o.resid = zs; o.ldr = cz; o.m = rows; o.n = cz; o.k = ch; o.n_split = cz;
+    pair_store(o, zout, sg, col);
     linear(o);
   });
   arena.release(mk0);
 }
 
+// Triangle attention.  Two forms of the per-segment work, named after the node whose row chunks
+// they serve: the STARTING form (one problem per row of the segment: queries along the row, keys
+// and values from the same row, i.e. from the segment itself; bias[h][query][key] whole) and
+// the ENDING form (one problem per column: queries are the segment's rows, keys and values
+// come from every row, so they are whole operands; bias rows of the segment).  Because
+// ending(z) = starting(z^T)^T, a column chunk of either node is the other node's form applied
+// to the gathered (transposed) segment.
 void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) {
   const ac_model_desc& m = p->m;
   const int64_t N = m.n_res, cz = m.c_z, H = m.tri_heads, dh = m.tri_head_dim, hd = H * dh, R = N * N;
   const int e = eb();
   const bool ending = kind == AC_REGION_TRIATT_END;
+  const bool col = p->set[kind].chunk_dim == AC_DIM_COL;
+  const bool ending_form = ending != col;
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t mk0 = arena.mark();
   enter(kind);
   const std::vector<RowSeg> segs = row_segments(N, seg_len(kind));
-  // ---- whole operands.  Starting node: the pair bias [h][j][k].  Ending node: the bias as
-  // [h][i][k] (= projection at position (k, i)), all keys regrouped by column, [(j, k)][h*d]
-  // (the projection stores the row of position (k, j) at (j, k), 256 contiguous bytes at a
-  // time, so that a column's keys are consecutive rows for the attention kernel), and all values
-  // channel-major [h*d][j][k]; the transposes are done in place per channel.
+  // ---- whole operands, built from runs of rows of z.  The pair bias [h][q][k]: the projection at
+  // position (q, k) for the starting node, at (k, q) for the ending node (transposed in place
+  // per head afterwards).  For the ENDING form also all keys as [(problem, key)][h*d] and all
+  // values channel-major [h*d][problem][key]: for the ending node's row chunks the problem is the
+  // column j and the key index the row k of z, so the projection stores the row of position
+  // (k, j) at (j, k), 256 contiguous bytes at a time, and the values are transposed in place per
+  // channel; for the starting node's column chunks problem and key are (i, k) as z has them.
   void* bias = arena.push((uint64_t)H * R * e);
-  void* k_all = ending ? arena.push((uint64_t)R * hd * e) : nullptr;
-  void* v_all = ending ? arena.push((uint64_t)hd * R * e) : nullptr;
-  const bool fuse_a = ending ? fuses_ln_proj(cz, {H, hd, hd}) : fuses_ln_proj(cz, {H});
-  const bool fuse_b = ending ? fuses_ln_proj(cz, {hd, hd}) : fuses_ln_proj(cz, {hd, hd, hd, hd});
+  void* k_all = ending_form ? arena.push((uint64_t)R * hd * e) : nullptr;
+  void* v_all = ending_form ? arena.push((uint64_t)hd * R * e) : nullptr;
+  const bool fuse_a = ending_form ? fuses_ln_proj(cz, {H, hd, hd}) : fuses_ln_proj(cz, {H});
+  const bool fuse_b = ending_form ? fuses_ln_proj(cz, {hd, hd}) : fuses_ln_proj(cz, {hd, hd, hd, hd});
   seg_loop(segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    // keys of the whole tensor: regrouped by column for the ending node, as they are otherwise
+    void* k_dst = !k_all ? nullptr : (ending ? atw(k_all, sg.i0 * hd) : atw(k_all, r0 * hd));
     if (fuse_a) {
       ProjPart pb{}, pk{}, pv{};
       pb.w = W[TA_W_BIAS]; pb.n = H; pb.out_t = atw(bias, r0); pb.t_s2 = 1; pb.t_s3 = R;
-      pk.w = W[TA_W_K]; pk.n = hd; pk.out = k_all ? atw(k_all, sg.i0 * hd) : nullptr; pk.ldo = hd;
-      pk.o_period = N; pk.o_s1 = hd; pk.o_s2 = N * hd;     // row (k - i0, j) -> (j, k)
+      pk.w = W[TA_W_K]; pk.n = hd; pk.out = k_dst; pk.ldo = hd;
+      if (ending) { pk.o_period = N; pk.o_s1 = hd; pk.o_s2 = N * hd; }     // row (k - i0, j) -> (j, k)
       pv.w = W[TA_W_V]; pv.n = hd; pv.out_t = v_all ? atw(v_all, r0) : nullptr; pv.t_s2 = 1; pv.t_s3 = R;
-      if (ending) ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pb, pk, pv});
+      if (ending_form) ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pb, pk, pv});
       else ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pb});
       return;
     }
@@ -650,11 +699,11 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
     b.a = t; b.lda = cz; b.w = W[TA_W_BIAS]; b.ldw = cz; b.m = rows; b.n = H; b.k = cz;
     b.out_t = atw(bias, r0); b.n_split = 0; b.t_s2 = 1; b.t_s3 = R;
     linear(b);
-    if (ending) {
+    if (ending_form) {
       LinearArgs kk{};
       kk.a = t; kk.lda = cz; kk.w = W[TA_W_K]; kk.ldw = cz; kk.m = rows; kk.n = hd; kk.k = cz;
-      kk.out = atw(k_all, sg.i0 * hd); kk.ldo = hd; kk.n_split = hd;
-      kk.o_period = N; kk.o_s1 = hd; kk.o_s2 = N * hd;     // row (k - i0, j) -> (j, k)
+      kk.out = k_dst; kk.ldo = hd; kk.n_split = hd;
+      if (ending) { kk.o_period = N; kk.o_s1 = hd; kk.o_s2 = N * hd; }
       linear(kk);
       LinearArgs vv{};
       vv.a = t; vv.lda = cz; vv.w = W[TA_W_V]; vv.ldw = cz; vv.m = rows; vv.n = hd; vv.k = cz;
@@ -664,30 +713,31 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   });
   if (ending) {
     transpose_inplace(bias, N, R, N, H);
-    transpose_inplace(v_all, N, R, N, hd);
+    if (ending_form) transpose_inplace(v_all, N, R, N, hd);
   }
   // ---- chunked part
   seg_loop(segs, [&](const RowSeg& sg) {
-    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const int64_t rows = sg.ni * N;
+    const void* zs = pair_segment(zin, sg, col);
     void* t = fuse_b ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* q = arena.push((uint64_t)rows * hd * e);
     void* gate = arena.push((uint64_t)rows * hd * e);
     void* ctx = arena.push((uint64_t)rows * hd * e);
-    void* k_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);
-    void* v_seg = ending ? nullptr : arena.push((uint64_t)rows * hd * e);   // [i][h*d][k]
+    void* k_seg = ending_form ? nullptr : arena.push((uint64_t)rows * hd * e);
+    void* v_seg = ending_form ? nullptr : arena.push((uint64_t)rows * hd * e);   // [segment row][h*d][key]
     LinearArgs lq{};
     lq.a = t; lq.lda = cz; lq.w = W[TA_W_Q]; lq.ldw = cz; lq.m = rows; lq.n = hd; lq.k = cz;
     lq.out = q; lq.ldo = hd; lq.n_split = hd;
-    if (fuse_b) {   // LayerNorm, q, gate (and k, v of the row for the starting node) in one kernel
+    if (fuse_b) {   // LayerNorm, q, gate (and k, v of the segment for the starting form) in one kernel
       ProjPart pq{}, pg{}, pk{}, pv{};
       pq.w = W[TA_W_Q]; pq.n = hd; pq.out = q; pq.ldo = hd;
       pg.w = W[TA_W_G]; pg.bias = W[TA_B_G]; pg.act = AC_ACT_SIGMOID; pg.n = hd; pg.out = gate; pg.ldo = hd;
       pk.w = W[TA_W_K]; pk.n = hd; pk.out = k_seg; pk.ldo = hd;
       pv.w = W[TA_W_V]; pv.n = hd; pv.out_t = v_seg; pv.t_period = N; pv.t_s1 = hd * N; pv.t_s2 = 1; pv.t_s3 = N;
-      if (ending) ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg});
-      else ln_proj(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg, pk, pv});
+      if (ending_form) ln_proj(zs, cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg});
+      else ln_proj(zs, cz, W[TA_LN_G], W[TA_LN_B], rows, cz, {pq, pg, pk, pv});
     } else {
-      ln(at(zin, r0 * cz), cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
+      ln(zs, cz, W[TA_LN_G], W[TA_LN_B], t, cz, rows, cz);
       linear(lq);
       LinearArgs lg = lq;
       lg.w = W[TA_W_G]; lg.bias = W[TA_B_G]; lg.act = AC_ACT_SIGMOID; lg.out = gate;
@@ -696,7 +746,7 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
     AttnArgs a{};
     a.heads = (int)H; a.head_dim = (int)dh; a.causal = 0; a.q_offset = 0; a.v_transposed = 1; a.sk = N;
     a.q = q; a.gate = gate; a.ctx = ctx;
-    if (!ending) {
+    if (!ending_form) {
       if (!fuse_b) {
         LinearArgs lk = lq;
         lk.w = W[TA_W_K]; lk.out = k_seg;
@@ -706,14 +756,14 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
         lv.out_t = v_seg; lv.n_split = 0; lv.t_period = N; lv.t_s1 = hd * N; lv.t_s2 = 1; lv.t_s3 = N;
         linear(lv);
       }
-      // one problem per row i: queries j, keys k of the same row
+      // one problem per row of the segment: queries and keys along that row
       a.batch = sg.ni; a.sq = N;
       a.ldq = hd; a.sq_b = N * hd; a.ldg = hd; a.sg_b = N * hd; a.ldc = hd; a.sc_b = N * hd;
       a.k = k_seg; a.ldk = hd; a.sk_b = N * hd;
       a.v = v_seg; a.ldv = N; a.sv_b = hd * N;
       a.bias = bias; a.ld_bias = N; a.s_bias_h = R;
     } else {
-      // one problem per column j: queries i of the segment, keys k of that column
+      // one problem per column: queries are the segment's rows, keys every row of that column
       a.batch = N; a.sq = sg.ni;
       a.ldq = N * hd; a.sq_b = hd; a.ldg = N * hd; a.sg_b = hd; a.ldc = N * hd; a.sc_b = hd;
       a.k = k_all; a.ldk = hd; a.sk_b = N * hd;
@@ -722,8 +772,9 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
     }
     attention(a);
     LinearArgs o{};
-    o.a = ctx; o.lda = hd; o.w = W[TA_W_O]; o.ldw = hd; o.bias = W[TA_B_O]; o.resid = at(zin, r0 * cz); o.ldr = cz;
-    o.out = atw(zout, r0 * cz); o.ldo = cz; o.m = rows; o.n = cz; o.k = hd; o.n_split = cz;
+    o.a = ctx; o.lda = hd; o.w = W[TA_W_O]; o.ldw = hd; o.bias = W[TA_B_O]; o.resid = zs; o.ldr = cz;
+    o.m = rows; o.n = cz; o.k = hd; o.n_split = cz;
+    pair_store(o, zout, sg, col);
     linear(o);
   });
   arena.release(mk0);
@@ -733,23 +784,31 @@ void Walk::transition(const void* const* W, const void* zin, void* zout) {
   const ac_model_desc& m = p->m;
   const int64_t N = m.n_res, cz = m.c_z, F = (int64_t)m.transition_factor * cz;
   const int e = eb();
-  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
-  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  const bool col = p->set[AC_REGION_PAIR_TRANSITION].chunk_dim == AC_DIM_COL;
   enter(AC_REGION_PAIR_TRANSITION);
   seg_loop(row_segments(N, seg_len(AC_REGION_PAIR_TRANSITION)), [&](const RowSeg& sg) {
-    const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
+    const int64_t rows = sg.ni * N;
+    const void* zs = pair_segment(zin, sg, col);
     const bool fuse_up = fuses_ln_proj(cz, {F});
     void* u = fuse_up ? nullptr : arena.push((uint64_t)rows * cz * e);
     void* hid = arena.push((uint64_t)rows * F * e);
     if (fuse_up) {
       ProjPart pu{};
       pu.w = W[PT_W_1]; pu.bias = W[PT_B_1]; pu.act = m.activation; pu.n = F; pu.out = hid; pu.ldo = F;
-      ln_proj(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], rows, cz, {pu});
+      ln_proj(zs, cz, W[PT_LN_G], W[PT_LN_B], rows, cz, {pu});
     } else {
-      ln(at(zin, r0 * cz), cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
+      ln(zs, cz, W[PT_LN_G], W[PT_LN_B], u, cz, rows, cz);
       proj(u, cz, W[PT_W_1], cz, W[PT_B_1], m.activation, nullptr, 0, hid, F, rows, F);
     }
-    proj(hid, F, W[PT_W_2], F, W[PT_B_2], AC_ACT_NONE, at(zin, r0 * cz), cz, atw(zout, r0 * cz), cz, rows, cz);
+    if (m.flags & AC_FLAG_UNFUSED_ELEMENTWISE) {   // standalone passes (row chunks only, checked at plan creation)
+      proj(hid, F, W[PT_W_2], F, W[PT_B_2], AC_ACT_NONE, zs, cz, (uint8_t*)zout + sg.i0 * N * cz * e, cz, rows, cz);
+      return;
+    }
+    LinearArgs o{};
+    o.a = hid; o.lda = F; o.w = W[PT_W_2]; o.ldw = F; o.bias = W[PT_B_2]; o.resid = zs; o.ldr = cz;
+    o.m = rows; o.n = cz; o.k = F; o.n_split = cz;
+    pair_store(o, zout, sg, col);
+    linear(o);
   });
 }
 
@@ -960,9 +1019,9 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
                   "region %d reduces over dim %d: its segments would not concatenate to the unchunked output",
                   r.kind, r.chunk_dim);
     }
-    if (m.workload == AC_PAIR_STACK && r.chunk_dim == AC_DIM_COL) {
+    if (m.workload == AC_PAIR_STACK && r.chunk_dim == AC_DIM_COL && (m.flags & AC_FLAG_UNFUSED_ELEMENTWISE)) {
       delete p;
-      return fail(AC_ERR_UNSUPPORTED, "column chunks of pair regions are legal but not implemented");
+      return fail(AC_ERR_UNSUPPORTED, "column chunks store through the GEMM epilogue: not with AC_FLAG_UNFUSED_ELEMENTWISE");
     }
     if (r.chunk_len < 0) { delete p; return fail(AC_ERR_ARG, "chunk_len must be >= 0"); }
     s.present = true;

@@ -58,13 +58,14 @@ def test_layernorm_channel_major(B, dtype, ch, pos):
     check(host(dst), O.layer_norm(x.T, g, b), dtype)
 
 
-def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, flags=0):
+def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, flags=0, dims=None):
     import torch
     z, w = I.pair_inputs(cfg, bias_std=bias_std, ln_jitter=ln_jitter)
     names = [n for n, _ in I.pair_tensor_shapes(cfg)]
     dz = B.to_device(z, cfg.dtype)
     dw = [B.to_device(w[n], cfg.dtype) for n in names]
-    regs = [(k, B.AC_DIM_ROW, c) for k, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), chunk)]
+    dims = dims or (B.AC_DIM_ROW,) * 5
+    regs = [(k, d, c) for k, d, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), dims, chunk)]
     p = B.Plan(B.pair_desc(cfg, flags=flags), regs)
     info = p.ac_plan_query()
     assert p.weight_names() == names
@@ -130,6 +131,44 @@ def test_pair_fused_projections_equal_the_separate_kernels(B):
         check(host(ym), P.pair_module(name, z, w, cfg.heads, cfg.activation, cfg.ln_eps), "bf16", what=name)
 
 
+@pytest.mark.parametrize("dtype,n,cz,ch,heads,dh", [("f32", 40, 32, 16, 2, 16), ("bf16", 72, 128, 128, 4, 32),
+                                                    ("bf16", 96, 64, 32, 2, 32)])
+def test_pair_column_chunks_equal_the_oracle(B, dtype, n, cz, ch, heads, dh):
+    """Chunks along the second dimension of z (legal by the rules of section 3.3 just as rows are):
+    every module alone and the whole block, against the oracle; every column chunk length gives
+    the same bits; rows and columns mixed in one plan; the gathered copy shows in the planned bytes."""
+    import torch
+    cfg = I.PairConfig("tpc", 44, n, cz, ch, heads, dh, 4, dtype)
+    col = (B.AC_DIM_COL,) * 5
+    z, w, y, info = run_pair(B, cfg, (16,) * 5, dims=col)
+    assert [r.chunk_dim for r in info.regions[:5]] == [B.AC_DIM_COL] * 5
+    ref = P.pair_block(z, w, heads, cfg.activation, cfg.ln_eps)
+    check(host(y), ref, dtype, what="columns of 16", depth=5)
+    outs = [y]
+    for chunk in ((n,) * 5, (24, 8, n, 40, 3)):
+        _, _, yc, _ = run_pair(B, cfg, chunk, dims=col)
+        outs.append(yc)
+    for yc in outs[1:]:
+        assert torch.equal(yc, outs[0])
+    _, _, ym, _ = run_pair(B, cfg, (16, 24, 8, 40, 16), dims=(B.AC_DIM_ROW, B.AC_DIM_COL, B.AC_DIM_COL, B.AC_DIM_ROW, B.AC_DIM_COL))
+    check(host(ym), ref, dtype, what="rows and columns mixed", depth=5)
+    _, _, yr, info_r = run_pair(B, cfg, (16,) * 5)
+    check(host(y), host(yr), dtype, what="columns vs rows", depth=5)
+    assert info.workspace_bytes > info_r.workspace_bytes       # the gathered segment counts
+    names = [nm for nm, _ in I.pair_tensor_shapes(cfg)]
+    dz = B.to_device(z, dtype)
+    dw = [B.to_device(w[nm], dtype) for nm in names]
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+        p = B.Plan(B.pair_desc(cfg, flags=B.AC_FLAG_LISTED_REGIONS_ONLY), [(k, B.AC_DIM_COL, 24)])
+        p.ac_plan_bind_weights(dw)
+        ws = B.empty_workspace(p.ac_plan_query().workspace_bytes)
+        ymod = torch.full_like(dz, float("nan"))
+        p.ac_execute(dz, ymod, ws)
+        torch.cuda.synchronize()
+        p.close()
+        check(host(ymod), P.pair_module(name, z, w, heads, cfg.activation, cfg.ln_eps), dtype, what=name + " columns")
+
+
 def test_pair_legality(B):
     d = B.pair_desc(I.C4)
     for kind in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS):
@@ -137,8 +176,9 @@ def test_pair_legality(B):
             with pytest.raises(B.AcError) as ei:
                 B.Plan(d, [(kind, dim, 64)])
             assert ei.value.status == B.AC_ERR_ILLEGAL_CHUNK_DIM
-        with pytest.raises(B.AcError) as ei:
-            B.Plan(d, [(kind, B.AC_DIM_COL, 64)])
+        B.Plan(d, [(kind, B.AC_DIM_COL, 64)]).close()         # rows and columns are both legal
+        with pytest.raises(B.AcError) as ei:                  # column chunks store through the GEMM epilogue
+            B.Plan(B.pair_desc(I.C4, flags=B.AC_FLAG_UNFUSED_ELEMENTWISE), [(kind, B.AC_DIM_COL, 64)])
         assert ei.value.status == B.AC_ERR_UNSUPPORTED
     with pytest.raises(B.AcError) as ei:
         B.Plan(d, [(B.AC_REGION_FFN, 0, 64)])
