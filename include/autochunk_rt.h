@@ -141,6 +141,9 @@ typedef struct ac_region_info {
   int64_t extent;            /* size of the chunk dim */
   int64_t chunk_len;         /* chosen rows per segment */
   int64_t n_segments;        /* the paper's n */
+  int64_t launches;          /* segment-loop iterations that launch kernels: n_segments, except that the fused
+                                attention, which keeps nothing of a segment in memory, runs consecutive
+                                segments in one launch where that needs no more workspace than the plan's */
   uint64_t model_bytes;      /* paper-style sum X + Y + A/n of this region, ops unfused */
   uint64_t model_bytes_unchunked; /* the same with n = 1 (first activation equation) */
 } ac_region_info;

@@ -47,7 +47,8 @@ class ac_region_desc(C.Structure):
 
 class ac_region_info(C.Structure):
     _fields_ = [("kind", C.c_int32), ("chunk_dim", C.c_int32), ("extent", C.c_int64),
-                ("chunk_len", C.c_int64), ("n_segments", C.c_int64), ("model_bytes", C.c_uint64),
+                ("chunk_len", C.c_int64), ("n_segments", C.c_int64), ("launches", C.c_int64),
+                ("model_bytes", C.c_uint64),
                 ("model_bytes_unchunked", C.c_uint64)]
 
 

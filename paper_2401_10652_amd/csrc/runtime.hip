@@ -96,11 +96,14 @@ struct ac_plan {
   std::vector<hipEvent_t> sync_pool;
   size_t sync_used = 0;
   int sync_needed = 0;
+  int64_t attention_launches = 0;
 };
 
 namespace ac {
 
 static int elem_bytes(int dtype) { return dtype == AC_BF16 ? 2 : 4; }
+
+static uint64_t attention_split_bytes(int64_t rows, int64_t batch, int heads, int head_dim, int ns);
 
 // A run [i0, i0 + ni) of rows (or columns) of a pair tensor.
 struct RowSeg { int64_t i0, ni; };
@@ -127,6 +130,7 @@ struct Walk {
   void enter(int kind) { arena.watch = &region_high[kind]; }
 
   int sync_events = 0;     // planning: events one execute needs for its forks and joins
+  int64_t attention_launches = 0;   // launches of the attention region per layer (segments may share one)
   void fork() {
     if (dry && lanes == 2) ++sync_events;
     if (dry || lanes != 2 || !ok()) return;
@@ -230,7 +234,8 @@ struct Walk {
     if (g.resid) by += (double)g.m * g.n * eb();
     run(K_GEMM, 2.0 * g.m * g.n * g.k, by, "linear", [&] { return launch_linear(g, stream); });
   }
-  void attention(AttnArgs a) {
+  // max_split_bytes caps the fp32 partial results of the launch's key splits (fewer splits if needed)
+  void attention(AttnArgs a, uint64_t max_split_bytes = UINT64_MAX) {
     a.dtype = p->m.dtype;
     double pairs;   // visible (query, key) pairs per head and problem
     if (a.causal) {
@@ -254,6 +259,8 @@ struct Walk {
     const uint64_t mk = arena.mark();
     // (a causal segment sees keys up to its last row only: early segments need fewer runs or none)
     a.n_splits = attention_key_splits(a.sq, keys_seen, a.heads, a.batch, a.head_dim, a.dtype, a.v_transposed);
+    while (a.n_splits > 1 && attention_split_bytes(a.sq, a.batch, a.heads, a.head_dim, a.n_splits) > max_split_bytes)
+      --a.n_splits;
     if (a.n_splits > 1) {
       const uint64_t rh = (uint64_t)a.n_splits * a.batch * a.sq * a.heads;
       a.part_o = arena.push(rh * a.head_dim * 4);
@@ -422,6 +429,50 @@ static std::vector<Seg> token_segments(const ac_model_desc& m, int chunk_dim, in
   return v;
 }
 
+// Bytes of fp32 partial results an attention launch with ns key splits keeps in the arena,
+// exactly as Walk::attention pushes them.
+static uint64_t attention_split_bytes(int64_t rows, int64_t batch, int heads, int head_dim, int ns) {
+  if (ns <= 1) return 0;
+  const uint64_t rh = (uint64_t)ns * batch * rows * heads;
+  return align_up(rh * head_dim * 4, 256) + align_up(rh * 2 * 4, 256);
+}
+// ... of the launch the plan's own segment g would be, with the split count the launch shape calls for
+static uint64_t attention_launch_bytes(const ac_model_desc& m, const Seg& g) {
+  const int64_t keys_seen = m.causal ? std::min<int64_t>(m.seq, g.s0 + g.ns) : m.seq;
+  const int ns = attention_key_splits(g.ns, keys_seen, m.heads, g.nb, m.head_dim, m.dtype, m.dtype == AC_BF16 ? 1 : 0);
+  return attention_split_bytes(g.ns, g.nb, m.heads, m.head_dim, ns);
+}
+
+// The fused attention keeps no intermediate of a segment in memory (the scores live in
+// registers), so consecutive segments of its region may share a launch without raising the
+// bytes the plan needs: runs of consecutive segments (rows of one sequence, then whole
+// sequences of consecutive batch elements) become one launch, whose key splits are capped so
+// that their partial results stay within `bound`, the bytes of the region's largest single
+// segment.  The segments are still computed block by block in order; what is saved is the fixed
+// cost of a launch and its under-filled tail per segment (section 3.4's computation-density
+// term).  A pure function of the shapes: planning and execution agree.
+static std::vector<Seg> attention_launch_groups(const ac_model_desc& m, const std::vector<Seg>& segs, uint64_t& bound) {
+  bound = 0;
+  for (const Seg& sg : segs) bound = std::max(bound, attention_launch_bytes(m, sg));
+  std::vector<Seg> rows;
+  for (const Seg& sg : segs) {
+    if (!rows.empty() && rows.back().nb == 1 && sg.nb == 1 && rows.back().b0 == sg.b0 &&
+        sg.s0 == rows.back().s0 + rows.back().ns)
+      rows.back().ns += sg.ns;
+    else
+      rows.push_back(sg);
+  }
+  std::vector<Seg> out;
+  for (const Seg& sg : rows) {
+    if (!out.empty() && out.back().s0 == 0 && sg.s0 == 0 && out.back().ns == m.seq && sg.ns == m.seq &&
+        sg.b0 == out.back().b0 + out.back().nb)
+      out.back().nb += sg.nb;
+    else
+      out.push_back(sg);
+  }
+  return out;
+}
+
 void Walk::transformer(const void* x, void* y) {
   const ac_model_desc& m = p->m;
   const int64_t T = (int64_t)m.batch * m.seq, S = m.seq, d = m.d_model, F = m.d_ffn;
@@ -481,7 +532,11 @@ void Walk::transformer(const void* x, void* y) {
     }
     // ---- region 2: attention of a query segment over whole k, v; writes its rows of the context
     enter(AC_REGION_ATTENTION);
-    seg_loop(token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION)), [&](const Seg& sg) {
+    std::vector<Seg> attn_segs = token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION));
+    uint64_t split_bound = UINT64_MAX;
+    if (!stored_scores) attn_segs = attention_launch_groups(m, attn_segs, split_bound);
+    attention_launches = (int64_t)attn_segs.size();
+    seg_loop(attn_segs, [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0;
       AttnArgs a{};
       a.q = at(qk, r0 * ldqk); a.ldq = ldqk; a.sq_b = S * ldqk;
@@ -495,7 +550,7 @@ void Walk::transformer(const void* x, void* y) {
         a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1;
         attention_materialized(a);
       } else {
-        attention(a);
+        attention(a, split_bound);
       }
     });
 
@@ -907,7 +962,7 @@ static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& f
   arena_bytes = wk.arena.high;
   flops = wk.flops;
   if (region_high) memcpy(region_high, wk.region_high, sizeof(wk.region_high));
-  if (!unchunked) p->sync_needed = wk.sync_events;
+  if (!unchunked) { p->sync_needed = wk.sync_events; p->attention_launches = wk.attention_launches; }
 }
 
 static uint64_t io_bytes(const ac_model_desc& m) {
@@ -1176,6 +1231,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     ri.extent = s.extent;
     ri.chunk_len = s.chunk_len;
     ri.n_segments = ceil_div(s.extent, s.chunk_len);
+    ri.launches = k == AC_REGION_ATTENTION && m.workload == AC_TRANSFORMER_STACK ? p->attention_launches : ri.n_segments;
     ri.model_bytes = model_bytes(m, k, rows_of(s, s.chunk_len));
     ri.model_bytes_unchunked = model_bytes(m, k, rows_of(s, s.extent));
     inf.peak_bytes_model = std::max(inf.peak_bytes_model, ri.model_bytes);

@@ -128,7 +128,8 @@ def test_budget_sized_plan_runs(B):
     # attention core (fp32 partial results of its key splits) have to be cut
     budget = 9 << 19
     y, info = r.run(regions(B, 0, 0, 0), budget=budget)
-    assert [x.n_segments for x in info.regions[:4]] == [1, 3, 1, 3] and info.regions[3].chunk_len == 384
+    assert [x.n_segments for x in info.regions[:4]] == [1, 2, 1, 3] and info.regions[3].chunk_len == 384
+    assert info.regions[1].launches == 1       # the attention's two segments share a launch with capped key splits
     assert info.peak_bytes_planned <= budget < info.peak_bytes_unchunked_planned
     check(host(y), ref, "bf16")
     # ... and, on request, the paper-style bytes of the unfused graph as well: the attention core is cut
@@ -151,7 +152,9 @@ def test_profiling_reports_kernel_classes(B):
     p.ac_execute(r.dx, y, ws)
     stats = {s["name"]: s for s in p.ac_plan_read_profile()}
     assert set(stats) == {"gemm", "attention", "layernorm"}
-    assert stats["gemm"]["launches"] == 2 * 2 * 4 and stats["attention"]["launches"] == 4
+    # per layer: 4 GEMMs and 2 LayerNorms per segment; the attention's two segments share one launch
+    assert stats["gemm"]["launches"] == 2 * 2 * 4 and stats["attention"]["launches"] == 2
+    assert info.regions[1].n_segments == 2 and info.regions[1].launches == 1
     assert stats["layernorm"]["launches"] == 8
     total = sum(s["flops"] for s in stats.values())
     assert abs(total - info.flops_per_execute) <= 1e-9 * total

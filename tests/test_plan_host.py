@@ -65,16 +65,39 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None,
     if cfg.layers > 1:
         whole += al(T * d * e)
     r1 = al(c_qkv * d * e)
-    ns = key_splits_by_hand(c_attn, cfg.seq, cfg.heads, 1, cfg.head_dim, cfg.dtype)
-    parts = (al(ns * c_attn * d * 4) + al(ns * c_attn * cfg.heads * 8)) if ns > 1 else 0
-    r2 = parts
+    groups = attention_groups_by_hand(cfg, c_attn)
+    r2 = max(b for _, _, b in groups)
     if stored_scores:                      # scores and probabilities of one segment, every head
         r2 = 2 * al(cfg.heads * c_attn * cfg.seq * e)
+        groups = [None] * -(-cfg.seq // c_attn)
     r2b = al(c_out * d * e) if unfused else 0
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
-    # two segments in flight: a region with more than one segment holds two per-segment sets
+    # two segments in flight: a region with more than one segment (launch) holds two per-segment sets
     mult = lambda c: lanes if c < cfg.seq else 1
-    return whole + max(r1 * mult(c_qkv), r2 * mult(c_attn), r2b * mult(c_out), r3 * mult(c_ffn))
+    return whole + max(r1 * mult(c_qkv), r2 * (lanes if len(groups) > 1 else 1), r2b * mult(c_out), r3 * mult(c_ffn))
+
+
+def attention_launch_bytes_by_hand(cfg, s0, rows):
+    """fp32 partial results (unnormalised context, running maximum and sum) of the key splits of one
+    attention launch over query rows [s0, s0 + rows) of one sequence; a causal launch splits the keys
+    its last row sees."""
+    keys = min(cfg.seq, s0 + rows) if cfg.causal else cfg.seq
+    ns = key_splits_by_hand(rows, keys, cfg.heads, 1, cfg.head_dim, cfg.dtype)
+    return 0 if ns <= 1 else al(ns * rows * cfg.d_model * 4) + al(ns * rows * cfg.heads * 8)
+
+
+def attention_groups_by_hand(cfg, c_attn):
+    """The fused attention keeps nothing of a segment in memory, so the consecutive segments of a
+    sequence share one launch, whose key splits are capped so that their partial results stay within
+    those of the plan's largest single segment.  Returns (first row, rows, bytes) per launch."""
+    segs = [(s, min(c_attn, cfg.seq - s)) for s in range(0, cfg.seq, c_attn)]
+    bound = max(attention_launch_bytes_by_hand(cfg, s, r) for s, r in segs)
+    rows = cfg.seq
+    ns = key_splits_by_hand(rows, cfg.seq, cfg.heads, 1, cfg.head_dim, cfg.dtype)
+    size = lambda n: 0 if n <= 1 else al(n * rows * cfg.d_model * 4) + al(n * rows * cfg.heads * 8)
+    while ns > 1 and size(ns) > bound:
+        ns -= 1
+    return [(0, rows, size(ns))]
 
 
 @pytest.mark.parametrize("cfg,c", [(I.C1, (64, 64, 64)), (I.C3, (512, 512, 512)), (I.C2, (1024, 1024, 1024)),
