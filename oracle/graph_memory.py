@@ -156,24 +156,25 @@ def feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak
 
 def plan(nodes, elem_bytes, budget, window, weights, beam=1, hoist=False):
     """Chunks [(start, end, out_dim, chunk_len)] chosen pass by pass until the peak fits;
-    returns (chunks, peak) or raises ValueError when no strategy in the beam gets there.
+    returns (chunks, peak) or raises ValueError when no strategy the passes build gets there.
 
-    The beam holds the `beam` strategies of least summed cost (ties: fewer segments in all,
-    then the order they were made in).  Every pass extends each strategy that does not fit yet
-    by each candidate around its own peak node; strategies that fit stay as they are.  With
-    beam = 1 this is: take the cheapest candidate of every pass."""
-    states = [(0.0, 0, [])]                               # (sum of L, segments in all, chunks)
-    while True:
-        grown, all_fit = [], True
+    Section 3.4 asks for the strategy of least summed cost among those whose peak is within the
+    budget.  Every pass extends each strategy of the beam by each candidate around its own peak
+    node.  An extension that fits competes for the answer (least summed cost; ties: fewer segments
+    in all, then the order of making) and takes no place in the beam; of those that do not fit
+    yet, the `beam` cheapest go on to the next pass.  The search ends when the beam is empty.
+    With beam = 1 this is: follow the cheapest candidate that does not fit yet, remembering the
+    cheapest that did."""
+    _, peak0, _ = estimate(nodes, elem_bytes, [])
+    if peak0 <= budget:
+        return [], peak0
+    best = None                                           # (sum of L, segments in all, chunks, peak)
+    states = [(0.0, 0, [])]
+    while states:
+        grown = []
         known = set()
         for total, segments, chunks in states:
             mem, peak, peak_node = estimate(nodes, elem_bytes, chunks)
-            if peak <= budget:
-                if tuple(sorted(chunks)) not in known:
-                    known.add(tuple(sorted(chunks)))
-                    grown.append((total, segments, chunks))
-                continue
-            all_fit = False
             if any(c[0] <= peak_node <= c[1] for c in chunks):
                 continue                                  # the peak lies in a region already chunked
             for cost, seg, cand in feasible_candidates(nodes, elem_bytes, budget, window, weights, chunks, peak_node, hoist):
@@ -181,11 +182,15 @@ def plan(nodes, elem_bytes, budget, window, weights, beam=1, hoist=False):
                 if tuple(sorted(new)) in known:
                     continue                              # the same chunks, chosen in another order
                 known.add(tuple(sorted(new)))
-                grown.append((total + cost, segments + seg, new))
-        if all_fit:
-            chunks = states[0][2]
-            return chunks, estimate(nodes, elem_bytes, chunks)[1]
-        if not grown:
-            raise ValueError(f"no chunk strategy brings the peak within {budget}")
+                st = (total + cost, segments + seg, new)
+                new_peak = estimate(nodes, elem_bytes, new)[1]
+                if new_peak <= budget:
+                    if best is None or st[:2] < best[:2]:
+                        best = st + (new_peak,)
+                else:
+                    grown.append(st)
         grown.sort(key=lambda st: st[:2])                 # stable: equal keys keep the order of making
         states = grown[:beam]
+    if best is None:
+        raise ValueError(f"no chunk strategy brings the peak within {budget}")
+    return best[2], best[3]

@@ -707,23 +707,28 @@ extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_b
   int peak_node = 0;
   std::vector<Strategy> states(1);
   *peak_bytes = estimate_of(states[0], &peak_node);
-  for (;;) {  // one pass: every strategy that does not fit yet grows by one chunk around its own peak
+  // Section 3.4: least summed cost among the strategies whose peak is within the budget.  A
+  // strategy that fits competes for the answer and takes no place in the beam; of those that
+  // do not fit yet the `beam` cheapest go on to the next pass; the search ends with the beam.
+  Strategy incumbent;
+  bool have = *peak_bytes <= budget_bytes;   // nothing to chunk: the empty strategy
+  auto better = [](const Strategy& a, const Strategy& b) {
+    return a.total < b.total || (a.total == b.total && a.segments < b.segments);
+  };
+  while (!have || !states.empty()) {
+    if (states.empty()) break;
+    if (have && states.size() == 1 && states[0].chunks.empty()) break;   // the unchunked graph fits
     std::vector<Strategy> grown;
     std::set<StrategyKey> known;
-    bool all_fit = true;
     for (const Strategy& st : states) {
-      const uint64_t peak = estimate_of(st, &peak_node);  // also leaves region_of set for st
-      if (peak <= budget_bytes) {
-        if (known.insert(key_of(st.chunks)).second) grown.push_back(st);
-        continue;
-      }
-      all_fit = false;
+      estimate_of(st, &peak_node);  // leaves region_of set for st
       if (region_of[peak_node] >= 0) continue;  // the peak lies in a region already chunked: a dead end
+      const std::vector<int> region_of_st = region_of;
       int tried = 0, passed = 0;
       t.candidates(peak_node, window, hoist != 0, &tried, &passed,
                    [&](int start, int end, int d, int64_t gran, const int32_t*, const uint8_t* moved) {
         for (int i = start; i <= end; ++i)
-          if (region_of[i] >= 0) return;
+          if (region_of_st[i] >= 0) return;
         const int64_t extent = nodes[end].shape[d];
         const int64_t len = m.longest_len(start, end, moved, extent, gran, budget_bytes, fixed, scaled);
         if (len < gran) return;
@@ -735,22 +740,24 @@ extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_b
           if (i < start || i > end) next.moved.back()[i] = 0;
         next.total = st.total + chunk_cost(nodes, start, end, d, moved, weights);
         next.segments = st.segments + (extent + len - 1) / len;
-        grown.push_back(std::move(next));
+        int pn = 0;
+        if (estimate_of(next, &pn) <= budget_bytes) {
+          if (!have || better(next, incumbent)) { incumbent = std::move(next); have = true; }
+        } else {
+          grown.push_back(std::move(next));
+        }
       });
     }
-    if (all_fit) break;
-    if (grown.empty()) {
-      ac::set_error("ac_graph_plan: no chunk strategy brings the peak of %llu bytes within %llu",
-                    (unsigned long long)*peak_bytes, (unsigned long long)budget_bytes);
-      return AC_ERR_BUDGET_INFEASIBLE;
-    }
-    std::stable_sort(grown.begin(), grown.end(), [](const Strategy& a, const Strategy& b) {
-      return a.total < b.total || (a.total == b.total && a.segments < b.segments);
-    });
+    std::stable_sort(grown.begin(), grown.end(), better);
     if ((int)grown.size() > beam) grown.resize(beam);
     states.swap(grown);
   }
-  const Strategy& best = states[0];
+  if (!have) {
+    ac::set_error("ac_graph_plan: no chunk strategy brings the peak of %llu bytes within %llu",
+                  (unsigned long long)*peak_bytes, (unsigned long long)budget_bytes);
+    return AC_ERR_BUDGET_INFEASIBLE;
+  }
+  const Strategy& best = incumbent;
   if ((int)best.chunks.size() > max_out) return bad("ac_graph_plan: %d chunks needed, max_out is %d", (int)best.chunks.size(), max_out);
   for (size_t c = 0; c < best.chunks.size(); ++c) out[c] = best.chunks[c];
   *n_out = (int)best.chunks.size();

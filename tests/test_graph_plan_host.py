@@ -88,7 +88,8 @@ def test_plan_equals_the_oracle_on_random_graphs():
                 rescued += got is None and wide is not None
             both_plans(on, ln, 2, int(whole * frac), 7, WEIGHTS[seed % len(WEIGHTS)], 2, hoist=True)
 
-    assert planned > 40 and failed > 20 and rescued > 5
+    # (a beam of 1 now remembers every extension that fits, so a wider beam rescues it less often than it did)
+    assert planned > 40 and failed > 20 and rescued >= 1
 
 
 def test_plan_equals_the_oracle_on_the_block_graph():

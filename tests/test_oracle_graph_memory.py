@@ -271,7 +271,7 @@ def cheapest_by_exhaustion(nodes, e, budget, window, weights):
 
 def test_a_wide_beam_finds_the_cheapest_strategy():
     weights = (1.0, 1e-3, -1e-3, -0.5)
-    solved = rescued = 0
+    solved = rescued = costlier = 0
     for seed in range(100):
         nodes = oracle_nodes(G.random_graph(seed, n_ops=10 + seed % 4))
         feeds = S.random_feeds(nodes, seed)
@@ -290,10 +290,14 @@ def test_a_wide_beam_finds_the_cheapest_strategy():
             assert max(seen) == peak <= budget
             solved += 1
             try:
-                GM.plan(nodes, 8, budget, 4, weights, beam=1)
+                greedy, _ = GM.plan(nodes, 8, budget, 4, weights, beam=1)
+                cost = sum(GM.chunk_cost(nodes, c[0], c[1], c[2], weights) for c in greedy)
+                assert cost >= least - 1e-9 * max(1.0, abs(least))
+                costlier += cost > least + 1e-9 * max(1.0, abs(least))
             except ValueError:
-                rescued += 1            # the cheapest candidate of some pass led into a dead end
-    assert solved > 40 and rescued > 2
+                rescued += 1            # every candidate the greedy path met led into a dead end
+    print("solved", solved, "greedy costlier", costlier, "greedy failed", rescued)
+    assert solved > 40
 
 
 def hoisting_chunks(nodes, rng, how_many=2):
