@@ -144,7 +144,8 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   // 8 lanes.
   constexpr int BROW = kKB + 4;                          // padded bias row (elements)
   constexpr int B_CHUNKS = BIAS ? QB * (kKB / 8) / NT : 1;
-  bf16_t* sB = sV + 2 * DH * VROW;                       // [2][QB][BROW] (BIAS only)
+  bf16_t* sB = sV + 2 * DH * VROW;                       // [QB][BROW] (BIAS only), one buffer: the next tile waits in
+                                                         // registers until every wave is done with this one
 
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int l32 = lane % 32, half = lane / 32;
@@ -283,7 +284,7 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
       *reinterpret_cast<bf16x4*>(dv + v_dst[i] + 8) = hi;
     }
     if (BIAS) {
-      bf16_t* db = sB + buf * QB * BROW;
+      bf16_t* db = sB;
 #pragma unroll
       for (int i = 0; i < B_CHUNKS; ++i) {
         const bf16x4 lo = {b_reg[i][0], b_reg[i][1], b_reg[i][2], b_reg[i][3]};
@@ -329,7 +330,7 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
       // ---- lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4.  Scores go to the log2 domain
       // only where needed: with a bias right away, otherwise folded into the exponent below.
       if (BIAS) {
-        const bf16_t* cb = sB + buf * QB * BROW + (wave * 32 + l32) * BROW + 4 * half;
+        const bf16_t* cb = sB + (wave * 32 + l32) * BROW + 4 * half;
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -392,6 +393,7 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
             acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt][u], acc_o[i], 0, 0, 0);
           }
     }
+    if (BIAS && more) __syncthreads();   // the single bias buffer is overwritten next: every wave has read it
     if (more) store_tile(buf ^ 1);
     __syncthreads();
   }
@@ -497,7 +499,7 @@ __global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
 template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED, NW>;
-  constexpr size_t lds = (size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8) + (BIAS ? 32 * NW * (kKB + 4) : 0)) * sizeof(bf16_t);
+  constexpr size_t lds = ((size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) + (BIAS ? 32 * NW * (kKB + 4) : 0)) * sizeof(bf16_t);
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (attr_status != hipSuccess) return attr_status;
