@@ -157,7 +157,17 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   const int64_t bq = t / ns;
   const int64_t bh = bq / nqb;
   int qb = (int)(bq % nqb);
-  if (CAUSAL) qb = nqb - 1 - qb;      // longest rows first
+  if (CAUSAL) {
+    // Longest rows first, in a snake over runs of 32 (the CUs of an XCD, which take consecutive
+    // blocks in turn): the first 32 blocks of a head are its longest in descending order, the next
+    // 32 the following ones in ascending order, and so on, so that when all blocks of a launch are
+    // resident at once (one sequence of a few thousand rows) every CU holds about the same number
+    // of key tiles; with more blocks than places the order is still longest-first run by run.
+    const int run = qb / 32, col = qb % 32;
+    const int len = nqb - run * 32 < 32 ? nqb - run * 32 : 32;
+    const int rank = run * 32 + ((run & 1) ? len - 1 - col : col);
+    qb = nqb - 1 - rank;
+  }
   // Problem-major order keeps the heads of one problem together (their q/k/v rows interleave in
   // memory).  Head-major order (set by the host when a bias shared by all problems is the
   // largest operand) gives each XCD a run of problems of ONE head, so that head's bias stays
