@@ -20,6 +20,8 @@
 // Generic kernel (fp32, odd head sizes, row-major v): one thread per query row.
 #include "common.h"
 
+#include <type_traits>
+
 namespace ac {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -121,11 +123,24 @@ __global__ void __launch_bounds__(128) attention_rows(AttnArgs a) {
 constexpr int kQB = 128;   // query rows per block of the 4-wave kernel (32 per wave)
 constexpr int kKB = 64;    // keys per LDS tile
 
+// Which instantiations run the software-pipelined loop with direct global-to-LDS staging: no bias tile to
+// stage, whole key tiles only (a direct load cannot zero-fill), heads of 64 or 128.  The loop needs two
+// score tiles in registers, which leaves two waves per SIMD where the plain loop has three at 64-wide
+// heads; a causal launch at that width (many short blocks, three per CU co-resident) measured faster plain.
+constexpr bool attention_pipelined(int dh, bool causal, bool bias, bool ragged) {
+  return !bias && !ragged && (dh == 128 || (dh == 64 && !causal));
+}
+constexpr size_t attention_lds_bytes(int dh, bool causal, bool bias, bool ragged, int nw) {
+  return attention_pipelined(dh, causal, bias, ragged)
+             ? (size_t)2 * 1040 * (kKB * dh * 2 / 1024 + dh * kKB * 2 / 1024)
+             : ((size_t)2 * (kKB * (dh + 8) + dh * (kKB + 8)) + (bias ? 32 * nw * (kKB + 4) : 0)) * sizeof(bf16_t);
+}
+
 // RAGGED: the key count is not a multiple of the tile (or of the 16-byte vector): loads are
 // guarded and keys past the end are masked.  The other instantiation has no bounds work in
 // its main loop.
 template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
-__global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
+__global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS, RAGGED) ? 2 : 1) attention_mfma_bf16(AttnArgs a) {
   constexpr int NT = 64 * NW;         // threads
   constexpr int QB = 32 * NW;         // query rows per block
   constexpr int KROW = DH + 8;        // padded K row (elements): conflict-free 128-bit reads
@@ -135,6 +150,7 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   constexpr int K_CHUNKS = kKB * (DH / 8) / NT;   // 16-byte chunks per thread, K tile
   constexpr int V_CHUNKS = DH * (kKB / 8) / NT;   // and V^T tile
   static_assert(K_CHUNKS >= 1 && V_CHUNKS >= 1, "tile too small for the block");
+  constexpr bool PIPE = attention_pipelined(DH, CAUSAL, BIAS, RAGGED);
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);     // [2][kKB][KROW]
   bf16_t* sV = sK + 2 * kKB * KROW;                      // [2][DH][VROW]
@@ -314,98 +330,335 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_bf16(AttnArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = rsqrtf((float)DH) * kLog2e;
 
-  if (tile_lo < tile_hi) { load_tile(tile_lo * kKB); store_tile(tile_lo & 1); }
-  __syncthreads();
+  if constexpr (!PIPE) {
+    if (tile_lo < tile_hi) { load_tile(tile_lo * kKB); store_tile(tile_lo & 1); }
+    __syncthreads();
 
-  for (int kt = tile_lo; kt < tile_hi; ++kt) {
-    const int buf = kt & 1;
-    const int k0 = kt * kKB;
-    const bool more = kt + 1 < tile_hi;
-    if (more) load_tile(k0 + kKB);
+    for (int kt = tile_lo; kt < tile_hi; ++kt) {
+      const int buf = kt & 1;
+      const int k0 = kt * kKB;
+      const bool more = kt + 1 < tile_hi;
+      if (more) load_tile(k0 + kKB);
 
-    if (wave_active && (!CAUSAL || k0 <= wave_last)) {
-      // ---- S^T = K Q^T for two 32-key tiles
-      f32x16 acc_s[2];
-      const bf16_t* ck = sK + buf * kKB * KROW + l32 * KROW + half * 8;
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[tt][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ck + tt * 32 * KROW + ks * 16);
-          acc_s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[tt], 0, 0, 0);
+      if (wave_active && (!CAUSAL || k0 <= wave_last)) {
+        // ---- S^T = K Q^T for two 32-key tiles
+        f32x16 acc_s[2];
+        const bf16_t* ck = sK + buf * kKB * KROW + l32 * KROW + half * 8;
+  #pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+  #pragma unroll
+          for (int r = 0; r < 16; ++r) acc_s[tt][r] = 0.f;
+  #pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ck + tt * 32 * KROW + ks * 16);
+            acc_s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[tt], 0, 0, 0);
+          }
         }
-      }
-      // ---- lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4.  Scores go to the log2 domain
-      // only where needed: with a bias right away, otherwise folded into the exponent below.
-      if (BIAS) {
-        const bf16_t* cb = sB + (wave * 32 + l32) * BROW + 4 * half;
-#pragma unroll
+        // ---- lane holds keys k0 + tt*32 + 8*(r/4) + 4*half + r%4.  Scores go to the log2 domain
+        // only where needed: with a bias right away, otherwise folded into the exponent below.
+        if (BIAS) {
+          const bf16_t* cb = sB + (wave * 32 + l32) * BROW + 4 * half;
+  #pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+  #pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+              const bf16x4 bb = *reinterpret_cast<const bf16x4*>(cb + tt * 32 + 8 * g4);
+  #pragma unroll
+              for (int j = 0; j < 4; ++j)
+                acc_s[tt][4 * g4 + j] = fmaf(acc_s[tt][4 * g4 + j], scale2, bf2f(bb[j]) * kLog2e);
+            }
+        }
+        const bool need_mask = (RAGGED && k0 + kKB > sk) || (CAUSAL && k0 + kKB - 1 > wave_first);
+        if (need_mask) {
+  #pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+  #pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int kj = k0 + tt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+              if ((RAGGED && kj >= sk) || (CAUSAL && kj > qpos)) acc_s[tt][r] = -INFINITY;
+            }
+        }
+        float mx = acc_s[0][0];
+  #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(cb + tt * 32 + 8 * g4);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              acc_s[tt][4 * g4 + j] = fmaf(acc_s[tt][4 * g4 + j], scale2, bf2f(bb[j]) * kLog2e);
-          }
-      }
-      const bool need_mask = (RAGGED && k0 + kKB > sk) || (CAUSAL && k0 + kKB - 1 > wave_first);
-      if (need_mask) {
-#pragma unroll
+  #pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[tt][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if (!BIAS) mx *= scale2;                       // scale2 > 0: max commutes with the scaling
+        // rescale only when some row of the wave saw a new maximum
+        if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
+          m_run = m_new;
+          l_run *= alpha;
+  #pragma unroll
+          for (int i = 0; i < DT; ++i)
+  #pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+        }
+        float psum = 0.f;
+        bf16x8 pf[2][2];
+  #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
+  #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int kj = k0 + tt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if ((RAGGED && kj >= sk) || (CAUSAL && kj > qpos)) acc_s[tt][r] = -INFINITY;
+            const float e = BIAS ? acc_s[tt][r] - m_run : fmaf(acc_s[tt][r], scale2, -m_run);
+            const float p = __builtin_amdgcn_exp2f(e);
+            psum += p;
+            pf[tt][r / 8][r % 8] = f2bf(p);
           }
+        l_run += psum;
+        // ---- O^T += V^T P^T
+        const bf16_t* cv = sV + buf * DH * VROW + l32 * VROW + 8 * half;
+  #pragma unroll
+        for (int i = 0; i < DT; ++i)
+  #pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+  #pragma unroll
+            for (int u = 0; u < 2; ++u) {
+              const bf16x8 vf = *reinterpret_cast<const bf16x8*>(cv + i * 32 * VROW + (tt * 2 + u) * 16);
+              acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt][u], acc_o[i], 0, 0, 0);
+            }
       }
-      float mx = acc_s[0][0];
+      if (BIAS && more) __syncthreads();   // the single bias buffer is overwritten next: every wave has read it
+      if (more) store_tile(buf ^ 1);
+      __syncthreads();
+    }
+
+  } else {
+    // Software-pipelined loop.  The matrix instructions of the NEXT tile's scores are issued among
+    // the exponentials of THIS tile, and this tile's probability-value products among the maximum of
+    // the next: a SIMD overlaps the matrix and the vector instructions of one wave far better than
+    // those of two different waves, and at 64- and 128-wide heads the two kinds of work are about
+    // equal.  K is therefore staged one tile ahead of V: iteration kt reads K(kt+1) and V(kt) while
+    // K(kt+2) and V(kt+1) arrive.
+    //
+    // Tiles come in by direct global-to-LDS loads (no staging registers, no LDS store instructions):
+    // one wave instruction moves 64 x 16 bytes into 1 KB of consecutive LDS, i.e. RPI whole rows of
+    // the tile.  Row r goes to group r % G at index r / G, and groups are 1 KB + 16 bytes apart, so
+    // any 8 consecutive lanes of a fragment read (8 consecutive rows, same 16-byte column) fall into 8
+    // different 16-byte slots modulo 128 bytes, which is what makes a 128-bit LDS read conflict free.
+    constexpr int GB = 1040;                       // bytes from one group to the next
+    constexpr int KRB = DH * 2;                    // bytes per K row
+    constexpr int KG = kKB * KRB / 1024;           // groups (load instructions) per K tile: 16 or 8
+    constexpr int VRB = kKB * 2;                   // bytes per V^T row
+    constexpr int VG = DH * VRB / 1024;            // groups per V^T tile: 16 or 8
+    static_assert((KG == 16 || (KG == 8 && KRB == 128)) && (VG == 16 || VG == 8), "row-to-group rule needs 8 or 16 groups");
+    static_assert(KG % NW == 0 && VG % NW == 0, "groups are dealt to the waves in turn");
+    constexpr int KBUF = KG * GB, VBUF = VG * GB;  // bytes per buffer
+    unsigned char* const sKb = smem_raw;           // [2][KBUF]
+    unsigned char* const sVb = smem_raw + 2 * KBUF;   // [2][VBUF]
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+
+    // Global source of a load instruction: a wave-uniform base (scalar registers; advanced per tile and per
+    // instruction) plus this lane's byte offset inside the wave's first group.
+    // (K rows sit in LDS in the order the lanes of a score MFMA read them: LDS row x holds key swap23(x), see below)
+    auto swap23 = [](int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); };
+    const uint32_t kg_off = (uint32_t)(swap23((lane / (KRB / 16)) * KG + wave) * (int)a.ldk + (lane % (KRB / 16)) * 8) * 2u;
+    const uint32_t vg_off = (uint32_t)(((lane / (VRB / 16)) * VG + wave) * (int)a.ldv + (lane % (VRB / 16)) * 8) * 2u;
+    auto uniform = [](const void* ptr) {
+      const uint64_t v = (uint64_t)ptr;
+      const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+      return (const unsigned char*)(((uint64_t)hi << 32) | lo);
+    };
+    const unsigned char* const kg_base = uniform(kbase);
+    const unsigned char* const vg_base = uniform(vbase);
+    auto dma_k = [&](int kt, int buf) {
+      const unsigned char* src = kg_base + (int64_t)kt * kKB * a.ldk * 2;
+#pragma unroll
+      for (int j = 0; j < KG / NW; ++j)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (int64_t)swap23(j * NW) * a.ldk * 2 + kg_off),
+                                         (__attribute__((address_space(3))) void*)(sKb + buf * KBUF + (wave_u + NW * j) * GB), 16, 0, 0);
+    };
+    auto dma_v = [&](int kt, int buf) {
+      const unsigned char* src = vg_base + (int64_t)kt * kKB * 2;
+#pragma unroll
+      for (int j = 0; j < VG / NW; ++j)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (int64_t)j * NW * a.ldv * 2 + vg_off),
+                                         (__attribute__((address_space(3))) void*)(sVb + buf * VBUF + (wave_u + NW * j) * GB), 16, 0, 0);
+    };
+    auto arrived = [&]() {   // this wave's loads have landed, then every wave's
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+      __syncthreads();
+    };
+
+    // The score MFMA takes key pi(m) of a 32-key half as its row m, pi = m with bits 2 and 3 swapped:
+    // a lane's accumulator registers 8u .. 8u+7 then hold the 8 CONSECUTIVE keys 16u + 8 half + (0..7),
+    // so the probabilities go to the second MFMA as they are and its V^T fragment is one 16-byte read
+    // of an unpermuted row.
+    // K is laid out in LDS by MFMA row, not by key (LDS row x = key pi(x) of the tile), so that here too 8
+    // consecutive lanes read 8 different 16-byte slots modulo 128 bytes.
+    const unsigned char* const k_frag = sKb + (l32 % KG) * GB + (l32 / KG) * KRB + half * 16;
+    const unsigned char* const v_frag = sVb + (l32 % VG) * GB + (l32 / VG) * VRB + half * 16;
+
+    int w_hi = tile_hi;                               // this wave computes tiles [tile_lo, w_hi)
+    if (CAUSAL) { const int vis = wave_last / kKB + 1; if (vis < w_hi) w_hi = vis; }
+    if (!wave_active) w_hi = tile_lo;
+    float m_exp = 0.f;   // m_run, or 0 while the row has seen no key: exp2(-inf - m_exp) is then 0, not NaN
+
+    // S^T = K Q^T of the tile in K buffer `buf`, one 32-key half after the other
+    auto scores = [&](f32x16 (&s)[2], int buf) {
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[tt][r]);
+        for (int r = 0; r < 16; ++r) s[tt][r] = 0.f;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_frag + buf * KBUF + tt * (32 / KG) * KRB + ks * 32);
+          s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[tt], 0, 0, 0);
+        }
+    };
+    auto needs_mask = [&](int kt) { return CAUSAL && kt * kKB + kKB - 1 > wave_first; };
+    auto mask = [&](f32x16 (&s)[2], int kt) {
+      const int k0 = kt * kKB;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kj = k0 + tt * 32 + 16 * (r / 8) + 8 * half + 4 * ((r / 4) % 2) + (r % 4);
+          if (kj > qpos) s[tt][r] = -INFINITY;
+        }
+    };
+    // the running maximum takes in a tile's largest score per lane; the accumulators are rescaled only when
+    // some row of the wave saw a new maximum
+    auto new_max = [&](float mx) {
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      if (!BIAS) mx *= scale2;                       // scale2 > 0: max commutes with the scaling
-      // rescale only when some row of the wave saw a new maximum
+      mx *= scale2;                                  // scale2 > 0: max commutes with the scaling
       if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
         const float m_new = fmaxf(m_run, mx);
         const float alpha = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
         m_run = m_new;
+        m_exp = m_new == -INFINITY ? 0.f : m_new;
         l_run *= alpha;
 #pragma unroll
         for (int i = 0; i < DT; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
       }
-      float psum = 0.f;
-      bf16x8 pf[2][2];
+    };
+    auto take_max = [&](const f32x16 (&s)[2]) {
+      float mx = s[0][0];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float e = BIAS ? acc_s[tt][r] - m_run : fmaf(acc_s[tt][r], scale2, -m_run);
-          const float p = __builtin_amdgcn_exp2f(e);
-          psum += p;
-          pf[tt][r / 8][r % 8] = f2bf(p);
-        }
-      l_run += psum;
-      // ---- O^T += V^T P^T
-      const bf16_t* cv = sV + buf * DH * VROW + l32 * VROW + 8 * half;
-#pragma unroll
-      for (int i = 0; i < DT; ++i)
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[tt][r]);
+      new_max(mx);
+    };
+    // One tile of this wave: probabilities of `cur` (whose maximum m_run already holds), their products with the
+    // V^T tile in V buffer `buf`, and meanwhile the scores of the next tile, in K buffer `buf ^ 1`, into `next`.
+    // The order of issue is written out and pinned group by group (nothing crosses a scheduling barrier): one
+    // matrix instruction, the read of the fragment PD instructions ahead, and a share of the vector work -
+    // exponentials of this tile at a steady rate that has each quarter of the probabilities ready before the
+    // products that consume it, then the maximum of the next tile's scores once those are complete.
+    auto step = [&](auto has_next, auto mask_next, f32x16 (&cur)[2], f32x16 (&next)[2], int kt, int buf) {
+      constexpr bool NEXT = decltype(has_next)::value, MASK = decltype(mask_next)::value;
+      // (the three instantiations begin alike; an empty statement that differs keeps the compiler from
+      // moving their common exponentials out in front of the branch, away from the matrix instructions)
+      asm volatile("; tile step %c1" : "+v"(m_exp) : "n"(2 * (int)NEXT + (int)MASK));
+      constexpr int NQK = NEXT ? 2 * KS : 0, NPV = 4 * DT, N = NQK + NPV, PD = DH >= 128 ? 4 : 2;
+      constexpr int EXPS = NEXT ? (32 + NQK + 3 * DT - 2) / (NQK + 3 * DT - 1) : 32;   // exponentials per group
+      constexpr int MAX0 = NQK + 2;                                   // first group that may read `next`
+      constexpr int MAXS = (16 + N - MAX0 - 1) / (N - MAX0);          // pairs of scores per group for the maximum
+      const unsigned char* const kf_base = k_frag + (buf ^ 1) * KBUF;
+      const unsigned char* const vf_base = v_frag + buf * VBUF;
+      auto frag = [&](int j) {
+        if (j < NQK) return *reinterpret_cast<const bf16x8*>(kf_base + (j / KS) * (32 / KG) * KRB + (j % KS) * 32);
+        const int pq = (j - NQK) / DT, i = (j - NQK) % DT;
+        return *reinterpret_cast<const bf16x8*>(vf_base + i * (32 / VG) * VRB + pq * 32);
+      };
+      if (NEXT) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(cv + i * 32 * VROW + (tt * 2 + u) * 16);
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt][u], acc_o[i], 0, 0, 0);
+          for (int r = 0; r < 16; ++r) next[tt][r] = 0.f;
+      }
+      bf16x8 fr[PD];
+#pragma unroll
+      for (int j = 0; j < PD; ++j) fr[j] = frag(j);
+      float psum = 0.f, mx = 0.f;
+      bf16x8 pf[2][2];
+      int e_done = 0, m_done = 0;
+      auto exponential = [&](int e) {
+        const int tt = e / 16, r = e % 16;
+        const float p = __builtin_amdgcn_exp2f(fmaf(cur[tt][r], scale2, -m_exp));
+        psum += p;
+        pf[tt][r / 8][r % 8] = f2bf(p);
+      };
+      if (!NEXT) {   // the wave's last tile: nothing to hide the exponentials under
+#pragma unroll
+        for (int e = 0; e < 32; ++e) exponential(e);
+        e_done = 32;
+      }
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        if (j < NQK) {
+          next[j / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % PD], qf[j % KS], next[j / KS], 0, 0, 0);
+        } else {
+          const int pq = (j - NQK) / DT, i = (j - NQK) % DT;
+          acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % PD], pf[pq / 2][pq % 2], acc_o[i], 0, 0, 0);
+        }
+        if (j + PD < N) fr[j % PD] = frag(j + PD);
+#pragma unroll
+        for (int c = 0; c < EXPS; ++c) {
+          if (e_done < 32) exponential(e_done++);
+        }
+        if (NEXT && !MASK && j >= MAX0) {
+#pragma unroll
+          for (int c = 0; c < MAXS; ++c) {
+            if (m_done < 16) {
+              const float s0 = next[m_done / 8][2 * (m_done % 8)], s1 = next[m_done / 8][2 * (m_done % 8) + 1];
+              mx = m_done == 0 ? fmaxf(s0, s1) : fmaxf(fmaxf(mx, s0), s1);
+              ++m_done;
+            }
           }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      l_run += psum;
+      if constexpr (NEXT) {
+        if constexpr (MASK) {
+          mask(next, kt + 1);
+          mx = next[0][0];
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, next[tt][r]);
+        }
+        new_max(mx);
+      }
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    // buf = (kt - tile_lo) % 2: K(kt) and V(kt) are in buffers `buf`, K(kt+1) in `buf ^ 1`
+    auto iteration = [&](f32x16 (&cur)[2], f32x16 (&next)[2], int kt, int buf) {
+      if (kt + 2 < tile_hi) dma_k(kt + 2, buf);          // K(kt) was last read in the iteration before
+      if (kt + 1 < tile_hi) dma_v(kt + 1, buf ^ 1);      // and so was V(kt-1)
+      if (kt < w_hi) {
+        if (kt + 1 >= w_hi) step(no{}, no{}, cur, next, kt, buf);
+        else if (needs_mask(kt + 1)) step(yes{}, yes{}, cur, next, kt, buf);
+        else step(yes{}, no{}, cur, next, kt, buf);
+      }
+      arrived();
+    };
+
+    f32x16 s_a[2], s_b[2];
+    if (tile_lo < tile_hi) {
+      dma_k(tile_lo, 0); dma_v(tile_lo, 0);
+      if (tile_lo + 1 < tile_hi) dma_k(tile_lo + 1, 1);
     }
-    if (BIAS && more) __syncthreads();   // the single bias buffer is overwritten next: every wave has read it
-    if (more) store_tile(buf ^ 1);
-    __syncthreads();
+    arrived();
+    if (tile_lo < w_hi) {
+      scores(s_a, 0);
+      if (needs_mask(tile_lo)) mask(s_a, tile_lo);
+      take_max(s_a);
+    }
+    __syncthreads();   // K(tile_lo)'s buffer is written again from the first iteration on
+    for (int kt = tile_lo; kt < tile_hi; kt += 2) {
+      iteration(s_a, s_b, kt, 0);
+      if (kt + 1 < tile_hi) iteration(s_b, s_a, kt + 1, 1);
+    }
   }
 
   if (row >= sq) return;
@@ -509,7 +762,7 @@ __global__ void __launch_bounds__(256) attention_merge_splits(AttnArgs a) {
 template <int DH, bool CAUSAL, bool BIAS, bool RAGGED, int NW>
 static hipError_t mfma_attn_launch(const AttnArgs& a, hipStream_t s) {
   auto kern = attention_mfma_bf16<DH, CAUSAL, BIAS, RAGGED, NW>;
-  constexpr size_t lds = ((size_t)2 * (kKB * (DH + 8) + DH * (kKB + 8)) + (BIAS ? 32 * NW * (kKB + 4) : 0)) * sizeof(bf16_t);
+  constexpr size_t lds = attention_lds_bytes(DH, CAUSAL, BIAS, RAGGED, NW);
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (attr_status != hipSuccess) return attr_status;
@@ -551,6 +804,7 @@ static bool mfma_attn_eligible(const AttnArgs& a) {
   if (a.dtype != AC_BF16 || !a.v_transposed) return false;
   if (a.head_dim != 32 && a.head_dim != 64 && a.head_dim != 128) return false;
   if (a.ldq % 8 || a.ldk % 8 || a.ldv % 8 || a.sq_b % 8 || a.sk_b % 8 || a.sv_b % 8) return false;
+  if (a.ldk >= (1 << 24) || a.ldv >= (1 << 24)) return false;   // a tile's rows are addressed with 32-bit byte offsets
   if (a.ldc % 4 || a.sc_b % 4) return false;
   if (!al(a.q, 16) || !al(a.k, 16) || !al(a.v, 16) || !al(a.ctx, 8)) return false;
   if (a.bias && (a.sk % 4 || a.ld_bias % 8 || a.s_bias_h % 8 || !al(a.bias, 16))) return false;   // 16-byte bias chunks
