@@ -455,7 +455,11 @@ __global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS,
     // (K rows sit in LDS in the order the lanes of a score MFMA read them: LDS row x holds key swap23(x), see below)
     auto swap23 = [](int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); };
     const uint32_t kg_off = (uint32_t)(swap23((lane / (KRB / 16)) * KG + wave) * (int)a.ldk + (lane % (KRB / 16)) * 8) * 2u;
-    const uint32_t vg_off = (uint32_t)(((lane / (VRB / 16)) * VG + wave) * (int)a.ldv + (lane % (VRB / 16)) * 8) * 2u;
+    // (with 16 groups a V^T group holds 8 rows that are 16 apart; they sit in it in the order v_slot() gives, so
+    // that rows l and l + 16, which the two quarter-waves of a fragment read fetch together, are 256 bytes apart
+    // and the 32 lanes fall into 32 different 16-byte slots modulo 512 bytes)
+    auto v_row_of_slot = [](int x) { return VG == 16 ? 2 * ((x & 1) + 2 * (x >> 2)) + ((x >> 1) & 1) : x; };
+    const uint32_t vg_off = (uint32_t)((v_row_of_slot(lane / (VRB / 16)) * VG + wave) * (int)a.ldv + (lane % (VRB / 16)) * 8) * 2u;
     auto uniform = [](const void* ptr) {
       const uint64_t v = (uint64_t)ptr;
       const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
@@ -489,7 +493,7 @@ __global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS,
     // K is laid out in LDS by MFMA row, not by key (LDS row x = key pi(x) of the tile), so that here too 8
     // consecutive lanes read 8 different 16-byte slots modulo 128 bytes.
     const unsigned char* const k_frag = sKb + (l32 % KG) * GB + (l32 / KG) * KRB + half * 16;
-    const unsigned char* const v_frag = sVb + (l32 % VG) * GB + (l32 / VG) * VRB + half * 16;
+    const unsigned char* const v_frag = sVb + (l32 % VG) * GB + (VG == 16 ? 2 * (l32 / 16) : l32 / VG) * VRB + half * 16;
 
     int w_hi = tile_hi;                               // this wave computes tiles [tile_lo, w_hi)
     if (CAUSAL) { const int vis = wave_last / kKB + 1; if (vis < w_hi) w_hi = vis; }
@@ -558,7 +562,7 @@ __global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS,
       // moving their common exponentials out in front of the branch, away from the matrix instructions)
       asm volatile("; tile step %c1" : "+v"(m_exp) : "n"(2 * (int)NEXT + (int)MASK));
       constexpr int NQK = NEXT ? 2 * KS : 0, NPV = 4 * DT, N = NQK + NPV, PD = DH >= 128 ? 4 : 2;
-      constexpr int EXPS = NEXT ? (32 + NQK + 3 * DT - 2) / (NQK + 3 * DT - 1) : 32;   // exponentials per group
+      constexpr int EXPD = NQK + 3 * DT - 1;   // the 32 exponentials are spread evenly over the groups before the last quarter's products
       constexpr int MAX0 = NQK + 2;                                   // first group that may read `next`
       constexpr int MAXS = (16 + N - MAX0 - 1) / (N - MAX0);          // pairs of scores per group for the maximum
       const unsigned char* const kf_base = k_frag + (buf ^ 1) * KBUF;
@@ -566,7 +570,7 @@ __global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS,
       auto frag = [&](int j) {
         if (j < NQK) return *reinterpret_cast<const bf16x8*>(kf_base + (j / KS) * (32 / KG) * KRB + (j % KS) * 32);
         const int pq = (j - NQK) / DT, i = (j - NQK) % DT;
-        return *reinterpret_cast<const bf16x8*>(vf_base + i * (32 / VG) * VRB + pq * 32);
+        return *reinterpret_cast<const bf16x8*>(vf_base + (VG == 16 ? (i & 1) + 4 * (i >> 1) : i * (32 / VG)) * VRB + pq * 32);
       };
       if (NEXT) {
 #pragma unroll
@@ -601,8 +605,8 @@ __global__ void __launch_bounds__(64 * NW, attention_pipelined(DH, CAUSAL, BIAS,
         }
         if (j + PD < N) fr[j % PD] = frag(j + PD);
 #pragma unroll
-        for (int c = 0; c < EXPS; ++c) {
-          if (e_done < 32) exponential(e_done++);
+        for (int c = 0; c < 4; ++c) {
+          if (e_done < 32 && e_done < (j + 1) * 32 / EXPD) exponential(e_done++);
         }
         if (NEXT && !MASK && j >= MAX0) {
 #pragma unroll
