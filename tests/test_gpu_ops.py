@@ -185,6 +185,25 @@ def test_attention_mfma(B, dh, sq, sk, causal, q_offset):
     assert _attn_case(B, "bf16", sq, sk, 3, dh, causal, q_offset, False, False, True) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("dh", [64, 128])
+@pytest.mark.parametrize("sq,sk,causal,q_offset", [
+    (300, 512, False, 0),       # whole key tiles and no bias: the software-pipelined loop, several tiles
+    (384, 640, True, 256),      # diagonal tiles of every wave inside the loop
+    (200, 448, True, 248),      # a segment offset that is no multiple of the tile
+    (96, 1024, True, 928),      # a short segment at the end of a long sequence
+    (64, 128, True, 64),        # two tiles: prologue and last step only
+])
+def test_attention_whole_key_tiles(B, dh, sq, sk, causal, q_offset):
+    assert _attn_case(B, "bf16", sq, sk, 3, dh, causal, q_offset, False, False, True) <= TOL["bf16"]
+    assert _attn_case(B, "bf16", sq, sk, 2, dh, causal, q_offset, False, True, True) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dh,causal", [(64, False), (128, True), (128, False)])
+def test_attention_256_row_blocks(B, dh, causal):
+    """A launch with at least 1024 blocks of 256 query rows runs 8 waves per block."""
+    assert _attn_case(B, "bf16", 1024, 1024, 256, dh, causal, 0, False, False, True) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dh", [32, 64, 128])
 @pytest.mark.parametrize("n_splits", [2, 3, 7])
 def test_attention_key_splits(B, dh, n_splits):
