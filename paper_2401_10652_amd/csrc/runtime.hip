@@ -96,7 +96,7 @@ struct ac_plan {
   std::vector<hipEvent_t> sync_pool;
   size_t sync_used = 0;
   int sync_needed = 0;
-  int64_t attention_launches = 0;
+  int64_t region_launches[AC_REGION_KINDS] = {};   // launches per layer of a region whose segments share launches (0: one per segment)
 };
 
 namespace ac {
@@ -130,7 +130,7 @@ struct Walk {
   void enter(int kind) { arena.watch = &region_high[kind]; }
 
   int sync_events = 0;     // planning: events one execute needs for its forks and joins
-  int64_t attention_launches = 0;   // launches of the attention region per layer (segments may share one)
+  int64_t region_launches[AC_REGION_KINDS] = {};   // launches per layer of a region whose segments share launches
   void fork() {
     if (dry && lanes == 2) ++sync_events;
     if (dry || lanes != 2 || !ok()) return;
@@ -443,17 +443,9 @@ static uint64_t attention_launch_bytes(const ac_model_desc& m, const Seg& g) {
   return attention_split_bytes(g.ns, g.nb, m.heads, m.head_dim, ns);
 }
 
-// The fused attention keeps no intermediate of a segment in memory (the scores live in
-// registers), so consecutive segments of its region may share a launch without raising the
-// bytes the plan needs: runs of consecutive segments (rows of one sequence, then whole
-// sequences of consecutive batch elements) become one launch, whose key splits are capped so
-// that their partial results stay within `bound`, the bytes of the region's largest single
-// segment.  The segments are still computed block by block in order; what is saved is the fixed
-// cost of a launch and its under-filled tail per segment (section 3.4's computation-density
-// term).  A pure function of the shapes: planning and execution agree.
-static std::vector<Seg> attention_launch_groups(const ac_model_desc& m, const std::vector<Seg>& segs, uint64_t& bound) {
-  bound = 0;
-  for (const Seg& sg : segs) bound = std::max(bound, attention_launch_bytes(m, sg));
+// Runs of consecutive segments (rows of one sequence, then whole sequences of consecutive batch
+// elements) as single segments: the launches of a region whose segments hold no tensor of their own.
+static std::vector<Seg> merged_segments(const ac_model_desc& m, const std::vector<Seg>& segs) {
   std::vector<Seg> rows;
   for (const Seg& sg : segs) {
     if (!rows.empty() && rows.back().nb == 1 && sg.nb == 1 && rows.back().b0 == sg.b0 &&
@@ -471,6 +463,19 @@ static std::vector<Seg> attention_launch_groups(const ac_model_desc& m, const st
       out.push_back(sg);
   }
   return out;
+}
+// The fused attention keeps no intermediate of a segment in memory (the scores live in
+// registers), so consecutive segments of its region may share a launch without raising the
+// bytes the plan needs: runs of consecutive segments (rows of one sequence, then whole
+// sequences of consecutive batch elements) become one launch, whose key splits are capped so
+// that their partial results stay within `bound`, the bytes of the region's largest single
+// segment.  The segments are still computed block by block in order; what is saved is the fixed
+// cost of a launch and its under-filled tail per segment (section 3.4's computation-density
+// term).  A pure function of the shapes: planning and execution agree.
+static std::vector<Seg> attention_launch_groups(const ac_model_desc& m, const std::vector<Seg>& segs, uint64_t& bound) {
+  bound = 0;
+  for (const Seg& sg : segs) bound = std::max(bound, attention_launch_bytes(m, sg));
+  return merged_segments(m, segs);
 }
 
 void Walk::transformer(const void* x, void* y) {
@@ -499,10 +504,16 @@ void Walk::transformer(const void* x, void* y) {
     auto W = [&](int slot) { return w(l, slot, 12); };
 
     // ---- region 1: LayerNorm 1 + packed projection, writes whole q, k, v
+    // The normalised rows go to the context buffer, which holds nothing between the output projection of
+    // the layer before and this layer's attention.  The region then has no tensor of a segment's own, and
+    // (as for the attention core below) consecutive segments share a launch: the plan's segments bound
+    // memory, and where they bound nothing they cost nothing.
     enter(AC_REGION_QKV);
-    seg_loop(token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV)), [&](const Seg& sg) {
+    const std::vector<Seg> qkv_segs = merged_segments(m, token_segments(m, p->set[AC_REGION_QKV].chunk_dim, seg_len(AC_REGION_QKV)));
+    region_launches[AC_REGION_QKV] = (int64_t)qkv_segs.size();
+    seg_loop(qkv_segs, [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      void* u = arena.push((uint64_t)rows * d * e);
+      void* u = atw(ctx_all, r0 * d);
       ln(at(in, r0 * d), d, W(W_LN1G), W(W_LN1B), u, d, rows, d);
       LinearArgs g{};
       g.a = u; g.lda = d; g.w = W(W_QKV); g.ldw = d; g.m = rows; g.n = 3 * d; g.k = d;
@@ -535,7 +546,7 @@ void Walk::transformer(const void* x, void* y) {
     std::vector<Seg> attn_segs = token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION));
     uint64_t split_bound = UINT64_MAX;
     if (!stored_scores) attn_segs = attention_launch_groups(m, attn_segs, split_bound);
-    attention_launches = (int64_t)attn_segs.size();
+    region_launches[AC_REGION_ATTENTION] = (int64_t)attn_segs.size();
     seg_loop(attn_segs, [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0;
       AttnArgs a{};
@@ -556,7 +567,10 @@ void Walk::transformer(const void* x, void* y) {
 
     // ---- region 2b: output projection + residual
     enter(AC_REGION_OUT_PROJ);
-    seg_loop(token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ)), [&](const Seg& sg) {
+    std::vector<Seg> out_segs = token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ));
+    if (!(m.flags & AC_FLAG_UNFUSED_ELEMENTWISE)) out_segs = merged_segments(m, out_segs);   // bias and residual in the epilogue: no tensor per segment
+    region_launches[AC_REGION_OUT_PROJ] = (int64_t)out_segs.size();
+    seg_loop(out_segs, [&](const Seg& sg) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
       proj(at(ctx_all, r0 * d), d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
     });
@@ -962,7 +976,7 @@ static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& f
   arena_bytes = wk.arena.high;
   flops = wk.flops;
   if (region_high) memcpy(region_high, wk.region_high, sizeof(wk.region_high));
-  if (!unchunked) { p->sync_needed = wk.sync_events; p->attention_launches = wk.attention_launches; }
+  if (!unchunked) { p->sync_needed = wk.sync_events; memcpy(p->region_launches, wk.region_launches, sizeof(wk.region_launches)); }
 }
 
 static uint64_t io_bytes(const ac_model_desc& m) {
@@ -1231,7 +1245,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     ri.extent = s.extent;
     ri.chunk_len = s.chunk_len;
     ri.n_segments = ceil_div(s.extent, s.chunk_len);
-    ri.launches = k == AC_REGION_ATTENTION && m.workload == AC_TRANSFORMER_STACK ? p->attention_launches : ri.n_segments;
+    ri.launches = p->region_launches[k] > 0 ? p->region_launches[k] : ri.n_segments;
     ri.model_bytes = model_bytes(m, k, rows_of(s, s.chunk_len));
     ri.model_bytes_unchunked = model_bytes(m, k, rows_of(s, s.extent));
     inf.peak_bytes_model = std::max(inf.peak_bytes_model, ri.model_bytes);

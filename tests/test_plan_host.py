@@ -52,7 +52,8 @@ def key_splits_by_hand(sq, sk, heads, batch, dh, dtype):
 
 def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None, stored_scores=False):
     """Whole tensors q,k (2Td) + v^T (Td) [bf16] or qkv (3Td) [fp32], context (Td), h (Td),
-    inter-layer t (Td if layers > 1), plus the largest per-segment set: u (c d) | fp32 split
+    inter-layer t (Td if layers > 1), plus the largest per-segment set: nothing for LayerNorm 1 +
+    projection (the normalised rows sit in the context buffer, which is idle then) | fp32 split
     partials of the attention (ns c H (d_h + 2) floats) | nothing for the output projection
     (its unfused form holds c d) | u (c d) + hidden (c F)."""
     c_out = c_attn if c_out is None else c_out
@@ -64,7 +65,7 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None,
     whole += 2 * al(T * d * e)
     if cfg.layers > 1:
         whole += al(T * d * e)
-    r1 = al(c_qkv * d * e)
+    r1 = 0
     groups = attention_groups_by_hand(cfg, c_attn)
     r2 = max(b for _, _, b in groups)
     if stored_scores:                      # scores and probabilities of one segment, every head
@@ -74,7 +75,7 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None,
     r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
     # two segments in flight: a region with more than one segment (launch) holds two per-segment sets
     mult = lambda c: lanes if c < cfg.seq else 1
-    return whole + max(r1 * mult(c_qkv), r2 * (lanes if len(groups) > 1 else 1), r2b * mult(c_out), r3 * mult(c_ffn))
+    return whole + max(r1, r2 * (lanes if len(groups) > 1 else 1), r2b * mult(c_out), r3 * mult(c_ffn))
 
 
 def attention_launch_bytes_by_hand(cfg, s0, rows):
