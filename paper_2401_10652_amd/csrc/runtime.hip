@@ -576,12 +576,18 @@ void Walk::transformer(const void* x, void* y) {
     });
 
     // ---- region 3: LayerNorm 2 + feed-forward + residual
+    // LayerNorm 2 writes into the context buffer as well (the output projection has consumed it), for all
+    // rows at once; what a segment of this region holds is its hidden tensor.
     enter(AC_REGION_FFN);
-    seg_loop(token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN)), [&](const Seg& sg) {
+    const std::vector<Seg> ffn_segs = token_segments(m, p->set[AC_REGION_FFN].chunk_dim, seg_len(AC_REGION_FFN));
+    for (const Seg& sg : merged_segments(m, ffn_segs)) {
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      void* u = arena.push((uint64_t)rows * d * e);
+      ln(at(hbuf, r0 * d), d, W(W_LN2G), W(W_LN2B), atw(ctx_all, r0 * d), d, rows, d);
+    }
+    seg_loop(ffn_segs, [&](const Seg& sg) {
+      const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
+      const void* u = at(ctx_all, r0 * d);
       void* hid = arena.push((uint64_t)rows * F * e);
-      ln(at(hbuf, r0 * d), d, W(W_LN2G), W(W_LN2B), u, d, rows, d);
       proj(u, d, W(W_1), d, W(W_B1), m.activation, nullptr, 0, hid, F, rows, F);
       proj(hid, F, W(W_2), F, W(W_B2), AC_ACT_NONE, at(hbuf, r0 * d), d, atw(out, r0 * d), d, rows, d);
     });

@@ -128,7 +128,7 @@ def test_budget_sized_plan_runs(B):
     # attention core (fp32 partial results of its key splits) have to be cut
     budget = 9 << 19
     y, info = r.run(regions(B, 0, 0, 0), budget=budget)
-    assert [x.n_segments for x in info.regions[:4]] == [1, 2, 1, 3] and info.regions[3].chunk_len == 384
+    assert [x.n_segments for x in info.regions[:4]] == [1, 2, 1, 2] and info.regions[3].chunk_len == 512
     assert info.regions[1].launches == 1       # the attention's two segments share a launch with capped key splits
     assert info.peak_bytes_planned <= budget < info.peak_bytes_unchunked_planned
     check(host(y), ref, "bf16")
@@ -152,12 +152,12 @@ def test_profiling_reports_kernel_classes(B):
     p.ac_execute(r.dx, y, ws)
     stats = {s["name"]: s for s in p.ac_plan_read_profile()}
     assert set(stats) == {"gemm", "attention", "layernorm"}
-    # per layer: the two segments of the feed-forward region run a LayerNorm and 2 GEMMs each; those of the
+    # per layer: the two segments of the feed-forward region run 2 GEMMs each; those of the
     # other three regions hold no tensor of their own and share one launch (LayerNorm + GEMM, attention, GEMM)
     assert stats["gemm"]["launches"] == 2 * (1 + 1 + 2 * 2) and stats["attention"]["launches"] == 2
     assert [x.n_segments for x in info.regions[:4]] == [2, 2, 2, 2]
     assert [x.launches for x in info.regions[:4]] == [1, 1, 1, 2]
-    assert stats["layernorm"]["launches"] == 2 * (1 + 2)
+    assert stats["layernorm"]["launches"] == 2 * 2      # both LayerNorms of a layer run over all rows at once
     total = sum(s["flops"] for s in stats.values())
     assert abs(total - info.flops_per_execute) <= 1e-9 * total
     assert all(s["total_ms"] > 0 for s in stats.values())

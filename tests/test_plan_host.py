@@ -55,7 +55,8 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None,
     inter-layer t (Td if layers > 1), plus the largest per-segment set: nothing for LayerNorm 1 +
     projection (the normalised rows sit in the context buffer, which is idle then) | fp32 split
     partials of the attention (ns c H (d_h + 2) floats) | nothing for the output projection
-    (its unfused form holds c d) | u (c d) + hidden (c F)."""
+    (its unfused form holds c d) | the hidden tensor (c F) of the feed-forward (LayerNorm 2 also writes
+    into the context buffer; the unfused second projection holds c d more)."""
     c_out = c_attn if c_out is None else c_out
     e = 2 if cfg.dtype == "bf16" else 4
     T, d, F = cfg.seq * cfg.batch, cfg.d_model, cfg.d_ffn
@@ -72,7 +73,7 @@ def arena_by_hand(cfg, c_qkv, c_attn, c_ffn, unfused=False, lanes=1, c_out=None,
         r2 = 2 * al(cfg.heads * c_attn * cfg.seq * e)
         groups = [None] * -(-cfg.seq // c_attn)
     r2b = al(c_out * d * e) if unfused else 0
-    r3 = al(c_ffn * d * e) + al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
+    r3 = al(c_ffn * F * e) + (al(c_ffn * d * e) if unfused else 0)
     # two segments in flight: a region with more than one segment (launch) holds two per-segment sets
     mult = lambda c: lanes if c < cfg.seq else 1
     return whole + max(r1, r2 * (lanes if len(groups) > 1 else 1), r2b * mult(c_out), r3 * mult(c_ffn))
@@ -200,27 +201,28 @@ def test_budget_bounds_the_executor_bytes():
         info = B.Plan(B.transformer_desc(cfg), regions(0, 0, 0, c_out=0), budget).ac_plan_query()
         assert [r.n_segments for r in info.regions[:4]] == [1, 1, 1, 1]
         assert info.peak_bytes_planned == info.peak_bytes_unchunked_planned <= budget
-    # C5, 3 GiB: only the feed-forward region (LayerNorm output + hidden tensor of a segment on
-    # top of the whole tensors) exceeds it; it gets the largest multiple of 128 rows that fits
+    # C5, 2.75 GiB: only the feed-forward region (the hidden tensor of a segment on top of the whole
+    # tensors) exceeds it; it gets the largest multiple of 128 rows that fits
     e = 2
     S, d, F = I.C5.seq, I.C5.d_model, I.C5.d_ffn
+    BUD = 11 * GIB // 4
     whole = 2 * S * d * e + 6 * S * d * e          # x, y; q, k, v, context, h, inter-layer buffer
-    info3 = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0, c_out=0), 3 * GIB).ac_plan_query()
-    fits = lambda c: whole + c * (d + F) * e <= 3 * GIB
+    info3 = B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0, c_out=0), BUD).ac_plan_query()
+    fits = lambda c: whole + c * F * e <= BUD
     assert [r.n_segments for r in info3.regions[:3]] == [1, 1, 1]
-    assert info3.regions[3].chunk_len == M.largest_chunk_len(S, 128, fits) == 52352
-    assert info3.peak_bytes_planned <= 3 * GIB < info3.peak_bytes_unchunked_planned
-    assert info3.peak_bytes_planned == arena_by_hand(I.C5, S, S, 52352, c_out=S) + 2 * S * d * e
+    assert info3.regions[3].chunk_len == M.largest_chunk_len(S, 128, fits) == 49152
+    assert info3.peak_bytes_planned <= BUD < info3.peak_bytes_unchunked_planned
+    assert info3.peak_bytes_planned == arena_by_hand(I.C5, S, S, 49152, c_out=S) + 2 * S * d * e
     # one granule more would not fit
-    over = B.Plan(B.transformer_desc(I.C5), regions(S, S, 52352 + 128, c_out=S)).ac_plan_query()
-    assert over.peak_bytes_planned > 3 * GIB
+    over = B.Plan(B.transformer_desc(I.C5), regions(S, S, 49152 + 128, c_out=S)).ac_plan_query()
+    assert over.peak_bytes_planned > BUD
     # an explicit length that does not fit is an error, as is a budget below the whole tensors
-    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, S, c_out=0), 3 * GIB))
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, S, c_out=0), BUD))
     expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.transformer_desc(I.C5), regions(0, 0, 0, c_out=0), 2 * GIB))
     # two segments in flight: the budget bounds the doubled per-segment sets too
     info2 = B.Plan(B.transformer_desc(I.C5, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT), regions(0, 0, 0, c_out=0),
-                   3 * GIB).ac_plan_query()
-    assert info2.peak_bytes_planned <= 3 * GIB and info2.regions[3].chunk_len <= 52352 // 2 + 128
+                   BUD).ac_plan_query()
+    assert info2.peak_bytes_planned <= BUD and info2.regions[3].chunk_len <= 49152 // 2 + 128
 
 
 def test_budget_sizes_batch_chunks():
