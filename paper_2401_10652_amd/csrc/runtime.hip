@@ -661,8 +661,10 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
   // ---- whole operands: a and b of every position, channel-major.  Row r = (i, k) of z lands
   // at [c][r]; for the incoming form r = (k, i), and the per-channel matrices are transposed
   // in place afterwards.  (Built in runs of rows of the segment length whatever the chunk dim.)
+  // The fused kernel keeps nothing of a run of rows in memory, so it takes them all in one launch.
   const bool fuse_ab = fuses_ln_proj(cz, {ch, ch}), fuse_g = fuses_ln_proj(cz, {cz});
-  seg_loop(segs, [&](const RowSeg& sg) {
+  const std::vector<RowSeg> all_rows{RowSeg{0, N}};
+  seg_loop(fuse_ab ? all_rows : segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
     if (fuse_ab) {   // LayerNorm and the four projections in one kernel; the gates stay in registers
       ProjPart pa{}, pb{};
@@ -754,7 +756,8 @@ void Walk::tri_att(int kind, const void* const* W, const void* zin, void* zout) 
   void* v_all = ending_form ? arena.push((uint64_t)hd * R * e) : nullptr;
   const bool fuse_a = ending_form ? fuses_ln_proj(cz, {H, hd, hd}) : fuses_ln_proj(cz, {H});
   const bool fuse_b = ending_form ? fuses_ln_proj(cz, {hd, hd}) : fuses_ln_proj(cz, {hd, hd, hd, hd});
-  seg_loop(segs, [&](const RowSeg& sg) {
+  const std::vector<RowSeg> all_rows{RowSeg{0, N}};   // the fused kernel holds nothing per run of rows: one launch
+  seg_loop(fuse_a ? all_rows : segs, [&](const RowSeg& sg) {
     const int64_t r0 = sg.i0 * N, rows = sg.ni * N;
     // keys of the whole tensor: regrouped by column for the ending node, as they are otherwise
     void* k_dst = !k_all ? nullptr : (ending ? atw(k_all, sg.i0 * hd) : atw(k_all, r0 * hd));
