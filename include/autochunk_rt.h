@@ -79,8 +79,12 @@ typedef enum ac_region_kind {
  * (blocks of output columns).  Otherwise feature, head_dim, key, channel and contraction
  * index are illegal.  A column chunk of a pair region gathers its positions with the two
  * indices swapped (a copy that counts as activation memory, section 3.4) and runs the module's
- * transposed form on them.  The two legal feature chunks are not implemented
- * (AC_ERR_UNSUPPORTED). */
+ * transposed form on them.  A feature chunk spans all rows: chunk_len counts features and must be
+ * a multiple of head_dim for the attention region (a segment is a run of whole heads) and of 8
+ * for the output projection (a block of output columns), else AC_ERR_ARG.  Regions whose
+ * segments hold no tensor of their own (the fused attention core, the fused output projection,
+ * LayerNorm + packed projection) run consecutive segments in one launch; ac_region_info.launches
+ * says how many launches a layer's region takes. */
 enum { AC_DIM_BATCH = 0, AC_DIM_SEQ = 1, AC_DIM_FEATURE = 2, AC_DIM_HEAD_DIM = 3, AC_DIM_KEY = 4 };
 enum { AC_DIM_ROW = 0, AC_DIM_COL = 1, AC_DIM_CHANNEL = 2, AC_DIM_CONTRACT = 3 };
 

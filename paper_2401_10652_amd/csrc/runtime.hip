@@ -543,22 +543,34 @@ void Walk::transformer(const void* x, void* y) {
     }
     // ---- region 2: attention of a query segment over whole k, v; writes its rows of the context
     enter(AC_REGION_ATTENTION);
-    std::vector<Seg> attn_segs = token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION));
+    // A feature chunk is a run of whole heads over all rows.
+    const bool by_heads = p->set[AC_REGION_ATTENTION].chunk_dim == AC_DIM_FEATURE;
+    const int heads_per_seg = by_heads ? (int)(seg_len(AC_REGION_ATTENTION) / m.head_dim) : m.heads;
+    std::vector<Seg> attn_segs = by_heads ? std::vector<Seg>{Seg{0, m.batch, 0, S}}
+                                          : token_segments(m, p->set[AC_REGION_ATTENTION].chunk_dim, seg_len(AC_REGION_ATTENTION));
     uint64_t split_bound = UINT64_MAX;
     if (!stored_scores) attn_segs = attention_launch_groups(m, attn_segs, split_bound);
-    region_launches[AC_REGION_ATTENTION] = (int64_t)attn_segs.size();
-    seg_loop(attn_segs, [&](const Seg& sg) {
-      const int64_t r0 = sg.b0 * S + sg.s0;
+    struct HeadSeg { Seg t; int h0, hc; };
+    std::vector<HeadSeg> head_segs;
+    for (const Seg& sg : attn_segs) {
+      // the fused kernel holds nothing per head either: only the stored-scores form runs head group by head group
+      const int step = stored_scores ? heads_per_seg : m.heads;
+      for (int h0 = 0; h0 < m.heads; h0 += step) head_segs.push_back(HeadSeg{sg, h0, std::min(step, m.heads - h0)});
+    }
+    region_launches[AC_REGION_ATTENTION] = (int64_t)head_segs.size();
+    seg_loop(head_segs, [&](const HeadSeg& hs) {
+      const Seg& sg = hs.t;
+      const int64_t r0 = sg.b0 * S + sg.s0, c0 = (int64_t)hs.h0 * m.head_dim;
       AttnArgs a{};
-      a.q = at(qk, r0 * ldqk); a.ldq = ldqk; a.sq_b = S * ldqk;
-      a.k = at(qk, sg.b0 * S * ldqk + d); a.ldk = ldqk; a.sk_b = S * ldqk;
-      if (bf) { a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1; }
-      else { a.v = at(qk, sg.b0 * S * ldqk + 2 * d); a.ldv = ldqk; a.sv_b = S * ldqk; a.v_transposed = 0; }
-      a.ctx = atw(ctx_all, r0 * d); a.ldc = d; a.sc_b = S * d;
-      a.batch = sg.nb; a.sq = sg.ns; a.sk = S; a.heads = m.heads; a.head_dim = m.head_dim;
+      a.q = at(qk, r0 * ldqk + c0); a.ldq = ldqk; a.sq_b = S * ldqk;
+      a.k = at(qk, sg.b0 * S * ldqk + d + c0); a.ldk = ldqk; a.sk_b = S * ldqk;
+      if (bf) { a.v = at(vt, sg.b0 * d * S + c0 * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1; }
+      else { a.v = at(qk, sg.b0 * S * ldqk + 2 * d + c0); a.ldv = ldqk; a.sv_b = S * ldqk; a.v_transposed = 0; }
+      a.ctx = atw(ctx_all, r0 * d + c0); a.ldc = d; a.sc_b = S * d;
+      a.batch = sg.nb; a.sq = sg.ns; a.sk = S; a.heads = hs.hc; a.head_dim = m.head_dim;
       a.causal = m.causal; a.q_offset = sg.s0;
       if (stored_scores) {
-        a.v = at(vt, sg.b0 * d * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1;
+        a.v = at(vt, sg.b0 * d * S + c0 * S); a.ldv = S; a.sv_b = d * S; a.v_transposed = 1;
         attention_materialized(a);
       } else {
         attention(a, split_bound);
@@ -567,12 +579,24 @@ void Walk::transformer(const void* x, void* y) {
 
     // ---- region 2b: output projection + residual
     enter(AC_REGION_OUT_PROJ);
-    std::vector<Seg> out_segs = token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ));
-    if (!(m.flags & AC_FLAG_UNFUSED_ELEMENTWISE)) out_segs = merged_segments(m, out_segs);   // bias and residual in the epilogue: no tensor per segment
-    region_launches[AC_REGION_OUT_PROJ] = (int64_t)out_segs.size();
-    seg_loop(out_segs, [&](const Seg& sg) {
+    // (a feature chunk is a block of output columns over all rows: rows of w_o, entries of its bias)
+    const bool by_cols = p->set[AC_REGION_OUT_PROJ].chunk_dim == AC_DIM_FEATURE;
+    const bool out_fused = !(m.flags & AC_FLAG_UNFUSED_ELEMENTWISE);   // bias and residual in the epilogue: no tensor per segment
+    std::vector<Seg> out_segs = by_cols ? std::vector<Seg>{Seg{0, m.batch, 0, S}}
+                                        : token_segments(m, p->set[AC_REGION_OUT_PROJ].chunk_dim, seg_len(AC_REGION_OUT_PROJ));
+    if (out_fused) out_segs = merged_segments(m, out_segs);
+    struct ColSeg { Seg t; int64_t n0, nc; };
+    std::vector<ColSeg> col_segs;
+    for (const Seg& sg : out_segs) {
+      const int64_t step = by_cols && !out_fused ? seg_len(AC_REGION_OUT_PROJ) : d;
+      for (int64_t n0 = 0; n0 < d; n0 += step) col_segs.push_back(ColSeg{sg, n0, std::min<int64_t>(step, d - n0)});
+    }
+    region_launches[AC_REGION_OUT_PROJ] = (int64_t)col_segs.size();
+    seg_loop(col_segs, [&](const ColSeg& cs) {
+      const Seg& sg = cs.t;
       const int64_t r0 = sg.b0 * S + sg.s0, rows = sg.nb * sg.ns;
-      proj(at(ctx_all, r0 * d), d, W(W_O), d, W(W_BO), AC_ACT_NONE, at(in, r0 * d), d, atw(hbuf, r0 * d), d, rows, d);
+      proj(at(ctx_all, r0 * d), d, at(W(W_O), cs.n0 * d), d, at(W(W_BO), cs.n0), AC_ACT_NONE, at(in, r0 * d + cs.n0), d,
+           atw(hbuf, r0 * d + cs.n0), d, rows, cs.nc);
     });
 
     // ---- region 3: LayerNorm 2 + feed-forward + residual
@@ -955,6 +979,9 @@ static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
 // batch element; batch chunk -> c * seq rows.
 static int64_t model_rows(const ac_model_desc& m, const Setting& s, int64_t len) {
   if (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_BATCH) return len * m.seq;
+  // a feature chunk holds the fraction len / d_model of the region's intermediates: the rows that do the same
+  if (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_FEATURE)
+    return ((int64_t)m.batch * m.seq * len + m.d_model - 1) / m.d_model;
   return len;
 }
 
@@ -963,11 +990,14 @@ static void region_kinds(const ac_model_desc& m, int& first, int& count) {
   else { first = AC_REGION_TRIMUL_OUT; count = 5; }
 }
 
-static bool dim_legal(const ac_model_desc& m, int dim, bool& known) {
+static bool dim_legal(const ac_model_desc& m, int kind, int dim, bool& known) {
   known = true;
   if (m.workload == AC_TRANSFORMER_STACK) {
     if (dim == AC_DIM_BATCH || dim == AC_DIM_SEQ) return true;
-    if (dim == AC_DIM_FEATURE || dim == AC_DIM_HEAD_DIM || dim == AC_DIM_KEY) return false;
+    // The feature dim of the context (whole heads) and of the output projection (blocks of output
+    // columns) can be cut: no node of those regions reduces over it.  The LayerNorms of the other two do.
+    if (dim == AC_DIM_FEATURE) return kind == AC_REGION_ATTENTION || kind == AC_REGION_OUT_PROJ;
+    if (dim == AC_DIM_HEAD_DIM || dim == AC_DIM_KEY) return false;
   } else {
     if (dim == AC_DIM_ROW || dim == AC_DIM_COL) return true;
     if (dim == AC_DIM_CHANNEL || dim == AC_DIM_CONTRACT) return false;
@@ -1082,15 +1112,8 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     }
     Setting& s = p->set[r.kind];
     if (s.present) { delete p; return fail(AC_ERR_ARG, "region kind %d listed twice (one chunk setting per region)", r.kind); }
-    // The feature dim of the context and of the output projection can be cut (whole heads;
-    // blocks of output columns): no node of those regions reduces over it.  No kernel here does.
-    if (m.workload == AC_TRANSFORMER_STACK && r.chunk_dim == AC_DIM_FEATURE &&
-        (r.kind == AC_REGION_ATTENTION || r.kind == AC_REGION_OUT_PROJ)) {
-      delete p;
-      return fail(AC_ERR_UNSUPPORTED, "feature chunks of region %d are legal but not implemented", r.kind);
-    }
     bool known;
-    if (!dim_legal(m, r.chunk_dim, known)) {
+    if (!dim_legal(m, r.kind, r.chunk_dim, known)) {
       delete p;
       if (!known) return fail(AC_ERR_ARG, "chunk_dim %d unknown", r.chunk_dim);
       return fail(AC_ERR_ILLEGAL_CHUNK_DIM,
@@ -1104,7 +1127,15 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     if (r.chunk_len < 0) { delete p; return fail(AC_ERR_ARG, "chunk_len must be >= 0"); }
     s.present = true;
     s.chunk_dim = r.chunk_dim;
-    s.extent = m.workload == AC_TRANSFORMER_STACK ? (r.chunk_dim == AC_DIM_BATCH ? m.batch : m.seq) : m.n_res;
+    s.extent = m.workload == AC_TRANSFORMER_STACK ? (r.chunk_dim == AC_DIM_BATCH ? m.batch : r.chunk_dim == AC_DIM_FEATURE ? m.d_model : m.seq) : m.n_res;
+    if (m.workload == AC_TRANSFORMER_STACK && r.chunk_dim == AC_DIM_FEATURE) {
+      // a segment of the context is a run of whole heads; a block of output columns starts on a 16-byte boundary
+      const int64_t g = r.kind == AC_REGION_ATTENTION ? m.head_dim : 8;
+      if (r.chunk_len % g != 0) {
+        delete p;
+        return fail(AC_ERR_ARG, "feature chunk of region %d must be a multiple of %lld", r.kind, (long long)g);
+      }
+    }
     if (r.chunk_len == 0) {
       s.sized_by_budget = act_budget_bytes > 0;
       s.chunk_len = s.extent;
@@ -1118,6 +1149,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
   // region bytes fit; explicit lengths are checked against the same bound.
   const int64_t row_granule = m.workload == AC_PAIR_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
   auto granule_of = [&](const Setting& s) -> int64_t {
+    if (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_FEATURE) return &s == &p->set[AC_REGION_ATTENTION] ? m.head_dim : 8;
     return (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_BATCH) ? 1 : row_granule;
   };
   auto rows_of = [&](const Setting& s, int64_t len) { return model_rows(m, s, len); };

@@ -120,6 +120,43 @@ def test_batch_and_batch_chunks(B):
     check(host(y), r32.oracle(), "f32")
 
 
+def test_feature_chunks(B):
+    """Section 3.3 leaves two feature dims legal: the attention core in runs of whole heads and the
+    output projection in blocks of output columns.  Both span all rows.  Fused, neither region holds a
+    tensor per segment, so the segments share one launch; with stored scores a head chunk divides the
+    stored score and probability tensors, and the unfused output projection holds its block only."""
+    import torch
+    cfg = I.TransformerConfig("tfeat", 37, 2, 200, 128, 4, 256, True, "bf16", 0.05, batch=2)
+    r = Runner(B, cfg, bias_std=0.05, ln_jitter=0.1)
+    ref = r.oracle()
+    F, S_ = B.AC_DIM_FEATURE, B.AC_DIM_SEQ
+    plan = lambda c_att, c_out: [(B.AC_REGION_QKV, S_, 64), (B.AC_REGION_ATTENTION, F, c_att),
+                                 (B.AC_REGION_OUT_PROJ, F, c_out), (B.AC_REGION_FFN, S_, 64)]
+    y0, _ = r.run(regions(B, 64, 64, 64))
+    yf, info = r.run(plan(64, 48))
+    assert [x.n_segments for x in info.regions[1:3]] == [2, 3] and [x.launches for x in info.regions[1:3]] == [1, 1]
+    assert torch.equal(yf, y0)
+    check(host(yf), ref, "bf16", depth=2)
+    # stored scores: one head at a time
+    st = B.AC_FLAG_MATERIALIZED_SCORES
+    ys, i_whole = r.run(regions(B, 200, 200, 200), flags=st)
+    yh, i_heads = r.run(plan(32, 128), flags=st)
+    assert i_heads.regions[1].n_segments == 4 and i_heads.regions[1].launches == 4
+    assert torch.equal(yh, ys)
+    check(host(yh), ref, "bf16", depth=2)
+    al = lambda n: (n + 255) // 256 * 256
+    scores = lambda batch, heads: 2 * al(batch * heads * cfg.seq * cfg.seq * 2)     # scores + probabilities, bf16
+    # a sequence segment is one batch element with all its heads, a head segment all batch elements with one head
+    assert i_whole.workspace_bytes - i_heads.workspace_bytes == scores(1, 4) - scores(cfg.batch, 1)
+    # unfused output projection, one block of 32 columns at a time
+    un = B.AC_FLAG_UNFUSED_ELEMENTWISE
+    yu0, _ = r.run(regions(B, 64, 64, 64), flags=un)
+    yu, i_un = r.run(plan(128, 32), flags=un)
+    assert i_un.regions[2].launches == 4
+    assert torch.equal(yu, yu0)
+    check(host(yu), ref, "bf16", depth=2)
+
+
 def test_budget_sized_plan_runs(B):
     cfg = I.TransformerConfig("tbud", 35, 1, 1024, 256, 4, 1024, True, "bf16", 0.05)
     r = Runner(B, cfg)

@@ -290,9 +290,15 @@ def test_legality_and_errors():
     for dim in (B.AC_DIM_FEATURE, B.AC_DIM_HEAD_DIM, B.AC_DIM_KEY):
         for kind in (B.AC_REGION_QKV, B.AC_REGION_ATTENTION, B.AC_REGION_OUT_PROJ, B.AC_REGION_FFN):
             # by the rules the context can be cut in whole heads and the output projection in blocks
-            # of columns (tests/test_search_host.py reads both off the graph); no kernel here does
+            # of columns (tests/test_search_host.py reads both off the graph)
             legal = dim == B.AC_DIM_FEATURE and kind in (B.AC_REGION_ATTENTION, B.AC_REGION_OUT_PROJ)
-            expect(B.AC_ERR_UNSUPPORTED if legal else B.AC_ERR_ILLEGAL_CHUNK_DIM, lambda: B.Plan(d, [(kind, dim, 64)]))
+            if not legal:
+                expect(B.AC_ERR_ILLEGAL_CHUNK_DIM, lambda: B.Plan(d, [(kind, dim, 64)]))
+                continue
+            info = B.Plan(d, [(kind, dim, 128)]).ac_plan_query()
+            assert info.regions[kind].n_segments == I.C3.d_model // 128 and info.regions[kind].launches == 1
+            # whole heads (64 wide here); blocks of columns that start on 16-byte boundaries
+            expect(B.AC_ERR_ARG, lambda: B.Plan(d, [(kind, dim, 96 if kind == B.AC_REGION_ATTENTION else 100)]))
     B.Plan(d, [(B.AC_REGION_ATTENTION, B.AC_DIM_BATCH, 1)]).close()
     expect(B.AC_ERR_ARG, lambda: B.Plan(d, [(B.AC_REGION_ATTENTION, 9, 64)]))
     expect(B.AC_ERR_ARG, lambda: B.Plan(d, [(B.AC_REGION_TRIMUL_OUT, 0, 64)]))
