@@ -165,10 +165,11 @@ int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int 
  * S = [s_1 .. s_l] of least summed cost (section 3.4).  One pass extends a strategy by one
  * chunk: the legal chunks of ac_chunk_search(peak node, window, hoist) that touch no region
  * chosen before get the longest chunk_len (multiple of the granule, below the extent) at
- * which their region fits the budget; those with none are dropped.  The `beam` strategies of
- * least summed cost (ties: fewer segments in all, then the order they were made in) are kept
- * from pass to pass; strategies that fit stay as they are; the call ends when all that are
- * kept fit and returns the first.  beam = 1: every pass takes its cheapest candidate.
+ * which their region fits the budget; those with none are dropped.  An extended strategy that
+ * fits competes for the answer (least summed cost; ties: fewer segments in all, then the order
+ * they were made in) and takes no place in the beam; of those that do not fit yet the `beam`
+ * cheapest go on to the next pass; the call ends when none is left and returns the cheapest
+ * strategy that fitted.  beam = 1: follow the cheapest candidate that does not fit yet.
  * out (max_out entries, caller's) receives the chunks in the order chosen, *n_out their
  * number, *peak_bytes the estimate with them.  AC_ERR_BUDGET_INFEASIBLE when no strategy in
  * the beam can be extended (*n_out = 0, *peak_bytes = the unchunked peak); AC_ERR_ARG when
@@ -177,6 +178,34 @@ int ac_graph_chunk_cost(const ac_graph_node* nodes, int n_nodes, int start, int 
 int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_bytes, uint64_t budget_bytes,
                   int window, const double* weights, int beam, int hoist, ac_graph_chunk* out,
                   int max_out, int* n_out, uint64_t* peak_bytes);
+
+/*
+ * What ties a node of a model's op graph to the executor of autochunk_rt.h: the region kind
+ * whose kernels compute the node (AC_REGION_*, -1: none), the layer or block it belongs to, and
+ * for every dim of its result the executor's chunk dim it is (AC_DIM_* of the workload, -1: the
+ * executor has no such dim) with the number of executor units one index of the graph dim
+ * stands for (a head of a [batch, heads, seq, head_dim] tensor is head_dim features).
+ */
+typedef struct ac_node_tag {
+  int32_t region_kind, group;
+  int32_t dim[AC_GRAPH_MAX_RANK];
+  int64_t unit[AC_GRAPH_MAX_RANK];
+} ac_node_tag;
+
+/*
+ * From chunks chosen on a graph (ac_graph_plan) to the chunk settings ac_plan_create takes
+ * (section 3.2: the plan found by the passes is what the runtime executes; section 3.3, rule 4:
+ * one setting per region).  A chunk goes to the region kind that holds all its nodes, within one
+ * group; the executor cuts a kind in every layer alike, so a kind takes the shortest length
+ * asked for in any group.  out (max_out entries, caller's) receives one ac_region_desc per kind,
+ * ordered by kind; *n_out their number.  AC_ERR_ARG: a chunk's nodes lie in no single kind or
+ * group, groups disagree on a kind's dim, bad indices, more kinds than max_out;
+ * AC_ERR_UNSUPPORTED: a chunk is cut along a dim the executor has no chunk dim for.  Whether
+ * the executor accepts the settings (legality, granules) is ac_plan_create's to say.
+ */
+struct ac_region_desc;
+int ac_graph_chunks_to_regions(const ac_node_tag* tags, int n_nodes, const ac_graph_chunk* chunks, int n_chunks,
+                               struct ac_region_desc* out, int max_out, int* n_out);
 
 #ifdef __cplusplus
 }

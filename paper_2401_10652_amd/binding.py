@@ -99,6 +99,11 @@ class ac_graph_chunk(C.Structure):
                 ("chunk_len", C.c_int64)]
 
 
+class ac_node_tag(C.Structure):
+    _fields_ = [("region_kind", C.c_int32), ("group", C.c_int32), ("dim", C.c_int32 * AC_GRAPH_MAX_RANK),
+                ("unit", C.c_int64 * AC_GRAPH_MAX_RANK)]
+
+
 I64, U64, VP, INT, F32 = C.c_int64, C.c_uint64, C.c_void_p, C.c_int, C.c_float
 I32P, INTP, U8P = C.POINTER(C.c_int32), C.POINTER(C.c_int), C.POINTER(C.c_uint8)
 
@@ -141,6 +146,8 @@ SIGNATURES = {
                                   C.POINTER(C.c_double)]),
     "ac_graph_plan": (INT, [C.POINTER(ac_graph_node), INT, INT, U64, INT, C.POINTER(C.c_double), INT, INT,
                             C.POINTER(ac_graph_chunk), INT, INTP, C.POINTER(U64)]),
+    "ac_graph_chunks_to_regions": (INT, [C.POINTER(ac_node_tag), INT, C.POINTER(ac_graph_chunk), INT,
+                                         C.POINTER(ac_region_desc), INT, INTP]),
 }
 
 _lib = None
@@ -511,6 +518,29 @@ def ac_graph_chunk_cost(nodes, start, end, out_dim, weights, hoist=False):
     _check(lib().ac_graph_chunk_cost(nodes, len(nodes), start, end, out_dim, int(hoist), w, C.byref(cost)),
            "ac_graph_chunk_cost")
     return cost.value
+
+
+def node_tags(tags):
+    """ctypes array of ac_node_tag from [(region_kind, group, ((dim, unit), ...))], one entry per node."""
+    arr = (ac_node_tag * len(tags))()
+    for t, (kind, group, dims) in zip(arr, tags):
+        t.region_kind, t.group = kind, group
+        for i in range(AC_GRAPH_MAX_RANK):
+            t.dim[i], t.unit[i] = dims[i] if i < len(dims) else (-1, 0)
+    return arr
+
+
+def ac_graph_chunks_to_regions(tags, chunks):
+    """[(kind, chunk_dim, chunk_len)] for ac_plan_create from chunks (start, end, out_dim, chunk_len[, hoist])."""
+    arr = (ac_graph_chunk * max(1, len(chunks)))()
+    for a, c in zip(arr, chunks):
+        a.start, a.end, a.out_dim, a.chunk_len = c[:4]
+        a.hoist = c[4] if len(c) > 4 else 0
+    out = (ac_region_desc * AC_REGION_KINDS)()
+    n_out = C.c_int(0)
+    _check(lib().ac_graph_chunks_to_regions(tags, len(tags), arr, len(chunks), out, AC_REGION_KINDS, C.byref(n_out)),
+           "ac_graph_chunks_to_regions")
+    return [(r.kind, r.chunk_dim, r.chunk_len) for r in out[:n_out.value]]
 
 
 def ac_graph_plan(nodes, elem_bytes, budget_bytes, window, weights, beam=1, max_out=64, hoist=False):

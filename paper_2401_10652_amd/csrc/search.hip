@@ -764,3 +764,45 @@ extern "C" int ac_graph_plan(const ac_graph_node* nodes, int n_nodes, int elem_b
   *peak_bytes = estimate_of(best, &peak_node);
   return AC_OK;
 }
+
+extern "C" int ac_graph_chunks_to_regions(const ac_node_tag* tags, int n_nodes, const ac_graph_chunk* chunks, int n_chunks,
+                                          ac_region_desc* out, int max_out, int* n_out) {
+  if (n_out) *n_out = 0;
+  if (!tags || !n_out || n_nodes < 1 || n_chunks < 0 || max_out < 0 || (n_chunks > 0 && (!chunks || !out)))
+    return bad("ac_graph_chunks_to_regions: null or negative argument");
+  struct Kind { bool set = false; int dim = 0, group = 0; int64_t len = 0; };
+  Kind kinds[AC_REGION_KINDS];
+  for (int c = 0; c < n_chunks; ++c) {
+    const ac_graph_chunk& ch = chunks[c];
+    if (ch.start < 0 || ch.end < ch.start || ch.end >= n_nodes || ch.out_dim < 0 || ch.out_dim >= AC_GRAPH_MAX_RANK || ch.chunk_len < 1)
+      return bad("ac_graph_chunks_to_regions: chunk %d: bad region [%d, %d], dim %d or length", c, ch.start, ch.end, ch.out_dim);
+    const ac_node_tag& last = tags[ch.end];
+    if (last.region_kind < 0 || last.region_kind >= AC_REGION_KINDS)
+      return bad("ac_graph_chunks_to_regions: chunk %d ends at node %d, which no region kind of the executor computes", c, ch.end);
+    for (int i = ch.start; i <= ch.end; ++i)
+      if (tags[i].region_kind != last.region_kind || tags[i].group != last.group)
+        return bad("ac_graph_chunks_to_regions: chunk [%d, %d] lies in no single region kind of one layer (node %d)", ch.start, ch.end, i);
+    const int dim = last.dim[ch.out_dim];
+    const int64_t unit = last.unit[ch.out_dim];
+    if (dim < 0 || unit < 1) {
+      ac::set_error("ac_graph_chunks_to_regions: chunk [%d, %d] is cut along dim %d of node %d: the executor has no such chunk dim",
+                    ch.start, ch.end, ch.out_dim, ch.end);
+      return AC_ERR_UNSUPPORTED;
+    }
+    Kind& k = kinds[last.region_kind];
+    const int64_t len = ch.chunk_len * unit;
+    if (k.set && k.dim != dim)
+      return bad("ac_graph_chunks_to_regions: layers %d and %d disagree on the chunk dim of region kind %d", k.group, last.group, last.region_kind);
+    k.len = k.set ? std::min(k.len, len) : len;
+    k.set = true; k.dim = dim; k.group = last.group;
+  }
+  int n = 0;
+  for (int kind = 0; kind < AC_REGION_KINDS; ++kind) {
+    if (!kinds[kind].set) continue;
+    if (n >= max_out) return bad("ac_graph_chunks_to_regions: more than %d region kinds", max_out);
+    out[n].kind = kind; out[n].chunk_dim = kinds[kind].dim; out[n].chunk_len = kinds[kind].len;
+    ++n;
+  }
+  *n_out = n;
+  return AC_OK;
+}

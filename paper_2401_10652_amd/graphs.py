@@ -56,44 +56,84 @@ def transformer_stack_graph(batch, seq, d_model, heads, d_ffn, layers=1):
     return g.spec, g.names
 
 
-# What each dimension of a node of transformer_stack_graph means, by node name.
-_BSD = ("batch", "seq", "feature")
-_BHSD = ("batch", "heads", "seq", "head_dim")
-_BHSS = ("batch", "heads", "seq", "key")
-_BSHD = ("batch", "seq", "heads", "head_dim")
-_MEANING = {"u": _BSD, "qkv": _BSD, "scores": _BHSS, "scaled": _BHSS, "probs": _BHSS, "ctx_h": _BHSD, "ctx_t": _BSHD,
-            "ctx": _BSD, "o": _BSD, "h": _BSD, "u2": _BSD, "t": _BSD, "act": _BSD, "down": _BSD, "y": _BSD}
-for _t in "qkv":
-    _MEANING.update({_t + "_flat": _BSD, _t + "_split": _BSHD, _t + "_h": _BHSD})
+# What each dimension of a node of transformer_stack_graph is to the executor, by node name:
+# (chunk dim, executor units per index).  A head is head_dim features; head_dim and key positions
+# are no chunk dims of the executor (section 3.3 excludes them anyway: they are reduced over).
+def _transformer_dims(name, head_dim):
+    b, s, f, h, no = (B.AC_DIM_BATCH, 1), (B.AC_DIM_SEQ, 1), (B.AC_DIM_FEATURE, 1), (B.AC_DIM_FEATURE, head_dim), (-1, 0)
+    if name in ("scores", "scaled", "probs") or name.endswith("_h"):
+        return (b, h, s, no)                       # [batch, heads, seq, key | head_dim]
+    if name.endswith("_split") or name == "ctx_t":
+        return (b, s, h, no)                       # [batch, seq, heads, head_dim]
+    return (b, s, f)                               # [batch, seq, feature]
+
 
 # Node spans of the executor's region kinds within a layer (first node, last node).
 _KIND_SPANS = ((B.AC_REGION_QKV, "u", "v_h"), (B.AC_REGION_ATTENTION, "scores", "ctx"),
                (B.AC_REGION_OUT_PROJ, "o", "h"), (B.AC_REGION_FFN, "u2", "y"))
 
 
-def executor_regions(chunks, names):
+def transformer_stack_tags(names, head_dim):
+    """ac_node_tag entries for the nodes of a transformer_stack_graph: which region kind of the executor
+    computes a node, in which layer, and what its dims are to the executor.  Data about the graph;
+    what is done with it is ac_graph_chunks_to_regions'."""
+    tags = [(-1, 0, ())] * len(names)
+    for full, idx in names.items():
+        prefix, _, last = full.rpartition(".")
+        layer = int(prefix[1:]) if prefix else 0
+        where = (lambda nm: names.get(f"{prefix}.{nm}" if prefix else nm, -1))
+        kind = next((k for k, a, b in _KIND_SPANS if where(a) >= 0 and where(a) <= idx <= where(b)), -1)
+        if kind >= 0:
+            tags[idx] = (kind, layer, _transformer_dims(last, head_dim))
+    return B.node_tags(tags)
+
+
+def executor_regions(chunks, names, head_dim=1):
     """Region settings for ac_plan_create, [(kind, chunk_dim, chunk_len)], from chunks
     [(start, end, out_dim, chunk_len)] of a transformer_stack_graph (as ac_graph_plan returns
-    them).  A chunk goes to the region kind whose nodes hold it; the executor cuts the whole
-    kind, in every layer, so one kind takes the shortest length asked for in any layer.
-    Raises ValueError for a chunk that spans two kinds, that is cut along a dimension the
-    executor has no kernel for, or when layers disagree on the dimension."""
-    by_index = {v: k for k, v in names.items()}
-    settings = {}
-    for start, end, out_dim, chunk_len in (c[:4] for c in chunks):     # a fifth entry (hoist) changes nothing here
-        prefix, _, last = by_index[end].rpartition(".")
-        where = (lambda nm: names[f"{prefix}.{nm}" if prefix else nm])
-        kind = next((k for k, a, b in _KIND_SPANS if where(a) <= start and end <= where(b)), None)
-        if kind is None:
-            raise ValueError(f"chunk [{by_index[start]}, {by_index[end]}] lies in no single region kind of the executor")
-        meaning = _MEANING[last][out_dim]
-        if meaning not in ("batch", "seq"):
-            raise ValueError(f"chunk [{by_index[start]}, {by_index[end]}] is cut along {meaning}: no kernel")
-        dim = B.AC_DIM_BATCH if meaning == "batch" else B.AC_DIM_SEQ
-        if kind in settings and settings[kind][0] != dim:
-            raise ValueError(f"layers disagree on the chunk dimension of region kind {kind}")
-        settings[kind] = (dim, min(chunk_len, settings.get(kind, (dim, chunk_len))[1]))
-    return [(kind, dim, clen) for kind, (dim, clen) in sorted(settings.items())]
+    them).  Raises AcError for a chunk that spans two kinds or layers, that is cut along a dimension
+    the executor has no chunk dim for, or when layers disagree on the dimension.  head_dim is needed
+    only for chunks along the heads."""
+    return B.ac_graph_chunks_to_regions(transformer_stack_tags(names, head_dim), chunks)
+
+
+# Pair block: the chunked part of each module (what the executor runs per segment; the whole operands of
+# a module, a and b, or keys, values and bias, are its non-chunkable inputs and belong to no kind).
+_PAIR_PARTS = {
+    "tmo": (B.AC_REGION_TRIMUL_OUT, ("gate", "o", "on", "ol", "upd", "z")),
+    "tmi": (B.AC_REGION_TRIMUL_IN, ("gate", "o", "on", "ol", "upd", "z")),
+    "tas": (B.AC_REGION_TRIATT_START, ("q", "q_split", "q_h", "gate", "scores", "biased", "probs", "ctx_h", "ctx_t", "ctx",
+                                        "gated", "o", "z")),
+    "tae": (B.AC_REGION_TRIATT_END, ("q", "q_split", "q_h", "gate", "scores", "biased", "probs", "ctx_h", "ctx_t", "ctx",
+                                      "gated", "o", "o_t", "z")),
+    "pt": (B.AC_REGION_PAIR_TRANSITION, ("u", "t", "act", "down", "z")),
+}
+
+
+def pair_block_tags(names):
+    """ac_node_tag entries for a pair_block_graph.  Dim 0 of a module's tensors is the row i of z and the
+    dim that holds the other position index its column j - except inside the ending-node attention,
+    which the graph writes on the transposed pair tensor: there dim 0 is the column."""
+    row, col, no = (B.AC_DIM_ROW, 1), (B.AC_DIM_COL, 1), (-1, 0)
+    tags = [(-1, 0, ())] * len(names)
+    for full, idx in names.items():
+        prefix, _, last = full.rpartition(".")
+        if prefix not in _PAIR_PARTS or last not in _PAIR_PARTS[prefix][1]:
+            continue
+        first, second = (col, row) if prefix == "tae" and last not in ("o_t", "z") else (row, col)
+        if last in ("q_h", "scores", "biased", "probs", "ctx_h"):
+            dims = (first, no, second, no)            # [i, heads, j, key | head_dim]
+        elif last in ("q_split", "ctx_t"):
+            dims = (first, second, no, no)            # [i, j, heads, head_dim]
+        else:
+            dims = (first, second, no)                # [i, j, channels]
+        tags[idx] = (_PAIR_PARTS[prefix][0], 0, dims)
+    return B.node_tags(tags)
+
+
+def pair_executor_regions(chunks, names):
+    """As executor_regions, for chunks of a pair_block_graph."""
+    return B.ac_graph_chunks_to_regions(pair_block_tags(names), chunks)
 
 
 def pair_block_graph(n_res, c_z, c_hidden, heads, head_dim, transition_factor):

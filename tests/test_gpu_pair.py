@@ -82,6 +82,29 @@ def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, 
     return z, w, y, info
 
 
+def test_chunks_planned_on_the_pair_graph_run_in_the_executor(B):
+    """The chain for the pair block: its unfused graph is chunked to 0.6 of its estimated peak (sections 3.2 to
+    3.4), ac_graph_chunks_to_regions turns the chunks into region settings - rows for the starting-node
+    attention, columns for the ending-node one - and the plan they give equals the oracle."""
+    from paper_2401_10652_amd import graphs as PG
+    n, cz, ch, heads, dh = 128, 64, 64, 4, 32
+    cfg = I.PairConfig("tpg", 45, n, cz, ch, heads, dh, 4, "bf16")
+    spec, names = PG.pair_block_graph(n, cz, ch, heads, dh, 4)
+    nodes = B.graph_nodes(spec)
+    _, whole, _ = B.ac_graph_estimate(nodes, 2)
+    chunks, peak = B.ac_graph_plan(nodes, 2, whole * 6 // 10, 12, (1.0, 0.0, 0.0, 0.0), beam=2)
+    regs = dict((k, (d, l)) for k, d, l in PG.pair_executor_regions(chunks, names))
+    assert regs[B.AC_REGION_TRIATT_START][0] == B.AC_DIM_ROW and regs[B.AC_REGION_TRIATT_END][0] == B.AC_DIM_COL
+    kinds = range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)
+    dims = tuple(regs.get(k, (B.AC_DIM_ROW, n))[0] for k in kinds)
+    lens = tuple(regs.get(k, (B.AC_DIM_ROW, n))[1] for k in kinds)
+    z, w, y, info = run_pair(B, cfg, lens, dims=dims)
+    assert any(r.n_segments > 1 for r in info.regions[:5])
+    check(host(y), P.pair_block(z, w, heads, cfg.activation, cfg.ln_eps), "bf16", depth=5)
+    _, _, y1, info1 = run_pair(B, cfg, (n,) * 5)
+    assert info.workspace_bytes < info1.workspace_bytes
+
+
 @pytest.mark.parametrize("dtype,n,cz,ch,heads,dh", [("f32", 40, 32, 16, 2, 16), ("bf16", 40, 32, 16, 2, 16),
                                                     ("bf16", 192, 64, 64, 2, 32), ("bf16", 72, 128, 128, 4, 32),
                                                     ("bf16", 136, 128, 64, 4, 32)])

@@ -10,6 +10,7 @@ from oracle import chunk_search as S
 from oracle import graph_memory as GM
 from paper_2401_10652_amd import binding as B
 from paper_2401_10652_amd import graphs as PG
+from paper_2401_10652_amd import inputs as I
 from tests import graphs as G
 from tests.test_oracle_graph_memory import hoisting_chunks, some_chunks
 from tests.test_search_host import library_nodes, oracle_nodes
@@ -173,13 +174,55 @@ def test_calibration_reads_the_four_terms_of_the_cost():
 
 
 def test_chunks_map_to_executor_region_settings():
+    """ac_graph_chunks_to_regions: a chunk goes to the region kind that holds its nodes; a kind takes the
+    shortest length any layer asks for; the graph side only says which node is what (the tags)."""
     spec, nm = PG.transformer_stack_graph(1, 64, 16, 2, 32, layers=2)
     regs = PG.executor_regions([(nm["scores"], nm["ctx_h"], 2, 24), (nm["l1.scores"], nm["l1.ctx"], 1, 16, 1),
                                 (nm["l1.t"], nm["l1.down"], 1, 32)], nm)
     assert regs == [(B.AC_REGION_ATTENTION, B.AC_DIM_SEQ, 16), (B.AC_REGION_FFN, B.AC_DIM_SEQ, 32)]
     assert PG.executor_regions([(nm["u"], nm["qkv"], 0, 1)], nm) == [(B.AC_REGION_QKV, B.AC_DIM_BATCH, 1)]
-    for bad in ([(nm["scores"], nm["ctx_h"], 1, 1)],                       # along the heads: no kernel
-                [(nm["ctx"], nm["h"], 1, 8)],                              # spans attention and output projection
-                [(nm["scores"], nm["ctx_h"], 2, 8), (nm["l1.scores"], nm["l1.ctx_h"], 0, 1)]):   # layers disagree
-        with pytest.raises(ValueError):
+    # along the heads: a feature chunk of whole heads (head_dim 8 here); along the output columns of the projection
+    assert PG.executor_regions([(nm["scores"], nm["ctx_h"], 1, 1)], nm, head_dim=8) == [(B.AC_REGION_ATTENTION, B.AC_DIM_FEATURE, 8)]
+    assert PG.executor_regions([(nm["o"], nm["h"], 2, 8)], nm) == [(B.AC_REGION_OUT_PROJ, B.AC_DIM_FEATURE, 8)]
+    # ... and the settings are ones the executor takes
+    cfg = I.TransformerConfig("tmap", 1, 2, 64, 16, 2, 32, True, "bf16", 0.05)
+    info = B.Plan(B.transformer_desc(cfg), PG.executor_regions([(nm["scores"], nm["ctx_h"], 1, 1)], nm, head_dim=8)).ac_plan_query()
+    assert info.regions[B.AC_REGION_ATTENTION].n_segments == 2
+    for bad, status in (([(nm["scores"], nm["ctx_h"], 3, 4)], B.AC_ERR_UNSUPPORTED),        # along head_dim: no such chunk dim
+                        ([(nm["ctx"], nm["h"], 1, 8)], B.AC_ERR_ARG),                       # spans attention and output projection
+                        ([(nm["y"], nm["l1.u"], 1, 8)], B.AC_ERR_ARG),                      # spans two layers
+                        ([(nm["scores"], nm["ctx_h"], 2, 8), (nm["l1.scores"], nm["l1.ctx_h"], 0, 1)], B.AC_ERR_ARG),   # layers disagree
+                        ([(nm["x"], nm["x"], 0, 1)], B.AC_ERR_ARG),                         # no region kind computes an input
+                        ([(nm["scores"], len(spec), 2, 8)], B.AC_ERR_ARG)):
+        with pytest.raises(B.AcError) as ei:
             PG.executor_regions(bad, nm)
+        assert ei.value.status == status
+
+
+def test_pair_chunks_map_to_executor_region_settings():
+    """The plan of the pair block's graph goes to the executor: rows of the starting-node attention, and for
+    the ending-node attention (which the graph writes on the transposed pair tensor) columns."""
+    n, c, ch, heads, dh = 64, 16, 16, 2, 8
+    spec, nm = PG.pair_block_graph(n, c, ch, heads, dh, 4)
+    nodes = B.graph_nodes(spec)
+    _, whole, peak_node = B.ac_graph_estimate(nodes, 2)
+    chunks, peak = B.ac_graph_plan(nodes, 2, whole // 2, 12, (1.0, 0.0, 0.0, 0.0), beam=2)
+    assert chunks and peak <= whole // 2
+    regs = PG.pair_executor_regions(chunks, nm)
+    kinds = {k: (d, l) for k, d, l in regs}
+    assert set(kinds) <= {B.AC_REGION_TRIATT_START, B.AC_REGION_TRIATT_END, B.AC_REGION_TRIMUL_OUT, B.AC_REGION_TRIMUL_IN,
+                          B.AC_REGION_PAIR_TRANSITION}
+    assert kinds[B.AC_REGION_TRIATT_START][0] == B.AC_DIM_ROW and kinds[B.AC_REGION_TRIATT_END][0] == B.AC_DIM_COL
+    assert all(1 <= l < n for _, l in kinds.values())
+    cfg = I.PairConfig("pmap", 2, n, c, ch, heads, dh, 4, "bf16")
+    info = B.Plan(B.pair_desc(cfg), regs).ac_plan_query()
+    by_kind = {r.kind: r for r in info.regions[:info.n_regions]}
+    assert by_kind[B.AC_REGION_TRIATT_END].chunk_dim == B.AC_DIM_COL
+    assert by_kind[B.AC_REGION_TRIATT_START].n_segments > 1
+    # by hand: rows of the scores of the starting node; the transposed tensor's rows are z's columns
+    assert PG.pair_executor_regions([(nm["tas.scores"], nm["tas.ctx_h"], 0, 5)], nm) == [(B.AC_REGION_TRIATT_START, B.AC_DIM_ROW, 5)]
+    assert PG.pair_executor_regions([(nm["tae.scores"], nm["tae.ctx_h"], 0, 5)], nm) == [(B.AC_REGION_TRIATT_END, B.AC_DIM_COL, 5)]
+    assert PG.pair_executor_regions([(nm["tae.scores"], nm["tae.ctx_h"], 2, 5)], nm) == [(B.AC_REGION_TRIATT_END, B.AC_DIM_ROW, 5)]
+    assert PG.pair_executor_regions([(nm["tmo.o"], nm["tmo.z"], 1, 6)], nm) == [(B.AC_REGION_TRIMUL_OUT, B.AC_DIM_COL, 6)]
+    with pytest.raises(B.AcError):      # the b operand is read whole by every segment: it belongs to no chunked part
+        PG.pair_executor_regions([(nm["tmo.b"], nm["tmo.z"], 0, 6)], nm)
