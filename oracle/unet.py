@@ -1,0 +1,69 @@
+"""fp64 CPU oracle: residual block of a UNet stage.  Test infrastructure.
+
+The paper (AutoChunk, section 4) evaluates a UNet (stable diffusion) without defining its
+modules.  The reading bound here is the residual block of the latent-diffusion UNet, written
+channels-last, x [B, H, W, C], one time-embedding vector per image already projected to C
+channels, temb [B, C]:
+
+  h = conv3x3(SiLU(GroupNorm(x)); w1) + b1 + temb[:, None, None, :]
+  y = x + conv3x3(SiLU(GroupNorm(h)); w2) + b2
+
+GroupNorm: the C channels of an image in `groups` runs of C / groups consecutive channels;
+mean and biased variance over a run's channels and all H * W positions, then a gain and a
+shift per channel.  SiLU(v) = v * sigmoid(v).  conv3x3: stride 1, zero padding 1, weights
+[C_out, 3, 3, C_in]: out[b, h, w, o] = sum_{kh, kw, i} in[b, h + kh - 1, w + kw - 1, i] w[o, kh, kw, i].
+Dropout omitted; the input and output channel counts are equal (no skip projection).
+
+Images are independent of each other in every op of the block (section 3.3: the batch dim is
+the legal chunk dim; GroupNorm reduces over positions and channels, the convolution over its
+window and the input channels), so `images` picks the ones to evaluate.  Nothing is blocked
+or reordered; the sum over the nine taps is written out, each tap a matrix product.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def silu(v):
+    v = np.asarray(v, np.float64)
+    return v / (1.0 + np.exp(-v))
+
+
+def group_norm(x, gain, shift, groups, eps=1e-5):
+    """x [B, H, W, C] -> same shape."""
+    x = np.asarray(x, np.float64)
+    b, h, w, c = x.shape
+    assert c % groups == 0
+    g = x.reshape(b, h * w, groups, c // groups)
+    mean = g.mean(axis=(1, 3), keepdims=True)
+    var = ((g - mean) ** 2).mean(axis=(1, 3), keepdims=True)
+    n = ((g - mean) / np.sqrt(var + eps)).reshape(b, h, w, c)
+    return n * np.asarray(gain, np.float64) + np.asarray(shift, np.float64)
+
+
+def conv3x3(x, w, bias=None):
+    """x [B, H, W, C_in], w [C_out, 3, 3, C_in] -> [B, H, W, C_out]."""
+    x = np.asarray(x, np.float64)
+    w = np.asarray(w, np.float64)
+    b, h, wd, ci = x.shape
+    co = w.shape[0]
+    assert w.shape == (co, 3, 3, ci)
+    xp = np.zeros((b, h + 2, wd + 2, ci))
+    xp[:, 1:h + 1, 1:wd + 1] = x
+    out = np.zeros((b, h, wd, co))
+    for kh in range(3):
+        for kw in range(3):
+            out += xp[:, kh:kh + h, kw:kw + wd] @ w[:, kh, kw].T
+    if bias is not None:
+        out += np.asarray(bias, np.float64)
+    return out
+
+
+def res_block(x, temb, w, groups, eps=1e-5, images=None):
+    """y [len(images), H, W, C]; w: gn1_g, gn1_b, w1, b1, gn2_g, gn2_b, w2, b2."""
+    x = np.asarray(x, np.float64)
+    temb = np.asarray(temb, np.float64)
+    if images is not None:
+        x, temb = x[np.asarray(images)], temb[np.asarray(images)]
+    h = conv3x3(silu(group_norm(x, w["gn1_g"], w["gn1_b"], groups, eps)), w["w1"], w["b1"]) + temb[:, None, None, :]
+    return x + conv3x3(silu(group_norm(h, w["gn2_g"], w["gn2_b"], groups, eps)), w["w2"], w["b2"])
