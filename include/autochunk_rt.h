@@ -48,10 +48,10 @@ typedef enum ac_status {
   AC_ERR_UNSUPPORTED = -8         /* legal, but no kernel here covers that shape or chunk dim */
 } ac_status;
 
-typedef enum ac_workload { AC_TRANSFORMER_STACK = 0, AC_PAIR_STACK = 1 } ac_workload;
+typedef enum ac_workload { AC_TRANSFORMER_STACK = 0, AC_PAIR_STACK = 1, AC_UNET_RES_STACK = 2 } ac_workload;
 typedef enum ac_dtype { AC_F32 = 0, AC_BF16 = 1 } ac_dtype;
 typedef enum ac_activation { AC_ACT_NONE = 0, AC_ACT_GELU_ERF = 1, AC_ACT_GELU_TANH = 2,
-                             AC_ACT_RELU = 3, AC_ACT_SIGMOID = 4 } ac_activation;
+                             AC_ACT_RELU = 3, AC_ACT_SIGMOID = 4, AC_ACT_SILU = 5 } ac_activation;
 
 /* Region kinds.  Transformer layer: QKV, ATTENTION, OUT_PROJ, FFN in this order.  Pair-stack
  * block: TRIMUL_OUT, TRIMUL_IN, TRIATT_START, TRIATT_END, PAIR_TRANSITION in this order.
@@ -68,7 +68,9 @@ typedef enum ac_region_kind {
   AC_REGION_TRIATT_START = 6,   /* triangle self-attention around the starting node       */
   AC_REGION_TRIATT_END = 7,     /* triangle self-attention around the ending node         */
   AC_REGION_PAIR_TRANSITION = 8,
-  AC_REGION_KINDS = 9
+  AC_REGION_RES_BLOCK = 9,      /* UNet residual block: GroupNorm, SiLU, 3x3 convolution, time
+                                   embedding, again, skip (section 4 names the family)       */
+  AC_REGION_KINDS = 10
 } ac_region_kind;
 
 /* Chunk dimensions are named per workload.  Transformer regions see their tensors as
@@ -129,7 +131,12 @@ typedef struct ac_model_desc {
   /* pair stack: z is [n_res, n_res, c_z] */
   int32_t n_res, c_z, c_hidden, tri_heads, tri_head_dim, transition_factor;
   int32_t flags;
-  float ln_eps;          /* LayerNorm epsilon (biased variance) */
+  float ln_eps;          /* LayerNorm / GroupNorm epsilon (biased variance) */
+  /* UNet residual stack (bf16 only): x and y are channels-last images [batch, img_h, img_w, channels];
+   * `layers` residual blocks one after another, GroupNorm over `groups` runs of consecutive channels.
+   * Its one region kind is chunked along the batch (AC_DIM_BATCH): every other dim is reduced over by
+   * a GroupNorm or by a convolution window (section 3.3). */
+  int32_t img_h, img_w, channels, groups;
 } ac_model_desc;
 
 typedef struct ac_region_desc {
@@ -413,6 +420,31 @@ int ac_op_transpose_square_inplace(void* data, int64_t ld, int64_t stride_batch,
 int ac_op_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain,
                                   const void* shift, void* dst, int64_t ldd, int64_t positions,
                                   int64_t channels, float eps, int dtype, void* stream);
+
+/*
+ * GroupNorm of channels-last images x [images, positions, channels] (the UNet residual block's
+ * normalisation; AutoChunk section 4 evaluates that family): per image and per run of
+ * channels / groups consecutive channels, mean and biased variance over the run's channels and all
+ * positions; y = act((x - mean) / sqrt(var + eps) * gain[c] + shift[c]), act = AC_ACT_NONE or
+ * AC_ACT_SILU.  workspace: ac_group_norm_workspace_bytes(images, groups) bytes of device memory
+ * (partial statistics), caller's.  channels a multiple of groups and of 8 (bf16) / 4 (fp32),
+ * groups <= 128, images <= 65535, else AC_ERR_ARG.
+ */
+uint64_t ac_group_norm_workspace_bytes(int64_t images, int groups);
+int ac_op_group_norm(const void* x, const void* gain, const void* shift, void* y, void* workspace,
+                     uint64_t workspace_bytes, int64_t images, int64_t positions, int channels, int groups,
+                     float eps, int activation, int dtype, void* stream);
+
+/*
+ * 3x3 convolution, stride 1, zero padding 1, of channels-last bf16 images:
+ * out[b,h,w,o] = sum_{kh,kw,i} x[b,h+kh-1,w+kw-1,i] * weight[o,kh,kw,i] + bias[b or 0][o] (+ residual[b,h,w,o]).
+ * x [images, height, width, c_in], weight [c_out, 3, 3, c_in], out and residual [images, height, width, c_out].
+ * bias: one vector [c_out] (bias_per_image = 0) or one per image [images, c_out] (the block's
+ * bias plus the image's time embedding), may be null.  c_in a multiple of 64, c_out of 8; images * height * width
+ * below 2^31; else AC_ERR_ARG / AC_ERR_UNSUPPORTED.
+ */
+int ac_op_conv3x3(const void* x, const void* weight, const void* bias, int bias_per_image, const void* residual,
+                  void* out, int64_t images, int height, int width, int c_in, int c_out, int dtype, void* stream);
 
 #ifdef __cplusplus
 }

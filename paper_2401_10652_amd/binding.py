@@ -15,12 +15,12 @@ from .build import LIB_PATH
 AC_OK = 0
 AC_ERR_ARG, AC_ERR_ILLEGAL_CHUNK_DIM, AC_ERR_BUDGET_INFEASIBLE, AC_ERR_WORKSPACE = -1, -2, -3, -4
 AC_ERR_ALIGN, AC_ERR_HIP, AC_ERR_STATE, AC_ERR_UNSUPPORTED = -5, -6, -7, -8
-AC_TRANSFORMER_STACK, AC_PAIR_STACK = 0, 1
+AC_TRANSFORMER_STACK, AC_PAIR_STACK, AC_UNET_RES_STACK = 0, 1, 2
 AC_F32, AC_BF16 = 0, 1
-AC_ACT_NONE, AC_ACT_GELU_ERF, AC_ACT_GELU_TANH, AC_ACT_RELU, AC_ACT_SIGMOID = 0, 1, 2, 3, 4
+AC_ACT_NONE, AC_ACT_GELU_ERF, AC_ACT_GELU_TANH, AC_ACT_RELU, AC_ACT_SIGMOID, AC_ACT_SILU = 0, 1, 2, 3, 4, 5
 (AC_REGION_QKV, AC_REGION_ATTENTION, AC_REGION_OUT_PROJ, AC_REGION_FFN, AC_REGION_TRIMUL_OUT,
  AC_REGION_TRIMUL_IN, AC_REGION_TRIATT_START, AC_REGION_TRIATT_END, AC_REGION_PAIR_TRANSITION,
- AC_REGION_KINDS) = range(10)
+ AC_REGION_RES_BLOCK, AC_REGION_KINDS) = range(11)
 AC_DIM_BATCH, AC_DIM_SEQ, AC_DIM_FEATURE, AC_DIM_HEAD_DIM, AC_DIM_KEY = range(5)
 AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
 AC_FLAG_UNFUSED_ELEMENTWISE = 1
@@ -38,7 +38,8 @@ class ac_model_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "workload", "dtype", "layers", "batch", "seq", "d_model", "heads", "head_dim", "d_ffn",
         "causal", "activation", "n_res", "c_z", "c_hidden", "tri_heads", "tri_head_dim",
-        "transition_factor", "flags")] + [("ln_eps", C.c_float)]
+        "transition_factor", "flags")] + [("ln_eps", C.c_float)] + [(n, C.c_int32) for n in (
+        "img_h", "img_w", "channels", "groups")]
 
 
 class ac_region_desc(C.Structure):
@@ -137,6 +138,9 @@ SIGNATURES = {
     "ac_op_triangle_contract": (INT, [VP, I64, I64, VP, I64, I64, VP, I64, I64, I64, I64, I64, INT, INT, VP]),
     "ac_op_transpose_square_inplace": (INT, [VP, I64, I64, I64, I64, INT, VP]),
     "ac_op_layernorm_channel_major": (INT, [VP, I64, VP, VP, VP, I64, I64, I64, C.c_float, INT, VP]),
+    "ac_group_norm_workspace_bytes": (U64, [I64, INT]),
+    "ac_op_group_norm": (INT, [VP, VP, VP, VP, VP, U64, I64, I64, INT, INT, C.c_float, INT, INT, VP]),
+    "ac_op_conv3x3": (INT, [VP, VP, VP, INT, VP, VP, I64, INT, INT, INT, INT, INT, VP]),
     "ac_chunk_trace": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, INT, I32P, U8P, INTP]),
     "ac_chunk_search": (INT, [C.POINTER(ac_graph_node), INT, INT, INT, INT, C.POINTER(ac_chunk_candidate), I32P, U8P,
                               INT, INTP, INTP, INTP]),
@@ -222,6 +226,17 @@ def pair_desc(cfg, flags=0) -> ac_model_desc:
     m.activation = ACTIVATIONS[cfg.activation]
     m.flags = flags
     m.ln_eps = cfg.ln_eps
+    return m
+
+
+def res_stack_desc(cfg, flags=0) -> ac_model_desc:
+    m = ac_model_desc()
+    m.workload = AC_UNET_RES_STACK
+    m.dtype = DTYPES[cfg.dtype]
+    m.layers, m.batch = cfg.layers, cfg.batch
+    m.img_h, m.img_w, m.channels, m.groups = cfg.height, cfg.width, cfg.channels, cfg.groups
+    m.flags = flags
+    m.ln_eps = cfg.eps
     return m
 
 
@@ -421,6 +436,25 @@ def ac_op_layernorm_channel_major(src, gain, shift, dst, eps=1e-5):
     _check(lib().ac_op_layernorm_channel_major(_ptr(src), src.stride(0), _ptr(gain), _ptr(shift), _ptr(dst),
                                                dst.stride(0), pos, ch, eps, _dt(src), _stream()),
            "ac_op_layernorm_channel_major")
+
+
+def ac_group_norm_workspace_bytes(images, groups):
+    return int(lib().ac_group_norm_workspace_bytes(images, groups))
+
+
+def ac_op_group_norm(x, gain, shift, y, workspace, groups, eps=1e-5, activation=AC_ACT_NONE):
+    """x, y [images, positions..., channels] channels-last."""
+    images, ch = x.shape[0], x.shape[-1]
+    positions = x.numel() // (images * ch) if images else 0
+    _check(lib().ac_op_group_norm(_ptr(x), _ptr(gain), _ptr(shift), _ptr(y), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  images, positions, ch, groups, eps, activation, _dt(x), _stream()), "ac_op_group_norm")
+
+
+def ac_op_conv3x3(x, weight, out, bias=None, bias_per_image=False, residual=None):
+    """x [images, H, W, c_in], weight [c_out, 3, 3, c_in] -> out [images, H, W, c_out]."""
+    images, h, w, c_in = x.shape
+    _check(lib().ac_op_conv3x3(_ptr(x), _ptr(weight), _ptr(bias), int(bias_per_image), _ptr(residual), _ptr(out), images, h, w,
+                               c_in, weight.shape[0], _dt(x), _stream()), "ac_op_conv3x3")
 
 
 # ---- helpers for callers (buffers only) ------------------------------------------------------

@@ -80,6 +80,7 @@ template <int ACT> __device__ __forceinline__ float apply_act(float x) {
   if (ACT == AC_ACT_GELU_TANH) return gelu_tanh(x);
   if (ACT == AC_ACT_RELU) return fmaxf(x, 0.0f);
   if (ACT == AC_ACT_SIGMOID) return sigmoidf(x);
+  if (ACT == AC_ACT_SILU) return x * sigmoidf(x);
   return x;
 }
 __device__ __forceinline__ float apply_act_rt(float x, int act) {
@@ -88,6 +89,7 @@ __device__ __forceinline__ float apply_act_rt(float x, int act) {
     case AC_ACT_GELU_TANH: return gelu_tanh(x);
     case AC_ACT_RELU: return fmaxf(x, 0.0f);
     case AC_ACT_SIGMOID: return sigmoidf(x);
+    case AC_ACT_SILU: return x * sigmoidf(x);
     default: return x;
   }
 }
@@ -131,6 +133,12 @@ struct LinearArgs {
   // batch > 1: `batch` independent products; a, w and out advance by these strides (elements).
   // bias / mul / resid / out_t must be null then.
   int64_t batch, sa_b, sw_b, so_b;
+  // conv_c > 0: a is a stack of channels-last images [m / (conv_h * conv_w)][conv_h][conv_w][conv_c] and the
+  // product is their 3x3 convolution (stride 1, zero padding 1): row m is a pixel, k = 9 * conv_c runs over
+  // (window row, window column, input channel), w is [n][3][3][conv_c].  lda is ignored (= conv_c).
+  int conv_h, conv_w, conv_c;
+  // bias_period > 0: row m takes bias row m / bias_period (bias is [m / bias_period][n]): one bias vector per image
+  int64_t bias_period;
 };
 
 struct AttnArgs {
@@ -188,6 +196,10 @@ hipError_t launch_bias_act(const void* x, int64_t ldx, const void* bias, void* y
 hipError_t launch_binary(const void* a, int64_t lda, const void* b, int64_t ldb, void* y, int64_t ldy,
                          int64_t rows, int64_t cols, int op, int dtype, hipStream_t s);
 hipError_t launch_linear(const LinearArgs& g, hipStream_t s);
+// GroupNorm (+ SiLU) of channels-last images [images, positions, channels]; partials: group_norm_workspace_bytes()
+uint64_t group_norm_workspace_bytes(int64_t images, int groups);
+hipError_t launch_group_norm(const void* x, const void* gain, const void* shift, void* y, void* partials, int64_t images,
+                             int64_t positions, int channels, int groups, float eps, int act, int dtype, hipStream_t s);
 // p = softmax(scale * s [causal]) over stored rows; row r is query r mod period at position
 // q_offset + (r mod period).
 hipError_t launch_softmax_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t rows, int64_t cols,

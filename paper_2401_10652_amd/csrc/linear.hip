@@ -191,6 +191,7 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
     const int64_t mc = row_ok ? m : g.m - 1;
     // offset of row m in the strided ("transposed") output, if any
     const int64_t t_base = g.n_split < g.n ? out_t_row(g, mc) : 0;
+    const int64_t bias_row = g.bias_period > 0 ? (int64_t)((uint32_t)mc / (uint32_t)g.bias_period) * g.n : 0;   // (m < 2^31)
 #pragma unroll
     for (int jb = 0; jb < TN; jb += JB) {
       bf16x4 bias_v[JB][4], mul_v[JB][4], res_v[JB][4];
@@ -201,7 +202,7 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
         for (int q = 0; q < 4; ++q) {
           const int64_t n = n0 + cl0 + (jb + j) * 32 + 8 * q;
           nc[j][q] = n < g.n ? n : g.n - 4;
-          bias_v[j][q] = g.bias ? *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + nc[j][q]) : zero4;
+          bias_v[j][q] = g.bias ? *reinterpret_cast<const bf16x4*>((const bf16_t*)g.bias + bias_row + nc[j][q]) : zero4;
         }
       if (g.mul) {
 #pragma unroll
@@ -293,7 +294,11 @@ __device__ __forceinline__ void epilogue_tile(const LinearArgs& g, f32x16 (&acc)
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+// CONV: the A operand is gathered from channels-last images as the 3x3 convolution needs it (implicit GEMM):
+// a k tile of 64 lies inside one window position (conv_c is a multiple of 64), so it is the same 64 input
+// channels of the pixel shifted by that position for every row of the tile, or zeros where the shifted pixel
+// falls outside its image.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool CONV = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(LinearArgs g) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;           // threads
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
@@ -322,12 +327,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
   const bf16_t* a_src[A_CHUNKS];
   const bf16_t* w_src[W_CHUNKS];
   int a_dst[A_CHUNKS], w_dst[W_CHUNKS];
+  int a_taps[A_CHUNKS];   // CONV: bit t set = window position t of this row's pixel lies inside the image
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
     const int c = tid + NT * i, row = c >> 3, ch = c & 7;
     int64_t gr = m0 + row; if (gr > g.m - 1) gr = g.m - 1;
-    a_src[i] = a + gr * g.lda + ch * 8;
+    a_src[i] = a + gr * (CONV ? (int64_t)g.conv_c : g.lda) + ch * 8;
     a_dst[i] = row * kLdsRow + ch * 8;
+    a_taps[i] = 0;
+    if (CONV) {
+      const int pix = (int)(gr % ((int64_t)g.conv_h * g.conv_w)), ph = pix / g.conv_w, pw = pix % g.conv_w;
+      for (int t = 0; t < 9; ++t) {
+        const int hh = ph + t / 3 - 1, ww = pw + t % 3 - 1;
+        if (hh >= 0 && hh < g.conv_h && ww >= 0 && ww < g.conv_w) a_taps[i] |= 1 << t;
+      }
+    }
   }
 #pragma unroll
   for (int i = 0; i < W_CHUNKS; ++i) {
@@ -358,8 +372,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
   constexpr int KSTEPS = kBK / 16;
   auto load_regs = [&](bf16x8 (&ar)[A_CHUNKS], bf16x8 (&wr)[W_CHUNKS], int64_t kt) {
     const int64_t koff = kt * kBK;
+    if (CONV) {
+      const int tap = (int)(koff / g.conv_c), c0 = (int)(koff % g.conv_c);
+      const int64_t shift = ((int64_t)(tap / 3 - 1) * g.conv_w + (tap % 3 - 1)) * g.conv_c + c0;
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) ar[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + koff);
+      for (int i = 0; i < A_CHUNKS; ++i) {
+        const bool inside = (a_taps[i] >> tap) & 1;
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(a_src[i] + (inside ? shift : (int64_t)c0));   // always a valid address
+        const bf16x8 zero = {};
+        ar[i] = inside ? v : zero;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) ar[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + koff);
+    }
 #pragma unroll
     for (int i = 0; i < W_CHUNKS; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(w_src[i] + koff);
   };
@@ -423,9 +449,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
 template <int BM, int BN>
 constexpr size_t mfma_lds_bytes() { return (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16_t) + kGeluTableBytes; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool CONV = false>
 static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
-  auto kern = linear_mfma_bf16<BM, BN, WAVES_M, WAVES_N>;
+  auto kern = linear_mfma_bf16<BM, BN, WAVES_M, WAVES_N, CONV>;
   constexpr size_t lds = mfma_lds_bytes<BM, BN>();
   // the attribute is per function; set once per process (the initialiser runs once, thread-safe)
   static const hipError_t attr_status = hipFuncSetAttribute(
@@ -754,6 +780,15 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
   if (g.batch > 1 && g.o_period != INT64_MAX) return hipErrorInvalidValue;
   if (g.batch > 1 && (g.bias || g.mul || g.resid || g.out_t || g.act != AC_ACT_NONE)) return hipErrorInvalidValue;
   if (g.batch > 65535 || g.m > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (g.conv_c > 0) {
+    // 3x3 convolution as an implicit GEMM on 128x128 tiles; bf16 images with channels in multiples of 64 only
+    if (g.dtype != AC_BF16 || g.conv_c % kBK != 0 || g.conv_h < 1 || g.conv_w < 1 || g.k != 9 * (int64_t)g.conv_c ||
+        g.m % ((int64_t)g.conv_h * g.conv_w) != 0 || g.batch != 1)
+      return hipErrorInvalidValue;
+    g.lda = g.conv_c;
+    if (!mfma_eligible(g)) return hipErrorInvalidValue;
+    return mfma_launch<128, 128, 2, 2, true>(g, s);
+  }
   if (mfma_eligible(g)) {
     // A CU takes in at most 64 bytes per clock from L2 while its matrix cores retire 4096
     // flops per clock, so a tile needs >= 64 flops per loaded byte just to break even: 128x128

@@ -464,4 +464,120 @@ hipError_t launch_softmax_rows(const void* src, int64_t lds_, void* dst, int64_t
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------
+// GroupNorm (+ SiLU) of channels-last images x [images, positions, C]: the C channels of an image
+// in `groups` runs of C / groups consecutive channels, mean and biased variance over a run's
+// channels and all positions.  Two kernels, both HBM-bound passes over the images:
+//   group_norm_partials: block (image * groups + group, part) reads its share of the positions twice
+//     (the second time from L2) and writes (count, mean, sum of squared deviations from that mean);
+//   group_norm_apply: every block first combines the partials of its image (pairwise, the
+//     parallel-variance formula; fixed order, so the result does not depend on timing), then
+//     normalises one 16-byte run of channels per lane with a gain and a shift per channel and applies the activation.
+// Statistics and arithmetic in fp32.
+// ------------------------------------------------------------------------------------
+constexpr int kGnParts = 16;          // position shares per (image, group)
+constexpr int kGnMaxGroups = 128;
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+group_norm_partials(const T* x, float* part, int64_t positions, int channels, int groups) {
+  __shared__ float red[4];
+  const int cg = channels / groups;
+  const int64_t bg = blockIdx.x;                  // image * groups + group
+  const int64_t image = bg / groups;
+  const int g = (int)(bg % groups);
+  const int part_i = blockIdx.y;
+  const int64_t per = (positions + kGnParts - 1) / kGnParts;
+  const int64_t p0 = part_i * per, p1 = p0 + per < positions ? p0 + per : positions;
+  const T* base = x + image * positions * channels + g * cg;
+  const int tid = threadIdx.x;
+  const int64_t count = p1 > p0 ? (p1 - p0) * cg : 0;
+  float sum = 0.f;
+  for (int64_t i = tid; i < count; i += 256) sum += Elem<T>::ld(base + (p0 + i / cg) * channels + i % cg);
+  sum = wave_sum(sum);
+  if (tid % 64 == 0) red[tid / 64] = sum;
+  __syncthreads();
+  const float mean = count > 0 ? (red[0] + red[1] + red[2] + red[3]) / (float)count : 0.f;
+  __syncthreads();
+  float m2 = 0.f;
+  for (int64_t i = tid; i < count; i += 256) {
+    const float d = Elem<T>::ld(base + (p0 + i / cg) * channels + i % cg) - mean;
+    m2 += d * d;
+  }
+  m2 = wave_sum(m2);
+  if (tid % 64 == 0) red[tid / 64] = m2;
+  __syncthreads();
+  if (tid == 0) {
+    float* o = part + (bg * kGnParts + part_i) * 3;
+    o[0] = (float)count; o[1] = mean; o[2] = red[0] + red[1] + red[2] + red[3];
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+group_norm_apply(const T* x, const float* part, const T* gain, const T* shift, T* y, int64_t positions, int channels,
+                 int groups, float eps, int act) {
+  __shared__ float s_mean[kGnMaxGroups], s_rstd[kGnMaxGroups];
+  const int64_t image = blockIdx.y;
+  const int tid = threadIdx.x;
+  for (int g = tid; g < groups; g += 256) {
+    const float* pp = part + ((image * groups + g) * kGnParts) * 3;
+    float n = 0.f, mean = 0.f, m2 = 0.f;
+    for (int i = 0; i < kGnParts; ++i) {           // combine in index order
+      const float nb = pp[3 * i], mb = pp[3 * i + 1], m2b = pp[3 * i + 2];
+      if (nb <= 0.f) continue;
+      const float tot = n + nb, delta = mb - mean;
+      mean += delta * (nb / tot);
+      m2 += m2b + delta * delta * (n * nb / tot);
+      n = tot;
+    }
+    s_mean[g] = mean;
+    s_rstd[g] = rsqrtf(m2 / n + eps);
+  }
+  __syncthreads();
+  constexpr int V = Elem<T>::kVec;                          // channels per lane: one 16-byte access
+  const int cg = channels / groups;
+  const int64_t chunks = positions * (channels / V);
+  const int64_t c = (int64_t)blockIdx.x * 256 + tid;
+  if (c >= chunks) return;
+  const int64_t pos = c / (channels / V);
+  const int ch0 = (int)(c % (channels / V)) * V;
+  const T* in = x + (image * positions + pos) * channels + ch0;
+  T* out = y + (image * positions + pos) * channels + ch0;
+  float v[V], gg[V], sh[V];
+  load_vec(in, v);
+  load_vec(gain + ch0, gg);
+  load_vec(shift + ch0, sh);
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    const int g = (ch0 + i) / cg;
+    const float t = (v[i] - s_mean[g]) * s_rstd[g] * gg[i] + sh[i];
+    v[i] = act == AC_ACT_SILU ? t * sigmoidf(t) : t;
+  }
+  store_vec(out, v);
+}
+
+uint64_t group_norm_workspace_bytes(int64_t images, int groups) { return (uint64_t)images * groups * kGnParts * 3 * sizeof(float); }
+
+hipError_t launch_group_norm(const void* x, const void* gain, const void* shift, void* y, void* partials, int64_t images,
+                             int64_t positions, int channels, int groups, float eps, int act, int dtype, hipStream_t s) {
+  if (images <= 0 || positions <= 0) return hipSuccess;
+  if (channels <= 0 || groups <= 0 || groups > kGnMaxGroups || channels % groups != 0 || channels % 8 != 0 || !partials ||
+      images > 65535 || (act != AC_ACT_NONE && act != AC_ACT_SILU))
+    return hipErrorInvalidValue;
+  const dim3 g1((unsigned)(images * groups), kGnParts);
+  const int64_t chunks = positions * (channels / (dtype == AC_BF16 ? 8 : 4));
+  const dim3 g2((unsigned)((chunks + 255) / 256), (unsigned)images);
+  if (dtype == AC_BF16) {
+    hipLaunchKernelGGL((group_norm_partials<bf16_t>), g1, dim3(256), 0, s, (const bf16_t*)x, (float*)partials, positions, channels, groups);
+    hipLaunchKernelGGL((group_norm_apply<bf16_t>), g2, dim3(256), 0, s, (const bf16_t*)x, (const float*)partials, (const bf16_t*)gain,
+                       (const bf16_t*)shift, (bf16_t*)y, positions, channels, groups, eps, act);
+  } else {
+    hipLaunchKernelGGL((group_norm_partials<float>), g1, dim3(256), 0, s, (const float*)x, (float*)partials, positions, channels, groups);
+    hipLaunchKernelGGL((group_norm_apply<float>), g2, dim3(256), 0, s, (const float*)x, (const float*)partials, (const float*)gain,
+                       (const float*)shift, (float*)y, positions, channels, groups, eps, act);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace ac

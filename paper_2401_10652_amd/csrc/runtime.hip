@@ -229,7 +229,7 @@ struct Walk {
   }
   void linear(LinearArgs g) {
     g.dtype = p->m.dtype;
-    double by = ((double)g.m * g.k + (double)g.n * g.k + (double)g.m * g.n) * eb();
+    double by = ((double)g.m * (g.conv_c > 0 ? g.conv_c : g.k) + (double)g.n * g.k + (double)g.m * g.n) * eb();
     if (g.mul) by += (double)g.m * g.n * eb();
     if (g.resid) by += (double)g.m * g.n * eb();
     run(K_GEMM, 2.0 * g.m * g.n * g.k, by, "linear", [&] { return launch_linear(g, stream); });
@@ -395,6 +395,7 @@ struct Walk {
 
   void transformer(const void* x, void* y);
   void pair(const void* x, void* y);
+  void res_stack(const void* x, void* y);
   const void* pair_segment(const void* zin, const RowSeg& sg, bool col);
   void pair_store(LinearArgs& o, void* zout, const RowSeg& sg, bool col);
   void tri_mul(int kind, const void* const* W, const void* zin, void* zout);
@@ -943,6 +944,67 @@ void Walk::pair(const void* x, void* y) {
 }
 
 // ---------------------------------------------------------------------------------------
+// UNet residual stack: x [B, H, W, C] channels-last.  Per block and per segment of images:
+//   a = SiLU(GroupNorm(x));  t = conv3x3(a, w1) + (b1 + temb[image]);  a = SiLU(GroupNorm(t));
+//   y = x + conv3x3(a, w2) + b2
+// with the bias and the time embedding (one vector per image), and the skip, in the convolutions'
+// epilogues.  A segment holds a and t; whole: the [B, C] bias-plus-embedding table, the GroupNorm
+// partial statistics, one inter-block buffer.
+// ---------------------------------------------------------------------------------------
+enum { RB_GN1_G, RB_GN1_B, RB_W1, RB_B1, RB_GN2_G, RB_GN2_B, RB_W2, RB_B2, RB_TEMB, RB_COUNT };
+static const char* const kRbName[RB_COUNT] = {"gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb"};
+
+void Walk::res_stack(const void* x, void* y) {
+  const ac_model_desc& m = p->m;
+  const int64_t HW = (int64_t)m.img_h * m.img_w, C = m.channels;
+  const int e = eb();
+  auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
+  auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
+  const uint64_t img_bytes = (uint64_t)HW * C * e;
+  void* tbuf[2] = {nullptr, nullptr};
+  if (m.layers > 1) tbuf[0] = arena.push((uint64_t)m.batch * img_bytes);
+  if (m.layers > 2) tbuf[1] = arena.push((uint64_t)m.batch * img_bytes);
+  void* bt = arena.push((uint64_t)m.batch * C * e);                                  // b1 + temb, per image
+  void* stats = arena.push(group_norm_workspace_bytes(m.batch, m.groups));
+  enter(AC_REGION_RES_BLOCK);
+  std::vector<RowSeg> segs;
+  for (int64_t b = 0; b < m.batch; b += seg_len(AC_REGION_RES_BLOCK)) segs.push_back(RowSeg{b, std::min<int64_t>(seg_len(AC_REGION_RES_BLOCK), m.batch - b)});
+  const int dt = m.dtype;
+  for (int l = 0; l < m.layers && ok(); ++l) {
+    const void* in = l == 0 ? x : (const void*)tbuf[(l - 1) % 2];
+    void* out = l == m.layers - 1 ? y : tbuf[l % 2];
+    auto W = [&](int slot) { return w(l, slot, RB_COUNT); };
+    bias_act(W(RB_TEMB), C, W(RB_B1), bt, C, m.batch, C, AC_ACT_NONE);
+    seg_loop(segs, [&](const RowSeg& sg) {
+      const int64_t nb = sg.ni, px = nb * HW;
+      const void* xs = at(in, sg.i0 * HW * C);
+      void* a = arena.push((uint64_t)nb * img_bytes);
+      void* t = arena.push((uint64_t)nb * img_bytes);
+      // the partial statistics of the segment's images sit at the images' own place in the table, so two
+      // segments in flight do not share any of it
+      void* st = dry ? nullptr : (void*)((uint8_t*)stats + group_norm_workspace_bytes(sg.i0, m.groups));
+      auto gn = [&](const void* src, int gslot, int bslot, void* dst) {
+        const void* gg = W(gslot); const void* bb = W(bslot);
+        hipStream_t s_ = stream;
+        run(K_LN, 8.0 * px * C, 3.0 * px * C * e, "group norm",
+            [&] { return launch_group_norm(src, gg, bb, dst, st, nb, HW, (int)C, m.groups, m.ln_eps, AC_ACT_SILU, dt, s_); });
+      };
+      auto conv = [&](const void* src, int wslot, const void* bias, int64_t bias_period, const void* resid, void* dst) {
+        LinearArgs g{};
+        g.a = src; g.lda = C; g.w = W(wslot); g.ldw = 9 * C; g.bias = bias; g.bias_period = bias_period;
+        g.resid = resid; g.ldr = C; g.out = dst; g.ldo = C; g.m = px; g.n = C; g.k = 9 * C; g.n_split = C;
+        g.conv_h = m.img_h; g.conv_w = m.img_w; g.conv_c = (int)C;
+        linear(g);
+      };
+      gn(xs, RB_GN1_G, RB_GN1_B, a);
+      conv(a, RB_W1, at(bt, sg.i0 * C), HW, nullptr, t);
+      gn(t, RB_GN2_G, RB_GN2_B, a);
+      conv(a, RB_W2, W(RB_B2), 0, xs, atw(out, sg.i0 * HW * C));
+    });
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Paper-style byte counts of the regions (section 2: M = X + Y + A, chunked M = X + Y + A/n
 // with every op output a tensor of its own), used to size chunk lengths from a budget.
 // ---------------------------------------------------------------------------------------
@@ -958,6 +1020,12 @@ static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
       case AC_REGION_FFN: return 2 * T * d * b + (uint64_t)c * d * b + 2 * (uint64_t)c * F * b;
       default: return 0;
     }
+  }
+  if (m.workload == AC_UNET_RES_STACK) {
+    // x and y whole; per segment of c images the seven intermediates of the unfused block
+    // (two normalised, two activated, two convolved tensors and the sum with the embedding)
+    const uint64_t img = (uint64_t)m.img_h * m.img_w * m.channels * b;
+    return 2 * (uint64_t)m.batch * img + 7 * (uint64_t)c * img;
   }
   const uint64_t n = m.n_res, cz = m.c_z, ch = m.c_hidden, hd = (uint64_t)m.tri_heads * m.tri_head_dim;
   const uint64_t H = m.tri_heads, cc = (uint64_t)c;
@@ -987,6 +1055,7 @@ static int64_t model_rows(const ac_model_desc& m, const Setting& s, int64_t len)
 
 static void region_kinds(const ac_model_desc& m, int& first, int& count) {
   if (m.workload == AC_TRANSFORMER_STACK) { first = AC_REGION_QKV; count = 4; }
+  else if (m.workload == AC_UNET_RES_STACK) { first = AC_REGION_RES_BLOCK; count = 1; }
   else { first = AC_REGION_TRIMUL_OUT; count = 5; }
 }
 
@@ -998,6 +1067,10 @@ static bool dim_legal(const ac_model_desc& m, int kind, int dim, bool& known) {
     // columns) can be cut: no node of those regions reduces over it.  The LayerNorms of the other two do.
     if (dim == AC_DIM_FEATURE) return kind == AC_REGION_ATTENTION || kind == AC_REGION_OUT_PROJ;
     if (dim == AC_DIM_HEAD_DIM || dim == AC_DIM_KEY) return false;
+  } else if (m.workload == AC_UNET_RES_STACK) {
+    // images are independent; positions and channels are reduced over by the GroupNorms and the windows
+    if (dim == AC_DIM_BATCH) return true;
+    if (dim == AC_DIM_SEQ || dim == AC_DIM_FEATURE) return false;
   } else {
     if (dim == AC_DIM_ROW || dim == AC_DIM_COL) return true;
     if (dim == AC_DIM_CHANNEL || dim == AC_DIM_CONTRACT) return false;
@@ -1011,6 +1084,7 @@ static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& f
   Walk wk{p, true, unchunked, nullptr};
   wk.lanes = (p->m.flags & AC_FLAG_TWO_SEGMENTS_IN_FLIGHT) ? 2 : 1;
   if (p->m.workload == AC_TRANSFORMER_STACK) wk.transformer(nullptr, nullptr);
+  else if (p->m.workload == AC_UNET_RES_STACK) wk.res_stack(nullptr, nullptr);
   else wk.pair(nullptr, nullptr);
   arena_bytes = wk.arena.high;
   flops = wk.flops;
@@ -1020,6 +1094,7 @@ static void dry_run(ac_plan* p, bool unchunked, uint64_t& arena_bytes, double& f
 
 static uint64_t io_bytes(const ac_model_desc& m) {
   if (m.workload == AC_TRANSFORMER_STACK) return 2ull * m.batch * m.seq * m.d_model * elem_bytes(m.dtype);
+  if (m.workload == AC_UNET_RES_STACK) return 2ull * m.batch * m.img_h * m.img_w * m.channels * elem_bytes(m.dtype);
   return 2ull * m.n_res * m.n_res * m.c_z * elem_bytes(m.dtype);
 }
 
@@ -1082,6 +1157,16 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
       return fail(AC_ERR_UNSUPPORTED, "c_hidden %d too wide for the channel-major LayerNorm tile", m.c_hidden);
     if (m.c_hidden > 65535 || (int64_t)m.tri_heads * m.tri_head_dim > 65535)
       return fail(AC_ERR_UNSUPPORTED, "too many channels for one launch");
+  } else if (m.workload == AC_UNET_RES_STACK) {
+    if (m.batch < 1 || m.img_h < 1 || m.img_w < 1 || m.channels < 1 || m.groups < 1)
+      return fail(AC_ERR_ARG, "residual-stack sizes must be positive");
+    if (m.channels % m.groups != 0) return fail(AC_ERR_ARG, "channels (%d) must be a multiple of groups (%d)", m.channels, m.groups);
+    if (m.dtype != AC_BF16 || m.channels % 64 != 0 || m.groups > 128 || m.batch > 65535 ||
+        (int64_t)m.batch * m.img_h * m.img_w >= (1ll << 31))
+      return fail(AC_ERR_UNSUPPORTED, "the 3x3 convolution kernel takes bf16 images with channels in multiples of 64, "
+                                      "at most 128 groups and fewer than 2^31 pixels");
+    if (m.flags & (AC_FLAG_UNFUSED_ELEMENTWISE | AC_FLAG_BUDGET_PAPER_MODEL))
+      return fail(AC_ERR_UNSUPPORTED, "flags %d do not apply to the residual stack", m.flags);
   } else {
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
@@ -1100,8 +1185,8 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
   region_kinds(m, first, count);
   for (int k = first; k < first + count; ++k) {
     Setting& s = p->set[k];
-    s.chunk_dim = m.workload == AC_TRANSFORMER_STACK ? AC_DIM_SEQ : AC_DIM_ROW;
-    s.extent = m.workload == AC_TRANSFORMER_STACK ? m.seq : m.n_res;
+    s.chunk_dim = m.workload == AC_TRANSFORMER_STACK ? AC_DIM_SEQ : m.workload == AC_UNET_RES_STACK ? AC_DIM_BATCH : AC_DIM_ROW;
+    s.extent = m.workload == AC_TRANSFORMER_STACK ? m.seq : m.workload == AC_UNET_RES_STACK ? m.batch : m.n_res;
     s.chunk_len = s.extent;
   }
   for (int i = 0; i < n_regions; ++i) {
@@ -1127,7 +1212,8 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     if (r.chunk_len < 0) { delete p; return fail(AC_ERR_ARG, "chunk_len must be >= 0"); }
     s.present = true;
     s.chunk_dim = r.chunk_dim;
-    s.extent = m.workload == AC_TRANSFORMER_STACK ? (r.chunk_dim == AC_DIM_BATCH ? m.batch : r.chunk_dim == AC_DIM_FEATURE ? m.d_model : m.seq) : m.n_res;
+    s.extent = m.workload == AC_TRANSFORMER_STACK ? (r.chunk_dim == AC_DIM_BATCH ? m.batch : r.chunk_dim == AC_DIM_FEATURE ? m.d_model : m.seq)
+               : m.workload == AC_UNET_RES_STACK ? m.batch : m.n_res;
     if (m.workload == AC_TRANSFORMER_STACK && r.chunk_dim == AC_DIM_FEATURE) {
       // a segment of the context is a run of whole heads; a block of output columns starts on a 16-byte boundary
       const int64_t g = r.kind == AC_REGION_ATTENTION ? m.head_dim : 8;
@@ -1147,7 +1233,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
   // ---- paper-style model bytes as an additional bound (AC_FLAG_BUDGET_PAPER_MODEL): largest
   // length (the extent itself, or a multiple of the region's granule below it) whose unfused
   // region bytes fit; explicit lengths are checked against the same bound.
-  const int64_t row_granule = m.workload == AC_PAIR_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
+  const int64_t row_granule = m.workload != AC_TRANSFORMER_STACK ? 1 : (m.dtype == AC_BF16 ? 128 : 64);
   auto granule_of = [&](const Setting& s) -> int64_t {
     if (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_FEATURE) return &s == &p->set[AC_REGION_ATTENTION] ? m.head_dim : 8;
     return (m.workload == AC_TRANSFORMER_STACK && s.chunk_dim == AC_DIM_BATCH) ? 1 : row_granule;
@@ -1190,6 +1276,16 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
       for (int t = 0; t < 12; ++t) {
         char nm[48];
         snprintf(nm, sizeof(nm), "L%d.%s", l, kLayerTensor[t]);
+        p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
+      }
+  }
+  if (m.workload == AC_UNET_RES_STACK) {
+    const int64_t C = m.channels;
+    const int64_t shp[RB_COUNT][2] = {{1, C}, {1, C}, {C, 9 * C}, {1, C}, {1, C}, {1, C}, {C, 9 * C}, {1, C}, {m.batch, C}};
+    for (int l = 0; l < m.layers; ++l)
+      for (int t = 0; t < RB_COUNT; ++t) {
+        char nm[48];
+        snprintf(nm, sizeof(nm), "R%d.%s", l, kRbName[t]);
         p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
       }
   }
@@ -1362,6 +1458,7 @@ int ac_execute(ac_plan* plan, const void* x_dev, void* y_dev, void* workspace_de
     plan->sync_used = 0;
   }
   if (plan->m.workload == AC_TRANSFORMER_STACK) wk.transformer(x_dev, y_dev);
+  else if (plan->m.workload == AC_UNET_RES_STACK) wk.res_stack(x_dev, y_dev);
   else wk.pair(x_dev, y_dev);
   if (measured_peak_bytes) *measured_peak_bytes = plan->info.io_bytes + wk.arena.high;
   if (!wk.ok()) return fail(AC_ERR_HIP, "%s: %s", wk.err_where, hipGetErrorString(wk.err));
@@ -1638,6 +1735,39 @@ int ac_op_layernorm_channel_major(const void* src, int64_t stride_c, const void*
   return hip_status(launch_layernorm_channel_major(src, stride_c, gain, shift, dst, ldd, positions, channels, eps,
                                                    dtype, (hipStream_t)stream),
                     "layernorm_channel_major");
+}
+
+uint64_t ac_group_norm_workspace_bytes(int64_t images, int groups) {
+  return images > 0 && groups > 0 ? group_norm_workspace_bytes(images, groups) : 0;
+}
+
+int ac_op_group_norm(const void* x, const void* gain, const void* shift, void* y, void* workspace, uint64_t workspace_bytes,
+                     int64_t images, int64_t positions, int channels, int groups, float eps, int activation, int dtype,
+                     void* stream) {
+  if (!x || !gain || !shift || !y || images < 0 || positions < 0 || channels < 1 || groups < 1 || groups > 128 ||
+      channels % groups != 0 || channels % (dtype == AC_BF16 ? 8 : 4) != 0 || images > 65535 || !dtype_ok(dtype) ||
+      (activation != AC_ACT_NONE && activation != AC_ACT_SILU) || !(eps > 0.f))
+    return fail(AC_ERR_ARG, "ac_op_group_norm: bad argument");
+  if (!workspace || workspace_bytes < group_norm_workspace_bytes(images, groups))
+    return fail(AC_ERR_WORKSPACE, "ac_op_group_norm: workspace of %llu bytes, %llu needed", (unsigned long long)workspace_bytes,
+                (unsigned long long)group_norm_workspace_bytes(images, groups));
+  return hip_status(launch_group_norm(x, gain, shift, y, workspace, images, positions, channels, groups, eps, activation, dtype,
+                                      (hipStream_t)stream), "group_norm");
+}
+
+int ac_op_conv3x3(const void* x, const void* weight, const void* bias, int bias_per_image, const void* residual, void* out,
+                  int64_t images, int height, int width, int c_in, int c_out, int dtype, void* stream) {
+  if (!x || !weight || !out || images < 0 || height < 1 || width < 1 || c_in < 1 || c_out < 1 || !dtype_ok(dtype))
+    return fail(AC_ERR_ARG, "ac_op_conv3x3: bad argument");
+  if (dtype != AC_BF16 || c_in % 64 != 0 || c_out % 8 != 0 || images * height * width >= (1ll << 31))
+    return fail(AC_ERR_UNSUPPORTED, "ac_op_conv3x3: bf16 images with c_in a multiple of 64, c_out of 8 and fewer than 2^31 pixels");
+  if (images == 0) return AC_OK;
+  LinearArgs g{};
+  g.a = x; g.lda = c_in; g.w = weight; g.ldw = 9 * (int64_t)c_in; g.bias = bias;
+  g.bias_period = bias && bias_per_image ? (int64_t)height * width : 0;
+  g.resid = residual; g.ldr = c_out; g.out = out; g.ldo = c_out; g.m = images * height * width; g.n = c_out;
+  g.k = 9 * (int64_t)c_in; g.n_split = c_out; g.conv_h = height; g.conv_w = width; g.conv_c = c_in; g.dtype = dtype;
+  return hip_status(launch_linear(g, (hipStream_t)stream), "conv3x3");
 }
 
 }  // extern "C"

@@ -222,6 +222,60 @@ def transformer_inputs(cfg: TransformerConfig, seed: int = BASE_SEED, bias_std: 
 
 
 # Tensor order of the pair-stack block's weights (also the bind order of the executor).
+@dataclass(frozen=True)
+class ResStackConfig:
+    """UNet residual blocks one after another on channels-last images [batch, height, width, channels]."""
+    name: str
+    index: int
+    layers: int
+    batch: int
+    height: int
+    width: int
+    channels: int
+    groups: int
+    dtype: str = "bf16"
+    eps: float = 1e-5
+    chunk_len: int = 1    # images per segment
+
+
+# a latent-diffusion stage: 64 x 64 latents, 320 channels, 32 groups
+U1 = ResStackConfig("U1_unet_res_b8_c320_64x64", 5, 2, 8, 64, 64, 320, 32, chunk_len=2)
+
+RES_BLOCK_TENSORS = ("gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb")
+
+
+def res_stack_inputs(cfg: ResStackConfig, seed: int = BASE_SEED, bias_std: float = 0.0, gn_jitter: float = 0.0):
+    """Returns (x, layers): x [batch, height, width, channels]; layers = list of dicts with the tensors of
+    RES_BLOCK_TENSORS: convolution weights [C, 3, 3, C] ~ N(0, 1 / sqrt(9 C)), the time embedding of every image
+    [batch, C] ~ N(0, 0.5), GroupNorm gain 1 and shift 0 (jittered on request), biases 0 (or N(0, bias_std))."""
+    st = _Streams(cfg.index, seed)
+    c = cfg.channels
+    x = st.normal((cfg.batch, cfg.height, cfg.width, c), 1.0, cfg.dtype)
+    layers = []
+    for _ in range(cfg.layers):
+        w = {}
+        for name in RES_BLOCK_TENSORS:
+            if name in ("w1", "w2"):
+                w[name] = st.normal((c, 3, 3, c), 1.0 / math.sqrt(9 * c), cfg.dtype)
+            elif name == "temb":
+                w[name] = st.normal((cfg.batch, c), 0.5, cfg.dtype)
+            elif name.endswith("_g"):
+                if gn_jitter > 0:
+                    w[name] = round_to_storage(1.0 + st.normal((c,), gn_jitter, "f32"), cfg.dtype)
+                else:
+                    st.skip()
+                    w[name] = np.ones((c,), np.float32)
+            else:
+                std = gn_jitter if name.startswith("gn") else bias_std
+                if std > 0:
+                    w[name] = st.normal((c,), std, cfg.dtype)
+                else:
+                    st.skip()
+                    w[name] = np.zeros((c,), np.float32)
+        layers.append(w)
+    return x, layers
+
+
 def pair_tensor_shapes(cfg: PairConfig) -> "list[tuple[str, tuple]]":
     cz, ch, hd = cfg.c_z, cfg.c_hidden, cfg.heads * cfg.head_dim
     ft = cfg.transition_factor * cz
