@@ -80,6 +80,22 @@ def cpu_baseline_pair(cfg, z, w):
                       "the per-row cost of a full run"}
 
 
+def cpu_baseline_res(cfg, x, layers):
+    """The oracle as it stands on a bounded sample: the first residual block on the first two images."""
+    from oracle import unet as U
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    n = min(2, cfg.batch)
+    t0 = time.perf_counter()
+    U.res_block(x, layers[0]["temb"], layers[0], cfg.groups, cfg.eps, images=list(range(n)))
+    dt = time.perf_counter() - t0
+    return {"value": n * cfg.height * cfg.width / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"block 1 of {cfg.layers} on {n} of {cfg.batch} images in fp64 ({dt:.1f} s), scaled to {cfg.layers} blocks"}
+
+
 def cpu_baseline_rows(cfg, x, layers, cores):
     """The oracle as it stands on a bounded sample of a long sequence: the keys and values of every
     token of layer 1 (which any row needs) and 8 blocks of 16 query rows spread evenly over the
@@ -194,8 +210,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5"],
-                    help="workload (default: C5, the largest that one GPU holds)")
+    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5", "U1"],
+                    help="workload (default: C5, the largest that one GPU holds; U1: UNet residual blocks, beside the five)")
     ap.add_argument("--chunk", type=int, nargs=3, default=None, metavar=("QKV", "ATTN", "FFN"),
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
@@ -235,7 +251,14 @@ def main():
     is_pair = isinstance(cfg, I.PairConfig)
     lanes_flag = B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if args.in_flight == 2 else 0
     pm_flag = B.AC_FLAG_BUDGET_PAPER_MODEL
-    if is_pair:
+    is_res = isinstance(cfg, I.ResStackConfig)
+    if is_res:
+        x, layers = I.res_stack_inputs(cfg)
+        dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in I.RES_BLOCK_TENSORS]
+        make_desc = lambda flags: B.res_stack_desc(cfg, flags=flags)
+        regs, budget = [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, args.chunk[0] if args.chunk else cfg.chunk_len)], 0
+        regs1 = [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, cfg.batch)]
+    elif is_pair:
         x, layers = I.pair_inputs(cfg)
         dw = [B.to_device(layers[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
         make_desc = lambda flags: B.pair_desc(cfg, flags=flags)
@@ -290,7 +313,9 @@ def main():
              "budget_bounds": ("executor bytes" if args.budget_on == "executor" else "executor and paper-model bytes") if budget else None,
              "segments_in_flight": args.in_flight, **chunk_lens(info),
              **({"chunk_dim": args.pair_dim} if is_pair else {})},
-            **({"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
+            **({"layers": cfg.layers, "batch": cfg.batch, "height": cfg.height, "width": cfg.width, "channels": cfg.channels,
+                "groups": cfg.groups, "tokens": "pixels (batch * height * width)"} if is_res else
+               {"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
                 "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
                {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,
                 "d_ffn": cfg.d_ffn, "causal": cfg.causal})),
@@ -336,7 +361,7 @@ def main():
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
         out["two_segments_in_flight"] = timed_variant(desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, regs, budget)
-    if extras and not (is_pair and args.pair_dim == "col"):
+    if extras and not is_res and not (is_pair and args.pair_dim == "col"):
         # The standalone row passes (bias + activation, residual add, LayerNorm), which the fused
         # plan folds into GEMM epilogues, timed with HIP events in a plan that runs them unfused.
         pu = B.Plan(make_desc(B.AC_FLAG_UNFUSED_ELEMENTWISE), regs, 0 if is_pair else budget)
@@ -350,7 +375,7 @@ def main():
                                         for s_ in su if s_["name"] in ("elementwise", "layernorm")}
         pu.close()
         del wu
-    if extras and not is_pair:
+    if extras and not is_pair and not is_res:
         # The same two plans with the attention core run as an unfused graph would (scores and
         # probabilities stored in the workspace): here the workspace really holds the intermediate
         # activations the paper's equations count, so the memory ratio of chunking is measured.
@@ -403,9 +428,9 @@ def main():
             out["planned_on_the_graph"] = entry
     if args.sweep:
         sweep = []
-        c = cfg.n_res if is_pair else cfg.seq
-        while c >= (8 if is_pair else 128):
-            ps = B.Plan(desc, pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
+        c = cfg.batch if is_res else cfg.n_res if is_pair else cfg.seq
+        while c >= (1 if is_res else 8 if is_pair else 128):
+            ps = B.Plan(desc, [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, c)] if is_res else pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
             ps.ac_plan_bind_weights(dw)
             inf = ps.ac_plan_query()
             if inf.workspace_bytes > ws.numel():
@@ -417,7 +442,7 @@ def main():
             c //= 2
         out["sweep"] = sweep
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_pair(cfg, x, layers) if is_pair else cpu_baseline(cfg, x, layers)
+        out["cpu_baseline"] = cpu_baseline_res(cfg, x, layers) if is_res else cpu_baseline_pair(cfg, x, layers) if is_pair else cpu_baseline(cfg, x, layers)
     print(json.dumps(out))
 
 

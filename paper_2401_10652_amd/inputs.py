@@ -237,9 +237,15 @@ class ResStackConfig:
     eps: float = 1e-5
     chunk_len: int = 1    # images per segment
 
+    @property
+    def tokens(self) -> int:
+        return self.batch * self.height * self.width      # pixels
+
 
 # a latent-diffusion stage: 64 x 64 latents, 320 channels, 32 groups
 U1 = ResStackConfig("U1_unet_res_b8_c320_64x64", 5, 2, 8, 64, 64, 320, 32, chunk_len=2)
+
+CONFIGS["U1"] = U1
 
 RES_BLOCK_TENSORS = ("gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb")
 

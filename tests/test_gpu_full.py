@@ -256,3 +256,37 @@ def test_c4_pair_block_half_size_against_whole_oracle(B):
     ref = P.pair_block(z, w, cfg.heads, cfg.activation, cfg.ln_eps)
     e, m = report("C4 block N=256", host(y), ref)
     assert e <= TOL["bf16"] and m <= 5 ** 0.5      # five modules in a chain
+
+
+def test_u1_unet_residual_blocks_full_size(B):
+    """The UNet workload (two residual blocks on 8 latents of 64 x 64 x 320, two images per segment): every
+    image of the first block against the oracle, the second block on the device's own output of the first
+    (read back) for two images, and the chunked run bit-equal to the one-segment run."""
+    import torch
+    from oracle import unet as U
+    cfg = I.U1
+    x, layers = I.res_stack_inputs(cfg)
+    dx = B.to_device(x, cfg.dtype)
+    flat = lambda w: [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for n in I.RES_BLOCK_TENSORS]
+
+    def run(c, n_layers, inp, weights):
+        one = I.ResStackConfig(cfg.name, cfg.index, n_layers, cfg.batch, cfg.height, cfg.width, cfg.channels, cfg.groups)
+        p = B.Plan(B.res_stack_desc(one), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, c)])
+        info = p.ac_plan_query()
+        p.ac_plan_bind_weights(weights)
+        y = torch.full_like(inp, float("nan"))
+        peak = p.ac_execute(inp, y, B.empty_workspace(info.workspace_bytes))
+        torch.cuda.synchronize()
+        assert peak == info.peak_bytes_planned
+        p.close()
+        return y, info
+
+    y1, _ = run(cfg.chunk_len, 1, dx, flat(layers[0]))
+    check(host(y1), U.res_block(x, layers[0]["temb"], layers[0], cfg.groups, cfg.eps), "bf16", what="block 1")
+    y2, info = run(cfg.chunk_len, 2, dx, flat(layers[0]) + flat(layers[1]))
+    h1 = host(y1)
+    ref2 = U.res_block(h1, layers[1]["temb"], layers[1], cfg.groups, cfg.eps, images=[0, cfg.batch - 1])
+    check(host(y2)[[0, cfg.batch - 1]], ref2, "bf16", what="block 2 on the device output of block 1")
+    y2w, info_w = run(cfg.batch, 2, dx, flat(layers[0]) + flat(layers[1]))
+    assert torch.equal(y2, y2w)
+    assert info.regions[0].n_segments == cfg.batch // cfg.chunk_len and info.workspace_bytes < info_w.workspace_bytes
