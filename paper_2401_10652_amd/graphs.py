@@ -136,6 +136,18 @@ def pair_executor_regions(chunks, names):
     return B.ac_graph_chunks_to_regions(pair_block_tags(names), chunks)
 
 
+def unet_stage_tags(names):
+    """ac_node_tag entries for a unet_stage_graph: the executor runs its residual block (nodes "res.*"), whose
+    tensors [batch, channels, height, width] it cuts along the batch only; the spatial transformer has no
+    region kind here."""
+    tags = [(-1, 0, ())] * len(names)
+    for full, idx in names.items():
+        prefix, _, last = full.rpartition(".")
+        if prefix == "res" and last in ("n1", "a1", "c1", "t", "n2", "a2", "c2", "y"):
+            tags[idx] = (B.AC_REGION_RES_BLOCK, 0, ((B.AC_DIM_BATCH, 1), (-1, 0), (-1, 0), (-1, 0)))
+    return B.node_tags(tags)
+
+
 def pair_block_graph(n_res, c_z, c_hidden, heads, head_dim, transition_factor):
     """One pair-stack block on z [n_res, n_res, c_z] as an unfused graph: triangle
     multiplicative update (outgoing "tmo", incoming "tmi"), triangle self-attention around the

@@ -226,3 +226,26 @@ def test_pair_chunks_map_to_executor_region_settings():
     assert PG.pair_executor_regions([(nm["tmo.o"], nm["tmo.z"], 1, 6)], nm) == [(B.AC_REGION_TRIMUL_OUT, B.AC_DIM_COL, 6)]
     with pytest.raises(B.AcError):      # the b operand is read whole by every segment: it belongs to no chunked part
         PG.pair_executor_regions([(nm["tmo.b"], nm["tmo.z"], 0, 6)], nm)
+
+
+def test_unet_residual_block_chunks_map_to_the_executor():
+    """Chunks of the residual block of the UNet stage graph: along the batch they become the executor's setting;
+    output channels of a convolution are legal by the rules (section 3.3) but the executor has no such dim; the
+    spatial transformer's chunks have no region kind."""
+    spec, nm = PG.unet_stage_graph(4, 64, 8, 8, 2, 7, 32, groups=8)
+    nodes = B.graph_nodes(spec)
+    tags = PG.unet_stage_tags(nm)
+    assert B.ac_chunk_trace(nodes, nm["res.n1"], nm["res.y"], 0) is not None
+    assert B.ac_graph_chunks_to_regions(tags, [(nm["res.n1"], nm["res.y"], 0, 2)]) == [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, 2)]
+    cfg = I.ResStackConfig("tmapu", 3, 1, 4, 8, 8, 64, 8)
+    info = B.Plan(B.res_stack_desc(cfg), B.ac_graph_chunks_to_regions(tags, [(nm["res.n1"], nm["res.y"], 0, 2)])).ac_plan_query()
+    assert info.regions[0].n_segments == 2
+    for bad, status in (([(nm["res.c2"], nm["res.c2"], 1, 16)], B.AC_ERR_UNSUPPORTED),      # output channels of the convolution
+                        ([(nm["tr.sa.scores"], nm["tr.sa.ctx_h"], 2, 16)], B.AC_ERR_ARG),   # the spatial transformer
+                        ([(nm["res.n1"], nm["tr.n"], 0, 1)], B.AC_ERR_ARG)):
+        with pytest.raises(B.AcError) as ei:
+            B.ac_graph_chunks_to_regions(tags, bad)
+        assert ei.value.status == status
+    # the executor's one legal dim is what the rules say: no other dim of the whole block is legal
+    for d in (1, 2, 3):
+        assert B.ac_chunk_trace(nodes, nm["res.n1"], nm["res.y"], d) is None

@@ -362,3 +362,31 @@ def test_public_headers_are_plain_c(tmp_path):
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_unet_residual_stack_plan():
+    """The residual stack's arena by hand (inter-block buffers, the bias-plus-embedding table, the GroupNorm
+    partial statistics, two tensors of a segment's images), its paper-style bytes (x and y whole, seven
+    intermediates of a segment), the one legal chunk dim and what the kernels do not take."""
+    cfg = I.ResStackConfig("tu", 9, 3, 6, 16, 16, 128, 32)
+    img = 16 * 16 * 128 * 2
+    whole = 2 * al(6 * img) + al(6 * 128 * 2) + al(6 * 32 * 16 * 3 * 4)
+    for c, lanes in ((6, 1), (2, 1), (4, 1), (1, 2)):
+        flags = B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if lanes == 2 else 0
+        info = B.Plan(B.res_stack_desc(cfg, flags=flags), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, c)]).ac_plan_query()
+        assert info.io_bytes == 2 * 6 * img and info.n_weights == 27 and info.n_regions == 1
+        assert info.workspace_bytes == whole + lanes * 2 * al(c * img)
+        assert info.peak_bytes_model == 2 * 6 * img + 7 * c * img and info.peak_bytes_model_unchunked == 9 * 6 * img
+        assert info.regions[0].n_segments == -(-6 // c) and info.regions[0].extent == 6
+    # the budget sizes the images per segment
+    one = B.Plan(B.res_stack_desc(cfg), []).ac_plan_query()
+    sized = B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, 0)], one.peak_bytes_planned - 2 * img).ac_plan_query()
+    assert sized.regions[0].chunk_len == 5 and sized.peak_bytes_planned <= one.peak_bytes_planned - 2 * img
+    expect(B.AC_ERR_BUDGET_INFEASIBLE, lambda: B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, 0)], 2 * 6 * img))
+    for dim in (B.AC_DIM_SEQ, B.AC_DIM_FEATURE):
+        expect(B.AC_ERR_ILLEGAL_CHUNK_DIM, lambda: B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_RES_BLOCK, dim, 2)]))
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_FFN, B.AC_DIM_BATCH, 2)]))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(I.ResStackConfig("f", 9, 1, 2, 8, 8, 64, 8, dtype="f32")), []))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(I.ResStackConfig("c", 9, 1, 2, 8, 8, 96, 8)), []))
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(I.ResStackConfig("g", 9, 1, 2, 8, 8, 64, 7)), []))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(cfg, flags=B.AC_FLAG_UNFUSED_ELEMENTWISE), []))
