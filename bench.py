@@ -36,7 +36,7 @@ PAIR_DIM = "row"     # --pair-dim: the chunk dimension of the pair-stack regions
 
 def pair_regions(B, c):
     dim = B.AC_DIM_COL if PAIR_DIM == "col" else B.AC_DIM_ROW
-    return [(k, dim, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)]
+    return [(k, dim, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1)]
 
 
 def time_plan(B, torch, plan, dx, y, ws, steps, warmup):

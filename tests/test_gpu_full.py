@@ -230,7 +230,7 @@ def test_c4_pair_block_link_by_link(B):
     dw = None
     cur = B.to_device(z, cfg.dtype)
     cur_host = np.asarray(z, np.float64)
-    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1), P.PAIR_MODULES):
         y, info, _, dw = run_pair(B, cfg, None, w, [k], c, flags=B.AC_FLAG_LISTED_REGIONS_ONLY, dz=cur, dw=dw)
         assert info.regions[k - B.AC_REGION_TRIMUL_OUT].n_segments == 16
         assert bool(torch.isfinite(y.float()).all())
@@ -240,7 +240,7 @@ def test_c4_pair_block_link_by_link(B):
         cur = y
         cur_host = host(y)
     del cur_host
-    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
+    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1))
     ya, infa, dz, _ = run_pair(B, cfg, z, w, kinds, c, dw=dw)
     assert torch.equal(ya, cur)          # the chain of single-module plans is the block
     yb, infb, _, _ = run_pair(B, cfg, z, w, kinds, n, dz=dz, dw=dw)
@@ -251,7 +251,7 @@ def test_c4_pair_block_link_by_link(B):
 def test_c4_pair_block_half_size_against_whole_oracle(B):
     cfg = dataclasses.replace(I.C4, n_res=256)
     z, w = I.pair_inputs(cfg)
-    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS))
+    kinds = list(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1))
     y, _, _, _ = run_pair(B, cfg, z, w, kinds, 64)
     ref = P.pair_block(z, w, cfg.heads, cfg.activation, cfg.ln_eps)
     e, m = report("C4 block N=256", host(y), ref)

@@ -65,7 +65,7 @@ def run_pair(B, cfg, chunk, modules_expected=True, bias_std=0.1, ln_jitter=0.1, 
     dz = B.to_device(z, cfg.dtype)
     dw = [B.to_device(w[n], cfg.dtype) for n in names]
     dims = dims or (B.AC_DIM_ROW,) * 5
-    regs = [(k, d, c) for k, d, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), dims, chunk)]
+    regs = [(k, d, c) for k, d, c in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1), dims, chunk)]
     p = B.Plan(B.pair_desc(cfg, flags=flags), regs)
     info = p.ac_plan_query()
     assert p.weight_names() == names
@@ -95,7 +95,7 @@ def test_chunks_planned_on_the_pair_graph_run_in_the_executor(B):
     chunks, peak = B.ac_graph_plan(nodes, 2, whole * 6 // 10, 12, (1.0, 0.0, 0.0, 0.0), beam=2)
     regs = dict((k, (d, l)) for k, d, l in PG.pair_executor_regions(chunks, names))
     assert regs[B.AC_REGION_TRIATT_START][0] == B.AC_DIM_ROW and regs[B.AC_REGION_TRIATT_END][0] == B.AC_DIM_COL
-    kinds = range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS)
+    kinds = range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1)
     dims = tuple(regs.get(k, (B.AC_DIM_ROW, n))[0] for k in kinds)
     lens = tuple(regs.get(k, (B.AC_DIM_ROW, n))[1] for k in kinds)
     z, w, y, info = run_pair(B, cfg, lens, dims=dims)
@@ -139,7 +139,7 @@ def test_pair_fused_projections_equal_the_separate_kernels(B):
     check(host(y), host(yu), "bf16", what="fused vs separate", depth=5)
     assert info.workspace_bytes < infu.workspace_bytes      # no normalised rows, no gates in memory
     # every module on its own against the oracle (one stage: the mixed gate at the tolerance itself)
-    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1), P.PAIR_MODULES):
         import torch
         dz = B.to_device(z, "bf16")
         names = [n for n, _ in I.pair_tensor_shapes(cfg)]
@@ -181,7 +181,7 @@ def test_pair_column_chunks_equal_the_oracle(B, dtype, n, cz, ch, heads, dh):
     names = [nm for nm, _ in I.pair_tensor_shapes(cfg)]
     dz = B.to_device(z, dtype)
     dw = [B.to_device(w[nm], dtype) for nm in names]
-    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS), P.PAIR_MODULES):
+    for k, name in zip(range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1), P.PAIR_MODULES):
         p = B.Plan(B.pair_desc(cfg, flags=B.AC_FLAG_LISTED_REGIONS_ONLY), [(k, B.AC_DIM_COL, 24)])
         p.ac_plan_bind_weights(dw)
         ws = B.empty_workspace(p.ac_plan_query().workspace_bytes)
@@ -194,7 +194,7 @@ def test_pair_column_chunks_equal_the_oracle(B, dtype, n, cz, ch, heads, dh):
 
 def test_pair_legality(B):
     d = B.pair_desc(I.C4)
-    for kind in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_KINDS):
+    for kind in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1):
         for dim in (B.AC_DIM_CHANNEL, B.AC_DIM_CONTRACT):
             with pytest.raises(B.AcError) as ei:
                 B.Plan(d, [(kind, dim, 64)])
