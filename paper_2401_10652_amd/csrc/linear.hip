@@ -359,17 +359,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // Software pipeline over k tiles with two register stages.  During step kt the wave
-  //   - has the global loads of tile kt+2 in flight into one register set,
+  // Software pipeline over k tiles with S register sets.  During step kt the wave
+  //   - has the global loads of tiles kt+2 .. kt+S in flight into S-1 register sets,
   //   - multiplies tile kt out of LDS buffer kt & 1, and
-  //   - between the MFMA groups of that multiply, writes tile kt+1 (loaded during the
-  //     previous step, so long since landed) from the other register set into the other LDS
+  //   - between the MFMA groups of that multiply, writes tile kt+1 (loaded S-1 steps ago,
+  //     so long since landed) from the remaining register set into the other LDS
   //     buffer.  LDS takes writes at about a third of its read rate, and all waves of the
   //     block reach the barrier together, so the writes must hide under the matrix work
   //     rather than sit between the multiply and the barrier.
-  bf16x8 a_r0[A_CHUNKS], w_r0[W_CHUNKS], a_r1[A_CHUNKS], w_r1[W_CHUNKS];
+  // Two sets are what the large tiles' accumulators leave room for.  The small tiles take four:
+  // inside a model their operands were written by the kernel before (another XCD's L2, so they
+  // come from memory), and a 512 x 768 x 3072 product on 32x64 tiles went from 15.6 to 12.3 us;
+  // with operands that are already in L2 the depth makes no difference.
   const int64_t kt_count = g.k / kBK;
   constexpr int KSTEPS = kBK / 16;
+  constexpr int S = TM * TN >= 4 ? 2 : 4;   // register sets of the staging ring (registers allow four only in the small tiles)
   auto load_regs = [&](bf16x8 (&ar)[A_CHUNKS], bf16x8 (&wr)[W_CHUNKS], int64_t kt) {
     const int64_t koff = kt * kBK;
     if (CONV) {
@@ -400,7 +404,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
     // No branches in the step: a conditional load would make the compiler lose count of the
     // loads in flight and wait for the newest ones before every LDS store.  Past the end the
     // last tile is simply loaded (and stored to the idle buffer) again.
-    load_regs(fill_a, fill_w, kt + 2 < kt_count ? kt + 2 : kt_count - 1);
+    load_regs(fill_a, fill_w, kt + S < kt_count ? kt + S : kt_count - 1);
     const int buf = (int)(kt & 1);
     const bf16_t* cA = sA + buf * BM * kLdsRow + (wave_m * WM + l32) * kLdsRow + half * 8;
     const bf16_t* cW = sW + buf * BN * kLdsRow + (wave_n * WN + l32) * kLdsRow + half * 8;
@@ -423,17 +427,84 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
     __syncthreads();
   };
 
-  load_regs(a_r0, w_r0, 0);
+  // One MFMA tile per wave (64x64 blocks: launches of a few hundred rows, one wave per SIMD): a k step is
+  // then one matrix instruction behind two LDS reads, and with the reads issued just before it the loop
+  // runs at the LDS latency, a third of the matrix rate.  Here the fragments of the WHOLE next tile are
+  // read while this tile's (already in registers) are multiplied, so everything is staged one tile earlier:
+  // during step kt the wave loads tile kt+S+1 from memory, reads the fragments of tile kt+1 out of LDS buffer
+  // (kt+1) & 1, multiplies tile kt from registers and writes tile kt+2 into buffer kt & 1 (whose reads were
+  // issued a step ago and have completed before the barrier).  Same instructions on the same operands in the
+  // same order per output element as the loop above, so results do not depend on which loop ran.
+  constexpr bool FRAGS_AHEAD = TM == 1 && TN == 1 && !CONV;
+  if constexpr (FRAGS_AHEAD) {
+    bf16x8 ra[S][A_CHUNKS], rw[S][W_CHUNKS];
+    bf16x8 fa[2][KSTEPS], fw[2][KSTEPS];
+    auto read_frags = [&](bf16x8 (&fa_)[KSTEPS], bf16x8 (&fw_)[KSTEPS], int buf) {
+      const bf16_t* cA = sA + buf * BM * kLdsRow + (wave_m * WM + l32) * kLdsRow + half * 8;
+      const bf16_t* cW = sW + buf * BN * kLdsRow + (wave_n * WN + l32) * kLdsRow + half * 8;
 #pragma unroll
-  for (int c = 0; c < CHUNKS; ++c) store_chunk(a_r0, w_r0, 0, c);
-  load_regs(a_r0, w_r0, kt_count > 1 ? 1 : 0);
-  __syncthreads();
-  int64_t kt = 0;
-  for (; kt + 1 < kt_count; kt += 2) {
-    step(kt, a_r0, w_r0, a_r1, w_r1);
-    step(kt + 1, a_r1, w_r1, a_r0, w_r0);
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        fa_[ks] = *reinterpret_cast<const bf16x8*>(cA + ks * 16);
+        fw_[ks] = *reinterpret_cast<const bf16x8*>(cW + ks * 16);
+      }
+    };
+    auto clamp_kt = [&](int64_t t) { return t < kt_count ? t : kt_count - 1; };   // past the end: the last tile again
+    // step kt: set `hold` carries tile kt+2, set `fill` (stored a step ago) takes tile kt+S+1
+    auto ahead = [&](int64_t kt, bf16x8 (&hold_a)[A_CHUNKS], bf16x8 (&hold_w)[W_CHUNKS],
+                     bf16x8 (&fill_a)[A_CHUNKS], bf16x8 (&fill_w)[W_CHUNKS],
+                     const bf16x8 (&cur_a)[KSTEPS], const bf16x8 (&cur_w)[KSTEPS],
+                     bf16x8 (&next_a)[KSTEPS], bf16x8 (&next_w)[KSTEPS]) {
+      load_regs(fill_a, fill_w, clamp_kt(kt + S + 1));
+      const int buf = (int)(kt & 1);
+      read_frags(next_a, next_w, buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);   // the reads go out before the first matrix instruction
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_w[ks], cur_a[ks], acc[0][0], 0, 0, 0);
+#pragma unroll
+        for (int c = ks * CHUNKS / KSTEPS; c < (ks + 1) * CHUNKS / KSTEPS; ++c) store_chunk(hold_a, hold_w, buf, c);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();
+    };
+    load_regs(ra[0], rw[0], 0);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) store_chunk(ra[0], rw[0], 0, c);
+    load_regs(ra[S - 1], rw[S - 1], clamp_kt(1));
+#pragma unroll
+    for (int u = 0; u + 1 < S; ++u) load_regs(ra[u], rw[u], clamp_kt(2 + u));
+    __syncthreads();
+    read_frags(fa[0], fw[0], 0);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) store_chunk(ra[S - 1], rw[S - 1], 1, c);
+    __syncthreads();
+    int64_t kt = 0;
+    for (; kt + S <= kt_count; kt += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u)
+        ahead(kt + u, ra[u], rw[u], ra[(u + S - 1) % S], rw[(u + S - 1) % S], fa[u & 1], fw[u & 1], fa[(u & 1) ^ 1], fw[(u & 1) ^ 1]);
+    }
+#pragma unroll
+    for (int u = 0; u + 1 < S; ++u)
+      if (kt + u < kt_count)
+        ahead(kt + u, ra[u], rw[u], ra[(u + S - 1) % S], rw[(u + S - 1) % S], fa[u & 1], fw[u & 1], fa[(u & 1) ^ 1], fw[(u & 1) ^ 1]);
+  } else {
+    bf16x8 ra[S][A_CHUNKS], rw[S][W_CHUNKS];
+    load_regs(ra[0], rw[0], 0);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) store_chunk(ra[0], rw[0], 0, c);
+#pragma unroll
+    for (int u = 0; u + 1 < S; ++u) load_regs(ra[u], rw[u], 1 + u < kt_count ? 1 + u : kt_count - 1);
+    __syncthreads();
+    int64_t kt = 0;
+    for (; kt + S <= kt_count; kt += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u) step(kt + u, ra[u], rw[u], ra[(u + S - 1) % S], rw[(u + S - 1) % S]);
+    }
+#pragma unroll
+    for (int u = 0; u + 1 < S; ++u)
+      if (kt + u < kt_count) step(kt + u, ra[u], rw[u], ra[(u + S - 1) % S], rw[(u + S - 1) % S]);
   }
-  if (kt < kt_count) step(kt, a_r0, w_r0, a_r1, w_r1);
 
   // acc[i][j][r]: row m = .. + l32, column n = .. + 8*(r/4) + 4*half + (r%4).
   bf16_t* lds = reinterpret_cast<bf16_t*>(smem_raw);
@@ -795,11 +866,18 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
     // tiles sit exactly there, 256x256 tiles have twice that.  Pick the tile with the least
     // estimated time: tiles per CU (rounded up) x padded tile area / measured efficiency of
     // that tile shape.  The k order is the same for all of them.
+    // The small tiles are for launches of a few hundred rows.  Their k loop runs at the rate one CU
+    // stages operands (measured: ~80 GB/s per CU, i.e. (BM + BN) x 128 bytes per k step), so with at
+    // most one tile per CU the time goes with BM + BN, and a launch that needs a second tile on some
+    // CUs takes twice as long: 512 x 768 is faster as 192 tiles of 32x64 than as 96 of 64x64 (and no
+    // faster as 384 of 32x32).  64x128 tiles were measured too: 512 x 3072 x 768 takes 12.7 us as 192
+    // of those against 11.0 us as 384 tiles of 64x64.
     struct Cand { int bm, bn; double eff; };
-    static const Cand cands[5] = {{256, 256, 0.41}, {256, 128, 0.376}, {128, 128, 0.36}, {64, 256, 0.26}, {64, 64, 0.253}};
-    int best = 4;
+    static const Cand cands[6] = {{256, 256, 0.41}, {256, 128, 0.376}, {128, 128, 0.36}, {64, 256, 0.26},
+                                  {64, 64, 0.253}, {32, 64, 0.169}};
+    int best = 0;
     double best_t = 0;
-    for (int c = 0; c < 5; ++c) {
+    for (int c = 0; c < 6; ++c) {
       const int64_t tiles = ((g.m + cands[c].bm - 1) / cands[c].bm) * ((g.n + cands[c].bn - 1) / cands[c].bn) * g.batch;
       const double t = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn / cands[c].eff;
       if (c == 0 || t < best_t) { best = c; best_t = t; }
@@ -809,7 +887,8 @@ hipError_t launch_linear(const LinearArgs& g_in, hipStream_t s) {
       case 1: return mfma_launch<256, 128, 4, 2>(g, s);
       case 2: return mfma_launch<128, 128, 2, 2>(g, s);
       case 3: return mfma_launch<64, 256, 1, 4>(g, s);
-      default: return mfma_launch<64, 64, 2, 2>(g, s);
+      case 4: return mfma_launch<64, 64, 2, 2>(g, s);
+      default: return mfma_launch<32, 64, 1, 2>(g, s);
     }
   }
   dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((g.m + 63) / 64), (unsigned)g.batch);

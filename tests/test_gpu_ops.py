@@ -38,7 +38,9 @@ def test_layernorm(B, dtype, rows, cols):
 
 
 @pytest.mark.parametrize("dtype,m,n,k", [
-    ("bf16", 300, 200, 192),      # 64x64 tiles, ragged m and n
+    ("bf16", 300, 200, 192),      # 32x64 tiles, ragged m and n
+    ("bf16", 500, 2040, 192),     # 64x64 tiles (256 of them), ragged m and n
+    ("bf16", 520, 3000, 128),     # 64x64 tiles in two rounds, ragged m and n
     ("bf16", 2048, 2048, 256),    # 128x128 tiles
     ("bf16", 1100, 3072, 128),    # 128x128 tiles, ragged m
     ("bf16", 77, 37, 100),        # odd shape -> generic kernel
