@@ -35,8 +35,11 @@ PAIR_DIM = "row"     # --pair-dim: the chunk dimension of the pair-stack regions
 
 
 def pair_regions(B, c):
-    dim = B.AC_DIM_COL if PAIR_DIM == "col" else B.AC_DIM_ROW
-    return [(k, dim, c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1)]
+    def dim(k):
+        if PAIR_DIM == "natural":   # rows, except the ending node's attention, whose problems are columns
+            return B.AC_DIM_COL if k == B.AC_REGION_TRIATT_END else B.AC_DIM_ROW
+        return B.AC_DIM_COL if PAIR_DIM == "col" else B.AC_DIM_ROW
+    return [(k, dim(k), c) for k in range(B.AC_REGION_TRIMUL_OUT, B.AC_REGION_PAIR_TRANSITION + 1)]
 
 
 def time_plan(B, torch, plan, dx, y, ws, steps, warmup):
@@ -216,7 +219,7 @@ def main():
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
                     help="segments of a region in flight at once (2: two streams, two per-segment workspaces)")
-    ap.add_argument("--pair-dim", default="row", choices=["row", "col"],
+    ap.add_argument("--pair-dim", default="row", choices=["row", "col", "natural"],
                     help="pair stack: chunk along rows (the workload's plan) or columns of z")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sequential-only", action="store_true",
@@ -361,7 +364,7 @@ def main():
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
         out["two_segments_in_flight"] = timed_variant(desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, regs, budget)
-    if extras and not is_res and not (is_pair and args.pair_dim == "col"):
+    if extras and not is_res and not (is_pair and args.pair_dim != "row"):
         # The standalone row passes (bias + activation, residual add, LayerNorm), which the fused
         # plan folds into GEMM epilogues, timed with HIP events in a plan that runs them unfused.
         pu = B.Plan(make_desc(B.AC_FLAG_UNFUSED_ELEMENTWISE), regs, 0 if is_pair else budget)

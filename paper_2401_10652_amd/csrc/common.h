@@ -133,6 +133,10 @@ struct LinearArgs {
   // batch > 1: `batch` independent products; a, w and out advance by these strides (elements).
   // bias / mul / resid / out_t must be null then.
   int64_t batch, sa_b, sw_b, so_b;
+  // batch > 1: nonzero = blocks take the products last to first.  Results are the same; a caller that runs
+  // the same operands launch after launch alternates the direction so that each launch starts with the
+  // products whose operands the one before touched last (they are the ones still in the memory-side cache).
+  int batch_descending;
   // conv_c > 0: a is a stack of channels-last images [m / (conv_h * conv_w)][conv_h][conv_w][conv_c] and the
   // product is their 3x3 convolution (stride 1, zero padding 1): row m is a pixel, k = 9 * conv_c runs over
   // (window row, window column, input channel), w is [n][3][3][conv_c].  lda is ignored (= conv_c).
@@ -166,7 +170,7 @@ struct AttnArgs {
 // kernel: t = LN(x) stays on chip and every part computes act(t w^T + bias) or, for a gated
 // pair, sigmoid(t w_gate^T + bias_gate) * (t w^T + bias), each with its own output layout.
 constexpr int kMaxProjParts = 5;
-constexpr int kMaxProjTiles = 24;
+constexpr int kMaxProjTiles = 48;
 struct ProjPart {
   const void* w; const void* bias;             // [n, K], [n] or null
   const void* w_gate; const void* bias_gate;   // of a gated pair

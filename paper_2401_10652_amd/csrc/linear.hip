@@ -318,9 +318,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
   int64_t tm_, tn_;
   tile_of_block(tiles_m, tiles_n, tm_, tn_);
   const int64_t m0 = tm_ * BM, n0 = tn_ * BN;
-  const bf16_t* a = (const bf16_t*)g.a + (int64_t)blockIdx.y * g.sa_b;
-  const bf16_t* w = (const bf16_t*)g.w + (int64_t)blockIdx.y * g.sw_b;
-  g.out = (bf16_t*)g.out + (int64_t)blockIdx.y * g.so_b;
+  const int64_t product = g.batch_descending ? (int64_t)gridDim.y - 1 - blockIdx.y : (int64_t)blockIdx.y;
+  const bf16_t* a = (const bf16_t*)g.a + product * g.sa_b;
+  const bf16_t* w = (const bf16_t*)g.w + product * g.sw_b;
+  g.out = (bf16_t*)g.out + product * g.so_b;
 
   // Global source of each 16-byte chunk this thread stages (rows clamped into range; the
   // results of clamped rows are never stored).
@@ -373,7 +374,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_mfma_bf16(Linea
   // with operands that are already in L2 the depth makes no difference.
   const int64_t kt_count = g.k / kBK;
   constexpr int KSTEPS = kBK / 16;
-  constexpr int S = TM * TN >= 4 ? 2 : 4;   // register sets of the staging ring (registers allow four only in the small tiles)
+  // register sets of the staging ring (registers allow four only in the small tiles)
+  constexpr int S = TM * TN < 4 ? 4 : 2;
   auto load_regs = [&](bf16x8 (&ar)[A_CHUNKS], bf16x8 (&wr)[W_CHUNKS], int64_t kt) {
     const int64_t koff = kt * kBK;
     if (CONV) {
@@ -540,8 +542,11 @@ static hipError_t mfma_launch(const LinearArgs& g, hipStream_t s) {
 // the transition's first layer).  Separate launches re-read the normalised rows each time and
 // are bound by that traffic, not by the matrix cores.  Here a block normalises 64 rows once
 // (the whole row is one k tile), keeps them in LDS as the matrix operand, and walks a list of
-// 128-column weight tiles (64 rows keep the accumulators small enough for two or three blocks per CU,
-// whose phases interleave: while one waits for its rows another multiplies and a third stores): each tile is prefetched into registers while the previous one is
+// 64-column weight tiles.  Tiles of 64 x 64 keep accumulators and LDS small enough for four blocks per
+// CU, whose phases interleave: while one waits for its rows another multiplies and a third stores
+// (measured against 64 x 128 tiles, two blocks per CU: the pair block at N = 1024 takes 9.7 instead of
+// 10.4 ms in one segment per region, 11.7 instead of 12.5 ms in 64-row segments, where a launch's 1024
+// blocks are then resident at once).  Each tile is prefetched into registers while the previous one is
 // multiplied, and leaves through the same epilogue as the GEMM above (row-major, regrouped
 // or strided store).  A gated pair keeps sigmoid(gate) in registers and multiplies the
 // projection by it, so the gate never reaches memory.  Per-row arithmetic does not depend on
@@ -556,10 +561,12 @@ struct LnProjKernelArgs {
 };
 
 constexpr int kLnProjRows = 64;   // rows per block
+constexpr int kLnProjCols = 64;   // columns per weight tile
 
-template <int K>
+template <int K, int BN>
 __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka) {
-  constexpr int BM = kLnProjRows, BN = 128, NT = 256;
+  constexpr int BM = kLnProjRows, NT = 256;
+  constexpr int TN = BN / 64;                 // 32-column MFMA tiles per wave (waves 2 x 2, 32 rows each)
   constexpr int AROW = K + 8;                 // padded LDS row (elements)
   constexpr int G = K / 8;                    // lanes per row in the LayerNorm pass (16-byte chunks per row)
   constexpr int RPP = NT / G;                 // rows per pass
@@ -634,28 +641,28 @@ __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka
     const ProjPart& q = p.part[ka.tile_part[t]];
     load_w(q.gated ? q.w_gate : q.w, q.n, ka.tile_n0[t], tid);
   };
-  f32x16 acc[1][2];
+  f32x16 acc[1][TN];
   const bf16_t* cA = sA + (wave_m * 32 + l32) * AROW + half * 8;
-  const bf16_t* cW = sW + (wave_n * 64 + l32) * AROW + half * 8;
+  const bf16_t* cW = sW + (wave_n * (BN / 2) + l32) * AROW + half * 8;
   auto multiply = [&]() {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[0][j][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       const bf16x8 fa = *reinterpret_cast<const bf16x8*>(cA + ks * 16);
-      bf16x8 fw[2];
+      bf16x8 fw[TN];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(cW + j * 32 * AROW + ks * 16);
+      for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(cW + j * 32 * AROW + ks * 16);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
         acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fa, acc[0][j], 0, 0, 0);
     }
   };
   // this lane's 4 consecutive columns of group q in 32-column tile j: acc[i][j][4q .. 4q+3]
   auto lane_bias = [&](const void* bias, int64_t n_total, int64_t n0, int j, int q) {
-    int64_t n = n0 + wave_n * 64 + j * 32 + 8 * q + 4 * half;
+    int64_t n = n0 + wave_n * (BN / 2) + j * 32 + 8 * q + 4 * half;
     if (n > n_total - 4) n = n_total - 4;
     bf16x4 bv = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
     if (bias) bv = *reinterpret_cast<const bf16x4*>((const bf16_t*)bias + n);
@@ -679,9 +686,9 @@ __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka
     __syncthreads();                         // every wave is done reading the weight tile
     if (gated) {
       // sigmoid(gate) stays in registers; the projection tile of the pair follows at once
-      f32x16 sg[1][2];
+      f32x16 sg[1][TN];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const bf16x4 bv = lane_bias(pp.bias_gate, pp.n, n0, j, q);
@@ -696,7 +703,7 @@ __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka
       multiply();
       __syncthreads();
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const bf16x4 bv = lane_bias(pp.bias, pp.n, n0, j, q);
@@ -711,7 +718,7 @@ __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka
       // bias and activation here, one uniform branch per tile, so that the epilogue below exists once
       const int act = pp.act;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const bf16x4 bv = lane_bias(pp.bias, pp.n, n0, j, q);
@@ -724,28 +731,28 @@ __global__ void __launch_bounds__(256, 2) ln_multi_proj_bf16(LnProjKernelArgs ka
 #pragma unroll
         for (int i = 0; i < 1; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_table(acc[i][j][r], gelu_tab);
       } else if (act == AC_ACT_SIGMOID) {
 #pragma unroll
         for (int i = 0; i < 1; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = sigmoidf(acc[i][j][r]);
       } else if (act == AC_ACT_RELU) {
 #pragma unroll
         for (int i = 0; i < 1; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = fmaxf(acc[i][j][r], 0.f);
       } else if (act == AC_ACT_GELU_TANH) {
 #pragma unroll
         for (int i = 0; i < 1; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_tanh(acc[i][j][r]);
       }
@@ -771,21 +778,21 @@ bool ln_proj_shapes_ok(int dtype, int64_t k, const int64_t* n, int n_parts) {
   int64_t tiles = 0;
   for (int i = 0; i < n_parts; ++i) {
     if (n[i] < 4 || n[i] % 4 != 0) return false;
-    tiles += (n[i] + 127) / 128;
+    tiles += (n[i] + kLnProjCols - 1) / kLnProjCols;
   }
   return tiles <= kMaxProjTiles;
 }
 
-template <int K>
+template <int K, int BN>
 static hipError_t ln_proj_launch(const LnProjKernelArgs& ka, hipStream_t s) {
-  auto kern = ln_multi_proj_bf16<K>;
-  constexpr int AROW = K + 8, STAGE = 128 * (kLnProjRows + 8);
-  constexpr int WBUF = 128 * AROW > STAGE ? 128 * AROW : STAGE;
+  auto kern = ln_multi_proj_bf16<K, BN>;
+  constexpr int AROW = K + 8, STAGE = BN * (kLnProjRows + 8);
+  constexpr int WBUF = BN * AROW > STAGE ? BN * AROW : STAGE;
   constexpr size_t lds_max = (size_t)(kLnProjRows * AROW + WBUF) * sizeof(bf16_t) + kGeluTableBytes;
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
   if (attr_status != hipSuccess) return attr_status;
-  // the GELU table is only there when a part needs it: without it three blocks fit a CU's LDS
+  // the GELU table is only there when a part needs it
   const size_t lds = lds_max - (ka.any_gelu ? 0 : kGeluTableBytes);
   const int64_t blocks = (ka.a.rows + kLnProjRows - 1) / kLnProjRows;
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, ka);
@@ -814,12 +821,13 @@ hipError_t launch_ln_proj(const LnProjArgs& p_in, hipStream_t s) {
     if (pp.o_period <= 0) pp.o_period = INT64_MAX;
     if (pp.o_period != INT64_MAX && (pp.o_s1 % 4 != 0 || pp.o_s2 % 4 != 0)) return hipErrorNotSupported;
     if (pp.act == AC_ACT_GELU_ERF && !pp.gated) ka.any_gelu = 1;
-    for (int64_t n0 = 0; n0 < pp.n; n0 += 128) {   // a gated pair is one entry: two weight tiles, one output tile
+  }
+  for (int i = 0; i < p.n_parts; ++i)
+    for (int64_t n0 = 0; n0 < p.part[i].n; n0 += kLnProjCols) {   // a gated pair is one entry: two weight tiles, one output tile
       ka.tile_part[ka.n_tiles] = i;
       ka.tile_n0[ka.n_tiles++] = (int)n0;
     }
-  }
-  return p.k == 128 ? ln_proj_launch<128>(ka, s) : ln_proj_launch<64>(ka, s);
+  return p.k == 128 ? ln_proj_launch<128, kLnProjCols>(ka, s) : ln_proj_launch<64, kLnProjCols>(ka, s);
 }
 
 static bool aligned_to(const void* p, uintptr_t a) { return p == nullptr || ((uintptr_t)p % a) == 0; }

@@ -361,8 +361,9 @@ struct Walk {
   }
   // out_c[c][i][j] = sum_k a_t[c][i][k] * b_t[c][j][k]: one NT product per channel.
   void contract(const void* a_t, int64_t lda, int64_t sa_c, const void* b_t, int64_t ldb, int64_t sb_c, void* out_c,
-                int64_t ldo, int64_t so_c, int64_t ni, int64_t nj, int64_t nk, int64_t channels) {
+                int64_t ldo, int64_t so_c, int64_t ni, int64_t nj, int64_t nk, int64_t channels, bool descending = false) {
     LinearArgs g{};
+    g.batch_descending = descending;
     g.a = a_t; g.lda = lda; g.sa_b = sa_c; g.w = b_t; g.ldw = ldb; g.sw_b = sb_c; g.out = out_c; g.ldo = ldo;
     g.so_b = so_c; g.m = ni; g.n = nj; g.k = nk; g.n_split = nj; g.batch = channels; g.dtype = p->m.dtype;
     const double by = ((double)ni * nk + (double)nj * nk + (double)ni * nj) * channels * eb();
@@ -739,7 +740,10 @@ void Walk::tri_mul(int kind, const void* const* W, const void* zin, void* zout) 
       g.out = gate; g.ldo = cz; g.m = rows; g.n = cz; g.k = cz; g.n_split = cz;
       linear(g);
     }
-    contract(at(col ? b_t : a_t, sg.i0 * N), N, R, col ? a_t : b_t, N, R, o_c, N, rows, sg.ni, N, N, ch);
+    // every segment reads the whole second operand, which is about the size of the memory-side cache: odd
+    // segments walk the channels backwards, so a segment starts on the channels the one before ended on
+    contract(at(col ? b_t : a_t, sg.i0 * N), N, R, col ? a_t : b_t, N, R, o_c, N, rows, sg.ni, N, N, ch,
+             (sg.i0 / seg_len(kind)) % 2 == 1);
     ln_channel_major(o_c, rows, W[TM_LN_OUT_G], W[TM_LN_OUT_B], lo, ch, rows, ch);
     LinearArgs o{};
     o.a = lo; o.lda = ch; o.w = W[TM_W_O]; o.ldw = ch; o.bias = W[TM_B_O]; o.mul = gate; o.ldmul = cz;
