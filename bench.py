@@ -364,6 +364,15 @@ def main():
         # the same plan with two segments of a region in flight on two streams (an executor option
         # on top of the strictly sequential schedule timed above)
         out["two_segments_in_flight"] = timed_variant(desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, regs, budget)
+    if extras and is_pair and args.pair_dim == "row":
+        # The workload fixes row chunks.  The ending node's attention has one problem per COLUMN, so a row
+        # chunk gives each problem 64 queries and reads every key and value of the tensor per segment; the
+        # same module chunked along columns (legal by section 3.3, and the dimension the stride term of
+        # section 3.4 prefers) is the starting node's form on a gathered segment.  Reported beside the plan.
+        natural = [(k, B.AC_DIM_COL if k == B.AC_REGION_TRIATT_END else d, c) for (k, d, c) in regs]
+        out["ending_node_chunked_along_columns"] = timed_variant(desc.flags, natural, budget)
+        out["ending_node_chunked_along_columns"]["two_segments_in_flight_ms_per_step"] = timed_variant(
+            desc.flags | B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, natural, budget)["ms_per_step"]
     if extras and not is_res and not (is_pair and args.pair_dim != "row"):
         # The standalone row passes (bias + activation, residual add, LayerNorm), which the fused
         # plan folds into GEMM epilogues, timed with HIP events in a plan that runs them unfused.

@@ -3,7 +3,8 @@
 C1-C3: the whole stack against the whole fp64 oracle (C3 also layer by layer).  C4: the pair
 block at N_res = 1024 link by link: each module runs on the device output of the module before
 it and is compared, on 64 output rows spread over all 16 segments, with the oracle fed that same
-device output; the chain equals the block run as one plan bit for bit; plus a whole block at
+device output; the chain equals the block run as one plan bit for bit, and so does the plan that
+chunks the ending node's attention along columns; plus a whole block at
 N_res = 256 against the whole oracle.  C5 (S = 65536): layer 1 against 1024 oracle rows that lie
 at the start, on both sides of two segment boundaries and at the end; layer 2 of the two-layer
 stack against the oracle's layer 2 evaluated on the device's own layer-1 output (read back; the
@@ -198,13 +199,13 @@ def test_c5_layer_2_on_the_device_output_of_layer_1(B, c5):
 # ---------------------------------------------------------------------------------------
 # C4
 # ---------------------------------------------------------------------------------------
-def run_pair(B, cfg, z, w, kinds, chunk, flags=0, dz=None, dw=None):
+def run_pair(B, cfg, z, w, kinds, chunk, flags=0, dz=None, dw=None, col_kinds=()):
     import torch
     if dz is None:
         dz = B.to_device(z, cfg.dtype)
     if dw is None:
         dw = [B.to_device(w[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
-    p = B.Plan(B.pair_desc(cfg, flags=flags), [(k, B.AC_DIM_ROW, chunk) for k in kinds])
+    p = B.Plan(B.pair_desc(cfg, flags=flags), [(k, B.AC_DIM_COL if k in col_kinds else B.AC_DIM_ROW, chunk) for k in kinds])
     info = p.ac_plan_query()
     p.ac_plan_bind_weights(dw)
     ws = B.empty_workspace(info.workspace_bytes)
@@ -246,6 +247,11 @@ def test_c4_pair_block_link_by_link(B):
     yb, infb, _, _ = run_pair(B, cfg, z, w, kinds, n, dz=dz, dw=dw)
     assert torch.equal(ya, yb)           # and the chunk length does not change a bit
     assert infa.peak_bytes_planned < infb.peak_bytes_planned
+    # the ending node's attention chunked along columns instead (the plan bench.py reports beside the
+    # workload's): one problem per column either way, the same arithmetic per (query, problem)
+    yc, infc, _, _ = run_pair(B, cfg, z, w, kinds, c, dz=dz, dw=dw, col_kinds=(B.AC_REGION_TRIATT_END,))
+    assert torch.equal(ya, yc)
+    assert infc.peak_bytes_planned <= infa.peak_bytes_planned
 
 
 def test_c4_pair_block_half_size_against_whole_oracle(B):
