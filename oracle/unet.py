@@ -1,4 +1,4 @@
-"""fp64 CPU oracle: residual block of a UNet stage.  Test infrastructure.
+"""fp64 CPU oracle: residual block and attention block of a UNet stage.  Test infrastructure.
 
 The paper (AutoChunk, section 4) evaluates a UNet (stable diffusion) without defining its
 modules.  The reading bound here is the residual block of the latent-diffusion UNet, written
@@ -18,10 +18,25 @@ Images are independent of each other in every op of the block (section 3.3: the 
 the legal chunk dim; GroupNorm reduces over positions and channels, the convolution over its
 window and the input channels), so `images` picks the ones to evaluate.  Nothing is blocked
 or reordered; the sum over the nine taps is written out, each tap a matrix product.
+
+The attention block that follows a residual block at the attention resolutions of that UNet
+(its "spatial transformer") is read here as: the H * W positions of an image are the tokens,
+
+  t = GroupNorm(x) W_in^T + b_in                  (no activation; a 1x1 convolution is a linear map per position)
+  t' = T(t)                                       (the pre-LN transformer block of oracle/transformer.py, non-causal:
+                                                   self-attention over the positions of one image, then the feed-forward)
+  y = x + t' W_out^T + b_out
+
+The cross-attention to a text context of the published model is left out (the workload has no
+context input) and the feed-forward is the GELU one of the other workloads, not the gated variant.
+Images are independent here too; nothing in the block knows a position's place in the image, so
+permuting the positions of x permutes y the same way.
 """
 from __future__ import annotations
 
 import numpy as np
+
+from oracle import transformer as _T
 
 
 def silu(v):
@@ -67,3 +82,18 @@ def res_block(x, temb, w, groups, eps=1e-5, images=None):
         x, temb = x[np.asarray(images)], temb[np.asarray(images)]
     h = conv3x3(silu(group_norm(x, w["gn1_g"], w["gn1_b"], groups, eps)), w["w1"], w["b1"]) + temb[:, None, None, :]
     return x + conv3x3(silu(group_norm(h, w["gn2_g"], w["gn2_b"], groups, eps)), w["w2"], w["b2"])
+
+
+ATTN_LAYER_TENSORS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
+
+
+def attn_block(x, w, groups, heads, eps=1e-5, images=None):
+    """y [len(images), H, W, C]; w: gn_g, gn_b, w_in, b_in, the twelve tensors of a transformer block, w_out, b_out."""
+    x = np.asarray(x, np.float64)
+    if images is not None:
+        x = x[np.asarray(images)]
+    b, h, wd, c = x.shape
+    t = _T.linear(group_norm(x, w["gn_g"], w["gn_b"], groups, eps).reshape(b * h * wd, c), w["w_in"], w["b_in"])
+    layer = {n: w[n] for n in ATTN_LAYER_TENSORS}
+    t = _T.transformer_block(t, layer, heads, False, eps=eps, batch=b)
+    return x + _T.linear(t, w["w_out"], w["b_out"]).reshape(b, h, wd, c)

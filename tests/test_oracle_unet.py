@@ -116,3 +116,96 @@ def test_res_block_equals_torch_composition_and_special_cases():
     # added to every channel changes nothing, different values per channel do
     np.testing.assert_allclose(U.res_block(x, temb + 1.0, w, groups), U.res_block(x, temb, w, groups), rtol=0, atol=1e-11)
     assert np.abs(U.res_block(x, temb + np.arange(c), w, groups) - U.res_block(x, temb, w, groups)).max() > 1e-3
+
+
+# ---- attention block ---------------------------------------------------------------------------
+
+def attn_weights(r, c, f, scale=0.5):
+    w = {"gn_g": 1 + 0.1 * r.standard_normal(c), "gn_b": 0.1 * r.standard_normal(c),
+         "ln1_g": 1 + 0.1 * r.standard_normal(c), "ln1_b": 0.1 * r.standard_normal(c),
+         "ln2_g": 1 + 0.1 * r.standard_normal(c), "ln2_b": 0.1 * r.standard_normal(c)}
+    for name, shp in (("w_in", (c, c)), ("w_qkv", (3 * c, c)), ("w_o", (c, c)), ("w_1", (f, c)), ("w_2", (c, f)), ("w_out", (c, c))):
+        w[name] = scale * r.standard_normal(shp) / np.sqrt(shp[1])
+        w["b_" + name[2:]] = 0.1 * r.standard_normal(shp[0])
+    return w
+
+
+def attn_block_loops(x, w, groups, heads, eps):
+    """The block written out scalar by scalar for one image (pure Python, math.erf / math.exp)."""
+    import math
+    h, wd, c = x.shape
+    n, cg, dh = h * wd, c // groups, c // heads
+    xs = [[float(x[i // wd, i % wd, ch]) for ch in range(c)] for i in range(n)]
+
+    def lin(rows, wm, bv):
+        return [[bv[o] + sum(row[i] * wm[o][i] for i in range(len(row))) for o in range(len(wm))] for row in rows]
+
+    def ln(rows, g, b):
+        out = []
+        for row in rows:
+            mu = sum(row) / len(row)
+            var = sum((v - mu) ** 2 for v in row) / len(row)
+            out.append([(v - mu) / math.sqrt(var + eps) * g[i] + b[i] for i, v in enumerate(row)])
+        return out
+
+    gn = [[0.0] * c for _ in range(n)]
+    for g in range(groups):
+        vals = [xs[i][ch] for i in range(n) for ch in range(g * cg, (g + 1) * cg)]
+        mu = sum(vals) / len(vals)
+        var = sum((v - mu) ** 2 for v in vals) / len(vals)
+        for i in range(n):
+            for ch in range(g * cg, (g + 1) * cg):
+                gn[i][ch] = (xs[i][ch] - mu) / math.sqrt(var + eps) * w["gn_g"][ch] + w["gn_b"][ch]
+    t = lin(gn, w["w_in"], w["b_in"])
+    qkv = lin(ln(t, w["ln1_g"], w["ln1_b"]), w["w_qkv"], w["b_qkv"])
+    ctx = [[0.0] * c for _ in range(n)]
+    for hd in range(heads):
+        for i in range(n):
+            sc = [sum(qkv[i][hd * dh + d] * qkv[j][c + hd * dh + d] for d in range(dh)) / math.sqrt(dh) for j in range(n)]
+            mx = max(sc)
+            ex = [math.exp(v - mx) for v in sc]
+            z = sum(ex)
+            for d in range(dh):
+                ctx[i][hd * dh + d] = sum(ex[j] / z * qkv[j][2 * c + hd * dh + d] for j in range(n))
+    o = lin(ctx, w["w_o"], w["b_o"])
+    t2 = [[t[i][ch] + o[i][ch] for ch in range(c)] for i in range(n)]
+    hid = lin(ln(t2, w["ln2_g"], w["ln2_b"]), w["w_1"], w["b_1"])
+    act = [[0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in row] for row in hid]
+    dn = lin(act, w["w_2"], w["b_2"])
+    t3 = [[t2[i][ch] + dn[i][ch] for ch in range(c)] for i in range(n)]
+    out = lin(t3, w["w_out"], w["b_out"])
+    return np.array([[xs[i][ch] + out[i][ch] for ch in range(c)] for i in range(n)]).reshape(h, wd, c)
+
+
+def test_attn_block_equals_scalar_loops():
+    r = rng(20)
+    x = r.standard_normal((2, 3, 2, 8))
+    w = attn_weights(r, 8, 16)
+    got = U.attn_block(x, w, groups=2, heads=2, eps=1e-5)
+    for b in range(2):
+        np.testing.assert_allclose(got[b], attn_block_loops(x[b], w, 2, 2, 1e-5), rtol=0, atol=1e-12)
+
+
+def test_attn_block_special_cases():
+    r = rng(21)
+    x = r.standard_normal((3, 4, 4, 8))
+    w = attn_weights(r, 8, 32)
+    y = U.attn_block(x, w, groups=4, heads=2)
+    # images are independent, and `images` picks them
+    np.testing.assert_array_equal(U.attn_block(x, w, 4, 2, images=[2, 0]), y[[2, 0]])
+    np.testing.assert_allclose(U.attn_block(x[1:2], w, 4, 2)[0], y[1], rtol=0, atol=1e-13)
+    # no op of the block knows where a position lies: permuting the positions permutes the result
+    perm = r.permutation(16)
+    xp = x.reshape(3, 16, 8)[:, perm].reshape(3, 4, 4, 8)
+    np.testing.assert_allclose(U.attn_block(xp, w, 4, 2).reshape(3, 16, 8), y.reshape(3, 16, 8)[:, perm], rtol=0, atol=1e-12)
+    # a zero output projection leaves the skip alone
+    w0 = dict(w, w_out=np.zeros((8, 8)), b_out=np.zeros(8))
+    np.testing.assert_array_equal(U.attn_block(x, w0, 4, 2), x)
+    # with the attention's and the feed-forward's output projections zero the transformer block is the
+    # identity and what is left is two linear maps of the normalised image
+    wi = dict(w, w_o=np.zeros((8, 8)), b_o=np.zeros(8), w_2=np.zeros((8, 32)), b_2=np.zeros(8))
+    gn = U.group_norm(x, w["gn_g"], w["gn_b"], 4)
+    want = x + np.einsum("bhwc,oc->bhwo", np.einsum("bhwc,oc->bhwo", gn, w["w_in"]) + w["b_in"], w["w_out"]) + w["b_out"]
+    np.testing.assert_allclose(U.attn_block(x, wi, 4, 2), want, rtol=0, atol=1e-12)
+    # one head or four: different results (the head split is really applied)
+    assert np.abs(U.attn_block(x, w, 4, 4) - y).max() > 1e-3
