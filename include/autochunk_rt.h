@@ -70,7 +70,9 @@ typedef enum ac_region_kind {
   AC_REGION_PAIR_TRANSITION = 8,
   AC_REGION_RES_BLOCK = 9,      /* UNet residual block: GroupNorm, SiLU, 3x3 convolution, time
                                    embedding, again, skip (section 4 names the family)       */
-  AC_REGION_KINDS = 10
+  AC_REGION_UNET_ATTN = 10,     /* UNet attention block: GroupNorm, linear in, pre-LN self-attention
+                                   over the positions of an image and feed-forward, linear out, skip */
+  AC_REGION_KINDS = 11
 } ac_region_kind;
 
 /* Chunk dimensions are named per workload.  Transformer regions see their tensors as
@@ -135,7 +137,13 @@ typedef struct ac_model_desc {
   /* UNet residual stack (bf16 only): x and y are channels-last images [batch, img_h, img_w, channels];
    * `layers` residual blocks one after another, GroupNorm over `groups` runs of consecutive channels.
    * Its one region kind is chunked along the batch (AC_DIM_BATCH): every other dim is reduced over by
-   * a GroupNorm or by a convolution window (section 3.3). */
+   * a GroupNorm or by a convolution window (section 3.3).
+   * With heads > 0 every residual block is followed by an attention block (region kind
+   * AC_REGION_UNET_ATTN, also chunked along the batch: its GroupNorm and its attention reduce over the
+   * positions): `heads` heads of channels / heads = 32, 64 or 128 channels each, feed-forward width
+   * d_ffn (a multiple of 64) with `activation`; head_dim is ignored.  A layer's weights are then the
+   * nine tensors of the residual block followed by the eighteen of the attention block (names and
+   * shapes from ac_plan_weight_info). */
   int32_t img_h, img_w, channels, groups;
 } ac_model_desc;
 

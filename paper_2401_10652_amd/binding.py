@@ -20,7 +20,7 @@ AC_F32, AC_BF16 = 0, 1
 AC_ACT_NONE, AC_ACT_GELU_ERF, AC_ACT_GELU_TANH, AC_ACT_RELU, AC_ACT_SIGMOID, AC_ACT_SILU = 0, 1, 2, 3, 4, 5
 (AC_REGION_QKV, AC_REGION_ATTENTION, AC_REGION_OUT_PROJ, AC_REGION_FFN, AC_REGION_TRIMUL_OUT,
  AC_REGION_TRIMUL_IN, AC_REGION_TRIATT_START, AC_REGION_TRIATT_END, AC_REGION_PAIR_TRANSITION,
- AC_REGION_RES_BLOCK, AC_REGION_KINDS) = range(11)
+ AC_REGION_RES_BLOCK, AC_REGION_UNET_ATTN, AC_REGION_KINDS) = range(12)
 AC_DIM_BATCH, AC_DIM_SEQ, AC_DIM_FEATURE, AC_DIM_HEAD_DIM, AC_DIM_KEY = range(5)
 AC_DIM_ROW, AC_DIM_COL, AC_DIM_CHANNEL, AC_DIM_CONTRACT = range(4)
 AC_FLAG_UNFUSED_ELEMENTWISE = 1
@@ -235,6 +235,8 @@ def res_stack_desc(cfg, flags=0) -> ac_model_desc:
     m.dtype = DTYPES[cfg.dtype]
     m.layers, m.batch = cfg.layers, cfg.batch
     m.img_h, m.img_w, m.channels, m.groups = cfg.height, cfg.width, cfg.channels, cfg.groups
+    m.heads, m.d_ffn = cfg.heads, cfg.d_ffn              # heads > 0: an attention block after every residual block
+    m.activation = ACTIVATIONS[cfg.activation]
     m.flags = flags
     m.ln_eps = cfg.eps
     return m

@@ -954,9 +954,19 @@ void Walk::pair(const void* x, void* y) {
 // with the bias and the time embedding (one vector per image), and the skip, in the convolutions'
 // epilogues.  A segment holds a and t; whole: the [B, C] bias-plus-embedding table, the GroupNorm
 // partial statistics, one inter-block buffer.
+//
+// With heads > 0 an attention block follows every residual block; the positions of an image are its tokens:
+//   t = GroupNorm(x) W_in^T + b_in;  t += attention(LN1(t)) W_o^T + b_o;  t += act(LN2(t) W_1^T + b_1) W_2^T + b_2;
+//   y = x + t W_out^T + b_out
+// Per segment of images it holds the normalised rows (GroupNorm, then either LayerNorm), t (updated in place
+// by the two residual epilogues), q | k and the transposed v, the context and the feed-forward's hidden rows.
 // ---------------------------------------------------------------------------------------
 enum { RB_GN1_G, RB_GN1_B, RB_W1, RB_B1, RB_GN2_G, RB_GN2_B, RB_W2, RB_B2, RB_TEMB, RB_COUNT };
 static const char* const kRbName[RB_COUNT] = {"gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb"};
+enum { AB_GN_G, AB_GN_B, AB_W_IN, AB_B_IN, AB_LN1_G, AB_LN1_B, AB_W_QKV, AB_B_QKV, AB_W_O, AB_B_O,
+       AB_LN2_G, AB_LN2_B, AB_W_1, AB_B_1, AB_W_2, AB_B_2, AB_W_OUT, AB_B_OUT, AB_COUNT };
+static const char* const kAbName[AB_COUNT] = {"gn_g", "gn_b", "w_in", "b_in", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                                              "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2", "w_out", "b_out"};
 
 void Walk::res_stack(const void* x, void* y) {
   const ac_model_desc& m = p->m;
@@ -965,45 +975,89 @@ void Walk::res_stack(const void* x, void* y) {
   auto at = [&](const void* base, int64_t elems) { return (const void*)((const uint8_t*)base + elems * e); };
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t img_bytes = (uint64_t)HW * C * e;
+  const bool with_attn = m.heads > 0;
+  const int per_layer = RB_COUNT + (with_attn ? AB_COUNT : 0);
+  const int modules = m.layers * (with_attn ? 2 : 1);          // each maps [B, H, W, C] to the same shape
   void* tbuf[2] = {nullptr, nullptr};
-  if (m.layers > 1) tbuf[0] = arena.push((uint64_t)m.batch * img_bytes);
-  if (m.layers > 2) tbuf[1] = arena.push((uint64_t)m.batch * img_bytes);
+  if (modules > 1) tbuf[0] = arena.push((uint64_t)m.batch * img_bytes);
+  if (modules > 2) tbuf[1] = arena.push((uint64_t)m.batch * img_bytes);
   void* bt = arena.push((uint64_t)m.batch * C * e);                                  // b1 + temb, per image
   void* stats = arena.push(group_norm_workspace_bytes(m.batch, m.groups));
-  enter(AC_REGION_RES_BLOCK);
-  std::vector<RowSeg> segs;
-  for (int64_t b = 0; b < m.batch; b += seg_len(AC_REGION_RES_BLOCK)) segs.push_back(RowSeg{b, std::min<int64_t>(seg_len(AC_REGION_RES_BLOCK), m.batch - b)});
+  auto image_segments = [&](int kind) {
+    std::vector<RowSeg> segs;
+    for (int64_t b = 0; b < m.batch; b += seg_len(kind)) segs.push_back(RowSeg{b, std::min<int64_t>(seg_len(kind), m.batch - b)});
+    return segs;
+  };
   const int dt = m.dtype;
-  for (int l = 0; l < m.layers && ok(); ++l) {
-    const void* in = l == 0 ? x : (const void*)tbuf[(l - 1) % 2];
-    void* out = l == m.layers - 1 ? y : tbuf[l % 2];
-    auto W = [&](int slot) { return w(l, slot, RB_COUNT); };
-    bias_act(W(RB_TEMB), C, W(RB_B1), bt, C, m.batch, C, AC_ACT_NONE);
-    seg_loop(segs, [&](const RowSeg& sg) {
-      const int64_t nb = sg.ni, px = nb * HW;
-      const void* xs = at(in, sg.i0 * HW * C);
-      void* a = arena.push((uint64_t)nb * img_bytes);
-      void* t = arena.push((uint64_t)nb * img_bytes);
-      // the partial statistics of the segment's images sit at the images' own place in the table, so two
-      // segments in flight do not share any of it
+  for (int idx = 0; idx < modules && ok(); ++idx) {
+    const int l = with_attn ? idx / 2 : idx;
+    const bool attn = with_attn && idx % 2 == 1;
+    const void* in = idx == 0 ? x : (const void*)tbuf[(idx - 1) % 2];
+    void* out = idx == modules - 1 ? y : tbuf[idx % 2];
+    auto W = [&](int slot) { return w(l, (attn ? RB_COUNT : 0) + slot, per_layer); };
+    // GroupNorm of a segment's images; their partial statistics sit at the images' own place in the table,
+    // so two segments in flight do not share any of it
+    auto gn = [&](const RowSeg& sg, const void* src, int gslot, int bslot, void* dst, int act) {
+      const void* gg = W(gslot); const void* bb = W(bslot);
       void* st = dry ? nullptr : (void*)((uint8_t*)stats + group_norm_workspace_bytes(sg.i0, m.groups));
-      auto gn = [&](const void* src, int gslot, int bslot, void* dst) {
-        const void* gg = W(gslot); const void* bb = W(bslot);
-        hipStream_t s_ = stream;
-        run(K_LN, 8.0 * px * C, 3.0 * px * C * e, "group norm",
-            [&] { return launch_group_norm(src, gg, bb, dst, st, nb, HW, (int)C, m.groups, m.ln_eps, AC_ACT_SILU, dt, s_); });
-      };
-      auto conv = [&](const void* src, int wslot, const void* bias, int64_t bias_period, const void* resid, void* dst) {
-        LinearArgs g{};
-        g.a = src; g.lda = C; g.w = W(wslot); g.ldw = 9 * C; g.bias = bias; g.bias_period = bias_period;
-        g.resid = resid; g.ldr = C; g.out = dst; g.ldo = C; g.m = px; g.n = C; g.k = 9 * C; g.n_split = C;
-        g.conv_h = m.img_h; g.conv_w = m.img_w; g.conv_c = (int)C;
-        linear(g);
-      };
-      gn(xs, RB_GN1_G, RB_GN1_B, a);
-      conv(a, RB_W1, at(bt, sg.i0 * C), HW, nullptr, t);
-      gn(t, RB_GN2_G, RB_GN2_B, a);
-      conv(a, RB_W2, W(RB_B2), 0, xs, atw(out, sg.i0 * HW * C));
+      const int64_t nb = sg.ni;
+      hipStream_t s_ = stream;
+      run(K_LN, 8.0 * nb * HW * C, 3.0 * nb * HW * C * e, "group norm",
+          [&] { return launch_group_norm(src, gg, bb, dst, st, nb, HW, (int)C, m.groups, m.ln_eps, act, dt, s_); });
+    };
+    if (!attn) {
+      enter(AC_REGION_RES_BLOCK);
+      bias_act(W(RB_TEMB), C, W(RB_B1), bt, C, m.batch, C, AC_ACT_NONE);
+      seg_loop(image_segments(AC_REGION_RES_BLOCK), [&](const RowSeg& sg) {
+        const int64_t nb = sg.ni, px = nb * HW;
+        const void* xs = at(in, sg.i0 * HW * C);
+        void* a = arena.push((uint64_t)nb * img_bytes);
+        void* t = arena.push((uint64_t)nb * img_bytes);
+        auto conv = [&](const void* src, int wslot, const void* bias, int64_t bias_period, const void* resid, void* dst) {
+          LinearArgs g{};
+          g.a = src; g.lda = C; g.w = W(wslot); g.ldw = 9 * C; g.bias = bias; g.bias_period = bias_period;
+          g.resid = resid; g.ldr = C; g.out = dst; g.ldo = C; g.m = px; g.n = C; g.k = 9 * C; g.n_split = C;
+          g.conv_h = m.img_h; g.conv_w = m.img_w; g.conv_c = (int)C;
+          linear(g);
+        };
+        gn(sg, xs, RB_GN1_G, RB_GN1_B, a, AC_ACT_SILU);
+        conv(a, RB_W1, at(bt, sg.i0 * C), HW, nullptr, t);
+        gn(sg, t, RB_GN2_G, RB_GN2_B, a, AC_ACT_SILU);
+        conv(a, RB_W2, W(RB_B2), 0, xs, atw(out, sg.i0 * HW * C));
+      });
+      continue;
+    }
+    enter(AC_REGION_UNET_ATTN);
+    const int64_t F = m.d_ffn, dh = C / m.heads;
+    seg_loop(image_segments(AC_REGION_UNET_ATTN), [&](const RowSeg& sg) {
+      const int64_t nb = sg.ni, T = nb * HW;
+      const void* xs = at(in, sg.i0 * HW * C);
+      void* u = arena.push((uint64_t)T * C * e);        // normalised rows: GroupNorm, then LayerNorm 1, then LayerNorm 2
+      void* t = arena.push((uint64_t)T * C * e);        // the block's stream, updated in place by the residual epilogues
+      void* qk = arena.push((uint64_t)T * 2 * C * e);   // q | k row-major
+      void* vt = arena.push((uint64_t)T * C * e);       // v transposed per image: [image][C][HW]
+      void* ctx = arena.push((uint64_t)T * C * e);
+      void* hid = arena.push((uint64_t)T * F * e);
+      gn(sg, xs, AB_GN_G, AB_GN_B, u, AC_ACT_NONE);
+      proj(u, C, W(AB_W_IN), C, W(AB_B_IN), AC_ACT_NONE, nullptr, 0, t, C, T, C);
+      ln(t, C, W(AB_LN1_G), W(AB_LN1_B), u, C, T, C);
+      LinearArgs g{};
+      g.a = u; g.lda = C; g.w = W(AB_W_QKV); g.ldw = C; g.bias = W(AB_B_QKV); g.m = T; g.n = 3 * C; g.k = C;
+      g.out = qk; g.ldo = 2 * C; g.n_split = 2 * C;
+      g.out_t = vt; g.t_period = HW; g.t_s1 = C * HW; g.t_s2 = 1; g.t_s3 = HW;
+      linear(g);
+      AttnArgs a{};
+      a.q = qk; a.ldq = 2 * C; a.sq_b = HW * 2 * C;
+      a.k = at(qk, C); a.ldk = 2 * C; a.sk_b = HW * 2 * C;
+      a.v = vt; a.ldv = HW; a.sv_b = C * HW; a.v_transposed = 1;
+      a.ctx = ctx; a.ldc = C; a.sc_b = HW * C;
+      a.batch = nb; a.sq = HW; a.sk = HW; a.heads = m.heads; a.head_dim = (int)dh; a.causal = 0; a.q_offset = 0;
+      attention(a);
+      proj(ctx, C, W(AB_W_O), C, W(AB_B_O), AC_ACT_NONE, t, C, t, C, T, C);
+      ln(t, C, W(AB_LN2_G), W(AB_LN2_B), u, C, T, C);
+      proj(u, C, W(AB_W_1), C, W(AB_B_1), m.activation, nullptr, 0, hid, F, T, F);
+      proj(hid, F, W(AB_W_2), F, W(AB_B_2), AC_ACT_NONE, t, C, t, C, T, C);
+      proj(t, C, W(AB_W_OUT), C, W(AB_B_OUT), AC_ACT_NONE, xs, C, atw(out, sg.i0 * HW * C), C, T, C);
     });
   }
 }
@@ -1029,6 +1083,14 @@ static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
     // x and y whole; per segment of c images the seven intermediates of the unfused block
     // (two normalised, two activated, two convolved tensors and the sum with the embedding)
     const uint64_t img = (uint64_t)m.img_h * m.img_w * m.channels * b;
+    if (kind == AC_REGION_UNET_ATTN) {
+      // per image of a segment, every op output a tensor: the normalised image, t, LayerNorm 1, q, k, v, the
+      // context, its projection, the sum, LayerNorm 2, the down projection, the sum, the output projection
+      // (13 images' worth), the hidden rows before and after the activation, scores and probabilities
+      const uint64_t hw = (uint64_t)m.img_h * m.img_w;
+      return 2 * (uint64_t)m.batch * img +
+             (uint64_t)c * (13 * img + 2 * hw * m.d_ffn * b + 2 * (uint64_t)m.heads * hw * hw * b);
+    }
     return 2 * (uint64_t)m.batch * img + 7 * (uint64_t)c * img;
   }
   const uint64_t n = m.n_res, cz = m.c_z, ch = m.c_hidden, hd = (uint64_t)m.tri_heads * m.tri_head_dim;
@@ -1059,7 +1121,7 @@ static int64_t model_rows(const ac_model_desc& m, const Setting& s, int64_t len)
 
 static void region_kinds(const ac_model_desc& m, int& first, int& count) {
   if (m.workload == AC_TRANSFORMER_STACK) { first = AC_REGION_QKV; count = 4; }
-  else if (m.workload == AC_UNET_RES_STACK) { first = AC_REGION_RES_BLOCK; count = 1; }
+  else if (m.workload == AC_UNET_RES_STACK) { first = AC_REGION_RES_BLOCK; count = m.heads > 0 ? 2 : 1; }
   else { first = AC_REGION_TRIMUL_OUT; count = 5; }
 }
 
@@ -1171,6 +1233,14 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
                                       "at most 128 groups and fewer than 2^31 pixels");
     if (m.flags & (AC_FLAG_UNFUSED_ELEMENTWISE | AC_FLAG_BUDGET_PAPER_MODEL))
       return fail(AC_ERR_UNSUPPORTED, "flags %d do not apply to the residual stack", m.flags);
+    if (m.heads < 0) return fail(AC_ERR_ARG, "heads must be >= 0");
+    if (m.heads > 0) {
+      if (m.channels % m.heads != 0) return fail(AC_ERR_ARG, "channels (%d) must be a multiple of heads (%d)", m.channels, m.heads);
+      const int dh = m.channels / m.heads;
+      if ((dh != 32 && dh != 64 && dh != 128) || m.d_ffn < 64 || m.d_ffn % 64 != 0 || (int64_t)m.img_h * m.img_w % 64 != 0)
+        return fail(AC_ERR_UNSUPPORTED, "the attention block takes heads of 32, 64 or 128 channels, a feed-forward width in "
+                                        "multiples of 64 and images of a multiple of 64 positions");
+    }
   } else {
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
@@ -1286,12 +1356,20 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
   if (m.workload == AC_UNET_RES_STACK) {
     const int64_t C = m.channels;
     const int64_t shp[RB_COUNT][2] = {{1, C}, {1, C}, {C, 9 * C}, {1, C}, {1, C}, {1, C}, {C, 9 * C}, {1, C}, {m.batch, C}};
-    for (int l = 0; l < m.layers; ++l)
+    const int64_t F = m.d_ffn;
+    const int64_t ashp[AB_COUNT][2] = {{1, C}, {1, C}, {C, C}, {1, C}, {1, C}, {1, C}, {3 * C, C}, {1, 3 * C}, {C, C}, {1, C},
+                                       {1, C}, {1, C}, {F, C}, {1, F}, {C, F}, {1, C}, {C, C}, {1, C}};
+    for (int l = 0; l < m.layers; ++l) {
+      char nm[48];
       for (int t = 0; t < RB_COUNT; ++t) {
-        char nm[48];
         snprintf(nm, sizeof(nm), "R%d.%s", l, kRbName[t]);
         p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
       }
+      for (int t = 0; m.heads > 0 && t < AB_COUNT; ++t) {
+        snprintf(nm, sizeof(nm), "A%d.%s", l, kAbName[t]);
+        p->weights.push_back(WeightSlot{nm, ashp[t][0], ashp[t][1]});
+      }
+    }
   }
   if (m.workload == AC_PAIR_STACK) {
     const int64_t cz = m.c_z, ch = m.c_hidden, hd = (int64_t)m.tri_heads * m.tri_head_dim, H = m.tri_heads;

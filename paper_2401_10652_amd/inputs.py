@@ -236,6 +236,9 @@ class ResStackConfig:
     dtype: str = "bf16"
     eps: float = 1e-5
     chunk_len: int = 1    # images per segment
+    heads: int = 0        # > 0: every residual block is followed by an attention block with this many heads
+    d_ffn: int = 0        # ... and a feed-forward of this width
+    activation: str = "gelu_erf"
 
     @property
     def tokens(self) -> int:
@@ -245,9 +248,16 @@ class ResStackConfig:
 # a latent-diffusion stage: 64 x 64 latents, 320 channels, 32 groups
 U1 = ResStackConfig("U1_unet_res_b8_c320_64x64", 5, 2, 8, 64, 64, 320, 32, chunk_len=2)
 
+# the same stage at an attention resolution: every residual block followed by an attention block over the
+# 4096 positions of an image (5 heads of 64 channels, feed-forward 4 x 320)
+U2 = ResStackConfig("U2_unet_res_attn_b8_c320_64x64", 6, 1, 8, 64, 64, 320, 32, chunk_len=2, heads=5, d_ffn=1280)
+
 CONFIGS["U1"] = U1
+CONFIGS["U2"] = U2
 
 RES_BLOCK_TENSORS = ("gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb")
+ATTN_BLOCK_TENSORS = ("gn_g", "gn_b", "w_in", "b_in", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                      "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2", "w_out", "b_out")
 
 
 def res_stack_inputs(cfg: ResStackConfig, seed: int = BASE_SEED, bias_std: float = 0.0, gn_jitter: float = 0.0):
@@ -278,6 +288,31 @@ def res_stack_inputs(cfg: ResStackConfig, seed: int = BASE_SEED, bias_std: float
                 else:
                     st.skip()
                     w[name] = np.zeros((c,), np.float32)
+        if cfg.heads > 0:
+            f = cfg.d_ffn
+            shapes = {"w_in": (c, c), "w_qkv": (3 * c, c), "w_o": (c, c), "w_1": (f, c), "w_2": (c, f), "w_out": (c, c)}
+            for name in ATTN_BLOCK_TENSORS:
+                if name.startswith("w_"):
+                    w[name] = st.normal(shapes[name], 1.0 / math.sqrt(shapes[name][1]), cfg.dtype)
+                elif name.startswith("b_"):
+                    n = shapes["w_" + name[2:]][0]
+                    if bias_std > 0:
+                        w[name] = st.normal((n,), bias_std, cfg.dtype)
+                    else:
+                        st.skip()
+                        w[name] = np.zeros((n,), np.float32)
+                elif name.endswith("_g"):
+                    if gn_jitter > 0:
+                        w[name] = round_to_storage(1.0 + st.normal((c,), gn_jitter, "f32"), cfg.dtype)
+                    else:
+                        st.skip()
+                        w[name] = np.ones((c,), np.float32)
+                else:
+                    if gn_jitter > 0:
+                        w[name] = st.normal((c,), gn_jitter, cfg.dtype)
+                    else:
+                        st.skip()
+                        w[name] = np.zeros((c,), np.float32)
         layers.append(w)
     return x, layers
 

@@ -1,5 +1,5 @@
-"""GPU parity of the UNet residual block: its two kernels alone and whole chunk plans against the fp64 oracle,
-through the C-ABI."""
+"""GPU parity of the UNet stage: the residual block's two kernels alone, and whole chunk plans of residual blocks
+and of residual + attention blocks against the fp64 oracle, through the C-ABI."""
 import numpy as np
 import pytest
 
@@ -149,3 +149,97 @@ def test_res_stack_budget_and_legality(B):
     with pytest.raises(B.AcError) as ei:
         B.Plan(B.res_stack_desc(I.ResStackConfig("bad", 48, 1, 2, 8, 8, 48, 8)), [])
     assert ei.value.status == B.AC_ERR_UNSUPPORTED
+
+
+# ---- residual block + attention block ------------------------------------------------------------
+
+def stage_tensors(cfg):
+    return list(I.RES_BLOCK_TENSORS) + (list(I.ATTN_BLOCK_TENSORS) if cfg.heads > 0 else [])
+
+
+def run_stage(B, cfg, chunk_res, chunk_attn, flags=0, budget=0, inputs=None):
+    """A plan of the stage (each layer: residual block, then attention block) with its two regions' chunk lengths."""
+    import torch
+    x, layers = inputs if inputs is not None else I.res_stack_inputs(cfg, bias_std=0.2, gn_jitter=0.2)
+    dx = B.to_device(x, cfg.dtype)
+    dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in stage_tensors(cfg)]
+    regs = []
+    if chunk_res is not None:
+        regs.append((B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, chunk_res))
+    if chunk_attn is not None:
+        regs.append((B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, chunk_attn))
+    p = B.Plan(B.res_stack_desc(cfg, flags=flags), regs, budget)
+    info = p.ac_plan_query()
+    assert p.weight_names() == [f"{'R' if n in I.RES_BLOCK_TENSORS else 'A'}{l}.{n}" for l in range(cfg.layers) for n in stage_tensors(cfg)]
+    p.ac_plan_bind_weights(dw)
+    need = int(info.workspace_bytes)
+    ws = torch.full((need + 4096,), CANARY, dtype=torch.uint8, device="cuda")
+    y = torch.full_like(dx, float("nan"))
+    peak = p.ac_execute(dx, y, ws[:need])
+    torch.cuda.synchronize()
+    assert bool((ws[need:] == CANARY).all())
+    assert peak == info.peak_bytes_planned
+    p.close()
+    return x, layers, y, info
+
+
+def oracle_stage(cfg, x, layers):
+    y = x
+    for w in layers:
+        y = U.res_block(y, w["temb"], w, cfg.groups, cfg.eps)
+        y = U.attn_block(y, w, cfg.groups, cfg.heads, cfg.eps)
+    return y
+
+
+@pytest.mark.parametrize("layers,batch,h,w,c,groups,heads,f", [(1, 3, 8, 8, 64, 8, 2, 128), (2, 4, 16, 8, 128, 32, 2, 256),
+                                                              (1, 2, 16, 16, 320, 32, 5, 640), (1, 2, 8, 8, 128, 16, 1, 64)])
+def test_stage_with_attention_chunked_equals_oracle(B, layers, batch, h, w, c, groups, heads, f):
+    """Heads of 32, 64 and 128 channels; every chunk length of the two regions gives the same bits, because images
+    never meet (the attention of an image sees its own positions only)."""
+    import torch
+    cfg = I.ResStackConfig("tua", 49, layers, batch, h, w, c, groups, heads=heads, d_ffn=f)
+    x, lw, y1, i1 = run_stage(B, cfg, None, None)
+    assert [i1.regions[k].n_segments for k in range(2)] == [1, 1]
+    ref = oracle_stage(cfg, x, lw)
+    check(host(y1), ref, "bf16", what="one segment per region", depth=2 * layers)
+    for cr, ca in ((1, 1), (2, 1), (batch, 2), (3, batch)):
+        _, _, y, info = run_stage(B, cfg, cr, ca, inputs=(x, lw))
+        assert info.regions[1].n_segments == -(-batch // min(ca, batch)) and info.regions[1].kind == B.AC_REGION_UNET_ATTN
+        assert torch.equal(y, y1), (cr, ca)
+        if ca < batch:      # the attention block's segment is the larger of the two
+            assert info.peak_bytes_planned < i1.peak_bytes_planned
+    _, _, y2, _ = run_stage(B, cfg, 1, 1, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, inputs=(x, lw))
+    assert torch.equal(y2, y1)
+
+
+def test_stage_with_attention_bytes_and_legality(B):
+    cfg = I.ResStackConfig("tub2", 50, 1, 4, 8, 8, 64, 8, heads=2, d_ffn=128)
+    al = lambda n: (n + 255) // 256 * 256
+    hw, c, f, e = 64, 64, 128, 2
+    img = hw * c * e
+    _, _, _, info = run_stage(B, cfg, 4, 1)
+    # whole: one buffer between the two blocks, the bias + embedding table, the GroupNorm statistics; the attention
+    # block's segment of one image holds u, t, q|k (two), v^T, the context and the hidden rows; the residual block's
+    # segment of four images two tensors
+    whole = al(4 * img) + al(4 * c * e) + al(4 * 8 * 16 * 3 * 4)
+    attn_seg = 2 * al(img) + al(2 * img) + 2 * al(img) + al(hw * f * e)
+    res_seg = 2 * al(4 * img)
+    assert info.workspace_bytes == whole + max(attn_seg, res_seg)
+    assert info.regions[1].model_bytes == 2 * 4 * img + 13 * img + 2 * hw * f * e + 2 * 2 * hw * hw * e
+    for dim in (B.AC_DIM_SEQ, B.AC_DIM_FEATURE):
+        with pytest.raises(B.AcError) as ei:
+            B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_UNET_ATTN, dim, 1)])
+        assert ei.value.status == B.AC_ERR_ILLEGAL_CHUNK_DIM
+    # heads of 48 channels have no attention kernel here; without heads the region kind does not exist
+    with pytest.raises(B.AcError) as ei:
+        B.Plan(B.res_stack_desc(I.ResStackConfig("bad", 51, 1, 2, 8, 8, 192, 8, heads=4, d_ffn=128)), [])
+    assert ei.value.status == B.AC_ERR_UNSUPPORTED
+    with pytest.raises(B.AcError) as ei:
+        B.Plan(B.res_stack_desc(I.ResStackConfig("bad", 52, 1, 2, 8, 8, 64, 8)), [(B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, 1)])
+    assert ei.value.status == B.AC_ERR_ARG
+    # a budget sizes the attention block's segments
+    _, _, y1, i1 = run_stage(B, cfg, None, None)
+    budget = i1.peak_bytes_planned - 2 * attn_seg
+    _, _, yb, ib = run_stage(B, cfg, 4, 0, budget=budget)
+    import torch
+    assert ib.regions[1].chunk_len < 4 and ib.peak_bytes_planned <= budget and torch.equal(yb, y1)
