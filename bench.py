@@ -84,7 +84,8 @@ def cpu_baseline_pair(cfg, z, w):
 
 
 def cpu_baseline_res(cfg, x, layers):
-    """The oracle as it stands on a bounded sample: the first residual block on the first two images."""
+    """The oracle as it stands on a bounded sample: the first layer (residual block, and the attention block where
+    the stage has one) on the first two images."""
     from oracle import unet as U
     try:
         from threadpoolctl import threadpool_info
@@ -93,10 +94,13 @@ def cpu_baseline_res(cfg, x, layers):
         cores = os.cpu_count()
     n = min(2, cfg.batch)
     t0 = time.perf_counter()
-    U.res_block(x, layers[0]["temb"], layers[0], cfg.groups, cfg.eps, images=list(range(n)))
+    h = U.res_block(x, layers[0]["temb"], layers[0], cfg.groups, cfg.eps, images=list(range(n)))
+    if cfg.heads > 0:
+        U.attn_block(h, layers[0], cfg.groups, cfg.heads, cfg.eps)
     dt = time.perf_counter() - t0
+    what = "residual + attention block" if cfg.heads > 0 else "block"
     return {"value": n * cfg.height * cfg.width / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"block 1 of {cfg.layers} on {n} of {cfg.batch} images in fp64 ({dt:.1f} s), scaled to {cfg.layers} blocks"}
+            "sample": f"{what} 1 of {cfg.layers} on {n} of {cfg.batch} images in fp64 ({dt:.1f} s), scaled to {cfg.layers} layers"}
 
 
 def cpu_baseline_rows(cfg, x, layers, cores):
@@ -213,8 +217,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5", "U1"],
-                    help="workload (default: C5, the largest that one GPU holds; U1: UNet residual blocks, beside the five)")
+    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5", "U1", "U2"],
+                    help="workload (default: C5, the largest that one GPU holds; beside the five: U1, UNet residual blocks; "
+                         "U2, a residual block followed by an attention block)")
     ap.add_argument("--chunk", type=int, nargs=3, default=None, metavar=("QKV", "ATTN", "FFN"),
                     help="rows per segment for the three regions (default: the workload's plan)")
     ap.add_argument("--in-flight", type=int, default=1, choices=[1, 2],
@@ -257,10 +262,13 @@ def main():
     is_res = isinstance(cfg, I.ResStackConfig)
     if is_res:
         x, layers = I.res_stack_inputs(cfg)
-        dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in I.RES_BLOCK_TENSORS]
+        names = I.RES_BLOCK_TENSORS + (I.ATTN_BLOCK_TENSORS if cfg.heads > 0 else ())
+        dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in names]
         make_desc = lambda flags: B.res_stack_desc(cfg, flags=flags)
-        regs, budget = [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, args.chunk[0] if args.chunk else cfg.chunk_len)], 0
-        regs1 = [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, cfg.batch)]
+        res_regions = lambda c: [(k, B.AC_DIM_BATCH, c) for k in ((B.AC_REGION_RES_BLOCK, B.AC_REGION_UNET_ATTN) if cfg.heads > 0
+                                                                  else (B.AC_REGION_RES_BLOCK,))]
+        regs, budget = res_regions(args.chunk[0] if args.chunk else cfg.chunk_len), 0
+        regs1 = res_regions(cfg.batch)
     elif is_pair:
         x, layers = I.pair_inputs(cfg)
         dw = [B.to_device(layers[n], cfg.dtype) for n, _ in I.pair_tensor_shapes(cfg)]
@@ -317,7 +325,7 @@ def main():
              "segments_in_flight": args.in_flight, **chunk_lens(info),
              **({"chunk_dim": args.pair_dim} if is_pair else {})},
             **({"layers": cfg.layers, "batch": cfg.batch, "height": cfg.height, "width": cfg.width, "channels": cfg.channels,
-                "groups": cfg.groups, "tokens": "pixels (batch * height * width)"} if is_res else
+                "groups": cfg.groups, "heads": cfg.heads, "d_ffn": cfg.d_ffn, "tokens": "pixels (batch * height * width)"} if is_res else
                {"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
                 "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
                {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,
@@ -442,7 +450,7 @@ def main():
         sweep = []
         c = cfg.batch if is_res else cfg.n_res if is_pair else cfg.seq
         while c >= (1 if is_res else 8 if is_pair else 128):
-            ps = B.Plan(desc, [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, c)] if is_res else pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
+            ps = B.Plan(desc, res_regions(c) if is_res else pair_regions(B, c) if is_pair else plan_regions(B, c, c, c), 0)
             ps.ac_plan_bind_weights(dw)
             inf = ps.ac_plan_query()
             if inf.workspace_bytes > ws.numel():

@@ -296,3 +296,42 @@ def test_u1_unet_residual_blocks_full_size(B):
     y2w, info_w = run(cfg.batch, 2, dx, flat(layers[0]) + flat(layers[1]))
     assert torch.equal(y2, y2w)
     assert info.regions[0].n_segments == cfg.batch // cfg.chunk_len and info.workspace_bytes < info_w.workspace_bytes
+
+
+def test_u2_unet_residual_and_attention_block_full_size(B):
+    """The UNet stage at an attention resolution (8 latents of 64 x 64 x 320: a residual block, then an attention
+    block over the 4096 positions of each image, 5 heads of 64 channels; two images per segment): the residual
+    block of every image against the oracle, the attention block on the device's own output of the residual block
+    (read back) for the first and the last image, and the chunked run against the one-segment run (their attention
+    launches cut the keys differently, so they agree to rounding, not bitwise)."""
+    import torch
+    from oracle import unet as U
+    cfg = I.U2
+    x, layers = I.res_stack_inputs(cfg)
+    w = layers[0]
+    dx = B.to_device(x, cfg.dtype)
+    flat = lambda names: [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for n in names]
+
+    def run(c, heads):
+        one = dataclasses.replace(cfg, heads=heads, d_ffn=cfg.d_ffn if heads else 0)
+        kinds = (B.AC_REGION_RES_BLOCK, B.AC_REGION_UNET_ATTN) if heads else (B.AC_REGION_RES_BLOCK,)
+        p = B.Plan(B.res_stack_desc(one), [(k, B.AC_DIM_BATCH, c) for k in kinds])
+        info = p.ac_plan_query()
+        p.ac_plan_bind_weights(flat(I.RES_BLOCK_TENSORS + (I.ATTN_BLOCK_TENSORS if heads else ())))
+        y = torch.full_like(dx, float("nan"))
+        peak = p.ac_execute(dx, y, B.empty_workspace(info.workspace_bytes))
+        torch.cuda.synchronize()
+        assert peak == info.peak_bytes_planned
+        p.close()
+        return y, info
+
+    yr, _ = run(cfg.chunk_len, 0)
+    check(host(yr), U.res_block(x, w["temb"], w, cfg.groups, cfg.eps), "bf16", what="residual block")
+    y, info = run(cfg.chunk_len, cfg.heads)
+    assert bool(torch.isfinite(y.float()).all())
+    pick = [0, cfg.batch - 1]
+    ref = U.attn_block(host(yr)[pick], w, cfg.groups, cfg.heads, cfg.eps)
+    check(host(y)[pick], ref, "bf16", what="attention block on the device output of the residual block")
+    yw, info_w = run(cfg.batch, cfg.heads)
+    assert rel_err(host(y), host(yw)) <= 0.5 * TOL["bf16"]
+    assert [info.regions[k].n_segments for k in range(2)] == [4, 4] and info.workspace_bytes < info_w.workspace_bytes
