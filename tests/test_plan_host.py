@@ -1,6 +1,7 @@
 """Host-side checks that need no GPU: the library loads and exports what the header
 declares; plan arithmetic against the paper-style memory model and against the arena
 worked out by hand; legality and error codes."""
+import dataclasses
 import os
 import re
 
@@ -390,3 +391,36 @@ def test_unet_residual_stack_plan():
     expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(I.ResStackConfig("c", 9, 1, 2, 8, 8, 96, 8)), []))
     expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(I.ResStackConfig("g", 9, 1, 2, 8, 8, 64, 7)), []))
     expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(cfg, flags=B.AC_FLAG_UNFUSED_ELEMENTWISE), []))
+
+
+def test_unet_stage_with_attention_plan():
+    """A residual block followed by an attention block per layer: the weight list, the two regions, the attention
+    block's arena by hand at 4096 positions (where its attention launch also holds the partial results of its key
+    splits), its paper-style bytes, and the shapes the attention kernels do not take."""
+    cfg = I.ResStackConfig("tua", 10, 2, 4, 64, 64, 320, 32, heads=5, d_ffn=1280)
+    hw, c, f, e = 4096, 320, 1280, 2
+    img = hw * c * e
+    p = B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, 4), (B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, 1)])
+    info = p.ac_plan_query()
+    names = p.weight_names()
+    assert info.n_weights == 2 * 27 and info.n_regions == 2
+    assert names[:9] == [f"R0.{n}" for n in I.RES_BLOCK_TENSORS] and names[9:27] == [f"A0.{n}" for n in I.ATTN_BLOCK_TENSORS]
+    assert names[27] == "R1.gn1_g" and names[-1] == "A1.b_out"
+    shapes = {p.ac_plan_weight_info(i).name.decode(): (p.ac_plan_weight_info(i).rows, p.ac_plan_weight_info(i).cols) for i in range(27)}
+    assert shapes["A0.w_qkv"] == (3 * c, c) and shapes["A0.w_1"] == (f, c) and shapes["A0.w_2"] == (c, f) and shapes["A0.b_qkv"] == (1, 3 * c)
+    assert [info.regions[k].kind for k in range(2)] == [B.AC_REGION_RES_BLOCK, B.AC_REGION_UNET_ATTN]
+    assert [info.regions[k].n_segments for k in range(2)] == [1, 4]
+    assert info.regions[1].model_bytes == 2 * 4 * img + 13 * img + 2 * hw * f * e + 2 * 5 * hw * hw * e
+    assert info.regions[1].model_bytes_unchunked == 2 * 4 * img + 4 * (13 * img + 2 * hw * f * e + 2 * 5 * hw * hw * e)
+    # four modules: two whole buffers between them; one image of the attention block holds u, t, q|k, v^T, the
+    # context, the hidden rows (the residual block's segment of four images is smaller: 8 images' worth against 10)
+    whole = 2 * al(4 * img) + al(4 * c * e) + al(4 * 32 * 16 * 3 * 4)
+    seg = 2 * al(img) + al(2 * img) + 2 * al(img) + al(hw * f * e)
+    assert seg + whole <= info.workspace_bytes <= seg + whole + (64 << 20)      # + the key splits' fp32 partials
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=4)), []))       # 80 channels per head
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=7)), []))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, d_ffn=100)), []))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, height=5, width=5)), []))
+    expect(B.AC_ERR_ILLEGAL_CHUNK_DIM, lambda: B.Plan(B.res_stack_desc(cfg), [(B.AC_REGION_UNET_ATTN, B.AC_DIM_SEQ, 64)]))
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=0, d_ffn=0)),
+                                        [(B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, 1)]))
