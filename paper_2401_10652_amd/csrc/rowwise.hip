@@ -105,7 +105,10 @@ static hipError_t ln_dispatch(const void* x, int64_t ldx, const void* g, const v
       case 16:  return ln_launch<T, 16, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
       case 32:  return ln_launch<T, 32, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
       case 64:  return ln_launch<T, 64, 1>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 40:  return ln_launch<T, 8, 5>(x, ldx, g, b, y, ldy, rows, eps, s);     // 320 bf16 channels (UNet stages:
+      case 80:  return ln_launch<T, 16, 5>(x, ldx, g, b, y, ldy, rows, eps, s);    //  320, 640, 1280)
       case 96:  return ln_launch<T, 32, 3>(x, ldx, g, b, y, ldy, rows, eps, s);
+      case 160: return ln_launch<T, 32, 5>(x, ldx, g, b, y, ldy, rows, eps, s);
       case 128: return ln_launch<T, 64, 2>(x, ldx, g, b, y, ldy, rows, eps, s);
       case 192: return ln_launch<T, 64, 3>(x, ldx, g, b, y, ldy, rows, eps, s);
       case 256: return ln_launch<T, 64, 4>(x, ldx, g, b, y, ldy, rows, eps, s);

@@ -22,7 +22,8 @@ def dev(B, arr, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,cols", [(5, 64), (300, 128), (257, 768), (130, 1024), (70, 2048), (33, 100), (9, 24)])
+@pytest.mark.parametrize("rows,cols", [(5, 64), (300, 128), (257, 768), (130, 1024), (70, 2048), (33, 100), (9, 24),
+                                       (70, 320), (33, 640), (21, 1280)])
 def test_layernorm(B, dtype, rows, cols):
     import torch
     from paper_2401_10652_amd.inputs import round_to_storage
