@@ -105,14 +105,15 @@ def cpu_baseline_res(cfg, x, layers):
 
 def cpu_baseline_rows(cfg, x, layers, cores):
     """The oracle as it stands on a bounded sample of a long sequence: the keys and values of every
-    token of layer 1 (which any row needs) and 8 blocks of 16 query rows spread evenly over the
+    token of layer 1 (which any row needs) and 64 blocks of 16 query rows spread evenly over the
     sequence, through attention, output projection and feed-forward; scaled to all rows and layers."""
     from oracle import transformer as O
     S = cfg.seq
     t0 = time.perf_counter()
     O.transformer_block_row_blocks(x, layers[0], cfg.heads, cfg.causal, [], cfg.activation, cfg.ln_eps)
     t_kv = time.perf_counter() - t0
-    blocks = [(r, r + 16) for r in range(S // 16, S, S // 8)][:8]
+    n_blocks = 64          # about ten seconds of oracle time on the box's host cores
+    blocks = [(r, r + 16) for r in range(S // (2 * n_blocks), S, S // n_blocks)][:n_blocks]
     n_rows = sum(b - a for a, b in blocks)
     t0 = time.perf_counter()
     O.transformer_block_row_blocks(x, layers[0], cfg.heads, cfg.causal, blocks, cfg.activation, cfg.ln_eps)
@@ -120,7 +121,7 @@ def cpu_baseline_rows(cfg, x, layers, cores):
     per_layer = t_kv + t_rows * S / n_rows
     return {"value": S / (per_layer * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"layer 1 of {cfg.layers} in fp64: LayerNorm + key/value projection of all {S} tokens "
-                      f"({t_kv:.1f} s) and {n_rows} query rows in 8 blocks spread over the sequence through "
+                      f"({t_kv:.1f} s) and {n_rows} query rows in {len(blocks)} blocks spread over the sequence through "
                       f"attention, output projection and feed-forward ({t_rows:.1f} s); scaled to {S} rows "
                       f"and {cfg.layers} layers"}
 
