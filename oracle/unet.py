@@ -27,10 +27,19 @@ The attention block that follows a residual block at the attention resolutions o
                                                    self-attention over the positions of one image, then the feed-forward)
   y = x + t' W_out^T + b_out
 
-The cross-attention to a text context of the published model is left out (the workload has no
-context input) and the feed-forward is the GELU one of the other workloads, not the gated variant.
-Images are independent here too; nothing in the block knows a position's place in the image, so
-permuting the positions of x permutes y the same way.
+Two parts of the published block are optional here.  With a context [B, T_c, D] (one sequence per
+image, e.g. an encoded prompt) a cross-attention sits between the self-attention and the feed-forward,
+
+  t'' = t' + attention(LN_c(t') W_qc^T,  context W_kc^T,  context W_vc^T) W_oc^T + b_oc
+
+(queries from the image's positions, keys and values from its context; no biases on the three input
+projections; w_kvc stacks W_kc over W_vc), and with `gated` the feed-forward's first layer is 2F wide,
+
+  hidden = (u W_1[:F]^T + b_1[:F]) * gelu(u W_1[F:]^T + b_1[F:])
+
+instead of gelu(u W_1^T + b_1).  Images are independent here too; nothing in the block knows a
+position's place in the image, so permuting the positions of x permutes y the same way, and
+permuting the tokens of a context changes nothing.
 """
 from __future__ import annotations
 
@@ -87,13 +96,31 @@ def res_block(x, temb, w, groups, eps=1e-5, images=None):
 ATTN_LAYER_TENSORS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 
 
-def attn_block(x, w, groups, heads, eps=1e-5, images=None):
-    """y [len(images), H, W, C]; w: gn_g, gn_b, w_in, b_in, the twelve tensors of a transformer block, w_out, b_out."""
+def attn_block(x, w, groups, heads, eps=1e-5, images=None, context=None, gated=False):
+    """y [len(images), H, W, C]; w: gn_g, gn_b, w_in, b_in, the twelve tensors of a transformer block, w_out, b_out,
+    and with a context [B, T_c, D] also lnc_g, lnc_b, w_qc [C, C], w_kvc [2C, D], w_oc, b_oc."""
     x = np.asarray(x, np.float64)
     if images is not None:
         x = x[np.asarray(images)]
+        context = None if context is None else np.asarray(context, np.float64)[np.asarray(images)]
     b, h, wd, c = x.shape
-    t = _T.linear(group_norm(x, w["gn_g"], w["gn_b"], groups, eps).reshape(b * h * wd, c), w["w_in"], w["b_in"])
-    layer = {n: w[n] for n in ATTN_LAYER_TENSORS}
-    t = _T.transformer_block(t, layer, heads, False, eps=eps, batch=b)
-    return x + _T.linear(t, w["w_out"], w["b_out"]).reshape(b, h, wd, c)
+    n = h * wd
+    t = _T.linear(group_norm(x, w["gn_g"], w["gn_b"], groups, eps).reshape(b * n, c), w["w_in"], w["b_in"])
+    layer = {k: w[k] for k in ATTN_LAYER_TENSORS}
+    out = np.empty_like(t)
+    for i in range(b):
+        ti = _T.attention_region(t[i * n:(i + 1) * n], layer, heads, False, eps)
+        if context is not None:
+            u = _T.layer_norm(ti, w["lnc_g"], w["lnc_b"], eps)
+            kv = _T.linear(np.asarray(context[i], np.float64), w["w_kvc"])
+            ctx = _T.attention(_T.linear(u, w["w_qc"]), kv[:, :c], kv[:, c:], heads, False)
+            ti = ti + _T.linear(ctx, w["w_oc"], w["b_oc"])
+        u = _T.layer_norm(ti, w["ln2_g"], w["ln2_b"], eps)
+        hid = _T.linear(u, w["w_1"], w["b_1"])
+        if gated:
+            f = hid.shape[1] // 2
+            hid = hid[:, :f] * _T.gelu_erf(hid[:, f:])
+        else:
+            hid = _T.gelu_erf(hid)
+        out[i * n:(i + 1) * n] = ti + _T.linear(hid, w["w_2"], w["b_2"])
+    return x + _T.linear(out, w["w_out"], w["b_out"]).reshape(b, h, wd, c)

@@ -130,7 +130,7 @@ def attn_weights(r, c, f, scale=0.5):
     return w
 
 
-def attn_block_loops(x, w, groups, heads, eps):
+def attn_block_loops(x, w, groups, heads, eps, context=None, gated=False):
     """The block written out scalar by scalar for one image (pure Python, math.erf / math.exp)."""
     import math
     h, wd, c = x.shape
@@ -169,8 +169,28 @@ def attn_block_loops(x, w, groups, heads, eps):
                 ctx[i][hd * dh + d] = sum(ex[j] / z * qkv[j][2 * c + hd * dh + d] for j in range(n))
     o = lin(ctx, w["w_o"], w["b_o"])
     t2 = [[t[i][ch] + o[i][ch] for ch in range(c)] for i in range(n)]
+    gelu = lambda v: 0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0)))
+    if context is not None:
+        tc = len(context)
+        q2 = lin(ln(t2, w["lnc_g"], w["lnc_b"]), w["w_qc"], [0.0] * c)
+        kv2 = lin([[float(v) for v in row] for row in context], w["w_kvc"], [0.0] * (2 * c))
+        ctx2 = [[0.0] * c for _ in range(n)]
+        for hd in range(heads):
+            for i in range(n):
+                sc = [sum(q2[i][hd * dh + d] * kv2[j][hd * dh + d] for d in range(dh)) / math.sqrt(dh) for j in range(tc)]
+                mx = max(sc)
+                ex = [math.exp(v - mx) for v in sc]
+                z = sum(ex)
+                for d in range(dh):
+                    ctx2[i][hd * dh + d] = sum(ex[j] / z * kv2[j][c + hd * dh + d] for j in range(tc))
+        o2 = lin(ctx2, w["w_oc"], w["b_oc"])
+        t2 = [[t2[i][ch] + o2[i][ch] for ch in range(c)] for i in range(n)]
     hid = lin(ln(t2, w["ln2_g"], w["ln2_b"]), w["w_1"], w["b_1"])
-    act = [[0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in row] for row in hid]
+    if gated:
+        f = len(hid[0]) // 2
+        act = [[row[j] * gelu(row[f + j]) for j in range(f)] for row in hid]
+    else:
+        act = [[gelu(v) for v in row] for row in hid]
     dn = lin(act, w["w_2"], w["b_2"])
     t3 = [[t2[i][ch] + dn[i][ch] for ch in range(c)] for i in range(n)]
     out = lin(t3, w["w_out"], w["b_out"])
@@ -209,3 +229,54 @@ def test_attn_block_special_cases():
     np.testing.assert_allclose(U.attn_block(x, wi, 4, 2), want, rtol=0, atol=1e-12)
     # one head or four: different results (the head split is really applied)
     assert np.abs(U.attn_block(x, w, 4, 4) - y).max() > 1e-3
+
+
+def cross_weights(r, c, d, w):
+    w = dict(w)
+    w["lnc_g"], w["lnc_b"] = 1 + 0.1 * r.standard_normal(c), 0.1 * r.standard_normal(c)
+    w["w_qc"] = 0.5 * r.standard_normal((c, c)) / np.sqrt(c)
+    w["w_kvc"] = 0.5 * r.standard_normal((2 * c, d)) / np.sqrt(d)
+    w["w_oc"], w["b_oc"] = 0.5 * r.standard_normal((c, c)) / np.sqrt(c), 0.1 * r.standard_normal(c)
+    return w
+
+
+def test_attn_block_with_context_and_gate_equals_scalar_loops():
+    r = rng(22)
+    x = r.standard_normal((2, 2, 3, 8))
+    context = r.standard_normal((2, 5, 6))
+    w = cross_weights(r, 8, 6, attn_weights(r, 8, 16))
+    wg = dict(w, w_1=0.5 * r.standard_normal((32, 8)) / np.sqrt(8), b_1=0.1 * r.standard_normal(32))
+    for ww, ctx, gated in ((w, context, False), (wg, None, True), (wg, context, True)):
+        got = U.attn_block(x, ww, groups=2, heads=2, context=ctx, gated=gated)
+        for b in range(2):
+            want = attn_block_loops(x[b], ww, 2, 2, 1e-5, None if ctx is None else ctx[b], gated)
+            np.testing.assert_allclose(got[b], want, rtol=0, atol=1e-12)
+
+
+def test_attn_block_context_special_cases():
+    r = rng(23)
+    x = r.standard_normal((3, 4, 2, 8))
+    context = r.standard_normal((3, 7, 6))
+    w = cross_weights(r, 8, 6, attn_weights(r, 8, 16))
+    y = U.attn_block(x, w, 4, 2, context=context)
+    # the tokens of a context carry no order; every image meets its own context only
+    np.testing.assert_allclose(U.attn_block(x, w, 4, 2, context=context[:, r.permutation(7)]), y, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(U.attn_block(x, w, 4, 2, images=[2, 0], context=context), y[[2, 0]])
+    other = context.copy(); other[1] = r.standard_normal((7, 6))
+    y2 = U.attn_block(x, w, 4, 2, context=other)
+    np.testing.assert_array_equal(y2[[0, 2]], y[[0, 2]])
+    assert np.abs(y2[1] - y[1]).max() > 1e-3
+    # a context of one token: every query attends to it with weight 1, so the cross-attention adds the same row
+    # (that token's value, projected) to every position; with a zero output projection it adds nothing
+    one = context[:, :1]
+    w0 = dict(w, w_oc=np.zeros((8, 8)), b_oc=np.zeros(8))
+    np.testing.assert_allclose(U.attn_block(x, w0, 4, 2, context=one), U.attn_block(x, w, 4, 2), rtol=0, atol=1e-12)
+    # gate: a value half that is the constant 1 (zero weights, unit bias) leaves gelu(gate half): the plain block
+    ones = dict(w, w_1=np.concatenate([np.zeros((16, 8)), w["w_1"]]), b_1=np.concatenate([np.ones(16), w["b_1"]]))
+    np.testing.assert_allclose(U.attn_block(x, ones, 4, 2, gated=True), U.attn_block(x, w, 4, 2), rtol=0, atol=1e-12)
+    # ... and the two halves are really multiplied: doubling the value half's weights and bias doubles the hidden rows,
+    # which is the same as doubling the down projection's weights
+    wg = dict(w, w_1=r.standard_normal((32, 8)) / np.sqrt(8), b_1=0.1 * r.standard_normal(32))
+    dbl = dict(wg, w_1=np.concatenate([2 * wg["w_1"][:16], wg["w_1"][16:]]), b_1=np.concatenate([2 * wg["b_1"][:16], wg["b_1"][16:]]))
+    np.testing.assert_allclose(U.attn_block(x, dbl, 4, 2, gated=True), U.attn_block(x, dict(wg, w_2=2 * wg["w_2"]), 4, 2, gated=True),
+                               rtol=0, atol=1e-11)
