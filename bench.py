@@ -84,19 +84,20 @@ def cpu_baseline_pair(cfg, z, w):
 
 
 def cpu_baseline_res(cfg, x, layers):
-    """The oracle as it stands on a bounded sample: the first layer (residual block, and the attention block where
-    the stage has one) on the first two images."""
+    """The oracle as it stands on a bounded sample: the first layer on the first two images (residual blocks only),
+    or on all of them (residual + attention block, which the oracle finishes in seconds)."""
     from oracle import unet as U
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
     except Exception:
         cores = os.cpu_count()
-    n = min(2, cfg.batch)
+    n = cfg.batch if cfg.heads > 0 else min(2, cfg.batch)     # a few seconds either way
     t0 = time.perf_counter()
     h = U.res_block(x, layers[0]["temb"], layers[0], cfg.groups, cfg.eps, images=list(range(n)))
     if cfg.heads > 0:
-        U.attn_block(h, layers[0], cfg.groups, cfg.heads, cfg.eps)
+        ctx = layers[0].get("context")
+        U.attn_block(h, layers[0], cfg.groups, cfg.heads, cfg.eps, context=None if ctx is None else ctx[:n], gated=cfg.gated)
     dt = time.perf_counter() - t0
     what = "residual + attention block" if cfg.heads > 0 else "block"
     return {"value": n * cfg.height * cfg.width / (dt * cfg.layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
@@ -263,8 +264,9 @@ def main():
     is_res = isinstance(cfg, I.ResStackConfig)
     if is_res:
         x, layers = I.res_stack_inputs(cfg)
-        names = I.RES_BLOCK_TENSORS + (I.ATTN_BLOCK_TENSORS if cfg.heads > 0 else ())
-        dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in names]
+        names = I.RES_BLOCK_TENSORS + I.attn_block_tensors(cfg)
+        flat = lambda t: t.reshape(t.shape[0], -1) if t.ndim == 4 else t.reshape(-1, t.shape[-1]) if t.ndim == 3 else t
+        dw = [B.to_device(flat(w[n]), cfg.dtype) for w in layers for n in names]
         make_desc = lambda flags: B.res_stack_desc(cfg, flags=flags)
         res_regions = lambda c: [(k, B.AC_DIM_BATCH, c) for k in ((B.AC_REGION_RES_BLOCK, B.AC_REGION_UNET_ATTN) if cfg.heads > 0
                                                                   else (B.AC_REGION_RES_BLOCK,))]
@@ -326,7 +328,8 @@ def main():
              "segments_in_flight": args.in_flight, **chunk_lens(info),
              **({"chunk_dim": args.pair_dim} if is_pair else {})},
             **({"layers": cfg.layers, "batch": cfg.batch, "height": cfg.height, "width": cfg.width, "channels": cfg.channels,
-                "groups": cfg.groups, "heads": cfg.heads, "d_ffn": cfg.d_ffn, "tokens": "pixels (batch * height * width)"} if is_res else
+                "groups": cfg.groups, "heads": cfg.heads, "d_ffn": cfg.d_ffn, "context_tokens": cfg.context_tokens,
+                "context_dim": cfg.context_dim, "gated_ffn": cfg.gated, "tokens": "pixels (batch * height * width)"} if is_res else
                {"n_res": cfg.n_res, "c_z": cfg.c_z, "c_hidden": cfg.c_hidden, "heads": cfg.heads,
                 "head_dim": cfg.head_dim, "tokens": "pair positions (n_res^2)"} if is_pair else
                {"layers": cfg.layers, "seq": cfg.seq, "d_model": cfg.d_model, "heads": cfg.heads,

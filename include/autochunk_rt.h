@@ -113,13 +113,16 @@ enum {
                                       to the rounding of the stored scores and probabilities.  With a
                                       causal mask the masked half is computed and discarded;
                                       flops_per_execute counts what is executed. */
-  AC_FLAG_BUDGET_PAPER_MODEL = 16  /* act_budget_bytes additionally bounds, for every region, the bytes
+  AC_FLAG_BUDGET_PAPER_MODEL = 16, /* act_budget_bytes additionally bounds, for every region, the bytes
                                       the paper's two activation equations give for an unfused graph in
                                       which every op output is a tensor (ac_region_info.model_bytes:
                                       scores and probabilities of a segment included), as a planner that
                                       sees such a graph would size it (AutoChunk section 3.2, 3.4).
                                       Without the flag the budget bounds what this executor really
                                       holds, where the scores never reach memory. */
+  AC_FLAG_GATED_FFN = 32           /* UNet attention block only: the feed-forward's first layer is 2 * d_ffn
+                                      wide and its hidden rows are value * activation(gate), value from the
+                                      first d_ffn output features and gate from the second */
 };
 
 typedef struct ac_model_desc {
@@ -141,9 +144,12 @@ typedef struct ac_model_desc {
    * With heads > 0 every residual block is followed by an attention block (region kind
    * AC_REGION_UNET_ATTN, also chunked along the batch: its GroupNorm and its attention reduce over the
    * positions): `heads` heads of channels / heads = 32, 64 or 128 channels each, feed-forward width
-   * d_ffn (a multiple of 64) with `activation`; head_dim is ignored.  A layer's weights are then the
-   * nine tensors of the residual block followed by the eighteen of the attention block (names and
-   * shapes from ac_plan_weight_info). */
+   * d_ffn (a multiple of 64) with `activation`; head_dim is ignored.  With seq > 0 the attention block
+   * also has a cross-attention between its self-attention and its feed-forward: queries from the image's
+   * positions, keys and values from a context of `seq` tokens of width d_model per image, which is bound
+   * like a weight ("context", [batch * seq, d_model]: a whole input every segment of that image reads).
+   * A layer's weights are then the nine tensors of the residual block followed by those of the attention
+   * block: eighteen, plus seven with a context (names and shapes from ac_plan_weight_info). */
   int32_t img_h, img_w, channels, groups;
 } ac_model_desc;
 

@@ -28,6 +28,7 @@ AC_FLAG_LISTED_REGIONS_ONLY = 2
 AC_FLAG_TWO_SEGMENTS_IN_FLIGHT = 4
 AC_FLAG_MATERIALIZED_SCORES = 8
 AC_FLAG_BUDGET_PAPER_MODEL = 16
+AC_FLAG_GATED_FFN = 32
 
 ACTIVATIONS = {"none": AC_ACT_NONE, "gelu_erf": AC_ACT_GELU_ERF, "gelu_tanh": AC_ACT_GELU_TANH,
                "relu": AC_ACT_RELU, "sigmoid": AC_ACT_SIGMOID}
@@ -236,8 +237,9 @@ def res_stack_desc(cfg, flags=0) -> ac_model_desc:
     m.layers, m.batch = cfg.layers, cfg.batch
     m.img_h, m.img_w, m.channels, m.groups = cfg.height, cfg.width, cfg.channels, cfg.groups
     m.heads, m.d_ffn = cfg.heads, cfg.d_ffn              # heads > 0: an attention block after every residual block
+    m.seq, m.d_model = cfg.context_tokens, cfg.context_dim   # > 0: with a cross-attention to a context per image
     m.activation = ACTIVATIONS[cfg.activation]
-    m.flags = flags
+    m.flags = flags | (AC_FLAG_GATED_FFN if cfg.gated else 0)
     m.ln_eps = cfg.eps
     return m
 

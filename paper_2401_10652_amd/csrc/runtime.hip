@@ -956,17 +956,26 @@ void Walk::pair(const void* x, void* y) {
 // partial statistics, one inter-block buffer.
 //
 // With heads > 0 an attention block follows every residual block; the positions of an image are its tokens:
-//   t = GroupNorm(x) W_in^T + b_in;  t += attention(LN1(t)) W_o^T + b_o;  t += act(LN2(t) W_1^T + b_1) W_2^T + b_2;
+//   t = GroupNorm(x) W_in^T + b_in;  t += attention(LN1(t)) W_o^T + b_o;
+//   [with a context c of the image: t += attention(q = LNc(t) W_qc^T; k, v = c W_kvc^T) W_oc^T + b_oc;]
+//   t += act(LN2(t) W_1^T + b_1) W_2^T + b_2   [gated: (value half) * act(gate half) of a 2F-wide first layer];
 //   y = x + t W_out^T + b_out
 // Per segment of images it holds the normalised rows (GroupNorm, then either LayerNorm), t (updated in place
 // by the two residual epilogues), q | k and the transposed v, the context and the feed-forward's hidden rows.
 // ---------------------------------------------------------------------------------------
 enum { RB_GN1_G, RB_GN1_B, RB_W1, RB_B1, RB_GN2_G, RB_GN2_B, RB_W2, RB_B2, RB_TEMB, RB_COUNT };
 static const char* const kRbName[RB_COUNT] = {"gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb"};
+// (the seven tensors of the cross-attention, AB_LNC_G .. AB_CONTEXT, are only there with a context)
 enum { AB_GN_G, AB_GN_B, AB_W_IN, AB_B_IN, AB_LN1_G, AB_LN1_B, AB_W_QKV, AB_B_QKV, AB_W_O, AB_B_O,
+       AB_LNC_G, AB_LNC_B, AB_W_QC, AB_W_KVC, AB_W_OC, AB_B_OC, AB_CONTEXT,
        AB_LN2_G, AB_LN2_B, AB_W_1, AB_B_1, AB_W_2, AB_B_2, AB_W_OUT, AB_B_OUT, AB_COUNT };
 static const char* const kAbName[AB_COUNT] = {"gn_g", "gn_b", "w_in", "b_in", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                                              "lnc_g", "lnc_b", "w_qc", "w_kvc", "w_oc", "b_oc", "context",
                                               "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2", "w_out", "b_out"};
+constexpr int kAbCross = AB_CONTEXT - AB_LNC_G + 1;
+static int ab_tensors(const ac_model_desc& m) { return m.heads <= 0 ? 0 : AB_COUNT - (m.seq > 0 ? 0 : kAbCross); }
+// position of attention-block tensor `slot` among the block's bound tensors
+static int ab_index(const ac_model_desc& m, int slot) { return slot - (slot > AB_CONTEXT && m.seq <= 0 ? kAbCross : 0); }
 
 void Walk::res_stack(const void* x, void* y) {
   const ac_model_desc& m = p->m;
@@ -976,7 +985,7 @@ void Walk::res_stack(const void* x, void* y) {
   auto atw = [&](void* base, int64_t elems) { return (void*)((uint8_t*)base + elems * e); };
   const uint64_t img_bytes = (uint64_t)HW * C * e;
   const bool with_attn = m.heads > 0;
-  const int per_layer = RB_COUNT + (with_attn ? AB_COUNT : 0);
+  const int per_layer = RB_COUNT + ab_tensors(m);
   const int modules = m.layers * (with_attn ? 2 : 1);          // each maps [B, H, W, C] to the same shape
   void* tbuf[2] = {nullptr, nullptr};
   if (modules > 1) tbuf[0] = arena.push((uint64_t)m.batch * img_bytes);
@@ -994,7 +1003,7 @@ void Walk::res_stack(const void* x, void* y) {
     const bool attn = with_attn && idx % 2 == 1;
     const void* in = idx == 0 ? x : (const void*)tbuf[(idx - 1) % 2];
     void* out = idx == modules - 1 ? y : tbuf[idx % 2];
-    auto W = [&](int slot) { return w(l, (attn ? RB_COUNT : 0) + slot, per_layer); };
+    auto W = [&](int slot) { return w(l, attn ? RB_COUNT + ab_index(m, slot) : slot, per_layer); };
     // GroupNorm of a segment's images; their partial statistics sit at the images' own place in the table,
     // so two segments in flight do not share any of it
     auto gn = [&](const RowSeg& sg, const void* src, int gslot, int bslot, void* dst, int act) {
@@ -1029,6 +1038,8 @@ void Walk::res_stack(const void* x, void* y) {
     }
     enter(AC_REGION_UNET_ATTN);
     const int64_t F = m.d_ffn, dh = C / m.heads;
+    const bool gated = (m.flags & AC_FLAG_GATED_FFN) != 0;
+    const int64_t Tc = m.seq, D = m.d_model, Tcp = (Tc + 7) / 8 * 8;   // context tokens, width; padded row of its v^T
     seg_loop(image_segments(AC_REGION_UNET_ATTN), [&](const RowSeg& sg) {
       const int64_t nb = sg.ni, T = nb * HW;
       const void* xs = at(in, sg.i0 * HW * C);
@@ -1037,7 +1048,10 @@ void Walk::res_stack(const void* x, void* y) {
       void* qk = arena.push((uint64_t)T * 2 * C * e);   // q | k row-major
       void* vt = arena.push((uint64_t)T * C * e);       // v transposed per image: [image][C][HW]
       void* ctx = arena.push((uint64_t)T * C * e);
-      void* hid = arena.push((uint64_t)T * F * e);
+      void* hid = arena.push((uint64_t)T * (gated ? 2 : 1) * F * e);
+      void* act = gated ? arena.push((uint64_t)T * F * e) : hid;
+      void* kc = Tc > 0 ? arena.push((uint64_t)nb * Tc * C * e) : nullptr;     // keys of the contexts, row-major
+      void* vct = Tc > 0 ? arena.push((uint64_t)nb * C * Tcp * e) : nullptr;   // their values, transposed per image
       gn(sg, xs, AB_GN_G, AB_GN_B, u, AC_ACT_NONE);
       proj(u, C, W(AB_W_IN), C, W(AB_B_IN), AC_ACT_NONE, nullptr, 0, t, C, T, C);
       ln(t, C, W(AB_LN1_G), W(AB_LN1_B), u, C, T, C);
@@ -1054,9 +1068,35 @@ void Walk::res_stack(const void* x, void* y) {
       a.batch = nb; a.sq = HW; a.sk = HW; a.heads = m.heads; a.head_dim = (int)dh; a.causal = 0; a.q_offset = 0;
       attention(a);
       proj(ctx, C, W(AB_W_O), C, W(AB_B_O), AC_ACT_NONE, t, C, t, C, T, C);
+      if (Tc > 0) {
+        // queries go where q | k of the self-attention were; keys and values of the segment's contexts are projected
+        // once (a context is a whole input of its image: every position reads all of it)
+        ln(t, C, W(AB_LNC_G), W(AB_LNC_B), u, C, T, C);
+        proj(u, C, W(AB_W_QC), C, nullptr, AC_ACT_NONE, nullptr, 0, qk, C, T, C);
+        LinearArgs kv{};
+        kv.a = at(W(AB_CONTEXT), sg.i0 * Tc * D); kv.lda = D; kv.w = W(AB_W_KVC); kv.ldw = D; kv.m = nb * Tc; kv.n = 2 * C; kv.k = D;
+        kv.out = kc; kv.ldo = C; kv.n_split = C;
+        kv.out_t = vct; kv.t_period = Tc; kv.t_s1 = C * Tcp; kv.t_s2 = 1; kv.t_s3 = Tcp;
+        linear(kv);
+        AttnArgs c{};
+        c.q = qk; c.ldq = C; c.sq_b = HW * C;
+        c.k = kc; c.ldk = C; c.sk_b = Tc * C;
+        c.v = vct; c.ldv = Tcp; c.sv_b = C * Tcp; c.v_transposed = 1;
+        c.ctx = ctx; c.ldc = C; c.sc_b = HW * C;
+        c.batch = nb; c.sq = HW; c.sk = Tc; c.heads = m.heads; c.head_dim = (int)dh; c.causal = 0; c.q_offset = 0;
+        attention(c);
+        proj(ctx, C, W(AB_W_OC), C, W(AB_B_OC), AC_ACT_NONE, t, C, t, C, T, C);
+      }
       ln(t, C, W(AB_LN2_G), W(AB_LN2_B), u, C, T, C);
-      proj(u, C, W(AB_W_1), C, W(AB_B_1), m.activation, nullptr, 0, hid, F, T, F);
-      proj(hid, F, W(AB_W_2), F, W(AB_B_2), AC_ACT_NONE, t, C, t, C, T, C);
+      if (gated) {
+        proj(u, C, W(AB_W_1), C, W(AB_B_1), AC_ACT_NONE, nullptr, 0, hid, 2 * F, T, 2 * F);
+        void* gate = atw(hid, F);
+        bias_act(gate, 2 * F, nullptr, gate, 2 * F, T, F, m.activation);
+        binary(hid, 2 * F, gate, 2 * F, act, F, T, F, 1);
+      } else {
+        proj(u, C, W(AB_W_1), C, W(AB_B_1), m.activation, nullptr, 0, hid, F, T, F);
+      }
+      proj(act, F, W(AB_W_2), F, W(AB_B_2), AC_ACT_NONE, t, C, t, C, T, C);
       proj(t, C, W(AB_W_OUT), C, W(AB_B_OUT), AC_ACT_NONE, xs, C, atw(out, sg.i0 * HW * C), C, T, C);
     });
   }
@@ -1087,9 +1127,12 @@ static uint64_t model_bytes(const ac_model_desc& m, int kind, int64_t c) {
       // per image of a segment, every op output a tensor: the normalised image, t, LayerNorm 1, q, k, v, the
       // context, its projection, the sum, LayerNorm 2, the down projection, the sum, the output projection
       // (13 images' worth), the hidden rows before and after the activation, scores and probabilities
-      const uint64_t hw = (uint64_t)m.img_h * m.img_w;
-      return 2 * (uint64_t)m.batch * img +
-             (uint64_t)c * (13 * img + 2 * hw * m.d_ffn * b + 2 * (uint64_t)m.heads * hw * hw * b);
+      // with a context: its LayerNorm, queries, context, projection and sum (5 images' worth), keys and values of
+      // the context, scores and probabilities against it; gated: first layer twice as wide, activation, product
+      const uint64_t hw = (uint64_t)m.img_h * m.img_w, tc = m.seq > 0 ? m.seq : 0;
+      const uint64_t ffn = ((m.flags & AC_FLAG_GATED_FFN) ? 4 : 2) * hw * m.d_ffn * b;
+      const uint64_t cross = tc ? 5 * img + 2 * tc * m.channels * b + 2 * (uint64_t)m.heads * hw * tc * b : 0;
+      return 2 * (uint64_t)m.batch * img + (uint64_t)c * (13 * img + ffn + 2 * (uint64_t)m.heads * hw * hw * b + cross);
     }
     return 2 * (uint64_t)m.batch * img + 7 * (uint64_t)c * img;
   }
@@ -1240,11 +1283,17 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
       if ((dh != 32 && dh != 64 && dh != 128) || m.d_ffn < 64 || m.d_ffn % 64 != 0 || (int64_t)m.img_h * m.img_w % 64 != 0)
         return fail(AC_ERR_UNSUPPORTED, "the attention block takes heads of 32, 64 or 128 channels, a feed-forward width in "
                                         "multiples of 64 and images of a multiple of 64 positions");
+      if (m.seq < 0 || (m.seq > 0 && m.d_model < 1)) return fail(AC_ERR_ARG, "context tokens and width must be positive");
+      if (m.seq > 0 && m.d_model % 8 != 0) return fail(AC_ERR_UNSUPPORTED, "the context's width must be a multiple of 8");
+    } else if (m.seq != 0 || (m.flags & AC_FLAG_GATED_FFN)) {
+      return fail(AC_ERR_ARG, "a context or a gated feed-forward needs the attention block (heads > 0)");
     }
   } else {
     return fail(AC_ERR_ARG, "workload %d unknown", m.workload);
   }
 
+  if ((m.flags & AC_FLAG_GATED_FFN) && m.workload != AC_UNET_RES_STACK)
+    return fail(AC_ERR_ARG, "AC_FLAG_GATED_FFN applies to the UNet attention block only");
   if ((m.flags & AC_FLAG_MATERIALIZED_SCORES) && m.workload != AC_TRANSFORMER_STACK)
     return fail(AC_ERR_UNSUPPORTED, "AC_FLAG_MATERIALIZED_SCORES applies to the transformer stack only");
   if (m.flags & AC_FLAG_LISTED_REGIONS_ONLY) {
@@ -1357,8 +1406,10 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
     const int64_t C = m.channels;
     const int64_t shp[RB_COUNT][2] = {{1, C}, {1, C}, {C, 9 * C}, {1, C}, {1, C}, {1, C}, {C, 9 * C}, {1, C}, {m.batch, C}};
     const int64_t F = m.d_ffn;
+    const int64_t F1 = ((m.flags & AC_FLAG_GATED_FFN) ? 2 : 1) * F, D = m.d_model;
     const int64_t ashp[AB_COUNT][2] = {{1, C}, {1, C}, {C, C}, {1, C}, {1, C}, {1, C}, {3 * C, C}, {1, 3 * C}, {C, C}, {1, C},
-                                       {1, C}, {1, C}, {F, C}, {1, F}, {C, F}, {1, C}, {C, C}, {1, C}};
+                                       {1, C}, {1, C}, {C, C}, {2 * C, D}, {C, C}, {1, C}, {(int64_t)m.batch * m.seq, D},
+                                       {1, C}, {1, C}, {F1, C}, {1, F1}, {C, F}, {1, C}, {C, C}, {1, C}};
     for (int l = 0; l < m.layers; ++l) {
       char nm[48];
       for (int t = 0; t < RB_COUNT; ++t) {
@@ -1366,6 +1417,7 @@ int ac_plan_create(const ac_model_desc* model, const ac_region_desc* regions, in
         p->weights.push_back(WeightSlot{nm, shp[t][0], shp[t][1]});
       }
       for (int t = 0; m.heads > 0 && t < AB_COUNT; ++t) {
+        if (m.seq <= 0 && t >= AB_LNC_G && t <= AB_CONTEXT) continue;
         snprintf(nm, sizeof(nm), "A%d.%s", l, kAbName[t]);
         p->weights.push_back(WeightSlot{nm, ashp[t][0], ashp[t][1]});
       }

@@ -137,11 +137,10 @@ def pair_executor_regions(chunks, names):
 
 
 def unet_stage_tags(names):
-    """ac_node_tag entries for a unet_stage_graph.  The executor runs its residual block (nodes "res.*") and, as the
-    attention block, the part of the spatial transformer it has kernels for: group norm, convolution in,
-    self-attention, feed-forward, convolution out, skip ("tr.*" except the cross-attention "tr.ca.*", which belongs
-    to no region kind, so a chunk that spans it is refused).  Every tensor of both has the batch as its first dim,
-    and the batch is the only dim the executor cuts them along."""
+    """ac_node_tag entries for a unet_stage_graph.  The executor runs its residual block (nodes "res.*") and its
+    spatial transformer ("tr.*": group norm, convolution in, self-attention, cross-attention to the context, gated
+    feed-forward, convolution out, skip) as the attention block.  Every tensor of both has the batch as its first
+    dim, and the batch is the only dim the executor cuts them along."""
     tags = [(-1, 0, ())] * len(names)
     batch_only = ((B.AC_DIM_BATCH, 1), (-1, 0), (-1, 0), (-1, 0))
     params = {"ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo", "w1", "b1", "w2", "b2", "gn_g", "gn_b", "w_in", "b_in", "w_out", "b_out"}
@@ -149,7 +148,7 @@ def unet_stage_tags(names):
         prefix, _, last = full.rpartition(".")
         if prefix == "res" and last in ("n1", "a1", "c1", "t", "n2", "a2", "c2", "y"):
             tags[idx] = (B.AC_REGION_RES_BLOCK, 0, batch_only)
-        elif full.startswith("tr.") and not full.startswith("tr.ca.") and last not in params:
+        elif full.startswith("tr.") and last not in params:
             tags[idx] = (B.AC_REGION_UNET_ATTN, 0, batch_only)
     return B.node_tags(tags)
 

@@ -239,6 +239,9 @@ class ResStackConfig:
     heads: int = 0        # > 0: every residual block is followed by an attention block with this many heads
     d_ffn: int = 0        # ... and a feed-forward of this width
     activation: str = "gelu_erf"
+    context_tokens: int = 0   # > 0: the attention block has a cross-attention to this many context tokens per image
+    context_dim: int = 0      # ... of this width
+    gated: bool = False       # the feed-forward's hidden rows are value * activation(gate)
 
     @property
     def tokens(self) -> int:
@@ -249,8 +252,10 @@ class ResStackConfig:
 U1 = ResStackConfig("U1_unet_res_b8_c320_64x64", 5, 2, 8, 64, 64, 320, 32, chunk_len=2)
 
 # the same stage at an attention resolution: every residual block followed by an attention block over the
-# 4096 positions of an image (5 heads of 64 channels, feed-forward 4 x 320)
-U2 = ResStackConfig("U2_unet_res_attn_b8_c320_64x64", 6, 1, 8, 64, 64, 320, 32, chunk_len=2, heads=5, d_ffn=1280)
+# 4096 positions of an image (5 heads of 64 channels; cross-attention to 77 context tokens of width 768 per image;
+# gated feed-forward 4 x 320)
+U2 = ResStackConfig("U2_unet_res_attn_b8_c320_64x64", 6, 1, 8, 64, 64, 320, 32, chunk_len=2, heads=5, d_ffn=1280,
+                    context_tokens=77, context_dim=768, gated=True)
 
 CONFIGS["U1"] = U1
 CONFIGS["U2"] = U2
@@ -258,6 +263,16 @@ CONFIGS["U2"] = U2
 RES_BLOCK_TENSORS = ("gn1_g", "gn1_b", "w1", "b1", "gn2_g", "gn2_b", "w2", "b2", "temb")
 ATTN_BLOCK_TENSORS = ("gn_g", "gn_b", "w_in", "b_in", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                       "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2", "w_out", "b_out")
+CROSS_ATTN_TENSORS = ("lnc_g", "lnc_b", "w_qc", "w_kvc", "w_oc", "b_oc", "context")
+
+
+def attn_block_tensors(cfg) -> tuple:
+    """The attention block's tensors in bind order: the cross-attention's sit behind the self-attention's."""
+    if cfg.heads <= 0:
+        return ()
+    if cfg.context_tokens <= 0:
+        return ATTN_BLOCK_TENSORS
+    return ATTN_BLOCK_TENSORS[:10] + CROSS_ATTN_TENSORS + ATTN_BLOCK_TENSORS[10:]
 
 
 def res_stack_inputs(cfg: ResStackConfig, seed: int = BASE_SEED, bias_std: float = 0.0, gn_jitter: float = 0.0):
@@ -290,9 +305,14 @@ def res_stack_inputs(cfg: ResStackConfig, seed: int = BASE_SEED, bias_std: float
                     w[name] = np.zeros((c,), np.float32)
         if cfg.heads > 0:
             f = cfg.d_ffn
-            shapes = {"w_in": (c, c), "w_qkv": (3 * c, c), "w_o": (c, c), "w_1": (f, c), "w_2": (c, f), "w_out": (c, c)}
-            for name in ATTN_BLOCK_TENSORS:
-                if name.startswith("w_"):
+            shapes = {"w_in": (c, c), "w_qkv": (3 * c, c), "w_o": (c, c), "w_1": ((2 if cfg.gated else 1) * f, c), "w_2": (c, f),
+                      "w_out": (c, c), "w_qc": (c, c), "w_kvc": (2 * c, cfg.context_dim), "w_oc": (c, c)}
+            for name in attn_block_tensors(cfg):
+                if name == "context":
+                    w[name] = st.normal((cfg.batch, cfg.context_tokens, cfg.context_dim), 1.0, cfg.dtype)
+                elif name in ("w_qc", "w_kvc"):
+                    w[name] = st.normal(shapes[name], 1.0 / math.sqrt(shapes[name][1]), cfg.dtype)
+                elif name.startswith("w_"):
                     w[name] = st.normal(shapes[name], 1.0 / math.sqrt(shapes[name][1]), cfg.dtype)
                 elif name.startswith("b_"):
                     n = shapes["w_" + name[2:]][0]

@@ -300,7 +300,8 @@ def test_u1_unet_residual_blocks_full_size(B):
 
 def test_u2_unet_residual_and_attention_block_full_size(B):
     """The UNet stage at an attention resolution (8 latents of 64 x 64 x 320: a residual block, then an attention
-    block over the 4096 positions of each image, 5 heads of 64 channels; two images per segment): the residual
+    block over the 4096 positions of each image, 5 heads of 64 channels, with the cross-attention to 77 context tokens
+    of width 768 and the gated feed-forward; two images per segment): the residual
     block of every image against the oracle, the attention block on the device's own output of the residual block
     (read back) for the first and the last image, and the chunked run against the one-segment run (their attention
     launches cut the keys differently, so they agree to rounding, not bitwise)."""
@@ -310,14 +311,15 @@ def test_u2_unet_residual_and_attention_block_full_size(B):
     x, layers = I.res_stack_inputs(cfg)
     w = layers[0]
     dx = B.to_device(x, cfg.dtype)
-    flat = lambda names: [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for n in names]
+    flat2 = lambda t: t.reshape(t.shape[0], -1) if t.ndim == 4 else t.reshape(-1, t.shape[-1]) if t.ndim == 3 else t
+    flat = lambda names: [B.to_device(flat2(w[n]), cfg.dtype) for n in names]
 
     def run(c, heads):
-        one = dataclasses.replace(cfg, heads=heads, d_ffn=cfg.d_ffn if heads else 0)
+        one = cfg if heads else dataclasses.replace(cfg, heads=0, d_ffn=0, context_tokens=0, context_dim=0, gated=False)
         kinds = (B.AC_REGION_RES_BLOCK, B.AC_REGION_UNET_ATTN) if heads else (B.AC_REGION_RES_BLOCK,)
         p = B.Plan(B.res_stack_desc(one), [(k, B.AC_DIM_BATCH, c) for k in kinds])
         info = p.ac_plan_query()
-        p.ac_plan_bind_weights(flat(I.RES_BLOCK_TENSORS + (I.ATTN_BLOCK_TENSORS if heads else ())))
+        p.ac_plan_bind_weights(flat(I.RES_BLOCK_TENSORS + I.attn_block_tensors(one)))
         y = torch.full_like(dx, float("nan"))
         peak = p.ac_execute(dx, y, B.empty_workspace(info.workspace_bytes))
         torch.cuda.synchronize()
@@ -330,7 +332,7 @@ def test_u2_unet_residual_and_attention_block_full_size(B):
     y, info = run(cfg.chunk_len, cfg.heads)
     assert bool(torch.isfinite(y.float()).all())
     pick = [0, cfg.batch - 1]
-    ref = U.attn_block(host(yr)[pick], w, cfg.groups, cfg.heads, cfg.eps)
+    ref = U.attn_block(host(yr)[pick], w, cfg.groups, cfg.heads, cfg.eps, context=w["context"][pick], gated=cfg.gated)
     check(host(y)[pick], ref, "bf16", what="attention block on the device output of the residual block")
     yw, info_w = run(cfg.batch, cfg.heads)
     assert rel_err(host(y), host(yw)) <= 0.5 * TOL["bf16"]

@@ -154,7 +154,7 @@ def test_res_stack_budget_and_legality(B):
 # ---- residual block + attention block ------------------------------------------------------------
 
 def stage_tensors(cfg):
-    return list(I.RES_BLOCK_TENSORS) + (list(I.ATTN_BLOCK_TENSORS) if cfg.heads > 0 else [])
+    return list(I.RES_BLOCK_TENSORS) + list(I.attn_block_tensors(cfg))
 
 
 def run_stage(B, cfg, chunk_res, chunk_attn, flags=0, budget=0, inputs=None):
@@ -162,7 +162,8 @@ def run_stage(B, cfg, chunk_res, chunk_attn, flags=0, budget=0, inputs=None):
     import torch
     x, layers = inputs if inputs is not None else I.res_stack_inputs(cfg, bias_std=0.2, gn_jitter=0.2)
     dx = B.to_device(x, cfg.dtype)
-    dw = [B.to_device(w[n].reshape(w[n].shape[0], -1) if w[n].ndim == 4 else w[n], cfg.dtype) for w in layers for n in stage_tensors(cfg)]
+    flat = lambda t: t.reshape(t.shape[0], -1) if t.ndim == 4 else t.reshape(-1, t.shape[-1]) if t.ndim == 3 else t
+    dw = [B.to_device(flat(w[n]), cfg.dtype) for w in layers for n in stage_tensors(cfg)]
     regs = []
     if chunk_res is not None:
         regs.append((B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, chunk_res))
@@ -187,7 +188,7 @@ def oracle_stage(cfg, x, layers):
     y = x
     for w in layers:
         y = U.res_block(y, w["temb"], w, cfg.groups, cfg.eps)
-        y = U.attn_block(y, w, cfg.groups, cfg.heads, cfg.eps)
+        y = U.attn_block(y, w, cfg.groups, cfg.heads, cfg.eps, context=w.get("context"), gated=cfg.gated)
     return y
 
 
@@ -243,3 +244,27 @@ def test_stage_with_attention_bytes_and_legality(B):
     _, _, yb, ib = run_stage(B, cfg, 4, 0, budget=budget)
     import torch
     assert ib.regions[1].chunk_len < 4 and ib.peak_bytes_planned <= budget and torch.equal(yb, y1)
+
+
+@pytest.mark.parametrize("tc,d,gated", [(77, 768, True), (5, 48, False), (64, 128, True), (1, 8, False), (130, 64, False)])
+def test_stage_with_cross_attention_and_gate_equals_oracle(B, tc, d, gated):
+    """The attention block with a context per image (77 tokens of width 768 as in the published model; fewer tokens
+    than one key tile, exactly one tile, a single token, more than two tiles) and with the gated feed-forward."""
+    import torch
+    cfg = I.ResStackConfig("tuc", 53, 1, 3, 8, 8, 128, 16, heads=2, d_ffn=256, context_tokens=tc, context_dim=d, gated=gated)
+    x, lw, y1, i1 = run_stage(B, cfg, None, None)
+    names = [f"A0.{n}" for n in I.attn_block_tensors(cfg)]
+    assert "A0.context" in names and names.index("A0.lnc_g") == 10
+    check(host(y1), oracle_stage(cfg, x, lw), "bf16", what="one segment per region", depth=2)
+    for ca in (1, 2):
+        _, _, y, info = run_stage(B, cfg, 3, ca, inputs=(x, lw))
+        assert torch.equal(y, y1) and info.peak_bytes_planned < i1.peak_bytes_planned
+    _, _, y2, _ = run_stage(B, cfg, 1, 1, flags=B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT, inputs=(x, lw))
+    assert torch.equal(y2, y1)
+    # the contexts are whole inputs: another image's context changes that image only
+    lw2 = [dict(lw[0])]
+    ctx = lw2[0]["context"].copy()
+    ctx[1] = I.round_to_storage(draw(ctx[1].shape, 70, "bf16"), "bf16")
+    lw2[0]["context"] = ctx
+    _, _, y3, _ = run_stage(B, cfg, 3, 1, inputs=(x, lw2))
+    assert torch.equal(y3[0], y1[0]) and torch.equal(y3[2], y1[2]) and not torch.equal(y3[1], y1[1])

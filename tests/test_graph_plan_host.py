@@ -229,10 +229,9 @@ def test_pair_chunks_map_to_executor_region_settings():
 
 
 def test_unet_residual_block_chunks_map_to_the_executor():
-    """Chunks of the UNet stage graph: along the batch, those of the residual block and of the spatial transformer's
-    self-attention and feed-forward become the executor's settings; output channels of a convolution and query rows
-    of the scores are legal by the rules (section 3.3) but the executor has no such dim there; the cross-attention
-    belongs to no region kind."""
+    """Chunks of the UNet stage graph: along the batch, those of the residual block and of the spatial transformer
+    become the executor's settings; output channels of a convolution and query rows of the scores are legal by the
+    rules (section 3.3) but the executor has no such dim there; a chunk across the two blocks belongs to no kind."""
     spec, nm = PG.unet_stage_graph(4, 64, 8, 8, 2, 7, 32, groups=8)
     nodes = B.graph_nodes(spec)
     tags = PG.unet_stage_tags(nm)
@@ -243,18 +242,17 @@ def test_unet_residual_block_chunks_map_to_the_executor():
     assert info.regions[0].n_segments == 2
     for bad, status in (([(nm["res.c2"], nm["res.c2"], 1, 16)], B.AC_ERR_UNSUPPORTED),      # output channels of the convolution
                         ([(nm["tr.sa.scores"], nm["tr.sa.ctx_h"], 2, 16)], B.AC_ERR_UNSUPPORTED),   # query rows of an image
-                        ([(nm["tr.ca.u"], nm["tr.ca.h"], 0, 1)], B.AC_ERR_ARG),             # the cross-attention
-                        ([(nm["tr.sa.u"], nm["tr.ff.h"], 0, 1)], B.AC_ERR_ARG),             # ... and what spans it
+                        ([(nm["tr.ca.scores"], nm["tr.ca.ctx_h"], 3, 4)], B.AC_ERR_UNSUPPORTED),    # context tokens (were it legal)
                         ([(nm["res.n1"], nm["tr.n"], 0, 1)], B.AC_ERR_ARG)):
         with pytest.raises(B.AcError) as ei:
             B.ac_graph_chunks_to_regions(tags, bad)
         assert ei.value.status == status
     # the attention block: batch chunks of the self-attention and of the feed-forward meet in one setting (the shorter)
     assert B.ac_chunk_trace(nodes, nm["tr.sa.u"], nm["tr.sa.h"], 0) is not None
-    both = [(nm["tr.sa.u"], nm["tr.sa.h"], 0, 2), (nm["tr.ff.u"], nm["tr.ff.h"], 0, 1), (nm["res.n1"], nm["res.y"], 0, 2)]
+    both = [(nm["tr.sa.u"], nm["tr.ca.h"], 0, 2), (nm["tr.ff.u"], nm["tr.ff.h"], 0, 1), (nm["res.n1"], nm["res.y"], 0, 2)]
     regs = B.ac_graph_chunks_to_regions(tags, both)
     assert regs == [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, 2), (B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, 1)]
-    cfga = I.ResStackConfig("tmapa", 3, 1, 4, 8, 8, 64, 8, heads=2, d_ffn=128)
+    cfga = I.ResStackConfig("tmapa", 3, 1, 4, 8, 8, 64, 8, heads=2, d_ffn=256, context_tokens=7, context_dim=32, gated=True)
     infa = B.Plan(B.res_stack_desc(cfga), regs).ac_plan_query()
     assert [infa.regions[k].n_segments for k in range(2)] == [2, 4]
     # the executor's one legal dim is what the rules say: no other dim of the whole block is legal

@@ -417,6 +417,21 @@ def test_unet_stage_with_attention_plan():
     whole = 2 * al(4 * img) + al(4 * c * e) + al(4 * 32 * 16 * 3 * 4)
     seg = 2 * al(img) + al(2 * img) + 2 * al(img) + al(hw * f * e)
     assert seg + whole <= info.workspace_bytes <= seg + whole + (64 << 20)      # + the key splits' fp32 partials
+    # with a context and the gate: seven more tensors per attention block, a first layer twice as wide
+    full = dataclasses.replace(cfg, context_tokens=77, context_dim=768, gated=True)
+    pf = B.Plan(B.res_stack_desc(full), [(B.AC_REGION_UNET_ATTN, B.AC_DIM_BATCH, 1)])
+    inf = pf.ac_plan_query()
+    assert inf.n_weights == 2 * (9 + 25) and pf.weight_names()[9:34] == [f"A0.{n}" for n in I.attn_block_tensors(full)]
+    sh = {pf.ac_plan_weight_info(i).name.decode(): (pf.ac_plan_weight_info(i).rows, pf.ac_plan_weight_info(i).cols) for i in range(34)}
+    assert sh["A0.context"] == (4 * 77, 768) and sh["A0.w_kvc"] == (2 * c, 768) and sh["A0.w_1"] == (2 * f, c) and sh["A0.w_2"] == (c, f)
+    assert inf.regions[1].model_bytes == 2 * 4 * img + 13 * img + 4 * hw * f * e + 2 * 5 * hw * hw * e + \
+        5 * img + 2 * 77 * c * e + 2 * 5 * hw * 77 * e
+    seg_full = seg + al(hw * f * e) + al(hw * f * e) + al(77 * c * e) + al(c * 80 * e)      # 2F-wide first layer, its product, k and v^T
+    assert seg_full + whole <= inf.workspace_bytes <= seg_full + whole + (64 << 20)
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=0, d_ffn=0, gated=True)), []))
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=0, d_ffn=0, context_tokens=7, context_dim=64)), []))
+    expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, context_tokens=7, context_dim=12)), []))
+    expect(B.AC_ERR_ARG, lambda: B.Plan(B.transformer_desc(I.C1, flags=B.AC_FLAG_GATED_FFN), []))
     expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=4)), []))       # 80 channels per head
     expect(B.AC_ERR_ARG, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, heads=7)), []))
     expect(B.AC_ERR_UNSUPPORTED, lambda: B.Plan(B.res_stack_desc(dataclasses.replace(cfg, d_ffn=100)), []))
