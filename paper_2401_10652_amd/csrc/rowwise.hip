@@ -471,14 +471,20 @@ hipError_t launch_softmax_rows(const void* src, int64_t lds_, void* dst, int64_t
 // GroupNorm (+ SiLU) of channels-last images x [images, positions, C]: the C channels of an image
 // in `groups` runs of C / groups consecutive channels, mean and biased variance over a run's
 // channels and all positions.  Two kernels, both HBM-bound passes over the images:
-//   group_norm_partials: block (image * groups + group, part) reads its share of the positions twice
-//     (the second time from L2) and writes (count, mean, sum of squared deviations from that mean);
+//   group_norm_partials_rows: block (image, part) reads whole rows of its share of the positions once (a lane
+//     keeps one 16-byte run of channels and accumulates, per channel, the sum and the sum of squares of the
+//     deviations from the first value it saw), turns them into (count, mean, sum of squared deviations) per
+//     lane and channel, and one thread per group merges its channels' in fixed order; written per (image,
+//     group, part).  Rows wider than 256 such runs take group_norm_partials, one block per (image, group,
+//     part), which reads only its group's channels of every row: with 10-channel groups every cache line is
+//     then fetched by six blocks on different XCDs, twice (measured: 12 times the image per launch);
 //   group_norm_apply: every block first combines the partials of its image (pairwise, the
 //     parallel-variance formula; fixed order, so the result does not depend on timing), then
 //     normalises one 16-byte run of channels per lane with a gain and a shift per channel and applies the activation.
 // Statistics and arithmetic in fp32.
 // ------------------------------------------------------------------------------------
-constexpr int kGnParts = 16;          // position shares per (image, group)
+constexpr int kGnParts = 64;          // position shares per (image, group): enough blocks to fill the chip at 2 images
+constexpr int kGnApplyChunks = 4;     // 16-byte runs per thread of the apply kernel (amortises the merge of the partials)
 constexpr int kGnMaxGroups = 128;
 
 template <typename T>
@@ -518,46 +524,131 @@ group_norm_partials(const T* x, float* part, int64_t positions, int channels, in
 
 template <typename T>
 __global__ void __launch_bounds__(256)
+group_norm_partials_rows(const T* x, float* part, int64_t positions, int channels, int groups) {
+  constexpr int V = Elem<T>::kVec;
+  __shared__ float s_s1[256][V + 1], s_s2[256][V + 1];   // (padded: a thread's row starts in its own bank)
+  const int vpr = channels / V;                    // 16-byte runs per row (<= 256)
+  const int rpp = 256 / vpr;                       // rows per pass of the block
+  const int cg = channels / groups;
+  const int64_t image = blockIdx.x;
+  const int part_i = blockIdx.y;
+  const int64_t per = (positions + kGnParts - 1) / kGnParts;
+  const int64_t p0 = part_i * per, p1 = p0 + per < positions ? p0 + per : positions;
+  const int tid = threadIdx.x, v = tid % vpr, r = tid / vpr;
+  const T* img = x + image * positions * channels;
+  // Sums of the deviations from one value per group, the group's first channel at the share's first position
+  // (the shifted-data form: the sums stay small whatever the mean is, and merging lanes is plain addition).
+  float k[V], s1[V], s2[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) { k[j] = 0.f; s1[j] = 0.f; s2[j] = 0.f; }
+  if (r < rpp && p0 + r < p1) {
+#pragma unroll
+    for (int j = 0; j < V; ++j) k[j] = Elem<T>::ld(img + p0 * channels + (v * V + j) / cg * cg);
+    const T* col = img + v * V;
+    constexpr int B = 8;     // rows in flight per thread: the rows were written by the kernel before and come from memory
+    for (int64_t base = p0 + r; base < p1; base += (int64_t)B * rpp) {
+      float val[B][V];
+#pragma unroll
+      for (int i = 0; i < B; ++i) {
+        const int64_t pos = base + (int64_t)i * rpp;
+        load_vec(col + (pos < p1 ? pos : p1 - 1) * channels, val[i]);    // past the end: a valid row, not counted
+      }
+#pragma unroll
+      for (int i = 0; i < B; ++i) {
+        const float live = base + (int64_t)i * rpp < p1 ? 1.f : 0.f;
+#pragma unroll
+        for (int j = 0; j < V; ++j) { const float d = (val[i][j] - k[j]) * live; s1[j] += d; s2[j] += d * d; }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < V; ++j) { s_s1[tid][j] = s1[j]; s_s2[tid][j] = s2[j]; }
+  __syncthreads();
+  for (int g = tid; g < groups; g += 256) {
+    float a1 = 0.f, a2 = 0.f;
+    for (int c = g * cg; c < (g + 1) * cg; ++c)
+      for (int rr = 0; rr < rpp; ++rr) {             // fixed order: the result does not depend on timing
+        a1 += s_s1[rr * vpr + c / V][c % V];
+        a2 += s_s2[rr * vpr + c / V][c % V];
+      }
+    const float cnt = p1 > p0 ? (float)((p1 - p0) * cg) : 0.f;
+    const float kg = p1 > p0 ? Elem<T>::ld(img + p0 * channels + g * cg) : 0.f;
+    float* o = part + ((image * groups + g) * kGnParts + part_i) * 3;
+    o[0] = cnt;
+    o[1] = cnt > 0.f ? kg + a1 / cnt : 0.f;
+    o[2] = cnt > 0.f ? fmaxf(a2 - a1 * a1 / cnt, 0.f) : 0.f;
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
 group_norm_apply(const T* x, const float* part, const T* gain, const T* shift, T* y, int64_t positions, int channels,
                  int groups, float eps, int act) {
   __shared__ float s_mean[kGnMaxGroups], s_rstd[kGnMaxGroups];
   const int64_t image = blockIdx.y;
   const int tid = threadIdx.x;
-  for (int g = tid; g < groups; g += 256) {
-    const float* pp = part + ((image * groups + g) * kGnParts) * 3;
-    float n = 0.f, mean = 0.f, m2 = 0.f;
-    for (int i = 0; i < kGnParts; ++i) {           // combine in index order
-      const float nb = pp[3 * i], mb = pp[3 * i + 1], m2b = pp[3 * i + 2];
-      if (nb <= 0.f) continue;
-      const float tot = n + nb, delta = mb - mean;
-      mean += delta * (nb / tot);
-      m2 += m2b + delta * delta * (n * nb / tot);
-      n = tot;
+  // a wave merges the 64 partials of a group as a tree (lane l holds part l; fixed shape, so the result does
+  // not depend on timing): a thread that walked them one after the other cost more than the pass itself
+  static_assert(kGnParts == kWave, "one partial per lane");
+  constexpr int GB = 8;                            // groups whose partials a wave has in flight at a time
+  for (int g0 = tid / kWave; g0 < groups; g0 += GB * (256 / kWave)) {
+    float n[GB], mean[GB], m2[GB];
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+      const int g = g0 + i * (256 / kWave);
+      const float* pp = part + ((image * groups + (g < groups ? g : groups - 1)) * kGnParts + tid % kWave) * 3;
+      n[i] = pp[0]; mean[i] = pp[1]; m2[i] = pp[2];
     }
-    s_mean[g] = mean;
-    s_rstd[g] = rsqrtf(m2 / n + eps);
+#pragma unroll
+    for (int off = kWave / 2; off >= 1; off /= 2) {
+#pragma unroll
+      for (int i = 0; i < GB; ++i) {                 // (the groups' chains are independent: their exchanges overlap)
+        const float nb = __shfl_down(n[i], off, kWave), mb = __shfl_down(mean[i], off, kWave), m2b = __shfl_down(m2[i], off, kWave);
+        const float tot = n[i] + nb;
+        const float delta = mb - mean[i], f = nb > 0.f ? nb * __builtin_amdgcn_rcpf(tot) : 0.f;   // (a weight, good to 1 ulp)
+        mean[i] += delta * f;
+        m2[i] += m2b + delta * delta * (n[i] * f);
+        n[i] = tot;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+      const int g = g0 + i * (256 / kWave);
+      if (g < groups && tid % kWave == 0) {
+        s_mean[g] = mean[i];
+        s_rstd[g] = rsqrtf(m2[i] / n[i] + eps);
+      }
+    }
   }
   __syncthreads();
-  constexpr int V = Elem<T>::kVec;                          // channels per lane: one 16-byte access
+  constexpr int V = Elem<T>::kVec;                          // channels per lane and access: 16 bytes
   const int cg = channels / groups;
   const int64_t chunks = positions * (channels / V);
-  const int64_t c = (int64_t)blockIdx.x * 256 + tid;
-  if (c >= chunks) return;
-  const int64_t pos = c / (channels / V);
-  const int ch0 = (int)(c % (channels / V)) * V;
-  const T* in = x + (image * positions + pos) * channels + ch0;
-  T* out = y + (image * positions + pos) * channels + ch0;
-  float v[V], gg[V], sh[V];
-  load_vec(in, v);
-  load_vec(gain + ch0, gg);
-  load_vec(shift + ch0, sh);
+  float v[kGnApplyChunks][V];
+  int64_t off[kGnApplyChunks];
+  int ch0[kGnApplyChunks];
 #pragma unroll
-  for (int i = 0; i < V; ++i) {
-    const int g = (ch0 + i) / cg;
-    const float t = (v[i] - s_mean[g]) * s_rstd[g] * gg[i] + sh[i];
-    v[i] = act == AC_ACT_SILU ? t * sigmoidf(t) : t;
+  for (int k = 0; k < kGnApplyChunks; ++k) {       // all loads of the thread first, so that they overlap
+    int64_t c = ((int64_t)blockIdx.x * kGnApplyChunks + k) * 256 + tid;
+    if (c >= chunks) c = chunks - 1;               // (a valid run; not stored below)
+    ch0[k] = (int)(c % (channels / V)) * V;
+    off[k] = (image * positions + c / (channels / V)) * channels + ch0[k];
+    load_vec(x + off[k], v[k]);
   }
-  store_vec(out, v);
+#pragma unroll
+  for (int k = 0; k < kGnApplyChunks; ++k) {
+    if (((int64_t)blockIdx.x * kGnApplyChunks + k) * 256 + tid >= chunks) break;
+    float gg[V], sh[V];
+    load_vec(gain + ch0[k], gg);
+    load_vec(shift + ch0[k], sh);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const int g = (ch0[k] + i) / cg;
+      const float t = (v[k][i] - s_mean[g]) * s_rstd[g] * gg[i] + sh[i];
+      v[k][i] = act == AC_ACT_SILU ? t * sigmoidf(t) : t;
+    }
+    store_vec(y + off[k], v[k]);
+  }
 }
 
 uint64_t group_norm_workspace_bytes(int64_t images, int groups) { return (uint64_t)images * groups * kGnParts * 3 * sizeof(float); }
@@ -568,15 +659,18 @@ hipError_t launch_group_norm(const void* x, const void* gain, const void* shift,
   if (channels <= 0 || groups <= 0 || groups > kGnMaxGroups || channels % groups != 0 || channels % 8 != 0 || !partials ||
       images > 65535 || (act != AC_ACT_NONE && act != AC_ACT_SILU))
     return hipErrorInvalidValue;
-  const dim3 g1((unsigned)(images * groups), kGnParts);
+  const bool by_rows = channels / (dtype == AC_BF16 ? 8 : 4) <= 256;
+  const dim3 g1 = by_rows ? dim3((unsigned)images, kGnParts) : dim3((unsigned)(images * groups), kGnParts);
   const int64_t chunks = positions * (channels / (dtype == AC_BF16 ? 8 : 4));
-  const dim3 g2((unsigned)((chunks + 255) / 256), (unsigned)images);
+  const dim3 g2((unsigned)((chunks + 256 * kGnApplyChunks - 1) / (256 * kGnApplyChunks)), (unsigned)images);
   if (dtype == AC_BF16) {
-    hipLaunchKernelGGL((group_norm_partials<bf16_t>), g1, dim3(256), 0, s, (const bf16_t*)x, (float*)partials, positions, channels, groups);
+    if (by_rows) hipLaunchKernelGGL((group_norm_partials_rows<bf16_t>), g1, dim3(256), 0, s, (const bf16_t*)x, (float*)partials, positions, channels, groups);
+    else hipLaunchKernelGGL((group_norm_partials<bf16_t>), g1, dim3(256), 0, s, (const bf16_t*)x, (float*)partials, positions, channels, groups);
     hipLaunchKernelGGL((group_norm_apply<bf16_t>), g2, dim3(256), 0, s, (const bf16_t*)x, (const float*)partials, (const bf16_t*)gain,
                        (const bf16_t*)shift, (bf16_t*)y, positions, channels, groups, eps, act);
   } else {
-    hipLaunchKernelGGL((group_norm_partials<float>), g1, dim3(256), 0, s, (const float*)x, (float*)partials, positions, channels, groups);
+    if (by_rows) hipLaunchKernelGGL((group_norm_partials_rows<float>), g1, dim3(256), 0, s, (const float*)x, (float*)partials, positions, channels, groups);
+    else hipLaunchKernelGGL((group_norm_partials<float>), g1, dim3(256), 0, s, (const float*)x, (float*)partials, positions, channels, groups);
     hipLaunchKernelGGL((group_norm_apply<float>), g2, dim3(256), 0, s, (const float*)x, (const float*)partials, (const float*)gain,
                        (const float*)shift, (float*)y, positions, channels, groups, eps, act);
   }

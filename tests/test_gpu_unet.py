@@ -21,10 +21,12 @@ def B():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("images,h,w,c,groups,act", [(2, 9, 7, 64, 8, "silu"), (3, 16, 16, 320, 32, "silu"),
-                                                     (1, 5, 3, 24, 3, "none"), (2, 1, 1, 16, 2, "none")])
+                                                     (1, 5, 3, 24, 3, "none"), (2, 1, 1, 16, 2, "none"),
+                                                     (1, 6, 5, 2304, 32, "silu")])
 def test_group_norm(B, dtype, images, h, w, c, groups, act):
     """Groups of 10 channels straddle the 8-channel vectors; 63 positions do not divide into the 16 shares;
-    a single position leaves most shares empty."""
+    a single position leaves most shares empty; rows of 2304 channels take the kernel that reads a group's
+    channels only."""
     import torch
     x = draw((images, h, w, c), 50, dtype) * 2.0 + 0.5
     x = I.round_to_storage(x, dtype)
@@ -123,7 +125,7 @@ def test_res_stack_chunked_equals_oracle(B, layers, batch, h, w, c, groups):
     al = lambda n: (n + 255) // 256 * 256
     img = h * w * c * 2
     whole = (al(batch * img) if layers > 1 else 0) + (al(batch * img) if layers > 2 else 0) + al(batch * c * 2) + \
-        al(batch * groups * 16 * 3 * 4)
+        al(batch * groups * 64 * 3 * 4)
     for chunk, (_, info) in zip((batch, 1, 2, 3), outs):
         assert info.workspace_bytes == whole + 2 * al(min(chunk, batch) * img)
         assert info.peak_bytes_model == 2 * batch * img + 7 * min(chunk, batch) * img
@@ -222,7 +224,7 @@ def test_stage_with_attention_bytes_and_legality(B):
     # whole: one buffer between the two blocks, the bias + embedding table, the GroupNorm statistics; the attention
     # block's segment of one image holds u, t, q|k (two), v^T, the context and the hidden rows; the residual block's
     # segment of four images two tensors
-    whole = al(4 * img) + al(4 * c * e) + al(4 * 8 * 16 * 3 * 4)
+    whole = al(4 * img) + al(4 * c * e) + al(4 * 8 * 64 * 3 * 4)
     attn_seg = 2 * al(img) + al(2 * img) + 2 * al(img) + al(hw * f * e)
     res_seg = 2 * al(4 * img)
     assert info.workspace_bytes == whole + max(attn_seg, res_seg)

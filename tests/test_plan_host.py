@@ -371,7 +371,7 @@ def test_unet_residual_stack_plan():
     intermediates of a segment), the one legal chunk dim and what the kernels do not take."""
     cfg = I.ResStackConfig("tu", 9, 3, 6, 16, 16, 128, 32)
     img = 16 * 16 * 128 * 2
-    whole = 2 * al(6 * img) + al(6 * 128 * 2) + al(6 * 32 * 16 * 3 * 4)
+    whole = 2 * al(6 * img) + al(6 * 128 * 2) + al(6 * 32 * 64 * 3 * 4)
     for c, lanes in ((6, 1), (2, 1), (4, 1), (1, 2)):
         flags = B.AC_FLAG_TWO_SEGMENTS_IN_FLIGHT if lanes == 2 else 0
         info = B.Plan(B.res_stack_desc(cfg, flags=flags), [(B.AC_REGION_RES_BLOCK, B.AC_DIM_BATCH, c)]).ac_plan_query()
@@ -414,7 +414,7 @@ def test_unet_stage_with_attention_plan():
     assert info.regions[1].model_bytes_unchunked == 2 * 4 * img + 4 * (13 * img + 2 * hw * f * e + 2 * 5 * hw * hw * e)
     # four modules: two whole buffers between them; one image of the attention block holds u, t, q|k, v^T, the
     # context, the hidden rows (the residual block's segment of four images is smaller: 8 images' worth against 10)
-    whole = 2 * al(4 * img) + al(4 * c * e) + al(4 * 32 * 16 * 3 * 4)
+    whole = 2 * al(4 * img) + al(4 * c * e) + al(4 * 32 * 64 * 3 * 4)
     seg = 2 * al(img) + al(2 * img) + 2 * al(img) + al(hw * f * e)
     assert seg + whole <= info.workspace_bytes <= seg + whole + (64 << 20)      # + the key splits' fp32 partials
     # with a context and the gate: seven more tensors per attention block, a first layer twice as wide
