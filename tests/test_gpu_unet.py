@@ -24,7 +24,7 @@ def B():
                                                      (1, 5, 3, 24, 3, "none"), (2, 1, 1, 16, 2, "none"),
                                                      (1, 6, 5, 2304, 32, "silu")])
 def test_group_norm(B, dtype, images, h, w, c, groups, act):
-    """Groups of 10 channels straddle the 8-channel vectors; 63 positions do not divide into the 16 shares;
+    """Groups of 10 channels straddle the 8-channel vectors; 63 positions do not divide into the 64 shares;
     a single position leaves most shares empty; rows of 2304 channels take the kernel that reads a group's
     channels only."""
     import torch
