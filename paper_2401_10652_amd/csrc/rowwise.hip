@@ -349,12 +349,63 @@ transpose_square_inplace(T* __restrict__ data, int64_t ld, int64_t stride_b, int
   }
 }
 
+// The same with 16-byte global accesses (n, ld, stride_b multiples of the vector and a 16-byte aligned base):
+// a thread moves runs of V elements of a row; the transposition happens in LDS, element by element.
+template <typename T>
+__global__ void __launch_bounds__(256)
+transpose_square_inplace_vec(T* __restrict__ data, int64_t ld, int64_t stride_b, int64_t n, int tiles) {
+  constexpr int V = Elem<T>::kVec, CPR = 64 / V;      // 16-byte runs per tile row
+  __shared__ float ta[64][65];
+  __shared__ float tb[64][65];
+  int p = blockIdx.x, bi = 0;
+  while (p >= tiles - bi) { p -= tiles - bi; ++bi; }
+  const int bj = bi + p;
+  T* mat = data + (int64_t)blockIdx.y * stride_b;
+  const int64_t r0 = (int64_t)bi * 64, c0 = (int64_t)bj * 64;
+  const int tid = threadIdx.x;
+  // all loads of the thread first (both tiles), so that they are in flight together
+  constexpr int RUNS = 64 * CPR / 256;                // runs per thread and tile: 2 (bf16) or 4 (fp32)
+  float va[RUNS][V], vb[RUNS][V];
+#pragma unroll
+  for (int k = 0; k < RUNS; ++k) {
+    const int q = tid + 256 * k, row = q / CPR, col = (q % CPR) * V;
+    const bool ina = r0 + row < n && c0 + col < n, inb = bi != bj && c0 + row < n && r0 + col < n;
+    load_vec(mat + (ina ? (r0 + row) * ld + c0 + col : 0), va[k]);
+    load_vec(mat + (inb ? (c0 + row) * ld + r0 + col : 0), vb[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < RUNS; ++k) {
+    const int q = tid + 256 * k, row = q / CPR, col = (q % CPR) * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) { ta[col + e][row] = va[k][e]; tb[col + e][row] = vb[k][e]; }   // stored transposed
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < RUNS; ++k) {
+    const int q = tid + 256 * k, row = q / CPR, col = (q % CPR) * V;
+    float oa[V], ob[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) { oa[e] = ta[row][col + e]; ob[e] = tb[row][col + e]; }
+    // tile (bj, bi) receives ta transposed; tile (bi, bj) receives tb transposed
+    if (c0 + row < n && r0 + col < n) store_vec(mat + (c0 + row) * ld + r0 + col, oa);
+    if (bi != bj && r0 + row < n && c0 + col < n) store_vec(mat + (r0 + row) * ld + c0 + col, ob);
+  }
+}
+
 hipError_t launch_transpose_square_inplace(void* data, int64_t ld, int64_t stride_b, int64_t n, int64_t batch,
                                            int dtype, hipStream_t s) {
   if (n <= 0 || batch <= 0) return hipSuccess;
   if (batch > 65535) return hipErrorInvalidValue;
   const int tiles = (int)((n + 63) / 64);
   dim3 grid((unsigned)(tiles * (tiles + 1) / 2), (unsigned)batch);
+  const int64_t vec = dtype == AC_BF16 ? 8 : 4;
+  if (n % vec == 0 && ld % vec == 0 && stride_b % vec == 0 && ((uintptr_t)data % 16) == 0) {
+    if (dtype == AC_BF16)
+      hipLaunchKernelGGL((transpose_square_inplace_vec<bf16_t>), grid, dim3(256), 0, s, (bf16_t*)data, ld, stride_b, n, tiles);
+    else
+      hipLaunchKernelGGL((transpose_square_inplace_vec<float>), grid, dim3(256), 0, s, (float*)data, ld, stride_b, n, tiles);
+    return hipGetLastError();
+  }
   if (dtype == AC_BF16)
     hipLaunchKernelGGL((transpose_square_inplace<bf16_t>), grid, dim3(256), 0, s, (bf16_t*)data, ld, stride_b, n, tiles);
   else
@@ -400,6 +451,62 @@ layernorm_channel_major(const T* __restrict__ src, int64_t stride_c, const T* __
   }
 }
 
+// The same with 16-byte global accesses on both sides (positions, stride_c and ldd multiples of the vector,
+// channels a multiple of 16 vectors, 16-byte aligned bases): a thread reads runs of V positions of one channel,
+// and each of the 16 lanes of a position's group owns channels / 16 consecutive channels.
+template <typename T>
+__global__ void __launch_bounds__(256)
+layernorm_channel_major_vec(const T* __restrict__ src, int64_t stride_c, const T* __restrict__ gain,
+                            const T* __restrict__ shift, T* __restrict__ dst, int64_t ldd, int64_t positions,
+                            int channels, float eps) {
+  constexpr int V = Elem<T>::kVec, PR = 64 / V;        // 16-byte runs of positions per channel and block
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* tile = reinterpret_cast<float*>(smem_raw);   // [64][channels + 1]
+  const int ldt = channels + 1;
+  const int64_t p0 = (int64_t)blockIdx.x * 64;
+  const int tid = threadIdx.x;
+  constexpr int B = 4;                                 // runs in flight per thread
+  for (int q0 = tid; q0 < channels * PR; q0 += 256 * B) {
+    float v[B][V];
+#pragma unroll
+    for (int k = 0; k < B; ++k) {
+      const int q = q0 + 256 * k, c = q / PR, pr = (q % PR) * V;
+      const bool in = q < channels * PR && p0 + pr < positions;
+      load_vec(src + (in ? (int64_t)c * stride_c + p0 + pr : 0), v[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < B; ++k) {
+      const int q = q0 + 256 * k, c = q / PR, pr = (q % PR) * V;
+      if (q >= channels * PR) break;
+      const bool in = p0 + pr < positions;
+#pragma unroll
+      for (int e = 0; e < V; ++e) tile[(pr + e) * ldt + c] = in ? v[k][e] : 0.f;
+    }
+  }
+  __syncthreads();
+  const int grp = tid / 16, lane = tid % 16;
+  const int cpl = channels / 16;                        // consecutive channels per lane (a multiple of V)
+  for (int pp = grp; pp < 64; pp += 16) {
+    const int64_t p = p0 + pp;
+    const float* row = tile + pp * ldt + lane * cpl;
+    float sum = 0.f;
+    for (int c = 0; c < cpl; ++c) sum += row[c];
+    const float mean = group_sum<16>(sum) / (float)channels;
+    float sq = 0.f;
+    for (int c = 0; c < cpl; ++c) { const float d = row[c] - mean; sq += d * d; }
+    const float rstd = rsqrtf(group_sum<16>(sq) / (float)channels + eps);
+    if (p < positions)
+      for (int c = 0; c < cpl; c += V) {
+        float g[V], b[V], o[V];
+        load_vec(gain + lane * cpl + c, g);
+        load_vec(shift + lane * cpl + c, b);
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] = (row[c + e] - mean) * rstd * g[e] + b[e];
+        store_vec(dst + p * ldd + lane * cpl + c, o);
+      }
+  }
+}
+
 hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, const void* gain, const void* shift,
                                           void* dst, int64_t ldd, int64_t positions, int64_t channels, float eps,
                                           int dtype, hipStream_t s) {
@@ -407,6 +514,18 @@ hipError_t launch_layernorm_channel_major(const void* src, int64_t stride_c, con
   const size_t lds = (size_t)64 * (channels + 1) * sizeof(float);
   if (lds > 64 * 1024) return hipErrorNotSupported;
   dim3 grid((unsigned)((positions + 63) / 64));
+  const int64_t vec = dtype == AC_BF16 ? 8 : 4;
+  auto al16 = [](const void* p) { return ((uintptr_t)p % 16) == 0; };
+  if (positions % vec == 0 && stride_c % vec == 0 && ldd % vec == 0 && channels % (16 * vec) == 0 && al16(src) && al16(dst) &&
+      al16(gain) && al16(shift)) {
+    if (dtype == AC_BF16)
+      hipLaunchKernelGGL((layernorm_channel_major_vec<bf16_t>), grid, dim3(256), lds, s, (const bf16_t*)src, stride_c,
+                         (const bf16_t*)gain, (const bf16_t*)shift, (bf16_t*)dst, ldd, positions, (int)channels, eps);
+    else
+      hipLaunchKernelGGL((layernorm_channel_major_vec<float>), grid, dim3(256), lds, s, (const float*)src, stride_c,
+                         (const float*)gain, (const float*)shift, (float*)dst, ldd, positions, (int)channels, eps);
+    return hipGetLastError();
+  }
   if (dtype == AC_BF16)
     hipLaunchKernelGGL((layernorm_channel_major<bf16_t>), grid, dim3(256), lds, s, (const bf16_t*)src, stride_c,
                        (const bf16_t*)gain, (const bf16_t*)shift, (bf16_t*)dst, ldd, positions, (int)channels, eps);

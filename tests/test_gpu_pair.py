@@ -33,7 +33,7 @@ def test_triangle_contract(B, dtype, ch, ni, nj, nk):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("n,batch", [(64, 3), (200, 2), (72, 5), (8, 1)])
+@pytest.mark.parametrize("n,batch", [(64, 3), (200, 2), (72, 5), (8, 1), (203, 2), (1024, 2)])
 def test_transpose_square_inplace(B, dtype, n, batch):
     import torch
     a = draw((batch, n, n), 52, dtype)
@@ -44,7 +44,7 @@ def test_transpose_square_inplace(B, dtype, n, batch):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("ch,pos", [(128, 1000), (16, 64), (40, 130)])
+@pytest.mark.parametrize("ch,pos", [(128, 1000), (16, 64), (40, 130), (128, 1003), (128, 72), (192, 136), (64, 4096)])
 def test_layernorm_channel_major(B, dtype, ch, pos):
     import torch
     from paper_2401_10652_amd.inputs import round_to_storage
