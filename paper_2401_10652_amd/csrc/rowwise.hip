@@ -573,10 +573,113 @@ softmax_rows(const T* src, int64_t lds_, T* dst, int64_t ldd, int64_t cols, floa
     Elem<T>::st(out + j, j < vis ? __expf(Elem<T>::ld(in + j) * scale - m) * inv : 0.f);
 }
 
+// The same with 16-byte accesses (cols and both row strides multiples of the vector, aligned bases).  NV > 0: the
+// row (at most 256 * NV vectors) stays in registers between the three steps, so it is read once; NV = 0: any
+// length, three passes as above.
+template <typename T, int NV>
+__global__ void __launch_bounds__(256)
+softmax_rows_vec(const T* src, int64_t lds_, T* dst, int64_t ldd, int64_t cols, float scale,
+                 int causal, int64_t q_offset, int64_t period) {
+  constexpr int V = Elem<T>::kVec;
+  constexpr int R = NV > 0 ? NV : 1;
+  __shared__ float red[4];
+  const int64_t r = blockIdx.x;
+  const T* in = src + r * lds_;
+  T* out = dst + r * ldd;
+  int64_t vis = cols;
+  if (causal) {
+    const int64_t last = q_offset + r % period;
+    if (last + 1 < vis) vis = last + 1;
+  }
+  const int tid = threadIdx.x;
+  const int64_t nvec = cols / V;
+  float v[R][V];
+  float m = -INFINITY;
+  if (NV > 0) {
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const int64_t i = tid + 256 * k;
+      if (i * V < vis) load_vec(in + i * V, v[k]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        if (!(i * V + e < vis)) v[k][e] = -INFINITY;
+        m = fmaxf(m, v[k][e]);
+      }
+    }
+  } else {
+    for (int64_t i = tid; i * V < vis; i += 256) {
+      load_vec(in + i * V, v[0]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) if (i * V + e < vis) m = fmaxf(m, v[0][e]);
+    }
+  }
+  m = wave_max(m);
+  if (tid % 64 == 0) red[tid / 64] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * scale;      // scale > 0
+  __syncthreads();
+  float l = 0.f;
+  if (NV > 0) {
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+#pragma unroll
+      for (int e = 0; e < V; ++e) { v[k][e] = __expf(v[k][e] * scale - m); l += v[k][e]; }    // exp(-inf) = 0
+  } else {
+    for (int64_t i = tid; i * V < vis; i += 256) {
+      load_vec(in + i * V, v[0]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) if (i * V + e < vis) l += __expf(v[0][e] * scale - m);
+    }
+  }
+  l = wave_sum(l);
+  if (tid % 64 == 0) red[tid / 64] = l;
+  __syncthreads();
+  const float inv = 1.0f / (red[0] + red[1] + red[2] + red[3]);
+  if (NV > 0) {
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const int64_t i = tid + 256 * k;
+      if (i >= nvec) continue;
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[k][e] *= inv;
+      store_vec(out + i * V, v[k]);
+    }
+  } else {
+    for (int64_t i = tid; i < nvec; i += 256) {
+      if (i * V < vis) load_vec(in + i * V, v[0]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[0][e] = i * V + e < vis ? __expf(v[0][e] * scale - m) * inv : 0.f;
+      store_vec(out + i * V, v[0]);
+    }
+  }
+}
+
+template <typename T>
+static hipError_t softmax_rows_vec_launch(const void* src, int64_t lds_, void* dst, int64_t ldd, int64_t rows, int64_t cols,
+                                          float scale, int causal, int64_t q_offset, int64_t period, hipStream_t s) {
+  const int64_t nvec = cols / Elem<T>::kVec;
+  const dim3 grid((unsigned)rows);
+#define AC_SOFTMAX_VEC(NV)                                                                                        \
+  hipLaunchKernelGGL((softmax_rows_vec<T, NV>), grid, dim3(256), 0, s, (const T*)src, lds_, (T*)dst, ldd, cols, scale, \
+                     causal, q_offset, period)
+  if (nvec <= 256) AC_SOFTMAX_VEC(1);
+  else if (nvec <= 512) AC_SOFTMAX_VEC(2);
+  else if (nvec <= 1024) AC_SOFTMAX_VEC(4);
+  else if (nvec <= 2048) AC_SOFTMAX_VEC(8);
+  else AC_SOFTMAX_VEC(0);
+#undef AC_SOFTMAX_VEC
+  return hipGetLastError();
+}
+
 hipError_t launch_softmax_rows(const void* src, int64_t lds_, void* dst, int64_t ldd, int64_t rows, int64_t cols,
                                float scale, int causal, int64_t q_offset, int64_t period, int dtype, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   if (period <= 0 || !(scale > 0.f) || rows > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int64_t vec = dtype == AC_BF16 ? 8 : 4;
+  if (cols % vec == 0 && lds_ % vec == 0 && ldd % vec == 0 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)dst % 16) == 0) {
+    if (dtype == AC_BF16) return softmax_rows_vec_launch<bf16_t>(src, lds_, dst, ldd, rows, cols, scale, causal, q_offset, period, s);
+    return softmax_rows_vec_launch<float>(src, lds_, dst, ldd, rows, cols, scale, causal, q_offset, period, s);
+  }
   if (dtype == AC_BF16)
     hipLaunchKernelGGL((softmax_rows<bf16_t>), dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)src, lds_,
                        (bf16_t*)dst, ldd, cols, scale, causal, q_offset, period);
@@ -592,14 +695,13 @@ hipError_t launch_softmax_rows(const void* src, int64_t lds_, void* dst, int64_t
 // channels and all positions.  Two kernels, both HBM-bound passes over the images:
 //   group_norm_partials_rows: block (image, part) reads whole rows of its share of the positions once (a lane
 //     keeps one 16-byte run of channels and accumulates, per channel, the sum and the sum of squares of the
-//     deviations from the first value it saw), turns them into (count, mean, sum of squared deviations) per
-//     lane and channel, and one thread per group merges its channels' in fixed order; written per (image,
-//     group, part).  Rows wider than 256 such runs take group_norm_partials, one block per (image, group,
+//     deviations from one value per group), one thread per group adds up its channels' sums in fixed order and
+//     writes (count, mean, sum of squared deviations) per (image, group, part).  Rows wider than 256 such runs take group_norm_partials, one block per (image, group,
 //     part), which reads only its group's channels of every row: with 10-channel groups every cache line is
 //     then fetched by six blocks on different XCDs, twice (measured: 12 times the image per launch);
-//   group_norm_apply: every block first combines the partials of its image (pairwise, the
-//     parallel-variance formula; fixed order, so the result does not depend on timing), then
-//     normalises one 16-byte run of channels per lane with a gain and a shift per channel and applies the activation.
+//   group_norm_apply: every block first merges the partials of its image (a tree of the parallel-variance
+//     formula per group, one partial per lane; fixed shape, so the result does not depend on timing), then
+//     normalises 16-byte runs of channels with a gain and a shift per channel and applies the activation.
 // Statistics and arithmetic in fp32.
 // ------------------------------------------------------------------------------------
 constexpr int kGnParts = 64;          // position shares per (image, group): enough blocks to fill the chip at 2 images

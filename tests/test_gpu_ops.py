@@ -286,6 +286,7 @@ def test_bf16_store_rounds_to_nearest_even(B):
 @pytest.mark.parametrize("rows,cols,period,q_offset,causal", [
     (12, 100, 4, 0, False), (12, 100, 4, 96, True), (6, 1000, 3, 10, True), (8, 8, 8, 0, True),
     (5, 4097, 5, 4000, True), (3, 1, 3, 0, True),
+    (4, 4096, 4, 100, True), (3, 8192, 3, 5000, True), (2, 16384, 2, 0, False), (2, 20000, 2, 12345, True),
 ])
 def test_softmax_rows(B, dtype, rows, cols, period, q_offset, causal):
     """Stored scores -> stored probabilities; row r is query r mod period at position q_offset +
